@@ -1,0 +1,424 @@
+"""fp64 / exact-integer oracle of the WSVD decode step (TEST INFRASTRUCTURE ONLY).
+
+What is computed, and where the paper defines it
+------------------------------------------------
+* latent projection of a token, ``c_Kh = x A_Kh`` and ``c_Vh = x A_Vh``
+  (Section 3.1, the per-head decomposition W_Kh = A_Kh B_Kh and the latent
+  C_Kh = X A_Kh; Section 3.4 decoding pipeline: the new token is down-projected
+  and its K and V latents are stored in the cache);
+* storage of the latent row: fp32, bf16, or quantised.  The paper fixes only
+  "per-token symmetric" activation quantisation (Section 4.2); the exact rounding
+  rules used here are this build's reading and are written out in
+  ``quantize_int8_rows`` / ``quantize_int4_rows``;
+* attention: K_h = C_Kh B_Kh and V_h = C_Vh B_Vh are MATERIALISED (the "naive
+  reconstruction" schedule of Section 3.4, Fig. 4(a)), then plain max-subtracted
+  softmax attention of the single query against them;
+* a second routine computes the same result with B_K folded into the query and B_V
+  applied after the weighted sum of value latents (the algebraic regrouping behind the
+  fused kernel of Section 3.4); it exists only to cross-check the first;
+* the closed forms of Eq. 2 and Eq. 3 (traffic ratio r/R, parameter ratio rho_1,
+  cache ratio rho_2);
+* for the full attention block: per-token symmetric int8 activation quantisation and an
+  int4-weight x int8-activation linear layer with exact integer accumulation
+  (Section 4.2: weights round-to-nearest per-channel symmetric, activations per-token
+  symmetric).
+
+Parity pins (tests/test_oracle_pins.py): identity factors reduce to library attention;
+absorbed == reconstructed; softmax rows sum to one; single-row cache returns that V row;
+zero query returns the mean V row; a two-token scalar case by hand; row-permutation
+invariance; large-score stability; quantiser round trip within one step; nibble packing
+exhaustive; one-hot token reproduces a row of A; the printed instance of Eq. 3
+(rho_2 = 50 % gives rho_1 ~ 51.5 %, Section 4.4) and the 25 % cache figure of Section 4.2.
+The numeric value of the output on Gaussian inputs is not printed anywhere in the paper:
+for that, parity rests on the pins above.
+
+Conventions: x [B,E]; A_K, A_V [Hkv,E,r]; B_K, B_V [Hkv,r,d]; q [B,Hq,d];
+kv(h) = h // (Hq // Hkv).  bf16 values are carried as uint16 bit patterns, fp16 as
+numpy float16.  No blocking, fusion or reordering beyond the definitions.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "bf16_bits_from_f32", "f64_from_bf16_bits", "to_f64",
+    "quantize_int8_rows", "dequantize_int8_rows",
+    "quantize_int4_rows", "dequantize_int4_rows", "pack_int4", "unpack_int4",
+    "LatentCache", "project_latents", "latent_append",
+    "dequant_cache_rows", "decode_attn_reconstructed", "decode_attn_absorbed",
+    "softmax_weights",
+    "traffic_ratio", "param_ratio_rho1", "cache_ratio_rho2", "cache_row_bytes",
+    "latent_cache_bytes",
+    "quantize_act_i8", "pack_w4", "unpack_w4", "linear_w4a8", "linear_w4a8_int_accum",
+    "attention_block_w4a8",
+]
+
+# --------------------------------------------------------------------------- storage formats
+
+
+def bf16_bits_from_f32(x32: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (round-to-nearest-even on the dropped 16 bits); returns uint16 bits.
+
+    NaN is not expected in this workload; infinities pass through unchanged.
+    """
+    x32 = np.ascontiguousarray(x32, dtype=np.float32)
+    u = x32.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    rounded = (u + 0x7FFF + lsb) >> 16
+    return rounded.astype(np.uint16).reshape(x32.shape)
+
+
+def f64_from_bf16_bits(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns to fp64."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    u = bits.astype(np.uint32) << 16
+    return u.view(np.float32).astype(np.float64).reshape(bits.shape)
+
+
+def to_f64(arr: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact conversion of a stored tensor ("f32", "bf16", "f16") to fp64."""
+    if dtype == "f32":
+        return np.asarray(arr, dtype=np.float32).astype(np.float64)
+    if dtype == "bf16":
+        return f64_from_bf16_bits(arr)
+    if dtype == "f16":
+        return np.asarray(arr, dtype=np.float16).astype(np.float64)
+    raise ValueError(f"to_f64: unsupported dtype {dtype}")
+
+
+# --------------------------------------------------------------------------- quantisers
+# The paper states the granularity (per-token symmetric, Section 4.2) and nothing else.
+# The rules below are this build's normative reading; all arithmetic is IEEE fp32 with
+# round-to-nearest-even and true division, so that a GPU can reproduce it bit for bit.
+
+_F16_TINY = np.float16(2.0 ** -24)   # smallest positive fp16 (subnormal)
+_F16_MAX = np.float16(65504.0)
+
+
+def _guard_scale_f16(s32: np.ndarray) -> np.ndarray:
+    """fp32 scale -> fp16 (RNE) with the zero / overflow guards."""
+    with np.errstate(over="ignore"):
+        s16 = s32.astype(np.float16)
+    s16 = np.where(s16 == 0, _F16_TINY, s16)
+    s16 = np.where(np.isinf(s16), _F16_MAX, s16)
+    return s16.astype(np.float16)
+
+
+def quantize_int8_rows(c32: np.ndarray):
+    """Symmetric int8, one fp16 scale per row (= per token per head).
+
+    a = max|c_j|; a == 0 -> scale 1, codes 0.  Otherwise s = fp16(a / 127) (guarded),
+    code_j = clamp(rint(c_j / float(s)), -127, 127).  Returns (codes int8 [...,r],
+    scale fp16 [...]).
+    """
+    c32 = np.asarray(c32, dtype=np.float32)
+    a = np.max(np.abs(c32), axis=-1)
+    s32 = a / np.float32(127.0)
+    s16 = _guard_scale_f16(s32)
+    s16 = np.where(a == 0, np.float16(1.0), s16).astype(np.float16)
+    sf = s16.astype(np.float32)[..., None]
+    codes = np.clip(np.rint(c32 / sf), -127, 127).astype(np.int8)
+    return codes, s16
+
+
+def dequantize_int8_rows(codes: np.ndarray, scale16: np.ndarray) -> np.ndarray:
+    """fp64 value of the stored row: code * scale (exact)."""
+    return codes.astype(np.float64) * np.asarray(scale16, dtype=np.float16).astype(np.float64)[..., None]
+
+
+def pack_int4(codes: np.ndarray) -> np.ndarray:
+    """Codes in [0,15], last dim even -> bytes; element 2i in the LOW nibble of byte i."""
+    codes = np.asarray(codes).astype(np.uint8)
+    assert codes.shape[-1] % 2 == 0
+    lo = codes[..., 0::2]
+    hi = codes[..., 1::2]
+    return (lo | (hi << 4)).astype(np.uint8)
+
+
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    packed = np.asarray(packed, dtype=np.uint8)
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.uint8)
+    out[..., 0::2] = packed & 0x0F
+    out[..., 1::2] = packed >> 4
+    return out
+
+
+def quantize_int4_rows(c32: np.ndarray):
+    """Asymmetric int4, one group per row, fp16 scale and integer-valued fp16 zero point.
+
+    lo = min(min_j c_j, 0), hi = max(max_j c_j, 0); hi == lo -> s=1, z=0, codes 0.
+    s = fp16((hi - lo) / 15) (guarded); z = clamp(rint(-lo / float(s)), 0, 15);
+    code_j = clamp(int(rint(c_j / float(s))) + int(z), 0, 15).
+    Returns (packed uint8 [...,r/2], scale fp16 [...], zero fp16 [...]).
+    """
+    c32 = np.asarray(c32, dtype=np.float32)
+    lo = np.minimum(np.min(c32, axis=-1), np.float32(0))
+    hi = np.maximum(np.max(c32, axis=-1), np.float32(0))
+    flat = hi == lo
+    s32 = (hi - lo) / np.float32(15.0)
+    s16 = _guard_scale_f16(s32)
+    s16 = np.where(flat, np.float16(1.0), s16).astype(np.float16)
+    sf = s16.astype(np.float32)
+    z = np.clip(np.rint(-lo / sf), 0, 15)
+    z = np.where(flat, np.float32(0), z).astype(np.float32)
+    code = np.rint(c32 / sf[..., None]).astype(np.int64) + z.astype(np.int64)[..., None]
+    code = np.clip(code, 0, 15).astype(np.uint8)
+    return pack_int4(code), s16, z.astype(np.float16)
+
+
+def dequantize_int4_rows(packed: np.ndarray, scale16: np.ndarray, zero16: np.ndarray) -> np.ndarray:
+    code = unpack_int4(packed).astype(np.float64)
+    z = np.asarray(zero16, dtype=np.float16).astype(np.float64)[..., None]
+    s = np.asarray(scale16, dtype=np.float16).astype(np.float64)[..., None]
+    return (code - z) * s
+
+
+# --------------------------------------------------------------------------- the latent cache
+
+
+class LatentCache:
+    """Logical per-head latent cache (Section 3.1): row t of head h of sequence b.
+
+    latent_dtype "f32": k/v float32 [B,Hkv,t_cap,r]
+                 "bf16": uint16 bit patterns [B,Hkv,t_cap,r]
+                 "i8":   int8 codes [B,Hkv,t_cap,r] + fp16 scale [B,Hkv,t_cap]
+                 "i4":   packed uint8 [B,Hkv,t_cap,r/2] + fp16 scale, fp16 zero point
+    seq_lens int32 [B] = number of valid rows.
+    """
+
+    def __init__(self, batch, n_kv_heads, t_cap, rank, latent_dtype):
+        self.B, self.Hkv, self.t_cap, self.r, self.dtype = batch, n_kv_heads, t_cap, rank, latent_dtype
+        shp = (batch, n_kv_heads, t_cap)
+        if latent_dtype == "f32":
+            self.k = np.zeros(shp + (rank,), np.float32); self.v = np.zeros(shp + (rank,), np.float32)
+        elif latent_dtype == "bf16":
+            self.k = np.zeros(shp + (rank,), np.uint16); self.v = np.zeros(shp + (rank,), np.uint16)
+        elif latent_dtype == "i8":
+            self.k = np.zeros(shp + (rank,), np.int8); self.v = np.zeros(shp + (rank,), np.int8)
+        elif latent_dtype == "i4":
+            self.k = np.zeros(shp + (rank // 2,), np.uint8); self.v = np.zeros(shp + (rank // 2,), np.uint8)
+        else:
+            raise ValueError(latent_dtype)
+        quant = latent_dtype in ("i8", "i4")
+        self.k_scale = np.ones(shp, np.float16) if quant else None
+        self.v_scale = np.ones(shp, np.float16) if quant else None
+        self.k_zero = np.zeros(shp, np.float16) if latent_dtype == "i4" else None
+        self.v_zero = np.zeros(shp, np.float16) if latent_dtype == "i4" else None
+        self.seq_lens = np.zeros(batch, np.int32)
+
+    def store_rows(self, which, b, t0, c64):
+        """Round fp64 latents c64 [Hkv,n,r] to the storage format and write rows t0..t0+n of sequence b."""
+        n = c64.shape[1]
+        c32 = c64.astype(np.float32)
+        codes = self.k if which == "k" else self.v
+        scale = self.k_scale if which == "k" else self.v_scale
+        zero = self.k_zero if which == "k" else self.v_zero
+        if self.dtype == "f32":
+            codes[b, :, t0:t0 + n] = c32
+        elif self.dtype == "bf16":
+            codes[b, :, t0:t0 + n] = bf16_bits_from_f32(c32)
+        elif self.dtype == "i8":
+            cq, s = quantize_int8_rows(c32)
+            codes[b, :, t0:t0 + n] = cq; scale[b, :, t0:t0 + n] = s
+        else:
+            cq, s, z = quantize_int4_rows(c32)
+            codes[b, :, t0:t0 + n] = cq; scale[b, :, t0:t0 + n] = s; zero[b, :, t0:t0 + n] = z
+
+
+def project_latents(x64: np.ndarray, A64: np.ndarray) -> np.ndarray:
+    """c[b,h,:] = sum_e x[b,e] A[h,e,:]  (C_Kh = X A_Kh, Section 3.1).  x [B,E], A [Hkv,E,r] -> [B,Hkv,r]."""
+    B, E = x64.shape
+    Hkv, E2, r = A64.shape
+    assert E == E2
+    out = np.empty((B, Hkv, r), np.float64)
+    for h in range(Hkv):
+        out[:, h, :] = x64 @ A64[h]
+    return out
+
+
+def latent_append(cache: LatentCache, x64: np.ndarray, AK64: np.ndarray, AV64: np.ndarray):
+    """Decode-step cache update (Section 3.4): project the new token of every sequence and
+    store its K and V latents at row seq_lens[b]; seq_lens[b] += 1.  A sequence already at
+    capacity is left untouched; the returned bool array flags those."""
+    cK = project_latents(x64, AK64)
+    cV = project_latents(x64, AV64)
+    overflow = np.zeros(cache.B, bool)
+    for b in range(cache.B):
+        n = int(cache.seq_lens[b])
+        if n >= cache.t_cap:
+            overflow[b] = True
+            continue
+        cache.store_rows("k", b, n, cK[b][:, None, :])
+        cache.store_rows("v", b, n, cV[b][:, None, :])
+        cache.seq_lens[b] = n + 1
+    return overflow
+
+
+def dequant_cache_rows(cache: LatentCache, which: str, b: int, kv: int, n: int) -> np.ndarray:
+    """fp64 value of the first n stored rows of one (sequence, kv head): [n, r]."""
+    codes = (cache.k if which == "k" else cache.v)[b, kv, :n]
+    if cache.dtype == "f32":
+        return codes.astype(np.float64)
+    if cache.dtype == "bf16":
+        return f64_from_bf16_bits(codes)
+    scale = (cache.k_scale if which == "k" else cache.v_scale)[b, kv, :n]
+    if cache.dtype == "i8":
+        return dequantize_int8_rows(codes, scale)
+    zero = (cache.k_zero if which == "k" else cache.v_zero)[b, kv, :n]
+    return dequantize_int4_rows(codes, scale, zero)
+
+
+# --------------------------------------------------------------------------- attention
+
+
+def softmax_weights(s: np.ndarray) -> np.ndarray:
+    """Max-subtracted softmax of a score vector in fp64."""
+    e = np.exp(s - np.max(s))
+    return e / np.sum(e)
+
+
+def _heads(q64, BK64):
+    B, Hq, d = q64.shape
+    Hkv = BK64.shape[0]
+    assert Hq % Hkv == 0
+    return B, Hq, d, Hkv, Hq // Hkv
+
+
+def decode_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndarray, BV64: np.ndarray,
+                              sm_scale: float, heads=None) -> np.ndarray:
+    """The definition: K = C_K B_K and V = C_V B_V materialised per head (Section 3.1 and the
+    naive schedule of Section 3.4), then o = softmax(sm_scale * q K^T) V.
+
+    q64 [B,Hq,d] fp64 (already dequantised), BK64/BV64 [Hkv,r,d].  Returns [B,Hq,d] fp64.
+    A sequence with no rows yields zeros.  ``heads`` optionally restricts the (b,h) pairs
+    computed (others are left as NaN) so that sampled outputs of a large case stay cheap.
+    """
+    B, Hq, d, Hkv, G = _heads(q64, BK64)
+    out = np.full((B, Hq, d), np.nan) if heads is not None else np.zeros((B, Hq, d))
+    pairs = heads if heads is not None else [(b, h) for b in range(B) for h in range(Hq)]
+    for (b, h) in pairs:
+        n = int(cache.seq_lens[b]); kv = h // G
+        if n == 0:
+            out[b, h] = 0.0
+            continue
+        K = dequant_cache_rows(cache, "k", b, kv, n) @ BK64[kv]      # [n,d]
+        V = dequant_cache_rows(cache, "v", b, kv, n) @ BV64[kv]      # [n,d]
+        s = sm_scale * (K @ q64[b, h])                               # [n]
+        p = softmax_weights(s)
+        out[b, h] = p @ V
+    return out
+
+
+def decode_attn_absorbed(cache: LatentCache, q64: np.ndarray, BK64: np.ndarray, BV64: np.ndarray,
+                         sm_scale: float, heads=None) -> np.ndarray:
+    """Same result by associativity: q~ = B_K q, s = C_K q~, u = p^T C_V, o = u B_V.
+    Used only to cross-check decode_attn_reconstructed (and, being ~d/2 times cheaper, to
+    extend sampled checks at the largest shapes after agreeing with it on a subset)."""
+    B, Hq, d, Hkv, G = _heads(q64, BK64)
+    out = np.full((B, Hq, d), np.nan) if heads is not None else np.zeros((B, Hq, d))
+    pairs = heads if heads is not None else [(b, h) for b in range(B) for h in range(Hq)]
+    for (b, h) in pairs:
+        n = int(cache.seq_lens[b]); kv = h // G
+        if n == 0:
+            out[b, h] = 0.0
+            continue
+        qt = BK64[kv] @ q64[b, h]                                    # [r]
+        s = sm_scale * (dequant_cache_rows(cache, "k", b, kv, n) @ qt)
+        p = softmax_weights(s)
+        u = p @ dequant_cache_rows(cache, "v", b, kv, n)             # [r]
+        out[b, h] = u @ BV64[kv]
+    return out
+
+
+# --------------------------------------------------------------------------- closed forms (Eq. 2, Eq. 3)
+
+
+def traffic_ratio(r: int, R: int) -> float:
+    """Eq. 2: gamma_wsvd / gamma_svd = eta_wsvd / eta_svd = r / R."""
+    return r / R
+
+
+def param_ratio_rho1(E: int, d_head: int, r: int) -> float:
+    """Eq. 3: rho_1 = (E + H) r / (E H) with H the head dimension."""
+    return (E + d_head) * r / (E * d_head)
+
+
+def cache_ratio_rho2(d_head: int, r: int) -> float:
+    """Eq. 3: rho_2 = r / H."""
+    return r / d_head
+
+
+def cache_row_bytes(rank: int, latent_dtype: str):
+    """(code bytes, metadata bytes) of one stored latent row."""
+    bits = {"f32": 32, "bf16": 16, "i8": 8, "i4": 4}[latent_dtype]
+    meta = {"f32": 0, "bf16": 0, "i8": 2, "i4": 4}[latent_dtype]
+    return rank * bits // 8, meta
+
+
+def latent_cache_bytes(seq_lens, n_kv_heads: int, rank: int, latent_dtype: str) -> int:
+    """Bytes of K plus V latent rows (codes and metadata) that one attention call must read."""
+    code, meta = cache_row_bytes(rank, latent_dtype)
+    return int(np.sum(np.asarray(seq_lens, dtype=np.int64))) * n_kv_heads * 2 * (code + meta)
+
+
+# --------------------------------------------------------------------------- W4A8 block (Section 4.2 formats)
+
+
+def quantize_act_i8(x32: np.ndarray):
+    """Per-token symmetric int8 of activation rows [M,K]: same rule as quantize_int8_rows."""
+    return quantize_int8_rows(x32)
+
+
+def pack_w4(w_codes: np.ndarray) -> np.ndarray:
+    """Signed int4 weight codes in [-8,7], shape [N,K] (one row per output channel, K even)
+    -> two's-complement nibbles, element 2i in the low nibble of byte i: uint8 [N,K/2]."""
+    w = np.asarray(w_codes).astype(np.int8)
+    assert w.min() >= -8 and w.max() <= 7
+    return pack_int4((w.astype(np.int16) & 0xF).astype(np.uint8))
+
+
+def unpack_w4(packed: np.ndarray) -> np.ndarray:
+    u = unpack_int4(packed).astype(np.int16)
+    return np.where(u >= 8, u - 16, u).astype(np.int8)
+
+
+def linear_w4a8_int_accum(x_codes: np.ndarray, w_packed: np.ndarray) -> np.ndarray:
+    """Exact integer accumulator acc[m,n] = sum_k x[m,k] * w[n,k] (int64)."""
+    w = unpack_w4(w_packed).astype(np.int64)        # [N,K]
+    return x_codes.astype(np.int64) @ w.T
+
+
+def linear_w4a8(x_codes, x_scale16, w_packed, w_scale16) -> np.ndarray:
+    """y[m,n] = acc[m,n] * s_x[m] * s_w[n] in fp64 (per-token activation scale, per-output-channel weight scale)."""
+    acc = linear_w4a8_int_accum(x_codes, w_packed).astype(np.float64)
+    sx = np.asarray(x_scale16, np.float16).astype(np.float64)[:, None]
+    sw = np.asarray(w_scale16, np.float16).astype(np.float64)[None, :]
+    return acc * sx * sw
+
+
+def attention_block_w4a8(cache: LatentCache, x_codes, x_scale16, wq_packed, wq_scale16,
+                         ak_packed, ak_scale16, av_packed, av_scale16,
+                         BK64, BV64, wo_packed, wo_scale16, n_q_heads, d_head, sm_scale, heads=None):
+    """One grouped-query attention block in the quantised setting of Section 4.2:
+    q = W4A8(x, W_Q); K/V latents of the new token = W4A8(x, A_K), W4A8(x, A_V), stored in
+    the cache; decode attention over the cache; o quantised per token to int8; y = W4A8(o, W_O).
+    ak_packed / av_packed are [Hkv*r, E/2] with output channel index kv*r + j.
+    Returns dict with q, cK, cV (fp64), attn (fp64 [B,Hq,d]), o_codes, o_scale, y (fp64)."""
+    B = x_codes.shape[0]
+    q = linear_w4a8(x_codes, x_scale16, wq_packed, wq_scale16).reshape(B, n_q_heads, d_head)
+    cK = linear_w4a8(x_codes, x_scale16, ak_packed, ak_scale16).reshape(B, cache.Hkv, cache.r)
+    cV = linear_w4a8(x_codes, x_scale16, av_packed, av_scale16).reshape(B, cache.Hkv, cache.r)
+    for b in range(B):
+        n = int(cache.seq_lens[b])
+        cache.store_rows("k", b, n, cK[b][:, None, :])
+        cache.store_rows("v", b, n, cV[b][:, None, :])
+        cache.seq_lens[b] = n + 1
+    # the query enters attention in the precision it leaves the projection with (fp32)
+    q32 = q.astype(np.float32).astype(np.float64)
+    attn = decode_attn_reconstructed(cache, q32, BK64, BV64, sm_scale, heads=heads)
+    res = {"q": q, "cK": cK, "cV": cV, "attn": attn}
+    if heads is None:
+        o_codes, o_scale = quantize_act_i8(attn.reshape(B, n_q_heads * d_head).astype(np.float32))
+        res["o_codes"], res["o_scale"] = o_codes, o_scale
+        res["y"] = linear_w4a8(o_codes, o_scale, wo_packed, wo_scale16)
+    return res

@@ -1,0 +1,347 @@
+"""Pins for the CPU oracle: each checks it against something other than itself (a library
+routine, a closed form, a hand-computed tiny case, an invariant, a value the paper prints)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from conftest import read_golden
+
+
+def _rand_cache(rng, B, Hkv, n, r, dtype, t_cap=None, scale=1.0):
+    t_cap = t_cap or n
+    c = O.LatentCache(B, Hkv, t_cap, r, dtype)
+    for b in range(B):
+        c.store_rows("k", b, 0, rng.standard_normal((Hkv, n, r)) * scale)
+        c.store_rows("v", b, 0, rng.standard_normal((Hkv, n, r)) * scale)
+        c.seq_lens[b] = n
+    return c
+
+
+# ---- P1: identity factors with r = d reduce to library attention (torch fp64) -------------
+@pytest.mark.parametrize("G", [1, 2])
+def test_identity_factors_equal_library_attention(G):
+    rng = np.random.default_rng(1)
+    B, Hkv, n, d = 2, 3, 37, 8
+    Hq = Hkv * G
+    cache = _rand_cache(rng, B, Hkv, n, d, "f32")
+    q = rng.standard_normal((B, Hq, d))
+    I = np.broadcast_to(np.eye(d), (Hkv, d, d)).copy()
+    sm = 0.31
+    got = O.decode_attn_reconstructed(cache, q, I, I, sm)
+    K = torch.from_numpy(cache.k[:, :, :n].astype(np.float64)).repeat_interleave(G, dim=1)  # kv(h) = h // G
+    V = torch.from_numpy(cache.v[:, :, :n].astype(np.float64)).repeat_interleave(G, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[:, :, None, :], K, V, scale=sm)[:, :, 0].numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_general_factors_equal_library_attention_on_reconstructed_kv():
+    """K = C B_K, V = C B_V formed with torch, attention by torch: pins the association and head indexing."""
+    rng = np.random.default_rng(2)
+    B, Hkv, G, n, r, d = 2, 2, 3, 21, 4, 6
+    cache = _rand_cache(rng, B, Hkv, n, r, "f32")
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    q = rng.standard_normal((B, Hkv * G, d))
+    got = O.decode_attn_reconstructed(cache, q, BK, BV, 0.5)
+    CK = torch.from_numpy(cache.k[:, :, :n].astype(np.float64)); CV = torch.from_numpy(cache.v[:, :, :n].astype(np.float64))
+    K = torch.einsum("bhtr,hrd->bhtd", CK, torch.from_numpy(BK)).repeat_interleave(G, dim=1)
+    V = torch.einsum("bhtr,hrd->bhtd", CV, torch.from_numpy(BV)).repeat_interleave(G, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[:, :, None, :], K, V, scale=0.5)[:, :, 0].numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-13)
+
+
+# ---- P2: absorbed == reconstructed ---------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i8", "i4"])
+def test_absorbed_equals_reconstructed(dtype):
+    rng = np.random.default_rng(3)
+    B, Hkv, G, n, r, d = 2, 2, 2, 50, 32, 16
+    cache = _rand_cache(rng, B, Hkv, n, r, dtype, t_cap=64)
+    cache.seq_lens[1] = 17
+    BK = rng.standard_normal((Hkv, r, d)) / np.sqrt(r); BV = rng.standard_normal((Hkv, r, d)) / np.sqrt(r)
+    q = rng.standard_normal((B, Hkv * G, d))
+    a = O.decode_attn_reconstructed(cache, q, BK, BV, d ** -0.5)
+    b = O.decode_attn_absorbed(cache, q, BK, BV, d ** -0.5)
+    np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)
+
+
+# ---- P3: softmax rows sum to one ----------------------------------------------------------
+def test_softmax_sums_to_one_and_matches_scipy():
+    from scipy.special import softmax
+    rng = np.random.default_rng(4)
+    s = rng.standard_normal(1000) * 30
+    p = O.softmax_weights(s)
+    assert abs(p.sum() - 1) < 1e-14 and (p >= 0).all()
+    np.testing.assert_allclose(p, softmax(s), rtol=1e-12, atol=0)
+
+
+# ---- P4: a single cached token returns that token's V -------------------------------------
+def test_single_token_returns_its_value():
+    rng = np.random.default_rng(5)
+    B, Hkv, r, d = 2, 2, 4, 5
+    cache = _rand_cache(rng, B, Hkv, 1, r, "f32", t_cap=3)
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    q = rng.standard_normal((B, Hkv, d)) * 7
+    got = O.decode_attn_reconstructed(cache, q, BK, BV, 1.0)
+    for b in range(B):
+        for h in range(Hkv):
+            np.testing.assert_allclose(got[b, h], cache.v[b, h, 0].astype(np.float64) @ BV[h], rtol=1e-13)
+
+
+# ---- P5: zero query gives the mean value row ---------------------------------------------
+def test_zero_query_gives_mean_value():
+    rng = np.random.default_rng(6)
+    B, Hkv, n, r, d = 1, 2, 13, 4, 5
+    cache = _rand_cache(rng, B, Hkv, n, r, "f32")
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    got = O.decode_attn_reconstructed(cache, np.zeros((B, Hkv, d)), BK, BV, 1.0)
+    for h in range(Hkv):
+        V = cache.v[0, h, :n].astype(np.float64) @ BV[h]
+        np.testing.assert_allclose(got[0, h], V.mean(axis=0), rtol=1e-12)
+
+
+# ---- P6: two tokens, r = d = 1, by hand -----------------------------------------------------
+def test_two_token_scalar_case_by_hand():
+    import math
+    cache = O.LatentCache(1, 1, 2, 1, "f32")
+    cache.store_rows("k", 0, 0, np.array([[[0.5], [-1.25]]]))
+    cache.store_rows("v", 0, 0, np.array([[[2.0], [3.0]]]))
+    cache.seq_lens[0] = 2
+    bk, bv, q, sm = 1.5, -0.5, 0.75, 2.0
+    got = O.decode_attn_reconstructed(cache, np.array([[[q]]]), np.array([[[bk]]]), np.array([[[bv]]]), sm)[0, 0, 0]
+    s1 = sm * q * (0.5 * bk); s2 = sm * q * (-1.25 * bk)
+    v1 = 2.0 * bv; v2 = 3.0 * bv
+    want = (math.exp(s1) * v1 + math.exp(s2) * v2) / (math.exp(s1) + math.exp(s2))
+    assert abs(got - want) < 1e-14
+
+
+# ---- P7: permuting cache rows (K and V together) leaves the output unchanged ---------------
+def test_row_permutation_invariance():
+    rng = np.random.default_rng(7)
+    B, Hkv, n, r, d = 1, 2, 40, 8, 8
+    cache = _rand_cache(rng, B, Hkv, n, r, "i8")
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d)); q = rng.standard_normal((B, Hkv, d))
+    a = O.decode_attn_reconstructed(cache, q, BK, BV, 0.3)
+    perm = rng.permutation(n)
+    for name in ("k", "v", "k_scale", "v_scale"):
+        arr = getattr(cache, name)
+        arr[:, :, :n] = arr[:, :, perm]
+    b = O.decode_attn_reconstructed(cache, q, BK, BV, 0.3)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+# ---- P8: huge scores stay finite and select the arg-max row ---------------------------------
+def test_large_scores_select_argmax():
+    rng = np.random.default_rng(8)
+    B, Hkv, n, r, d = 1, 1, 30, 4, 4
+    cache = _rand_cache(rng, B, Hkv, n, r, "f32")
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d)); q = rng.standard_normal((B, Hkv, d))
+    got = O.decode_attn_reconstructed(cache, q, BK, BV, 1e4)
+    K = cache.k[0, 0, :n].astype(np.float64) @ BK[0]; V = cache.v[0, 0, :n].astype(np.float64) @ BV[0]
+    t = int(np.argmax(K @ q[0, 0]))
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got[0, 0], V[t], rtol=1e-9)
+
+
+# ---- sequence of length zero ---------------------------------------------------------------
+def test_empty_sequence_gives_zeros():
+    cache = O.LatentCache(2, 1, 4, 2, "f32")
+    cache.store_rows("k", 1, 0, np.ones((1, 1, 2))); cache.store_rows("v", 1, 0, np.ones((1, 1, 2))); cache.seq_lens[1] = 1
+    out = O.decode_attn_reconstructed(cache, np.ones((2, 1, 3)), np.ones((1, 2, 3)), np.ones((1, 2, 3)), 1.0)
+    assert (out[0] == 0).all() and np.allclose(out[1], 2.0)
+
+
+# ---- P9: quantiser invariants -----------------------------------------------------------------
+def test_int8_quantiser_round_trip_and_ranges():
+    rng = np.random.default_rng(9)
+    c = (rng.standard_normal((500, 32)) * np.exp(rng.standard_normal((500, 1)) * 3)).astype(np.float32)
+    c[0] = 0; c[1, 5] = 1e-9; c[2] *= 1e6
+    codes, s = O.quantize_int8_rows(c)
+    assert codes.dtype == np.int8 and s.dtype == np.float16
+    assert codes.min() >= -127 and codes.max() <= 127
+    assert (codes[0] == 0).all() and s[0] == np.float16(1.0)
+    deq = O.dequantize_int8_rows(codes, s)
+    sf = s.astype(np.float64)
+    # one-step round trip holds where the fp16 scale is a normal number (relative rounding error <= 2^-11);
+    # a saturated scale clamps, and a subnormal scale can under-represent a/127 by more than 1/127
+    ok = (sf < 65504) & (sf >= 2.0 ** -14)
+    assert ok.sum() > 300
+    assert (np.abs(deq - c)[ok] <= sf[ok, None] * 1.0000001 + 0).all()
+    # typical rows: the abs-max element lands on +-127
+    amax = np.argmax(np.abs(c), axis=1)
+    typical = ok & (np.abs(c).max(axis=1) > 1e-3)
+    assert (np.abs(codes[np.arange(500), amax])[typical] == 127).all()
+    # half-step error away from the clamp
+    inner = np.abs(codes) < 127
+    assert (np.abs(deq - c)[inner & ok[:, None]] <= 0.5000001 * np.broadcast_to(sf[:, None], c.shape)[inner & ok[:, None]]).all()
+
+
+def test_int8_quantiser_rounds_half_to_even_and_uses_rounded_scale():
+    # a = 127 -> s = 1 exactly; values k + 0.5 must go to the even neighbour
+    c = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.49]], np.float32)
+    codes, s = O.quantize_int8_rows(c)
+    assert s[0] == np.float16(1.0)
+    assert codes[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 3]
+    # a/127 not representable in fp16: the division must use the fp16-rounded scale
+    c = np.array([[1000.0, 3.9375, 7.8740234, 500.0]], np.float32)
+    codes, s = O.quantize_int8_rows(c)
+    s_expect = np.float16(np.float32(1000.0) / np.float32(127.0))
+    assert s[0] == s_expect
+    assert codes[0].tolist() == [int(np.clip(np.rint(np.float32(v) / np.float32(s_expect)), -127, 127)) for v in c[0]]
+    assert codes[0, 0] == 127
+
+
+def test_int4_quantiser_invariants():
+    rng = np.random.default_rng(10)
+    c = (rng.standard_normal((400, 32)) * np.exp(rng.standard_normal((400, 1)) * 2) + rng.standard_normal((400, 1))).astype(np.float32)
+    c[0] = 0; c[1] = np.abs(c[1]); c[2] = -np.abs(c[2])
+    packed, s, z = O.quantize_int4_rows(c)
+    assert packed.shape == (400, 16) and packed.dtype == np.uint8
+    codes = O.unpack_int4(packed)
+    assert codes.max() <= 15
+    assert (codes[0] == 0).all() and s[0] == 1 and z[0] == 0
+    zf = z.astype(np.float64)
+    assert (zf == np.rint(zf)).all() and zf.min() >= 0 and zf.max() <= 15
+    assert z[1] == 0                         # all-positive row: range starts at 0
+    assert z[2] == 15                        # all-negative row: zero maps to the top code
+    deq = O.dequantize_int4_rows(packed, s, z)
+    sf = s.astype(np.float64)
+    assert (np.abs(deq - c) <= sf[:, None] * 1.0000001).all()
+    rows = np.arange(400)
+    lo_idx = np.argmin(c, axis=1); hi_idx = np.argmax(c, axis=1)
+    has_neg = c.min(axis=1) < 0
+    assert (codes[rows, lo_idx][has_neg] <= 1).all()
+    has_pos = c.max(axis=1) > 0
+    assert (codes[rows, hi_idx][has_pos] >= 14).all()
+
+
+def test_int4_hand_case():
+    # lo = -3, hi = 12 -> s = 1, z = 3; ties to even on c/s
+    c = np.array([[-3.0, 12.0, 0.0, 0.5, 1.5, 2.5, -0.5, 7.0]], np.float32)
+    packed, s, z = O.quantize_int4_rows(c)
+    assert s[0] == 1 and z[0] == 3
+    assert O.unpack_int4(packed)[0].tolist() == [0, 15, 3, 3, 5, 5, 3, 10]
+    assert packed[0].tolist() == [0 | (15 << 4), 3 | (3 << 4), 5 | (5 << 4), 3 | (10 << 4)]
+
+
+# ---- P10: nibble packing, exhaustive -------------------------------------------------------
+def test_nibble_pack_exhaustive_and_order():
+    allb = np.arange(256, dtype=np.uint8)[:, None]
+    un = O.unpack_int4(allb)
+    assert (un[:, 0] == (allb[:, 0] & 15)).all() and (un[:, 1] == (allb[:, 0] >> 4)).all()
+    assert (O.pack_int4(un) == allb).all()
+    w = np.arange(-8, 8, dtype=np.int8)[None, :]
+    assert (O.unpack_w4(O.pack_w4(w)) == w).all()
+    assert O.pack_w4(np.array([[-1, 2]], np.int8))[0, 0] == (0xF | (2 << 4))
+
+
+def test_bf16_rounding_against_torch():
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal(20000) * np.exp(rng.standard_normal(20000) * 5)).astype(np.float32)
+    x[:4] = [1.00390625, 1.01171875, -1.00390625, 0.0]        # exact ties: to even
+    bits = O.bf16_bits_from_f32(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (bits == ref).all()
+    back = O.f64_from_bf16_bits(bits)
+    assert (back == torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()).all()
+
+
+# ---- P11: integer GEMM is exact ---------------------------------------------------------------
+def test_w4a8_linear_exact_and_scaled():
+    rng = np.random.default_rng(12)
+    M, K, N = 3, 64, 5
+    x = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    w = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    sx = np.array([0.5, 0.25, 2.0], np.float16); sw = (rng.random(N) + 0.5).astype(np.float16)
+    acc = O.linear_w4a8_int_accum(x, O.pack_w4(w))
+    brute = np.array([[sum(int(x[m, k]) * int(w[n, k]) for k in range(K)) for n in range(N)] for m in range(M)])
+    assert (acc == brute).all()
+    y = O.linear_w4a8(x, sx, O.pack_w4(w), sw)
+    np.testing.assert_allclose(y, brute * sx.astype(np.float64)[:, None] * sw.astype(np.float64)[None, :], rtol=1e-15)
+
+
+# ---- P12: closed forms and the values the paper prints -------------------------------------
+def test_closed_forms_match_paper_values():
+    g = read_golden("paper_printed_values.txt")
+    v, tol, _ = g["rho2_at_r64_d128"]
+    assert abs(O.cache_ratio_rho2(128, 64) - v) <= tol
+    v, tol, _ = g["rho1_at_r64_d128_E4096"]
+    assert abs(O.param_ratio_rho1(4096, 128, 64) - v) <= tol
+    assert abs(O.param_ratio_rho1(4096, 128, 64) - (1 + 128 / 4096) * 0.5) < 1e-15
+    v, tol, _ = g["cache_fraction_int8_rho2_half"]
+    code, _meta = O.cache_row_bytes(64, "i8")
+    assert abs(code / (128 * 2) - v) <= tol                 # latent codes vs an fp16 K (or V) row of the head
+    assert O.traffic_ratio(64, 2048) == 64 / 2048           # Eq. 2
+    # byte accounting used for the roofline: config-3 shape
+    assert O.latent_cache_bytes([2048] * 16, 32, 32, "i8") == 71303168
+    assert O.latent_cache_bytes([257], 8, 16, "f32") == 263168
+    assert O.cache_row_bytes(32, "i4") == (16, 4)
+
+
+# ---- P13: one-hot token reproduces a row of A ---------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_hot_token_appends_row_of_A(dtype):
+    rng = np.random.default_rng(13)
+    B, Hkv, E, r = 2, 3, 10, 4
+    AK = rng.standard_normal((Hkv, E, r)).astype(np.float32); AV = rng.standard_normal((Hkv, E, r)).astype(np.float32)
+    cache = O.LatentCache(B, Hkv, 5, r, dtype)
+    cache.seq_lens[:] = [2, 0]
+    x = np.zeros((B, E)); x[0, 7] = 1.0; x[1, 3] = 1.0
+    ov = O.latent_append(cache, x, AK.astype(np.float64), AV.astype(np.float64))
+    assert not ov.any() and cache.seq_lens.tolist() == [3, 1]
+    for b, e, t in ((0, 7, 2), (1, 3, 0)):
+        for h in range(Hkv):
+            wantk, wantv = AK[h, e], AV[h, e]
+            if dtype == "bf16":
+                np.testing.assert_array_equal(cache.k[b, h, t], O.bf16_bits_from_f32(wantk))
+                np.testing.assert_array_equal(cache.v[b, h, t], O.bf16_bits_from_f32(wantv))
+            else:
+                np.testing.assert_array_equal(cache.k[b, h, t], wantk); np.testing.assert_array_equal(cache.v[b, h, t], wantv)
+    # untouched rows stay zero; capacity overflow is flagged and leaves the cache alone
+    assert (cache.k[0, :, 3:] == 0).all()
+    cache.seq_lens[:] = [5, 1]
+    before = cache.k.copy()
+    ov = O.latent_append(cache, x, AK.astype(np.float64), AV.astype(np.float64))
+    assert ov.tolist() == [True, False] and cache.seq_lens.tolist() == [5, 2]
+    assert (cache.k[0] == before[0]).all()
+
+
+def test_projection_matches_einsum():
+    rng = np.random.default_rng(14)
+    x = rng.standard_normal((3, 11)); A = rng.standard_normal((4, 11, 5))
+    np.testing.assert_allclose(O.project_latents(x, A), np.einsum("be,her->bhr", x, A), rtol=1e-13)
+
+
+def test_append_quantised_matches_quantiser_of_projection():
+    rng = np.random.default_rng(15)
+    B, Hkv, E, r = 2, 2, 16, 32
+    AK = rng.standard_normal((Hkv, E, r)); AV = rng.standard_normal((Hkv, E, r)); x = rng.standard_normal((B, E))
+    for dtype in ("i8", "i4"):
+        cache = O.LatentCache(B, Hkv, 2, r, dtype)
+        O.latent_append(cache, x, AK, AV)
+        c32 = np.einsum("be,her->bhr", x, AK).astype(np.float32)
+        if dtype == "i8":
+            codes, s = O.quantize_int8_rows(c32)
+            assert (cache.k[:, :, 0] == codes).all() and (cache.k_scale[:, :, 0] == s).all()
+        else:
+            codes, s, z = O.quantize_int4_rows(c32)
+            assert (cache.k[:, :, 0] == codes).all() and (cache.k_scale[:, :, 0] == s).all() and (cache.k_zero[:, :, 0] == z).all()
+
+
+def test_attention_block_w4a8_consistency():
+    """The block composes the pinned pieces: q and latents are the W4A8 products, y is W4A8 of quantised attention."""
+    rng = np.random.default_rng(16)
+    B, Hq, Hkv, d, r, E, n = 2, 4, 2, 8, 4, 32, 9
+    cache = _rand_cache(rng, B, Hkv, n, r, "i8", t_cap=n + 1)
+    xq, xs = O.quantize_act_i8(rng.standard_normal((B, E)).astype(np.float32))
+    def w(nout):
+        return O.pack_w4(rng.integers(-8, 8, (nout, E)).astype(np.int8)), (rng.random(nout) * 0.1 + 0.05).astype(np.float16)
+    wq, wqs = w(Hq * d); ak, aks = w(Hkv * r); av, avs = w(Hkv * r)
+    wo = O.pack_w4(rng.integers(-8, 8, (E, Hq * d)).astype(np.int8)); wos = (rng.random(E) * 0.1 + 0.05).astype(np.float16)
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    res = O.attention_block_w4a8(cache, xq, xs, wq, wqs, ak, aks, av, avs, BK, BV, wo, wos, Hq, d, d ** -0.5)
+    assert cache.seq_lens.tolist() == [n + 1] * B
+    codes, s = O.quantize_int8_rows(res["cK"].astype(np.float32))
+    assert (cache.k[:, :, n] == codes).all()
+    q32 = res["q"].astype(np.float32).astype(np.float64)
+    np.testing.assert_allclose(res["attn"], O.decode_attn_absorbed(cache, q32, BK, BV, d ** -0.5), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(res["y"], O.linear_w4a8(res["o_codes"], res["o_scale"], wo, wos), rtol=0)
