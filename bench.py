@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the WSVD decode hot path on one MI355X.
+
+A step is one pass of the whole path on the batched int8 workload (16 sequences x 32 heads, head dim 128,
+per-head rank 32, 2048 cached tokens, int8 latents with one fp16 scale per token per head, int8 queries):
+latent append of the new token (projection, quantise, store) followed by decode attention (query absorption,
+score pass, online softmax, value pass, split merge, B_V epilogue).  All inputs are resident in HBM before the
+timed region; consecutive steps rotate over distinct cache sets whose total size exceeds the 256 MB last-level
+cache, so the latent stream comes from HBM.
+
+Prints ONE JSON line.  `value` = latent-cache bytes one step must read / time of one step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy kernel of known
+# size; see profiles/.  None until measured for the current kernel.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=320)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--sets", type=int, default=16, help="distinct cache sets rotated through (cold HBM)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (every box has one MI355X); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2604_02570_amd as W
+    import wsvd_inputs as WI
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    W.lib()   # fails loudly if the HIP library is missing
+
+    sp = WI.spec("c3")
+    B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
+    n_sets = max(1, args.sets)
+    total_steps = args.warmup + args.steps
+    visits = (total_steps + n_sets - 1) // n_sets
+    t_cap = (T + visits + 63) // 64 * 64
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "i8", "f32", 0.0)
+    ctx = W.wsvd_create(0)
+    ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(ctx, ws)
+    cb, mb = W.wsvd_cache_bytes(desc)
+
+    def bf16_bits(x32):
+        return torch.from_numpy((np.ascontiguousarray(x32, np.float32).view(np.uint32) >> 16).astype(np.uint16).view(np.int16)).cuda()
+
+    # ---- factors, hidden state of the new token, queries (generator), all made resident
+    AK, AV, BK, BV = WI.factors(sp)
+    AKd, AVd, BKd, BVd = (bf16_bits(a) for a in (AK, AV, BK, BV))
+    x_new = WI.hidden_states(sp, B, 1.0, which="new")                     # bf16-exact fp32 [B,E]
+    xd = bf16_bits(x_new)
+    q32 = (x_new.astype(np.float64) @ WI.dense_wq(sp).astype(np.float64)).astype(np.float32)      # [B, Hq*d]
+    q32d = torch.from_numpy(q32).cuda()
+    qd = torch.empty((B, Hq * d), dtype=torch.int8, device="cuda")
+    qsd = torch.empty(B, dtype=torch.int16, device="cuda")
+    W.wsvd_quantize_act_i8(ctx, q32d, "f32", B, Hq * d, qd, qsd)
+
+    # ---- context latents -> the library's own quantiser -> device layout (set 0), then cloned into the other sets
+    T0 = T - 1            # the timed step appends one token, so attention runs over T rows on the first visit
+    k0 = torch.zeros(cb, dtype=torch.uint8, device="cuda"); v0 = torch.zeros(cb, dtype=torch.uint8, device="cuda")
+    km0 = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm0 = torch.zeros(mb, dtype=torch.uint8, device="cuda")
+    sl0 = torch.full((B,), T0, dtype=torch.int32, device="cuda")
+    cache0 = W.make_cache(k0, v0, km0, vm0, sl0)
+    for which, A, plane in (("k", AK, 0), ("v", AV, 1)):
+        lat = np.stack([WI.latents_from_law(sp, A, which, b, T0) for b in range(B)])          # [B,Hkv,T0,r] fp32
+        latd = torch.from_numpy(lat).cuda()
+        codes = torch.empty((B * Hkv * T0, r), dtype=torch.int8, device="cuda")
+        meta = torch.empty(B * Hkv * T0, dtype=torch.int16, device="cuda")
+        W.wsvd_quantize_rows(ctx, desc, latd, B * Hkv * T0, codes, meta)
+        W.wsvd_cache_import(ctx, desc, plane, codes, meta, 0, T0, cache0)
+    assert W.wsvd_check(ctx) == 0
+    sets = [(k0, v0, km0, vm0, sl0, cache0)]
+    for _ in range(n_sets - 1):
+        t = [x.clone() for x in (k0, v0, km0, vm0, sl0)]
+        sets.append((*t, W.make_cache(*t)))
+    outs = [torch.empty((B, Hq, d), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
+    torch.cuda.synchronize()
+
+    def step(i):
+        s = sets[i % n_sets]
+        if not args.attn_only:
+            W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, s[5])
+        W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+
+    def attn_only(i):
+        s = sets[i % n_sets]
+        W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+
+    # rows attended at timed step i: T0 + (number of appends that set has seen so far)
+    def rows_at(i):
+        return T0 + (0 if args.attn_only else i // n_sets + 1)
+
+    stream = torch.cuda.Stream()
+    use_graph = not args.no_graph
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(i)
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(args.warmup, total_steps):
+                    step(i)
+            stream.synchronize()
+            torch.cuda.synchronize()
+            t_wall0 = time.perf_counter()
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            stream.synchronize()
+            torch.cuda.synchronize()
+            t_wall1 = time.perf_counter()
+        else:
+            torch.cuda.synchronize()
+            t_wall0 = time.perf_counter()
+            e0.record(stream)
+            for i in range(args.warmup, total_steps):
+                step(i)
+            e1.record(stream)
+            stream.synchronize()
+            torch.cuda.synchronize()
+            t_wall1 = time.perf_counter()
+        ms_total = e0.elapsed_time(e1)
+        assert W.wsvd_check(ctx, stream) == 0
+        seq_after = [int(s[4][0]) for s in sets]
+
+        # ---- dominant kernel alone: decode attention, back-to-back launches, HIP events on the launch stream
+        n_attn = max(args.steps, 64)
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(n_sets):
+            attn_only(i)
+        stream.synchronize()
+        if use_graph:
+            ga = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(ga, stream=stream):
+                for i in range(n_attn):
+                    attn_only(i)
+            stream.synchronize()
+            a0.record(stream); ga.replay(); a1.record(stream)
+        else:
+            a0.record(stream)
+            for i in range(n_attn):
+                attn_only(i)
+            a1.record(stream)
+        stream.synchronize()
+        attn_us = a0.elapsed_time(a1) * 1e3 / n_attn
+        assert W.wsvd_check(ctx, stream) == 0
+
+    row_bytes = Hkv * 2 * (r + 2)                         # K and V code rows plus their fp16 scales, all kv heads
+    bytes_steps = sum(B * rows_at(i) * row_bytes for i in range(args.warmup, total_steps))
+    bytes_per_step = bytes_steps / args.steps
+    ms_per_step = ms_total / args.steps
+    value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    rows_attn = [int(s[4][0]) for s in sets]
+    attn_bytes = sum(B * rows_attn[i % n_sets] * row_bytes for i in range(n_attn)) / n_attn
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+
+    res = {
+        "metric": "latent_kv_hbm_GBps_per_decode_step",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "us_per_decode_step": round(ms_per_step * 1e3, 3),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "i8",
+        "data": "synthetic",
+        "config": {
+            "workload": "c3: batched int8 decode step (append + attention), B=16 H=32 d_head=128 d_model=4096 r=32 T=2048",
+            "batch": B, "heads": Hq, "d_head": d, "d_model": E, "rank": r, "context": T,
+            "context_drift_rows": max(seq_after) - T,
+            "cache_sets_rotated": n_sets, "cache_set_MB": round(2 * (cb + mb) / 1e6, 1),
+            "launch": "hip_graph_replay" if use_graph else "eager",
+            "step": "attention only" if args.attn_only else "wsvd_latent_append + wsvd_decode_attn",
+            "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / args.steps, 6),
+        },
+        "roofline": {
+            "kernel": "k_attn_mfma<32,1,false> (decode attention over int8 latents)",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "algorithmic_bytes_per_launch": int(attn_bytes),
+            "avg_launch_us": round(attn_us, 3),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(np, row_bytes)
+    print(json.dumps(res))
+    W.wsvd_destroy(ctx)
+
+
+def cpu_baseline(np, row_bytes):
+    """The fp64 oracle, as it stands, on the same workload: one decode step (append + attention) on the host cores."""
+    import oracle as O
+    from cases import build_case
+    import wsvd_inputs as WI
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    c = build_case("c3")
+    sp = c.sp
+    AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
+    x = WI.bf16_exact(c.x_new[0]).astype(np.float64)
+    codes, s = O.quantize_act_i8(c.q32[0].reshape(sp.batch, -1))
+    q64 = (codes.astype(np.float64) * s.astype(np.float64)[:, None]).reshape(c.q32[0].shape)
+    reps = 0
+    t0 = time.perf_counter()
+    while True:
+        c.cache.seq_lens[:] = sp.context - 1
+        O.latent_append(c.cache, x, AK64, AV64)
+        O.decode_attn_reconstructed(c.cache, q64, BK64, BV64, c.sm_scale)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > 10.0 or reps >= 20:
+            break
+    per_step = dt / reps
+    nbytes = sp.batch * sp.context * row_bytes
+    return {"value": round(nbytes / per_step / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"the whole c3 step (append + attention over all {sp.batch * sp.n_q_heads} sequence-heads), "
+                      f"{reps} repetitions, {per_step * 1e3:.1f} ms per step",
+            "us_per_decode_step": round(per_step * 1e6, 1)}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,194 @@
+/*
+ * wsvd.h - C ABI of the MI355X (gfx950) WSVD decode library.
+ *
+ * The library implements the decode-stage hot path of WSVD: single-token attention over a
+ * per-head low-rank latent KV cache.  For head h the cache holds C_Kh = X A_Kh and
+ * C_Vh = X A_Vh (Section 3.1 of the paper, per-head decomposition W_Kh = A_Kh B_Kh), keys and
+ * values are K_h = C_Kh B_Kh, V_h = C_Vh B_Vh, and the fused decode kernel of Section 3.4
+ * consumes the latent tiles in place.  Here B_Kh is folded into the query and B_Vh is applied
+ * after the weighted sum of value latents, so each head's latent stream is read from HBM once.
+ *
+ * Conventions
+ *  - Every pointer named below is a DEVICE pointer unless it says HOST.  All buffers are owned
+ *    by the caller; the library allocates only in wsvd_create (one error word) and never in a
+ *    hot call.  Device pointers must be 16-byte aligned.
+ *  - Hot calls enqueue on the caller's HIP stream (passed as void*, NULL = default stream) and
+ *    return without synchronising.  One context per stream; calls on one context that overlap
+ *    in time race on its workspace.
+ *  - Errors detectable on the host (NULL, unsupported shape / dtype, misalignment, workspace
+ *    too small) return a non-zero status and enqueue nothing.  Conditions only the device can
+ *    see (a sequence already at capacity on append) are recorded in the context's error word and
+ *    reported by wsvd_check.
+ *  - Head mapping for grouped-query attention: kv(h) = h / (n_q_heads / n_kv_heads).
+ *  - bf16 / fp16 values are raw 16-bit patterns.
+ *
+ * Supported set: d_head in {64,128}; rank in {16,32,64}; n_q_heads / n_kv_heads in 1..8;
+ *   latent F32  : factors, x, q F32; any rank above.
+ *   latent BF16 : factors, x, q BF16.
+ *   latent I8   : rank 32 or 64; factors BF16; x BF16 or F32; q I8 (+fp16 scale per token), F32 or BF16.
+ *   latent I4   : rank 32; otherwise as I8.
+ *   out F32.  t_cap must be a multiple of 64.
+ */
+#ifndef WSVD_H
+#define WSVD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct wsvd_ctx wsvd_ctx; /* opaque: device ordinal, error word, caller-provided workspace */
+
+typedef enum {
+  WSVD_OK = 0,
+  WSVD_E_NULL = 1,        /* a required pointer is NULL */
+  WSVD_E_SHAPE = 2,       /* a size is out of the supported set or inconsistent */
+  WSVD_E_DTYPE = 3,       /* dtype combination not supported */
+  WSVD_E_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
+  WSVD_E_CAPACITY = 5,    /* a sequence was at t_cap on append (device-detected), or max_seq_len > t_cap */
+  WSVD_E_UNSUPPORTED = 6, /* valid request this build does not implement */
+  WSVD_E_HIP = 7,         /* a HIP runtime call failed */
+  WSVD_E_WORKSPACE = 8    /* workspace missing or too small */
+} wsvd_status;
+
+typedef enum { WSVD_F32 = 0, WSVD_BF16 = 1, WSVD_F16 = 2, WSVD_I8 = 3, WSVD_I4 = 4 } wsvd_dtype;
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, d_head, d_model, rank; /* rank = r_K = r_V (uniform per-head rank) */
+  int32_t t_cap;        /* rows of capacity per (sequence, kv head); multiple of 64 */
+  int32_t latent_dtype; /* F32 | BF16 | I8 (symmetric, fp16 scale per row) | I4 (asymmetric, fp16 scale + zero point per row) */
+  int32_t factor_dtype; /* dtype of A_K, A_V, B_K, B_V */
+  int32_t x_dtype;      /* dtype of the hidden state given to wsvd_latent_append */
+  int32_t q_dtype;      /* dtype of the query given to wsvd_decode_attn; I8 carries one fp16 scale per token */
+  int32_t out_dtype;    /* F32 */
+  float sm_scale;       /* softmax scale; 0 means 1/sqrt(d_head) */
+} wsvd_layer_desc;
+
+/*
+ * The latent cache (Section 3.1: C_Kh, C_Vh of shape L x r per head), one K plane and one V plane.
+ * Logical content: row t of kv head h of sequence b, t < seq_lens[b].
+ *
+ * DEVICE layout of the code planes.  F32 / BF16: row-major [B, Hkv, t_cap, rank].
+ * I8 / I4: each block of tokens is stored as the register image of the gfx950 MFMA operand it
+ * feeds, so a wavefront's 64 x 16-byte load IS the operand (no unpack, no shuffle):
+ *   I8, K plane: per (b,h) blocks of 32 tokens, rank*32 bytes each; byte of (token n, dim j) at
+ *        ((j/32*2 + (j%32)/16)*32 + n)*16 + j%16
+ *   I8, V plane: same block size; byte of (token n, dim j) at
+ *        ((j/32*2 + n/16)*32 + j%32)*16 + n%16          (token-minor: the contraction runs over tokens)
+ *   I4 (rank 32), K plane: blocks of 64 tokens, 1024 bytes; token tt = slot*32 + n, dims (j, j+1) share a byte:
+ *        (j/16)*512 + n*16 + slot*8 + (j%16)/2, low nibble = even j
+ *   I4, V plane: blocks of 64 tokens; tokens (tt, tt+1) share a byte:
+ *        ((tt/32)*32 + j)*16 + (tt%32)/2, low nibble = even tt
+ * Callers never need these formulas: wsvd_cache_import / wsvd_cache_export convert from / to the
+ * plain row-major ("logical") format in which wsvd_quantize_rows writes.
+ * Metadata planes: I8: fp16 scale [B,Hkv,t_cap]; I4: {fp16 scale, fp16 zero point} [B,Hkv,t_cap][2];
+ * F32/BF16: unused (may be NULL).
+ */
+typedef struct {
+  void *k_codes, *v_codes;
+  void *k_meta, *v_meta;
+  int32_t *seq_lens; /* [B] valid rows per sequence; wsvd_latent_append increments it on the device */
+} wsvd_cache;
+
+/* Create / destroy a context bound to a device ordinal.  Allocates a 4-byte device error word. */
+wsvd_status wsvd_create(wsvd_ctx **out, int device_ordinal);
+wsvd_status wsvd_destroy(wsvd_ctx *ctx);
+
+/* Bytes of ONE code plane and ONE metadata plane (K or V) for this layer (HOST outputs). */
+wsvd_status wsvd_cache_bytes(const wsvd_layer_desc *desc, size_t *codes_bytes, size_t *meta_bytes);
+
+/* Scratch the hot calls need for this layer (split partials, tickets); HOST output. */
+wsvd_status wsvd_workspace_bytes(const wsvd_layer_desc *desc, size_t *bytes);
+
+/* Hand the context a caller-owned device scratch buffer.  Clears it (synchronously). */
+wsvd_status wsvd_set_workspace(wsvd_ctx *ctx, void *dev_ptr, size_t bytes);
+
+/*
+ * Decode-step cache update (Section 3.4, decoding pipeline: the new token is down-projected per head
+ * and its K and V latents are stored in the cache).  For every sequence b and kv head h:
+ *   c_K = x[b,:] A_K[h], c_V = x[b,:] A_V[h]  (fp32 accumulation), rounded to latent_dtype
+ *   (I8 / I4: the quantiser documented at wsvd_quantize_rows), written at row seq_lens[b];
+ * then seq_lens[b] += 1.  A sequence with seq_lens[b] >= t_cap is left unchanged and the
+ * context's error word is set to WSVD_E_CAPACITY.
+ *   x       [B, d_model] of x_dtype;  x_scale: fp16 [B] iff x_dtype == I8, else NULL
+ *   A_K,A_V [Hkv, d_model, rank] of factor_dtype
+ */
+wsvd_status wsvd_latent_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
+                               const void *A_K, const void *A_V, wsvd_cache *cache, void *hip_stream);
+
+/*
+ * Decode attention over the latent cache (Section 3.4 fused kernel; Section 2.4 flash-decoding
+ * schedule: sequence tiles, online softmax, parallel sequence splits merged at the end).
+ * For every b and query head h with kv = kv(h), n = seq_lens[b]:
+ *   out[b,h,:] = softmax_t( sm_scale * q[b,h,:] . (C_K[b,kv,t,:] B_K[kv]) ) . (C_V[b,kv,:,:] B_V[kv])
+ * over rows t < n; n == 0 gives zeros.  Computed as q~ = B_K q, scores on the latent rows, u = p^T C_V,
+ * out = u B_V (associativity only).
+ *   q [B,Hq,d_head] of q_dtype; q_scale fp16 [B] iff q_dtype == I8
+ *   B_K,B_V [Hkv, rank, d_head] of factor_dtype;  out [B,Hq,d_head] F32
+ *   max_seq_len: HOST upper bound on seq_lens (sizes the grid); must be <= t_cap.
+ */
+wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
+                             const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,
+                             void *out, void *hip_stream);
+
+/* Process-wide tuning knobs for benchmarks; correct use never needs them.
+ *   "wg_per_cu": workgroups per compute unit the attention grid aims for (default 4)
+ *   "min_chunk": smallest context chunk per workgroup in rows, multiple of 64, at least 256 */
+wsvd_status wsvd_set_option(const char *name, int value);
+
+/* Synchronise the stream and return (then clear) the device-side error word. */
+wsvd_status wsvd_check(wsvd_ctx *ctx, void *hip_stream);
+
+const char *wsvd_status_str(wsvd_status s);
+
+/*
+ * Quantise fp32 latent rows into the LOGICAL row-major format (the same device routine the append
+ * uses).  Per-token-per-head granularity after the per-token symmetric activation quantisation of
+ * Section 4.2; rounding rules (IEEE fp32, round-to-nearest-even, true division):
+ *   I8: a = max|c_j|; a == 0 -> scale 1, codes 0; else s = fp16(a/127) (0 -> 2^-24, inf -> 65504),
+ *       code_j = clamp(rint(c_j / float(s)), -127, 127).
+ *   I4: lo = min(min c, 0), hi = max(max c, 0); hi == lo -> s = 1, z = 0, codes 0; else
+ *       s = fp16((hi-lo)/15) (same guards), z = clamp(rint(-lo/float(s)), 0, 15),
+ *       code_j = clamp(int(rint(c_j/float(s))) + int(z), 0, 15); element 2i in the low nibble of byte i.
+ *   c [n_rows, rank] fp32 -> codes [n_rows, rank] int8 or [n_rows, rank/2] bytes;
+ *   meta: fp16 [n_rows] (I8) or {scale, zero point} fp16 [n_rows][2] (I4).
+ */
+wsvd_status wsvd_quantize_rows(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const float *c, int64_t n_rows,
+                               void *codes, void *meta, void *hip_stream);
+
+/*
+ * Copy rows [t0, t0+n_rows) of every (b, kv head) between the logical row-major format
+ * ([B,Hkv,n_rows,row_bytes] codes, [B,Hkv,n_rows(,2)] metadata) and the device layout of one plane.
+ * which_plane: 0 = K, 1 = V.  Bit-preserving.  Does not touch seq_lens.
+ */
+wsvd_status wsvd_cache_import(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_t which_plane, const void *codes,
+                              const void *meta, int32_t t0, int32_t n_rows, wsvd_cache *cache, void *hip_stream);
+wsvd_status wsvd_cache_export(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_t which_plane,
+                              const wsvd_cache *cache, int32_t t0, int32_t n_rows, void *codes, void *meta,
+                              void *hip_stream);
+
+/*
+ * Per-token symmetric int8 quantisation of activation rows (Section 4.2), same rounding rules as the
+ * I8 latent quantiser with one scale per row of `cols` channels.
+ *   x [rows, cols] of x_dtype (F32 or BF16) -> codes int8 [rows, cols], scale fp16 [rows].
+ */
+wsvd_status wsvd_quantize_act_i8(wsvd_ctx *ctx, const void *x, int32_t x_dtype, int64_t rows, int64_t cols,
+                                 int8_t *codes, void *scale_f16, void *hip_stream);
+
+/*
+ * int4-weight x int8-activation linear layer (Section 4.2: per-channel symmetric weights, per-token
+ * symmetric activations): out[m,n] = (sum_k x[m,k] * w[n,k]) * x_scale[m] * w_scale[n], the sum
+ * exact in int32.
+ *   x int8 [M,K]; x_scale fp16 [M]; w_i4 [N, K/2] two's-complement nibbles, element 2i in the low
+ *   nibble of byte i; w_scale fp16 [N]; out [M,N] F32.  K multiple of 64, N multiple of 32, M <= 64.
+ */
+wsvd_status wsvd_linear_w4a8(wsvd_ctx *ctx, const int8_t *x, const void *x_scale, const void *w_i4,
+                             const void *w_scale_f16, int64_t M, int64_t K, int64_t N, void *out,
+                             int32_t out_dtype, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WSVD_H */

@@ -159,7 +159,7 @@ def quantize_int4_rows(c32: np.ndarray):
     s16 = _guard_scale_f16(s32)
     s16 = np.where(flat, np.float16(1.0), s16).astype(np.float16)
     sf = s16.astype(np.float32)
-    z = np.clip(np.rint(-lo / sf), 0, 15)
+    z = np.abs(np.clip(np.rint(-lo / sf), 0, 15))     # an integer in [0,15]: lo == 0 must give +0, not -0
     z = np.where(flat, np.float32(0), z).astype(np.float32)
     code = np.rint(c32 / sf[..., None]).astype(np.int64) + z.astype(np.int64)[..., None]
     code = np.clip(code, 0, 15).astype(np.uint8)

@@ -1,0 +1,304 @@
+// C ABI of the library: argument validation on the host, then kernel launches on the caller's stream.
+#include <cstring>
+#include <new>
+
+#include "wsvd_attn_common.h"
+#include "wsvd_internal.h"
+
+hipError_t wsvd_launch_attn_generic(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
+hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
+hipError_t wsvd_launch_attn_gqa(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
+
+namespace {
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+inline bool is_pow2_rank(int r) { return r == 16 || r == 32 || r == 64; }
+
+int g_opt_wg_per_cu = 4;      // workgroups per CU the attention grid aims for
+int g_opt_min_chunk = 256;    // smallest context chunk per workgroup (rows)
+
+wsvd_status check_desc(const wsvd_layer_desc* d) {
+  if (!d) return WSVD_E_NULL;
+  if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->d_model <= 0) return WSVD_E_SHAPE;
+  if (d->d_head != 64 && d->d_head != 128) return WSVD_E_SHAPE;
+  if (!is_pow2_rank(d->rank)) return WSVD_E_SHAPE;
+  if (d->n_q_heads % d->n_kv_heads != 0) return WSVD_E_SHAPE;
+  const int G = d->n_q_heads / d->n_kv_heads;
+  if (G < 1 || G > 8) return WSVD_E_SHAPE;
+  if (d->t_cap <= 0 || d->t_cap % 64 != 0) return WSVD_E_SHAPE;
+  if ((int64_t)d->batch * d->n_kv_heads > kWsCounterInts / 4) return WSVD_E_SHAPE;
+  if (d->out_dtype != WSVD_F32) return WSVD_E_DTYPE;
+  switch (d->latent_dtype) {
+    case WSVD_F32:
+      if (d->factor_dtype != WSVD_F32 || d->x_dtype != WSVD_F32 || d->q_dtype != WSVD_F32) return WSVD_E_DTYPE;
+      break;
+    case WSVD_BF16:
+      if (d->factor_dtype != WSVD_BF16 || d->x_dtype != WSVD_BF16 || d->q_dtype != WSVD_BF16) return WSVD_E_DTYPE;
+      break;
+    case WSVD_I8:
+    case WSVD_I4:
+      if (d->factor_dtype != WSVD_BF16) return WSVD_E_DTYPE;
+      if (d->x_dtype != WSVD_BF16 && d->x_dtype != WSVD_F32) return WSVD_E_DTYPE;
+      if (d->q_dtype != WSVD_I8 && d->q_dtype != WSVD_F32 && d->q_dtype != WSVD_BF16) return WSVD_E_DTYPE;
+      if (d->latent_dtype == WSVD_I8 && d->rank != 32 && d->rank != 64) return WSVD_E_UNSUPPORTED;
+      if (d->latent_dtype == WSVD_I4 && d->rank != 32) return WSVD_E_UNSUPPORTED;
+      break;
+    default:
+      return WSVD_E_DTYPE;
+  }
+  return WSVD_OK;
+}
+
+int row_bytes_host(const wsvd_layer_desc& d) {
+  switch (d.latent_dtype) {
+    case WSVD_F32: return d.rank * 4;
+    case WSVD_BF16: return d.rank * 2;
+    case WSVD_I8: return d.rank;
+    default: return d.rank / 2;
+  }
+}
+int meta_bytes_host(const wsvd_layer_desc& d) { return d.latent_dtype == WSVD_I8 ? 2 : d.latent_dtype == WSVD_I4 ? 4 : 0; }
+
+wsvd_status check_cache(const wsvd_layer_desc& d, const wsvd_cache* c) {
+  if (!c || !c->k_codes || !c->v_codes || !c->seq_lens) return WSVD_E_NULL;
+  const bool quant = d.latent_dtype == WSVD_I8 || d.latent_dtype == WSVD_I4;
+  if (quant && (!c->k_meta || !c->v_meta)) return WSVD_E_NULL;
+  if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta) ||
+      ((uintptr_t)c->seq_lens & 3u))
+    return WSVD_E_ALIGN;
+  return WSVD_OK;
+}
+
+}  // namespace
+
+size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d) {
+  const size_t max_chunks = (size_t)(d.t_cap + 255) / 256;
+  return (size_t)d.batch * d.n_q_heads * max_chunks * (d.rank + 2);
+}
+
+extern "C" {
+
+const char* wsvd_status_str(wsvd_status s) {
+  switch (s) {
+    case WSVD_OK: return "ok";
+    case WSVD_E_NULL: return "null pointer";
+    case WSVD_E_SHAPE: return "unsupported or inconsistent shape";
+    case WSVD_E_DTYPE: return "unsupported dtype combination";
+    case WSVD_E_ALIGN: return "pointer not 16-byte aligned";
+    case WSVD_E_CAPACITY: return "sequence at cache capacity";
+    case WSVD_E_UNSUPPORTED: return "not implemented in this build";
+    case WSVD_E_HIP: return "HIP runtime error";
+    case WSVD_E_WORKSPACE: return "workspace missing or too small";
+  }
+  return "unknown status";
+}
+
+wsvd_status wsvd_create(wsvd_ctx** out, int device_ordinal) {
+  if (!out) return WSVD_E_NULL;
+  *out = nullptr;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess) return WSVD_E_HIP;
+  if (device_ordinal < 0 || device_ordinal >= n_dev) return WSVD_E_SHAPE;
+  if (hipSetDevice(device_ordinal) != hipSuccess) return WSVD_E_HIP;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device_ordinal) != hipSuccess) return WSVD_E_HIP;
+  wsvd_ctx* c = new (std::nothrow) wsvd_ctx();
+  if (!c) return WSVD_E_HIP;
+  c->device = device_ordinal;
+  c->n_cu = prop.multiProcessorCount;
+  c->ws = nullptr;
+  c->ws_bytes = 0;
+  if (hipMalloc((void**)&c->err_word, 4) != hipSuccess) { delete c; return WSVD_E_HIP; }
+  if (hipMemset(c->err_word, 0, 4) != hipSuccess) { (void)hipFree(c->err_word); delete c; return WSVD_E_HIP; }
+  *out = c;
+  return WSVD_OK;
+}
+
+wsvd_status wsvd_destroy(wsvd_ctx* ctx) {
+  if (!ctx) return WSVD_E_NULL;
+  hipError_t e = hipFree(ctx->err_word);
+  delete ctx;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_cache_bytes(const wsvd_layer_desc* desc, size_t* codes_bytes, size_t* meta_bytes) {
+  if (!codes_bytes || !meta_bytes) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  const size_t rows = (size_t)desc->batch * desc->n_kv_heads * desc->t_cap;
+  *codes_bytes = rows * row_bytes_host(*desc);
+  *meta_bytes = rows * meta_bytes_host(*desc);
+  return WSVD_OK;
+}
+
+wsvd_status wsvd_workspace_bytes(const wsvd_layer_desc* desc, size_t* bytes) {
+  if (!bytes) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  const size_t a = wsvd_attn_partial_floats(*desc), b = wsvd_append_partial_floats(*desc);
+  *bytes = (size_t)kWsCounterInts * 4 + (a > b ? a : b) * 4;
+  return WSVD_OK;
+}
+
+wsvd_status wsvd_set_workspace(wsvd_ctx* ctx, void* dev_ptr, size_t bytes) {
+  if (!ctx || !dev_ptr) return WSVD_E_NULL;
+  if (!aligned16(dev_ptr)) return WSVD_E_ALIGN;
+  if (bytes < (size_t)kWsCounterInts * 4) return WSVD_E_WORKSPACE;
+  if (hipSetDevice(ctx->device) != hipSuccess) return WSVD_E_HIP;
+  if (hipMemset(dev_ptr, 0, (size_t)kWsCounterInts * 4) != hipSuccess) return WSVD_E_HIP;
+  if (hipDeviceSynchronize() != hipSuccess) return WSVD_E_HIP;
+  ctx->ws = dev_ptr;
+  ctx->ws_bytes = bytes;
+  return WSVD_OK;
+}
+
+// Tuning knobs for benchmarks ("wg_per_cu", "min_chunk"); not needed for correct use.
+wsvd_status wsvd_set_option(const char* name, int value) {
+  if (!name) return WSVD_E_NULL;
+  if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { g_opt_wg_per_cu = value; return WSVD_OK; }
+  if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
+  return WSVD_E_SHAPE;
+}
+
+wsvd_status wsvd_latent_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* x, const void* x_scale,
+                               const void* A_K, const void* A_V, wsvd_cache* cache, void* hip_stream) {
+  if (!ctx || !x || !A_K || !A_V) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
+  if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  hipError_t e = wsvd_launch_append(ctx, *desc, x, x_scale, A_K, A_V, *cache, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_decode_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
+                             const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len, void* out,
+                             void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 0) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  hipError_t e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_check(wsvd_ctx* ctx, void* hip_stream) {
+  if (!ctx) return WSVD_E_NULL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  int host = 0;
+  if (hipMemcpyAsync(&host, ctx->err_word, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return WSVD_E_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return WSVD_E_HIP;
+  if (host != 0) {
+    if (hipMemsetAsync(ctx->err_word, 0, 4, s) != hipSuccess) return WSVD_E_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return WSVD_E_HIP;
+  }
+  return (wsvd_status)host;
+}
+
+wsvd_status wsvd_quantize_rows(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const float* c, int64_t n_rows, void* codes,
+                               void* meta, void* hip_stream) {
+  if (!ctx || !c || !codes || !meta) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if (desc->latent_dtype != WSVD_I8 && desc->latent_dtype != WSVD_I4) return WSVD_E_DTYPE;
+  if (n_rows < 0) return WSVD_E_SHAPE;
+  if (!aligned16(c) || !aligned16(codes) || !aligned16(meta)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_quantize_rows(desc->latent_dtype, desc->rank, c, n_rows, codes, meta, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+static wsvd_status cache_copy(bool to_device, wsvd_ctx* ctx, const wsvd_layer_desc* desc, int32_t plane, void* codes,
+                              void* meta, int32_t t0, int32_t n_rows, const wsvd_cache* cache, void* hip_stream) {
+  if (!ctx || !codes) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  const bool quant = desc->latent_dtype == WSVD_I8 || desc->latent_dtype == WSVD_I4;
+  if (quant && !meta) return WSVD_E_NULL;
+  if (plane != 0 && plane != 1) return WSVD_E_SHAPE;
+  if (t0 < 0 || n_rows < 0 || (int64_t)t0 + n_rows > desc->t_cap) return WSVD_E_SHAPE;
+  if (!aligned16(codes) || !aligned16(meta)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_cache_copy(to_device, *desc, plane, codes, meta, t0, n_rows,
+                                        plane == 0 ? cache->k_codes : cache->v_codes,
+                                        plane == 0 ? cache->k_meta : cache->v_meta, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_cache_import(wsvd_ctx* ctx, const wsvd_layer_desc* desc, int32_t which_plane, const void* codes,
+                              const void* meta, int32_t t0, int32_t n_rows, wsvd_cache* cache, void* hip_stream) {
+  return cache_copy(true, ctx, desc, which_plane, (void*)codes, (void*)meta, t0, n_rows, cache, hip_stream);
+}
+
+wsvd_status wsvd_cache_export(wsvd_ctx* ctx, const wsvd_layer_desc* desc, int32_t which_plane, const wsvd_cache* cache,
+                              int32_t t0, int32_t n_rows, void* codes, void* meta, void* hip_stream) {
+  return cache_copy(false, ctx, desc, which_plane, codes, meta, t0, n_rows, cache, hip_stream);
+}
+
+wsvd_status wsvd_quantize_act_i8(wsvd_ctx* ctx, const void* x, int32_t x_dtype, int64_t rows, int64_t cols, int8_t* codes,
+                                 void* scale_f16, void* hip_stream) {
+  if (!ctx || !x || !codes || !scale_f16) return WSVD_E_NULL;
+  if (x_dtype != WSVD_F32 && x_dtype != WSVD_BF16) return WSVD_E_DTYPE;
+  if (rows < 0 || cols <= 0) return WSVD_E_SHAPE;
+  hipError_t e = wsvd_launch_quantize_act_i8(x, x_dtype, rows, cols, codes, scale_f16, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_linear_w4a8(wsvd_ctx* ctx, const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale_f16,
+                             int64_t M, int64_t K, int64_t N, void* out, int32_t out_dtype, void* hip_stream) {
+  if (!ctx || !x || !x_scale || !w_i4 || !w_scale_f16 || !out) return WSVD_E_NULL;
+  if (out_dtype != WSVD_F32) return WSVD_E_DTYPE;
+  if (M <= 0 || M > 64 || K <= 0 || K % 64 != 0 || N <= 0 || N % 32 != 0) return WSVD_E_SHAPE;
+  if (!aligned16(x) || !aligned16(w_i4) || !aligned16(out)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_linear_w4a8(x, x_scale, w_i4, w_scale_f16, M, K, N, (float*)out, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------- attention launch policy
+hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
+                            const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,
+                            hipStream_t s) {
+  AttnParams p;
+  p.q = q; p.q_scale = (const uint16_t*)q_scale; p.BK = B_K; p.BV = B_V;
+  p.k_codes = (const uint8_t*)cache.k_codes; p.v_codes = (const uint8_t*)cache.v_codes;
+  p.k_meta = (const uint16_t*)cache.k_meta; p.v_meta = (const uint16_t*)cache.v_meta;
+  p.seq_lens = cache.seq_lens;
+  p.out = (float*)out;
+  p.tickets = (int*)ctx->ws;
+  p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
+  p.B = d.batch; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.d = d.d_head;
+  p.t_cap = d.t_cap;
+  p.q_dtype = d.q_dtype; p.factor_dtype = d.factor_dtype;
+  const float sm = d.sm_scale != 0.f ? d.sm_scale : 1.0f / sqrtf((float)d.d_head);
+  p.c_scale = sm * kLog2e;
+  // Split the context so that about wg_per_cu workgroups land on every CU; a chunk is a multiple of 64 rows and
+  // never smaller than min_chunk (the workspace is sized for chunks of at least 256 rows).
+  const int n_units = d.batch * d.n_kv_heads;
+  const int max_rows = ((max_seq_len > 0 ? max_seq_len : 1) + 63) / 64 * 64;
+  const int target = ctx->n_cu * g_opt_wg_per_cu;
+  int chunks_wanted = target / n_units;
+  if (chunks_wanted < 1) chunks_wanted = 1;
+  int chunk_rows = ((max_rows + chunks_wanted - 1) / chunks_wanted + 63) / 64 * 64;
+  const int min_chunk = g_opt_min_chunk < 256 ? 256 : g_opt_min_chunk;
+  if (chunk_rows < min_chunk) chunk_rows = min_chunk;
+  p.chunk_rows = chunk_rows;
+  p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
+  dim3 grid((unsigned)((size_t)n_units * p.n_chunks));
+  if (d.latent_dtype == WSVD_F32 || d.latent_dtype == WSVD_BF16) return wsvd_launch_attn_generic(p, d.latent_dtype, d.rank, grid, s);
+  if (p.G <= 4) return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, s);
+  return wsvd_launch_attn_gqa(p, d.latent_dtype, d.rank, grid, s);
+}

@@ -1,0 +1,150 @@
+// Decode attention over F32 / BF16 latent caches (row-major planes), plain vector ALU.
+//
+// A latent row is rank*esize bytes; LPR = row_bytes/16 adjacent lanes share a row, each holding a
+// 16-byte slice, so a wavefront load covers 64/LPR consecutive rows = 1 KiB of contiguous cache.
+// Each lane group runs its own online softmax (running max, sum, latent-space accumulator) over the
+// rows it streams; the groups are merged once at the end, like sequence splits.
+#include "wsvd_attn_common.h"
+#include "wsvd_internal.h"
+
+template <int ESZ>
+WSVD_DEV void unpack16(const v4i& raw, float* f) {
+  if (ESZ == 4) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) f[i] = __int_as_float(raw[i]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      f[2 * i] = __uint_as_float((uint32_t)raw[i] << 16);
+      f[2 * i + 1] = __uint_as_float((uint32_t)raw[i] & 0xFFFF0000u);
+    }
+  }
+}
+
+constexpr int kMaxG = 8;
+
+template <int ESZ, int R, int G>
+__global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
+  constexpr int ROWB = R * ESZ;          // bytes per latent row
+  constexpr int LPR = ROWB / 16;         // lanes per row
+  constexpr int VPL = 16 / ESZ;          // values per lane
+  constexpr int RPW = 64 / LPR;          // rows per wavefront load
+  constexpr int NGRP = 4 * RPW;          // lane groups per workgroup
+  constexpr int UNROLL = 4;
+
+  __shared__ float qts[G * R];
+  __shared__ float Msh[G], Lsh[G], Ush[G * R];
+  __shared__ float gm[NGRP * G], gl[NGRP * G];
+  __shared__ float gu[NGRP * G * R];
+  __shared__ int flag_sh;
+
+  const WorkItem w = decode_work(p);
+  if (w.n == 0) { write_zero_outputs(p, w); return; }
+  if (!w.active) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sl = lane % LPR;                       // which 16-byte slice of the row
+  const int grp = wave * RPW + lane / LPR;         // lane group id within the workgroup
+
+  compute_qtilde<R>(p, w, qts);
+  float qt[G][VPL];
+#pragma unroll
+  for (int g = 0; g < G; g++)
+#pragma unroll
+    for (int v = 0; v < VPL; v++) qt[g][v] = qts[g * R + sl * VPL + v];
+
+  const size_t plane = ((size_t)w.b * p.Hkv + w.kv) * (size_t)p.t_cap * ROWB;
+  const uint8_t* kb = p.k_codes + plane + sl * 16;
+  const uint8_t* vb = p.v_codes + plane + sl * 16;
+
+  float m[G], l[G], u[G][VPL];
+#pragma unroll
+  for (int g = 0; g < G; g++) {
+    m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+    for (int v = 0; v < VPL; v++) u[g][v] = 0.f;
+  }
+
+  for (int t0 = w.row_begin + grp; t0 < w.row_end; t0 += NGRP * UNROLL) {
+    v4i kr[UNROLL], vr[UNROLL];
+#pragma unroll
+    for (int k = 0; k < UNROLL; k++) {
+      const int t = t0 + k * NGRP;
+      if (t < w.row_end) {
+        kr[k] = *(const v4i*)(kb + (size_t)t * ROWB);
+        vr[k] = *(const v4i*)(vb + (size_t)t * ROWB);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < UNROLL; k++) {
+      const int t = t0 + k * NGRP;
+      if (t < w.row_end) {          // uniform within a lane group
+        float kf[VPL], vf[VPL];
+        unpack16<ESZ>(kr[k], kf);
+        unpack16<ESZ>(vr[k], vf);
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+          float s = 0.f;
+#pragma unroll
+          for (int v = 0; v < VPL; v++) s = fmaf(qt[g][v], kf[v], s);
+          s = group_sum<LPR>(s);
+          const float mn = fmaxf(m[g], s);
+          const float alpha = __builtin_amdgcn_exp2f(m[g] - mn);
+          const float pw = __builtin_amdgcn_exp2f(s - mn);
+          l[g] = fmaf(l[g], alpha, pw);
+#pragma unroll
+          for (int v = 0; v < VPL; v++) u[g][v] = fmaf(u[g][v], alpha, pw * vf[v]);
+          m[g] = mn;
+        }
+      }
+    }
+  }
+  // NOTE: group_sum uses DPP across the LPR lanes of a row; lanes of a group take the same branch
+  // (t depends only on the group), so the exchanged values are always defined.
+
+#pragma unroll
+  for (int g = 0; g < G; g++) {
+    if (sl == 0) { gm[grp * G + g] = m[g]; gl[grp * G + g] = l[g]; }
+#pragma unroll
+    for (int v = 0; v < VPL; v++) gu[(grp * G + g) * R + sl * VPL + v] = u[g][v];
+  }
+  __syncthreads();
+  for (int i = tid; i < G * R; i += 256) {
+    const int g = i / R, j = i % R;
+    float M = -INFINITY;
+    for (int k = 0; k < NGRP; k++) M = fmaxf(M, gm[k * G + g]);
+    float L = 0.f, U = 0.f;
+    for (int k = 0; k < NGRP; k++) {
+      const float e = __builtin_amdgcn_exp2f(gm[k * G + g] - M);
+      L = fmaf(gl[k * G + g], e, L);
+      U = fmaf(gu[(k * G + g) * R + j], e, U);
+    }
+    Ush[i] = U;
+    if (j == 0) { Msh[g] = M; Lsh[g] = L; }
+  }
+  __syncthreads();
+  attn_tail<R>(p, w, Msh, Lsh, Ush, &flag_sh);
+}
+
+template <int ESZ, int R>
+static hipError_t launch_g(const AttnParams& p, dim3 grid, hipStream_t s) {
+  switch (p.G) {
+    case 1: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 1>), grid, dim3(256), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 2>), grid, dim3(256), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 4>), grid, dim3(256), 0, s, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t wsvd_launch_attn_generic(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s) {
+  if (latent_dtype == WSVD_F32) {
+    if (rank == 16) return launch_g<4, 16>(p, grid, s);
+    if (rank == 32) return launch_g<4, 32>(p, grid, s);
+    if (rank == 64) return launch_g<4, 64>(p, grid, s);
+  } else if (latent_dtype == WSVD_BF16) {
+    if (rank == 16) return launch_g<2, 16>(p, grid, s);
+    if (rank == 32) return launch_g<2, 32>(p, grid, s);
+    if (rank == 64) return launch_g<2, 64>(p, grid, s);
+  }
+  return hipErrorInvalidValue;
+}

@@ -1,0 +1,288 @@
+// Decode attention over I8 / I4 latent caches on the gfx950 matrix cores.
+//
+// The cache planes are stored as MFMA operand images (layout in wsvd.h), so the 16 bytes a lane loads
+// ARE its slice of the B operand of V_MFMA_I32_32X32X32_I8: no unpack for I8, two mask/shift pairs per
+// dword for I4.  The float side of each product is carried as three signed 7-bit limbs:
+//   * score pass:  q~ (B_K folded into the query) = delta * (h*2^14 + m*2^7 + l); rows of the A operand
+//     are the limbs, columns of B are tokens, so D[limb][token] are exact int32 dot products;
+//   * value pass:  w_t = p_t * scale_V[t] = omega * (h*2^14 + m*2^7 + l) per tile; A rows are the
+//     limbs over tokens (transposed through LDS), B is the token-minor V block, D[limb][dim].
+// A tile is 64 tokens: two 32-token blocks whose score MFMAs are chained into disjoint row groups so
+// that lane L ends up with the scores of token L of the tile.
+// Operand / result register layouts used here were checked on hardware:
+//   A: lane L holds row L%32, k = 16*(L/32)..+15;  B: lane L holds column L%32, same k;
+//   D: lane L, register v holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
+#include "wsvd_attn_common.h"
+#include "wsvd_internal.h"
+
+template <int R, bool I4>
+struct TileRegs {
+  // I8: k[kk][blk], v[jj][blk] with kk, jj < R/32 and blk < 2.  I4 (R == 32): k[0][0], v[0][0] hold 64 tokens.
+  v4i k[R / 32][2];
+  v4i v[R / 32][2];
+  uint32_t kmeta, vmeta;   // I8: fp16 scale in the low half; I4: scale | zero point << 16
+};
+
+template <int R, bool I4>
+WSVD_DEV void load_tile(TileRegs<R, I4>& t, const uint8_t* kplane, const uint8_t* vplane, const uint16_t* kmeta,
+                        const uint16_t* vmeta, int tile, int lane) {
+  if (I4) {
+    const size_t off = (size_t)tile * 1024 + lane * 16;
+    t.k[0][0] = __builtin_nontemporal_load((const v4i*)(kplane + off));
+    t.v[0][0] = __builtin_nontemporal_load((const v4i*)(vplane + off));
+    t.kmeta = __builtin_nontemporal_load((const uint32_t*)kmeta + (size_t)tile * 64 + lane);
+    t.vmeta = __builtin_nontemporal_load((const uint32_t*)vmeta + (size_t)tile * 64 + lane);
+  } else {
+    const size_t off = (size_t)tile * (64 * R) + lane * 16;
+#pragma unroll
+    for (int blk = 0; blk < 2; blk++)
+#pragma unroll
+      for (int kk = 0; kk < R / 32; kk++) {
+        t.k[kk][blk] = __builtin_nontemporal_load((const v4i*)(kplane + off + blk * (32 * R) + kk * 1024));
+        t.v[kk][blk] = __builtin_nontemporal_load((const v4i*)(vplane + off + blk * (32 * R) + kk * 1024));
+      }
+    t.kmeta = __builtin_nontemporal_load(kmeta + (size_t)tile * 64 + lane);
+    t.vmeta = __builtin_nontemporal_load(vmeta + (size_t)tile * 64 + lane);
+  }
+}
+
+WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+
+// three limb dot products -> float: h*2^14 + m*2^7 + l
+WSVD_DEV float limbs_to_f32(int h, int m, int l) { return fmaf((float)h, 16384.f, fmaf((float)m, 128.f, (float)l)); }
+
+constexpr float kLimbFull = 1048576.f;   // 2^20: |quantised value| <= 2^20 fits three 7-bit limbs
+
+template <int R, int G, bool I4>
+__global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p) {
+  static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
+  static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
+  constexpr int KK = R / 32;
+
+  __shared__ float qts[G * R];
+  __shared__ __attribute__((aligned(16))) int8_t qlimb[G][3][R];   // limbs of q~ in operand k-order
+  __shared__ float qdelta[G], qzsum[G];
+  __shared__ __attribute__((aligned(16))) uint8_t wl[4][G][3][64]; // per wave: limbs of the value weights, by token
+  __shared__ float wm[4][G], wls[4][G];
+  __shared__ float wu[4][G][R];
+  __shared__ float Msh[G], Lsh[G], Ush[G * R];
+  __shared__ int flag_sh;
+
+  const WorkItem w = decode_work(p);
+  if (w.n == 0) { write_zero_outputs(p, w); return; }
+  if (!w.active) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile_begin = w.row_begin >> 6, tile_end = (w.row_end + 63) >> 6;
+
+  const size_t ph = (size_t)w.b * p.Hkv + w.kv;
+  const size_t plane_bytes = (size_t)p.t_cap * (I4 ? R / 2 : R);
+  const uint8_t* kplane = p.k_codes + ph * plane_bytes;
+  const uint8_t* vplane = p.v_codes + ph * plane_bytes;
+  const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
+  const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
+
+  // ---- start streaming before anything else: two tiles per wave in flight
+  TileRegs<R, I4> bufA, bufB;
+  int T = tile_begin + wave;
+  if (T < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T, lane);
+  if (T + 4 < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + 4, lane);
+
+  // ---- query absorption and its limbs
+  compute_qtilde<R>(p, w, qts);
+  if (tid < G * R) {
+    const int g = tid / R, j = tid % R;
+    const float v = qts[tid];
+    const float amax = (R == 64) ? wave_max(fabsf(v)) : half_max(fabsf(v), lane);
+    const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
+    const int Q = (int)__builtin_rintf(v * inv);
+    const int l0 = ((Q + 64) & 127) - 64;
+    const int Q1 = (Q - l0) >> 7;
+    const int l1 = ((Q1 + 64) & 127) - 64;
+    const int l2 = (Q1 - l1) >> 7;
+    // position of dim j in the operand k-order.  I8: identity.  I4: a lane's 8 bytes hold dims 16g..16g+15 as
+    // nibble pairs; masking gives operand dwords [even dims 0..6, odd 1..7, even 8..14, odd 9..15].
+    int pos = j;
+    if (I4) {
+      const int jj = j & 15;
+      pos = (j & 16) + ((jj >> 3) << 3) + ((jj & 1) << 2) + ((jj & 7) >> 1);
+    }
+    qlimb[g][0][pos] = (int8_t)l2;
+    qlimb[g][1][pos] = (int8_t)l1;
+    qlimb[g][2][pos] = (int8_t)l0;
+    const float zs = (R == 64) ? wave_sum((float)Q) : half_sum((float)Q, lane);
+    if (j == 0) { qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f; qzsum[g] = zs; }
+  }
+  __syncthreads();
+
+  // A operands of the score MFMAs.  Row i of A: query slot a = i/8, row group (i/4)%2, limb i%4 (limb 3 unused).
+  // a1 feeds block 0 of a tile (rows of group 0 only), a2 feeds block 1 (rows of group 1 only).
+  v4i a1[KK], a2[KK];
+  {
+    const int i = lane & 31, g2 = lane >> 5;
+    const int a = i >> 3, grp = (i >> 2) & 1, limb = i & 3;
+    const bool act = (a < G) && (limb < 3);
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      v4i val = {0, 0, 0, 0};
+      if (act) val = *(const v4i*)&qlimb[a < G ? a : 0][limb < 3 ? limb : 0][kk * 32 + g2 * 16];
+      const v4i zero = {0, 0, 0, 0};
+      a1[kk] = (act && grp == 0) ? val : zero;
+      a2[kk] = (act && grp == 1) ? val : zero;
+    }
+  }
+  float delta[G], zsum[G];
+#pragma unroll
+  for (int g = 0; g < G; g++) { delta[g] = qdelta[g]; zsum[g] = qzsum[g]; }
+
+  float m[G], lsum[G], zacc[G], u[G][KK];
+#pragma unroll
+  for (int g = 0; g < G; g++) {
+    m[g] = -INFINITY; lsum[g] = 0.f; zacc[g] = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < KK; jj++) u[g][jj] = 0.f;
+  }
+
+  // weights operand read position: row i -> (query slot, limb); both row groups read the same limbs
+  const int wr_a = min((lane & 31) >> 3, G - 1), wr_limb = min(lane & 3, 2), wr_g2 = lane >> 5;
+
+  auto compute = [&](TileRegs<R, I4>& t, int tile) {
+    const int tok = tile * 64 + lane;
+    const bool valid = tok < w.row_end;
+    // ---------------- score pass
+    v16i acc = {0};
+    float ksc, kz = 0.f, vsc, vz = 0.f;
+    if (I4) {
+      const uint32_t msk = 0x0F0F0F0Fu;
+      const v4i raw = t.k[0][0];
+      v4i s0, s1;   // slot 0 = tokens 0..31 (dwords 0,1), slot 1 = tokens 32..63 (dwords 2,3)
+      s0[0] = raw[0] & msk; s0[1] = ((uint32_t)raw[0] >> 4) & msk; s0[2] = raw[1] & msk; s0[3] = ((uint32_t)raw[1] >> 4) & msk;
+      s1[0] = raw[2] & msk; s1[1] = ((uint32_t)raw[2] >> 4) & msk; s1[2] = raw[3] & msk; s1[3] = ((uint32_t)raw[3] >> 4) & msk;
+      acc = mfma_i8(a1[0], s0, acc);
+      acc = mfma_i8(a2[0], s1, acc);
+      ksc = f16_bits_to_f32((uint16_t)(t.kmeta & 0xFFFF)); kz = f16_bits_to_f32((uint16_t)(t.kmeta >> 16));
+      vsc = f16_bits_to_f32((uint16_t)(t.vmeta & 0xFFFF)); vz = f16_bits_to_f32((uint16_t)(t.vmeta >> 16));
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < KK; kk++) acc = mfma_i8(a1[kk], t.k[kk][0], acc);
+#pragma unroll
+      for (int kk = 0; kk < KK; kk++) acc = mfma_i8(a2[kk], t.k[kk][1], acc);
+      ksc = f16_bits_to_f32((uint16_t)t.kmeta);
+      vsc = f16_bits_to_f32((uint16_t)t.vmeta);
+    }
+    float alpha[G], omega[G];
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+      float dot = limbs_to_f32(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2]);
+      if (I4) dot -= kz * zsum[g];
+      float s = valid ? ksc * dot * delta[g] : -INFINITY;
+      const float mn = fmaxf(m[g], wave_max(s));
+      alpha[g] = __builtin_amdgcn_exp2f(m[g] - mn);
+      m[g] = mn;
+      const float pw = __builtin_amdgcn_exp2f(s - mn);
+      lsum[g] = fmaf(lsum[g], alpha[g], pw);
+      // ---------------- value weights -> limbs
+      const float wt = valid ? pw * vsc : 0.f;
+      const float wmax = wave_max(wt);
+      const float winv = wmax > 0.f ? kLimbFull / wmax : 0.f;
+      omega[g] = wmax > 0.f ? wmax / kLimbFull : 0.f;
+      const int Q = (int)__builtin_rintf(wt * winv);      // 0 .. 2^20
+      if (I4) zacc[g] = fmaf(zacc[g], alpha[g], (float)Q * omega[g] * vz);
+      // token order inside the wave's limb rows: I8: token L at byte L.  I4: a V byte holds tokens (2b, 2b+1) of a
+      // 32-token half; the low-nibble operand covers even tokens, the high-nibble operand odd tokens.
+      int pos = lane;
+      if (I4) pos = ((lane & 1) << 5) + ((lane >> 5) << 4) + ((lane & 31) >> 1);
+      wl[wave][g][0][pos] = (uint8_t)(Q >> 14);
+      wl[wave][g][1][pos] = (uint8_t)((Q >> 7) & 127);
+      wl[wave][g][2][pos] = (uint8_t)(Q & 127);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---------------- value pass
+    const v4i w0 = *(const v4i*)&wl[wave][wr_a][wr_limb][wr_g2 * 16];
+    const v4i w1 = *(const v4i*)&wl[wave][wr_a][wr_limb][32 + wr_g2 * 16];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (I4) {
+      const uint32_t msk = 0x0F0F0F0Fu;
+      const v4i raw = t.v[0][0];
+      v4i lo, hi;
+#pragma unroll
+      for (int x = 0; x < 4; x++) { lo[x] = raw[x] & msk; hi[x] = ((uint32_t)raw[x] >> 4) & msk; }
+      v16i vacc = {0};
+      vacc = mfma_i8(w0, lo, vacc);   // w0: limbs of even tokens, k = 16*g2 + b  <->  token 32*g2 + 2b
+      vacc = mfma_i8(w1, hi, vacc);   // w1: limbs of odd tokens
+#pragma unroll
+      for (int g = 0; g < G; g++)
+        u[g][0] = fmaf(u[g][0], alpha[g], omega[g] * limbs_to_f32(vacc[4 * g], vacc[4 * g + 1], vacc[4 * g + 2]));
+    } else {
+#pragma unroll
+      for (int jj = 0; jj < KK; jj++) {
+        v16i vacc = {0};
+        vacc = mfma_i8(w0, t.v[jj][0], vacc);
+        vacc = mfma_i8(w1, t.v[jj][1], vacc);
+#pragma unroll
+        for (int g = 0; g < G; g++)
+          u[g][jj] = fmaf(u[g][jj], alpha[g], omega[g] * limbs_to_f32(vacc[4 * g], vacc[4 * g + 1], vacc[4 * g + 2]));
+      }
+    }
+  };
+
+  // ---- ping-pong over this wave's tiles (tile_begin + wave, step 4)
+  while (T < tile_end) {
+    compute(bufA, T);
+    if (T + 8 < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T + 8, lane);
+    T += 4;
+    if (T >= tile_end) break;
+    compute(bufB, T);
+    if (T + 8 < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + 8, lane);
+    T += 4;
+  }
+
+  // ---- per-wave state -> workgroup merge
+#pragma unroll
+  for (int g = 0; g < G; g++) {
+    const float lw = wave_sum(lsum[g]);
+    const float zc = I4 ? wave_sum(zacc[g]) : 0.f;
+    if (lane == 0) { wm[wave][g] = m[g]; wls[wave][g] = lw; }
+    if (lane < 32) {
+#pragma unroll
+      for (int jj = 0; jj < KK; jj++) wu[wave][g][jj * 32 + lane] = u[g][jj] - zc;
+    }
+  }
+  __syncthreads();
+  if (tid < G * R) {
+    const int g = tid / R, j = tid % R;
+    const float M = fmaxf(fmaxf(wm[0][g], wm[1][g]), fmaxf(wm[2][g], wm[3][g]));
+    float L = 0.f, U = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
+      L = fmaf(wls[k][g], e, L);
+      U = fmaf(wu[k][g][j], e, U);
+    }
+    Ush[tid] = U;
+    if (j == 0) { Msh[g] = M; Lsh[g] = L; }
+  }
+  __syncthreads();
+  attn_tail<R>(p, w, Msh, Lsh, Ush, &flag_sh);
+}
+
+template <int R, bool I4>
+static hipError_t launch_m(const AttnParams& p, dim3 grid, hipStream_t s) {
+  switch (p.G) {
+    case 1: hipLaunchKernelGGL((k_attn_mfma<R, 1, I4>), grid, dim3(256), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4>), grid, dim3(256), 0, s, p); break;
+    case 3: hipLaunchKernelGGL((k_attn_mfma<R, 3, I4>), grid, dim3(256), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((k_attn_mfma<R, 4, I4>), grid, dim3(256), 0, s, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s) {
+  if (latent_dtype == WSVD_I8 && rank == 32) return launch_m<32, false>(p, grid, s);
+  if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false>(p, grid, s);
+  if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true>(p, grid, s);
+  return hipErrorInvalidValue;
+}

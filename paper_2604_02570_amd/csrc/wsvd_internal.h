@@ -1,0 +1,33 @@
+// Host-side launchers of the kernel translation units (internal; not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/wsvd.h"
+
+struct wsvd_ctx {
+  int device;
+  int n_cu;
+  int* err_word;     // device, 4 bytes
+  void* ws;          // caller-owned workspace
+  size_t ws_bytes;
+};
+
+hipError_t wsvd_launch_quantize_rows(int latent_dtype, int rank, const float* c, int64_t n_rows, void* codes, void* meta,
+                                     hipStream_t s);
+hipError_t wsvd_launch_cache_copy(bool to_device, const wsvd_layer_desc& d, int plane, void* logical_codes,
+                                  void* logical_meta, int t0, int n_rows, void* dev_codes, void* dev_meta, hipStream_t s);
+hipError_t wsvd_launch_quantize_act_i8(const void* x, int x_dtype, int64_t rows, int64_t cols, int8_t* codes,
+                                       void* scale_f16, hipStream_t s);
+hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,
+                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s);
+hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
+                            const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,
+                            hipStream_t s);
+hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
+                                   int64_t K, int64_t N, float* out, hipStream_t s);
+
+// workspace sizing shared by the API and the launchers
+size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
+size_t wsvd_append_partial_floats(const wsvd_layer_desc& d);
+int wsvd_append_esplits(const wsvd_layer_desc& d);

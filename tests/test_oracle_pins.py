@@ -202,6 +202,7 @@ def test_int4_quantiser_invariants():
     zf = z.astype(np.float64)
     assert (zf == np.rint(zf)).all() and zf.min() >= 0 and zf.max() <= 15
     assert z[1] == 0                         # all-positive row: range starts at 0
+    assert z.view(np.uint16)[1] == 0          # ... stored as +0 (the zero point is an integer code, never -0)
     assert z[2] == 15                        # all-negative row: zero maps to the top code
     deq = O.dequantize_int4_rows(packed, s, z)
     sf = s.astype(np.float64)
