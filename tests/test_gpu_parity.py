@@ -197,18 +197,19 @@ def test_attention_independent_of_split_count(dtype):
     L.upload(c.cache)
     outs = []
     try:
-        for wg in (1, 4, 16, 64):      # 1 -> a single workgroup per (b, kv); 64 -> the finest split (256-row chunks)
-            W.wsvd_set_option("wg_per_cu", wg)
+        for mc in (2048, 1024, 512, 256):   # 1, 2, 3 and 6 context chunks per (sequence, kv head)
+            W.wsvd_set_option("min_chunk", mc)
             got, ref = run_attend(c, L)
-            check_out(got, ref, dtype, f"splits wg_per_cu={wg}")
+            check_out(got, ref, dtype, f"splits min_chunk={mc}")
             outs.append(got)
     finally:
-        W.wsvd_set_option("wg_per_cu", 4)
+        W.wsvd_set_option("min_chunk", 256)
     for o in outs[1:]:
         assert np.abs(o - outs[0]).max() <= 1e-5 * np.abs(outs[0]).max()
     # repeatability: same launch twice gives identical bits (fixed merge order)
     g1, _ = run_attend(c, L); g2, _ = run_attend(c, L)
     assert (g1 == g2).all()
+    assert any((o != outs[0]).any() for o in outs[1:]), "split count had no effect: the option is not reaching the launch"
     L.close()
 
 
