@@ -6,7 +6,8 @@
 #include "wsvd_internal.h"
 
 hipError_t wsvd_launch_attn_generic(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
-hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
+hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s);
+int wsvd_attn_mfma_max_threads(int latent_dtype, int rank);
 hipError_t wsvd_launch_attn_gqa(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
 
 namespace {
@@ -16,6 +17,7 @@ inline bool is_pow2_rank(int r) { return r == 16 || r == 32 || r == 64; }
 
 int g_opt_wg_per_cu = 4;      // workgroups per CU the attention grid aims for
 int g_opt_min_chunk = 256;    // smallest context chunk per workgroup (rows)
+int g_opt_max_threads = 0;    // cap on the MFMA kernels' workgroup size (0 = their launch bound)
 
 wsvd_status check_desc(const wsvd_layer_desc* d) {
   if (!d) return WSVD_E_NULL;
@@ -157,6 +159,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!name) return WSVD_E_NULL;
   if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { g_opt_wg_per_cu = value; return WSVD_OK; }
   if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
+  if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
 
@@ -285,12 +288,23 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   p.q_dtype = d.q_dtype; p.factor_dtype = d.factor_dtype;
   const float sm = d.sm_scale != 0.f ? d.sm_scale : 1.0f / sqrtf((float)d.d_head);
   p.c_scale = sm * kLog2e;
-  // Split the context so that about wg_per_cu workgroups land on every CU; a chunk is a multiple of 64 rows and
-  // never smaller than min_chunk (the workspace is sized for chunks of at least 256 rows).
+  // Work decomposition.  One unit = one (sequence, kv head) stream.  The grid should put about 16 wavefronts on
+  // every CU.  Wavefronts are cheapest to add inside a workgroup (merge through LDS), so the workgroup grows first
+  // (MFMA kernels: up to their launch bound); only then is the context split over several workgroups, whose partial
+  // results are merged by the last one to finish.  A chunk is a multiple of 64 rows, at least min_chunk (>= 256).
   const int n_units = d.batch * d.n_kv_heads;
   const int max_rows = ((max_seq_len > 0 ? max_seq_len : 1) + 63) / 64 * 64;
-  const int target = ctx->n_cu * g_opt_wg_per_cu;
-  int chunks_wanted = target / n_units;
+  const bool mfma = !(d.latent_dtype == WSVD_F32 || d.latent_dtype == WSVD_BF16);
+  const int waves_target = ctx->n_cu * 4 * g_opt_wg_per_cu;
+  int waves_per_unit = (waves_target + n_units - 1) / n_units;
+  const int max_tiles = max_rows / 64;
+  if (waves_per_unit > max_tiles) waves_per_unit = max_tiles;
+  int nw = 4;
+  if (mfma && p.G <= 4) {
+    const int nw_max = (g_opt_max_threads ? g_opt_max_threads : wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank)) / 64;
+    while (nw * 2 <= nw_max && nw * 2 <= waves_per_unit) nw *= 2;
+  }
+  int chunks_wanted = waves_per_unit / nw;
   if (chunks_wanted < 1) chunks_wanted = 1;
   int chunk_rows = ((max_rows + chunks_wanted - 1) / chunks_wanted + 63) / 64 * 64;
   const int min_chunk = g_opt_min_chunk < 256 ? 256 : g_opt_min_chunk;
@@ -298,7 +312,7 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   p.chunk_rows = chunk_rows;
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
   dim3 grid((unsigned)((size_t)n_units * p.n_chunks));
-  if (d.latent_dtype == WSVD_F32 || d.latent_dtype == WSVD_BF16) return wsvd_launch_attn_generic(p, d.latent_dtype, d.rank, grid, s);
-  if (p.G <= 4) return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, s);
+  if (!mfma) return wsvd_launch_attn_generic(p, d.latent_dtype, d.rank, grid, s);
+  if (p.G <= 4) return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, nw * 64, s);
   return wsvd_launch_attn_gqa(p, d.latent_dtype, d.rank, grid, s);
 }

@@ -73,10 +73,11 @@ WSVD_DEV void store_row(const AppendParams& p, int pl, int b, int kv, int t, con
   }
 }
 
-template <int R>
+template <int R, int FESZ>
 __global__ __launch_bounds__(256) void k_append(AppendParams p) {
-  constexpr int EL = 256 / R;   // threads along d_model per latent dim
-  __shared__ float xs[kAppendBB][kAppendMaxESL];
+  constexpr int EL = 256 / R;                 // threads along d_model per latent dim
+  constexpr int NA = kAppendMaxESL / EL;      // factor elements per thread (one d_model slice, one latent dim)
+  __shared__ __attribute__((aligned(16))) float xs[kAppendMaxESL][kAppendBB];
   __shared__ float red[EL][kAppendBB][R];
   __shared__ float crow[64][R + 1];
   __shared__ int flag_sh;
@@ -89,21 +90,35 @@ __global__ __launch_bounds__(256) void k_append(AppendParams p) {
   const int e0 = s * p.ESL;
   float* part = p.partials + ((((size_t)pl * p.Hkv + kv) * p.ES + s) * p.B) * R;
 
+  // this thread's slice of the factor: read once (all loads in flight together), reused for every batch row
+  float a[NA];
+#pragma unroll
+  for (int i = 0; i < NA; i++) {
+    const int e = el + i * EL;
+    const size_t idx = ((size_t)kv * p.E + e0 + e) * R + j;
+    a[i] = 0.f;
+    if (e < p.ESL) a[i] = FESZ == 4 ? ((const float*)p.A[pl])[idx] : bf16_to_f32(((const uint16_t*)p.A[pl])[idx]);
+  }
+
   for (int b0 = 0; b0 < p.B; b0 += kAppendBB) {
     const int nb = min(kAppendBB, p.B - b0);
     __syncthreads();
     for (int i = tid; i < kAppendBB * p.ESL; i += 256) {
       const int bb = i / p.ESL, e = i % p.ESL;
-      xs[bb][e] = bb < nb ? load_x(p, b0 + bb, e0 + e) : 0.f;
+      xs[e][bb] = bb < nb ? load_x(p, b0 + bb, e0 + e) : 0.f;
     }
     __syncthreads();
     float acc[kAppendBB];
 #pragma unroll
     for (int bb = 0; bb < kAppendBB; bb++) acc[bb] = 0.f;
-    for (int e = el; e < p.ESL; e += EL) {
-      const float a = load_as_f32(p.A[pl], ((size_t)kv * p.E + e0 + e) * R + j, p.factor_dtype);
 #pragma unroll
-      for (int bb = 0; bb < kAppendBB; bb++) acc[bb] = fmaf(xs[bb][e], a, acc[bb]);
+    for (int i = 0; i < NA; i++) {
+      const int e = el + i * EL;
+      if (e < p.ESL) {
+        const v4f x0 = *(const v4f*)&xs[e][0], x1 = *(const v4f*)&xs[e][4];
+#pragma unroll
+        for (int bb = 0; bb < 4; bb++) { acc[bb] = fmaf(x0[bb], a[i], acc[bb]); acc[4 + bb] = fmaf(x1[bb], a[i], acc[4 + bb]); }
+      }
     }
 #pragma unroll
     for (int bb = 0; bb < kAppendBB; bb++) red[el][bb][j] = acc[bb];
@@ -112,22 +127,21 @@ __global__ __launch_bounds__(256) void k_append(AppendParams p) {
       const int bb = i / R, jj = i % R;
       float sum = 0.f;
       for (int k = 0; k < EL; k++) sum += red[k][bb][jj];
-      part[(size_t)(b0 + bb) * R + jj] = sum;
+      agent_store(&part[(size_t)(b0 + bb) * R + jj], sum);
     }
   }
-  // ---- ticket of this (plane, kv head)
-  __threadfence();
+  // ---- ticket of this (plane, kv head).  Partials travel as agent-scope accesses (no cache-wide fences);
+  // the barrier makes sure every thread's stores have completed before the ticket is taken.
   __syncthreads();
   if (tid == 0) {
     int* t = p.tickets + pl * p.Hkv + kv;
-    const int old = atomicAdd(t, 1);
+    const int old = __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int last = (old == p.ES - 1);
-    if (last) atomicExch(t, 0);
+    if (last) __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     flag_sh = last;
   }
   __syncthreads();
   if (!flag_sh) return;
-  __threadfence();
   const float* pbase = p.partials + (((size_t)pl * p.Hkv + kv) * p.ES) * p.B * R;
   for (int b0 = 0; b0 < p.B; b0 += 64) {
     const int nb = min(64, p.B - b0);
@@ -135,7 +149,7 @@ __global__ __launch_bounds__(256) void k_append(AppendParams p) {
     for (int i = tid; i < nb * R; i += 256) {
       const int bb = i / R, jj = i % R;
       float sum = 0.f;
-      for (int k = 0; k < p.ES; k++) sum += __builtin_nontemporal_load(pbase + ((size_t)k * p.B + b0 + bb) * R + jj);
+      for (int k = 0; k < p.ES; k++) sum += agent_load(pbase + ((size_t)k * p.B + b0 + bb) * R + jj);
       crow[bb][jj] = sum;
     }
     __syncthreads();
@@ -145,14 +159,14 @@ __global__ __launch_bounds__(256) void k_append(AppendParams p) {
       if (n >= 0 && n < p.t_cap) store_row<R>(p, pl, b, kv, n, crow[tid]);
     }
   }
-  // ---- global ticket: the last finisher advances the sequence lengths
-  __threadfence();
+  // ---- global ticket: the last finisher advances the sequence lengths (it only touches seq_lens, which no
+  // other workgroup writes; the rows stored above are consumed by later launches)
   __syncthreads();
   if (tid == 0) {
     int* t = p.tickets + 2 * p.Hkv;
-    const int old = atomicAdd(t, 1);
+    const int old = __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int last = (old == 2 * p.Hkv - 1);
-    if (last) atomicExch(t, 0);
+    if (last) __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     flag_sh = last;
   }
   __syncthreads();
@@ -188,10 +202,11 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
   p.ES = wsvd_append_esplits(d); p.ESL = d.d_model / p.ES;
   p.x_dtype = d.x_dtype; p.factor_dtype = d.factor_dtype; p.latent_dtype = d.latent_dtype;
   dim3 grid((unsigned)(p.ES * p.Hkv * 2)), block(256);
+  const bool f32 = d.factor_dtype == WSVD_F32;
   switch (d.rank) {
-    case 16: hipLaunchKernelGGL(k_append<16>, grid, block, 0, s, p); break;
-    case 32: hipLaunchKernelGGL(k_append<32>, grid, block, 0, s, p); break;
-    case 64: hipLaunchKernelGGL(k_append<64>, grid, block, 0, s, p); break;
+    case 16: if (f32) hipLaunchKernelGGL((k_append<16, 4>), grid, block, 0, s, p); else hipLaunchKernelGGL((k_append<16, 2>), grid, block, 0, s, p); break;
+    case 32: if (f32) hipLaunchKernelGGL((k_append<32, 4>), grid, block, 0, s, p); else hipLaunchKernelGGL((k_append<32, 2>), grid, block, 0, s, p); break;
+    case 64: if (f32) hipLaunchKernelGGL((k_append<64, 4>), grid, block, 0, s, p); else hipLaunchKernelGGL((k_append<64, 2>), grid, block, 0, s, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

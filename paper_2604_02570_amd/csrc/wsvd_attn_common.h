@@ -53,27 +53,82 @@ WSVD_DEV void write_zero_outputs(const AttnParams& p, const WorkItem& w) {
     p.out[((size_t)w.b * p.Hq + w.kv * p.G) * p.d + i] = 0.f;
 }
 
+// ---- staging of the per-head factors into LDS.
+// B_K[kv] and B_V[kv] are contiguous R*d blocks.  All global loads are issued first (predicated, fully
+// unrolled) and committed to LDS later, so the caller can put other loads in flight in between and a
+// single wait covers everything.
+template <int MAXIT>
+struct StageRegs { v4i v[MAXIT]; };
+
+template <int MAXIT>
+WSVD_DEV void stage_issue(StageRegs<MAXIT>& r, const void* src, int n16) {
+#pragma unroll
+  for (int it = 0; it < MAXIT; it++) {
+    const int idx = it * (int)blockDim.x + (int)threadIdx.x;
+    if (idx < n16) r.v[it] = ((const v4i*)src)[idx];
+  }
+}
+template <int MAXIT>
+WSVD_DEV void stage_commit(const StageRegs<MAXIT>& r, void* lds, int n16) {
+#pragma unroll
+  for (int it = 0; it < MAXIT; it++) {
+    const int idx = it * (int)blockDim.x + (int)threadIdx.x;
+    if (idx < n16) ((v4i*)lds)[idx] = r.v[it];
+  }
+}
+
+// element c of the query of head slot g (any q_dtype) as float
 WSVD_DEV float load_q(const AttnParams& p, size_t idx, float qs) {
   if (p.q_dtype == WSVD_I8) return (float)((const int8_t*)p.q)[idx] * qs;
   return load_as_f32(p.q, idx, p.q_dtype);
 }
 
-// q~[g][j] = c_scale * sum_c B_K[kv][j][c] * q[b, kv*G+g][c]   (query absorption; 256 threads).
-// Ends with a __syncthreads.
-template <int R>
-WSVD_DEV void compute_qtilde(const AttnParams& p, const WorkItem& w, float* qts /* LDS [G][R] */) {
-  constexpr int TPJ = 256 / R;            // threads cooperating on one latent dim
-  const int tid = threadIdx.x;
-  const int j = tid / TPJ, part = tid % TPJ;
-  const int CP = p.d / TPJ;               // head-dim columns per thread
+// queries of the G heads of this kv head -> LDS floats [G][d] (one element per thread and pass)
+WSVD_DEV void stage_q(const AttnParams& p, const WorkItem& w, float* q_lds) {
   const float qs = p.q_dtype == WSVD_I8 ? f16_bits_to_f32(p.q_scale[w.b]) : 1.f;
-  const size_t brow = ((size_t)w.kv * R + j) * p.d + (size_t)part * CP;
-  for (int g = 0; g < p.G; g++) {
-    const size_t qrow = ((size_t)w.b * p.Hq + (size_t)w.kv * p.G + g) * p.d + (size_t)part * CP;
-    float acc = 0.f;
-    for (int c = 0; c < CP; c++) acc = fmaf(load_as_f32(p.BK, brow + c, p.factor_dtype), load_q(p, qrow + c, qs), acc);
-    acc = group_sum<TPJ>(acc);
-    if (part == 0) qts[g * R + j] = acc * p.c_scale;
+  const size_t base = ((size_t)w.b * p.Hq + (size_t)w.kv * p.G) * p.d;
+  for (int i = threadIdx.x; i < p.G * p.d; i += blockDim.x) q_lds[i] = load_q(p, base + i, qs);
+}
+
+// 8 consecutive factor elements from LDS as float
+template <int ESZ>
+WSVD_DEV void lds_load8(const void* lds, int idx, float* f) {
+  if (ESZ == 4) {
+    const v4f a = *(const v4f*)((const float*)lds + idx), b = *(const v4f*)((const float*)lds + idx + 4);
+#pragma unroll
+    for (int i = 0; i < 4; i++) { f[i] = a[i]; f[4 + i] = b[i]; }
+  } else {
+    const v4i raw = *(const v4i*)((const uint16_t*)lds + idx);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      f[2 * i] = __uint_as_float((uint32_t)raw[i] << 16);
+      f[2 * i + 1] = __uint_as_float((uint32_t)raw[i] & 0xFFFF0000u);
+    }
+  }
+}
+
+// q~[g][j] = c_scale * sum_c B_K[kv][j][c] * q[b, kv*G+g][c]   (query absorption; whole workgroup, any multiple of 64 threads).
+// bk_lds holds B_K[kv] (R x d, element size ESZ); q_lds [G][d] floats.  Work is split into chunks of 8
+// columns: chunk id -> (row j, column block); the d/8 lanes of a row are adjacent.  Ends with a barrier.
+template <int R, int ESZ>
+WSVD_DEV void compute_qtilde(const AttnParams& p, const void* bk_lds, const float* q_lds, float* qts /* LDS [G][R] */) {
+  const int tid = threadIdx.x;
+  const int cpr = p.d >> 3;                 // chunks per row: 16 (d = 128) or 8 (d = 64)
+  const int n_chunks = R * cpr;
+  const int nt = blockDim.x;
+  for (int ch = tid; ch < (n_chunks + nt - 1) / nt * nt; ch += nt) {   // uniform trip count: DPP needs whole rows active
+    const bool on = ch < n_chunks;
+    const int j = on ? ch / cpr : 0, cb = on ? ch % cpr : 0;
+    float bk[8];
+    lds_load8<ESZ>(bk_lds, j * p.d + cb * 8, bk);
+    for (int g = 0; g < p.G; g++) {
+      const v4f q0 = *(const v4f*)(q_lds + g * p.d + cb * 8), q1 = *(const v4f*)(q_lds + g * p.d + cb * 8 + 4);
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; i++) { acc = fmaf(bk[i], q0[i], acc); acc = fmaf(bk[4 + i], q1[i], acc); }
+      acc = cpr == 16 ? group_sum<16>(acc) : group_sum<8>(acc);
+      if (on && cb == 0) qts[g * R + j] = acc * p.c_scale;
+    }
   }
   __syncthreads();
 }
@@ -82,53 +137,56 @@ WSVD_DEV void compute_qtilde(const AttnParams& p, const WorkItem& w, float* qts 
 // max (log2 domain), sum and un-normalised latent-space accumulator, visible to all threads.
 // If the sequence was split over several workgroups the partials go to the workspace and the last
 // workgroup to arrive (ticket) merges them in split order; then out = (u / l) B_V.
-template <int R>
-WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, float* Lsh, float* Ush, int* flag_sh) {
+template <int R, int ESZ>
+WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, float* Lsh, float* Ush, int* flag_sh,
+                        const void* bv_lds) {
   const int tid = threadIdx.x;
   const int G = p.G;
   if (w.n_splits > 1) {
+    // Cross-workgroup hand-off without cache-wide fences: partials are written and read with agent-scope
+    // (write-through / cache-bypassing) accesses, ordered by the workgroup barriers around the ticket.
     for (int i = tid; i < G * (R + 2); i += blockDim.x) {
       const int g = i / (R + 2), k = i % (R + 2);
       const float v = k == 0 ? Msh[g] : k == 1 ? Lsh[g] : Ush[g * R + (k - 2)];
-      p.partials[(((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks + w.chunk) * (R + 2) + k] = v;
+      agent_store(&p.partials[(((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks + w.chunk) * (R + 2) + k], v);
     }
-    __threadfence();
-    __syncthreads();
+    __syncthreads();   // every thread's partial stores have completed (vmcnt 0) before the ticket is taken
     if (tid == 0) {
       int* t = p.tickets + (size_t)w.b * p.Hkv + w.kv;
-      const int old = atomicAdd(t, 1);
+      const int old = __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const int last = (old == w.n_splits - 1);
-      if (last) atomicExch(t, 0);   // every other workgroup of this (b, kv) has already taken its ticket
+      if (last) __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // all other tickets of this (b, kv) are taken
       *flag_sh = last;
     }
     __syncthreads();
     if (!*flag_sh) return;
-    __threadfence();
     for (int i = tid; i < G * R; i += blockDim.x) {
       const int g = i / R, j = i % R;
       const float* base = p.partials + (((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks) * (R + 2);
       float M = -INFINITY;
-      for (int c = 0; c < w.n_splits; c++) M = fmaxf(M, __builtin_nontemporal_load(base + (size_t)c * (R + 2)));
+      for (int c = 0; c < w.n_splits; c++) M = fmaxf(M, agent_load(base + (size_t)c * (R + 2)));
       float L = 0.f, U = 0.f;
       for (int c = 0; c < w.n_splits; c++) {
         const float* pc = base + (size_t)c * (R + 2);
-        const float e = __builtin_amdgcn_exp2f(__builtin_nontemporal_load(pc) - M);
-        L = fmaf(__builtin_nontemporal_load(pc + 1), e, L);
-        U = fmaf(__builtin_nontemporal_load(pc + 2 + j), e, U);
+        const float e = __builtin_amdgcn_exp2f(agent_load(pc) - M);
+        L = fmaf(agent_load(pc + 1), e, L);
+        U = fmaf(agent_load(pc + 2 + j), e, U);
       }
       Ush[i] = U;
       if (j == 0) { Lsh[g] = L; Msh[g] = M; }
     }
     __syncthreads();
   }
-  // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c]
+  // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c], B_V[kv] staged in LDS
   for (int i = tid; i < G * p.d; i += blockDim.x) {
     const int g = i / p.d, c = i % p.d;
     const float inv = 1.f / Lsh[g];
     float acc = 0.f;
 #pragma unroll 8
-    for (int j = 0; j < R; j++)
-      acc = fmaf(Ush[g * R + j], load_as_f32(p.BV, ((size_t)w.kv * R + j) * p.d + c, p.factor_dtype), acc);
+    for (int j = 0; j < R; j++) {
+      const float b = ESZ == 4 ? ((const float*)bv_lds)[j * p.d + c] : bf16_to_f32(((const uint16_t*)bv_lds)[j * p.d + c]);
+      acc = fmaf(Ush[g * R + j], b, acc);
+    }
     p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = acc * inv;
   }
 }

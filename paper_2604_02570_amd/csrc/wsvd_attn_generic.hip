@@ -32,6 +32,9 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
   constexpr int NGRP = 4 * RPW;          // lane groups per workgroup
   constexpr int UNROLL = 4;
 
+  constexpr int FIT = R * ESZ / 32;     // 16-byte staging passes for an R x 128 factor
+  __shared__ v4i fac_lds[R * 128 * ESZ / 16];
+  __shared__ __attribute__((aligned(16))) float q_lds[G * 128];
   __shared__ float qts[G * R];
   __shared__ float Msh[G], Lsh[G], Ush[G * R];
   __shared__ float gm[NGRP * G], gl[NGRP * G];
@@ -45,7 +48,15 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
   const int sl = lane % LPR;                       // which 16-byte slice of the row
   const int grp = wave * RPW + lane / LPR;         // lane group id within the workgroup
 
-  compute_qtilde<R>(p, w, qts);
+  const int fac16 = R * p.d * ESZ / 16;
+  {
+    StageRegs<FIT> st;
+    stage_issue<FIT>(st, (const char*)p.BK + (size_t)w.kv * R * p.d * ESZ, fac16);
+    stage_q(p, w, q_lds);
+    stage_commit<FIT>(st, fac_lds, fac16);
+  }
+  __syncthreads();
+  compute_qtilde<R, ESZ>(p, fac_lds, q_lds, qts);
   float qt[G][VPL];
 #pragma unroll
   for (int g = 0; g < G; g++)
@@ -121,8 +132,13 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
     Ush[i] = U;
     if (j == 0) { Msh[g] = M; Lsh[g] = L; }
   }
+  {
+    StageRegs<FIT> st;   // B_K is no longer needed: reuse its LDS for B_V
+    stage_issue<FIT>(st, (const char*)p.BV + (size_t)w.kv * R * p.d * ESZ, fac16);
+    stage_commit<FIT>(st, fac_lds, fac16);
+  }
   __syncthreads();
-  attn_tail<R>(p, w, Msh, Lsh, Ush, &flag_sh);
+  attn_tail<R, ESZ>(p, w, Msh, Lsh, Ush, &flag_sh, fac_lds);
 }
 
 template <int ESZ, int R>

@@ -53,25 +53,32 @@ WSVD_DEV float limbs_to_f32(int h, int m, int l) { return fmaf((float)h, 16384.f
 
 constexpr float kLimbFull = 1048576.f;   // 2^20: |quantised value| <= 2^20 fits three 7-bit limbs
 
-template <int R, int G, bool I4>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p) {
+constexpr int kMaxWaves = 16;
+
+// NT = launch bound (threads); the workgroup may be launched with any multiple of 64 threads up to NT.
+template <int R, int G, bool I4, int NT>
+__global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
+  constexpr int NWMAX = NT / 64;
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
 
+  constexpr int FIT = R / 16;           // 16-byte staging passes for an R x 128 bf16 factor
+  __shared__ v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
+  __shared__ __attribute__((aligned(16))) float q_lds[G * 128];
   __shared__ float qts[G * R];
   __shared__ __attribute__((aligned(16))) int8_t qlimb[G][3][R];   // limbs of q~ in operand k-order
   __shared__ float qdelta[G], qzsum[G];
-  __shared__ __attribute__((aligned(16))) uint8_t wl[4][G][3][64]; // per wave: limbs of the value weights, by token
-  __shared__ float wm[4][G], wls[4][G];
-  __shared__ float wu[4][G][R];
+  __shared__ __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
+  __shared__ float wm[NWMAX][G], wls[NWMAX][G];
+  __shared__ float wu[NWMAX][G][R];
   __shared__ float Msh[G], Lsh[G], Ush[G * R];
   __shared__ int flag_sh;
 
   const WorkItem w = decode_work(p);
   if (w.n == 0) { write_zero_outputs(p, w); return; }
   if (!w.active) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
   const int tile_begin = w.row_begin >> 6, tile_end = (w.row_end + 63) >> 6;
 
   const size_t ph = (size_t)w.b * p.Hkv + w.kv;
@@ -81,14 +88,22 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p) {
   const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
   const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
 
-  // ---- start streaming before anything else: two tiles per wave in flight
+  // ---- factors of this head first (small, they return first), then start streaming: two tiles per wave in flight
+  const int fac16 = R * p.d * 2 / 16;
+  StageRegs<FIT> stk, stv;
+  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)w.kv * R * p.d * 2, fac16);
+  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)w.kv * R * p.d * 2, fac16);
+  stage_q(p, w, q_lds);
   TileRegs<R, I4> bufA, bufB;
   int T = tile_begin + wave;
   if (T < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T, lane);
-  if (T + 4 < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + 4, lane);
+  if (T + NW < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + NW, lane);
 
   // ---- query absorption and its limbs
-  compute_qtilde<R>(p, w, qts);
+  stage_commit<FIT>(stk, bk_lds, fac16);
+  stage_commit<FIT>(stv, bv_lds, fac16);
+  __syncthreads();
+  compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   if (tid < G * R) {
     const int g = tid / R, j = tid % R;
     const float v = qts[tid];
@@ -228,15 +243,15 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p) {
     }
   };
 
-  // ---- ping-pong over this wave's tiles (tile_begin + wave, step 4)
+  // ---- ping-pong over this wave's tiles (tile_begin + wave, step NW)
   while (T < tile_end) {
     compute(bufA, T);
-    if (T + 8 < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T + 8, lane);
-    T += 4;
+    if (T + 2 * NW < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T + 2 * NW, lane);
+    T += NW;
     if (T >= tile_end) break;
     compute(bufB, T);
-    if (T + 8 < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + 8, lane);
-    T += 4;
+    if (T + 2 * NW < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + 2 * NW, lane);
+    T += NW;
   }
 
   // ---- per-wave state -> workgroup merge
@@ -253,10 +268,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p) {
   __syncthreads();
   if (tid < G * R) {
     const int g = tid / R, j = tid % R;
-    const float M = fmaxf(fmaxf(wm[0][g], wm[1][g]), fmaxf(wm[2][g], wm[3][g]));
+    float M = wm[0][g];
+    for (int k = 1; k < NW; k++) M = fmaxf(M, wm[k][g]);
     float L = 0.f, U = 0.f;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
+    for (int k = 0; k < NW; k++) {
       const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
       L = fmaf(wls[k][g], e, L);
       U = fmaf(wu[k][g][j], e, U);
@@ -265,24 +280,28 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p) {
     if (j == 0) { Msh[g] = M; Lsh[g] = L; }
   }
   __syncthreads();
-  attn_tail<R>(p, w, Msh, Lsh, Ush, &flag_sh);
+  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, bv_lds);
 }
 
-template <int R, bool I4>
-static hipError_t launch_m(const AttnParams& p, dim3 grid, hipStream_t s) {
+template <int R, bool I4, int NT>
+static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
+  if (threads > NT || threads % 64) return hipErrorInvalidValue;
   switch (p.G) {
-    case 1: hipLaunchKernelGGL((k_attn_mfma<R, 1, I4>), grid, dim3(256), 0, s, p); break;
-    case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4>), grid, dim3(256), 0, s, p); break;
-    case 3: hipLaunchKernelGGL((k_attn_mfma<R, 3, I4>), grid, dim3(256), 0, s, p); break;
-    case 4: hipLaunchKernelGGL((k_attn_mfma<R, 4, I4>), grid, dim3(256), 0, s, p); break;
+    case 1: hipLaunchKernelGGL((k_attn_mfma<R, 1, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 3: hipLaunchKernelGGL((k_attn_mfma<R, 3, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((k_attn_mfma<R, 4, I4, NT>), grid, dim3(threads), 0, s, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
-hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s) {
-  if (latent_dtype == WSVD_I8 && rank == 32) return launch_m<32, false>(p, grid, s);
-  if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false>(p, grid, s);
-  if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true>(p, grid, s);
+// largest workgroup (threads) each instantiation may be launched with
+int wsvd_attn_mfma_max_threads(int latent_dtype, int rank) { return (latent_dtype == WSVD_I8 && rank == 64) ? 512 : 1024; }
+
+hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (latent_dtype == WSVD_I8 && rank == 32) return launch_m<32, false, 1024>(p, grid, threads, s);
+  if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false, 512>(p, grid, threads, s);
+  if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true, 1024>(p, grid, threads, s);
   return hipErrorInvalidValue;
 }

@@ -31,6 +31,13 @@ WSVD_DEV float load_as_f32(const void* p, size_t idx, int dtype) {
   return dtype == WSVD_F32 ? ((const float*)p)[idx] : bf16_to_f32(((const uint16_t*)p)[idx]);
 }
 
+// ---------------------------------------------------------------- cross-workgroup hand-off
+// Agent-scope relaxed accesses: the store is written through and the load bypasses non-coherent cache
+// lines, so data handed from one workgroup to another (possibly on another XCD, behind another L2) needs
+// no cache-wide write-back / invalidate.  Ordering comes from the barriers and waits around the ticket.
+WSVD_DEV void agent_store(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+WSVD_DEV float agent_load(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
 // ---------------------------------------------------------------- wave64 reductions (DPP)
 template <int CTRL>
 WSVD_DEV float dpp_mov_f(float x) {

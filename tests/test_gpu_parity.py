@@ -196,7 +196,11 @@ def test_attention_independent_of_split_count(dtype):
     L = layer_for(c)
     L.upload(c.cache)
     outs = []
+    got, ref = run_attend(c, L)             # default policy: one large workgroup per (sequence, kv head)
+    check_out(got, ref, dtype, "splits default policy")
+    outs.append(got)
     try:
+        W.wsvd_set_option("max_threads", 256)
         for mc in (2048, 1024, 512, 256):   # 1, 2, 3 and 6 context chunks per (sequence, kv head)
             W.wsvd_set_option("min_chunk", mc)
             got, ref = run_attend(c, L)
@@ -204,6 +208,7 @@ def test_attention_independent_of_split_count(dtype):
             outs.append(got)
     finally:
         W.wsvd_set_option("min_chunk", 256)
+        W.wsvd_set_option("max_threads", 0)
     for o in outs[1:]:
         assert np.abs(o - outs[0]).max() <= 1e-5 * np.abs(outs[0]).max()
     # repeatability: same launch twice gives identical bits (fixed merge order)
