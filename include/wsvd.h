@@ -125,7 +125,7 @@ wsvd_status wsvd_latent_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const
  *   out[b,h,:] = softmax_t( sm_scale * q[b,h,:] . (C_K[b,kv,t,:] B_K[kv]) ) . (C_V[b,kv,:,:] B_V[kv])
  * over rows t < n; n == 0 gives zeros.  Computed as q~ = B_K q, scores on the latent rows, u = p^T C_V,
  * out = u B_V (associativity only).
- *   q [B,Hq,d_head] of q_dtype; q_scale fp16 [B] iff q_dtype == I8
+ *   q [B,Hq,d_head] of q_dtype; q_scale fp16 [B] iff q_dtype == I8 (buffer padded to a multiple of 4 bytes)
  *   B_K,B_V [Hkv, rank, d_head] of factor_dtype;  out [B,Hq,d_head] F32
  *   max_seq_len: HOST upper bound on seq_lens (sizes the grid); must be <= t_cap.
  */

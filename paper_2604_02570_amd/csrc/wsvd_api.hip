@@ -311,7 +311,7 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   if (chunk_rows < min_chunk) chunk_rows = min_chunk;
   p.chunk_rows = chunk_rows;
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
-  dim3 grid((unsigned)((size_t)n_units * p.n_chunks));
+  dim3 grid((unsigned)d.n_kv_heads, (unsigned)p.n_chunks, (unsigned)d.batch);
   if (!mfma) return wsvd_launch_attn_generic(p, d.latent_dtype, d.rank, grid, s);
   if (p.G <= 4) return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, nw * 64, s);
   return wsvd_launch_attn_gqa(p, d.latent_dtype, d.rank, grid, s);

@@ -28,15 +28,14 @@ struct WorkItem {
   bool active;
 };
 
-// blockIdx.x -> (b, chunk, kv) with kv fastest: workgroups are dealt round-robin to the 8 XCDs, so with
-// Hkv a multiple of 8 each XCD's L2 only ever sees the B factors of Hkv/8 heads.
+// Grid = (Hkv, n_chunks, B): blockIdx.x = kv head, .y = context chunk, .z = sequence.  The linear workgroup id
+// (x fastest) is dealt round-robin to the 8 XCDs, so with Hkv a multiple of 8 each XCD's L2 only ever sees the
+// B factors of Hkv/8 heads.  No integer division on the way to the first load.
 WSVD_DEV WorkItem decode_work(const AttnParams& p) {
   WorkItem w;
-  int id = blockIdx.x;
-  w.kv = id % p.Hkv;
-  id /= p.Hkv;
-  w.chunk = id % p.n_chunks;
-  w.b = id / p.n_chunks;
+  w.kv = blockIdx.x;
+  w.chunk = blockIdx.y;
+  w.b = blockIdx.z;
   w.n = p.seq_lens[w.b];
   w.n = w.n < 0 ? 0 : (w.n > p.t_cap ? p.t_cap : w.n);
   w.n_splits = (w.n + p.chunk_rows - 1) / p.chunk_rows;
@@ -62,10 +61,12 @@ struct StageRegs { v4i v[MAXIT]; };
 
 template <int MAXIT>
 WSVD_DEV void stage_issue(StageRegs<MAXIT>& r, const void* src, int n16) {
+  // Unconditional loads (index clamped): a load under a branch would force every later wait to drain the whole
+  // queue, tile prefetches included, because the wait-count bookkeeping is conservative across control flow.
 #pragma unroll
   for (int it = 0; it < MAXIT; it++) {
-    const int idx = it * (int)blockDim.x + (int)threadIdx.x;
-    if (idx < n16) r.v[it] = ((const v4i*)src)[idx];
+    const int idx = min(it * (int)blockDim.x + (int)threadIdx.x, n16 - 1);
+    r.v[it] = ((const v4i*)src)[idx];
   }
 }
 template <int MAXIT>
@@ -77,17 +78,41 @@ WSVD_DEV void stage_commit(const StageRegs<MAXIT>& r, void* lds, int n16) {
   }
 }
 
-// element c of the query of head slot g (any q_dtype) as float
-WSVD_DEV float load_q(const AttnParams& p, size_t idx, float qs) {
-  if (p.q_dtype == WSVD_I8) return (float)((const int8_t*)p.q)[idx] * qs;
-  return load_as_f32(p.q, idx, p.q_dtype);
+// queries of the G heads of kv head `kv` of sequence `b` -> LDS floats [G][d].  Split into issue (global loads
+// into registers) and commit (LDS stores) so that other loads can be put in flight in between.  G*d <= 512.
+// The issue phase only loads raw bits (no arithmetic on them), so it never waits.
+struct QRegs { uint32_t raw[2]; };
+WSVD_DEV void q_issue(const AttnParams& p, int b, int kv, QRegs& r) {
+  // one unconditional dword load per element: the aligned dword that contains it (4 int8, 2 bf16 or 1 fp32)
+  const size_t base = ((size_t)b * p.Hq + (size_t)kv * p.G) * p.d;
+  const int sh = p.q_dtype == WSVD_I8 ? 2 : p.q_dtype == WSVD_BF16 ? 1 : 0;
+  const int n = p.G * p.d;
+#pragma unroll
+  for (int it = 0; it < 2; it++) {
+    const int i = min(it * 256 + (int)(threadIdx.x & 255), n - 1);
+    r.raw[it] = ((const uint32_t*)p.q)[(base + i) >> sh];
+  }
 }
-
-// queries of the G heads of this kv head -> LDS floats [G][d] (one element per thread and pass)
-WSVD_DEV void stage_q(const AttnParams& p, const WorkItem& w, float* q_lds) {
-  const float qs = p.q_dtype == WSVD_I8 ? f16_bits_to_f32(p.q_scale[w.b]) : 1.f;
-  const size_t base = ((size_t)w.b * p.Hq + (size_t)w.kv * p.G) * p.d;
-  for (int i = threadIdx.x; i < p.G * p.d; i += blockDim.x) q_lds[i] = load_q(p, base + i, qs);
+// fp16 scale of sequence b's int8 query through a scalar dword load (the buffer is 4-byte aligned and padded)
+WSVD_DEV float q_scale_of(const AttnParams& p, int b) {
+  if (p.q_dtype != WSVD_I8) return 1.f;
+  const uint32_t wraw = ((const uint32_t*)p.q_scale)[b >> 1];
+  return f16_bits_to_f32((uint16_t)((b & 1) ? (wraw >> 16) : (wraw & 0xFFFFu)));
+}
+WSVD_DEV void q_commit(const AttnParams& p, const QRegs& r, float qs, float* q_lds) {
+  const int n = p.G * p.d;
+#pragma unroll
+  for (int it = 0; it < 2; it++) {
+    const int i = it * 256 + (int)threadIdx.x;
+    if (threadIdx.x < 256 && i < n) {
+      // (b*Hq + kv*G)*d is a multiple of 64, so element i sits at position i % (4 >> ...) of its dword
+      float v;
+      if (p.q_dtype == WSVD_I8) v = (float)(int8_t)(r.raw[it] >> ((i & 3) * 8)) * qs;
+      else if (p.q_dtype == WSVD_BF16) v = __uint_as_float((i & 1) ? (r.raw[it] & 0xFFFF0000u) : (r.raw[it] << 16));
+      else v = __uint_as_float(r.raw[it]);
+      q_lds[i] = v;
+    }
+  }
 }
 
 // 8 consecutive factor elements from LDS as float

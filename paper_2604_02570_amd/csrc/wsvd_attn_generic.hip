@@ -51,9 +51,11 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
   const int fac16 = R * p.d * ESZ / 16;
   {
     StageRegs<FIT> st;
+    QRegs qr;
     stage_issue<FIT>(st, (const char*)p.BK + (size_t)w.kv * R * p.d * ESZ, fac16);
-    stage_q(p, w, q_lds);
+    q_issue(p, w.b, w.kv, qr);
     stage_commit<FIT>(st, fac_lds, fac16);
+    q_commit(p, qr, q_scale_of(p, w.b), q_lds);
   }
   __syncthreads();
   compute_qtilde<R, ESZ>(p, fac_lds, q_lds, qts);

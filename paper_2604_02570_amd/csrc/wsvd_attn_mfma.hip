@@ -2,13 +2,17 @@
 //
 // The cache planes are stored as MFMA operand images (layout in wsvd.h), so the 16 bytes a lane loads
 // ARE its slice of the B operand of V_MFMA_I32_32X32X32_I8: no unpack for I8, two mask/shift pairs per
-// dword for I4.  The float side of each product is carried as three signed 7-bit limbs:
+// dword for I4.  The float side of each product is carried as three 7-bit limbs:
 //   * score pass:  q~ (B_K folded into the query) = delta * (h*2^14 + m*2^7 + l); rows of the A operand
 //     are the limbs, columns of B are tokens, so D[limb][token] are exact int32 dot products;
-//   * value pass:  w_t = p_t * scale_V[t] = omega * (h*2^14 + m*2^7 + l) per tile; A rows are the
-//     limbs over tokens (transposed through LDS), B is the token-minor V block, D[limb][dim].
+//   * value pass:  w_t = p_t * scale_V[t] = omega * (h*2^14 + m*2^7 + l); A rows are the limbs over tokens
+//     (transposed through LDS), B is the token-minor V block, D[limb][dim] accumulates exactly in int32
+//     ACROSS tiles for as long as the softmax reference m and the weight unit omega stay put.
 // A tile is 64 tokens: two 32-token blocks whose score MFMAs are chained into disjoint row groups so
 // that lane L ends up with the scores of token L of the tile.
+// The online softmax is lazy: the wave-wide max reduction, the rescale of the accumulators and the
+// int32 -> float flush only run for tiles that raise the running max or overflow the weight unit
+// (wave-uniform branches); the common tile costs a few dozen vector-ALU instructions.
 // Operand / result register layouts used here were checked on hardware:
 //   A: lane L holds row L%32, k = 16*(L/32)..+15;  B: lane L holds column L%32, same k;
 //   D: lane L, register v holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
@@ -23,26 +27,30 @@ struct TileRegs {
   uint32_t kmeta, vmeta;   // I8: fp16 scale in the low half; I4: scale | zero point << 16
 };
 
+// All offsets are 32-bit and relative to wave-uniform plane pointers, so the loads use the
+// scalar-base + vector-offset addressing form (one address instruction per tile).
 template <int R, bool I4>
 WSVD_DEV void load_tile(TileRegs<R, I4>& t, const uint8_t* kplane, const uint8_t* vplane, const uint16_t* kmeta,
                         const uint16_t* vmeta, int tile, int lane) {
   if (I4) {
-    const size_t off = (size_t)tile * 1024 + lane * 16;
+    const uint32_t off = (uint32_t)tile * 1024u + (uint32_t)lane * 16u;
     t.k[0][0] = __builtin_nontemporal_load((const v4i*)(kplane + off));
     t.v[0][0] = __builtin_nontemporal_load((const v4i*)(vplane + off));
-    t.kmeta = __builtin_nontemporal_load((const uint32_t*)kmeta + (size_t)tile * 64 + lane);
-    t.vmeta = __builtin_nontemporal_load((const uint32_t*)vmeta + (size_t)tile * 64 + lane);
+    const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
+    t.kmeta = __builtin_nontemporal_load((const uint32_t*)kmeta + moff);
+    t.vmeta = __builtin_nontemporal_load((const uint32_t*)vmeta + moff);
   } else {
-    const size_t off = (size_t)tile * (64 * R) + lane * 16;
+    const uint32_t off = (uint32_t)tile * (uint32_t)(64 * R) + (uint32_t)lane * 16u;
 #pragma unroll
     for (int blk = 0; blk < 2; blk++)
 #pragma unroll
       for (int kk = 0; kk < R / 32; kk++) {
-        t.k[kk][blk] = __builtin_nontemporal_load((const v4i*)(kplane + off + blk * (32 * R) + kk * 1024));
-        t.v[kk][blk] = __builtin_nontemporal_load((const v4i*)(vplane + off + blk * (32 * R) + kk * 1024));
+        t.k[kk][blk] = __builtin_nontemporal_load((const v4i*)(kplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
+        t.v[kk][blk] = __builtin_nontemporal_load((const v4i*)(vplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
       }
-    t.kmeta = __builtin_nontemporal_load(kmeta + (size_t)tile * 64 + lane);
-    t.vmeta = __builtin_nontemporal_load(vmeta + (size_t)tile * 64 + lane);
+    const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
+    t.kmeta = __builtin_nontemporal_load(kmeta + moff);
+    t.vmeta = __builtin_nontemporal_load(vmeta + moff);
   }
 }
 
@@ -51,23 +59,22 @@ WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_3
 // three limb dot products -> float: h*2^14 + m*2^7 + l
 WSVD_DEV float limbs_to_f32(int h, int m, int l) { return fmaf((float)h, 16384.f, fmaf((float)m, 128.f, (float)l)); }
 
-constexpr float kLimbFull = 1048576.f;   // 2^20: |quantised value| <= 2^20 fits three 7-bit limbs
-
-constexpr int kMaxWaves = 16;
+constexpr float kLimbFull = 1048576.f;    // 2^20: |quantised value| <= 2^20 fits three 7-bit limbs
+constexpr int kMaxTilesPerFlush = 1024;   // 64 tokens * 127 * 127 per tile and limb: int32 holds > 2000 tiles
 
 // NT = launch bound (threads); the workgroup may be launched with any multiple of 64 threads up to NT.
 template <int R, int G, bool I4, int NT>
 __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
-  constexpr int NWMAX = NT / 64;
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
-
+  constexpr int NWMAX = NT / 64;
   constexpr int FIT = R / 16;           // 16-byte staging passes for an R x 128 bf16 factor
+
   __shared__ v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
   __shared__ __attribute__((aligned(16))) float q_lds[G * 128];
   __shared__ float qts[G * R];
-  __shared__ __attribute__((aligned(16))) int8_t qlimb[G][3][R];   // limbs of q~ in operand k-order
+  __shared__ __attribute__((aligned(16))) int8_t qlimb[G][3][R];       // limbs of q~ in operand k-order
   __shared__ float qdelta[G], qzsum[G];
   __shared__ __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
   __shared__ float wm[NWMAX][G], wls[NWMAX][G];
@@ -75,33 +82,45 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   __shared__ float Msh[G], Lsh[G], Ush[G * R];
   __shared__ int flag_sh;
 
-  const WorkItem w = decode_work(p);
-  if (w.n == 0) { write_zero_outputs(p, w); return; }
-  if (!w.active) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
-  const int tile_begin = w.row_begin >> 6, tile_end = (w.row_end + 63) >> 6;
-
-  const size_t ph = (size_t)w.b * p.Hkv + w.kv;
+  const size_t ph = (size_t)blockIdx.z * p.Hkv + blockIdx.x;
   const size_t plane_bytes = (size_t)p.t_cap * (I4 ? R / 2 : R);
   const uint8_t* kplane = p.k_codes + ph * plane_bytes;
   const uint8_t* vplane = p.v_codes + ph * plane_bytes;
   const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
   const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
 
-  // ---- factors of this head first (small, they return first), then start streaming: two tiles per wave in flight
+  // ---- loads, in the order they should come back: the small per-head inputs (B_K, B_V, queries) first, then
+  // DEPTH tiles per wave (a tile = 64 rows of K and V codes plus metadata), requested before the sequence length
+  // is known.  Every tile below t_cap is allocated memory, so the loads are safe; tiles past the sequence end are
+  // never consumed.  The prologue below then runs in the shadow of the first tiles' latency.
   const int fac16 = R * p.d * 2 / 16;
   StageRegs<FIT> stk, stv;
-  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)w.kv * R * p.d * 2, fac16);
-  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)w.kv * R * p.d * 2, fac16);
-  stage_q(p, w, q_lds);
-  TileRegs<R, I4> bufA, bufB;
-  int T = tile_begin + wave;
-  if (T < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T, lane);
-  if (T + NW < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + NW, lane);
+  QRegs qr;
+  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)blockIdx.x * R * p.d * 2, fac16);
+  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
+  q_issue(p, blockIdx.z, blockIdx.x, qr);
+  constexpr int DEPTH = 2;
+  TileRegs<R, I4> buf[DEPTH];
+  const int chunk_tiles = p.chunk_rows >> 6;
+  int T = (int)blockIdx.y * chunk_tiles + wave;
+  {
+    // unconditional (clamped to the chunk's last allocated tile): see stage_issue
+    const int spec_last = min(((int)blockIdx.y + 1) * chunk_tiles, p.t_cap >> 6) - 1;
+#pragma unroll
+    for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+  }
+
+  const float qs = q_scale_of(p, blockIdx.z);
+  const WorkItem w = decode_work(p);
+  if (w.n == 0) { write_zero_outputs(p, w); return; }
+  if (!w.active) return;
+  const int tile_end = (w.row_end + 63) >> 6;
 
   // ---- query absorption and its limbs
   stage_commit<FIT>(stk, bk_lds, fac16);
   stage_commit<FIT>(stv, bv_lds, fac16);
+  q_commit(p, qr, qs, q_lds);
   __syncthreads();
   compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   if (tid < G * R) {
@@ -110,7 +129,7 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
     const float amax = (R == 64) ? wave_max(fabsf(v)) : half_max(fabsf(v), lane);
     const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
     const int Q = (int)__builtin_rintf(v * inv);
-    const int l0 = ((Q + 64) & 127) - 64;
+    const int l0 = ((Q + 64) & 127) - 64;          // balanced digits, each in [-64, 64]
     const int Q1 = (Q - l0) >> 7;
     const int l1 = ((Q1 + 64) & 127) - 64;
     const int l2 = (Q1 - l1) >> 7;
@@ -138,8 +157,7 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
     const bool act = (a < G) && (limb < 3);
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
-      v4i val = {0, 0, 0, 0};
-      if (act) val = *(const v4i*)&qlimb[a < G ? a : 0][limb < 3 ? limb : 0][kk * 32 + g2 * 16];
+      const v4i val = *(const v4i*)&qlimb[a < G ? a : 0][limb < 3 ? limb : 0][kk * 32 + g2 * 16];
       const v4i zero = {0, 0, 0, 0};
       a1[kk] = (act && grp == 0) ? val : zero;
       a2[kk] = (act && grp == 1) ? val : zero;
@@ -149,20 +167,39 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
 #pragma unroll
   for (int g = 0; g < G; g++) { delta[g] = qdelta[g]; zsum[g] = qzsum[g]; }
 
-  float m[G], lsum[G], zacc[G], u[G][KK];
+  // running state: m (log2-domain reference), wref (fixed-point range of the value weights), their derived
+  // omega = wref / 2^20 and winv = 2^20 / wref; lsum, zacc, u are per-lane partial sums
+  float m[G], wref[G], omega[G], winv[G], lsum[G], zacc[G], u[G][KK];
+  v16i vacc[KK];
 #pragma unroll
   for (int g = 0; g < G; g++) {
-    m[g] = -INFINITY; lsum[g] = 0.f; zacc[g] = 0.f;
+    m[g] = -INFINITY; wref[g] = 0.f; omega[g] = 0.f; winv[g] = 0.f; lsum[g] = 0.f; zacc[g] = 0.f;
 #pragma unroll
     for (int jj = 0; jj < KK; jj++) u[g][jj] = 0.f;
   }
+#pragma unroll
+  for (int jj = 0; jj < KK; jj++)
+#pragma unroll
+    for (int x = 0; x < 16; x++) vacc[jj][x] = 0;
+  int since_flush = 0;
+
+  // int32 accumulators of head slot g -> float accumulators, in units of the current omega
+  auto flush = [&](int g) {
+#pragma unroll
+    for (int jj = 0; jj < KK; jj++) {
+      u[g][jj] = fmaf(omega[g], limbs_to_f32(vacc[jj][4 * g], vacc[jj][4 * g + 1], vacc[jj][4 * g + 2]), u[g][jj]);
+      vacc[jj][4 * g] = 0; vacc[jj][4 * g + 1] = 0; vacc[jj][4 * g + 2] = 0;
+    }
+  };
 
   // weights operand read position: row i -> (query slot, limb); both row groups read the same limbs
   const int wr_a = min((lane & 31) >> 3, G - 1), wr_limb = min(lane & 3, 2), wr_g2 = lane >> 5;
+  // token order inside the wave's limb rows.  I8: token L at byte L.  I4: a V byte holds tokens (2b, 2b+1) of a
+  // 32-token half; the low-nibble operand covers even tokens, the high-nibble operand odd tokens.
+  const int wpos = I4 ? ((lane & 1) << 5) + ((lane >> 5) << 4) + ((lane & 31) >> 1) : lane;
 
   auto compute = [&](TileRegs<R, I4>& t, int tile) {
-    const int tok = tile * 64 + lane;
-    const bool valid = tok < w.row_end;
+    const bool valid = tile * 64 + lane < w.row_end;
     // ---------------- score pass
     v16i acc = {0};
     float ksc, kz = 0.f, vsc, vz = 0.f;
@@ -184,36 +221,45 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
       ksc = f16_bits_to_f32((uint16_t)t.kmeta);
       vsc = f16_bits_to_f32((uint16_t)t.vmeta);
     }
-    float alpha[G], omega[G];
+    if (++since_flush >= kMaxTilesPerFlush) {
+      since_flush = 0;
+#pragma unroll
+      for (int g = 0; g < G; g++) flush(g);
+    }
 #pragma unroll
     for (int g = 0; g < G; g++) {
       float dot = limbs_to_f32(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2]);
-      if (I4) dot -= kz * zsum[g];
-      float s = valid ? ksc * dot * delta[g] : -INFINITY;
-      const float mn = fmaxf(m[g], wave_max(s));
-      alpha[g] = __builtin_amdgcn_exp2f(m[g] - mn);
-      m[g] = mn;
-      const float pw = __builtin_amdgcn_exp2f(s - mn);
-      lsum[g] = fmaf(lsum[g], alpha[g], pw);
-      // ---------------- value weights -> limbs
+      if (I4) dot = fmaf(-kz, zsum[g], dot);
+      const float s = valid ? ksc * dot * delta[g] : -INFINITY;
+      if (__builtin_amdgcn_ballot_w64(s > m[g]) != 0) {          // a new running max somewhere in this tile
+        const float mn = fmaxf(m[g], wave_max(s));
+        const float alpha = __builtin_amdgcn_exp2f(m[g] - mn);
+        flush(g);
+#pragma unroll
+        for (int jj = 0; jj < KK; jj++) u[g][jj] *= alpha;
+        lsum[g] *= alpha; zacc[g] *= alpha;
+        m[g] = mn;
+      }
+      const float pw = __builtin_amdgcn_exp2f(s - m[g]);          // <= 1
+      lsum[g] += pw;
       const float wt = valid ? pw * vsc : 0.f;
-      const float wmax = wave_max(wt);
-      const float winv = wmax > 0.f ? kLimbFull / wmax : 0.f;
-      omega[g] = wmax > 0.f ? wmax / kLimbFull : 0.f;
-      const int Q = (int)__builtin_rintf(wt * winv);      // 0 .. 2^20
-      if (I4) zacc[g] = fmaf(zacc[g], alpha[g], (float)Q * omega[g] * vz);
-      // token order inside the wave's limb rows: I8: token L at byte L.  I4: a V byte holds tokens (2b, 2b+1) of a
-      // 32-token half; the low-nibble operand covers even tokens, the high-nibble operand odd tokens.
-      int pos = lane;
-      if (I4) pos = ((lane & 1) << 5) + ((lane >> 5) << 4) + ((lane & 31) >> 1);
-      wl[wave][g][0][pos] = (uint8_t)(Q >> 14);
-      wl[wave][g][1][pos] = (uint8_t)((Q >> 7) & 127);
-      wl[wave][g][2][pos] = (uint8_t)(Q & 127);
+      if (__builtin_amdgcn_ballot_w64(wt > wref[g]) != 0) {       // a weight beyond the fixed-point range
+        flush(g);
+        wref[g] = 2.f * wave_max(wt);
+        winv[g] = kLimbFull * __builtin_amdgcn_rcpf(wref[g]);
+        omega[g] = wref[g] * (1.f / kLimbFull);
+      }
+      const int Q = (int)__builtin_rintf(wt * winv[g]);           // 0 .. 2^20
+      if (I4) zacc[g] = fmaf((float)Q * omega[g], vz, zacc[g]);
+      wl[wave][g][0][wpos] = (uint8_t)(Q >> 14);
+      wl[wave][g][1][wpos] = (uint8_t)((Q >> 7) & 127);
+      wl[wave][g][2][wpos] = (uint8_t)(Q & 127);
     }
+    // the wave's own LDS writes, then reads: same-wave LDS operations execute in order
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // ---------------- value pass
+    // ---------------- value pass: exact int32 accumulation, no conversion on the common path
     const v4i w0 = *(const v4i*)&wl[wave][wr_a][wr_limb][wr_g2 * 16];
     const v4i w1 = *(const v4i*)&wl[wave][wr_a][wr_limb][32 + wr_g2 * 16];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -224,39 +270,47 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
       v4i lo, hi;
 #pragma unroll
       for (int x = 0; x < 4; x++) { lo[x] = raw[x] & msk; hi[x] = ((uint32_t)raw[x] >> 4) & msk; }
-      v16i vacc = {0};
-      vacc = mfma_i8(w0, lo, vacc);   // w0: limbs of even tokens, k = 16*g2 + b  <->  token 32*g2 + 2b
-      vacc = mfma_i8(w1, hi, vacc);   // w1: limbs of odd tokens
-#pragma unroll
-      for (int g = 0; g < G; g++)
-        u[g][0] = fmaf(u[g][0], alpha[g], omega[g] * limbs_to_f32(vacc[4 * g], vacc[4 * g + 1], vacc[4 * g + 2]));
+      vacc[0] = mfma_i8(w0, lo, vacc[0]);   // w0: limbs of even tokens, k = 16*g2 + b  <->  token 32*g2 + 2b
+      vacc[0] = mfma_i8(w1, hi, vacc[0]);   // w1: limbs of odd tokens
     } else {
 #pragma unroll
       for (int jj = 0; jj < KK; jj++) {
-        v16i vacc = {0};
-        vacc = mfma_i8(w0, t.v[jj][0], vacc);
-        vacc = mfma_i8(w1, t.v[jj][1], vacc);
-#pragma unroll
-        for (int g = 0; g < G; g++)
-          u[g][jj] = fmaf(u[g][jj], alpha[g], omega[g] * limbs_to_f32(vacc[4 * g], vacc[4 * g + 1], vacc[4 * g + 2]));
+        vacc[jj] = mfma_i8(w0, t.v[jj][0], vacc[jj]);
+        vacc[jj] = mfma_i8(w1, t.v[jj][1], vacc[jj]);
       }
     }
   };
 
-  // ---- ping-pong over this wave's tiles (tile_begin + wave, step NW)
-  while (T < tile_end) {
-    compute(bufA, T);
-    if (T + 2 * NW < tile_end) load_tile<R, I4>(bufA, kplane, vplane, kmeta, vmeta, T + 2 * NW, lane);
-    T += NW;
-    if (T >= tile_end) break;
-    compute(bufB, T);
-    if (T + 2 * NW < tile_end) load_tile<R, I4>(bufB, kplane, vplane, kmeta, vmeta, T + 2 * NW, lane);
-    T += NW;
+  // ---- software pipeline over this wave's n tiles (T, T + NW, ...): compute a buffer, refill it.
+  // The steady-state rounds issue their refills unconditionally, in straight-line code: a load under a branch
+  // makes the compiler's wait-count bookkeeping drain the whole queue before every use, which would serialise
+  // the prefetch.  Only the last rounds, where refills run out, use conditional loads.
+  const int n = T < tile_end ? (tile_end - T + NW - 1) / NW : 0;
+  int done = 0;
+  while (done + 2 * DEPTH <= n) {
+#pragma unroll
+    for (int i = 0; i < DEPTH; i++) {
+      compute(buf[i], T + (done + i) * NW);
+      load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
+    }
+    done += DEPTH;
   }
+#pragma unroll
+  for (int i = 0; i < DEPTH; i++) {
+    if (done + i < n) {
+      compute(buf[i], T + (done + i) * NW);
+      if (done + i + DEPTH < n) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
+    }
+  }
+  done += DEPTH;
+#pragma unroll
+  for (int i = 0; i < DEPTH; i++)
+    if (done + i < n) compute(buf[i], T + (done + i) * NW);
 
   // ---- per-wave state -> workgroup merge
 #pragma unroll
   for (int g = 0; g < G; g++) {
+    flush(g);
     const float lw = wave_sum(lsum[g]);
     const float zc = I4 ? wave_sum(zacc[g]) : 0.f;
     if (lane == 0) { wm[wave][g] = m[g]; wls[wave][g] = lw; }
