@@ -73,7 +73,11 @@ def main():
 
     # ---- factors, hidden state of the new token, queries (generator), all made resident
     AK, AV, BK, BV = WI.factors(sp)
-    AKd, AVd, BKd, BVd = (bf16_bits(a) for a in (AK, AV, BK, BV))
+    # the down-projection factors go through the library's one-time packing
+    AKd, AVd = (torch.empty(W.wsvd_factor_a_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(2))
+    for src, dst in ((AK, AKd), (AV, AVd)):
+        W.wsvd_pack_factor_a(ctx, desc, bf16_bits(src), dst)
+    BKd, BVd = (bf16_bits(a) for a in (BK, BV))
     x_new = WI.hidden_states(sp, B, 1.0, which="new")                     # bf16-exact fp32 [B,E]
     xd = bf16_bits(x_new)
     q32 = (x_new.astype(np.float64) @ WI.dense_wq(sp).astype(np.float64)).astype(np.float32)      # [B, Hq*d]

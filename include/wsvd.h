@@ -106,6 +106,17 @@ wsvd_status wsvd_workspace_bytes(const wsvd_layer_desc *desc, size_t *bytes);
 wsvd_status wsvd_set_workspace(wsvd_ctx *ctx, void *dev_ptr, size_t bytes);
 
 /*
+ * Down-projection factors are constants of the layer; the append kernels read them in a matrix-core friendly
+ * packing: blocks of 32 latent channels x 16 model dims stored as the 64-lane x 16-byte register image of a
+ * 32x32x16 MFMA operand (channels padded to a multiple of 32).  wsvd_pack_factor_a converts, once, from the
+ * paper's shape A_h in R^{E x r} (Section 3.1), given row-major as [Hkv, d_model, rank] of factor_dtype.
+ * Both pointers are device pointers; A_packed must hold wsvd_factor_a_bytes bytes.
+ */
+wsvd_status wsvd_factor_a_bytes(const wsvd_layer_desc *desc, size_t *bytes);
+wsvd_status wsvd_pack_factor_a(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *A_row_major, void *A_packed,
+                               void *hip_stream);
+
+/*
  * Decode-step cache update (Section 3.4, decoding pipeline: the new token is down-projected per head
  * and its K and V latents are stored in the cache).  For every sequence b and kv head h:
  *   c_K = x[b,:] A_K[h], c_V = x[b,:] A_V[h]  (fp32 accumulation), rounded to latent_dtype
@@ -113,7 +124,7 @@ wsvd_status wsvd_set_workspace(wsvd_ctx *ctx, void *dev_ptr, size_t bytes);
  * then seq_lens[b] += 1.  A sequence with seq_lens[b] >= t_cap is left unchanged and the
  * context's error word is set to WSVD_E_CAPACITY.
  *   x       [B, d_model] of x_dtype;  x_scale: fp16 [B] iff x_dtype == I8, else NULL
- *   A_K,A_V [Hkv, d_model, rank] of factor_dtype
+ *   A_K,A_V PACKED by wsvd_pack_factor_a (wsvd_factor_a_bytes bytes each).  d_model must be a multiple of 64.
  */
 wsvd_status wsvd_latent_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
                                const void *A_K, const void *A_V, wsvd_cache *cache, void *hip_stream);

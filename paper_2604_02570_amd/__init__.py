@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "WSVD_OK", 1: "WSVD_E_NULL", 2: "WSVD_E_SHAPE", 3: "WSVD_E_DT
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
            "wsvd_set_option", "wsvd_latent_append", "wsvd_decode_attn", "wsvd_check", "wsvd_status_str",
-           "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8"]
+           "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8"]
 
 
 class WsvdError(RuntimeError):
@@ -69,6 +69,8 @@ def lib():
         L.wsvd_decode_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                        POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_check.argtypes = [c_void_p, c_void_p]
+        L.wsvd_factor_a_bytes.argtypes = [POINTER(LayerDesc), POINTER(c_size_t)]
+        L.wsvd_pack_factor_a.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p]
         L.wsvd_quantize_rows.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int64, c_void_p, c_void_p, c_void_p]
         L.wsvd_cache_import.argtypes = [c_void_p, POINTER(LayerDesc), c_int32, c_void_p, c_void_p, c_int32, c_int32,
                                         POINTER(Cache), c_void_p]
@@ -146,6 +148,16 @@ def wsvd_set_workspace(ctx, ws_tensor):
 
 def wsvd_set_option(name: str, value: int):
     _ck(lib().wsvd_set_option(name.encode(), int(value)), "wsvd_set_option")
+
+
+def wsvd_factor_a_bytes(desc):
+    a = c_size_t()
+    _ck(lib().wsvd_factor_a_bytes(byref(desc), byref(a)), "wsvd_factor_a_bytes")
+    return a.value
+
+
+def wsvd_pack_factor_a(ctx, desc, A_row_major, A_packed, stream=None):
+    _ck(lib().wsvd_pack_factor_a(ctx, byref(desc), _ptr(A_row_major), _ptr(A_packed), _stream(stream)), "wsvd_pack_factor_a")
 
 
 def make_cache(k_codes, v_codes, k_meta, v_meta, seq_lens) -> Cache:

@@ -10,6 +10,8 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank);
 hipError_t wsvd_launch_attn_gqa(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
 
+extern int g_append_mode;
+
 namespace {
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -21,7 +23,7 @@ int g_opt_max_threads = 0;    // cap on the MFMA kernels' workgroup size (0 = th
 
 wsvd_status check_desc(const wsvd_layer_desc* d) {
   if (!d) return WSVD_E_NULL;
-  if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->d_model <= 0) return WSVD_E_SHAPE;
+  if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->d_model <= 0 || d->d_model % 64 != 0) return WSVD_E_SHAPE;
   if (d->d_head != 64 && d->d_head != 128) return WSVD_E_SHAPE;
   if (!is_pow2_rank(d->rank)) return WSVD_E_SHAPE;
   if (d->n_q_heads % d->n_kv_heads != 0) return WSVD_E_SHAPE;
@@ -159,6 +161,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!name) return WSVD_E_NULL;
   if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { g_opt_wg_per_cu = value; return WSVD_OK; }
   if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
+  if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { g_append_mode = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
@@ -194,6 +197,23 @@ wsvd_status wsvd_decode_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
   hipError_t e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, (hipStream_t)hip_stream);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_factor_a_bytes(const wsvd_layer_desc* desc, size_t* bytes) {
+  if (!bytes) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  *bytes = (size_t)desc->n_kv_heads * ((desc->rank + 31) / 32) * 32 * desc->d_model * (desc->factor_dtype == WSVD_F32 ? 4 : 2);
+  return WSVD_OK;
+}
+
+wsvd_status wsvd_pack_factor_a(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* A_row_major, void* A_packed, void* hip_stream) {
+  if (!ctx || !A_row_major || !A_packed) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if (!aligned16(A_row_major) || !aligned16(A_packed)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_pack_factor_a(*desc, A_row_major, A_packed, (hipStream_t)hip_stream);
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 

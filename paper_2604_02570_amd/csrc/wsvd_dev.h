@@ -168,6 +168,14 @@ WSVD_DEV size_t i4_v_offset(int t, int j, int* nib) {
   return (size_t)(t >> 6) * 1024 + (size_t)(((tt >> 5) * 32 + j) * 16 + ((tt & 31) >> 1));
 }
 
+// ---------------------------------------------------------------- packed down-projection factor
+// Element (kv head, latent channel j, model dim e) of a packed A factor: blocks of 32 channels x 16 model dims stored
+// as the 64-lane x 8-element image of a 32x32x16 matrix-core operand (lane = (e%16)/8 * 32 + j%32).
+WSVD_DEV size_t a_packed_offset(int kv, int j, int e, int rank, int d_model) {
+  const int tiles = (rank + 31) >> 5;
+  return ((((size_t)(kv * tiles + (j >> 5)) * (size_t)(d_model >> 4) + (size_t)(e >> 4)) * 2 + ((e & 15) >> 3)) * 32 + (j & 31)) * 8 + (e & 7);
+}
+
 // ---------------------------------------------------------------- workspace layout (host + device)
 // [0, kWsCounterInts*4): tickets (zeroed by wsvd_set_workspace, self-resetting), then fp32 partials.
 constexpr int kWsCounterInts = 16384;

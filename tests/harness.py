@@ -93,6 +93,14 @@ class DeviceLayer:
         assert st == 0, W.status_str(st)
         return self.out.cpu().numpy().astype(np.float64)
 
+    def pack_A(self, A32: np.ndarray, dtype: str) -> torch.Tensor:
+        """Down-projection factor [Hkv,E,r] (the paper's shape, row-major) -> the library's packed layout."""
+        src = as_dtype_dev(A32, dtype)
+        dst = torch.empty(W.wsvd_factor_a_bytes(self.desc), dtype=torch.uint8, device="cuda")
+        W.wsvd_pack_factor_a(self.ctx, self.desc, src, dst)
+        torch.cuda.synchronize()
+        return dst
+
     def append(self, x_dev, x_scale_dev, AK_dev, AV_dev):
         W.wsvd_latent_append(self.ctx, self.desc, x_dev, x_scale_dev, AK_dev, AV_dev, self.cache)
         return W.wsvd_check(self.ctx)

@@ -273,7 +273,7 @@ def test_append_matches_oracle(name, over):
     L = layer_for(c)
     L.upload(c.cache)
     xdt = "f32" if sp.factor_dtype == "f32" else "bf16"
-    AKd, AVd = as_dtype_dev(c.AK, sp.factor_dtype), as_dtype_dev(c.AV, sp.factor_dtype)
+    AKd, AVd = L.pack_A(c.AK, sp.factor_dtype), L.pack_A(c.AV, sp.factor_dtype)
     total_flips = 0
     for step in range(min(sp.steps, 3) if sp.steps > 1 else 2):
         x = c.x_new[step % c.x_new.shape[0]]
@@ -304,7 +304,7 @@ def test_append_one_hot_token_and_capacity():
     c.cache.seq_lens[:] = [5, c.t_cap, 0]
     L.upload(c.cache)
     x = np.zeros((3, sp.d_model), np.float32); x[0, 17] = 1; x[1, 3] = 1; x[2, 400] = 1
-    st = L.append(as_dtype_dev(x, "bf16"), None, as_dtype_dev(c.AK, "bf16"), as_dtype_dev(c.AV, "bf16"))
+    st = L.append(as_dtype_dev(x, "bf16"), None, L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16"))
     assert st == 5, "capacity overflow must be reported by wsvd_check"
     assert L.seq_lens.cpu().numpy().tolist() == [6, c.t_cap, 1]
     assert W.wsvd_check(L.ctx) == 0, "error word must clear after being read"
@@ -353,7 +353,7 @@ def test_config1_fp32_full():
     check_out(got, ref, "f32", "c1 attend(256)")
     x = c.x_new[0]
     O.latent_append(c.cache, x.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
-    assert L.append(dev(x), None, dev(c.AK), dev(c.AV)) == 0
+    assert L.append(dev(x), None, L.pack_A(c.AK, "f32"), L.pack_A(c.AV, "f32")) == 0
     qd, qs, q64 = q_to_device(c.q32[0], "f32")
     got = L.attend(qd, qs, dev(c.BK), dev(c.BV), 257)  # GPU-appended row 256 included
     ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
@@ -367,7 +367,7 @@ def test_config2_bf16_32_steps():
     c = build_case("c2")
     sp = c.sp
     L = layer_for(c); L.upload(c.cache)
-    AKd, AVd = as_dtype_dev(c.AK, "bf16"), as_dtype_dev(c.AV, "bf16")
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
     BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
     worst = 0.0
