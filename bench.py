@@ -25,9 +25,8 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy kernel of known
-# size; see profiles/.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy of known size.
+MEASURED_TRAFFIC_BYTES = 72_360_000   # 72.10 MB fetched + 0.26 MB written (profiles/attn_mfma_int8_c3_hbm_traffic.md)
 
 
 def parse():
@@ -39,6 +38,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -177,6 +178,13 @@ def main():
         stream.synchronize()
         attn_us = a0.elapsed_time(a1) * 1e3 / n_attn
         assert W.wsvd_check(ctx, stream) == 0
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     row_bytes = Hkv * 2 * (r + 2)                         # K and V code rows plus their fp16 scales, all kv heads
     bytes_steps = sum(B * rows_at(i) * row_bytes for i in range(args.warmup, total_steps))
