@@ -31,13 +31,12 @@ struct WorkItem {
 // Grid = (Hkv, n_chunks, B): blockIdx.x = kv head, .y = context chunk, .z = sequence.  The linear workgroup id
 // (x fastest) is dealt round-robin to the 8 XCDs, so with Hkv a multiple of 8 each XCD's L2 only ever sees the
 // B factors of Hkv/8 heads.  No integer division on the way to the first load.
-WSVD_DEV WorkItem decode_work(const AttnParams& p) {
+WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) {
   WorkItem w;
   w.kv = blockIdx.x;
   w.chunk = blockIdx.y;
   w.b = blockIdx.z;
-  w.n = p.seq_lens[w.b];
-  w.n = w.n < 0 ? 0 : (w.n > p.t_cap ? p.t_cap : w.n);
+  w.n = n_raw < 0 ? 0 : (n_raw > p.t_cap ? p.t_cap : n_raw);
   w.n_splits = (w.n + p.chunk_rows - 1) / p.chunk_rows;
   w.row_begin = w.chunk * p.chunk_rows;
   w.row_end = min(w.n, w.row_begin + p.chunk_rows);
@@ -94,9 +93,12 @@ WSVD_DEV void q_issue(const AttnParams& p, int b, int kv, QRegs& r) {
   }
 }
 // fp16 scale of sequence b's int8 query through a scalar dword load (the buffer is 4-byte aligned and padded)
-WSVD_DEV float q_scale_of(const AttnParams& p, int b) {
+// Two-step so that the scalar load can be issued at the very top of a kernel and consumed late.
+WSVD_DEV uint32_t q_scale_raw(const AttnParams& p, int b) {
+  return p.q_dtype == WSVD_I8 ? ((const uint32_t*)p.q_scale)[b >> 1] : 0u;
+}
+WSVD_DEV float q_scale_value(const AttnParams& p, int b, uint32_t wraw) {
   if (p.q_dtype != WSVD_I8) return 1.f;
-  const uint32_t wraw = ((const uint32_t*)p.q_scale)[b >> 1];
   return f16_bits_to_f32((uint16_t)((b & 1) ? (wraw >> 16) : (wraw & 0xFFFFu)));
 }
 WSVD_DEV void q_commit(const AttnParams& p, const QRegs& r, float qs, float* q_lds) {
@@ -202,16 +204,22 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
     }
     __syncthreads();
   }
-  // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c], B_V[kv] staged in LDS
-  for (int i = tid; i < G * p.d; i += blockDim.x) {
-    const int g = i / p.d, c = i % p.d;
-    const float inv = 1.f / Lsh[g];
+  // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c], B_V[kv] staged in LDS.
+  // Four adjacent lanes share an output (a quarter of the latent dims each) and add up through DPP, which keeps
+  // the dependent LDS-read chain short at the very end of the kernel.
+  const int n_out = G * p.d;
+  for (int i0 = 0; i0 < n_out * 4; i0 += blockDim.x) {     // uniform trip count: whole quads stay active
+    const int i = i0 + tid;
+    const int o = min(i >> 2, n_out - 1), part = i & 3;
+    const int g = o / p.d, c = o % p.d;
     float acc = 0.f;
-#pragma unroll 8
-    for (int j = 0; j < R; j++) {
+#pragma unroll
+    for (int jj = 0; jj < R / 4; jj++) {
+      const int j = part * (R / 4) + jj;
       const float b = ESZ == 4 ? ((const float*)bv_lds)[j * p.d + c] : bf16_to_f32(((const uint16_t*)bv_lds)[j * p.d + c]);
       acc = fmaf(Ush[g * R + j], b, acc);
     }
-    p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = acc * inv;
+    acc = group_sum<4>(acc);
+    if (part == 0 && (i >> 2) < n_out) p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = acc / Lsh[g];
   }
 }

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
   __shared__ float gu[NGRP * G * R];
   __shared__ int flag_sh;
 
-  const WorkItem w = decode_work(p);
+  const WorkItem w = decode_work(p, p.seq_lens[blockIdx.z]);
   if (w.n == 0) { write_zero_outputs(p, w); return; }
   if (!w.active) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
     stage_issue<FIT>(st, (const char*)p.BK + (size_t)w.kv * R * p.d * ESZ, fac16);
     q_issue(p, w.b, w.kv, qr);
     stage_commit<FIT>(st, fac_lds, fac16);
-    q_commit(p, qr, q_scale_of(p, w.b), q_lds);
+    q_commit(p, qr, q_scale_value(p, w.b, q_scale_raw(p, w.b)), q_lds);
   }
   __syncthreads();
   compute_qtilde<R, ESZ>(p, fac_lds, q_lds, qts);

@@ -79,9 +79,14 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   __shared__ __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
   __shared__ float wm[NWMAX][G], wls[NWMAX][G];
   __shared__ float wu[NWMAX][G][R];
+  __shared__ float wo[NWMAX][G][128];                                  // per wave: its accumulator times B_V
   __shared__ float Msh[G], Lsh[G], Ush[G * R];
   __shared__ int flag_sh;
 
+  // scalar loads first: issued ahead of the flood of vector loads they come back quickly, and nothing needs them
+  // until the tile loop
+  const int n_raw = p.seq_lens[blockIdx.z];
+  const uint32_t qs_raw = q_scale_raw(p, blockIdx.z);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
   const size_t ph = (size_t)blockIdx.z * p.Hkv + blockIdx.x;
   const size_t plane_bytes = (size_t)p.t_cap * (I4 ? R / 2 : R);
@@ -111,16 +116,10 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
     for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
   }
 
-  const float qs = q_scale_of(p, blockIdx.z);
-  const WorkItem w = decode_work(p);
-  if (w.n == 0) { write_zero_outputs(p, w); return; }
-  if (!w.active) return;
-  const int tile_end = (w.row_end + 63) >> 6;
-
   // ---- query absorption and its limbs
   stage_commit<FIT>(stk, bk_lds, fac16);
   stage_commit<FIT>(stv, bv_lds, fac16);
-  q_commit(p, qr, qs, q_lds);
+  q_commit(p, qr, 1.f, q_lds);          // an int8 query's scale is applied to delta below
   __syncthreads();
   compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   if (tid < G * R) {
@@ -163,9 +162,15 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
       a2[kk] = (act && grp == 1) ? val : zero;
     }
   }
+  // only now are the sequence length and the query scale needed
+  const float qs = q_scale_value(p, blockIdx.z, qs_raw);
+  const WorkItem w = decode_work(p, n_raw);
+  if (w.n == 0) { write_zero_outputs(p, w); return; }
+  if (!w.active) return;
+  const int tile_end = (w.row_end + 63) >> 6;
   float delta[G], zsum[G];
 #pragma unroll
-  for (int g = 0; g < G; g++) { delta[g] = qdelta[g]; zsum[g] = qzsum[g]; }
+  for (int g = 0; g < G; g++) { delta[g] = qdelta[g] * qs; zsum[g] = qzsum[g]; }
 
   // running state: m (log2-domain reference), wref (fixed-point range of the value weights), their derived
   // omega = wref / 2^20 and winv = 2^20 / wref; lsum, zacc, u are per-lane partial sums
@@ -318,6 +323,45 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
 #pragma unroll
       for (int jj = 0; jj < KK; jj++) wu[wave][g][jj * 32 + lane] = u[g][jj] - zc;
     }
+  }
+  if (w.n_splits == 1) {
+    // Whole sequence in this workgroup.  Each wave applies B_V to its own accumulator as soon as it is done
+    // (o_w = u_w B_V, two adjacent head-dim columns per lane), while slower waves are still streaming; after the
+    // barrier only a short weighted sum over the waves is left.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint32_t* bv32 = (const uint32_t*)bv_lds;              // bf16 pairs (c, c+1)
+    const int half_d = p.d >> 1;                                  // column pairs per row: 64 (d = 128) or 32
+    if (lane < half_d) {
+#pragma unroll
+      for (int g = 0; g < G; g++) {
+        float o0 = 0.f, o1 = 0.f;
+#pragma unroll 8
+        for (int j = 0; j < R; j++) {
+          const float uj = wu[wave][g][j];
+          const uint32_t bb = bv32[j * half_d + lane];
+          o0 = fmaf(uj, __uint_as_float(bb << 16), o0);
+          o1 = fmaf(uj, __uint_as_float(bb & 0xFFFF0000u), o1);
+        }
+        wo[wave][g][2 * lane] = o0;
+        wo[wave][g][2 * lane + 1] = o1;
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < G * p.d; i += blockDim.x) {
+      const int g = i / p.d, c = i % p.d;
+      float M = wm[0][g];
+      for (int k = 1; k < NW; k++) M = fmaxf(M, wm[k][g]);
+      float L = 0.f, O = 0.f;
+      for (int k = 0; k < NW; k++) {
+        const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
+        L = fmaf(wls[k][g], e, L);
+        O = fmaf(wo[k][g][c], e, O);
+      }
+      p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = O / L;
+    }
+    return;
   }
   __syncthreads();
   if (tid < G * R) {
