@@ -105,7 +105,7 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   stage_issue<FIT>(stk, (const char*)p.BK + (size_t)blockIdx.x * R * p.d * 2, fac16);
   stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
   q_issue(p, blockIdx.z, blockIdx.x, qr);
-  constexpr int DEPTH = 2;
+  constexpr int DEPTH = 2;   // deeper prefetch costs registers and measured slower
   TileRegs<R, I4> buf[DEPTH];
   const int chunk_tiles = p.chunk_rows >> 6;
   int T = (int)blockIdx.y * chunk_tiles + wave;
