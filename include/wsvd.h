@@ -130,6 +130,17 @@ wsvd_status wsvd_latent_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const
                                const void *A_K, const void *A_V, wsvd_cache *cache, void *hip_stream);
 
 /*
+ * The store half of the cache update for callers that compute the new token's latents with their own GEMM
+ * (the quantised setting of Section 4.2, where the down-projection is an int4-weight / int8-activation matmul
+ * fused with the query projection: see wsvd_linear_w4a8).  For every sequence b and kv head h the fp32 row
+ *   c_K[b*ld + h*rank .. + rank),  c_V[b*ld + h*rank .. + rank)        (DEVICE pointers, ld in floats)
+ * is rounded to latent_dtype exactly as wsvd_latent_append would and written at row seq_lens[b]; then
+ * seq_lens[b] += 1.  Capacity handling as in wsvd_latent_append.  c_K and c_V may point into one buffer.
+ */
+wsvd_status wsvd_latent_store(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const float *c_K, const float *c_V,
+                              int64_t ld, wsvd_cache *cache, void *hip_stream);
+
+/*
  * Decode attention over the latent cache (Section 3.4 fused kernel; Section 2.4 flash-decoding
  * schedule: sequence tiles, online softmax, parallel sequence splits merged at the end).
  * For every b and query head h with kv = kv(h), n = seq_lens[b]:
@@ -193,7 +204,8 @@ wsvd_status wsvd_quantize_act_i8(wsvd_ctx *ctx, const void *x, int32_t x_dtype, 
  * symmetric activations): out[m,n] = (sum_k x[m,k] * w[n,k]) * x_scale[m] * w_scale[n], the sum
  * exact in int32.
  *   x int8 [M,K]; x_scale fp16 [M]; w_i4 [N, K/2] two's-complement nibbles, element 2i in the low
- *   nibble of byte i; w_scale fp16 [N]; out [M,N] F32.  K multiple of 64, N multiple of 32, M <= 64.
+ *   nibble of byte i; w_scale fp16 [N]; out [M,N] F32.  K multiple of 64 and <= 65536, N multiple of 32,
+ *   M <= 64.  All DEVICE pointers; x, w_i4 and out 16-byte aligned.
  */
 wsvd_status wsvd_linear_w4a8(wsvd_ctx *ctx, const int8_t *x, const void *x_scale, const void *w_i4,
                              const void *w_scale_f16, int64_t M, int64_t K, int64_t N, void *out,

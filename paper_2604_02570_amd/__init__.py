@@ -20,9 +20,11 @@ DTYPES = {"f32": F32, "bf16": BF16, "f16": F16, "i8": I8, "i4": I4}
 STATUS_NAMES = {0: "WSVD_OK", 1: "WSVD_E_NULL", 2: "WSVD_E_SHAPE", 3: "WSVD_E_DTYPE", 4: "WSVD_E_ALIGN",
                 5: "WSVD_E_CAPACITY", 6: "WSVD_E_UNSUPPORTED", 7: "WSVD_E_HIP", 8: "WSVD_E_WORKSPACE"}
 
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKSPACE = range(9)
+
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
-           "wsvd_set_option", "wsvd_latent_append", "wsvd_decode_attn", "wsvd_check", "wsvd_status_str",
+           "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8"]
 
 
@@ -66,6 +68,7 @@ def lib():
         L.wsvd_set_option.argtypes = [c_char_p, c_int]
         L.wsvd_latent_append.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                          POINTER(Cache), c_void_p]
+        L.wsvd_latent_store.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int64, POINTER(Cache), c_void_p]
         L.wsvd_decode_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                        POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_check.argtypes = [c_void_p, c_void_p]
@@ -169,6 +172,11 @@ def make_cache(k_codes, v_codes, k_meta, v_meta, seq_lens) -> Cache:
 def wsvd_latent_append(ctx, desc, x, x_scale, A_K, A_V, cache, stream=None):
     _ck(lib().wsvd_latent_append(ctx, byref(desc), _ptr(x), _ptr(x_scale), _ptr(A_K), _ptr(A_V), byref(cache),
                                  _stream(stream)), "wsvd_latent_append")
+
+
+def wsvd_latent_store(ctx, desc, c_K, c_V, ld, cache, stream=None):
+    _ck(lib().wsvd_latent_store(ctx, byref(desc), _ptr(c_K), _ptr(c_V), int(ld), byref(cache), _stream(stream)),
+        "wsvd_latent_store")
 
 
 def wsvd_decode_attn(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):

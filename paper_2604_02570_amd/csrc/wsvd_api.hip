@@ -7,8 +7,7 @@
 
 hipError_t wsvd_launch_attn_generic(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
 hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s);
-int wsvd_attn_mfma_max_threads(int latent_dtype, int rank);
-hipError_t wsvd_launch_attn_gqa(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
+int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G);
 
 extern int g_append_mode;
 
@@ -181,6 +180,18 @@ wsvd_status wsvd_latent_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_latent_store(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const float* c_K, const float* c_V, int64_t ld,
+                              wsvd_cache* cache, void* hip_stream) {
+  if (!ctx || !c_K || !c_V) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (ld < (int64_t)desc->n_kv_heads * desc->rank) return WSVD_E_SHAPE;
+  if (((uintptr_t)c_K & 3u) || ((uintptr_t)c_V & 3u)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_latent_store(ctx, *desc, c_K, c_V, ld, *cache, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                              const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len, void* out,
                              void* hip_stream) {
@@ -282,7 +293,7 @@ wsvd_status wsvd_linear_w4a8(wsvd_ctx* ctx, const int8_t* x, const void* x_scale
                              int64_t M, int64_t K, int64_t N, void* out, int32_t out_dtype, void* hip_stream) {
   if (!ctx || !x || !x_scale || !w_i4 || !w_scale_f16 || !out) return WSVD_E_NULL;
   if (out_dtype != WSVD_F32) return WSVD_E_DTYPE;
-  if (M <= 0 || M > 64 || K <= 0 || K % 64 != 0 || N <= 0 || N % 32 != 0) return WSVD_E_SHAPE;
+  if (M <= 0 || M > 64 || K <= 0 || K % 64 != 0 || K > 65536 || N <= 0 || N % 32 != 0 || M * N > INT32_MAX) return WSVD_E_SHAPE;
   if (!aligned16(x) || !aligned16(w_i4) || !aligned16(out)) return WSVD_E_ALIGN;
   hipError_t e = wsvd_launch_linear_w4a8(x, x_scale, w_i4, w_scale_f16, M, K, N, (float*)out, (hipStream_t)hip_stream);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
@@ -320,8 +331,9 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   const int max_tiles = max_rows / 64;
   if (waves_per_unit > max_tiles) waves_per_unit = max_tiles;
   int nw = 4;
-  if (mfma && p.G <= 4) {
-    const int nw_max = (g_opt_max_threads ? g_opt_max_threads : wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank)) / 64;
+  if (mfma) {
+    const int bound = wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank, p.G);
+    const int nw_max = (g_opt_max_threads && g_opt_max_threads < bound ? g_opt_max_threads : bound) / 64;
     while (nw * 2 <= nw_max && nw * 2 <= waves_per_unit) nw *= 2;
   }
   int chunks_wanted = waves_per_unit / nw;
@@ -333,6 +345,5 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
   dim3 grid((unsigned)d.n_kv_heads, (unsigned)p.n_chunks, (unsigned)d.batch);
   if (!mfma) return wsvd_launch_attn_generic(p, d.latent_dtype, d.rank, grid, s);
-  if (p.G <= 4) return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, nw * 64, s);
-  return wsvd_launch_attn_gqa(p, d.latent_dtype, d.rank, grid, s);
+  return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, nw * 64, s);
 }

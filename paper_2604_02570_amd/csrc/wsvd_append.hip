@@ -518,3 +518,53 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
   }
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------- store of latents computed elsewhere
+// The quantise-and-store half of the append for callers that produce the latents with another GEMM (the
+// int4-weight / int8-activation projection of the quantised setting, Section 4.2).  One workgroup per sequence:
+// it reads the sequence's length once, stores the 2*Hkv rows with R lanes per row and then advances the length,
+// so no cross-workgroup ordering is needed.
+template <int R>
+__global__ __launch_bounds__(1024) void k_latent_store(AppendParams p, const float* __restrict__ cK,
+                                                       const float* __restrict__ cV, long ld) {
+  __shared__ int n_sh;
+  const int b = blockIdx.x;
+  if (threadIdx.x == 0) n_sh = p.seq_lens[b];
+  __syncthreads();
+  const int n = n_sh;
+  if (n < 0 || n >= p.t_cap) {
+    if (threadIdx.x == 0) atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
+    return;
+  }
+  const int total = 2 * p.Hkv * R;     // a multiple of 64 whenever the latents are quantised (R >= 32)
+  for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
+    const int row = idx / R, j = idx % R;
+    const int pl = row / p.Hkv, kv = row % p.Hkv;
+    const float c = (pl ? cV : cK)[(size_t)b * ld + kv * R + j];
+    store_row_lanes<R>(p, pl, b, kv, n, j, c);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) p.seq_lens[b] = n + 1;
+}
+
+hipError_t wsvd_launch_latent_store(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const float* cK, const float* cV,
+                                    int64_t ld, const wsvd_cache& cache, hipStream_t s) {
+  AppendParams p = {};
+  p.codes[0] = (uint8_t*)cache.k_codes; p.codes[1] = (uint8_t*)cache.v_codes;
+  p.meta[0] = (uint16_t*)cache.k_meta; p.meta[1] = (uint16_t*)cache.v_meta;
+  p.seq_lens = cache.seq_lens;
+  p.err_word = ctx->err_word;
+  p.B = d.batch; p.E = d.d_model; p.Hkv = d.n_kv_heads; p.t_cap = d.t_cap;
+  p.latent_dtype = d.latent_dtype;
+  const int total = 2 * d.n_kv_heads * d.rank;
+  int threads = (total + 63) / 64 * 64;
+  if (threads > 1024) threads = 1024;
+  dim3 grid((unsigned)d.batch), block((unsigned)threads);
+  switch (d.rank) {
+    case 16: hipLaunchKernelGGL((k_latent_store<16>), grid, block, 0, s, p, cK, cV, (long)ld); break;
+    case 32: hipLaunchKernelGGL((k_latent_store<32>), grid, block, 0, s, p, cK, cV, (long)ld); break;
+    case 64: hipLaunchKernelGGL((k_latent_store<64>), grid, block, 0, s, p, cK, cV, (long)ld); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}

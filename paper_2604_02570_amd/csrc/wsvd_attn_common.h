@@ -78,16 +78,20 @@ WSVD_DEV void stage_commit(const StageRegs<MAXIT>& r, void* lds, int n16) {
 }
 
 // queries of the G heads of kv head `kv` of sequence `b` -> LDS floats [G][d].  Split into issue (global loads
-// into registers) and commit (LDS stores) so that other loads can be put in flight in between.  G*d <= 512.
+// into registers) and commit (LDS stores) so that other loads can be put in flight in between.  G*d <= 256*N
+// and the workgroup has at least 256 threads.
 // The issue phase only loads raw bits (no arithmetic on them), so it never waits.
-struct QRegs { uint32_t raw[2]; };
-WSVD_DEV void q_issue(const AttnParams& p, int b, int kv, QRegs& r) {
+template <int N>
+struct QRegsT { uint32_t raw[N]; };
+using QRegs = QRegsT<2>;
+template <int N>
+WSVD_DEV void q_issue(const AttnParams& p, int b, int kv, QRegsT<N>& r) {
   // one unconditional dword load per element: the aligned dword that contains it (4 int8, 2 bf16 or 1 fp32)
   const size_t base = ((size_t)b * p.Hq + (size_t)kv * p.G) * p.d;
   const int sh = p.q_dtype == WSVD_I8 ? 2 : p.q_dtype == WSVD_BF16 ? 1 : 0;
   const int n = p.G * p.d;
 #pragma unroll
-  for (int it = 0; it < 2; it++) {
+  for (int it = 0; it < N; it++) {
     const int i = min(it * 256 + (int)(threadIdx.x & 255), n - 1);
     r.raw[it] = ((const uint32_t*)p.q)[(base + i) >> sh];
   }
@@ -101,10 +105,11 @@ WSVD_DEV float q_scale_value(const AttnParams& p, int b, uint32_t wraw) {
   if (p.q_dtype != WSVD_I8) return 1.f;
   return f16_bits_to_f32((uint16_t)((b & 1) ? (wraw >> 16) : (wraw & 0xFFFFu)));
 }
-WSVD_DEV void q_commit(const AttnParams& p, const QRegs& r, float qs, float* q_lds) {
+template <int N>
+WSVD_DEV void q_commit(const AttnParams& p, const QRegsT<N>& r, float qs, float* q_lds) {
   const int n = p.G * p.d;
 #pragma unroll
-  for (int it = 0; it < 2; it++) {
+  for (int it = 0; it < N; it++) {
     const int i = it * 256 + (int)threadIdx.x;
     if (threadIdx.x < 256 && i < n) {
       // (b*Hq + kv*G)*d is a multiple of 64, so element i sits at position i % (4 >> ...) of its dword

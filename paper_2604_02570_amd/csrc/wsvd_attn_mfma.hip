@@ -381,6 +381,257 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, bv_lds);
 }
 
+// ---------------------------------------------------------------- 5 to 8 query heads per kv head (I8 latents)
+// One 32-token block per MFMA: all 32 rows of the A operand are in use (8 query slots x 3 limbs, slot = a + 4*h
+// for row 8a + 4h + limb), so D puts the scores of queries 0..3 of token L%32 in lanes 0..31 and those of queries
+// 4..7 of the same token in lanes 32..63.  Every per-query quantity (running max, weight unit, sums) is therefore a
+// per-half value and the reductions run over half a wave.  The value pass has the same shape: A rows are (slot, limb)
+// over the block's 32 tokens, D[slot, limb][dim] lands in the half that owns the slot.
+template <int R>
+struct GqaTile {
+  v4i k[R / 32][2];
+  v4i v[R / 32][2];
+  uint32_t kmeta[2], vmeta[2];   // fp16 scales of token L%32 of block 0 / block 1
+};
+
+template <int R>
+WSVD_DEV void load_gqa_tile(GqaTile<R>& t, const uint8_t* kplane, const uint8_t* vplane, const uint16_t* kmeta,
+                            const uint16_t* vmeta, int tile, int lane) {
+  const uint32_t off = (uint32_t)tile * (uint32_t)(64 * R) + (uint32_t)lane * 16u;
+#pragma unroll
+  for (int blk = 0; blk < 2; blk++)
+#pragma unroll
+    for (int kk = 0; kk < R / 32; kk++) {
+      t.k[kk][blk] = __builtin_nontemporal_load((const v4i*)(kplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
+      t.v[kk][blk] = __builtin_nontemporal_load((const v4i*)(vplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
+    }
+  const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)(lane & 31);
+#pragma unroll
+  for (int blk = 0; blk < 2; blk++) {
+    t.kmeta[blk] = __builtin_nontemporal_load(kmeta + moff + 32u * blk);
+    t.vmeta[blk] = __builtin_nontemporal_load(vmeta + moff + 32u * blk);
+  }
+}
+
+template <int R, int NT>
+__global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
+  constexpr int KK = R / 32;
+  constexpr int NWMAX = NT / 64;
+  constexpr int FIT = R / 16;
+  constexpr int GS = 8;                 // query slots
+
+  __shared__ v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
+  __shared__ __attribute__((aligned(16))) float q_lds[GS * 128];
+  __shared__ float qts[GS * R];
+  __shared__ __attribute__((aligned(16))) int8_t qlimb[GS][3][R];
+  __shared__ float qdelta[GS];
+  __shared__ __attribute__((aligned(16))) uint8_t wl[NWMAX][GS][3][32];
+  __shared__ float wm[NWMAX][GS], wls[NWMAX][GS];
+  __shared__ float wu[NWMAX][GS][R];
+  __shared__ float Msh[GS], Lsh[GS], Ush[GS * R];
+  __shared__ int flag_sh;
+
+  const int n_raw = p.seq_lens[blockIdx.z];
+  const uint32_t qs_raw = q_scale_raw(p, blockIdx.z);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+  const int G = p.G;
+  const size_t ph = (size_t)blockIdx.z * p.Hkv + blockIdx.x;
+  const size_t plane_bytes = (size_t)p.t_cap * R;
+  const uint8_t* kplane = p.k_codes + ph * plane_bytes;
+  const uint8_t* vplane = p.v_codes + ph * plane_bytes;
+  const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap;
+  const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap;
+
+  // loads in the order they should come back (factors, queries, then the first tiles, requested speculatively
+  // below t_cap before the sequence length is known)
+  const int fac16 = R * p.d * 2 / 16;
+  StageRegs<FIT> stk, stv;
+  QRegsT<4> qr;
+  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)blockIdx.x * R * p.d * 2, fac16);
+  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
+  q_issue<4>(p, blockIdx.z, blockIdx.x, qr);
+  constexpr int DEPTH = 2;
+  GqaTile<R> buf[DEPTH];
+  const int chunk_tiles = p.chunk_rows >> 6;
+  int T = (int)blockIdx.y * chunk_tiles + wave;
+  {
+    const int spec_last = min(((int)blockIdx.y + 1) * chunk_tiles, p.t_cap >> 6) - 1;
+#pragma unroll
+    for (int i = 0; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+  }
+
+  stage_commit<FIT>(stk, bk_lds, fac16);
+  stage_commit<FIT>(stv, bv_lds, fac16);
+  q_commit<4>(p, qr, 1.f, q_lds);
+  __syncthreads();
+  compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
+  // limbs of all 8 slots; slots past G are zero so they contribute nothing and cost nothing extra
+  for (int idx = tid; idx < GS * R; idx += blockDim.x) {
+    const int g = idx / R, j = idx % R;
+    const float v = g < G ? qts[idx] : 0.f;
+    const float amax = (R == 64) ? wave_max(fabsf(v)) : half_max(fabsf(v), lane);
+    const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
+    const int Q = (int)__builtin_rintf(v * inv);
+    const int l0 = ((Q + 64) & 127) - 64;
+    const int Q1 = (Q - l0) >> 7;
+    const int l1 = ((Q1 + 64) & 127) - 64;
+    const int l2 = (Q1 - l1) >> 7;
+    qlimb[g][0][j] = (int8_t)l2;
+    qlimb[g][1][j] = (int8_t)l1;
+    qlimb[g][2][j] = (int8_t)l0;
+    if (j == 0) qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f;
+  }
+  __syncthreads();
+
+  const int hf = lane >> 5, l32 = lane & 31;
+  v4i aop[KK];
+  {
+    const int a = l32 >> 3, hh = (l32 >> 2) & 1, limb = l32 & 3;
+#pragma unroll
+    for (int kk = 0; kk < KK; kk++) {
+      const v4i val = *(const v4i*)&qlimb[a + 4 * hh][limb < 3 ? limb : 0][kk * 32 + hf * 16];
+      const v4i zero = {0, 0, 0, 0};
+      aop[kk] = limb < 3 ? val : zero;
+    }
+  }
+  const float qs = q_scale_value(p, blockIdx.z, qs_raw);
+  const WorkItem w = decode_work(p, n_raw);
+  if (w.n == 0) { write_zero_outputs(p, w); return; }
+  if (!w.active) return;
+  const int tile_end = (w.row_end + 63) >> 6;
+
+  // slot a of this lane is query a + 4*hf
+  float delta[4], m[4], wref[4], omega[4], winv[4], lsum[4], u[4][KK];
+  v16i vacc[KK];
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    delta[a] = qdelta[a + 4 * hf] * qs;
+    m[a] = -INFINITY; wref[a] = 0.f; omega[a] = 0.f; winv[a] = 0.f; lsum[a] = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < KK; jj++) u[a][jj] = 0.f;
+  }
+#pragma unroll
+  for (int jj = 0; jj < KK; jj++)
+#pragma unroll
+    for (int x = 0; x < 16; x++) vacc[jj][x] = 0;
+  int since_flush = 0;
+
+  auto flush = [&](int a) {
+#pragma unroll
+    for (int jj = 0; jj < KK; jj++) {
+      u[a][jj] = fmaf(omega[a], limbs_to_f32(vacc[jj][4 * a], vacc[jj][4 * a + 1], vacc[jj][4 * a + 2]), u[a][jj]);
+      vacc[jj][4 * a] = 0; vacc[jj][4 * a + 1] = 0; vacc[jj][4 * a + 2] = 0;
+    }
+  };
+
+  // weights operand read position: row l32 -> slot (l32/8) + 4*((l32/4)%2), limb l32%4; k half = hf
+  const int wr_q = (l32 >> 3) + 4 * ((l32 >> 2) & 1), wr_limb = min(l32 & 3, 2);
+
+  auto compute = [&](GqaTile<R>& t, int tile) {
+    since_flush += 2;
+    if (since_flush >= 2 * kMaxTilesPerFlush) {
+      since_flush = 0;
+#pragma unroll
+      for (int a = 0; a < 4; a++) flush(a);
+    }
+#pragma unroll
+    for (int blk = 0; blk < 2; blk++) {
+      const bool valid = tile * 64 + blk * 32 + l32 < w.row_end;
+      v16i acc = {0};
+#pragma unroll
+      for (int kk = 0; kk < KK; kk++) acc = mfma_i8(aop[kk], t.k[kk][blk], acc);
+      const float ksc = f16_bits_to_f32((uint16_t)t.kmeta[blk]);
+      const float vsc = f16_bits_to_f32((uint16_t)t.vmeta[blk]);
+#pragma unroll
+      for (int a = 0; a < 4; a++) {
+        const float dot = limbs_to_f32(acc[4 * a], acc[4 * a + 1], acc[4 * a + 2]);
+        const float s = valid ? ksc * dot * delta[a] : -INFINITY;
+        if (__builtin_amdgcn_ballot_w64(s > m[a]) != 0) {          // a new running max for a query of either half
+          const float mn = fmaxf(m[a], half_max(s, lane));
+          const float alpha = __builtin_amdgcn_exp2f(m[a] - mn);     // 1 in the half whose max did not move
+          flush(a);
+#pragma unroll
+          for (int jj = 0; jj < KK; jj++) u[a][jj] *= alpha;
+          lsum[a] *= alpha;
+          m[a] = mn;
+        }
+        const float pw = __builtin_amdgcn_exp2f(s - m[a]);
+        lsum[a] += pw;
+        const float wt = valid ? pw * vsc : 0.f;
+        if (__builtin_amdgcn_ballot_w64(wt > wref[a]) != 0) {
+          flush(a);
+          const float wn = 2.f * half_max(wt, lane);
+          if (wn > wref[a]) {                                        // only the half that overflowed moves its unit
+            wref[a] = wn;
+            winv[a] = kLimbFull * __builtin_amdgcn_rcpf(wn);
+            omega[a] = wn * (1.f / kLimbFull);
+          }
+        }
+        const int Q = (int)__builtin_rintf(wt * winv[a]);
+        wl[wave][a + 4 * hf][0][l32] = (uint8_t)(Q >> 14);
+        wl[wave][a + 4 * hf][1][l32] = (uint8_t)((Q >> 7) & 127);
+        wl[wave][a + 4 * hf][2][l32] = (uint8_t)(Q & 127);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const v4i w0 = *(const v4i*)&wl[wave][wr_q][wr_limb][hf * 16];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int jj = 0; jj < KK; jj++) vacc[jj] = mfma_i8(w0, t.v[jj][blk], vacc[jj]);
+    }
+  };
+
+  const int n = T < tile_end ? (tile_end - T + NW - 1) / NW : 0;
+  int done = 0;
+  while (done + 2 * DEPTH <= n) {
+#pragma unroll
+    for (int i = 0; i < DEPTH; i++) {
+      compute(buf[i], T + (done + i) * NW);
+      load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
+    }
+    done += DEPTH;
+  }
+#pragma unroll
+  for (int i = 0; i < DEPTH; i++) {
+    if (done + i < n) {
+      compute(buf[i], T + (done + i) * NW);
+      if (done + i + DEPTH < n) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
+    }
+  }
+  done += DEPTH;
+#pragma unroll
+  for (int i = 0; i < DEPTH; i++)
+    if (done + i < n) compute(buf[i], T + (done + i) * NW);
+
+  // per-wave state -> LDS (a wave that had no tile contributes m = -inf, l = 0, u = 0)
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    flush(a);
+    const float lw = half_sum(lsum[a], lane);
+    if (l32 == 0) { wm[wave][a + 4 * hf] = m[a]; wls[wave][a + 4 * hf] = lw; }
+#pragma unroll
+    for (int jj = 0; jj < KK; jj++) wu[wave][a + 4 * hf][jj * 32 + l32] = u[a][jj];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * R; idx += blockDim.x) {
+    const int g = idx / R, j = idx % R;
+    float M = wm[0][g];
+    for (int k = 1; k < NW; k++) M = fmaxf(M, wm[k][g]);
+    float L = 0.f, U = 0.f;
+    for (int k = 0; k < NW; k++) {
+      const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
+      L = fmaf(wls[k][g], e, L);
+      U = fmaf(wu[k][g][j], e, U);
+    }
+    Ush[idx] = U;
+    if (j == 0) { Msh[g] = M; Lsh[g] = L; }
+  }
+  __syncthreads();
+  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, bv_lds);
+}
+
 template <int R, bool I4, int NT>
 static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
   if (threads > NT || threads % 64) return hipErrorInvalidValue;
@@ -395,9 +646,21 @@ static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStrea
 }
 
 // largest workgroup (threads) each instantiation may be launched with
-int wsvd_attn_mfma_max_threads(int latent_dtype, int rank) { return (latent_dtype == WSVD_I8 && rank == 64) ? 512 : 1024; }
+int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
+  if (G > 4) return 512;
+  return (latent_dtype == WSVD_I8 && rank == 64) ? 512 : 1024;
+}
 
 hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (p.G > 4) {
+    // 5..8 query heads per kv head: I8 latents only
+    if (latent_dtype != WSVD_I8 || p.G > 8) return hipErrorNotSupported;
+    if (threads > 512 || threads < 256 || threads % 64) return hipErrorInvalidValue;
+    if (rank == 32) hipLaunchKernelGGL((k_attn_gqa<32, 512>), grid, dim3(threads), 0, s, p);
+    else if (rank == 64) hipLaunchKernelGGL((k_attn_gqa<64, 512>), grid, dim3(threads), 0, s, p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
   if (latent_dtype == WSVD_I8 && rank == 32) return launch_m<32, false, 1024>(p, grid, threads, s);
   if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false, 512>(p, grid, threads, s);
   if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true, 1024>(p, grid, threads, s);

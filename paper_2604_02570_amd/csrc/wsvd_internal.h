@@ -21,6 +21,8 @@ hipError_t wsvd_launch_quantize_act_i8(const void* x, int x_dtype, int64_t rows,
                                        void* scale_f16, hipStream_t s);
 hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,
                               const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s);
+hipError_t wsvd_launch_latent_store(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const float* cK, const float* cV,
+                                    int64_t ld, const wsvd_cache& cache, hipStream_t s);
 hipError_t wsvd_launch_pack_factor_a(const wsvd_layer_desc& d, const void* src, void* dst, hipStream_t s);
 hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
                             const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,

@@ -50,3 +50,19 @@ def build_case(name, layer=0, extra_cap=64, **over) -> Case:
     WQ = WI.dense_wq(sp)
     c.q32 = (c.x_new.astype(np.float64) @ WQ.astype(np.float64)).astype(np.float32).reshape(sp.steps, sp.batch, sp.n_q_heads, sp.d_head)
     return c
+
+
+def build_block_case(name, layer=0, **over) -> Case:
+    """build_case plus the int4 weights of the quantised attention block: W_Q [Hq*d, E], A_K / A_V [Hkv*r, E]
+    (output channel kv*r + j) and W_O [E, Hq*d], each as (codes int8 in [-8,7], fp16 scale per output channel),
+    and the int8 activation of the next token as the oracle's quantiser leaves it."""
+    import dataclasses
+    c = build_case(name, layer=layer, **over)
+    sp = c.sp
+    c.wq = WI.int4_weight(sp, sp.n_q_heads * sp.d_head, 0, layer)
+    c.ak = WI.int4_weight(sp, sp.n_kv_heads * sp.rank, 1, layer)
+    c.av = WI.int4_weight(sp, sp.n_kv_heads * sp.rank, 2, layer)
+    c.wo = WI.int4_weight(dataclasses.replace(sp, d_model=sp.n_q_heads * sp.d_head), sp.d_model, 3, layer)
+    c.x32 = c.x_new[0].astype(np.float32)
+    c.x_codes, c.x_scale = O.quantize_act_i8(c.x32)
+    return c

@@ -158,6 +158,12 @@ SMALL = [
     ("c4_small", dict()),
     ("c4_small", dict(n_q_heads=8, n_kv_heads=4, q_dtype="bf16")),
     ("c5_small", dict(n_q_heads=8, n_kv_heads=2)),           # rank 64, G = 4 (paired-block kernel)
+    ("c5_small", dict()),                                    # rank 64, G = 7 (one-block-per-MFMA kernel)
+    ("c5_small", dict(n_q_heads=10)),                        # G = 5
+    ("c5_small", dict(n_q_heads=12)),                        # G = 6
+    ("c5_small", dict(n_q_heads=16, d_head=64)),             # G = 8, d_head 64
+    ("c5_small", dict(context=2000)),                        # G = 7 over several context chunks
+    ("c3_small", dict(n_q_heads=28, n_kv_heads=4)),          # G = 7, rank 32, int8 query
 ]
 
 
@@ -171,11 +177,13 @@ def test_attention_small(name, over):
     L.close()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16", "i8", "i4"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i8", "i4", "i8-gqa7"])
 def test_attention_edge_lengths(dtype):
-    """Empty sequences, a single row, lengths around the 64-row tile and the chunk boundary, one sequence at capacity."""
-    name = {"f32": "c1", "bf16": "c2_small", "i8": "c3_small", "i4": "c4_small"}[dtype]
-    lens = [0, 1, 2, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 640]
+    """Empty sequences, a single row, lengths around the 32-row block, the 64-row tile and the chunk boundary, one
+    sequence at capacity."""
+    name = {"f32": "c1", "bf16": "c2_small", "i8": "c3_small", "i4": "c4_small", "i8-gqa7": "c5_small"}[dtype]
+    dtype = dtype.split("-")[0]
+    lens = [0, 1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 255, 256, 257, 511, 512, 640]
     c = build_case(name, batch=len(lens), context=640, ragged=(), extra_cap=0, steps=1)
     for b, n in enumerate(lens):
         c.cache.seq_lens[b] = n
@@ -188,10 +196,11 @@ def test_attention_edge_lengths(dtype):
     L.close()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "i8", "i4"])
+@pytest.mark.parametrize("dtype", ["f32", "i8", "i4", "i8-gqa7"])
 def test_attention_independent_of_split_count(dtype):
     """The result may depend on the number of context splits only through fp32 rounding."""
-    name = {"f32": "c1", "i8": "c3_small", "i4": "c4_small"}[dtype]
+    name = {"f32": "c1", "i8": "c3_small", "i4": "c4_small", "i8-gqa7": "c5_small"}[dtype]
+    dtype = dtype.split("-")[0]
     c = build_case(name, batch=2, context=1500, ragged=())
     L = layer_for(c)
     L.upload(c.cache)
