@@ -113,16 +113,22 @@ def test_latent_store_matches_oracle(name, over):
     L.close()
 
 
-def _run_block(c, L, stagewise):
+def _oracle_block(c, heads=None):
+    sp = c.sp
+    return O.attention_block_w4a8(c.cache, c.x_codes, c.x_scale, O.pack_w4(c.wq[0]), c.wq[1], O.pack_w4(c.ak[0]), c.ak[1],
+                                  O.pack_w4(c.av[0]), c.av[1], c.BK.astype(np.float64), c.BV.astype(np.float64),
+                                  O.pack_w4(c.wo[0]), c.wo[1], sp.n_q_heads, sp.d_head, c.sm_scale, heads=heads)
+
+
+def _run_block(c, L, stagewise, ref=None, before=None):
     """The GPU chain.  stagewise=True re-seeds every stage with the oracle's output of the previous one, so each
     stage is compared on identical inputs; False lets the GPU's own intermediates flow through."""
     sp = c.sp
     B, E, Hq, Hkv, d, r = sp.batch, sp.d_model, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.rank
     u16 = lambda a: dev(np.asarray(a, np.float16).view(np.uint16))
-    BK64, BV64 = c.BK.astype(np.float64), c.BV.astype(np.float64)
-    before = c.cache.seq_lens.copy()
-    ref = O.attention_block_w4a8(c.cache, c.x_codes, c.x_scale, O.pack_w4(c.wq[0]), c.wq[1], O.pack_w4(c.ak[0]), c.ak[1],
-                                 O.pack_w4(c.av[0]), c.av[1], BK64, BV64, O.pack_w4(c.wo[0]), c.wo[1], Hq, d, c.sm_scale)
+    if ref is None:
+        before = c.cache.seq_lens.copy()
+        ref = _oracle_block(c)
     # 1. per-token int8 of the hidden state
     xq = torch.empty((B, E), dtype=torch.int8, device="cuda"); xs = torch.empty(B, dtype=torch.int16, device="cuda")
     W.wsvd_quantize_act_i8(L.ctx, dev(c.x32), W.F32, B, E, xq, xs)
@@ -144,7 +150,7 @@ def _run_block(c, L, stagewise):
     assert W.wsvd_check(L.ctx) == 0
     flips = _append_compare(L, c.cache, ref["cK"], ref["cV"], before, sp.latent_dtype)
     print(f"block store: boundary flips accepted = {flips}", flush=True)
-    assert flips <= 2
+    assert flips <= max(2, 2 * B * Hkv * r // 500)
     if stagewise:
         L.upload(c.cache)
     # 4. attention with the fp32 query as it left the projection
@@ -176,4 +182,31 @@ def test_block_c5_small(stagewise):
     c = build_block_case("c5_small")
     L = layer_for(c); L.upload(c.cache)
     _run_block(c, L, stagewise)
+    L.close()
+
+
+def test_config5_block_full_size():
+    """One layer of the 28-layer workload at its real shape (batch 32, 28 query / 4 kv heads, rank 64, 8192 rows of
+    context).  The reconstructing oracle runs on a sample of heads; the absorbed oracle, checked against it on that
+    sample, provides every head, from which the oracle's own quantiser and W_O give the reference block output."""
+    import time
+    t0 = time.time()
+    c = build_block_case("c5", layer=3)
+    sp = c.sp
+    print(f"c5 inputs built in {time.time() - t0:.1f}s", flush=True)
+    L = layer_for(c); L.upload(c.cache)
+    rng = np.random.default_rng(5)
+    heads = [(int(b), int(h)) for b, h in zip(rng.integers(0, sp.batch, 96), rng.integers(0, sp.n_q_heads, 96))]
+    before = c.cache.seq_lens.copy()
+    ref = _oracle_block(c, heads=heads)
+    q32 = ref["q"].astype(np.float32).astype(np.float64)
+    attn_all = O.decode_attn_absorbed(c.cache, q32, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    m = ~np.isnan(ref["attn"])
+    assert m.sum() >= 64 * sp.d_head          # the 96 draws contain a few repeats
+    assert np.abs(attn_all[m] - ref["attn"][m]).max() <= 1e-9 * np.abs(ref["attn"][m]).max()
+    ref["attn"] = attn_all
+    ref["o_codes"], ref["o_scale"] = O.quantize_act_i8(attn_all.reshape(sp.batch, -1).astype(np.float32))
+    ref["y"] = O.linear_w4a8(ref["o_codes"], ref["o_scale"], O.pack_w4(c.wo[0]), c.wo[1])
+    print(f"c5 oracle done at {time.time() - t0:.1f}s", flush=True)
+    _run_block(c, L, False, ref=ref, before=before)
     L.close()
