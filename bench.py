@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
+    ap.add_argument("--workload", choices=["c3", "c5"], default="c3",
+                    help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
+                         "c5: the 28-layer grouped-query W4A8 attention block (a secondary line, same JSON shape)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -56,6 +59,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     W.lib()   # fails loudly if the HIP library is missing
+    if args.workload == "c5":
+        return run_c5(args, np, torch, W, WI)
 
     sp = WI.spec("c3")
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
@@ -234,6 +239,143 @@ def main():
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(np, row_bytes)
+    print(json.dumps(res))
+    W.wsvd_destroy(ctx)
+
+
+def run_c5(args, np, torch, W, WI):
+    """28 grouped-query layers per decode step, each: int8 quantise of the hidden state, W4A8 W_Q and A_K|A_V
+    projections, latent store, decode attention (28 query / 4 kv heads, rank 64, int8 latents), int8 quantise of
+    the attention output, W4A8 W_O.  Layer l+1 takes layer l's output as its hidden state (a stand-in for the rest
+    of the network, so that the launches form one dependent chain as in a real decode step).  Every layer has its
+    own cache and weights in HBM (3.9 GB + 0.4 GB), so nothing is re-read from a cache between layers."""
+    sp = WI.spec("c5")
+    B, Hq, Hkv, d, E, r, T, NL = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context, sp.layers
+    steps = args.steps if args.steps != 320 else 20
+    warmup = args.warmup if args.warmup != 32 else 3
+    total = steps + warmup
+    T0 = T - 1
+    t_cap = (T0 + total + 63) // 64 * 64
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "f32", "f32", 0.0)
+    ctx = W.wsvd_create(0)
+    ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(ctx, ws)
+    cb, mb = W.wsvd_cache_bytes(desc)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    bf16_bits = lambda x32: dev((np.ascontiguousarray(x32, np.float32).view(np.uint32) >> 16).astype(np.uint16).view(np.int16))
+
+    def pack_w4(codes):     # [N,K] int8 in [-8,7] -> [N,K/2] bytes, element 2i in the low nibble (input formatting only)
+        u = (codes.astype(np.int16) & 0xF).astype(np.uint8)
+        return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+
+    AK, AV, BK, BV = WI.factors(sp)
+    BKd, BVd = bf16_bits(BK), bf16_bits(BV)
+    # layer 0's cache through the library's quantiser, cloned for the other layers (contents do not affect timing)
+    k0 = torch.zeros(cb, dtype=torch.uint8, device="cuda"); v0 = torch.zeros(cb, dtype=torch.uint8, device="cuda")
+    km0 = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm0 = torch.zeros(mb, dtype=torch.uint8, device="cuda")
+    sl0 = torch.full((B,), T0, dtype=torch.int32, device="cuda")
+    cache0 = W.make_cache(k0, v0, km0, vm0, sl0)
+    for which, A, plane in (("k", AK, 0), ("v", AV, 1)):
+        lat = np.stack([WI.latents_from_law(sp, A, which, b, T0) for b in range(B)])
+        latd = dev(lat)
+        codes = torch.empty((B * Hkv * T0, r), dtype=torch.int8, device="cuda")
+        meta = torch.empty(B * Hkv * T0, dtype=torch.int16, device="cuda")
+        W.wsvd_quantize_rows(ctx, desc, latd, B * Hkv * T0, codes, meta)
+        W.wsvd_cache_import(ctx, desc, plane, codes, meta, 0, T0, cache0)
+        del latd, codes, meta
+    assert W.wsvd_check(ctx) == 0
+    layers = []
+    sp_o = __import__("dataclasses").replace(sp, d_model=Hq * d)
+    for l in range(NL):
+        t = (k0, v0, km0, vm0, sl0) if l == 0 else tuple(x.clone() for x in (k0, v0, km0, vm0, sl0))
+        wq, wqs = WI.int4_weight(sp, Hq * d, 0, l)
+        ak, aks = WI.int4_weight(sp, Hkv * r, 1, l)
+        av, avs = WI.int4_weight(sp, Hkv * r, 2, l)
+        wo, wos = WI.int4_weight(sp_o, E, 3, l)
+        layers.append(dict(
+            t=t, cache=W.make_cache(*t),
+            wq=dev(pack_w4(wq)), wqs=dev(wqs.view(np.int16)),
+            akv=dev(pack_w4(np.concatenate([ak, av], 0))), akvs=dev(np.concatenate([aks, avs]).view(np.int16)),
+            wo=dev(pack_w4(wo)), wos=dev(wos.view(np.int16))))
+    x0 = dev(WI.hidden_states(sp, B, 1.0, which="new").astype(np.float32))
+    xs_buf = [torch.empty((B, E), dtype=torch.float32, device="cuda") for _ in range(2)]
+    xq = torch.empty((B, E), dtype=torch.int8, device="cuda"); xsc = torch.empty(B, dtype=torch.int16, device="cuda")
+    q = torch.empty((B, Hq * d), dtype=torch.float32, device="cuda")
+    lat = torch.empty((B, 2 * Hkv * r), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
+    oq = torch.empty((B, Hq * d), dtype=torch.int8, device="cuda"); osc = torch.empty(B, dtype=torch.int16, device="cuda")
+
+    def step(attn_only=False):
+        x = x0
+        for l, Ly in enumerate(layers):
+            if not attn_only:
+                y = xs_buf[l & 1]
+                W.wsvd_quantize_act_i8(ctx, x, W.F32, B, E, xq, xsc)
+                W.wsvd_linear_w4a8(ctx, xq, xsc, Ly["wq"], Ly["wqs"], B, E, Hq * d, q)
+                W.wsvd_linear_w4a8(ctx, xq, xsc, Ly["akv"], Ly["akvs"], B, E, 2 * Hkv * r, lat)
+                W.wsvd_latent_store(ctx, desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, Ly["cache"])
+            W.wsvd_decode_attn(ctx, desc, q, None, BKd, BVd, Ly["cache"], t_cap, o)
+            if not attn_only:
+                W.wsvd_quantize_act_i8(ctx, o, W.F32, B, Hq * d, oq, osc)
+                W.wsvd_linear_w4a8(ctx, oq, osc, Ly["wo"], Ly["wos"], B, Hq * d, E, y)
+                x = y
+
+    stream = torch.cuda.Stream()
+    use_graph = not args.no_graph
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            step()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for _ in range(steps):
+                    step()
+            stream.synchronize()
+            e0.record(stream); g.replay(); e1.record(stream)
+        else:
+            e0.record(stream)
+            for _ in range(steps):
+                step()
+            e1.record(stream)
+        stream.synchronize()
+        ms_total = e0.elapsed_time(e1)
+        assert W.wsvd_check(ctx, stream) == 0
+        rows_end = int(layers[0]["t"][4][0])
+        assert rows_end == T0 + total, (rows_end, T0, total)
+        # attention alone over the 28 caches
+        n_rep = 3
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        step(True); stream.synchronize()
+        a0.record(stream)
+        for _ in range(n_rep):
+            step(True)
+        a1.record(stream); stream.synchronize()
+        attn_us = a0.elapsed_time(a1) * 1e3 / (n_rep * NL)
+        assert torch.isfinite(o).all()
+    row_bytes = Hkv * 2 * (r + 2)
+    rows_mean = T0 + warmup + (steps + 1) / 2
+    bytes_per_step = NL * B * rows_mean * row_bytes
+    ms_per_step = ms_total / steps
+    value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    attn_bytes = B * rows_end * row_bytes
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    res = {
+        "metric": "latent_kv_hbm_GBps_per_decode_step", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
+        "us_per_decode_step": round(ms_per_step * 1e3, 3), "us_per_layer": round(ms_per_step * 1e3 / NL, 3),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": "c5: 28-layer grouped-query W4A8 attention block, B=32 Hq=28 Hkv=4 d_head=128 d_model=3584 r=64 T=8192",
+                   "batch": B, "q_heads": Hq, "kv_heads": Hkv, "d_head": d, "d_model": E, "rank": r, "context": T, "layers": NL,
+                   "launch": "hip_graph_replay" if use_graph else "eager",
+                   "step": "per layer: quantize_act_i8, linear_w4a8 (W_Q), linear_w4a8 (A_K|A_V), latent_store, decode_attn, quantize_act_i8, linear_w4a8 (W_O)"},
+        "roofline": {"kernel": "k_attn_gqa<64> (decode attention, 7 query heads per kv head, int8 latents)", "bound": "hbm",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 3)},
+    }
     print(json.dumps(res))
     W.wsvd_destroy(ctx)
 

@@ -527,23 +527,23 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
 template <int R>
 __global__ __launch_bounds__(1024) void k_latent_store(AppendParams p, const float* __restrict__ cK,
                                                        const float* __restrict__ cV, long ld) {
-  __shared__ int n_sh;
   const int b = blockIdx.x;
-  if (threadIdx.x == 0) n_sh = p.seq_lens[b];
-  __syncthreads();
-  const int n = n_sh;
+  const int total = 2 * p.Hkv * R;     // a multiple of 64 whenever the latents are quantised (R >= 32)
+  // every thread reads the length itself (one broadcast load) together with its first latent: one round trip
+  const int n = __hip_atomic_load(p.seq_lens + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int i0 = min((int)threadIdx.x, total - 1);
+  float c = ((i0 / R) / p.Hkv ? cV : cK)[(size_t)b * ld + ((i0 / R) % p.Hkv) * R + i0 % R];
   if (n < 0 || n >= p.t_cap) {
     if (threadIdx.x == 0) atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
     return;
   }
-  const int total = 2 * p.Hkv * R;     // a multiple of 64 whenever the latents are quantised (R >= 32)
   for (int idx = threadIdx.x; idx < total; idx += blockDim.x) {
     const int row = idx / R, j = idx % R;
     const int pl = row / p.Hkv, kv = row % p.Hkv;
-    const float c = (pl ? cV : cK)[(size_t)b * ld + kv * R + j];
+    if (idx != (int)threadIdx.x) c = (pl ? cV : cK)[(size_t)b * ld + kv * R + j];
     store_row_lanes<R>(p, pl, b, kv, n, j, c);
   }
-  __syncthreads();
+  __syncthreads();     // every thread has consumed the old length
   if (threadIdx.x == 0) p.seq_lens[b] = n + 1;
 }
 

@@ -45,6 +45,17 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) xrow[mb] = x + (size_t)min(mb * 16 + col, M - 1) * (size_t)K;
 
+  // output coordinates of this thread in the final pass, and their scales (requested now, used at the very end)
+  constexpr int OPT = (MB * 256 + kLinWaves * 64 - 1) / (kLinWaves * 64);
+  float sx[OPT], sw[OPT];
+#pragma unroll
+  for (int it = 0; it < OPT; it++) {
+    const int o = min(it * kLinWaves * 64 + tid, MB * 256 - 1);
+    const int m = min((o >> 8) * 16 + ((o & 255) >> 4), M - 1);
+    sx[it] = f16_bits_to_f32(xs[m]);
+    sw[it] = f16_bits_to_f32(wsc[n0 + (o & 15)]);
+  }
+
   v4i acc[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) acc[mb] = v4i{0, 0, 0, 0};
@@ -63,6 +74,9 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
 #pragma unroll
         for (int i = 0; i < 4; i++) xr[u][mb][i] = *(const v4i*)(xrow[mb] + kc + 16 * i);
     }
+    // keep the whole batch in flight: without this the scheduler sinks most loads below the first products to save
+    // registers, which turns one memory round trip into four
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < kLinU; u++) {
       const int k = (s0 + u * kLinWaves) * kLinStepK + 64 * grp;
@@ -95,7 +109,10 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
     for (int v = 0; v < 4; v++) red[wave][mb][lane][v] = acc[mb][v];
   __syncthreads();
   // thread -> (token, channel), channel fastest so a 16-lane group writes 64 contiguous bytes
-  for (int o = tid; o < MB * 256; o += kLinWaves * 64) {
+#pragma unroll
+  for (int it = 0; it < OPT; it++) {
+    const int o = it * kLinWaves * 64 + tid;
+    if (o >= MB * 256) break;
     const int mb = o >> 8, rem = o & 255;
     const int c = rem & 15, rr = rem >> 4;
     const int src_lane = (rr >> 2) * 16 + c, v = rr & 3;
@@ -103,7 +120,7 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
 #pragma unroll
     for (int k = 0; k < kLinWaves; k++) sum += red[k][mb][src_lane][v];
     const int m = mb * 16 + rr;
-    if (m < M) out[(size_t)m * N + n0 + c] = (float)(sum >> 4) * f16_bits_to_f32(xs[m]) * f16_bits_to_f32(wsc[n0 + c]);
+    if (m < M) out[(size_t)m * N + n0 + c] = (float)(sum >> 4) * sx[it] * sw[it];
   }
 }
 

@@ -88,10 +88,75 @@ __global__ __launch_bounds__(256) void k_quantize_act_i8(const void* __restrict_
   if (tid == 0) scale[row] = sh;
 }
 
+// Rows of up to 16384 elements: the row is read ONCE, 16 bytes per thread and pass with every pass in flight
+// together, kept in registers across the abs-max reduction, and the codes leave as packed dwords.  Same arithmetic
+// per element as the kernel above (max is exact in any order), so the stored bits are identical.
+constexpr int kActThreads = 1024;
+constexpr int kActPasses = 4;
+template <int ESZ>   // 4: fp32, 2: bf16
+__global__ __launch_bounds__(kActThreads) void k_quantize_act_i8_row(const void* __restrict__ x, int n16 /* 16-byte units per row */,
+                                                                      int8_t* __restrict__ codes, uint16_t* __restrict__ scale) {
+  constexpr int EPU = 16 / ESZ;      // elements per 16-byte unit
+  __shared__ float red[kActThreads / 64];
+  const int tid = threadIdx.x;
+  const v4i* src = (const v4i*)x + (size_t)blockIdx.x * n16;
+  v4i raw[kActPasses];
+#pragma unroll
+  for (int it = 0; it < kActPasses; it++) raw[it] = src[min(it * kActThreads + tid, n16 - 1)];   // unconditional, clamped
+  float f[kActPasses][EPU];
+  float a = 0.f;
+#pragma unroll
+  for (int it = 0; it < kActPasses; it++)
+#pragma unroll
+    for (int e = 0; e < EPU; e++) {
+      if (ESZ == 4) f[it][e] = __int_as_float(raw[it][e]);
+      else f[it][e] = __uint_as_float((e & 1) ? ((uint32_t)raw[it][e >> 1] & 0xFFFF0000u) : ((uint32_t)raw[it][e >> 1] << 16));
+      a = fmaxf(a, fabsf(f[it][e]));     // clamped duplicates repeat an element of the row: harmless for a max
+    }
+  a = wave_max(a);
+  if ((tid & 63) == 0) red[tid >> 6] = a;
+  __syncthreads();
+  a = red[0];
+#pragma unroll
+  for (int k = 1; k < kActThreads / 64; k++) a = fmaxf(a, red[k]);
+  uint16_t sh = 0x3C00u;
+  if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
+  const float sc = f16_bits_to_f32(sh);
+  uint32_t* dst = (uint32_t*)(codes + (size_t)blockIdx.x * n16 * EPU);
+#pragma unroll
+  for (int it = 0; it < kActPasses; it++) {
+    const int u = it * kActThreads + tid;
+    if (u < n16) {
+#pragma unroll
+      for (int w4 = 0; w4 < EPU / 4; w4++) {
+        uint32_t pk = 0;
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          float v = __builtin_rintf(f[it][w4 * 4 + e] / sc);
+          v = fminf(fmaxf(v, -127.f), 127.f);
+          pk |= ((uint32_t)(int)v & 0xFFu) << (8 * e);
+        }
+        dst[(size_t)u * (EPU / 4) + w4] = pk;
+      }
+    }
+  }
+  if (tid == 0) scale[blockIdx.x] = sh;
+}
+
 hipError_t wsvd_launch_quantize_act_i8(const void* x, int x_dtype, int64_t rows, int64_t cols, int8_t* codes,
                                        void* scale_f16, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_quantize_act_i8, dim3((unsigned)rows), dim3(256), 0, s, x, x_dtype, cols, codes, (uint16_t*)scale_f16);
+  const int esz = x_dtype == WSVD_F32 ? 4 : 2;
+  const int epu = 16 / esz;
+  const bool fast = (x_dtype == WSVD_F32 || x_dtype == WSVD_BF16) && cols % epu == 0 &&
+                    cols / epu <= (int64_t)kActThreads * kActPasses && ((uintptr_t)x & 15u) == 0 && ((uintptr_t)codes & 3u) == 0;
+  if (fast) {
+    const int n16 = (int)(cols / epu);
+    if (esz == 4) hipLaunchKernelGGL((k_quantize_act_i8_row<4>), dim3((unsigned)rows), dim3(kActThreads), 0, s, x, n16, codes, (uint16_t*)scale_f16);
+    else hipLaunchKernelGGL((k_quantize_act_i8_row<2>), dim3((unsigned)rows), dim3(kActThreads), 0, s, x, n16, codes, (uint16_t*)scale_f16);
+  } else {
+    hipLaunchKernelGGL(k_quantize_act_i8, dim3((unsigned)rows), dim3(256), 0, s, x, x_dtype, cols, codes, (uint16_t*)scale_f16);
+  }
   return hipGetLastError();
 }
 

@@ -88,14 +88,18 @@ def test_quantize_rows_bit_exact(dtype, r):
     L.close()
 
 
-def test_quantize_act_i8_bit_exact():
+@pytest.mark.parametrize("rows,cols,dt", [(37, 3584, "f32"), (5, 16384, "f32"), (3, 16388, "f32"), (4, 4098, "f32"),
+                                          (2, 40, "f32"), (6, 1792, "bf16"), (3, 32768, "bf16"), (2, 36, "bf16")])
+def test_quantize_act_i8_bit_exact(rows, cols, dt):
+    """Both activation-quantiser kernels (rows kept in registers; the strided fallback for long or odd rows)."""
     rng = np.random.default_rng(7)
-    rows, cols = 37, 3584
     x = (rng.standard_normal((rows, cols)) * np.exp(rng.standard_normal((rows, 1)))).astype(np.float32)
     x[0] = 0
+    if dt == "bf16":
+        x = WI.bf16_exact(x)
     L = DeviceLayer(1, 1, 1, 128, 512, 32, 64, "i8", "bf16", "bf16", "i8")
     codes = torch.zeros((rows, cols), dtype=torch.int8, device="cuda"); sc = torch.zeros(rows, dtype=torch.int16, device="cuda")
-    W.wsvd_quantize_act_i8(L.ctx, dev(x), "f32", rows, cols, codes, sc)
+    W.wsvd_quantize_act_i8(L.ctx, as_dtype_dev(x, dt), dt, rows, cols, codes, sc)
     assert W.wsvd_check(L.ctx) == 0
     oc, os_ = O.quantize_act_i8(x)
     assert (sc.cpu().numpy().view(np.uint16) == os_.view(np.uint16)).all()
