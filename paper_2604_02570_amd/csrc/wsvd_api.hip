@@ -8,6 +8,7 @@
 hipError_t wsvd_launch_attn_generic(const AttnParams& p, int latent_dtype, int rank, dim3 grid, hipStream_t s);
 hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s);
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G);
+int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G);
 
 extern int g_append_mode;
 
@@ -326,7 +327,11 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   const int n_units = d.batch * d.n_kv_heads;
   const int max_rows = ((max_seq_len > 0 ? max_seq_len : 1) + 63) / 64 * 64;
   const bool mfma = !(d.latent_dtype == WSVD_F32 || d.latent_dtype == WSVD_BF16);
-  const int waves_target = ctx->n_cu * 4 * g_opt_wg_per_cu;
+  // "wg_per_cu" scales the target: 4 (default) = as many wavefronts as fit on the chip at once (the generic kernels
+  // and the rank-32 matrix-core kernels hold 16 per CU, the rank-64 ones 8), so that the grid runs in a single round:
+  // a second round pays the prologue, the split merge and the B_V epilogue again with the memory system idle
+  const int resident = mfma ? wsvd_attn_mfma_waves_per_cu(d.latent_dtype, d.rank, p.G) : 16;
+  const int waves_target = ctx->n_cu * resident * g_opt_wg_per_cu / 4;
   int waves_per_unit = (waves_target + n_units - 1) / n_units;
   const int max_tiles = max_rows / 64;
   if (waves_per_unit > max_tiles) waves_per_unit = max_tiles;

@@ -192,17 +192,33 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
     }
     __syncthreads();
     if (!*flag_sh) return;
+    // The partials are read with cache-bypassing loads that cost a full memory round trip each, so they are
+    // requested a batch of 8 splits at a time (24 independent loads in flight) and folded in split order.
     for (int i = tid; i < G * R; i += blockDim.x) {
       const int g = i / R, j = i % R;
       const float* base = p.partials + (((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks) * (R + 2);
-      float M = -INFINITY;
-      for (int c = 0; c < w.n_splits; c++) M = fmaxf(M, agent_load(base + (size_t)c * (R + 2)));
-      float L = 0.f, U = 0.f;
-      for (int c = 0; c < w.n_splits; c++) {
-        const float* pc = base + (size_t)c * (R + 2);
-        const float e = __builtin_amdgcn_exp2f(agent_load(pc) - M);
-        L = fmaf(agent_load(pc + 1), e, L);
-        U = fmaf(agent_load(pc + 2 + j), e, U);
+      float M = -INFINITY, L = 0.f, U = 0.f;
+      for (int c0 = 0; c0 < w.n_splits; c0 += 8) {
+        float mv[8], lv[8], uv[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+          const float* pc = base + (size_t)min(c0 + k, w.n_splits - 1) * (R + 2);   // clamped: surplus slots are masked below
+          mv[k] = agent_load(pc);
+          lv[k] = agent_load(pc + 1);
+          uv[k] = agent_load(pc + 2 + j);
+        }
+        float Mn = M;
+#pragma unroll
+        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, mv[k]);                          // a clamped duplicate cannot change a max
+        const float keep = __builtin_amdgcn_exp2f(M - Mn);                           // 0 on the first batch (M = -inf, Mn finite)
+        L *= keep; U *= keep;
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+          const float e = (c0 + k < w.n_splits) ? __builtin_amdgcn_exp2f(mv[k] - Mn) : 0.f;
+          L = fmaf(lv[k], e, L);
+          U = fmaf(uv[k], e, U);
+        }
+        M = Mn;
       }
       Ush[i] = U;
       if (j == 0) { Lsh[g] = L; Msh[g] = M; }
@@ -212,6 +228,33 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
   // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c], B_V[kv] staged in LDS.
   // Four adjacent lanes share an output (a quarter of the latent dims each) and add up through DPP, which keeps
   // the dependent LDS-read chain short at the very end of the kernel.
+  if (ESZ == 2) {
+    // bf16 factors: two adjacent columns per lane (one LDS dword carries both), so half as many passes
+    const int half_d = p.d >> 1, n_pair = G * half_d;
+    const uint32_t* bv32 = (const uint32_t*)bv_lds;
+    for (int i0 = 0; i0 < n_pair * 4; i0 += blockDim.x) {   // uniform trip count: whole quads stay active
+      const int i = i0 + tid;
+      const int o = min(i >> 2, n_pair - 1), part = i & 3;
+      const int g = o / half_d, c2 = o % half_d;
+      float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < R / 4; jj++) {
+        const int j = part * (R / 4) + jj;
+        const uint32_t bb = bv32[j * half_d + c2];
+        const float u = Ush[g * R + j];
+        a0 = fmaf(u, __uint_as_float(bb << 16), a0);
+        a1 = fmaf(u, __uint_as_float(bb & 0xFFFF0000u), a1);
+      }
+      a0 = group_sum<4>(a0);
+      a1 = group_sum<4>(a1);
+      if (part == 0 && (i >> 2) < n_pair) {
+        const float L = Lsh[g];
+        float2 r; r.x = a0 / L; r.y = a1 / L;
+        *(float2*)&p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + 2 * c2] = r;
+      }
+    }
+    return;
+  }
   const int n_out = G * p.d;
   for (int i0 = 0; i0 < n_out * 4; i0 += blockDim.x) {     // uniform trip count: whole quads stay active
     const int i = i0 + tid;
@@ -221,8 +264,7 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
 #pragma unroll
     for (int jj = 0; jj < R / 4; jj++) {
       const int j = part * (R / 4) + jj;
-      const float b = ESZ == 4 ? ((const float*)bv_lds)[j * p.d + c] : bf16_to_f32(((const uint16_t*)bv_lds)[j * p.d + c]);
-      acc = fmaf(Ush[g * R + j], b, acc);
+      acc = fmaf(Ush[g * R + j], ((const float*)bv_lds)[j * p.d + c], acc);
     }
     acc = group_sum<4>(acc);
     if (part == 0 && (i >> 2) < n_out) p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = acc / Lsh[g];

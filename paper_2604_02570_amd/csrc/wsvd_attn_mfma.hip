@@ -19,6 +19,8 @@
 #include "wsvd_attn_common.h"
 #include "wsvd_internal.h"
 
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
 template <int R, bool I4>
 struct TileRegs {
   // I8: k[kk][blk], v[jj][blk] with kk, jj < R/32 and blk < 2.  I4 (R == 32): k[0][0], v[0][0] hold 64 tokens.
@@ -420,9 +422,8 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   constexpr int FIT = R / 16;
   constexpr int GS = 8;                 // query slots
 
-  __shared__ v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
-  __shared__ __attribute__((aligned(16))) float q_lds[GS * 128];
-  __shared__ float qts[GS * R];
+  __shared__ v4i bv_lds[R * 128 * 2 / 16];
+  __shared__ float qpart[NWMAX][32][GS];                                // per wave: partial q~ of its 32 latent dims
   __shared__ __attribute__((aligned(16))) int8_t qlimb[GS][3][R];
   __shared__ float qdelta[GS];
   __shared__ __attribute__((aligned(16))) uint8_t wl[NWMAX][GS][3][32];
@@ -434,6 +435,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   const int n_raw = p.seq_lens[blockIdx.z];
   const uint32_t qs_raw = q_scale_raw(p, blockIdx.z);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+  const int hf = lane >> 5, l32 = lane & 31;
   const int G = p.G;
   const size_t ph = (size_t)blockIdx.z * p.Hkv + blockIdx.x;
   const size_t plane_bytes = (size_t)p.t_cap * R;
@@ -442,14 +444,32 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap;
   const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap;
 
-  // loads in the order they should come back (factors, queries, then the first tiles, requested speculatively
-  // below t_cap before the sequence length is known)
-  const int fac16 = R * p.d * 2 / 16;
-  StageRegs<FIT> stk, stv;
-  QRegsT<4> qr;
-  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)blockIdx.x * R * p.d * 2, fac16);
-  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
-  q_issue<4>(p, blockIdx.z, blockIdx.x, qr);
+  // ---- query absorption q~ = B_K q on the matrix cores, operands straight from global memory (no staging):
+  // D[j][g] = sum_c B_K[j][c] q[g][c] as V_MFMA_F32_32X32X16_BF16 with A = a 32 x 16 block of B_K (row-major, so a
+  // lane's 8 operand elements are 16 contiguous bytes) and B = the queries.  An fp32 query is split into three bf16
+  // terms (hi + mid + lo reproduces it to 2^-24), so the result keeps fp32 accuracy.  The (row block, 16-column step)
+  // items are dealt round-robin to the waves; wave partials meet in LDS.
+  constexpr int RB = R / 32;
+  constexpr int MAXI = 4;                               // items per wave: RB * d/16 <= 16 items over >= 4 waves
+  const int n_items = RB * (p.d >> 4);
+  const int q_esz = p.q_dtype == WSVD_F32 ? 4 : p.q_dtype == WSVD_BF16 ? 2 : 1;
+  const size_t q_bytes = (size_t)p.B * p.Hq * p.d * q_esz;
+  const int gq = l32 < G ? l32 : 0;                     // query column of this lane (columns past G are zeroed below)
+  v4i bk_raw[MAXI], q_raw[MAXI][2];
+#pragma unroll
+  for (int i = 0; i < MAXI; i++) {
+    const int item = min(wave + i * NW, n_items - 1);   // unconditional, clamped
+    const int rb = item % RB, ks = item / RB;
+    bk_raw[i] = *(const v4i*)((const char*)p.BK + (((size_t)blockIdx.x * R + 32 * rb + l32) * p.d + 16 * ks + 8 * hf) * 2);
+    const size_t off = (((size_t)blockIdx.z * p.Hq + (size_t)blockIdx.x * G + gq) * p.d + 16 * ks + 8 * hf) * q_esz;
+    const size_t o0 = off & ~(size_t)15;
+    q_raw[i][0] = *(const v4i*)((const char*)p.q + o0);
+    q_raw[i][1] = *(const v4i*)((const char*)p.q + min(o0 + 16, q_bytes - 16));
+  }
+  // ---- then the first tiles, requested speculatively below t_cap before the sequence length is known.  The barrier
+  // (no memory wait) keeps every wave's small loads ahead of every wave's tile loads in the CU's memory pipeline, so
+  // the absorption does not queue behind a quarter of a megabyte of tile data.
+  __builtin_amdgcn_s_barrier();
   constexpr int DEPTH = 2;
   GqaTile<R> buf[DEPTH];
   const int chunk_tiles = p.chunk_rows >> 6;
@@ -460,15 +480,57 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     for (int i = 0; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
   }
 
-  stage_commit<FIT>(stk, bk_lds, fac16);
-  stage_commit<FIT>(stv, bv_lds, fac16);
-  q_commit<4>(p, qr, 1.f, q_lds);
+  {
+    v16f qacc = {0};
+#pragma unroll
+    for (int i = 0; i < MAXI; i++) {
+      if (wave + i * NW < n_items) {                    // wave-uniform
+        float f[8];
+        if (p.q_dtype == WSVD_F32) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) { f[e] = __int_as_float(q_raw[i][0][e]); f[4 + e] = __int_as_float(q_raw[i][1][e]); }
+        } else if (p.q_dtype == WSVD_BF16) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            f[2 * e] = __uint_as_float((uint32_t)q_raw[i][0][e] << 16);
+            f[2 * e + 1] = __uint_as_float((uint32_t)q_raw[i][0][e] & 0xFFFF0000u);
+          }
+        } else {                                        // int8: 8 bytes, in the low or the high half of the 16 loaded
+          const uint32_t d0 = (uint32_t)(hf ? q_raw[i][0][2] : q_raw[i][0][0]), d1 = (uint32_t)(hf ? q_raw[i][0][3] : q_raw[i][0][1]);
+#pragma unroll
+          for (int e = 0; e < 4; e++) { f[e] = (float)(int8_t)(d0 >> (8 * e)); f[4 + e] = (float)(int8_t)(d1 >> (8 * e)); }
+        }
+        if (l32 >= G) {
+#pragma unroll
+          for (int e = 0; e < 8; e++) f[e] = 0.f;
+        }
+        const v8bf a_op = __builtin_bit_cast(v8bf, bk_raw[i]);
+        const int n_terms = p.q_dtype == WSVD_F32 ? 3 : 1;   // bf16 and int8 values are exact in one bf16 term
+        for (int t3 = 0; t3 < n_terms; t3++) {
+          v4i packed;
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const uint32_t h0 = __float_as_uint(f[2 * e]) & 0xFFFF0000u, h1 = __float_as_uint(f[2 * e + 1]) & 0xFFFF0000u;
+            packed[e] = (int)((h0 >> 16) | h1);
+            f[2 * e] -= __uint_as_float(h0);            // exact: the remainder has at most 16 significant bits
+            f[2 * e + 1] -= __uint_as_float(h1);
+          }
+          qacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_op, __builtin_bit_cast(v8bf, packed), qacc, 0, 0, 0);
+        }
+      }
+    }
+    if (l32 < GS) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) qpart[wave][8 * (v >> 2) + 4 * hf + (v & 3)][l32] = qacc[v];
+    }
+  }
   __syncthreads();
-  compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   // limbs of all 8 slots; slots past G are zero so they contribute nothing and cost nothing extra
   for (int idx = tid; idx < GS * R; idx += blockDim.x) {
     const int g = idx / R, j = idx % R;
-    const float v = g < G ? qts[idx] : 0.f;
+    float v = 0.f;
+    for (int k = (j >> 5) % RB; k < NW; k += RB) v += qpart[k][j & 31][g];   // the waves that worked on this row block
+    v *= p.c_scale;
     const float amax = (R == 64) ? wave_max(fabsf(v)) : half_max(fabsf(v), lane);
     const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
     const int Q = (int)__builtin_rintf(v * inv);
@@ -483,7 +545,6 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   }
   __syncthreads();
 
-  const int hf = lane >> 5, l32 = lane & 31;
   v4i aop[KK];
   {
     const int a = l32 >> 3, hh = (l32 >> 2) & 1, limb = l32 & 3;
@@ -605,6 +666,11 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   for (int i = 0; i < DEPTH; i++)
     if (done + i < n) compute(buf[i], T + (done + i) * NW);
 
+  // B_V is only needed by the epilogue: requested now (it is shared by many workgroups and sits in L2), it arrives
+  // while the slower waves finish
+  const int fac16 = R * p.d * 2 / 16;
+  StageRegs<FIT> stv;
+  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
   // per-wave state -> LDS (a wave that had no tile contributes m = -inf, l = 0, u = 0)
 #pragma unroll
   for (int a = 0; a < 4; a++) {
@@ -614,6 +680,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
 #pragma unroll
     for (int jj = 0; jj < KK; jj++) wu[wave][a + 4 * hf][jj * 32 + l32] = u[a][jj];
   }
+  stage_commit<FIT>(stv, bv_lds, fac16);
   __syncthreads();
   for (int idx = tid; idx < G * R; idx += blockDim.x) {
     const int g = idx / R, j = idx % R;
@@ -646,6 +713,12 @@ static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStrea
 }
 
 // largest workgroup (threads) each instantiation may be launched with
+// wavefronts of these kernels one CU holds at a time (register-limited): the launch policy aims at one round
+int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G) {
+  (void)latent_dtype; (void)G;
+  return rank == 64 ? 8 : 16;
+}
+
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
   if (G > 4) return 512;
   return (latent_dtype == WSVD_I8 && rank == 64) ? 512 : 1024;
