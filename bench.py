@@ -244,8 +244,8 @@ def main():
 
 
 def run_c5(args, np, torch, W, WI):
-    """28 grouped-query layers per decode step, each: int8 quantise of the hidden state, W4A8 W_Q and A_K|A_V
-    projections, latent store, decode attention (28 query / 4 kv heads, rank 64, int8 latents), int8 quantise of
+    """28 grouped-query layers per decode step, each: int8 quantise of the hidden state, one W4A8 projection over
+    the stacked weight [W_Q; A_K; A_V], latent store, decode attention (28 query / 4 kv heads, rank 64, int8 latents), int8 quantise of
     the attention output, W4A8 W_O.  Layer l+1 takes layer l's output as its hidden state (a stand-in for the rest
     of the network, so that the launches form one dependent chain as in a real decode step).  Every layer has its
     own cache and weights in HBM (3.9 GB + 0.4 GB), so nothing is re-read from a cache between layers."""
@@ -294,8 +294,7 @@ def run_c5(args, np, torch, W, WI):
         wo, wos = WI.int4_weight(sp_o, E, 3, l)
         layers.append(dict(
             t=t, cache=W.make_cache(*t),
-            wq=dev(pack_w4(wq)), wqs=dev(wqs.view(np.int16)),
-            akv=dev(pack_w4(np.concatenate([ak, av], 0))), akvs=dev(np.concatenate([aks, avs]).view(np.int16)),
+            wqkv=dev(pack_w4(np.concatenate([wq, ak, av], 0))), wqkvs=dev(np.concatenate([wqs, aks, avs]).view(np.int16)),
             wo=dev(pack_w4(wo)), wos=dev(wos.view(np.int16))))
     x0 = dev(WI.hidden_states(sp, B, 1.0, which="new").astype(np.float32))
     xs_buf = [torch.empty((B, E), dtype=torch.float32, device="cuda") for _ in range(2)]
@@ -311,8 +310,7 @@ def run_c5(args, np, torch, W, WI):
             if not attn_only:
                 y = xs_buf[l & 1]
                 W.wsvd_quantize_act_i8(ctx, x, W.F32, B, E, xq, xsc)
-                W.wsvd_linear_w4a8(ctx, xq, xsc, Ly["wq"], Ly["wqs"], B, E, Hq * d, q)
-                W.wsvd_linear_w4a8(ctx, xq, xsc, Ly["akv"], Ly["akvs"], B, E, 2 * Hkv * r, lat)
+                W.wsvd_linear_w4a8_split(ctx, xq, xsc, Ly["wqkv"], Ly["wqkvs"], B, E, Hq * d + 2 * Hkv * r, Hq * d, q, lat)
                 W.wsvd_latent_store(ctx, desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, Ly["cache"])
             W.wsvd_decode_attn(ctx, desc, q, None, BKd, BVd, Ly["cache"], t_cap, o)
             if not attn_only:
@@ -370,7 +368,7 @@ def run_c5(args, np, torch, W, WI):
         "config": {"workload": "c5: 28-layer grouped-query W4A8 attention block, B=32 Hq=28 Hkv=4 d_head=128 d_model=3584 r=64 T=8192",
                    "batch": B, "q_heads": Hq, "kv_heads": Hkv, "d_head": d, "d_model": E, "rank": r, "context": T, "layers": NL,
                    "launch": "hip_graph_replay" if use_graph else "eager",
-                   "step": "per layer: quantize_act_i8, linear_w4a8 (W_Q), linear_w4a8 (A_K|A_V), latent_store, decode_attn, quantize_act_i8, linear_w4a8 (W_O)"},
+                   "step": "per layer: quantize_act_i8, linear_w4a8_split (W_Q | A_K | A_V), latent_store, decode_attn, quantize_act_i8, linear_w4a8 (W_O)"},
         "roofline": {"kernel": "k_attn_gqa<64> (decode attention, 7 query heads per kv head, int8 latents)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,

@@ -211,6 +211,17 @@ wsvd_status wsvd_linear_w4a8(wsvd_ctx *ctx, const int8_t *x, const void *x_scale
                              const void *w_scale_f16, int64_t M, int64_t K, int64_t N, void *out,
                              int32_t out_dtype, void *hip_stream);
 
+/*
+ * The same layer with its output columns delivered as two row-major matrices: columns [0, n_first) to
+ * out_first [M, n_first], columns [n_first, N) to out_rest [M, N - n_first].  One launch then serves the query
+ * projection and the latent down-projection of the quantised block (weight rows W_Q, then A_K, then A_V; Section
+ * 4.2 runs all of them in the same precision on the same activations): out_first is the query wsvd_decode_attn
+ * takes, out_rest the latents wsvd_latent_store takes.  n_first a multiple of 32, 0 < n_first <= N.
+ */
+wsvd_status wsvd_linear_w4a8_split(wsvd_ctx *ctx, const int8_t *x, const void *x_scale, const void *w_i4,
+                                   const void *w_scale_f16, int64_t M, int64_t K, int64_t N, int64_t n_first,
+                                   void *out_first, void *out_rest, int32_t out_dtype, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

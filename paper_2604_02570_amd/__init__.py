@@ -25,7 +25,8 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
            "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_check", "wsvd_status_str",
-           "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8"]
+           "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
+           "wsvd_linear_w4a8_split"]
 
 
 class WsvdError(RuntimeError):
@@ -82,6 +83,8 @@ def lib():
         L.wsvd_quantize_act_i8.argtypes = [c_void_p, c_void_p, c_int32, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
         L.wsvd_linear_w4a8.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
                                        c_void_p, c_int32, c_void_p]
+        L.wsvd_linear_w4a8_split.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
+                                             c_int64, c_void_p, c_void_p, c_int32, c_void_p]
         for name in EXPORTS:
             if name not in ("wsvd_status_str",):
                 getattr(L, name).restype = c_int
@@ -213,3 +216,9 @@ def wsvd_quantize_act_i8(ctx, x, x_dtype, rows, cols, codes, scale, stream=None)
 def wsvd_linear_w4a8(ctx, x, x_scale, w_i4, w_scale, M, K, N, out, stream=None):
     _ck(lib().wsvd_linear_w4a8(ctx, _ptr(x), _ptr(x_scale), _ptr(w_i4), _ptr(w_scale), int(M), int(K), int(N),
                                _ptr(out), F32, _stream(stream)), "wsvd_linear_w4a8")
+
+
+def wsvd_linear_w4a8_split(ctx, x, x_scale, w_i4, w_scale, M, K, N, n_first, out_first, out_rest, stream=None):
+    _ck(lib().wsvd_linear_w4a8_split(ctx, _ptr(x), _ptr(x_scale), _ptr(w_i4), _ptr(w_scale), int(M), int(K), int(N),
+                                     int(n_first), _ptr(out_first), _ptr(out_rest), F32, _stream(stream)),
+        "wsvd_linear_w4a8_split")

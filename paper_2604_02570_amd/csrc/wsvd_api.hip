@@ -290,15 +290,30 @@ wsvd_status wsvd_quantize_act_i8(wsvd_ctx* ctx, const void* x, int32_t x_dtype, 
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
-wsvd_status wsvd_linear_w4a8(wsvd_ctx* ctx, const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale_f16,
-                             int64_t M, int64_t K, int64_t N, void* out, int32_t out_dtype, void* hip_stream) {
+static wsvd_status linear_w4a8(wsvd_ctx* ctx, const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale_f16,
+                               int64_t M, int64_t K, int64_t N, void* out, int64_t n_first, void* out2, int32_t out_dtype,
+                               void* hip_stream) {
   if (!ctx || !x || !x_scale || !w_i4 || !w_scale_f16 || !out) return WSVD_E_NULL;
+  if (n_first < N && !out2) return WSVD_E_NULL;
   if (out_dtype != WSVD_F32) return WSVD_E_DTYPE;
   if (M <= 0 || M > 64 || K <= 0 || K % 64 != 0 || K > 65536 || N <= 0 || N % 32 != 0 || M * N > INT32_MAX) return WSVD_E_SHAPE;
-  if (!aligned16(x) || !aligned16(w_i4) || !aligned16(out)) return WSVD_E_ALIGN;
-  hipError_t e = wsvd_launch_linear_w4a8(x, x_scale, w_i4, w_scale_f16, M, K, N, (float*)out, (hipStream_t)hip_stream);
+  if (n_first <= 0 || n_first > N || n_first % 32 != 0) return WSVD_E_SHAPE;
+  if (!aligned16(x) || !aligned16(w_i4) || !aligned16(out) || !aligned16(out2)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_linear_w4a8(x, x_scale, w_i4, w_scale_f16, M, K, N, (float*)out, n_first, (float*)out2,
+                                         (hipStream_t)hip_stream);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_linear_w4a8(wsvd_ctx* ctx, const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale_f16,
+                             int64_t M, int64_t K, int64_t N, void* out, int32_t out_dtype, void* hip_stream) {
+  return linear_w4a8(ctx, x, x_scale, w_i4, w_scale_f16, M, K, N, out, N, nullptr, out_dtype, hip_stream);
+}
+
+wsvd_status wsvd_linear_w4a8_split(wsvd_ctx* ctx, const int8_t* x, const void* x_scale, const void* w_i4,
+                                   const void* w_scale_f16, int64_t M, int64_t K, int64_t N, int64_t n_first, void* out_first,
+                                   void* out_rest, int32_t out_dtype, void* hip_stream) {
+  return linear_w4a8(ctx, x, x_scale, w_i4, w_scale_f16, M, K, N, out_first, n_first, out_rest, out_dtype, hip_stream);
 }
 
 }  // extern "C"

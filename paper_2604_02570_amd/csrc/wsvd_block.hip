@@ -34,7 +34,8 @@ WSVD_DEV void split_even_odd(const v4i lo, const v4i hi, v4i& even, v4i& odd) {
 template <int MB>
 __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __restrict__ x, const uint16_t* __restrict__ xs,
                                                                const uint8_t* __restrict__ w, const uint16_t* __restrict__ wsc,
-                                                               int M, int K, int N, float* __restrict__ out) {
+                                                               int M, int K, int N, float* __restrict__ out,
+                                                               int N1, float* __restrict__ out2) {
   __shared__ int red[kLinWaves][MB][64][4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n0 = blockIdx.x * 16;
@@ -120,24 +121,28 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
 #pragma unroll
     for (int k = 0; k < kLinWaves; k++) sum += red[k][mb][src_lane][v];
     const int m = mb * 16 + rr;
-    if (m < M) out[(size_t)m * N + n0 + c] = (float)(sum >> 4) * sx[it] * sw[it];
+    // output columns [0, N1) form one row-major matrix, [N1, N) a second one (a 16-column tile never straddles)
+    float* dst = n0 < N1 ? out + (size_t)m * N1 + n0 : out2 + (size_t)m * (N - N1) + (n0 - N1);
+    if (m < M) dst[c] = (float)(sum >> 4) * sx[it] * sw[it];
   }
 }
 
 }  // namespace
 
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
-                                   int64_t K, int64_t N, float* out, hipStream_t s) {
+                                   int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s) {
   if (M < 1 || M > 64 || K < 64 || K % 64 != 0 || K > 65536 || N % 16 != 0) return hipErrorInvalidValue;
+  if (n_first < 0 || n_first > N || n_first % 16 != 0 || (n_first < N && !out2)) return hipErrorInvalidValue;
+  const int N1 = (int)n_first;
   dim3 grid((unsigned)(N / 16)), block(kLinWaves * 64);
   const uint16_t* xs = (const uint16_t*)x_scale;
   const uint16_t* ws = (const uint16_t*)w_scale;
   const uint8_t* w = (const uint8_t*)w_i4;
   switch ((M + 15) / 16) {
-    case 1: hipLaunchKernelGGL((k_linear_w4a8<1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out); break;
-    case 2: hipLaunchKernelGGL((k_linear_w4a8<2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out); break;
-    case 3: hipLaunchKernelGGL((k_linear_w4a8<3>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out); break;
-    default: hipLaunchKernelGGL((k_linear_w4a8<4>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out); break;
+    case 1: hipLaunchKernelGGL((k_linear_w4a8<1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+    case 2: hipLaunchKernelGGL((k_linear_w4a8<2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+    case 3: hipLaunchKernelGGL((k_linear_w4a8<3>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+    default: hipLaunchKernelGGL((k_linear_w4a8<4>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
   }
   return hipGetLastError();
 }

@@ -27,8 +27,9 @@ hipError_t wsvd_launch_pack_factor_a(const wsvd_layer_desc& d, const void* src, 
 hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
                             const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,
                             hipStream_t s);
+// output columns [0, n_first) go to out (row-major [M, n_first]), the rest to out2 ([M, N - n_first])
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
-                                   int64_t K, int64_t N, float* out, hipStream_t s);
+                                   int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s);
 
 // workspace sizing shared by the API and the launchers
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);

@@ -57,6 +57,29 @@ def test_linear_w4a8_scaled_matches_oracle():
     W.wsvd_destroy(L)
 
 
+def test_linear_w4a8_split_equals_unsplit():
+    rng = np.random.default_rng(3)
+    M, K, N, N1 = 19, 448, 160, 96
+    x = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    w = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    xs = (rng.random(M) + 0.5).astype(np.float16); ws = (rng.random(N) * 0.01 + 0.001).astype(np.float16)
+    L = W.wsvd_create(0)
+    whole = gpu_linear(L, x, xs, w, ws)
+    a = torch.full((M, N1), float("nan"), dtype=torch.float32, device="cuda")
+    b = torch.full((M, N - N1), float("nan"), dtype=torch.float32, device="cuda")
+    u16 = lambda v: dev(np.asarray(v, np.float16).view(np.uint16))
+    W.wsvd_linear_w4a8_split(L, dev(x), u16(xs), dev(O.pack_w4(w)), u16(ws), M, K, N, N1, a, b)
+    torch.cuda.synchronize()
+    assert (a.cpu().numpy() == whole[:, :N1]).all() and (b.cpu().numpy() == whole[:, N1:]).all()
+    ref = O.linear_w4a8(x, xs, O.pack_w4(w), ws)
+    assert np.abs(whole - ref).max() <= 1e-6 * np.abs(ref).max()
+    for bad in (0, 48, N + 32):
+        with pytest.raises(W.WsvdError) as e:
+            W.wsvd_linear_w4a8_split(L, dev(x), u16(xs), dev(O.pack_w4(w)), u16(ws), M, K, N, bad, a, b)
+        assert e.value.status == W.E_SHAPE
+    W.wsvd_destroy(L)
+
+
 def test_linear_w4a8_host_errors():
     L = W.wsvd_create(0)
     x = torch.zeros((4, 128), dtype=torch.int8, device="cuda")
@@ -137,8 +160,12 @@ def _run_block(c, L, stagewise, ref=None, before=None):
     q = torch.empty((B, Hq * d), dtype=torch.float32, device="cuda")
     lat = torch.empty((B, 2 * Hkv * r), dtype=torch.float32, device="cuda")
     akv = np.concatenate([c.ak[0], c.av[0]], 0); akv_s = np.concatenate([c.ak[1], c.av[1]])
-    W.wsvd_linear_w4a8(L.ctx, xq, xs, dev(O.pack_w4(c.wq[0])), u16(c.wq[1]), B, E, Hq * d, q)
-    W.wsvd_linear_w4a8(L.ctx, xq, xs, dev(O.pack_w4(akv)), u16(akv_s), B, E, 2 * Hkv * r, lat)
+    if stagewise:
+        W.wsvd_linear_w4a8(L.ctx, xq, xs, dev(O.pack_w4(c.wq[0])), u16(c.wq[1]), B, E, Hq * d, q)
+        W.wsvd_linear_w4a8(L.ctx, xq, xs, dev(O.pack_w4(akv)), u16(akv_s), B, E, 2 * Hkv * r, lat)
+    else:                      # one launch over the stacked weight [W_Q; A_K; A_V], two outputs
+        wall = np.concatenate([c.wq[0], akv], 0); wall_s = np.concatenate([c.wq[1], akv_s])
+        W.wsvd_linear_w4a8_split(L.ctx, xq, xs, dev(O.pack_w4(wall)), u16(wall_s), B, E, Hq * d + 2 * Hkv * r, Hq * d, q, lat)
     torch.cuda.synchronize()
     for what, got, want in (("q", q.cpu().numpy(), ref["q"].reshape(B, -1)),
                             ("latents", lat.cpu().numpy(), np.concatenate([ref["cK"].reshape(B, -1), ref["cV"].reshape(B, -1)], 1))):
