@@ -304,7 +304,7 @@ def run_c5(args, np, torch, W, WI):
     o = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
     oq = torch.empty((B, Hq * d), dtype=torch.int8, device="cuda"); osc = torch.empty(B, dtype=torch.int16, device="cuda")
 
-    def step(attn_only=False):
+    def step(attn_only=args.attn_only):
         x = x0
         for l, Ly in enumerate(layers):
             if not attn_only:

@@ -20,7 +20,7 @@ struct AppendParams {
   uint16_t* meta[2];
   int* seq_lens;
   float* partials;           // [2][Hkv][ES][B][R]
-  int* tickets;              // [2*Hkv] per (plane, kv head) tickets, then [1] the finishers' ticket
+  int* tickets;              // [2*Hkv] per (plane, kv head) tickets, then [1] the readers' ticket
   int* err_word;
   int B, E, Hkv, t_cap, ES, ESL;
   int x_dtype, factor_dtype, latent_dtype;
@@ -166,16 +166,19 @@ WSVD_DEV void append_read_lens(const AppendParams& p, int* n_sh) {
   __syncthreads();
 }
 
-// Called by the workgroup that stored the rows of one (plane, kv head), after its stores: the last of the 2*Hkv
-// such workgroups advances the sequence lengths.  By then every workgroup that needs the old lengths has read them
-// (each reads them before it can finish).
-WSVD_DEV void append_bump(const AppendParams& p, const int* n_sh, int* flag_sh) {
+// Advancing the sequence lengths only has to wait until every workgroup that USES the old ones (the 2*Hkv that end
+// up storing the rows of a plane and kv head) holds its copy; the consumer of the new lengths is a later kernel.
+// So such a workgroup draws a ticket as soon as it knows its role, before it sums and stores, and looks at the
+// answer on its way out: the atomic's round trip overlaps the remaining work.  Whoever drew the last ticket
+// advances the lengths (or reports a full sequence).
+WSVD_DEV int append_reader_ticket(const AppendParams& p) {
+  return __hip_atomic_fetch_add(p.tickets + 2 * p.Hkv, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+WSVD_DEV void append_bump(const AppendParams& p, const int* n_sh, int ticket /* thread 0's draw */, int* flag_sh) {
   __syncthreads();
   if (threadIdx.x == 0) {
-    int* t = p.tickets + 2 * p.Hkv;
-    const int old = __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int last = (old == 2 * p.Hkv - 1);
-    if (last) __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (ticket == 2 * p.Hkv - 1);
+    if (last) __hip_atomic_store(p.tickets + 2 * p.Hkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *flag_sh = last;
   }
   __syncthreads();
@@ -206,6 +209,7 @@ template <int R>
 WSVD_DEV void append_finish(const AppendParams& p, int pl, int kv, float (*crow)[R + 1], int* flag_sh, const int* n_sh) {
   const int tid = threadIdx.x;
   if (append_slice_ticket(p, pl, kv, flag_sh)) {
+    const int ticket = tid == 0 ? append_reader_ticket(p) : 0;   // n_sh is complete in every workgroup by now
     const float* pbase = p.partials + (((size_t)pl * p.Hkv + kv) * p.ES) * p.B * R;
     for (int b0 = 0; b0 < p.B; b0 += 64) {
       const int nb = min(64, p.B - b0);
@@ -226,7 +230,7 @@ WSVD_DEV void append_finish(const AppendParams& p, int pl, int kv, float (*crow)
       __syncthreads();
       append_store_rows<R>(p, pl, kv, b0, nb, crow, n_sh);
     }
-    append_bump(p, n_sh, flag_sh);
+    append_bump(p, n_sh, ticket, flag_sh);
   }
 }
 
@@ -307,7 +311,7 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 // NT = launch bound.  The workgroup's d_model slice [e0, e0 + ESL) is divided over its NW = blockDim/64 waves; a wave
 // walks its part in chunks of 4 k-steps (64 elements), the next chunk's operands in flight while the current one
 // multiplies.  With ES == 1 (one workgroup per plane and kv head, up to 16 waves) there is no cross-workgroup
-// hand-off at all.  Sequence lengths are fetched at the start but only waited for after the projection.
+// hand-off at all.  Sequence lengths are requested first and land in LDS together with the hidden states.
 template <int R, int NT>
 __global__ __launch_bounds__(NT) void k_append_mfma(AppendParams p) {
   constexpr int RT = R / 32;                  // 32-channel row tiles (R = 16 uses half a tile)
@@ -338,6 +342,7 @@ __global__ __launch_bounds__(NT) void k_append_mfma(AppendParams p) {
   const uint16_t* Ap = (const uint16_t*)p.A[pl];
   const uint16_t* xp = (const uint16_t*)p.x;
   bool lens_done = false;
+  int ticket = 0;
 
   for (int b0 = 0; b0 < p.B; b0 += 32) {
     const int nb = min(32, p.B - b0);
@@ -377,7 +382,17 @@ __global__ __launch_bounds__(NT) void k_append_mfma(AppendParams p) {
         const int r = i / ppr, c = i % ppr;
         *(v4i*)&xs[r][c * 8] = *(const v4i*)(xp + (size_t)(b0 + r) * p.E + s * p.ESL + c * 8);
       }
+      if (!lens_done) {
+        // the lengths were requested before everything else, so they are here by now
+#pragma unroll
+        for (int i = 0; i < NLEN; i++) {
+          const int b = i * (int)blockDim.x + tid;
+          if (b < p.B) n_sh[b] = nreg[i];
+        }
+      }
       __syncthreads();
+      if (!lens_done && tid == 0 && p.ES == 1) ticket = append_reader_ticket(p);   // the lengths are complete in LDS
+      lens_done = true;
     }
     for (int c0 = 0; c0 < ks_n; c0 += 2 * KS) {
       load_chunk(1, c0 + KS);
@@ -385,17 +400,9 @@ __global__ __launch_bounds__(NT) void k_append_mfma(AppendParams p) {
       load_chunk(0, c0 + 2 * KS);
       mul_chunk(1, c0 + KS);
     }
-    if (!lens_done) {
-#pragma unroll
-      for (int i = 0; i < NLEN; i++) {
-        const int b = i * (int)blockDim.x + tid;
-        if (b < p.B) n_sh[b] = nreg[i];
-      }
-    }
     // cross-wave sum in a fixed order: rounds of RW waves through LDS
     for (int r0 = 0; r0 < NW; r0 += RW) {
       __syncthreads();
-      lens_done = true;
       if (wave >= r0 && wave < r0 + RW) {
 #pragma unroll
         for (int rt = 0; rt < RTC; rt++)
@@ -423,7 +430,7 @@ __global__ __launch_bounds__(NT) void k_append_mfma(AppendParams p) {
     }
   }
   if (p.ES != 1) append_finish<R>(p, pl, kv, crow, &flag_sh, n_sh);
-  else append_bump(p, n_sh, &flag_sh);
+  else append_bump(p, n_sh, ticket, &flag_sh);
 }
 
 // ---------------------------------------------------------------- factor packing (set-up time)
