@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
     ap.add_argument("--workload", choices=["c3", "c5"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c5: the 28-layer grouped-query W4A8 attention block (a secondary line, same JSON shape)")
@@ -59,6 +61,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     W.lib()   # fails loudly if the HIP library is missing
+    if args.single_launch:
+        W.wsvd_set_option("fused_step", 2)
     if args.workload == "c5":
         return run_c5(args, np, torch, W, WI)
 
@@ -115,9 +119,13 @@ def main():
 
     def step(i):
         s = sets[i % n_sets]
-        if not args.attn_only:
+        if args.attn_only:
+            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+        elif args.single_launch:
+            W.wsvd_decode_step(ctx, desc, xd, None, AKd, AVd, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+        else:
             W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, s[5])
-        W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
 
     def attn_only(i):
         s = sets[i % n_sets]
@@ -221,7 +229,8 @@ def main():
             "context_drift_rows": max(seq_after) - T,
             "cache_sets_rotated": n_sets, "cache_set_MB": round(2 * (cb + mb) / 1e6, 1),
             "launch": "hip_graph_replay" if use_graph else "eager",
-            "step": "attention only" if args.attn_only else "wsvd_latent_append + wsvd_decode_attn",
+            "step": "attention only" if args.attn_only else ("wsvd_decode_step (single-launch kernel)" if args.single_launch
+                                                              else "wsvd_latent_append + wsvd_decode_attn"),
             "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / args.steps, 6),
         },
         "roofline": {

@@ -155,10 +155,27 @@ wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const v
                              const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,
                              void *out, void *hip_stream);
 
-/* Process-wide tuning knobs for benchmarks; correct use never needs them.
- *   "wg_per_cu": workgroups per compute unit the attention grid aims for (default 4)
- *   "min_chunk": smallest context chunk per workgroup in rows, multiple of 64, at least 256 */
+/* Process-wide tuning knobs for benchmarks and tests; correct use never needs them.
+ *   "wg_per_cu": scales the number of wavefronts the attention grid aims for (default 4 = one resident round)
+ *   "min_chunk": smallest context chunk per workgroup in rows, multiple of 64, at least 256
+ *   "max_threads": cap on the attention workgroup size (0 = the kernel's own bound)
+ *   "append_mode": number of d_model slices of the append (0 = automatic)
+ *   "fused_step": wsvd_decode_step uses 0 = two launches (default), 1 = the single-launch kernel where one exists,
+ *                 2 = the single-launch kernel or WSVD_E_UNSUPPORTED */
 wsvd_status wsvd_set_option(const char *name, int value);
+
+/*
+ * One decode step of a layer (Section 3.4, decoding pipeline): wsvd_latent_append followed by wsvd_decode_attn,
+ * with the same arguments and the same results (the attention includes the row just appended).  By default the
+ * two kernels are launched back to back.  A single-launch kernel exists for I8 / I4 latents with bf16 hidden
+ * states and factors and at most 4 query heads per kv head ("fused_step" option); it measured no faster on
+ * MI355X, so it is not the default.
+ *   max_seq_len: host upper bound on the sequence lengths AFTER the append (>= 1).
+ * Capacity handling as in wsvd_latent_append: a full sequence is attended as it is and reported by wsvd_check.
+ */
+wsvd_status wsvd_decode_step(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
+                             const void *A_K, const void *A_V, const void *q, const void *q_scale, const void *B_K,
+                             const void *B_V, wsvd_cache *cache, int32_t max_seq_len, void *out, void *hip_stream);
 
 /* Synchronise the stream and return (then clear) the device-side error word. */
 wsvd_status wsvd_check(wsvd_ctx *ctx, void *hip_stream);

@@ -20,6 +20,8 @@ inline bool is_pow2_rank(int r) { return r == 16 || r == 32 || r == 64; }
 int g_opt_wg_per_cu = 4;      // workgroups per CU the attention grid aims for
 int g_opt_min_chunk = 256;    // smallest context chunk per workgroup (rows)
 int g_opt_max_threads = 0;    // cap on the MFMA kernels' workgroup size (0 = their launch bound)
+int g_opt_fused_step = 0;     // wsvd_decode_step: 0 = two launches (default: the fused kernel measured no faster),
+                              // 1 = fused kernel where there is one, 2 = fused or WSVD_E_UNSUPPORTED (tests)
 
 wsvd_status check_desc(const wsvd_layer_desc* d) {
   if (!d) return WSVD_E_NULL;
@@ -112,6 +114,7 @@ wsvd_status wsvd_create(wsvd_ctx** out, int device_ordinal) {
   c->n_cu = prop.multiProcessorCount;
   c->ws = nullptr;
   c->ws_bytes = 0;
+  c->epoch = 0;
   if (hipMalloc((void**)&c->err_word, 4) != hipSuccess) { delete c; return WSVD_E_HIP; }
   if (hipMemset(c->err_word, 0, 4) != hipSuccess) { (void)hipFree(c->err_word); delete c; return WSVD_E_HIP; }
   *out = c;
@@ -140,7 +143,8 @@ wsvd_status wsvd_workspace_bytes(const wsvd_layer_desc* desc, size_t* bytes) {
   wsvd_status st = check_desc(desc);
   if (st != WSVD_OK) return st;
   const size_t a = wsvd_attn_partial_floats(*desc), b = wsvd_append_partial_floats(*desc);
-  *bytes = (size_t)kWsCounterInts * 4 + (a > b ? a : b) * 4;
+  // the fused decode step runs both at once: the append's partial sums sit behind the attention's (16-byte aligned)
+  *bytes = (size_t)kWsCounterInts * 4 + ((a + 3) / 4 * 4 + b) * 4;
   return WSVD_OK;
 }
 
@@ -162,6 +166,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { g_opt_wg_per_cu = value; return WSVD_OK; }
   if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
   if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { g_append_mode = value; return WSVD_OK; }
+  if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
@@ -209,6 +214,36 @@ wsvd_status wsvd_decode_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
   hipError_t e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, (hipStream_t)hip_stream);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* x, const void* x_scale, const void* A_K,
+                             const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,
+                             wsvd_cache* cache, int32_t max_seq_len, void* out, void* hip_stream) {
+  if (!ctx || !x || !A_K || !A_V || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V) || !aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out))
+    return WSVD_E_ALIGN;
+  if (max_seq_len < 1) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = g_opt_fused_step ? wsvd_launch_decode_step(ctx, *desc, x, x_scale, A_K, A_V, q, q_scale, B_K, B_V, *cache,
+                                                            max_seq_len, out, s)
+                                  : hipErrorNotSupported;
+  if (e == hipErrorNotSupported && g_opt_fused_step == 2) return WSVD_E_UNSUPPORTED;
+  if (e == hipErrorNotSupported) {
+    // no fused kernel for this combination: the two calls back to back on the stream
+    e = wsvd_launch_append(ctx, *desc, x, x_scale, A_K, A_V, *cache, s);
+    if (e == hipSuccess) e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, s);
+    if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  }
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
@@ -319,10 +354,11 @@ wsvd_status wsvd_linear_w4a8_split(wsvd_ctx* ctx, const int8_t* x, const void* x
 }  // extern "C"
 
 // ---------------------------------------------------------------- attention launch policy
-hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
-                            const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,
-                            hipStream_t s) {
-  AttnParams p;
+// Fills the kernel parameters and decides the decomposition: grid = (Hkv, n_chunks, B), threads per workgroup.
+void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale, const void* B_K,
+                    const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out, AttnParams& p, dim3& grid,
+                    int& threads, int force_threads) {
+  p = AttnParams{};
   p.q = q; p.q_scale = (const uint16_t*)q_scale; p.BK = B_K; p.BV = B_V;
   p.k_codes = (const uint8_t*)cache.k_codes; p.v_codes = (const uint8_t*)cache.v_codes;
   p.k_meta = (const uint16_t*)cache.k_meta; p.v_meta = (const uint16_t*)cache.v_meta;
@@ -355,6 +391,7 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
     const int bound = wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank, p.G);
     const int nw_max = (g_opt_max_threads && g_opt_max_threads < bound ? g_opt_max_threads : bound) / 64;
     while (nw * 2 <= nw_max && nw * 2 <= waves_per_unit) nw *= 2;
+    if (force_threads) nw = force_threads / 64;     // the fused step: one workgroup size for both roles
   }
   int chunks_wanted = waves_per_unit / nw;
   if (chunks_wanted < 1) chunks_wanted = 1;
@@ -363,7 +400,18 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
   if (chunk_rows < min_chunk) chunk_rows = min_chunk;
   p.chunk_rows = chunk_rows;
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
-  dim3 grid((unsigned)d.n_kv_heads, (unsigned)p.n_chunks, (unsigned)d.batch);
+  grid = dim3((unsigned)d.n_kv_heads, (unsigned)p.n_chunks, (unsigned)d.batch);
+  threads = nw * 64;
+}
+
+hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
+                            const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,
+                            hipStream_t s) {
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 0);
+  const bool mfma = !(d.latent_dtype == WSVD_F32 || d.latent_dtype == WSVD_BF16);
   if (!mfma) return wsvd_launch_attn_generic(p, d.latent_dtype, d.rank, grid, s);
-  return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, nw * 64, s);
+  return wsvd_launch_attn_mfma(p, d.latent_dtype, d.rank, grid, threads, s);
 }

@@ -21,6 +21,11 @@ struct AttnParams {
   int n_chunks;              // grid extent along the context
   int q_dtype, factor_dtype;
   float c_scale;             // sm_scale * log2(e): scores live in the log2 domain
+  // fused decode step only: the append workgroups of the same launch publish row seq_lens[b] of kv head h's K / V
+  // plane by setting flags[h] / flags[Hkv + h] to epoch
+  const int* flags;
+  int epoch;
+  int* err_word;
 };
 
 struct WorkItem {
@@ -31,11 +36,11 @@ struct WorkItem {
 // Grid = (Hkv, n_chunks, B): blockIdx.x = kv head, .y = context chunk, .z = sequence.  The linear workgroup id
 // (x fastest) is dealt round-robin to the 8 XCDs, so with Hkv a multiple of 8 each XCD's L2 only ever sees the
 // B factors of Hkv/8 heads.  No integer division on the way to the first load.
-WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) {
+WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw, int kv, int chunk, int b) {
   WorkItem w;
-  w.kv = blockIdx.x;
-  w.chunk = blockIdx.y;
-  w.b = blockIdx.z;
+  w.kv = kv;
+  w.chunk = chunk;
+  w.b = b;
   w.n = n_raw < 0 ? 0 : (n_raw > p.t_cap ? p.t_cap : n_raw);
   w.n_splits = (w.n + p.chunk_rows - 1) / p.chunk_rows;
   w.row_begin = w.chunk * p.chunk_rows;
@@ -43,6 +48,7 @@ WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) {
   w.active = w.chunk < w.n_splits;
   return w;
 }
+WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) { return decode_work(p, n_raw, blockIdx.x, blockIdx.y, blockIdx.z); }
 
 // A sequence with no rows: its outputs are zeros (written by the chunk-0 workgroup).
 WSVD_DEV void write_zero_outputs(const AttnParams& p, const WorkItem& w) {
@@ -182,7 +188,8 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       const float v = k == 0 ? Msh[g] : k == 1 ? Lsh[g] : Ush[g * R + (k - 2)];
       agent_store(&p.partials[(((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks + w.chunk) * (R + 2) + k], v);
     }
-    __syncthreads();   // every thread's partial stores have completed (vmcnt 0) before the ticket is taken
+    wait_vmem_done();  // this thread's partial stores are acknowledged ...
+    __syncthreads();   // ... and so are everybody's, before the ticket is taken
     if (tid == 0) {
       int* t = p.tickets + (size_t)w.b * p.Hkv + w.kv;
       const int old = __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -17,9 +17,8 @@
 //   A: lane L holds row L%32, k = 16*(L/32)..+15;  B: lane L holds column L%32, same k;
 //   D: lane L, register v holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
 #include "wsvd_attn_common.h"
+#include "wsvd_append_body.h"
 #include "wsvd_internal.h"
-
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 template <int R, bool I4>
 struct TileRegs {
@@ -56,6 +55,39 @@ WSVD_DEV void load_tile(TileRegs<R, I4>& t, const uint8_t* kplane, const uint8_t
   }
 }
 
+// The same tile through agent-scope loads (dword granularity): coherent with write-through stores made by other
+// workgroups of the running launch.
+WSVD_DEV v4i load16_coherent(const uint8_t* a) {
+  v4i r;
+#pragma unroll
+  for (int i = 0; i < 4; i++) r[i] = __hip_atomic_load((const int*)a + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return r;
+}
+template <int R, bool I4>
+WSVD_DEV void load_tile_coherent(TileRegs<R, I4>& t, const uint8_t* kplane, const uint8_t* vplane, const uint16_t* kmeta,
+                                 const uint16_t* vmeta, int tile, int lane) {
+  if (I4) {
+    const uint32_t off = (uint32_t)tile * 1024u + (uint32_t)lane * 16u;
+    t.k[0][0] = load16_coherent(kplane + off);
+    t.v[0][0] = load16_coherent(vplane + off);
+    const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
+    t.kmeta = __hip_atomic_load((const uint32_t*)kmeta + moff, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    t.vmeta = __hip_atomic_load((const uint32_t*)vmeta + moff, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    const uint32_t off = (uint32_t)tile * (uint32_t)(64 * R) + (uint32_t)lane * 16u;
+#pragma unroll
+    for (int blk = 0; blk < 2; blk++)
+#pragma unroll
+      for (int kk = 0; kk < R / 32; kk++) {
+        t.k[kk][blk] = load16_coherent(kplane + off + (uint32_t)(blk * (32 * R) + kk * 1024));
+        t.v[kk][blk] = load16_coherent(vplane + off + (uint32_t)(blk * (32 * R) + kk * 1024));
+      }
+    const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
+    t.kmeta = __hip_atomic_load(kmeta + moff, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    t.vmeta = __hip_atomic_load(vmeta + moff, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
 
 // three limb dot products -> float: h*2^14 + m*2^7 + l
@@ -65,32 +97,43 @@ constexpr float kLimbFull = 1048576.f;    // 2^20: |quantised value| <= 2^20 fit
 constexpr int kMaxTilesPerFlush = 1024;   // 64 tokens * 127 * 127 per tile and limb: int32 holds > 2000 tiles
 
 // NT = launch bound (threads); the workgroup may be launched with any multiple of 64 threads up to NT.
-template <int R, int G, bool I4, int NT>
-__global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
+template <int R, int G, int NT>
+struct AttnMfmaShared {
+  static constexpr int NWMAX = NT / 64;
+  v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
+  __attribute__((aligned(16))) float q_lds[G * 128];
+  float qts[G * R];
+  __attribute__((aligned(16))) int8_t qlimb[G][3][R];       // limbs of q~ in operand k-order
+  float qdelta[G], qzsum[G];
+  __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
+  float wm[NWMAX][G], wls[NWMAX][G];
+  float wu[NWMAX][G][R];
+  float wo[NWMAX][G][128];                                  // per wave: its accumulator times B_V
+  float Msh[G], Lsh[G], Ush[G * R];
+  int flag_sh;
+};
+
+// One workgroup's share of the decode attention: kv head cx, context chunk cy, sequence cz.
+// FUSED: the workgroup is part of a decode-step launch whose append workgroups are writing row seq_lens[b] at this
+// very moment.  The row counts as present; the 64-row tile that contains it is kept out of the streaming loop and
+// done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
+template <int R, int G, bool I4, int NT, bool FUSED>
+WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, const int cx, const int cy, const int cz) {
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
   constexpr int NWMAX = NT / 64;
   constexpr int FIT = R / 16;           // 16-byte staging passes for an R x 128 bf16 factor
-
-  __shared__ v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
-  __shared__ __attribute__((aligned(16))) float q_lds[G * 128];
-  __shared__ float qts[G * R];
-  __shared__ __attribute__((aligned(16))) int8_t qlimb[G][3][R];       // limbs of q~ in operand k-order
-  __shared__ float qdelta[G], qzsum[G];
-  __shared__ __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
-  __shared__ float wm[NWMAX][G], wls[NWMAX][G];
-  __shared__ float wu[NWMAX][G][R];
-  __shared__ float wo[NWMAX][G][128];                                  // per wave: its accumulator times B_V
-  __shared__ float Msh[G], Lsh[G], Ush[G * R];
-  __shared__ int flag_sh;
+  auto& bk_lds = sh.bk_lds; auto& bv_lds = sh.bv_lds; auto& q_lds = sh.q_lds; auto& qts = sh.qts; auto& qlimb = sh.qlimb;
+  auto& qdelta = sh.qdelta; auto& qzsum = sh.qzsum; auto& wl = sh.wl; auto& wm = sh.wm; auto& wls = sh.wls; auto& wu = sh.wu;
+  auto& wo = sh.wo; auto& Msh = sh.Msh; auto& Lsh = sh.Lsh; auto& Ush = sh.Ush; int& flag_sh = sh.flag_sh;
 
   // scalar loads first: issued ahead of the flood of vector loads they come back quickly, and nothing needs them
   // until the tile loop
-  const int n_raw = p.seq_lens[blockIdx.z];
-  const uint32_t qs_raw = q_scale_raw(p, blockIdx.z);
+  const int n_raw = p.seq_lens[cz];
+  const uint32_t qs_raw = q_scale_raw(p, cz);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
-  const size_t ph = (size_t)blockIdx.z * p.Hkv + blockIdx.x;
+  const size_t ph = (size_t)cz * p.Hkv + cx;
   const size_t plane_bytes = (size_t)p.t_cap * (I4 ? R / 2 : R);
   const uint8_t* kplane = p.k_codes + ph * plane_bytes;
   const uint8_t* vplane = p.v_codes + ph * plane_bytes;
@@ -104,16 +147,16 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   const int fac16 = R * p.d * 2 / 16;
   StageRegs<FIT> stk, stv;
   QRegs qr;
-  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)blockIdx.x * R * p.d * 2, fac16);
-  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
-  q_issue(p, blockIdx.z, blockIdx.x, qr);
+  stage_issue<FIT>(stk, (const char*)p.BK + (size_t)cx * R * p.d * 2, fac16);
+  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)cx * R * p.d * 2, fac16);
+  q_issue(p, cz, cx, qr);
   constexpr int DEPTH = 2;   // deeper prefetch costs registers and measured slower
   TileRegs<R, I4> buf[DEPTH];
   const int chunk_tiles = p.chunk_rows >> 6;
-  int T = (int)blockIdx.y * chunk_tiles + wave;
+  int T = (int)cy * chunk_tiles + wave;
   {
     // unconditional (clamped to the chunk's last allocated tile): see stage_issue
-    const int spec_last = min(((int)blockIdx.y + 1) * chunk_tiles, p.t_cap >> 6) - 1;
+    const int spec_last = min(((int)cy + 1) * chunk_tiles, p.t_cap >> 6) - 1;
 #pragma unroll
     for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
   }
@@ -165,11 +208,14 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
     }
   }
   // only now are the sequence length and the query scale needed
-  const float qs = q_scale_value(p, blockIdx.z, qs_raw);
-  const WorkItem w = decode_work(p, n_raw);
+  const float qs = q_scale_value(p, cz, qs_raw);
+  const bool has_new = FUSED && n_raw >= 0 && n_raw < p.t_cap;          // the row being appended by this launch
+  const WorkItem w = decode_work(p, n_raw + (has_new ? 1 : 0), cx, cy, cz);
   if (w.n == 0) { write_zero_outputs(p, w); return; }
   if (!w.active) return;
-  const int tile_end = (w.row_end + 63) >> 6;
+  const int new_tile = n_raw >> 6;                                      // tile of the new row (its chunk's last tile)
+  const bool own_new = has_new && new_tile >= cy * chunk_tiles && new_tile < (cy + 1) * chunk_tiles;
+  const int tile_end = ((w.row_end + 63) >> 6) - (own_new ? 1 : 0);
   float delta[G], zsum[G];
 #pragma unroll
   for (int g = 0; g < G; g++) { delta[g] = qdelta[g] * qs; zsum[g] = qzsum[g]; }
@@ -314,6 +360,21 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   for (int i = 0; i < DEPTH; i++)
     if (done + i < n) compute(buf[i], T + (done + i) * NW);
 
+  if (FUSED) {
+    // the tile with the row appended by this launch, taken by the wave whose turn it would have been
+    if (own_new && wave == (new_tile - cy * chunk_tiles) % NW) {
+      int budget = 1 << 16;
+      while (budget > 0 && (__hip_atomic_load(p.flags + cx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch ||
+                            __hip_atomic_load(p.flags + p.Hkv + cx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch)) {
+        __builtin_amdgcn_s_sleep(16);
+        budget--;
+      }
+      if (budget == 0 && lane == 0) atomicExch(p.err_word, (int)WSVD_E_HIP);   // never seen; keeps the kernel finite
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop whatever this CU / XCD cached of the tile earlier
+      load_tile_coherent<R, I4>(buf[0], kplane, vplane, kmeta, vmeta, new_tile, lane);
+      compute(buf[0], new_tile);
+    }
+  }
   // ---- per-wave state -> workgroup merge
 #pragma unroll
   for (int g = 0; g < G; g++) {
@@ -381,6 +442,12 @@ __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   }
   __syncthreads();
   attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, bv_lds);
+}
+
+template <int R, int G, bool I4, int NT>
+__global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
+  __shared__ AttnMfmaShared<R, G, NT> sh;
+  attn_mfma_body<R, G, I4, NT, false>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // ---------------------------------------------------------------- 5 to 8 query heads per kv head (I8 latents)
@@ -738,4 +805,102 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
   if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false, 512>(p, grid, threads, s);
   if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true, 1024>(p, grid, threads, s);
   return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------- fused decode step: append + attention in one launch
+// The append's chain of dependent memory round trips (slice hand-off, partial sums, row store) leaves the memory
+// system mostly idle; run as workgroups of the same launch as the attention it hides behind the cache stream.
+// Workgroups [0, n_append) do the latent append (dispatched first, they never wait for anything), the rest the
+// attention; an attention workgroup only needs the new row for the very last tile of its sequence, which it takes
+// last and only after the append has published it (flags; the wait is bounded, so the kernel ends whatever happens).
+// Measured on the batched int8 workload this buys nothing: with the append first the attention workgroups only get
+// their slots when the append's leave (27.0 us against 26.9 us for two launches); with the two kinds interleaved the
+// saturated memory system stretches every round trip of the append's chain (37 us); and the agent-scope release the
+// memory model asks for before the flag (an L2 write-back) costs far more than it hides (95 us).  wsvd_decode_step
+// therefore uses two launches unless the "fused_step" option asks for this kernel.  Every workgroup ends by counting itself; the last one
+// advances the sequence lengths, so every reader of the old lengths is done by then.
+struct StepParams {
+  AttnParams a;
+  AppendParams ap;
+  int n_append;
+  int* done;
+};
+
+template <int R, int G, int NT>
+union StepShared {
+  AttnMfmaShared<R, G, NT> attn;
+  AppendMfmaShared<R> app;
+};
+
+template <int R, int G, bool I4, int NT>
+__global__ __launch_bounds__(NT) void k_decode_step(StepParams sp) {
+  __shared__ StepShared<R, G, NT> sh;
+  __shared__ int last_sh;
+  const int id = blockIdx.x;
+  if (id < sp.n_append) {
+    append_mfma_body<R>(sp.ap, sh.app, id);
+  } else {
+    const int r = id - sp.n_append;
+    const int kv = r % sp.a.Hkv, r2 = r / sp.a.Hkv;
+    attn_mfma_body<R, G, I4, NT, true>(sp.a, sh.attn, kv, r2 % sp.a.n_chunks, r2 / sp.a.n_chunks);
+  }
+  __syncthreads();   // every wave of this workgroup has consumed the old lengths
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(sp.done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (old == (int)gridDim.x - 1);
+    if (last) __hip_atomic_store(sp.done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last_sh = last;
+  }
+  __syncthreads();
+  if (!last_sh) return;
+  // everything has finished: clear the row flags, so that a captured launch (whose epoch is baked into the graph) can
+  // be replayed any number of times
+  for (int i = threadIdx.x; i < 2 * sp.ap.Hkv; i += blockDim.x)
+    __hip_atomic_store(sp.ap.flags + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int b = threadIdx.x; b < sp.ap.B; b += blockDim.x) {
+    const int n = sp.ap.seq_lens[b];
+    if (n >= 0 && n < sp.ap.t_cap) sp.ap.seq_lens[b] = n + 1;
+    else atomicExch(sp.ap.err_word, (int)WSVD_E_CAPACITY);
+  }
+}
+
+template <int R, bool I4, int NT>
+static hipError_t launch_step(const StepParams& sp, int n_wg, int threads, hipStream_t s) {
+  switch (sp.a.G) {
+    case 1: hipLaunchKernelGGL((k_decode_step<R, 1, I4, NT>), dim3(n_wg), dim3(threads), 0, s, sp); break;
+    case 2: hipLaunchKernelGGL((k_decode_step<R, 2, I4, NT>), dim3(n_wg), dim3(threads), 0, s, sp); break;
+    case 3: hipLaunchKernelGGL((k_decode_step<R, 3, I4, NT>), dim3(n_wg), dim3(threads), 0, s, sp); break;
+    case 4: hipLaunchKernelGGL((k_decode_step<R, 4, I4, NT>), dim3(n_wg), dim3(threads), 0, s, sp); break;
+    default: return hipErrorNotSupported;
+  }
+  return hipGetLastError();
+}
+
+hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
+                                   const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,
+                                   const wsvd_cache& cache, int max_seq_len, void* out, hipStream_t s) {
+  const bool i8 = d.latent_dtype == WSVD_I8, i4 = d.latent_dtype == WSVD_I4;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  if (!(i8 || i4) || G > 4 || !wsvd_append_uses_mfma(d) || d.n_kv_heads > 1024 || d.batch > kAppendMaxB) return hipErrorNotSupported;
+  if (!((i8 && (d.rank == 32 || d.rank == 64)) || (i4 && d.rank == 32))) return hipErrorNotSupported;
+  StepParams sp;
+  dim3 grid;
+  int threads;
+  // one workgroup size for both roles: the append's (its wave count follows from the d_model slice)
+  const int want = wsvd_append_mfma_waves(d) * 64;
+  if (want < 256 || want > wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank, G)) return hipErrorNotSupported;
+  wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, sp.a, grid, threads, want);
+  wsvd_append_params(ctx, d, x, x_scale, A_K, A_V, cache, sp.ap);
+  if (threads != want) return hipErrorNotSupported;
+  ctx->epoch = ctx->epoch == 0x7FFFFFFF ? 1 : ctx->epoch + 1;
+  int* flags = (int*)ctx->ws + kWsStepFlagsInt;
+  sp.a.flags = flags; sp.a.epoch = ctx->epoch; sp.a.err_word = ctx->err_word;
+  sp.ap.fused = 1; sp.ap.epoch = ctx->epoch; sp.ap.flags = flags;
+  sp.ap.partials = sp.a.partials + (wsvd_attn_partial_floats(d) + 3) / 4 * 4;   // both kinds of partials are live at once
+  sp.n_append = sp.ap.ES * sp.ap.Hkv * 2;
+  sp.done = (int*)ctx->ws + kWsStepDoneInt;
+  const int n_wg = sp.n_append + (int)(grid.x * grid.y * grid.z);
+  if (i8 && d.rank == 32) return launch_step<32, false, 1024>(sp, n_wg, threads, s);
+  if (i8 && d.rank == 64) return launch_step<64, false, 512>(sp, n_wg, threads, s);
+  return launch_step<32, true, 1024>(sp, n_wg, threads, s);
 }

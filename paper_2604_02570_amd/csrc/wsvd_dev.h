@@ -35,6 +35,11 @@ WSVD_DEV float load_as_f32(const void* p, size_t idx, int dtype) {
 // Agent-scope relaxed accesses: the store is written through and the load bypasses non-coherent cache
 // lines, so data handed from one workgroup to another (possibly on another XCD, behind another L2) needs
 // no cache-wide write-back / invalidate.  Ordering comes from the barriers and waits around the ticket.
+// Wait until every vector-memory operation this wave has issued is complete (for stores: acknowledged).  A
+// workgroup barrier alone does not imply it: the barrier's workgroup-scope ordering needs no drain because the
+// waves of a workgroup share their path to memory.  Hand-offs to OTHER workgroups (write-through stores, then a
+// ticket or a flag) need the drain first.   Encoding: vmcnt = 0, expcnt and lgkmcnt left at their maxima.
+WSVD_DEV void wait_vmem_done() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 WSVD_DEV void agent_store(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 WSVD_DEV float agent_load(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
@@ -178,4 +183,8 @@ WSVD_DEV size_t a_packed_offset(int kv, int j, int e, int rank, int d_model) {
 
 // ---------------------------------------------------------------- workspace layout (host + device)
 // [0, kWsCounterInts*4): tickets (zeroed by wsvd_set_workspace, self-resetting), then fp32 partials.
+// ints [0, 8192): attention split tickets; [8192, 12288): append tickets; [12288, 16000): fused-step row flags
+// (2*Hkv, hold the epoch of the last step); [16000]: fused-step finished-workgroup counter.
 constexpr int kWsCounterInts = 16384;
+constexpr int kWsStepFlagsInt = 12288;
+constexpr int kWsStepDoneInt = 16000;

@@ -11,7 +11,11 @@ struct wsvd_ctx {
   int* err_word;     // device, 4 bytes
   void* ws;          // caller-owned workspace
   size_t ws_bytes;
+  int epoch;         // number of fused decode steps launched so far (value the append workgroups publish)
 };
+
+struct AttnParams;
+struct AppendParams;
 
 hipError_t wsvd_launch_quantize_rows(int latent_dtype, int rank, const float* c, int64_t n_rows, void* codes, void* meta,
                                      hipStream_t s);
@@ -28,6 +32,17 @@ hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const
                             const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out,
                             hipStream_t s);
 // output columns [0, n_first) go to out (row-major [M, n_first]), the rest to out2 ([M, N - n_first])
+void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale, const void* B_K,
+                    const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out, AttnParams& p, dim3& grid, int& threads,
+                    int force_threads);
+void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
+                        const void* A_V, const wsvd_cache& cache, AppendParams& p);
+int wsvd_append_mfma_waves(const wsvd_layer_desc& d);
+bool wsvd_append_uses_mfma(const wsvd_layer_desc& d);
+// hipErrorNotSupported when there is no fused kernel for the combination
+hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
+                                   const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,
+                                   const wsvd_cache& cache, int max_seq_len, void* out, hipStream_t s);
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
                                    int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s);
 

@@ -101,6 +101,14 @@ class DeviceLayer:
         torch.cuda.synchronize()
         return dst
 
+    def step(self, x_dev, AK_dev, AV_dev, q_dev, q_scale_dev, BK_dev, BV_dev, max_seq_len):
+        """wsvd_decode_step; returns (output, device status word)."""
+        self.out.fill_(float("nan"))
+        W.wsvd_decode_step(self.ctx, self.desc, x_dev, None, AK_dev, AV_dev, q_dev, q_scale_dev, BK_dev, BV_dev, self.cache,
+                           max_seq_len, self.out)
+        st = W.wsvd_check(self.ctx)
+        return self.out.cpu().numpy().astype(np.float64), st
+
     def append(self, x_dev, x_scale_dev, AK_dev, AV_dev):
         W.wsvd_latent_append(self.ctx, self.desc, x_dev, x_scale_dev, AK_dev, AV_dev, self.cache)
         return W.wsvd_check(self.ctx)

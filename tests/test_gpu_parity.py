@@ -358,6 +358,95 @@ def test_host_side_errors():
     L.close()
 
 
+# ------------------------------------------------------------------------------------------ fused decode step
+STEP_CASES = [
+    ("c3_small", dict(), 2),                                      # int8, one chunk per sequence
+    ("c3_small", dict(context=2000, batch=2), 2),                 # several chunks: split merge + late tile
+    ("c3_small", dict(rank=64, context=700), 2),                  # rank 64
+    ("c3_small", dict(n_q_heads=8, n_kv_heads=4, q_dtype="f32"), 2),   # two query heads per kv head
+    ("c4_small", dict(), 2),                                      # int4, ragged lengths
+    ("c2_small", dict(), 1),                                      # bf16 latents: no single-launch kernel, two launches
+    ("c1", dict(batch=3, context=70), 1),                         # fp32: likewise
+    ("c3_small", dict(), 0),                                      # the default: two launches
+]
+
+
+@pytest.mark.parametrize("name,over,mode", STEP_CASES, ids=[f"{n}-{'-'.join(f'{k}{v}' for k, v in o.items())}" for n, o, _ in STEP_CASES])
+def test_decode_step_matches_oracle(name, over, mode):
+    """wsvd_decode_step = append + attention (including the appended row).  mode 2 insists on the single-launch
+    kernel, mode 1 takes it where it exists, mode 0 is the default pair of launches.
+    Three consecutive steps on the GPU's own cache; each compared with the oracle doing the same on its cache."""
+    c = build_case(name, steps=3, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    xdt = "f32" if sp.factor_dtype == "f32" else "bf16"
+    AKd, AVd = L.pack_A(c.AK, sp.factor_dtype), L.pack_A(c.AV, sp.factor_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, sp.factor_dtype), as_dtype_dev(c.BV, sp.factor_dtype)
+    AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
+    flips = 0
+    try:
+        W.wsvd_set_option("fused_step", mode)
+        for step in range(3):
+            x = c.x_new[step]
+            if xdt == "bf16":
+                x = WI.bf16_exact(x)
+            before = c.cache.seq_lens.copy()
+            x64 = x.astype(np.float64)
+            cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+            O.latent_append(c.cache, x64, AK64, AV64)
+            qd, qs, q64 = q_to_device(c.q32[step], sp.q_dtype)
+            ref = O.decode_attn_reconstructed(c.cache, q64, BK64, BV64, c.sm_scale)
+            got, st = L.step(as_dtype_dev(x, xdt), AKd, AVd, qd, qs, BKd, BVd, int(c.cache.seq_lens.max()))
+            assert st == 0, W.status_str(st)
+            assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all(), "seq_lens not advanced by exactly one"
+            flips += _append_compare(L, c.cache, cK, cV, before, sp.latent_dtype)
+            check_out(got, ref, sp.latent_dtype, f"step {step} {name}{over}")
+            L.upload(c.cache)      # continue from the oracle's cache so that later steps compare like with like
+    finally:
+        W.wsvd_set_option("fused_step", 0)
+    assert flips <= max(2, 2 * sp.batch * sp.n_kv_heads * sp.rank * 3 // 500)
+    L.close()
+
+
+def test_decode_step_tile_boundaries_and_capacity():
+    """The appended row starts a new 64-row tile, ends one, starts a new chunk, is the first row ever; one sequence is
+    full (left alone and flagged, attended as it is).  Fused kernel; the unfused pair of calls must agree closely."""
+    lens = [0, 1, 62, 63, 64, 65, 127, 128, 255, 256, 257, 511, 512, 639, 640]
+    c = build_case("c3_small", batch=len(lens), context=640, ragged=(), extra_cap=0, steps=1)
+    for b, n in enumerate(lens):
+        c.cache.seq_lens[b] = n
+    sp = c.sp
+    assert c.t_cap == 640 + 64
+    c.cache.seq_lens[-1] = c.t_cap                      # full
+    L = layer_for(c); L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    x = WI.bf16_exact(c.x_new[0]); x64 = x.astype(np.float64)
+    qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+    outs = []
+    for mode in (2, 0):
+        L.upload(c.cache)
+        W.wsvd_set_option("fused_step", mode)
+        try:
+            got, st = L.step(as_dtype_dev(x, "bf16"), AKd, AVd, qd, qs, BKd, BVd, c.t_cap)
+        finally:
+            W.wsvd_set_option("fused_step", 0)
+        assert st == W.E_CAPACITY
+        lens_after = L.seq_lens.cpu().numpy()
+        assert (lens_after[:-1] == np.array(lens[:-1]) + 1).all() and lens_after[-1] == c.t_cap
+        outs.append(got)
+    oc = c.cache
+    full_rows = (oc.k[-1].copy(), oc.v[-1].copy())
+    ov = O.latent_append(oc, x64, c.AK.astype(np.float64), c.AV.astype(np.float64))
+    assert ov[-1] and not ov[:-1].any()
+    assert (oc.k[-1] == full_rows[0]).all() and (oc.v[-1] == full_rows[1]).all()
+    ref = O.decode_attn_reconstructed(oc, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    for got in outs:
+        check_out(got, ref, "i8", "step at tile boundaries")
+    assert np.abs(outs[0] - outs[1]).max() <= 1e-5 * np.abs(outs[1]).max()
+    L.close()
+
+
 # ------------------------------------------------------------------------------------------ the five workloads, full size
 def test_config1_fp32_full():
     c = build_case("c1")
