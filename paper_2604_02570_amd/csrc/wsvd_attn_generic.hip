@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
   const int fac16 = R * p.d * ESZ / 16;
   {
     StageRegs<FIT> st;
-    QRegs qr;
+    QRegsT<(G * 128 + 255) / 256> qr;               // 256 query elements per pass
     stage_issue<FIT>(st, (const char*)p.BK + (size_t)w.kv * R * p.d * ESZ, fac16);
     q_issue(p, w.b, w.kv, qr);
     stage_commit<FIT>(st, fac_lds, fac16);
@@ -148,8 +148,13 @@ static hipError_t launch_g(const AttnParams& p, dim3 grid, hipStream_t s) {
   switch (p.G) {
     case 1: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 1>), grid, dim3(256), 0, s, p); break;
     case 2: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 2>), grid, dim3(256), 0, s, p); break;
+    case 3: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 3>), grid, dim3(256), 0, s, p); break;
     case 4: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 4>), grid, dim3(256), 0, s, p); break;
-    default: return hipErrorInvalidValue;
+    case 5: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 5>), grid, dim3(256), 0, s, p); break;
+    case 6: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 6>), grid, dim3(256), 0, s, p); break;
+    case 7: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 7>), grid, dim3(256), 0, s, p); break;
+    case 8: hipLaunchKernelGGL((k_attn_generic<ESZ, R, 8>), grid, dim3(256), 0, s, p); break;
+    default: return hipErrorNotSupported;
   }
   return hipGetLastError();
 }

@@ -168,6 +168,10 @@ SMALL = [
     ("c5_small", dict(n_q_heads=16, d_head=64)),             # G = 8, d_head 64
     ("c5_small", dict(context=2000)),                        # G = 7 over several context chunks
     ("c3_small", dict(n_q_heads=28, n_kv_heads=4)),          # G = 7, rank 32, int8 query
+    ("c2_small", dict(n_q_heads=12)),                        # bf16 latents, G = 3
+    ("c2_small", dict(n_q_heads=28)),                        # bf16 latents, G = 7
+    ("c2_small", dict(n_q_heads=32, rank=64)),               # bf16 latents, G = 8, rank 64
+    ("c1", dict(n_q_heads=40, n_kv_heads=8)),                # fp32 latents, G = 5
 ]
 
 
