@@ -27,6 +27,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy of known size.
 MEASURED_TRAFFIC_BYTES = 72_360_000   # 72.10 MB fetched + 0.26 MB written (profiles/attn_mfma_int8_c3_hbm_traffic.md)
+MEASURED_TRAFFIC_BYTES_C5 = 141_840_000   # 140.8 MB fetched + 1.03 MB written (profiles/attn_gqa_int8_c5_hbm_traffic.md)
 
 
 def parse():
@@ -350,7 +351,7 @@ def run_c5(args, np, torch, W, WI):
         ms_total = e0.elapsed_time(e1)
         assert W.wsvd_check(ctx, stream) == 0
         rows_end = int(layers[0]["t"][4][0])
-        assert rows_end == T0 + total, (rows_end, T0, total)
+        assert rows_end == T0 + (0 if args.attn_only else total), (rows_end, T0, total)
         # attention alone over the 28 caches
         n_rep = 3
         a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -380,7 +381,7 @@ def run_c5(args, np, torch, W, WI):
                    "step": "per layer: quantize_act_i8, linear_w4a8_split (W_Q | A_K | A_V), latent_store, decode_attn, quantize_act_i8, linear_w4a8 (W_O)"},
         "roofline": {"kernel": "k_attn_gqa<64> (decode attention, 7 query heads per kv head, int8 latents)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES_C5,
                      "algorithmic_bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 3)},
     }
     print(json.dumps(res))
