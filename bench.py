@@ -41,9 +41,10 @@ def parse():
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
-    ap.add_argument("--workload", choices=["c3", "c5"], default="c3",
+    ap.add_argument("--workload", choices=["c3", "c4", "c5"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
-                         "c5: the 28-layer grouped-query W4A8 attention block (a secondary line, same JSON shape)")
+                         "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
+                         "c5: the 28-layer grouped-query W4A8 attention block (secondary lines, same JSON shape)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -67,13 +68,14 @@ def main():
     if args.workload == "c5":
         return run_c5(args, np, torch, W, WI)
 
-    sp = WI.spec("c3")
+    sp = WI.spec(args.workload)
+    i4 = sp.latent_dtype == "i4"
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
-    n_sets = max(1, args.sets)
+    n_sets = max(1, args.sets if args.workload == "c3" else min(args.sets, 4))    # a c4 set is 340 MB
     total_steps = args.warmup + args.steps
     visits = (total_steps + n_sets - 1) // n_sets
     t_cap = (T + visits + 63) // 64 * 64
-    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "i8", "f32", 0.0)
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, sp.latent_dtype, "bf16", "bf16", "i8", "f32", 0.0)
     ctx = W.wsvd_create(0)
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     W.wsvd_set_workspace(ctx, ws)
@@ -98,18 +100,23 @@ def main():
     W.wsvd_quantize_act_i8(ctx, q32d, "f32", B, Hq * d, qd, qsd)
 
     # ---- context latents -> the library's own quantiser -> device layout (set 0), then cloned into the other sets
-    T0 = T - 1            # the timed step appends one token, so attention runs over T rows on the first visit
+    # The timed step appends one token, so attention runs over the workload's lengths on the first visit.  Every
+    # sequence's plane is filled up to the longest length (rows past a sequence's own length are never read).
+    lens0 = WI.ragged_lengths(sp).astype(np.int64) - 1
+    T0 = int(lens0.max())
     k0 = torch.zeros(cb, dtype=torch.uint8, device="cuda"); v0 = torch.zeros(cb, dtype=torch.uint8, device="cuda")
     km0 = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm0 = torch.zeros(mb, dtype=torch.uint8, device="cuda")
-    sl0 = torch.full((B,), T0, dtype=torch.int32, device="cuda")
+    sl0 = torch.from_numpy(lens0.astype(np.int32)).cuda()
     cache0 = W.make_cache(k0, v0, km0, vm0, sl0)
     for which, A, plane in (("k", AK, 0), ("v", AV, 1)):
-        lat = np.stack([WI.latents_from_law(sp, A, which, b, T0) for b in range(B)])          # [B,Hkv,T0,r] fp32
-        latd = torch.from_numpy(lat).cuda()
-        codes = torch.empty((B * Hkv * T0, r), dtype=torch.int8, device="cuda")
-        meta = torch.empty(B * Hkv * T0, dtype=torch.int16, device="cuda")
-        W.wsvd_quantize_rows(ctx, desc, latd, B * Hkv * T0, codes, meta)
+        # one sequence at a time: [Hkv,T0,r] fp32 -> the library's quantiser -> this sequence's slice of the logical cache
+        codes = torch.empty((B, Hkv * T0, r // 2 if i4 else r), dtype=torch.uint8, device="cuda")
+        meta = torch.empty((B, Hkv * T0, 2 if i4 else 1), dtype=torch.int16, device="cuda")
+        for b in range(B):
+            latd = torch.from_numpy(WI.latents_from_law(sp, A, which, b, T0)).cuda()
+            W.wsvd_quantize_rows(ctx, desc, latd, Hkv * T0, codes[b], meta[b])
         W.wsvd_cache_import(ctx, desc, plane, codes, meta, 0, T0, cache0)
+        del codes, meta
     assert W.wsvd_check(ctx) == 0
     sets = [(k0, v0, km0, vm0, sl0, cache0)]
     for _ in range(n_sets - 1):
@@ -132,9 +139,9 @@ def main():
         s = sets[i % n_sets]
         W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
 
-    # rows attended at timed step i: T0 + (number of appends that set has seen so far)
+    # rows attended (summed over the batch) at timed step i: initial lengths + the appends that set has seen so far
     def rows_at(i):
-        return T0 + (0 if args.attn_only else i // n_sets + 1)
+        return int(lens0.sum()) + B * (0 if args.attn_only else i // n_sets + 1)
 
     stream = torch.cuda.Stream()
     use_graph = not args.no_graph
@@ -169,7 +176,7 @@ def main():
             t_wall1 = time.perf_counter()
         ms_total = e0.elapsed_time(e1)
         assert W.wsvd_check(ctx, stream) == 0
-        seq_after = [int(s[4][0]) for s in sets]
+        seq_after = [int(s[4].max()) for s in sets]
 
         # ---- dominant kernel alone: decode attention, back-to-back launches, HIP events on the launch stream
         n_attn = max(args.steps, 64)
@@ -200,13 +207,14 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    row_bytes = Hkv * 2 * (r + 2)                         # K and V code rows plus their fp16 scales, all kv heads
-    bytes_steps = sum(B * rows_at(i) * row_bytes for i in range(args.warmup, total_steps))
+    # K and V code rows plus their metadata (int8: fp16 scale; int4: fp16 scale + zero point), all kv heads
+    row_bytes = Hkv * 2 * ((r // 2 + 4) if i4 else (r + 2))
+    bytes_steps = sum(rows_at(i) * row_bytes for i in range(args.warmup, total_steps))
     bytes_per_step = bytes_steps / args.steps
     ms_per_step = ms_total / args.steps
     value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
-    rows_attn = [int(s[4][0]) for s in sets]
-    attn_bytes = sum(B * rows_attn[i % n_sets] * row_bytes for i in range(n_attn)) / n_attn
+    rows_attn = [int(s[4].sum()) for s in sets]
+    attn_bytes = sum(rows_attn[i % n_sets] * row_bytes for i in range(n_attn)) / n_attn
     achieved = attn_bytes / (attn_us * 1e-6) / 1e9
 
     res = {
@@ -222,12 +230,15 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "i8",
+        "dtype": "i4" if i4 else "i8",
         "data": "synthetic",
         "config": {
-            "workload": "c3: batched int8 decode step (append + attention), B=16 H=32 d_head=128 d_model=4096 r=32 T=2048",
+            "workload": ("c4: ragged int4 decode step (append + attention), B=64 H=32 d_head=128 d_model=4096 r=32 T=1024..4096"
+                         if i4 else
+                         "c3: batched int8 decode step (append + attention), B=16 H=32 d_head=128 d_model=4096 r=32 T=2048"),
             "batch": B, "heads": Hq, "d_head": d, "d_model": E, "rank": r, "context": T,
-            "context_drift_rows": max(seq_after) - T,
+            "context_drift_rows": max(seq_after) - int(lens0.max()) - 1,
+            "rows_in_batch": int(lens0.sum()) + B,
             "cache_sets_rotated": n_sets, "cache_set_MB": round(2 * (cb + mb) / 1e6, 1),
             "launch": "hip_graph_replay" if use_graph else "eager",
             "step": "attention only" if args.attn_only else ("wsvd_decode_step (single-launch kernel)" if args.single_launch
@@ -235,19 +246,20 @@ def main():
             "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / args.steps, 6),
         },
         "roofline": {
-            "kernel": "k_attn_mfma<32,1,false> (decode attention over int8 latents)",
+            "kernel": "k_attn_mfma<32,1,%s> (decode attention over %s latents)" % ("true", "int4") if i4 else
+                      "k_attn_mfma<32,1,false> (decode attention over int8 latents)",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic": None if i4 else MEASURED_TRAFFIC_BYTES,
             "algorithmic_bytes_per_launch": int(attn_bytes),
             "avg_launch_us": round(attn_us, 3),
         },
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == "c3":
         res["cpu_baseline"] = cpu_baseline(np, row_bytes)
     print(json.dumps(res))
     W.wsvd_destroy(ctx)

@@ -159,11 +159,25 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
   dim3 grid((unsigned)(p.ES * p.Hkv * 2));
   const bool f32 = d.factor_dtype == WSVD_F32;
   if (append_mfma_path(d)) {
-    dim3 block((unsigned)(wsvd_append_mfma_waves(d) * 64));
+    int nw = wsvd_append_mfma_waves(d);
+    if (d.batch > 32) {
+      // two groups of 32 sequences per pass over the factors; the second set of accumulators needs the register
+      // budget of a workgroup of at most 8 waves
+      if (nw > 8) nw = 8;
+      dim3 block((unsigned)(nw * 64));
+      switch (d.rank) {
+        case 16: hipLaunchKernelGGL((k_append_mfma<16, 512, 2>), grid, block, 0, s, p); break;
+        case 32: hipLaunchKernelGGL((k_append_mfma<32, 512, 2>), grid, block, 0, s, p); break;
+        case 64: hipLaunchKernelGGL((k_append_mfma<64, 512, 2>), grid, block, 0, s, p); break;
+        default: return hipErrorInvalidValue;
+      }
+      return hipGetLastError();
+    }
+    dim3 block((unsigned)(nw * 64));
     switch (d.rank) {
-      case 16: hipLaunchKernelGGL((k_append_mfma<16, 1024>), grid, block, 0, s, p); break;
-      case 32: hipLaunchKernelGGL((k_append_mfma<32, 1024>), grid, block, 0, s, p); break;
-      case 64: hipLaunchKernelGGL((k_append_mfma<64, 512>), grid, block, 0, s, p); break;
+      case 16: hipLaunchKernelGGL((k_append_mfma<16, 1024, 1>), grid, block, 0, s, p); break;
+      case 32: hipLaunchKernelGGL((k_append_mfma<32, 1024, 1>), grid, block, 0, s, p); break;
+      case 64: hipLaunchKernelGGL((k_append_mfma<64, 512, 1>), grid, block, 0, s, p); break;
       default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -228,18 +228,29 @@ WSVD_DEV void append_finish(const AppendParams& p, int pl, int kv, float (*crow)
     for (int b0 = 0; b0 < p.B; b0 += 64) {
       const int nb = min(64, p.B - b0);
       __syncthreads();
-      for (int i = tid; i < nb * R; i += blockDim.x) {
-        const int bb = i / R, jj = i % R;
-        // slices summed in order; loads issued 16 at a time (clamped index, masked) so they overlap
-        float sum = 0.f;
-        for (int k0 = 0; k0 < p.ES; k0 += 16) {
-          float v[16];
+      // Slices are summed in order.  The loads bypass the caches and cost a full round trip each, so every thread
+      // requests its (up to) four elements x 8 slices together (index clamped, surplus masked) instead of one
+      // element per trip.
+      for (int i0 = 0; i0 < nb * R; i0 += 4 * (int)blockDim.x) {
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int k0 = 0; k0 < p.ES; k0 += 8) {
+          float v[4][8];
 #pragma unroll
-          for (int k = 0; k < 16; k++) v[k] = agent_load(pbase + ((size_t)min(k0 + k, p.ES - 1) * p.B + b0 + bb) * R + jj);
+          for (int it = 0; it < 4; it++) {
+            const int i = min(i0 + it * (int)blockDim.x + tid, nb * R - 1);
 #pragma unroll
-          for (int k = 0; k < 16; k++) sum += (k0 + k < p.ES) ? v[k] : 0.f;
+            for (int k = 0; k < 8; k++) v[it][k] = agent_load(pbase + ((size_t)min(k0 + k, p.ES - 1) * p.B + b0) * R + i);
+          }
+#pragma unroll
+          for (int it = 0; it < 4; it++)
+#pragma unroll
+            for (int k = 0; k < 8; k++) sum[it] += (k0 + k < p.ES) ? v[it][k] : 0.f;
         }
-        crow[bb][jj] = sum;
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+          const int i = i0 + it * (int)blockDim.x + tid;
+          if (i < nb * R) crow[i / R][i % R] = sum[it];
+        }
       }
       __syncthreads();
       append_store_rows<R>(p, pl, kv, b0, nb, crow, n_sh);
@@ -266,25 +277,31 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 // walks its part in chunks of 4 k-steps (64 elements), the next chunk's operands in flight while the current one
 // multiplies.  With ES == 1 (one workgroup per plane and kv head, up to 16 waves) there is no cross-workgroup
 // hand-off at all.  Sequence lengths are requested first and land in LDS together with the hidden states.
-template <int R>
+// NG = groups of 32 sequences that share one pass over the factors (1, or 2 for batches above 32: the factor operand
+// is loaded once and multiplied with both groups' hidden states)
+template <int R, int NG>
 struct AppendMfmaShared {
   static constexpr int RW = R <= 32 ? 8 : 4;   // waves reduced per LDS round
-  float red[RW][32][R + 1];                    // [wave in round][sequence in group][channel]
   float crow[64][R + 1];
   int flag_sh;
   int n_sh[kAppendMaxB];
-  // hidden-state slice of up to 32 sequences, row stride = 4 dwords mod 32 banks so that the 16-byte operand reads
-  // of 8 consecutive sequences cover all banks once
-  __attribute__((aligned(16))) uint16_t xs[32][kAppendMfmaESL + 8];
+  // The hidden-state slice and the cross-wave reduction buffer are never live together (a barrier separates the
+  // last operand read from the first partial written, and the last sum from the next slice), so they share storage.
+  union {
+    // hidden-state slice of up to 32 * NG sequences, row stride = 4 dwords mod 32 banks so that the 16-byte operand
+    // reads of 8 consecutive sequences cover all banks once
+    __attribute__((aligned(16))) uint16_t xs[32 * NG][kAppendMfmaESL + 8];
+    float red[RW][32][R + 1];                  // [wave in round][sequence in group][channel]
+  };
 };
 
 // wg = index of the workgroup among the append workgroups of the launch
-template <int R>
-WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R>& sh, int wg) {
+template <int R, int NG>
+WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R, NG>& sh, int wg) {
   constexpr int RT = R / 32;                  // 32-channel row tiles (R = 16 uses half a tile)
   constexpr int RTC = RT > 0 ? RT : 1;
   constexpr int KS = 4;                       // k-steps of 16 per chunk
-  constexpr int RW = AppendMfmaShared<R>::RW;
+  constexpr int RW = AppendMfmaShared<R, NG>::RW;
   constexpr int NLEN = kAppendMaxB / 256;     // sequence lengths per thread (blockDim >= 256)
   auto& red = sh.red;
   auto& crow = sh.crow;
@@ -309,14 +326,18 @@ WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R>& sh, i
   bool lens_done = false;
   int ticket = 0;
 
-  for (int b0 = 0; b0 < p.B; b0 += 32) {
-    const int nb = min(32, p.B - b0);
-    const int xrow = min(col, nb - 1);
-    v16f acc[RTC];
+  for (int b0 = 0; b0 < p.B; b0 += 32 * NG) {
+    const int nb = min(32 * NG, p.B - b0);
+    int xrow[NG];
+    v16f acc[NG][RTC];
 #pragma unroll
-    for (int rt = 0; rt < RTC; rt++)
+    for (int gi = 0; gi < NG; gi++) {
+      xrow[gi] = min(32 * gi + col, nb - 1);
 #pragma unroll
-      for (int v = 0; v < 16; v++) acc[rt][v] = 0.f;
+      for (int rt = 0; rt < RTC; rt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[gi][rt][v] = 0.f;
+    }
     // factor operands of one chunk: unconditional loads (k-step clamped to the wave's last one); the hidden-state
     // operands come from the LDS copy, which the whole workgroup fills with coalesced 16-byte loads
     v8bf aop[2][RTC][KS];
@@ -333,19 +354,33 @@ WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R>& sh, i
 #pragma unroll
       for (int k = 0; k < KS; k++)
         if (c0 + k < ks_n) {
-          const v8bf xo = *(const v8bf*)&xs[xrow][wave * ew + (c0 + k) * 16 + g * 8];
 #pragma unroll
-          for (int rt = 0; rt < RTC; rt++)
-            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[buf][rt][k], xo, acc[rt], 0, 0, 0);
+          for (int gi = 0; gi < NG; gi++) {
+            const v8bf xo = *(const v8bf*)&xs[xrow[gi]][wave * ew + (c0 + k) * 16 + g * 8];
+#pragma unroll
+            for (int rt = 0; rt < RTC; rt++)
+              acc[gi][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[buf][rt][k], xo, acc[gi][rt], 0, 0, 0);
+          }
         }
     };
     load_chunk(0, 0);
     {
       const int ppr = p.ESL >> 3;                       // 16-byte pieces per row
       __syncthreads();                                  // the previous group's operand reads are done
-      for (int i = tid; i < nb * ppr; i += blockDim.x) {
-        const int r = i / ppr, c = i % ppr;
-        *(v4i*)&xs[r][c * 8] = *(const v4i*)(xp + (size_t)(b0 + r) * p.E + s * p.ESL + c * 8);
+      // four pieces per thread and trip, all four loads in flight before the first LDS write (one piece per trip
+      // made every trip a memory round trip of its own)
+      for (int i0 = 0; i0 < nb * ppr; i0 += 4 * (int)blockDim.x) {
+        v4i piece[4];
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+          const int i = min(i0 + it * (int)blockDim.x + tid, nb * ppr - 1);
+          piece[it] = *(const v4i*)(xp + (size_t)(b0 + i / ppr) * p.E + s * p.ESL + (i % ppr) * 8);
+        }
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+          const int i = i0 + it * (int)blockDim.x + tid;
+          if (i < nb * ppr) *(v4i*)&xs[i / ppr][(i % ppr) * 8] = piece[it];
+        }
       }
       if (!lens_done) {
         // the lengths were requested before everything else, so they are here by now
@@ -365,26 +400,31 @@ WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R>& sh, i
       load_chunk(0, c0 + 2 * KS);
       mul_chunk(1, c0 + KS);
     }
-    // cross-wave sum in a fixed order: rounds of RW waves through LDS
-    for (int r0 = 0; r0 < NW; r0 += RW) {
-      __syncthreads();
-      if (wave >= r0 && wave < r0 + RW) {
+    // cross-wave sum in a fixed order: per group of 32 sequences, rounds of RW waves through LDS
 #pragma unroll
-        for (int rt = 0; rt < RTC; rt++)
+    for (int gi = 0; gi < NG; gi++) {
+      const int nbg = min(32, nb - 32 * gi);             // sequences of this group (<= 0: none)
+      if (nbg <= 0) break;
+      for (int r0 = 0; r0 < NW; r0 += RW) {
+        __syncthreads();
+        if (wave >= r0 && wave < r0 + RW) {
 #pragma unroll
-          for (int v = 0; v < 16; v++) {
-            // lane holds sequence column `col`, channel rows 8*(v/4) + 4*g + v%4
-            const int ch = rt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
-            if (ch < R) red[wave - r0][col][ch] = acc[rt][v];
-          }
-      }
-      __syncthreads();
-      const int nr = min(RW, NW - r0);
-      for (int i = tid; i < nb * R; i += blockDim.x) {
-        const int bb = i / R, jj = i % R;
-        float sum = r0 == 0 ? 0.f : crow[bb][jj];
-        for (int k = 0; k < nr; k++) sum += red[k][bb][jj];
-        crow[bb][jj] = sum;
+          for (int rt = 0; rt < RTC; rt++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+              // lane holds sequence column `col`, channel rows 8*(v/4) + 4*g + v%4
+              const int ch = rt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
+              if (ch < R) red[wave - r0][col][ch] = acc[gi][rt][v];
+            }
+        }
+        __syncthreads();
+        const int nr = min(RW, NW - r0);
+        for (int i = tid; i < nbg * R; i += blockDim.x) {
+          const int bb = i / R, jj = i % R;
+          float sum = r0 == 0 ? 0.f : crow[32 * gi + bb][jj];
+          for (int k = 0; k < nr; k++) sum += red[k][bb][jj];
+          crow[32 * gi + bb][jj] = sum;
+        }
       }
     }
     __syncthreads();
@@ -399,9 +439,9 @@ WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R>& sh, i
   else append_bump(p, n_sh, ticket, &flag_sh);
 }
 
-template <int R, int NT>
+template <int R, int NT, int NG>
 __global__ __launch_bounds__(NT) void k_append_mfma(AppendParams p) {
-  __shared__ AppendMfmaShared<R> sh;
-  append_mfma_body<R>(p, sh, blockIdx.x);
+  __shared__ AppendMfmaShared<R, NG> sh;
+  append_mfma_body<R, NG>(p, sh, blockIdx.x);
 }
 

@@ -829,7 +829,7 @@ struct StepParams {
 template <int R, int G, int NT>
 union StepShared {
   AttnMfmaShared<R, G, NT> attn;
-  AppendMfmaShared<R> app;
+  AppendMfmaShared<R, 1> app;
 };
 
 template <int R, int G, bool I4, int NT>
@@ -838,7 +838,7 @@ __global__ __launch_bounds__(NT) void k_decode_step(StepParams sp) {
   __shared__ int last_sh;
   const int id = blockIdx.x;
   if (id < sp.n_append) {
-    append_mfma_body<R>(sp.ap, sh.app, id);
+    append_mfma_body<R, 1>(sp.ap, sh.app, id);
   } else {
     const int r = id - sp.n_append;
     const int kv = r % sp.a.Hkv, r2 = r / sp.a.Hkv;
@@ -881,7 +881,7 @@ hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, cons
                                    const wsvd_cache& cache, int max_seq_len, void* out, hipStream_t s) {
   const bool i8 = d.latent_dtype == WSVD_I8, i4 = d.latent_dtype == WSVD_I4;
   const int G = d.n_q_heads / d.n_kv_heads;
-  if (!(i8 || i4) || G > 4 || !wsvd_append_uses_mfma(d) || d.n_kv_heads > 1024 || d.batch > kAppendMaxB) return hipErrorNotSupported;
+  if (!(i8 || i4) || G > 4 || !wsvd_append_uses_mfma(d) || d.n_kv_heads > 1024 || d.batch > 32) return hipErrorNotSupported;
   if (!((i8 && (d.rank == 32 || d.rank == 64)) || (i4 && d.rank == 32))) return hipErrorNotSupported;
   StepParams sp;
   dim3 grid;

@@ -282,8 +282,10 @@ def _append_compare(L, oc, c64K, c64V, t_rows, dtype):
 
 
 @pytest.mark.parametrize("name,over", [("c1", dict(batch=3, context=70)), ("c2_small", dict()), ("c3_small", dict()),
-                                       ("c4_small", dict()), ("c3_small", dict(rank=64, batch=11))],
-                         ids=["f32", "bf16", "i8", "i4", "i8r64b11"])
+                                       ("c4_small", dict()), ("c3_small", dict(rank=64, batch=11)),
+                                       ("c3_small", dict(batch=40, context=130)), ("c4_small", dict(batch=70, context=200, ragged=(1, 200))),
+                                       ("c3_small", dict(batch=33, rank=64, context=100))],
+                         ids=["f32", "bf16", "i8", "i4", "i8r64b11", "i8b40", "i4b70", "i8r64b33"])
 def test_append_matches_oracle(name, over):
     c = build_case(name, **over)
     sp = c.sp
