@@ -104,8 +104,12 @@ def main():
     # sequence's plane is filled up to the longest length (rows past a sequence's own length are never read).
     lens0 = WI.ragged_lengths(sp).astype(np.int64) - 1
     T0 = int(lens0.max())
-    k0 = torch.zeros(cb, dtype=torch.uint8, device="cuda"); v0 = torch.zeros(cb, dtype=torch.uint8, device="cuda")
-    km0 = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm0 = torch.zeros(mb, dtype=torch.uint8, device="cuda")
+    # a cache set is ONE allocation (K codes, V codes, K metadata, V metadata), so that the streaming-read probe
+    # can run over exactly the bytes the attention streams
+    def carve(buf):
+        return buf[:cb], buf[cb:2 * cb], buf[2 * cb:2 * cb + mb], buf[2 * cb + mb:]
+    buf0 = torch.zeros(2 * cb + 2 * mb, dtype=torch.uint8, device="cuda")
+    k0, v0, km0, vm0 = carve(buf0)
     sl0 = torch.from_numpy(lens0.astype(np.int32)).cuda()
     cache0 = W.make_cache(k0, v0, km0, vm0, sl0)
     for which, A, plane in (("k", AK, 0), ("v", AV, 1)):
@@ -118,10 +122,11 @@ def main():
         W.wsvd_cache_import(ctx, desc, plane, codes, meta, 0, T0, cache0)
         del codes, meta
     assert W.wsvd_check(ctx) == 0
-    sets = [(k0, v0, km0, vm0, sl0, cache0)]
+    sets = [(k0, v0, km0, vm0, sl0, cache0, buf0)]
     for _ in range(n_sets - 1):
-        t = [x.clone() for x in (k0, v0, km0, vm0, sl0)]
-        sets.append((*t, W.make_cache(*t)))
+        b = buf0.clone(); sl = sl0.clone()
+        t = [*carve(b), sl]
+        sets.append((*t, W.make_cache(*t), b))
     outs = [torch.empty((B, Hq, d), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
     torch.cuda.synchronize()
 
@@ -200,6 +205,29 @@ def main():
         attn_us = a0.elapsed_time(a1) * 1e3 / n_attn
         assert W.wsvd_check(ctx, stream) == 0
 
+        # ---- the same launches replaced by a pure reader over the same cache sets (whole allocations, i.e. the
+        # t_cap slack included: a few per cent more bytes than the attention needs)
+        def probe(i):
+            W.wsvd_probe_stream_read(ctx, sets[i % n_sets][6], 2 * cb + 2 * mb, 2 * B * Hkv)
+        for i in range(n_sets):
+            probe(i)
+        stream.synchronize()
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if use_graph:
+            gp = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gp, stream=stream):
+                for i in range(n_attn):
+                    probe(i)
+            stream.synchronize()
+            p0.record(stream); gp.replay(); p1.record(stream)
+        else:
+            p0.record(stream)
+            for i in range(n_attn):
+                probe(i)
+            p1.record(stream)
+        stream.synchronize()
+        probe_us = p0.elapsed_time(p1) * 1e3 / n_attn
+
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -256,6 +284,10 @@ def main():
             "traffic": None if i4 else MEASURED_TRAFFIC_BYTES,
             "algorithmic_bytes_per_launch": int(attn_bytes),
             "avg_launch_us": round(attn_us, 3),
+            # context, not a peak: a kernel that only reads the same cache sets (t_cap slack included), same launch style
+            "stream_read_probe": {"bytes_per_launch": 2 * (cb + mb), "avg_launch_us": round(probe_us, 3),
+                                  "GBps": round(2 * (cb + mb) / (probe_us * 1e-6) / 1e9, 1),
+                                  "attention_time_over_probe_time": round(attn_us / probe_us, 3)},
         },
     }
 

@@ -209,6 +209,13 @@ wsvd_status wsvd_cache_export(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_
                               void *hip_stream);
 
 /*
+ * Measurement aid, not part of the method: a kernel that only READS `bytes` bytes (DEVICE pointer, 16-byte
+ * aligned) with `workgroups` workgroups of 512 threads, each streaming one contiguous share.  Benchmarks run it
+ * over the buffers the attention streams to report what a pure reader reaches on the same data.
+ */
+wsvd_status wsvd_probe_stream_read(wsvd_ctx *ctx, const void *ptr, size_t bytes, int32_t workgroups, void *hip_stream);
+
+/*
  * Per-token symmetric int8 quantisation of activation rows (Section 4.2), same rounding rules as the
  * I8 latent quantiser with one scale per row of `cols` channels.
  *   x [rows, cols] of x_dtype (F32 or BF16) -> codes int8 [rows, cols], scale fp16 [rows].

@@ -26,7 +26,7 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
            "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
-           "wsvd_linear_w4a8_split"]
+           "wsvd_linear_w4a8_split", "wsvd_probe_stream_read"]
 
 
 class WsvdError(RuntimeError):
@@ -86,6 +86,7 @@ def lib():
                                        c_void_p, c_int32, c_void_p]
         L.wsvd_linear_w4a8_split.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
                                              c_int64, c_void_p, c_void_p, c_int32, c_void_p]
+        L.wsvd_probe_stream_read.argtypes = [c_void_p, c_void_p, c_size_t, c_int32, c_void_p]
         for name in EXPORTS:
             if name not in ("wsvd_status_str",):
                 getattr(L, name).restype = c_int
@@ -229,3 +230,7 @@ def wsvd_linear_w4a8_split(ctx, x, x_scale, w_i4, w_scale, M, K, N, n_first, out
     _ck(lib().wsvd_linear_w4a8_split(ctx, _ptr(x), _ptr(x_scale), _ptr(w_i4), _ptr(w_scale), int(M), int(K), int(N),
                                      int(n_first), _ptr(out_first), _ptr(out_rest), F32, _stream(stream)),
         "wsvd_linear_w4a8_split")
+
+
+def wsvd_probe_stream_read(ctx, buf, nbytes, workgroups, stream=None):
+    _ck(lib().wsvd_probe_stream_read(ctx, _ptr(buf), int(nbytes), int(workgroups), _stream(stream)), "wsvd_probe_stream_read")

@@ -316,6 +316,14 @@ wsvd_status wsvd_cache_export(wsvd_ctx* ctx, const wsvd_layer_desc* desc, int32_
   return cache_copy(false, ctx, desc, which_plane, codes, meta, t0, n_rows, cache, hip_stream);
 }
 
+wsvd_status wsvd_probe_stream_read(wsvd_ctx* ctx, const void* ptr, size_t bytes, int32_t workgroups, void* hip_stream) {
+  if (!ctx || !ptr) return WSVD_E_NULL;
+  if (!aligned16(ptr)) return WSVD_E_ALIGN;
+  if (bytes < 16 || workgroups < 1 || workgroups > (1 << 20)) return WSVD_E_SHAPE;
+  hipError_t e = wsvd_launch_stream_read(ptr, bytes, workgroups, nullptr, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_quantize_act_i8(wsvd_ctx* ctx, const void* x, int32_t x_dtype, int64_t rows, int64_t cols, int8_t* codes,
                                  void* scale_f16, void* hip_stream) {
   if (!ctx || !x || !codes || !scale_f16) return WSVD_E_NULL;

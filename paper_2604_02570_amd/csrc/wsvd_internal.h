@@ -21,6 +21,7 @@ hipError_t wsvd_launch_quantize_rows(int latent_dtype, int rank, const float* c,
                                      hipStream_t s);
 hipError_t wsvd_launch_cache_copy(bool to_device, const wsvd_layer_desc& d, int plane, void* logical_codes,
                                   void* logical_meta, int t0, int n_rows, void* dev_codes, void* dev_meta, hipStream_t s);
+hipError_t wsvd_launch_stream_read(const void* ptr, size_t bytes, int workgroups, int* sink, hipStream_t s);
 hipError_t wsvd_launch_quantize_act_i8(const void* x, int x_dtype, int64_t rows, int64_t cols, int8_t* codes,
                                        void* scale_f16, hipStream_t s);
 hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,

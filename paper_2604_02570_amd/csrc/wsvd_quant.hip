@@ -272,3 +272,31 @@ hipError_t wsvd_launch_cache_copy(bool to_device, const wsvd_layer_desc& d, int 
   }
   return e;
 }
+
+// ---------------------------------------------------------------- streaming-read probe (measurement aid)
+// What the memory system gives a kernel that does nothing but read: each workgroup streams one contiguous share of
+// the buffer with 16-byte loads, four per thread in flight, and folds the data into a value that is (practically)
+// never stored.  Benchmarks run it over the very buffers the attention streams, to put the attention's bytes per
+// second next to the rate a pure reader reaches on the same data, launch for launch.
+__global__ __launch_bounds__(512) void k_stream_read(const v4i* __restrict__ base, size_t n16, int* __restrict__ sink) {
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = (size_t)blockIdx.x * per, hi = lo + per < n16 ? lo + per : n16;
+  int acc = 0;
+  for (size_t i = lo + threadIdx.x; i < hi; i += 4 * 512) {
+    v4i v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const size_t j = i + (size_t)u * 512;
+      v[u] = __builtin_nontemporal_load(base + (j < hi ? j : hi - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+  }
+  if (acc == 0x5A17C0DE && sink) *sink = acc;
+}
+
+hipError_t wsvd_launch_stream_read(const void* ptr, size_t bytes, int workgroups, int* sink, hipStream_t s) {
+  if (bytes < 16 || workgroups < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_stream_read, dim3((unsigned)workgroups), dim3(512), 0, s, (const v4i*)ptr, bytes / 16, sink);
+  return hipGetLastError();
+}
