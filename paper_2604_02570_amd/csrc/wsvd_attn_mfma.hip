@@ -107,7 +107,7 @@ struct AttnMfmaShared {
   float qdelta[G], qzsum[G];
   __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
   float wm[NWMAX][G], wls[NWMAX][G];
-  float wu[NWMAX][G][R];
+  __attribute__((aligned(16))) float wu[NWMAX][G][R];
   float wo[NWMAX][G][128];                                  // per wave: its accumulator times B_V
   float Msh[G], Lsh[G], Ush[G * R];
   int flag_sh;
@@ -400,12 +400,15 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
 #pragma unroll
       for (int g = 0; g < G; g++) {
         float o0 = 0.f, o1 = 0.f;
-#pragma unroll 8
-        for (int j = 0; j < R; j++) {
-          const float uj = wu[wave][g][j];
-          const uint32_t bb = bv32[j * half_d + lane];
-          o0 = fmaf(uj, __uint_as_float(bb << 16), o0);
-          o1 = fmaf(uj, __uint_as_float(bb & 0xFFFF0000u), o1);
+#pragma unroll
+        for (int j4 = 0; j4 < R; j4 += 4) {
+          const v4f u4 = *(const v4f*)&wu[wave][g][j4];          // same address in every lane: one broadcast read
+#pragma unroll
+          for (int jj = 0; jj < 4; jj++) {
+            const uint32_t bb = bv32[(j4 + jj) * half_d + lane];
+            o0 = fmaf(u4[jj], __uint_as_float(bb << 16), o0);
+            o1 = fmaf(u4[jj], __uint_as_float(bb & 0xFFFF0000u), o1);
+          }
         }
         wo[wave][g][2 * lane] = o0;
         wo[wave][g][2 * lane + 1] = o1;
