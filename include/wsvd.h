@@ -149,7 +149,9 @@ wsvd_status wsvd_latent_store(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const 
  * out = u B_V (associativity only).
  *   q [B,Hq,d_head] of q_dtype; q_scale fp16 [B] iff q_dtype == I8 (buffer padded to a multiple of 4 bytes)
  *   B_K,B_V [Hkv, rank, d_head] of factor_dtype;  out [B,Hq,d_head] F32
- *   max_seq_len: HOST upper bound on seq_lens (sizes the grid); must be <= t_cap.
+ *   max_seq_len: HOST upper bound on seq_lens (sizes the grid); must be <= t_cap.  A sequence found to be longer
+ *                than the rows the grid covers (max_seq_len rounded up to whole chunks) sets the device status word
+ *                to WSVD_E_SHAPE (wsvd_check); its output is then computed from the covered rows only.
  */
 wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
                              const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,

@@ -374,6 +374,7 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   p.out = (float*)out;
   p.tickets = (int*)ctx->ws;
   p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
+  p.err_word = ctx->err_word;
   p.B = d.batch; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.d = d.d_head;
   p.t_cap = d.t_cap;
   p.q_dtype = d.q_dtype; p.factor_dtype = d.factor_dtype;

@@ -21,11 +21,11 @@ struct AttnParams {
   int n_chunks;              // grid extent along the context
   int q_dtype, factor_dtype;
   float c_scale;             // sm_scale * log2(e): scores live in the log2 domain
+  int* err_word;             // device status word of the context
   // fused decode step only: the append workgroups of the same launch publish row seq_lens[b] of kv head h's K / V
   // plane by setting flags[h] / flags[Hkv + h] to epoch
   const int* flags;
   int epoch;
-  int* err_word;
 };
 
 struct WorkItem {
@@ -46,6 +46,8 @@ WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw, int kv, int chunk,
   w.row_begin = w.chunk * p.chunk_rows;
   w.row_end = min(w.n, w.row_begin + p.chunk_rows);
   w.active = w.chunk < w.n_splits;
+  // a sequence longer than the caller's bound: the grid does not cover its tail.  Reported, never silently truncated.
+  if (w.n > p.n_chunks * p.chunk_rows && chunk == 0 && threadIdx.x == 0) atomicExch(p.err_word, (int)WSVD_E_SHAPE);
   return w;
 }
 WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) { return decode_work(p, n_raw, blockIdx.x, blockIdx.y, blockIdx.z); }

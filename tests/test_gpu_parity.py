@@ -235,6 +235,19 @@ def test_attention_independent_of_split_count(dtype):
     L.close()
 
 
+def test_attention_reports_a_too_small_length_bound():
+    """max_seq_len is the caller's promise; a longer sequence must be reported, not silently truncated."""
+    c = build_case("c3_small", context=900)
+    L = layer_for(c); L.upload(c.cache)
+    qd, qs, q64 = q_to_device(c.q32[0], c.sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    W.wsvd_decode_attn(L.ctx, L.desc, qd, qs, BKd, BVd, L.cache, 200, L.out)      # 900 rows, bound 200
+    assert W.wsvd_check(L.ctx) == W.E_SHAPE
+    W.wsvd_decode_attn(L.ctx, L.desc, qd, qs, BKd, BVd, L.cache, 900, L.out)      # honest bound: clean again
+    assert W.wsvd_check(L.ctx) == 0
+    L.close()
+
+
 def test_large_scores_stay_finite():
     c = build_case("c3_small", q_dtype="f32")
     c.q32 = c.q32 * 200.0
