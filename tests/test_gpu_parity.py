@@ -248,6 +248,52 @@ def test_attention_reports_a_too_small_length_bound():
     L.close()
 
 
+@pytest.mark.parametrize("name,over", [("c3_small", dict(context=2000, batch=4)), ("c5_small", dict(context=2000)),
+                                       ("c4_small", dict(batch=6, context=1800, ragged=(900, 1800)))],
+                         ids=["i8", "i8-gqa7", "i4-ragged"])
+def test_cross_workgroup_handoffs_are_repeatable(name, over):
+    """Split merges and the append's slice hand-off go through tickets and write-through stores; a hand-off that is
+    not properly ordered shows up as a result that changes from launch to launch.  40 launches each, bit-identical."""
+    c = build_case(name, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    n_max = int(c.cache.seq_lens.max())
+    try:
+        W.wsvd_set_option("min_chunk", 256)
+        W.wsvd_set_option("max_threads", 256)          # many small chunks per sequence
+        first = None
+        for it in range(40):
+            got = L.attend(qd, qs, BKd, BVd, n_max)
+            if first is None:
+                first = got
+                ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+                check_out(got, ref, sp.latent_dtype, f"repeatable {name}")
+            assert (got == first).all(), f"launch {it} differs from launch 0"
+    finally:
+        W.wsvd_set_option("max_threads", 0)
+    if sp.n_q_heads // sp.n_kv_heads > 4:
+        L.close()
+        return
+    # the append, 30 times from the same state: identical rows every time
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    x = as_dtype_dev(WI.bf16_exact(c.x_new[0]), "bf16")
+    lens = c.cache.seq_lens.copy()
+    rows0 = None
+    for it in range(30):
+        L.seq_lens.copy_(torch.from_numpy(lens.astype(np.int32)))
+        assert L.append(x, None, AKd, AVd) == 0
+        rows = []
+        for plane in (0, 1):
+            gc, gs, gz = L.download(plane, int(lens.min()), int(lens.max() - lens.min()) + 1)
+            rows += [gc.copy(), gs.copy()] + ([gz.copy()] if gz is not None else [])
+        if rows0 is None:
+            rows0 = rows
+        assert all((a == b).all() for a, b in zip(rows, rows0)), f"append {it} differs from append 0"
+    L.close()
+
+
 def test_large_scores_stay_finite():
     c = build_case("c3_small", q_dtype="f32")
     c.q32 = c.q32 * 200.0
