@@ -46,6 +46,7 @@ __all__ = [
     "quantize_int4_rows", "dequantize_int4_rows", "pack_int4", "unpack_int4",
     "LatentCache", "project_latents", "latent_append",
     "dequant_cache_rows", "decode_attn_reconstructed", "decode_attn_absorbed",
+    "rope_inv_freq", "rope_rotate", "decode_attn_rope_reconstructed",
     "softmax_weights",
     "traffic_ratio", "param_ratio_rho1", "cache_ratio_rho2", "cache_row_bytes",
     "latent_cache_bytes",
@@ -306,6 +307,48 @@ def decode_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndar
         s = sm_scale * (K @ q64[b, h])                               # [n]
         p = softmax_weights(s)
         out[b, h] = p @ V
+    return out
+
+
+def rope_inv_freq(d_head: int, base: float) -> np.ndarray:
+    """Rotary frequencies theta_i = base^(-2i/d), i < d/2 (fp64)."""
+    i = np.arange(d_head // 2, dtype=np.float64)
+    return np.float64(base) ** (-2.0 * i / d_head)
+
+
+def rope_rotate(x64: np.ndarray, pos, base: float) -> np.ndarray:
+    """Rotary position embedding in the "rotate-half" pairing: dims (i, i + d/2) form a plane that is turned by the
+    angle pos * theta_i:  y_i = x_i cos - x_{i+d/2} sin,  y_{i+d/2} = x_{i+d/2} cos + x_i sin.
+    x64 [..., d]; pos broadcastable to x64.shape[:-1]."""
+    x = np.asarray(x64, np.float64)
+    d = x.shape[-1]
+    ang = np.asarray(pos, np.float64)[..., None] * rope_inv_freq(d, base)      # [..., d/2]
+    c, s = np.cos(ang), np.sin(ang)
+    lo, hi = x[..., : d // 2], x[..., d // 2:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def decode_attn_rope_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndarray, BV64: np.ndarray,
+                                   sm_scale: float, rope_base: float, heads=None, pos_offset: float = 0.0) -> np.ndarray:
+    """The kernel of Section 3.4 taken literally, for a backbone with rotary position embedding: the key tile
+    K = C_K B_K is formed, each key is rotated by its position (its row index), the query by the position of the
+    newest row (seq_lens[b] - 1), then o = softmax(sm_scale * q_rot K_rot^T) V with V = C_V B_V.
+    With a rotation between the reconstruction and the product, B_K can no longer be folded into the query.
+    ``pos_offset`` shifts every position by the same amount (the result must not depend on it)."""
+    B, Hq, d, Hkv, G = _heads(q64, BK64)
+    out = np.full((B, Hq, d), np.nan) if heads is not None else np.zeros((B, Hq, d))
+    pairs = heads if heads is not None else [(b, h) for b in range(B) for h in range(Hq)]
+    for (b, h) in pairs:
+        n = int(cache.seq_lens[b]); kv = h // G
+        if n == 0:
+            out[b, h] = 0.0
+            continue
+        K = dequant_cache_rows(cache, "k", b, kv, n) @ BK64[kv]                  # [n,d]
+        V = dequant_cache_rows(cache, "v", b, kv, n) @ BV64[kv]
+        K_rot = rope_rotate(K, np.arange(n, dtype=np.float64) + pos_offset, rope_base)
+        q_rot = rope_rotate(q64[b, h], np.float64(n - 1) + pos_offset, rope_base)
+        s = sm_scale * (K_rot @ q_rot)
+        out[b, h] = softmax_weights(s) @ V
     return out
 
 

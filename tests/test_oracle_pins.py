@@ -346,3 +346,79 @@ def test_attention_block_w4a8_consistency():
     q32 = res["q"].astype(np.float32).astype(np.float64)
     np.testing.assert_allclose(res["attn"], O.decode_attn_absorbed(cache, q32, BK, BV, d ** -0.5), rtol=1e-10, atol=1e-12)
     np.testing.assert_allclose(res["y"], O.linear_w4a8(res["o_codes"], res["o_scale"], wo, wos), rtol=0)
+
+
+# ---- rotary variant (reconstruct, rotate, then q K^T) ---------------------------------------
+def test_rope_rotation_is_the_textbook_one():
+    """Pairs (i, i + d/2) as complex numbers multiplied by exp(i pos theta_i): an independent formulation."""
+    rng = np.random.default_rng(40)
+    d, base = 16, 10000.0
+    x = rng.standard_normal((5, 7, d)); pos = rng.integers(0, 5000, (5, 7)).astype(np.float64)
+    got = O.rope_rotate(x, pos, base)
+    theta = np.array([base ** (-2.0 * i / d) for i in range(d // 2)])
+    z = (x[..., : d // 2] + 1j * x[..., d // 2:]) * np.exp(1j * pos[..., None] * theta)
+    np.testing.assert_allclose(got, np.concatenate([z.real, z.imag], -1), rtol=1e-12, atol=1e-12)
+    # d = 2: one plane, a plain 2x2 rotation by the angle pos (theta_0 = 1)
+    v = np.array([3.0, -1.5]); a = 0.7
+    np.testing.assert_allclose(O.rope_rotate(v, a, 123.0), [v[0] * np.cos(a) - v[1] * np.sin(a), v[1] * np.cos(a) + v[0] * np.sin(a)], atol=1e-15)
+    assert np.allclose(O.rope_inv_freq(8, 10000.0), [1.0, 0.1, 0.01, 0.001])
+
+
+def test_rope_rotation_invariants():
+    rng = np.random.default_rng(41)
+    d, base = 32, 10000.0
+    x = rng.standard_normal((9, d)); y = rng.standard_normal((9, d))
+    np.testing.assert_array_equal(O.rope_rotate(x, 0.0, base), x)                                     # position 0: identity
+    np.testing.assert_allclose(np.linalg.norm(O.rope_rotate(x, 77.0, base), axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-13)
+    np.testing.assert_allclose(O.rope_rotate(O.rope_rotate(x, 5.0, base), 11.0, base), O.rope_rotate(x, 16.0, base), atol=1e-12)
+    # the product of a rotated query and a rotated key depends on the difference of their positions only
+    a = np.sum(O.rope_rotate(x, 100.0, base) * O.rope_rotate(y, 37.0, base), -1)
+    b = np.sum(O.rope_rotate(x, 63.0, base) * y, -1)
+    c = np.sum(x * O.rope_rotate(y, -63.0, base), -1)
+    np.testing.assert_allclose(a, b, atol=1e-11); np.testing.assert_allclose(a, c, atol=1e-11)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "i8"])
+def test_rope_attention_against_torch_and_its_invariants(dtype):
+    rng = np.random.default_rng(42)
+    B, Hkv, G, n, r, d, base = 2, 2, 3, 37, 8, 16, 10000.0
+    cache = _rand_cache(rng, B, Hkv, n, r, dtype)
+    cache.seq_lens[1] = 20
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    q = rng.standard_normal((B, Hkv * G, d))
+    got = O.decode_attn_rope_reconstructed(cache, q, BK, BV, 0.3, base)
+    # K, V formed and rotated with torch / complex arithmetic, attention by torch
+    theta = torch.tensor([base ** (-2.0 * i / d) for i in range(d // 2)], dtype=torch.float64)
+    def rot(x, pos):
+        z = torch.complex(x[..., : d // 2], x[..., d // 2:]) * torch.polar(torch.ones_like(pos[..., None] * theta), pos[..., None] * theta)
+        return torch.cat([z.real, z.imag], -1)
+    for b in range(B):
+        nb = int(cache.seq_lens[b])
+        for h in range(Hkv * G):
+            kv = h // G
+            CK = torch.from_numpy(O.dequant_cache_rows(cache, "k", b, kv, nb)); CV = torch.from_numpy(O.dequant_cache_rows(cache, "v", b, kv, nb))
+            K = rot(CK @ torch.from_numpy(BK[kv]), torch.arange(nb, dtype=torch.float64))
+            V = CV @ torch.from_numpy(BV[kv])
+            qr = rot(torch.from_numpy(q[b, h]), torch.tensor(float(nb - 1), dtype=torch.float64))
+            ref = torch.nn.functional.scaled_dot_product_attention(qr[None, None, None, :], K[None, None], V[None, None], scale=0.3)[0, 0, 0].numpy()
+            np.testing.assert_allclose(got[b, h], ref, rtol=1e-11, atol=1e-12)
+    # shifting every position by the same amount changes nothing
+    np.testing.assert_allclose(O.decode_attn_rope_reconstructed(cache, q, BK, BV, 0.3, base, pos_offset=1234.0), got, atol=1e-10)
+    # it is NOT the unrotated attention (the rotation matters) ...
+    assert np.abs(got - O.decode_attn_reconstructed(cache, q, BK, BV, 0.3)).max() > 1e-3
+    # ... except for a single cached token, whose output is its value row whatever the rotation
+    one = _rand_cache(rng, 1, Hkv, 1, r, dtype)
+    np.testing.assert_allclose(O.decode_attn_rope_reconstructed(one, q[:1], BK, BV, 0.3, base),
+                               O.decode_attn_reconstructed(one, q[:1], BK, BV, 0.3), atol=1e-13)
+    # the regrouping the GPU kernel uses: s_t = sum_i cos(phi_i) A_i(t) + sin(phi_i) B_i(t), phi_i = theta_i (n-1-t),
+    # A_i = q_i k_i + q_i' k_i', B_i = q_i k_i' - q_i' k_i  (i' = i + d/2): checked here against the definition
+    b, h, kv = 0, 4, 4 // G
+    nb = int(cache.seq_lens[b])
+    K = O.dequant_cache_rows(cache, "k", b, kv, nb) @ BK[kv]
+    th = O.rope_inv_freq(d, base); half = d // 2
+    Ai = q[b, h, :half] * K[:, :half] + q[b, h, half:] * K[:, half:]
+    Bi = q[b, h, :half] * K[:, half:] - q[b, h, half:] * K[:, :half]
+    phi = (nb - 1 - np.arange(nb))[:, None] * th
+    s_regrouped = (np.cos(phi) * Ai + np.sin(phi) * Bi).sum(-1)
+    s_def = O.rope_rotate(K, np.arange(nb), base) @ O.rope_rotate(q[b, h], nb - 1, base)
+    np.testing.assert_allclose(s_regrouped, s_def, atol=1e-11)
