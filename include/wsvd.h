@@ -167,6 +167,20 @@ wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const v
 wsvd_status wsvd_set_option(const char *name, int value);
 
 /*
+ * Decode attention for a backbone with rotary position embedding: the kernel of Section 3.4 taken literally.
+ * The key tile K = C_K B_K is formed on chip, key t is rotated by its position t (its row index), the query by the
+ * position of the newest row, seq_lens[b] - 1, and the rotated product q_rot . K_rot[t] replaces q . K[t]; everything
+ * else is wsvd_decode_attn.  Rotation: dims (i, i + d_head/2) form a plane turned by position * theta_i with
+ * theta_i = rope_base^(-2i/d_head) ("rotate-half" pairing).  With the rotation between the reconstruction and the
+ * product, B_K cannot be folded into the query, so every cached row costs 2 * rank * d_head flops per query head.
+ * Supported: I8 latents, bf16 factors, rank 32 with up to 4 query heads per kv head or rank 64 with up to 2;
+ * WSVD_E_UNSUPPORTED otherwise.  rope_base > 1 (10000 is the usual value).
+ */
+wsvd_status wsvd_decode_attn_rope(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
+                                  const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,
+                                  float rope_base, void *out, void *hip_stream);
+
+/*
  * One decode step of a layer (Section 3.4, decoding pipeline): wsvd_latent_append followed by wsvd_decode_attn,
  * with the same arguments and the same results (the attention includes the row just appended).  By default the
  * two kernels are launched back to back.  A single-launch kernel exists for I8 / I4 latents with bf16 hidden

@@ -186,6 +186,26 @@ wsvd_status wsvd_latent_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_decode_attn_rope(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
+                                  const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len,
+                                  float rope_base, void* out, void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 0 || !(rope_base > 1.0f)) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  hipError_t e = wsvd_launch_attn_rope(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, (double)rope_base, out,
+                                       (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_latent_store(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const float* c_K, const float* c_V, int64_t ld,
                               wsvd_cache* cache, void* hip_stream) {
   if (!ctx || !c_K || !c_V) return WSVD_E_NULL;

@@ -113,12 +113,52 @@ struct AttnMfmaShared {
   int flag_sh;
 };
 
+// ---- rotary variant (reconstruct, rotate, then q K^T): extra state
+// With a position rotation between K = C B_K and q K^T the factor cannot be folded into the query.  Regrouping
+// the rotated product by frequency gives, for query position n-1 and key position t (i' = i + d/2):
+//   s_t = sum_i cos(theta_i (n-1-t)) A_i(t) + sin(theta_i (n-1-t)) B_i(t),
+//   A_i = q_i k_i + q_i' k_i',  B_i = q_i k_i' - q_i' k_i,   k = B_K^T c_t,
+// and A_i, B_i are linear in the latent: [A; B](t) = N^T c_t with N (r x d) built once per (sequence, head) from
+// q and B_K.  So the key tile is still "reconstructed" on the matrix cores, d outputs per token, straight from the
+// int8 stream (N carried as three 7-bit limbs, exact int32 products), and what is left per token is a dot product
+// with its d position features, which each lane advances from block to block by a fixed rotation.
+// Row layout of the N^T operand: a 32-row MFMA block gives each half of the wave 16 rows = 5 features x 3 limbs
+// (row 8(k/4) + 4h + k%4 <-> register k, feature k/3, limb k%3); half h owns the frequencies [h d/4, (h+1) d/4),
+// feature u of a half = frequency u/2, cosine (even u) or sine (odd u) term.
+template <int D>
+struct RopeGeom {
+  static constexpr int NFH = D / 4;                 // frequencies per half wave
+  static constexpr int NU = 2 * NFH;                // features per half wave
+  static constexpr int NMB = (NU + 4) / 5;          // 32-row operand blocks
+};
+template <int R, int G, int D>
+struct RopeShared {
+  __attribute__((aligned(16))) uint8_t img[G][RopeGeom<D>::NMB][R / 32][1024];   // N^T limbs as MFMA A operands
+  float rot[2][D / 2][2];                           // cos, sin of theta_i * shift for the two block-to-block shifts
+  float gmax[16][G];
+};
+struct RopeArgs {
+  uint32_t fq[64];                                  // theta_i / 2 pi as a 32-bit binary fraction of a revolution
+};
+
+// cos, sin of the angle `phase` (binary fraction of a revolution: the wrap-around of 32-bit arithmetic is the
+// reduction mod 2 pi, exact)
+WSVD_DEV void phase_sincos(uint32_t phase, float& c, float& s) {
+  const float x = (float)(int32_t)phase * (1.0f / 2147483648.0f);   // in [-1, 1): the angle in units of pi
+  sincospif(x, &s, &c);
+}
+
 // One workgroup's share of the decode attention: kv head cx, context chunk cy, sequence cz.
 // FUSED: the workgroup is part of a decode-step launch whose append workgroups are writing row seq_lens[b] at this
 // very moment.  The row counts as present; the 64-row tile that contains it is kept out of the streaming loop and
 // done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
-template <int R, int G, bool I4, int NT, bool FUSED>
-WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, const int cx, const int cy, const int cz) {
+// ROPE_D != 0: the rotary variant for head dimension ROPE_D (I8 latents; rs, ra non-null).
+template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0>
+WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, const int cx, const int cy, const int cz,
+                             RopeShared<R, G, (ROPE_D ? ROPE_D : 64)>* rs = nullptr, const RopeArgs* ra = nullptr) {
+  constexpr bool ROPE = ROPE_D != 0;
+  using RG = RopeGeom<(ROPE_D ? ROPE_D : 64)>;
+  static_assert(!ROPE || (!I4 && !FUSED), "rotary variant: int8 latents, stand-alone launch");
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
@@ -166,6 +206,60 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   stage_commit<FIT>(stv, bv_lds, fac16);
   q_commit(p, qr, 1.f, q_lds);          // an int8 query's scale is applied to delta below
   __syncthreads();
+  if constexpr (ROPE) {
+    constexpr int Dh = ROPE_D / 2;
+    // operand images start out zero (unused rows and features must contribute nothing)
+    for (int i = tid; i < (int)(sizeof(rs->img) / 16); i += blockDim.x) ((v4i*)rs->img)[i] = v4i{0, 0, 0, 0};
+    // block-to-block rotations: +32 tokens (second block of a tile), then on to the wave's next tile
+    if (tid < 2 * Dh) {
+      const int sft = tid / Dh ? 64 * NW - 32 : 32, i = tid % Dh;
+      float c, sn;
+      phase_sincos(ra->fq[i] * (uint32_t)sft, c, sn);
+      rs->rot[tid / Dh][i][0] = c; rs->rot[tid / Dh][i][1] = sn;
+    }
+    // N (r x d per query head): entry (j, f), f = type * d/2 + i; pass 1 finds the largest magnitude per head
+    const uint16_t* bk16 = (const uint16_t*)bk_lds;
+    auto n_entry = [&](int g, int j, int f) {
+      const int i = f % Dh, type = f / Dh;
+      const float qi = q_lds[g * ROPE_D + i], qj = q_lds[g * ROPE_D + i + Dh];
+      const float bi = bf16_to_f32(bk16[j * ROPE_D + i]), bj = bf16_to_f32(bk16[j * ROPE_D + i + Dh]);
+      return p.c_scale * (type == 0 ? fmaf(qi, bi, qj * bj) : fmaf(qi, bj, -(qj * bi)));
+    };
+    float mx[G];
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+      mx[g] = 0.f;
+      for (int e = tid; e < R * ROPE_D; e += blockDim.x) mx[g] = fmaxf(mx[g], fabsf(n_entry(g, e / ROPE_D, e % ROPE_D)));
+      mx[g] = wave_max(mx[g]);
+      if (lane == 0) rs->gmax[wave][g] = mx[g];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+      float amax = rs->gmax[0][g];
+      for (int k = 1; k < NW; k++) amax = fmaxf(amax, rs->gmax[k][g]);
+      const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
+      if (tid == 0) qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f;
+      for (int e = tid; e < R * ROPE_D; e += blockDim.x) {
+        const int j = e / ROPE_D, f = e % ROPE_D;
+        const int Q = (int)__builtin_rintf(n_entry(g, j, f) * inv);
+        const int l0 = ((Q + 64) & 127) - 64;
+        const int Q1 = (Q - l0) >> 7;
+        const int l1 = ((Q1 + 64) & 127) - 64;
+        const int l2 = (Q1 - l1) >> 7;
+        const int i = f % Dh, type = f / Dh;
+        const int hh = i / RG::NFH, uu = 2 * (i % RG::NFH) + type;        // half, feature within the half
+        const int mb = uu / 5, k0 = 3 * (uu % 5);
+        uint8_t* base = &rs->img[g][mb][j >> 5][(((j & 31) >> 4) * 32) * 16 + (j & 15)];
+        const int limbs[3] = {l2, l1, l0};
+#pragma unroll
+        for (int l = 0; l < 3; l++) {
+          const int k = k0 + l;
+          base[(8 * (k >> 2) + 4 * hh + (k & 3)) * 16] = (uint8_t)(int8_t)limbs[l];
+        }
+      }
+    }
+  } else {
   compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   if (tid < G * R) {
     const int g = tid / R, j = tid % R;
@@ -190,12 +284,13 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     const float zs = (R == 64) ? wave_sum((float)Q) : half_sum((float)Q, lane);
     if (j == 0) { qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f; qzsum[g] = zs; }
   }
+  }
   __syncthreads();
 
   // A operands of the score MFMAs.  Row i of A: query slot a = i/8, row group (i/4)%2, limb i%4 (limb 3 unused).
   // a1 feeds block 0 of a tile (rows of group 0 only), a2 feeds block 1 (rows of group 1 only).
   v4i a1[KK], a2[KK];
-  {
+  if constexpr (!ROPE) {
     const int i = lane & 31, g2 = lane >> 5;
     const int a = i >> 3, grp = (i >> 2) & 1, limb = i & 3;
     const bool act = (a < G) && (limb < 3);
@@ -218,7 +313,29 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   const int tile_end = ((w.row_end + 63) >> 6) - (own_new ? 1 : 0);
   float delta[G], zsum[G];
 #pragma unroll
-  for (int g = 0; g < G; g++) { delta[g] = qdelta[g] * qs; zsum[g] = qzsum[g]; }
+  for (int g = 0; g < G; g++) { delta[g] = qdelta[g] * qs; zsum[g] = I4 ? qzsum[g] : 0.f; }
+
+  // rotary variant: this lane's position features (its token of the current block, the frequencies of its half)
+  float fc[ROPE ? RG::NFH : 1], fs[ROPE ? RG::NFH : 1];
+  if constexpr (ROPE) {
+    const int hf = lane >> 5;
+    const uint32_t dist = (uint32_t)(n_raw - 1 - (T * 64 + (lane & 31)));   // query position minus key position
+#pragma unroll
+    for (int i = 0; i < RG::NFH; i++) phase_sincos(ra->fq[hf * RG::NFH + i] * dist, fc[i], fs[i]);
+  }
+  // advance the features by one of the two block-to-block shifts: the distance shrinks, so the angle turns back
+  auto rope_advance = [&](int which) {
+    if constexpr (ROPE) {
+      const int hf = lane >> 5;
+#pragma unroll
+      for (int i = 0; i < RG::NFH; i += 2) {
+        const v4f r4 = *(const v4f*)&rs->rot[which][hf * RG::NFH + i][0];    // (cos, sin) of two frequencies
+        const float c0 = fc[i], s0 = fs[i], c1 = fc[i + 1], s1 = fs[i + 1];
+        fc[i] = fmaf(c0, r4[0], s0 * r4[1]);      fs[i] = fmaf(s0, r4[0], -(c0 * r4[1]));
+        fc[i + 1] = fmaf(c1, r4[2], s1 * r4[3]);  fs[i + 1] = fmaf(s1, r4[2], -(c1 * r4[3]));
+      }
+    }
+  };
 
   // running state: m (log2-domain reference), wref (fixed-point range of the value weights), their derived
   // omega = wref / 2^20 and winv = 2^20 / wref; lsum, zacc, u are per-lane partial sums
@@ -266,6 +383,9 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       acc = mfma_i8(a2[0], s1, acc);
       ksc = f16_bits_to_f32((uint16_t)(t.kmeta & 0xFFFF)); kz = f16_bits_to_f32((uint16_t)(t.kmeta >> 16));
       vsc = f16_bits_to_f32((uint16_t)(t.vmeta & 0xFFFF)); vz = f16_bits_to_f32((uint16_t)(t.vmeta >> 16));
+    } else if constexpr (ROPE) {
+      ksc = f16_bits_to_f32((uint16_t)t.kmeta);
+      vsc = f16_bits_to_f32((uint16_t)t.vmeta);
     } else {
 #pragma unroll
       for (int kk = 0; kk < KK; kk++) acc = mfma_i8(a1[kk], t.k[kk][0], acc);
@@ -274,6 +394,33 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       ksc = f16_bits_to_f32((uint16_t)t.kmeta);
       vsc = f16_bits_to_f32((uint16_t)t.vmeta);
     }
+    float rdot[G];
+    if constexpr (ROPE) {
+      float sb[2][G];
+#pragma unroll
+      for (int blk = 0; blk < 2; blk++) {
+#pragma unroll
+        for (int g = 0; g < G; g++) {
+          float part = 0.f;
+#pragma unroll
+          for (int mb = 0; mb < RG::NMB; mb++) {
+            v16i d16 = {0};
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++) d16 = mfma_i8(*(const v4i*)&rs->img[g][mb][kk][lane * 16], t.k[kk][blk], d16);
+#pragma unroll
+            for (int k5 = 0; k5 < 5; k5++) {
+              const int uu = 5 * mb + k5;
+              if (uu < RG::NU)
+                part = fmaf(limbs_to_f32(d16[3 * k5], d16[3 * k5 + 1], d16[3 * k5 + 2]), (uu & 1) ? fs[uu >> 1] : fc[uu >> 1], part);
+            }
+          }
+          sb[blk][g] = part + __shfl_xor(part, 32);        // the other half of the wave holds the other frequencies
+        }
+        rope_advance(blk);                                  // to the next block of this wave: +32, then the next tile
+      }
+#pragma unroll
+      for (int g = 0; g < G; g++) rdot[g] = lane < 32 ? sb[0][g] : sb[1][g];
+    }
     if (++since_flush >= kMaxTilesPerFlush) {
       since_flush = 0;
 #pragma unroll
@@ -281,7 +428,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     }
 #pragma unroll
     for (int g = 0; g < G; g++) {
-      float dot = limbs_to_f32(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2]);
+      float dot = ROPE ? rdot[g] : limbs_to_f32(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2]);
       if (I4) dot = fmaf(-kz, zsum[g], dot);
       const float s = valid ? ksc * dot * delta[g] : -INFINITY;
       if (__builtin_amdgcn_ballot_w64(s > m[g]) != 0) {          // a new running max somewhere in this tile
@@ -808,6 +955,59 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
   if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false, 512>(p, grid, threads, s);
   if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true, 1024>(p, grid, threads, s);
   return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------- rotary variant: launch
+template <int R, int G, int D, int NT>
+__global__ __launch_bounds__(NT) void k_attn_rope(AttnParams p, RopeArgs ra) {
+  __shared__ AttnMfmaShared<R, G, NT> sh;
+  __shared__ RopeShared<R, G, D> rs;
+  attn_mfma_body<R, G, false, NT, false, D>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z, &rs, &ra);
+}
+
+template <int R, int G>
+static hipError_t launch_rope(const AttnParams& p, const RopeArgs& ra, dim3 grid, int threads, hipStream_t s) {
+  if (p.d == 128) hipLaunchKernelGGL((k_attn_rope<R, G, 128, 512>), grid, dim3(threads), 0, s, p, ra);
+  else if (p.d == 64) hipLaunchKernelGGL((k_attn_rope<R, G, 64, 512>), grid, dim3(threads), 0, s, p, ra);
+  else return hipErrorNotSupported;
+  return hipGetLastError();
+}
+
+// I8 latents; rank 32 with up to 4 query heads per kv head, rank 64 with up to 2 (the N^T operand images of all heads
+// of the group live in LDS).  hipErrorNotSupported otherwise.
+hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
+                                 const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, double rope_base,
+                                 void* out, hipStream_t s) {
+  const int G = d.n_q_heads / d.n_kv_heads;
+  if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16) return hipErrorNotSupported;
+  if (!((d.rank == 32 && G <= 4) || (d.rank == 64 && G <= 2))) return hipErrorNotSupported;
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 0);
+  if (threads > 512) {                       // this variant's register budget allows 8 waves per workgroup
+    wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 512);
+  }
+  RopeArgs ra;
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int i = 0; i < 64; i++) {
+    double rev = 0.0;
+    if (i < d.d_head / 2) {
+      const double theta = pow(rope_base, -2.0 * i / d.d_head);
+      rev = theta / two_pi;
+      rev -= floor(rev);
+    }
+    ra.fq[i] = (uint32_t)(unsigned long long)llround(rev * 4294967296.0);    // 2^32 wraps to 0: the same angle
+  }
+  if (d.rank == 32) {
+    switch (G) {
+      case 1: return launch_rope<32, 1>(p, ra, grid, threads, s);
+      case 2: return launch_rope<32, 2>(p, ra, grid, threads, s);
+      case 3: return launch_rope<32, 3>(p, ra, grid, threads, s);
+      default: return launch_rope<32, 4>(p, ra, grid, threads, s);
+    }
+  }
+  return G == 1 ? launch_rope<64, 1>(p, ra, grid, threads, s) : launch_rope<64, 2>(p, ra, grid, threads, s);
 }
 
 // ---------------------------------------------------------------- fused decode step: append + attention in one launch

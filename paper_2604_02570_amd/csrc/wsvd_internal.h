@@ -40,6 +40,9 @@ void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const voi
                         const void* A_V, const wsvd_cache& cache, AppendParams& p);
 int wsvd_append_mfma_waves(const wsvd_layer_desc& d);
 bool wsvd_append_uses_mfma(const wsvd_layer_desc& d);
+hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
+                                 const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, double rope_base,
+                                 void* out, hipStream_t s);
 // hipErrorNotSupported when there is no fused kernel for the combination
 hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
                                    const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,

@@ -93,6 +93,14 @@ class DeviceLayer:
         assert st == 0, W.status_str(st)
         return self.out.cpu().numpy().astype(np.float64)
 
+    def attend_rope(self, q_dev, q_scale_dev, BK_dev, BV_dev, max_seq_len, rope_base):
+        self.out.fill_(float("nan"))
+        W.wsvd_decode_attn_rope(self.ctx, self.desc, q_dev, q_scale_dev, BK_dev, BV_dev, self.cache, max_seq_len, rope_base,
+                                self.out)
+        st = W.wsvd_check(self.ctx)
+        assert st == 0, W.status_str(st)
+        return self.out.cpu().numpy().astype(np.float64)
+
     def pack_A(self, A32: np.ndarray, dtype: str) -> torch.Tensor:
         """Down-projection factor [Hkv,E,r] (the paper's shape, row-major) -> the library's packed layout."""
         src = as_dtype_dev(A32, dtype)

@@ -423,6 +423,58 @@ def test_host_side_errors():
     L.close()
 
 
+# ------------------------------------------------------------------------------------------ rotary variant
+ROPE_CASES = [
+    ("c3_small", dict()),                                     # rank 32, head dim 128, int8 query
+    ("c3_small", dict(q_dtype="f32", context=90)),
+    ("c3_small", dict(context=2000, batch=2)),                # several chunks, long distances
+    ("c3_small", dict(d_head=64)),                            # head dim 64
+    ("c3_small", dict(n_q_heads=8, n_kv_heads=4)),            # two query heads per kv head
+    ("c3_small", dict(n_q_heads=16, n_kv_heads=4, q_dtype="bf16", context=130)),   # four
+    ("c3_small", dict(rank=64, context=700)),                 # rank 64
+    ("c5_small", dict(n_q_heads=4, n_kv_heads=2, context=200)),    # rank 64, two query heads per kv head
+]
+
+
+@pytest.mark.parametrize("name,over", ROPE_CASES, ids=[f"{n}-{'-'.join(f'{k}{v}' for k, v in o.items())}" for n, o in ROPE_CASES])
+def test_attention_rope_small(name, over):
+    """Reconstruct-rotate-attend against the oracle that forms K = C B_K, rotates keys and query, and attends."""
+    c = build_case(name, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    got = L.attend_rope(qd, qs, BKd, BVd, int(c.cache.seq_lens.max()), 10000.0)
+    ref = O.decode_attn_rope_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale, 10000.0)
+    check_out(got, ref, "i8", f"rope {name}{over}")
+    plain = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    assert np.abs(ref - plain).max() > 1e-2, "the case does not exercise the rotation"
+    L.close()
+
+
+def test_attention_rope_edge_lengths_and_other_base():
+    lens = [0, 1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 640]
+    c = build_case("c3_small", batch=len(lens), context=640, ragged=(), extra_cap=0, steps=1)
+    for b, n in enumerate(lens):
+        c.cache.seq_lens[b] = n
+    L = layer_for(c); L.upload(c.cache)
+    qd, qs, q64 = q_to_device(c.q32[0], c.sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    for base in (10000.0, 500000.0):
+        got = L.attend_rope(qd, qs, BKd, BVd, 640, base)
+        ref = O.decode_attn_rope_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale, base)
+        assert (got[0] == 0).all()
+        check_out(got, ref, "i8", f"rope edges base={base}")
+    # unsupported combinations are refused, not mis-computed
+    c4 = build_case("c4_small")
+    L4 = layer_for(c4); L4.upload(c4.cache)
+    qd4, qs4, _ = q_to_device(c4.q32[0], c4.sp.q_dtype)
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_decode_attn_rope(L4.ctx, L4.desc, qd4, qs4, BKd, BVd, L4.cache, 64, 10000.0, L4.out)
+    assert e.value.status == W.E_UNSUPPORTED
+    L4.close(); L.close()
+
+
 # ------------------------------------------------------------------------------------------ fused decode step
 STEP_CASES = [
     ("c3_small", dict(), 2),                                      # int8, one chunk per sequence
