@@ -39,6 +39,10 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
+    ap.add_argument("--rope", action="store_true",
+                    help="c3 / c4: attention through wsvd_decode_attn_rope (rotary position embedding between the key "
+                         "reconstruction and q K^T), a secondary line")
+    ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
     ap.add_argument("--workload", choices=["c3", "c4", "c5"], default="c3",
@@ -65,6 +69,8 @@ def main():
     W.lib()   # fails loudly if the HIP library is missing
     if args.single_launch:
         W.wsvd_set_option("fused_step", 2)
+    if args.max_threads:
+        W.wsvd_set_option("max_threads", args.max_threads)
     if args.workload == "c5":
         return run_c5(args, np, torch, W, WI)
 
@@ -130,19 +136,27 @@ def main():
     outs = [torch.empty((B, Hq, d), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
     torch.cuda.synchronize()
 
+    ROPE_BASE = 10000.0
+
+    def attend(cache, out):
+        if args.rope:
+            W.wsvd_decode_attn_rope(ctx, desc, qd, qsd, BKd, BVd, cache, t_cap, ROPE_BASE, out)
+        else:
+            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, cache, t_cap, out)
+
     def step(i):
         s = sets[i % n_sets]
         if args.attn_only:
-            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+            attend(s[5], outs[i % n_sets])
         elif args.single_launch:
             W.wsvd_decode_step(ctx, desc, xd, None, AKd, AVd, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
         else:
             W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, s[5])
-            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+            attend(s[5], outs[i % n_sets])
 
     def attn_only(i):
         s = sets[i % n_sets]
-        W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
+        attend(s[5], outs[i % n_sets])
 
     # rows attended (summed over the batch) at timed step i: initial lengths + the appends that set has seen so far
     def rows_at(i):
@@ -291,7 +305,21 @@ def main():
         },
     }
 
-    if not args.no_cpu_baseline and args.workload == "c3":
+    if args.rope:
+        # the rotary variant is bound by vector arithmetic, not by the stream: per cached row and query head the
+        # method needs 2 r d flops to form the key, 3 d to rotate it and 2 d for the product.  Peak: the fp32 vector
+        # rate without packed operations, 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s.
+        rows_heads = attn_bytes / row_bytes * Hq
+        flops = rows_heads * (2 * r * d + 5 * d)
+        res["config"]["step"] = res["config"]["step"].replace("wsvd_decode_attn", "wsvd_decode_attn_rope")
+        res["config"]["rope_base"] = ROPE_BASE
+        hbm = dict(res["roofline"]); hbm.pop("stream_read_probe", None); hbm.pop("kernel", None)
+        res["roofline"] = {"kernel": "k_attn_rope<%d,1,%d> (reconstruct, rotate, attend; int8 latents)" % (r, d), "bound": "alu",
+                           "achieved": round(flops / (attn_us * 1e-6) / 1e12, 2), "peak": 78.6, "unit": "TFLOP/s",
+                           "frac": round(flops / (attn_us * 1e-6) / 1e12 / 78.6, 4), "traffic": None,
+                           "algorithmic_flops_per_launch": int(flops), "avg_launch_us": round(attn_us, 3),
+                           "hbm_view": hbm}
+    if not args.no_cpu_baseline and args.workload == "c3" and not args.rope:
         res["cpu_baseline"] = cpu_baseline(np, row_bytes)
     print(json.dumps(res))
     W.wsvd_destroy(ctx)

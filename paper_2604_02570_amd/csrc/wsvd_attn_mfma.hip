@@ -120,22 +120,24 @@ struct AttnMfmaShared {
 //   A_i = q_i k_i + q_i' k_i',  B_i = q_i k_i' - q_i' k_i,   k = B_K^T c_t,
 // and A_i, B_i are linear in the latent: [A; B](t) = N^T c_t with N (r x d) built once per (sequence, head) from
 // q and B_K.  So the key tile is still "reconstructed" on the matrix cores, d outputs per token, straight from the
-// int8 stream (N carried as three 7-bit limbs, exact int32 products), and what is left per token is a dot product
+// int8 stream (N carried as two 7-bit limbs, exact int32 products), and what is left per token is a dot product
 // with its d position features, which each lane advances from block to block by a fixed rotation.
-// Row layout of the N^T operand: a 32-row MFMA block gives each half of the wave 16 rows = 5 features x 3 limbs
-// (row 8(k/4) + 4h + k%4 <-> register k, feature k/3, limb k%3); half h owns the frequencies [h d/4, (h+1) d/4),
+// N is quantised per frequency: the rows A_i and B_i share the unit delta_i = max |.| / 16256, and delta_i is folded
+// into that frequency's features (delta_i cos, delta_i sin rotate like cos, sin), so it costs nothing per token.
+// Row layout of the N^T operand: a 32-row MFMA block gives each half of the wave 16 rows = 8 features x 2 limbs
+// (row 8(k/4) + 4h + k%4 <-> register k, feature k/2, limb k%2); half h owns the frequencies [h d/4, (h+1) d/4),
 // feature u of a half = frequency u/2, cosine (even u) or sine (odd u) term.
 template <int D>
 struct RopeGeom {
   static constexpr int NFH = D / 4;                 // frequencies per half wave
   static constexpr int NU = 2 * NFH;                // features per half wave
-  static constexpr int NMB = (NU + 4) / 5;          // 32-row operand blocks
+  static constexpr int NMB = NU / 8;                // 32-row operand blocks
 };
 template <int R, int G, int D>
 struct RopeShared {
   __attribute__((aligned(16))) uint8_t img[G][RopeGeom<D>::NMB][R / 32][1024];   // N^T limbs as MFMA A operands
   float rot[2][D / 2][2];                           // cos, sin of theta_i * shift for the two block-to-block shifts
-  float gmax[16][G];
+  uint32_t fmax_bits[D / 2];                        // per frequency: largest |entry| of its two rows over all heads
 };
 struct RopeArgs {
   uint32_t fq[64];                                  // theta_i / 2 pi as a 32-bit binary fraction of a revolution
@@ -146,6 +148,13 @@ struct RopeArgs {
 WSVD_DEV void phase_sincos(uint32_t phase, float& c, float& s) {
   const float x = (float)(int32_t)phase * (1.0f / 2147483648.0f);   // in [-1, 1): the angle in units of pi
   sincospif(x, &s, &c);
+}
+// the same through the hardware's sine / cosine of an angle given in revolutions (a few 1e-7 absolute error on
+// [-1/2, 1/2), against ~50 instructions for the library routine): used for the 2 x d/4 start values per lane
+WSVD_DEV void phase_sincos_fast(uint32_t phase, float& c, float& s) {
+  const float rev = (float)(int32_t)phase * (1.0f / 4294967296.0f);
+  c = __builtin_amdgcn_cosf(rev);
+  s = __builtin_amdgcn_sinf(rev);
 }
 
 // One workgroup's share of the decode attention: kv head cx, context chunk cy, sequence cz.
@@ -217,48 +226,55 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       phase_sincos(ra->fq[i] * (uint32_t)sft, c, sn);
       rs->rot[tid / Dh][i][0] = c; rs->rot[tid / Dh][i][1] = sn;
     }
-    // N (r x d per query head): entry (j, f), f = type * d/2 + i; pass 1 finds the largest magnitude per head
+    // N (r x d per query head).  A thread owns frequency i = tid % (d/2) and latent dims j = tid / (d/2), + step, ...:
+    // the cosine and the sine entry of (j, i) come from the same four numbers, and q_i, q_i' are read once.
     const uint16_t* bk16 = (const uint16_t*)bk_lds;
-    auto n_entry = [&](int g, int j, int f) {
-      const int i = f % Dh, type = f / Dh;
-      const float qi = q_lds[g * ROPE_D + i], qj = q_lds[g * ROPE_D + i + Dh];
-      const float bi = bf16_to_f32(bk16[j * ROPE_D + i]), bj = bf16_to_f32(bk16[j * ROPE_D + i + Dh]);
-      return p.c_scale * (type == 0 ? fmaf(qi, bi, qj * bj) : fmaf(qi, bj, -(qj * bi)));
-    };
-    float mx[G];
+    static_assert((R * Dh) % NT == 0 && NT % Dh == 0, "N build: whole (j, i) pairs per thread");
+    constexpr int NJMAX = R * Dh / NT;                  // (j, i) pairs per thread; the launch uses exactly NT threads
+    const int fi = tid % Dh, j0 = tid / Dh, jstep = NT / Dh;
+    for (int i = tid; i < Dh; i += blockDim.x) rs->fmax_bits[i] = 0u;
+    float ea[G][NJMAX], eb[G][NJMAX];
+    float mx = 0.f;
 #pragma unroll
     for (int g = 0; g < G; g++) {
-      mx[g] = 0.f;
-      for (int e = tid; e < R * ROPE_D; e += blockDim.x) mx[g] = fmaxf(mx[g], fabsf(n_entry(g, e / ROPE_D, e % ROPE_D)));
-      mx[g] = wave_max(mx[g]);
-      if (lane == 0) rs->gmax[wave][g] = mx[g];
-    }
-    __syncthreads();
+      const float qi = q_lds[g * ROPE_D + fi] * p.c_scale, qj = q_lds[g * ROPE_D + fi + Dh] * p.c_scale;
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-      float amax = rs->gmax[0][g];
-      for (int k = 1; k < NW; k++) amax = fmaxf(amax, rs->gmax[k][g]);
-      const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
-      if (tid == 0) qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f;
-      for (int e = tid; e < R * ROPE_D; e += blockDim.x) {
-        const int j = e / ROPE_D, f = e % ROPE_D;
-        const int Q = (int)__builtin_rintf(n_entry(g, j, f) * inv);
-        const int l0 = ((Q + 64) & 127) - 64;
-        const int Q1 = (Q - l0) >> 7;
-        const int l1 = ((Q1 + 64) & 127) - 64;
-        const int l2 = (Q1 - l1) >> 7;
-        const int i = f % Dh, type = f / Dh;
-        const int hh = i / RG::NFH, uu = 2 * (i % RG::NFH) + type;        // half, feature within the half
-        const int mb = uu / 5, k0 = 3 * (uu % 5);
-        uint8_t* base = &rs->img[g][mb][j >> 5][(((j & 31) >> 4) * 32) * 16 + (j & 15)];
-        const int limbs[3] = {l2, l1, l0};
-#pragma unroll
-        for (int l = 0; l < 3; l++) {
-          const int k = k0 + l;
-          base[(8 * (k >> 2) + 4 * hh + (k & 3)) * 16] = (uint8_t)(int8_t)limbs[l];
-        }
+      for (int k = 0; k < NJMAX; k++) {
+        const int j = j0 + k * jstep;
+        const float bi = bf16_to_f32(bk16[j * ROPE_D + fi]), bj = bf16_to_f32(bk16[j * ROPE_D + fi + Dh]);
+        ea[g][k] = fmaf(qi, bi, qj * bj);
+        eb[g][k] = fmaf(qi, bj, -(qj * bi));
+        mx = fmaxf(mx, fmaxf(fabsf(ea[g][k]), fabsf(eb[g][k])));
       }
     }
+    __syncthreads();                                     // fmax_bits cleared, image zeroed
+    atomicMax(&rs->fmax_bits[fi], __float_as_uint(mx));  // non-negative floats order like their bits
+    __syncthreads();
+    {
+      const float amax = __uint_as_float(rs->fmax_bits[fi]);
+      const float inv = amax > 0.f ? 16256.f / amax : 0.f;                 // |Q| <= 127 * 128: high limb in [-127, 127]
+      const int hh = fi / RG::NFH, fl = fi % RG::NFH;                      // half, frequency within the half
+#pragma unroll
+      for (int g = 0; g < G; g++)
+#pragma unroll
+        for (int k = 0; k < NJMAX; k++) {
+          const int j = j0 + k * jstep;
+          {
+#pragma unroll
+            for (int type = 0; type < 2; type++) {
+              const int Q = (int)__builtin_rintf((type ? eb[g][k] : ea[g][k]) * inv);
+              const int l0 = ((Q + 64) & 127) - 64;
+              const int l1 = (Q - l0) >> 7;
+              const int uu = 2 * fl + type;
+              const int mb = uu >> 3, k0 = 2 * (uu & 7);
+              uint8_t* base = &rs->img[g][mb][j >> 5][(((j & 31) >> 4) * 32) * 16 + (j & 15)];
+              base[(8 * (k0 >> 2) + 4 * hh + (k0 & 3)) * 16] = (uint8_t)(int8_t)l1;
+              base[(8 * ((k0 + 1) >> 2) + 4 * hh + ((k0 + 1) & 3)) * 16] = (uint8_t)(int8_t)l0;
+            }
+          }
+        }
+    }
+    if (tid < G) qdelta[tid] = 1.f;
   } else {
   compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   if (tid < G * R) {
@@ -321,7 +337,11 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     const int hf = lane >> 5;
     const uint32_t dist = (uint32_t)(n_raw - 1 - (T * 64 + (lane & 31)));   // query position minus key position
 #pragma unroll
-    for (int i = 0; i < RG::NFH; i++) phase_sincos(ra->fq[hf * RG::NFH + i] * dist, fc[i], fs[i]);
+    for (int i = 0; i < RG::NFH; i++) {
+      phase_sincos_fast(ra->fq[hf * RG::NFH + i] * dist, fc[i], fs[i]);
+      const float unit = __uint_as_float(rs->fmax_bits[hf * RG::NFH + i]) * (1.0f / 16256.f);
+      fc[i] *= unit; fs[i] *= unit;
+    }
   }
   // advance the features by one of the two block-to-block shifts: the distance shrinks, so the angle turns back
   auto rope_advance = [&](int which) {
@@ -397,25 +417,37 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     float rdot[G];
     if constexpr (ROPE) {
       float sb[2][G];
+      // N^T c for one (operand block, head) at a time, the next product issued while the last one's 16 outputs are
+      // folded into the score; the scheduling fences keep the compiler from hoisting all products (16 registers each)
+      constexpr int NI = G * RG::NMB;
+      auto product = [&](int idx, int blk) {
+        const int g = idx % G, mb = idx / G;
+        v16i d16 = {0};
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++) d16 = mfma_i8(*(const v4i*)&rs->img[g][mb][kk][lane * 16], t.k[kk][blk], d16);
+        return d16;
+      };
 #pragma unroll
       for (int blk = 0; blk < 2; blk++) {
+        float part[G];
 #pragma unroll
-        for (int g = 0; g < G; g++) {
-          float part = 0.f;
+        for (int g = 0; g < G; g++) part[g] = 0.f;
+        v16i dc = product(0, blk);
 #pragma unroll
-          for (int mb = 0; mb < RG::NMB; mb++) {
-            v16i d16 = {0};
+        for (int idx = 0; idx < NI; idx++) {
+          v16i dn = dc;
+          if (idx + 1 < NI) dn = product(idx + 1, blk);
+          const int g = idx % G, mb = idx / G;
 #pragma unroll
-            for (int kk = 0; kk < KK; kk++) d16 = mfma_i8(*(const v4i*)&rs->img[g][mb][kk][lane * 16], t.k[kk][blk], d16);
-#pragma unroll
-            for (int k5 = 0; k5 < 5; k5++) {
-              const int uu = 5 * mb + k5;
-              if (uu < RG::NU)
-                part = fmaf(limbs_to_f32(d16[3 * k5], d16[3 * k5 + 1], d16[3 * k5 + 2]), (uu & 1) ? fs[uu >> 1] : fc[uu >> 1], part);
-            }
+          for (int k8 = 0; k8 < 8; k8++) {
+            const int uu = 8 * mb + k8;
+            part[g] = fmaf((float)((dc[2 * k8] << 7) + dc[2 * k8 + 1]), (uu & 1) ? fs[uu >> 1] : fc[uu >> 1], part[g]);
           }
-          sb[blk][g] = part + __shfl_xor(part, 32);        // the other half of the wave holds the other frequencies
+          __builtin_amdgcn_sched_barrier(0);
+          dc = dn;
         }
+#pragma unroll
+        for (int g = 0; g < G; g++) sb[blk][g] = part[g] + __shfl_xor(part[g], 32);   // the other half wave: the other frequencies
         rope_advance(blk);                                  // to the next block of this wave: +32, then the next tile
       }
 #pragma unroll
@@ -984,10 +1016,9 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
   AttnParams p;
   dim3 grid;
   int threads;
-  wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 0);
-  if (threads > 512) {                       // this variant's register budget allows 8 waves per workgroup
-    wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 512);
-  }
+  // always 8 waves per workgroup: the register budget allows no more, and the N build divides its work over exactly
+  // that many threads (waves without a tile of their own idle through the loop)
+  wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 512);
   RopeArgs ra;
   const double two_pi = 6.283185307179586476925286766559;
   for (int i = 0; i < 64; i++) {
