@@ -120,22 +120,27 @@ struct AttnMfmaShared {
 //   A_i = q_i k_i + q_i' k_i',  B_i = q_i k_i' - q_i' k_i,   k = B_K^T c_t,
 // and A_i, B_i are linear in the latent: [A; B](t) = N^T c_t with N (r x d) built once per (sequence, head) from
 // q and B_K.  So the key tile is still "reconstructed" on the matrix cores, d outputs per token, straight from the
-// int8 stream (N carried as two 7-bit limbs, exact int32 products), and what is left per token is a dot product
-// with its d position features, which each lane advances from block to block by a fixed rotation.
-// N is quantised per frequency: the rows A_i and B_i share the unit delta_i = max |.| / 16256, and delta_i is folded
-// into that frequency's features (delta_i cos, delta_i sin rotate like cos, sin), so it costs nothing per token.
-// Row layout of the N^T operand: a 32-row MFMA block gives each half of the wave 16 rows = 8 features x 2 limbs
-// (row 8(k/4) + 4h + k%4 <-> register k, feature k/2, limb k%2); half h owns the frequencies [h d/4, (h+1) d/4),
-// feature u of a half = frequency u/2, cosine (even u) or sine (odd u) term.
+// cache stream (codes widened to fp16, exact; N carried as an fp16 pair hi + lo whose two products land in the same
+// fp32 accumulator), and what is left per token is a dot product with its d position features, which each lane
+// advances from block to block by a fixed rotation.
+// N is scaled per frequency: the rows A_i and B_i share the unit delta_i = max |.| / 2^15 (so hi uses fp16's upper
+// range and a lo that falls into the subnormals is below 2^-21 of the largest entry), and delta_i is folded into that
+// frequency's features (delta_i cos, delta_i sin rotate like cos, sin), so it costs nothing per token.
+// Row layout of the N^T operand: a 32-row MFMA block gives each half of the wave 16 rows = 16 features
+// (row 8(v/4) + 4h + v%4 <-> accumulator register v); half h owns the frequencies [h d/4, (h+1) d/4), feature u of a
+// half = frequency u/2, cosine (even u) or sine (odd u) term.  Contraction order of a 16-dim step: the lane of dim
+// group g2 supplies dims 16 g2 + 8 s + e (step s of the pair, e < 8) - the bytes it already holds of the int8 image.
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 template <int D>
 struct RopeGeom {
   static constexpr int NFH = D / 4;                 // frequencies per half wave
   static constexpr int NU = 2 * NFH;                // features per half wave
-  static constexpr int NMB = NU / 8;                // 32-row operand blocks
+  static constexpr int NMB = NU / 16;               // 32-row operand blocks
 };
 template <int R, int G, int D>
 struct RopeShared {
-  __attribute__((aligned(16))) uint8_t img[G][RopeGeom<D>::NMB][R / 32][1024];   // N^T limbs as MFMA A operands
+  // N^T as MFMA A operands: [head][operand block][16-dim step][hi, lo][lane][8]
+  __attribute__((aligned(16))) _Float16 img[G][RopeGeom<D>::NMB][R / 16][2][512];
   float rot[2][D / 2][2];                           // cos, sin of theta_i * shift for the two block-to-block shifts
   uint32_t fmax_bits[D / 2];                        // per frequency: largest |entry| of its two rows over all heads
 };
@@ -217,8 +222,6 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   __syncthreads();
   if constexpr (ROPE) {
     constexpr int Dh = ROPE_D / 2;
-    // operand images start out zero (unused rows and features must contribute nothing)
-    for (int i = tid; i < (int)(sizeof(rs->img) / 16); i += blockDim.x) ((v4i*)rs->img)[i] = v4i{0, 0, 0, 0};
     // block-to-block rotations: +32 tokens (second block of a tile), then on to the wave's next tile
     if (tid < 2 * Dh) {
       const int sft = tid / Dh ? 64 * NW - 32 : 32, i = tid % Dh;
@@ -252,25 +255,24 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     __syncthreads();
     {
       const float amax = __uint_as_float(rs->fmax_bits[fi]);
-      const float inv = amax > 0.f ? 16256.f / amax : 0.f;                 // |Q| <= 127 * 128: high limb in [-127, 127]
+      const float inv = amax > 0.f ? 32768.f / amax : 0.f;
       const int hh = fi / RG::NFH, fl = fi % RG::NFH;                      // half, frequency within the half
 #pragma unroll
       for (int g = 0; g < G; g++)
 #pragma unroll
         for (int k = 0; k < NJMAX; k++) {
           const int j = j0 + k * jstep;
-          {
+          const int ks = ((j >> 5) << 1) | ((j >> 3) & 1), g2 = (j >> 4) & 1, e = j & 7;
 #pragma unroll
-            for (int type = 0; type < 2; type++) {
-              const int Q = (int)__builtin_rintf((type ? eb[g][k] : ea[g][k]) * inv);
-              const int l0 = ((Q + 64) & 127) - 64;
-              const int l1 = (Q - l0) >> 7;
-              const int uu = 2 * fl + type;
-              const int mb = uu >> 3, k0 = 2 * (uu & 7);
-              uint8_t* base = &rs->img[g][mb][j >> 5][(((j & 31) >> 4) * 32) * 16 + (j & 15)];
-              base[(8 * (k0 >> 2) + 4 * hh + (k0 & 3)) * 16] = (uint8_t)(int8_t)l1;
-              base[(8 * ((k0 + 1) >> 2) + 4 * hh + ((k0 + 1) & 3)) * 16] = (uint8_t)(int8_t)l0;
-            }
+          for (int type = 0; type < 2; type++) {
+            const float val = (type ? eb[g][k] : ea[g][k]) * inv;
+            const _Float16 hi = (_Float16)val;
+            const _Float16 lo = (_Float16)(val - (float)hi);
+            const int uu = 2 * fl + type;
+            const int mb = uu >> 4, v = uu & 15;
+            const int row = 8 * (v >> 2) + 4 * hh + (v & 3);
+            rs->img[g][mb][ks][0][(g2 * 32 + row) * 8 + e] = hi;
+            rs->img[g][mb][ks][1][(g2 * 32 + row) * 8 + e] = lo;
           }
         }
     }
@@ -339,7 +341,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
 #pragma unroll
     for (int i = 0; i < RG::NFH; i++) {
       phase_sincos_fast(ra->fq[hf * RG::NFH + i] * dist, fc[i], fs[i]);
-      const float unit = __uint_as_float(rs->fmax_bits[hf * RG::NFH + i]) * (1.0f / 16256.f);
+      const float unit = __uint_as_float(rs->fmax_bits[hf * RG::NFH + i]) * (1.0f / 32768.f);
       fc[i] *= unit; fs[i] *= unit;
     }
   }
@@ -420,11 +422,15 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       // N^T c for one (operand block, head) at a time, the next product issued while the last one's 16 outputs are
       // folded into the score; the scheduling fences keep the compiler from hoisting all products (16 registers each)
       constexpr int NI = G * RG::NMB;
-      auto product = [&](int idx, int blk) {
+      v8h bop[2 * KK];                                      // this block's codes as fp16 B operands
+      auto product = [&](int idx) {
         const int g = idx % G, mb = idx / G;
-        v16i d16 = {0};
+        v16f d16 = {0};
 #pragma unroll
-        for (int kk = 0; kk < KK; kk++) d16 = mfma_i8(*(const v4i*)&rs->img[g][mb][kk][lane * 16], t.k[kk][blk], d16);
+        for (int ks = 0; ks < 2 * KK; ks++)
+#pragma unroll
+          for (int term = 0; term < 2; term++)
+            d16 = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const v8h*)&rs->img[g][mb][ks][term][lane * 8], bop[ks], d16, 0, 0, 0);
         return d16;
       };
 #pragma unroll
@@ -432,16 +438,24 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
         float part[G];
 #pragma unroll
         for (int g = 0; g < G; g++) part[g] = 0.f;
-        v16i dc = product(0, blk);
+#pragma unroll
+        for (int kk = 0; kk < KK; kk++)
+#pragma unroll
+          for (int x = 0; x < 4; x++) {
+            const int dw = t.k[kk][blk][x];
+#pragma unroll
+            for (int b = 0; b < 4; b++) bop[2 * kk + (x >> 1)][4 * (x & 1) + b] = (_Float16)(int)(int8_t)(dw >> (8 * b));
+          }
+        v16f dc = product(0);
 #pragma unroll
         for (int idx = 0; idx < NI; idx++) {
-          v16i dn = dc;
-          if (idx + 1 < NI) dn = product(idx + 1, blk);
+          v16f dn = dc;
+          if (idx + 1 < NI) dn = product(idx + 1);
           const int g = idx % G, mb = idx / G;
 #pragma unroll
-          for (int k8 = 0; k8 < 8; k8++) {
-            const int uu = 8 * mb + k8;
-            part[g] = fmaf((float)((dc[2 * k8] << 7) + dc[2 * k8 + 1]), (uu & 1) ? fs[uu >> 1] : fc[uu >> 1], part[g]);
+          for (int v = 0; v < 16; v++) {
+            const int uu = 16 * mb + v;
+            part[g] = fmaf(dc[v], (uu & 1) ? fs[uu >> 1] : fc[uu >> 1], part[g]);
           }
           __builtin_amdgcn_sched_barrier(0);
           dc = dn;
