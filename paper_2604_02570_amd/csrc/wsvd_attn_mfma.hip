@@ -146,20 +146,28 @@ struct RopeShared {
 };
 struct RopeArgs {
   uint32_t fq[64];                                  // theta_i / 2 pi as a 32-bit binary fraction of a revolution
+  float rot[2][64][2];                              // cos, sin of theta_i * 32 and of theta_i * (64 * 8 - 32): the
+                                                    // two block-to-block shifts of an 8-wave workgroup, from the host
 };
 
-// cos, sin of the angle `phase` (binary fraction of a revolution: the wrap-around of 32-bit arithmetic is the
-// reduction mod 2 pi, exact)
-WSVD_DEV void phase_sincos(uint32_t phase, float& c, float& s) {
-  const float x = (float)(int32_t)phase * (1.0f / 2147483648.0f);   // in [-1, 1): the angle in units of pi
-  sincospif(x, &s, &c);
-}
-// the same through the hardware's sine / cosine of an angle given in revolutions (a few 1e-7 absolute error on
-// [-1/2, 1/2), against ~50 instructions for the library routine): used for the 2 x d/4 start values per lane
+// cos, sin of the angle `phase`, a 32-bit binary fraction of a revolution (the wrap-around of 32-bit arithmetic is
+// the reduction mod 2 pi, exact), through the hardware's sine / cosine of an angle given in revolutions (a few 1e-7
+// absolute error on [-1/2, 1/2)): used for the 2 x d/4 start values per lane
 WSVD_DEV void phase_sincos_fast(uint32_t phase, float& c, float& s) {
   const float rev = (float)(int32_t)phase * (1.0f / 4294967296.0f);
   c = __builtin_amdgcn_cosf(rev);
   s = __builtin_amdgcn_sinf(rev);
+}
+
+// x * scale as an fp16 pair hi + lo.  The fp32 product is pinned in a register first: otherwise the compiler forms hi
+// twice, once by rounding the fp32 product and once by rounding the exact product straight to fp16 (a fused
+// multiply-convert), stores one and takes lo against the other; the two differ now and then by one fp16 step, which
+// shows up as a 1e-4 error in single outputs.
+WSVD_DEV void split_fp16_pair(float x, float scale, _Float16& hi, _Float16& lo) {
+  float val = x * scale;
+  asm volatile("" : "+v"(val));
+  hi = (_Float16)val;
+  lo = (_Float16)(val - (float)hi);
 }
 
 // One workgroup's share of the decode attention: kv head cx, context chunk cy, sequence cz.
@@ -224,57 +232,60 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     constexpr int Dh = ROPE_D / 2;
     // block-to-block rotations: +32 tokens (second block of a tile), then on to the wave's next tile
     if (tid < 2 * Dh) {
-      const int sft = tid / Dh ? 64 * NW - 32 : 32, i = tid % Dh;
-      float c, sn;
-      phase_sincos(ra->fq[i] * (uint32_t)sft, c, sn);
-      rs->rot[tid / Dh][i][0] = c; rs->rot[tid / Dh][i][1] = sn;
+      const int which = tid / Dh, i = tid % Dh;
+      rs->rot[which][i][0] = ra->rot[which][i][0]; rs->rot[which][i][1] = ra->rot[which][i][1];
     }
-    // N (r x d per query head).  A thread owns frequency i = tid % (d/2) and latent dims j = tid / (d/2), + step, ...:
-    // the cosine and the sine entry of (j, i) come from the same four numbers, and q_i, q_i' are read once.
+    // N (r x d per query head), written as whole 16-byte operand slots: a slot = one feature row (head, cosine or
+    // sine term, frequency i) x 8 consecutive latent dims.  Consecutive threads take consecutive frequencies.
     const uint16_t* bk16 = (const uint16_t*)bk_lds;
-    static_assert((R * Dh) % NT == 0 && NT % Dh == 0, "N build: whole (j, i) pairs per thread");
-    constexpr int NJMAX = R * Dh / NT;                  // (j, i) pairs per thread; the launch uses exactly NT threads
-    const int fi = tid % Dh, j0 = tid / Dh, jstep = NT / Dh;
-    for (int i = tid; i < Dh; i += blockDim.x) rs->fmax_bits[i] = 0u;
-    float ea[G][NJMAX], eb[G][NJMAX];
-    float mx = 0.f;
+    constexpr int NSLOT = G * 2 * (R / 8) * Dh;
+    constexpr int NS = (NSLOT + NT - 1) / NT;           // slots per thread; the launch uses exactly NT threads
+    for (int i = tid; i < Dh; i += NT) rs->fmax_bits[i] = 0u;
+    float ent[NS][8];
 #pragma unroll
-    for (int g = 0; g < G; g++) {
+    for (int k = 0; k < NS; k++) {
+      const int slot = min(tid + k * NT, NSLOT - 1);    // surplus threads repeat the last slot and do not write
+      const int fi = slot % Dh, jgrp = (slot / Dh) % (R / 8), type = (slot / (Dh * (R / 8))) % 2, g = slot / (Dh * (R / 8) * 2);
       const float qi = q_lds[g * ROPE_D + fi] * p.c_scale, qj = q_lds[g * ROPE_D + fi + Dh] * p.c_scale;
+      // cosine term: q_i k_i + q_i' k_i';  sine term: q_i k_i' - q_i' k_i
+      const float wa = type ? -qj : qi, wb = type ? qi : qj;
 #pragma unroll
-      for (int k = 0; k < NJMAX; k++) {
-        const int j = j0 + k * jstep;
-        const float bi = bf16_to_f32(bk16[j * ROPE_D + fi]), bj = bf16_to_f32(bk16[j * ROPE_D + fi + Dh]);
-        ea[g][k] = fmaf(qi, bi, qj * bj);
-        eb[g][k] = fmaf(qi, bj, -(qj * bi));
-        mx = fmaxf(mx, fmaxf(fabsf(ea[g][k]), fabsf(eb[g][k])));
+      for (int e = 0; e < 8; e++) {
+        const int j = 8 * jgrp + e;
+        ent[k][e] = fmaf(wa, bf16_to_f32(bk16[j * ROPE_D + fi]), wb * bf16_to_f32(bk16[j * ROPE_D + fi + Dh]));
       }
     }
-    __syncthreads();                                     // fmax_bits cleared, image zeroed
-    atomicMax(&rs->fmax_bits[fi], __float_as_uint(mx));  // non-negative floats order like their bits
+    __syncthreads();                                     // fmax_bits cleared
+#pragma unroll
+    for (int k = 0; k < NS; k++) {
+      float mx = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e++) mx = fmaxf(mx, fabsf(ent[k][e]));
+      const int slot = min(tid + k * NT, NSLOT - 1);
+      atomicMax(&rs->fmax_bits[slot % Dh], __float_as_uint(mx));   // non-negative floats order like their bits
+    }
     __syncthreads();
-    {
-      const float amax = __uint_as_float(rs->fmax_bits[fi]);
-      const float inv = amax > 0.f ? 32768.f / amax : 0.f;
-      const int hh = fi / RG::NFH, fl = fi % RG::NFH;                      // half, frequency within the half
 #pragma unroll
-      for (int g = 0; g < G; g++)
+    for (int k = 0; k < NS; k++) {
+      const int slot = tid + k * NT;
+      if (slot < NSLOT) {
+        const int fi = slot % Dh, jgrp = (slot / Dh) % (R / 8), type = (slot / (Dh * (R / 8))) % 2, g = slot / (Dh * (R / 8) * 2);
+        const float amax = __uint_as_float(rs->fmax_bits[fi]);
+        const float inv = amax > 0.f ? 32768.f / amax : 0.f;
+        const int hh = fi / RG::NFH, uu = 2 * (fi % RG::NFH) + type;         // half, feature within the half
+        const int mb = uu >> 4, v = uu & 15;
+        const int row = 8 * (v >> 2) + 4 * hh + (v & 3);
+        const int ks = ((jgrp >> 2) << 1) | (jgrp & 1), g2 = (jgrp >> 1) & 1;
+        v8h hi, lo;
 #pragma unroll
-        for (int k = 0; k < NJMAX; k++) {
-          const int j = j0 + k * jstep;
-          const int ks = ((j >> 5) << 1) | ((j >> 3) & 1), g2 = (j >> 4) & 1, e = j & 7;
-#pragma unroll
-          for (int type = 0; type < 2; type++) {
-            const float val = (type ? eb[g][k] : ea[g][k]) * inv;
-            const _Float16 hi = (_Float16)val;
-            const _Float16 lo = (_Float16)(val - (float)hi);
-            const int uu = 2 * fl + type;
-            const int mb = uu >> 4, v = uu & 15;
-            const int row = 8 * (v >> 2) + 4 * hh + (v & 3);
-            rs->img[g][mb][ks][0][(g2 * 32 + row) * 8 + e] = hi;
-            rs->img[g][mb][ks][1][(g2 * 32 + row) * 8 + e] = lo;
-          }
+        for (int e = 0; e < 8; e++) {
+          _Float16 h, l;
+          split_fp16_pair(ent[k][e], inv, h, l);
+          hi[e] = h; lo[e] = l;
         }
+        *(v8h*)&rs->img[g][mb][ks][0][(g2 * 32 + row) * 8] = hi;
+        *(v8h*)&rs->img[g][mb][ks][1][(g2 * 32 + row) * 8] = lo;
+      }
     }
     if (tid < G) qdelta[tid] = 1.f;
   } else {
@@ -1043,6 +1054,11 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
       rev -= floor(rev);
     }
     ra.fq[i] = (uint32_t)(unsigned long long)llround(rev * 4294967296.0);    // 2^32 wraps to 0: the same angle
+    // the rotations use the same rounded frequency as the start values, so that positions reached by stepping and
+    // positions evaluated directly agree
+    const double th = (double)ra.fq[i] / 4294967296.0 * two_pi;
+    ra.rot[0][i][0] = (float)cos(th * 32.0);  ra.rot[0][i][1] = (float)sin(th * 32.0);
+    ra.rot[1][i][0] = (float)cos(th * 480.0); ra.rot[1][i][1] = (float)sin(th * 480.0);
   }
   if (d.rank == 32) {
     switch (G) {
