@@ -23,6 +23,12 @@ What is computed, and where the paper defines it
   (Section 4.2: weights round-to-nearest per-channel symmetric, activations per-token
   symmetric).
 
+* the rest of the decoding pipeline of Section 3.4 (decoding-pipeline figure): the query is per-head low-rank
+  too, ``c_Qh = x A_Qh`` up-projected to ``q_h = c_Qh B_Qh``, and the V-path up-projection ``B_Vh`` is fused into
+  the output projection; ``fold_qk`` / ``fold_vo`` are those two offline products and ``decode_attn_latent_out`` the
+  regrouped attention that consumes them (pinned to the plain definition by associativity); ``decoder_layer_w4a8``
+  strings a whole pre-norm decoder layer together in the quantised setting of Section 4.2.
+
 Parity pins (tests/test_oracle_pins.py): identity factors reduce to library attention;
 absorbed == reconstructed; softmax rows sum to one; single-row cache returns that V row;
 zero query returns the mean V row; a two-token scalar case by hand; row-permutation
@@ -52,6 +58,8 @@ __all__ = [
     "latent_cache_bytes",
     "quantize_act_i8", "pack_w4", "unpack_w4", "linear_w4a8", "linear_w4a8_int_accum",
     "attention_block_w4a8",
+    "up_project_q", "fold_qk", "fold_vo", "decode_attn_lowrank_q", "decode_attn_latent_out",
+    "quantize_w4_rows", "rmsnorm", "silu", "decoder_layer_w4a8",
 ]
 
 # --------------------------------------------------------------------------- storage formats
@@ -464,4 +472,130 @@ def attention_block_w4a8(cache: LatentCache, x_codes, x_scale16, wq_packed, wq_s
         o_codes, o_scale = quantize_act_i8(attn.reshape(B, n_q_heads * d_head).astype(np.float32))
         res["o_codes"], res["o_scale"] = o_codes, o_scale
         res["y"] = linear_w4a8(o_codes, o_scale, wo_packed, wo_scale16)
+    return res
+
+
+# --------------------------------------------------------------------------- rest of the decoding pipeline (Section 3.4)
+
+
+def up_project_q(cQ64: np.ndarray, BQ64: np.ndarray) -> np.ndarray:
+    """q_h = c_Qh B_Qh (the Q latent is up-projected to form q, Section 3.4): cQ [B,Hq,rq], B_Q [Hq,rq,d] -> [B,Hq,d]."""
+    return np.einsum("bhj,hjc->bhc", cQ64, BQ64)
+
+
+def decode_attn_lowrank_q(cache: LatentCache, cQ64, BQ64, BK64, BV64, sm_scale: float, heads=None) -> np.ndarray:
+    """Decode attention of the paper's pipeline, in its order: up-project the Q latent, then attend over the
+    materialised K = C_K B_K, V = C_V B_V.  Returns o [B,Hq,d]."""
+    return decode_attn_reconstructed(cache, up_project_q(cQ64, BQ64), BK64, BV64, sm_scale, heads=heads)
+
+
+def fold_qk(BQ64: np.ndarray, BK64: np.ndarray) -> np.ndarray:
+    """M_h = B_Qh B_K,kv(h)^T [Hq,rq,r]: q_h K^T = c_Qh B_Qh B_K^T C_K^T = (c_Qh M_h) C_K^T, an offline product."""
+    Hq, Hkv = BQ64.shape[0], BK64.shape[0]
+    G = Hq // Hkv
+    return np.stack([BQ64[h] @ BK64[h // G].T for h in range(Hq)])
+
+
+def fold_vo(BV64: np.ndarray, WO64: np.ndarray, n_q_heads: int) -> np.ndarray:
+    """W'_O [E, Hq*r] with W'_O[:, h*r + j] = sum_c B_V,kv(h)[j,c] W_O[:, h*d + c]: the V up-projection fused into the
+    output projection (Section 3.4, following Palu), so that y = W_O o = W'_O u with u the latent-space output.
+    W_O is [E, Hq*d] (one row per output channel)."""
+    Hkv, r, d = BV64.shape
+    G = n_q_heads // Hkv
+    E = WO64.shape[0]
+    out = np.zeros((E, n_q_heads * r))
+    for h in range(n_q_heads):
+        out[:, h * r:(h + 1) * r] = WO64[:, h * d:(h + 1) * d] @ BV64[h // G].T
+    return out
+
+
+def decode_attn_latent_out(cache: LatentCache, cQ64: np.ndarray, M64: np.ndarray, sm_scale: float, heads=None) -> np.ndarray:
+    """The regrouped attention that goes with the two folds: scores sm_scale * C_K (c_Qh M_h)^T, softmax, and the
+    weighted sum of VALUE LATENTS u_h = p^T C_Vh [B,Hq,r]; B_V is never applied (it lives in W'_O)."""
+    B, Hq, _ = cQ64.shape
+    G = Hq // cache.Hkv
+    r = cache.r
+    out = np.full((B, Hq, r), np.nan) if heads is not None else np.zeros((B, Hq, r))
+    pairs = heads if heads is not None else [(b, h) for b in range(B) for h in range(Hq)]
+    for (b, h) in pairs:
+        n = int(cache.seq_lens[b]); kv = h // G
+        if n == 0:
+            out[b, h] = 0.0
+            continue
+        qt = cQ64[b, h] @ M64[h]                                     # [r]
+        s = sm_scale * (dequant_cache_rows(cache, "k", b, kv, n) @ qt)
+        out[b, h] = softmax_weights(s) @ dequant_cache_rows(cache, "v", b, kv, n)
+    return out
+
+
+def quantize_w4_rows(W64: np.ndarray):
+    """Round-to-nearest per-output-channel symmetric int4 (Section 4.2): rows are output channels.
+    a = max|w| of the row; a == 0 -> scale 1, codes 0; else s = fp16(a / 7) (guarded), code = clamp(rint(w / float(s)), -7, 7).
+    Returns (codes int8 [N,K], scale fp16 [N])."""
+    W32 = np.asarray(W64, dtype=np.float32)
+    a = np.max(np.abs(W32), axis=-1)
+    s16 = _guard_scale_f16(a / np.float32(7.0))
+    s16 = np.where(a == 0, np.float16(1.0), s16).astype(np.float16)
+    codes = np.clip(np.rint(W32 / s16.astype(np.float32)[:, None]), -7, 7).astype(np.int8)
+    return codes, s16
+
+
+def rmsnorm(x64: np.ndarray, g64: np.ndarray, eps: float) -> np.ndarray:
+    """x / sqrt(mean(x^2) + eps) * g over the last axis (the pre-norm of a LLaMA-type decoder layer)."""
+    return x64 / np.sqrt(np.mean(x64 * x64, axis=-1, keepdims=True) + eps) * g64
+
+
+def silu(x64: np.ndarray) -> np.ndarray:
+    return x64 / (1.0 + np.exp(-x64))
+
+
+def decoder_layer_w4a8(cache: LatentCache, x32: np.ndarray, g1, g2, wqkv_packed, wqkv_scale16, M64,
+                       wo_packed, wo_scale16, wgu_packed, wgu_scale16, wd_packed, wd_scale16,
+                       n_q_heads: int, rq: int, sm_scale: float, eps: float = 1e-5):
+    """One pre-norm decoder layer of the paper's decoding pipeline in the quantised setting of Section 4.2
+    (int4 weights per output channel, int8 activations per token, exact integer sums):
+
+      h1 = rmsnorm(x) g1                       -> int8 per token
+      [c_Q | c_K | c_V] = W4A8(h1, [A_Q; A_K; A_V])      (channels h*rq + j, then kv*r + j twice)
+      c_K, c_V stored as row seq_lens[b] of the cache (the cache's own quantiser), seq_lens += 1
+      u = decode_attn_latent_out(cache, c_Q, M)          (c_Q in the fp32 it leaves the projection with)
+      x1 = x + W4A8(int8(u), W'_O)                       (W'_O = the folded output projection, [E, Hq*r])
+      h2 = rmsnorm(x1) g2                      -> int8 per token
+      [gate | up] = W4A8(h2, [W_g; W_u])       a = silu(gate) * up  -> int8 per token
+      x2 = x1 + W4A8(a, W_d)
+
+    The residual stream is fp32 (each sum rounded to fp32).  Returns a dict of every stage."""
+    B, E = x32.shape
+    Hkv, r = cache.Hkv, cache.r
+    f32 = lambda a: np.asarray(a, np.float64).astype(np.float32)
+    res = {}
+    h1 = f32(rmsnorm(x32.astype(np.float64), np.asarray(g1, np.float64), eps))
+    res["h1_codes"], res["h1_scale"] = quantize_act_i8(h1)
+    z = linear_w4a8(res["h1_codes"], res["h1_scale"], wqkv_packed, wqkv_scale16)
+    nq = n_q_heads * rq
+    cQ = z[:, :nq].reshape(B, n_q_heads, rq)
+    cK = z[:, nq:nq + Hkv * r].reshape(B, Hkv, r)
+    cV = z[:, nq + Hkv * r:].reshape(B, Hkv, r)
+    res["cQ"], res["cK"], res["cV"] = cQ, cK, cV
+    for b in range(B):
+        n = int(cache.seq_lens[b])
+        cache.store_rows("k", b, n, cK[b][:, None, :])
+        cache.store_rows("v", b, n, cV[b][:, None, :])
+        cache.seq_lens[b] = n + 1
+    u = decode_attn_latent_out(cache, f32(cQ).astype(np.float64), M64, sm_scale)
+    res["u"] = u
+    res["u_codes"], res["u_scale"] = quantize_act_i8(f32(u.reshape(B, n_q_heads * r)))
+    y = linear_w4a8(res["u_codes"], res["u_scale"], wo_packed, wo_scale16)
+    x1 = f32(x32.astype(np.float64) + f32(y).astype(np.float64))
+    res["y"], res["x1"] = y, x1
+    h2 = f32(rmsnorm(x1.astype(np.float64), np.asarray(g2, np.float64), eps))
+    res["h2_codes"], res["h2_scale"] = quantize_act_i8(h2)
+    gu = linear_w4a8(res["h2_codes"], res["h2_scale"], wgu_packed, wgu_scale16)
+    F = gu.shape[1] // 2
+    a = silu(f32(gu[:, :F]).astype(np.float64)) * f32(gu[:, F:]).astype(np.float64)
+    res["gu"], res["a"] = gu, a
+    res["a_codes"], res["a_scale"] = quantize_act_i8(f32(a))
+    dn = linear_w4a8(res["a_codes"], res["a_scale"], wd_packed, wd_scale16)
+    res["down"] = dn
+    res["x2"] = f32(x1.astype(np.float64) + f32(dn).astype(np.float64))
     return res

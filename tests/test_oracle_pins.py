@@ -422,3 +422,141 @@ def test_rope_attention_against_torch_and_its_invariants(dtype):
     s_regrouped = (np.cos(phi) * Ai + np.sin(phi) * Bi).sum(-1)
     s_def = O.rope_rotate(K, np.arange(nb), base) @ O.rope_rotate(q[b, h], nb - 1, base)
     np.testing.assert_allclose(s_regrouped, s_def, atol=1e-11)
+
+
+# ---- rest of the decoding pipeline: low-rank Q, B_V folded into W_O, the quantised decoder layer ----------
+def _dequant_all(cache, which):
+    B, Hkv, n = cache.B, cache.Hkv, int(cache.seq_lens[0])
+    return np.stack([np.stack([O.dequant_cache_rows(cache, which, b, kv, n) for kv in range(Hkv)]) for b in range(B)])
+
+
+@pytest.mark.parametrize("dtype,G", [("f32", 1), ("i8", 2), ("bf16", 3)])
+def test_lowrank_q_pipeline_against_torch(dtype, G):
+    """q = c_Q B_Q, K = C_K B_K, V = C_V B_V all formed with torch, attention by torch."""
+    rng = np.random.default_rng(21)
+    B, Hkv, n, r, rq, d = 2, 2, 41, 8, 6, 16
+    Hq = Hkv * G
+    cache = _rand_cache(rng, B, Hkv, n, r, dtype)
+    cQ = rng.standard_normal((B, Hq, rq)); BQ = rng.standard_normal((Hq, rq, d))
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    sm = 0.27
+    got = O.decode_attn_lowrank_q(cache, cQ, BQ, BK, BV, sm)
+    t = torch.from_numpy
+    q = torch.einsum("bhj,hjc->bhc", t(cQ), t(BQ))
+    K = torch.einsum("bknr,krc->bknc", t(_dequant_all(cache, "k")), t(BK)).repeat_interleave(G, dim=1)
+    V = torch.einsum("bknr,krc->bknc", t(_dequant_all(cache, "v")), t(BV)).repeat_interleave(G, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(q[:, :, None, :], K, V, scale=sm)[:, :, 0].numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-11, atol=1e-12)
+
+
+def test_folds_reproduce_the_unfolded_pipeline():
+    """W_O applied to the plain attention output == W'_O applied to the latent-space output of the regrouped
+    attention (associativity); the folds themselves against einsum; the latent-space output against torch attention
+    whose values are the latent rows."""
+    rng = np.random.default_rng(22)
+    B, Hkv, G, n, r, rq, d, E = 2, 2, 2, 29, 8, 5, 16, 24
+    Hq = Hkv * G
+    cache = _rand_cache(rng, B, Hkv, n, r, "i8")
+    cQ = rng.standard_normal((B, Hq, rq)); BQ = rng.standard_normal((Hq, rq, d))
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    WO = rng.standard_normal((E, Hq * d))
+    sm = 0.4
+    M = O.fold_qk(BQ, BK); WOf = O.fold_vo(BV, WO, Hq)
+    t = torch.from_numpy
+    kvmap = torch.arange(Hq) // G
+    np.testing.assert_allclose(M, torch.einsum("hjc,hrc->hjr", t(BQ), t(BK)[kvmap]).numpy(), rtol=1e-13, atol=1e-13)
+    ref_f = torch.einsum("ehc,hjc->ehj", t(WO).reshape(E, Hq, d), t(BV)[kvmap]).reshape(E, Hq * r).numpy()
+    np.testing.assert_allclose(WOf, ref_f, rtol=1e-13, atol=1e-13)
+    o = O.decode_attn_lowrank_q(cache, cQ, BQ, BK, BV, sm)
+    u = O.decode_attn_latent_out(cache, cQ, M, sm)
+    np.testing.assert_allclose(u.reshape(B, Hq * r) @ WOf.T, o.reshape(B, Hq * d) @ WO.T, rtol=1e-10, atol=1e-10)
+    # u itself: torch attention with the query c_Q M, keys C_K and VALUES = the latent rows C_V
+    qt = torch.einsum("bhj,hjr->bhr", t(cQ), t(M))
+    CK = t(_dequant_all(cache, "k")).repeat_interleave(G, dim=1); CV = t(_dequant_all(cache, "v")).repeat_interleave(G, dim=1)
+    ref_u = torch.nn.functional.scaled_dot_product_attention(qt[:, :, None, :], CK, CV, scale=sm)[:, :, 0].numpy()
+    np.testing.assert_allclose(u, ref_u, rtol=1e-11, atol=1e-12)
+    # sampled heads and an empty sequence
+    cache.seq_lens[1] = 0
+    part = O.decode_attn_latent_out(cache, cQ, M, sm, heads=[(0, 1), (1, 2)])
+    np.testing.assert_allclose(part[0, 1], u[0, 1], rtol=0, atol=0)
+    assert (part[1, 2] == 0).all() and np.isnan(part[0, 0]).all()
+
+
+def test_int4_weight_quantiser():
+    rng = np.random.default_rng(23)
+    W = rng.standard_normal((9, 40)) * np.exp(rng.standard_normal((9, 1)))
+    W[3] = 0
+    W[4] = 0; W[4, 7] = -3.5                                  # scale fp16(0.5): codes 0 except -7
+    codes, s = O.quantize_w4_rows(W)
+    assert codes.dtype == np.int8 and s.dtype == np.float16 and codes.min() >= -7 and codes.max() <= 7
+    assert (codes[3] == 0).all() and s[3] == 1
+    assert s[4] == np.float16(0.5) and codes[4, 7] == -7 and np.count_nonzero(codes[4]) == 1
+    sf = s.astype(np.float64)[:, None]
+    assert (np.abs(codes * sf - W) <= 0.5 * sf * (1 + 1e-3) + 1e-12).all()          # round to nearest
+    for i in range(9):                                       # the largest entry of a row maps to +-7
+        if i != 3:
+            assert abs(int(codes[i, np.argmax(np.abs(W[i]))])) == 7
+    np.testing.assert_array_equal(O.quantize_w4_rows(-W)[0], -codes)           # symmetric
+    np.testing.assert_array_equal(O.unpack_w4(O.pack_w4(codes)), codes)
+
+
+def test_rmsnorm_and_silu_against_torch():
+    rng = np.random.default_rng(24)
+    x = rng.standard_normal((5, 48)) * 3; g = rng.standard_normal(48)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x), (48,), torch.from_numpy(g), eps=1e-5).numpy()
+    np.testing.assert_allclose(O.rmsnorm(x, g, 1e-5), ref, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(O.silu(x), torch.nn.functional.silu(torch.from_numpy(x)).numpy(), rtol=1e-13, atol=1e-13)
+    # unit gain, eps = 0: rows come out with mean square exactly 1
+    np.testing.assert_allclose(np.mean(O.rmsnorm(x, np.ones(48), 0.0) ** 2, axis=-1), 1.0, rtol=1e-13)
+
+
+def test_decoder_layer_glue_against_torch():
+    """The layer's order of operations, channel splits, residuals and cache update, re-done with torch linear /
+    rms_norm / silu / attention on de-quantised tensors.  The activation and cache quantisers are the oracle's own
+    (pinned above); what this pins is everything between them."""
+    rng = np.random.default_rng(25)
+    B, Hkv, G, n, r, rq, d, E, F = 3, 2, 2, 23, 8, 8, 16, 32, 48
+    Hq = Hkv * G
+    cache = _rand_cache(rng, B, Hkv, n, r, "i8", t_cap=n + 2)
+    before = (cache.k.copy(), cache.v.copy())
+    x = (rng.standard_normal((B, E)) * 2).astype(np.float32)
+    g1 = 1 + 0.1 * rng.standard_normal(E); g2 = 1 + 0.1 * rng.standard_normal(E)
+    def w4(N, K):
+        c, s = O.quantize_w4_rows(rng.standard_normal((N, K)) / np.sqrt(K))
+        return O.pack_w4(c), s, (c.astype(np.float64) * s.astype(np.float64)[:, None])
+    qkv_p, qkv_s, Wqkv = w4(Hq * rq + 2 * Hkv * r, E)
+    BQ = rng.standard_normal((Hq, rq, d)); BK = rng.standard_normal((Hkv, r, d))
+    M = O.fold_qk(BQ, BK)
+    wo_p, wo_s, Wo = w4(E, Hq * r)
+    gu_p, gu_s, Wgu = w4(2 * F, E)
+    wd_p, wd_s, Wd = w4(E, F)
+    sm, eps = 0.25, 1e-5
+    res = O.decoder_layer_w4a8(cache, x, g1, g2, qkv_p, qkv_s, M, wo_p, wo_s, gu_p, gu_s, wd_p, wd_s, Hq, rq, sm, eps)
+
+    t = torch.from_numpy
+    lin = torch.nn.functional.linear
+    fq = lambda a: (lambda c, s: t(c.astype(np.float64) * s.astype(np.float64)[:, None]))(*O.quantize_act_i8(np.asarray(a, np.float32)))
+    f32 = lambda a: a.to(torch.float32).to(torch.float64)
+    X = t(x.astype(np.float64))
+    h1 = fq(f32(torch.nn.functional.rms_norm(X, (E,), t(g1), eps=eps)).numpy())
+    z = lin(h1, t(Wqkv))
+    cQ = z[:, :Hq * rq].reshape(B, Hq, rq); cK = z[:, Hq * rq:Hq * rq + Hkv * r].reshape(B, Hkv, r); cV = z[:, Hq * rq + Hkv * r:].reshape(B, Hkv, r)
+    np.testing.assert_allclose(res["cQ"], cQ.numpy(), rtol=1e-12, atol=1e-12)
+    # cache: old rows untouched, row n = the cache quantiser applied to the new latents, lengths advanced
+    assert (cache.seq_lens == n + 1).all()
+    assert (cache.k[:, :, :n] == before[0][:, :, :n]).all() and (cache.v[:, :, :n] == before[1][:, :, :n]).all()
+    kc, ks = O.quantize_int8_rows(cK.numpy().astype(np.float32)); vc, vs = O.quantize_int8_rows(cV.numpy().astype(np.float32))
+    assert (cache.k[:, :, n] == kc).all() and (cache.k_scale[:, :, n] == ks).all()
+    assert (cache.v[:, :, n] == vc).all() and (cache.v_scale[:, :, n] == vs).all()
+    CK = t(_dequant_all(cache, "k")).repeat_interleave(G, dim=1); CV = t(_dequant_all(cache, "v")).repeat_interleave(G, dim=1)
+    qt = torch.einsum("bhj,hjr->bhr", f32(cQ), t(M))
+    u = torch.nn.functional.scaled_dot_product_attention(qt[:, :, None, :], CK, CV, scale=sm)[:, :, 0]
+    np.testing.assert_allclose(res["u"], u.numpy(), rtol=1e-10, atol=1e-11)
+    x1 = f32(X + f32(lin(fq(u.reshape(B, Hq * r).numpy()), t(Wo))))
+    np.testing.assert_allclose(res["x1"], x1.numpy(), rtol=1e-6, atol=1e-6)
+    h2 = fq(f32(torch.nn.functional.rms_norm(x1, (E,), t(g2), eps=eps)).numpy())
+    gu = lin(h2, t(Wgu))
+    a = torch.nn.functional.silu(f32(gu[:, :F])) * f32(gu[:, F:])
+    x2 = f32(x1 + f32(lin(fq(a.numpy()), t(Wd))))
+    np.testing.assert_allclose(res["x2"], x2.numpy(), rtol=1e-6, atol=1e-6)
+    assert np.abs(res["x2"] - x).max() > 0.1           # the layer does something
