@@ -225,6 +225,44 @@ wsvd_status wsvd_cache_export(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_
                               void *hip_stream);
 
 /*
+ * The rest of the decoding pipeline (Section 3.4, decoding-pipeline figure): the query is per-head low-rank too, and
+ * the V-path up-projection is fused into the output projection.
+ *
+ * wsvd_fold_qk: M_h = B_Q,h B_K,kv(h)^T, so that q_h K^T = (c_Q,h M_h) C_K^T.  Set-up, once per model.
+ *   B_Q [Hq, rq, d] and B_K [Hkv, r, d] of desc->factor_dtype (DEVICE); out [Hq, rq, r] F32 (DEVICE).  1 <= rq <= 64.
+ * wsvd_fold_vo: W'_O[:, h r + j] = sum_c B_V,kv(h)[j, c] W_O[:, h d + c], so that W_O o = W'_O u with u the latent-space
+ *   attention output.  Set-up, once per model.  B_V [Hkv, r, d] of desc->factor_dtype; W_O [E, Hq d] F32, one row per
+ *   output channel; out [E, Hq r] F32.  All DEVICE pointers.
+ * wsvd_decode_attn_latent: the attention that goes with the two folds.  c_Q [B, Hq, rq] F32 is the Q latent as it leaves
+ *   its down-projection, qk_fold the output of wsvd_fold_qk; scores sm_scale * C_K (c_Q M)^T, softmax, and
+ *   u_out[b, h, :] = p^T C_V [B, Hq, r] F32 (zeros for an empty sequence).  B_K and B_V are not read.
+ *   I8 or I4 latents, at most 4 query heads per kv head (WSVD_E_UNSUPPORTED otherwise); desc->q_dtype is ignored.
+ *   Pointers DEVICE, 16-byte aligned; max_seq_len, workspace, stream and error behaviour as wsvd_decode_attn.
+ */
+wsvd_status wsvd_fold_qk(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *B_Q, int32_t rq, const void *B_K, void *out,
+                         void *hip_stream);
+wsvd_status wsvd_fold_vo(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *B_V, const void *W_O, void *out,
+                         void *hip_stream);
+wsvd_status wsvd_decode_attn_latent(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *c_Q, int32_t rq,
+                                    const void *qk_fold, const wsvd_cache *cache, int32_t max_seq_len, void *u_out,
+                                    void *hip_stream);
+
+/*
+ * Row kernels of a pre-norm decoder layer in the quantised setting of Section 4.2 (activations per-token symmetric
+ * int8, same rounding rules as wsvd_quantize_act_i8).  rows <= any, cols / F multiples of 4 and <= 16384; DEVICE
+ * pointers, 16-byte aligned.
+ * wsvd_rmsnorm_quant_i8: r = x (+ y_add); if y_add is given the sum is written to x_out [rows, cols] F32 (the
+ *   residual stream; x_out may alias x); h = r / sqrt(mean(r^2) + eps) * gain; h -> codes int8 [rows, cols], scale fp16
+ *   [rows].  x, y_add [rows, cols] F32, gain [cols] F32.
+ * wsvd_swiglu_quant_i8: gate_up [rows, 2F] F32 with the gate in columns [0, F) and the up branch in [F, 2F);
+ *   a = silu(gate) * up -> codes int8 [rows, F], scale fp16 [rows].
+ */
+wsvd_status wsvd_rmsnorm_quant_i8(wsvd_ctx *ctx, const void *x, const void *y_add, const void *gain, float eps, int64_t rows,
+                                  int64_t cols, void *x_out, int8_t *codes, void *scale_f16, void *hip_stream);
+wsvd_status wsvd_swiglu_quant_i8(wsvd_ctx *ctx, const void *gate_up, int64_t rows, int64_t F, int8_t *codes, void *scale_f16,
+                                 void *hip_stream);
+
+/*
  * Measurement aid, not part of the method: a kernel that only READS `bytes` bytes (DEVICE pointer, 16-byte
  * aligned) with `workgroups` workgroups of 512 threads, each streaming one contiguous share.  Benchmarks run it
  * over the buffers the attention streams to report what a pure reader reaches on the same data.

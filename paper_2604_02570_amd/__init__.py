@@ -26,7 +26,8 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
            "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
-           "wsvd_linear_w4a8_split", "wsvd_probe_stream_read"]
+           "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
+           "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8"]
 
 
 class WsvdError(RuntimeError):
@@ -89,6 +90,13 @@ def lib():
         L.wsvd_linear_w4a8_split.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
                                              c_int64, c_void_p, c_void_p, c_int32, c_void_p]
         L.wsvd_probe_stream_read.argtypes = [c_void_p, c_void_p, c_size_t, c_int32, c_void_p]
+        L.wsvd_fold_qk.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
+        L.wsvd_fold_vo.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p]
+        L.wsvd_decode_attn_latent.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_void_p, POINTER(Cache), c_int32,
+                                              c_void_p, c_void_p]
+        L.wsvd_rmsnorm_quant_i8.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_float, c_int64, c_int64, c_void_p,
+                                            c_void_p, c_void_p, c_void_p]
+        L.wsvd_swiglu_quant_i8.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
         for name in EXPORTS:
             if name not in ("wsvd_status_str",):
                 getattr(L, name).restype = c_int
@@ -231,6 +239,29 @@ def wsvd_quantize_act_i8(ctx, x, x_dtype, rows, cols, codes, scale, stream=None)
 def wsvd_linear_w4a8(ctx, x, x_scale, w_i4, w_scale, M, K, N, out, stream=None):
     _ck(lib().wsvd_linear_w4a8(ctx, _ptr(x), _ptr(x_scale), _ptr(w_i4), _ptr(w_scale), int(M), int(K), int(N),
                                _ptr(out), F32, _stream(stream)), "wsvd_linear_w4a8")
+
+
+def wsvd_fold_qk(ctx, desc, B_Q, rq, B_K, out, stream=None):
+    _ck(lib().wsvd_fold_qk(ctx, byref(desc), _ptr(B_Q), int(rq), _ptr(B_K), _ptr(out), _stream(stream)), "wsvd_fold_qk")
+
+
+def wsvd_fold_vo(ctx, desc, B_V, W_O, out, stream=None):
+    _ck(lib().wsvd_fold_vo(ctx, byref(desc), _ptr(B_V), _ptr(W_O), _ptr(out), _stream(stream)), "wsvd_fold_vo")
+
+
+def wsvd_decode_attn_latent(ctx, desc, c_Q, rq, qk_fold, cache, max_seq_len, u_out, stream=None):
+    _ck(lib().wsvd_decode_attn_latent(ctx, byref(desc), _ptr(c_Q), int(rq), _ptr(qk_fold), byref(cache), int(max_seq_len),
+                                      _ptr(u_out), _stream(stream)), "wsvd_decode_attn_latent")
+
+
+def wsvd_rmsnorm_quant_i8(ctx, x, y_add, gain, eps, rows, cols, x_out, codes, scale, stream=None):
+    _ck(lib().wsvd_rmsnorm_quant_i8(ctx, _ptr(x), _ptr(y_add), _ptr(gain), float(eps), int(rows), int(cols), _ptr(x_out),
+                                    _ptr(codes), _ptr(scale), _stream(stream)), "wsvd_rmsnorm_quant_i8")
+
+
+def wsvd_swiglu_quant_i8(ctx, gate_up, rows, F, codes, scale, stream=None):
+    _ck(lib().wsvd_swiglu_quant_i8(ctx, _ptr(gate_up), int(rows), int(F), _ptr(codes), _ptr(scale), _stream(stream)),
+        "wsvd_swiglu_quant_i8")
 
 
 def wsvd_linear_w4a8_split(ctx, x, x_scale, w_i4, w_scale, M, K, N, n_first, out_first, out_rest, stream=None):

@@ -336,6 +336,75 @@ wsvd_status wsvd_cache_export(wsvd_ctx* ctx, const wsvd_layer_desc* desc, int32_
   return cache_copy(false, ctx, desc, which_plane, codes, meta, t0, n_rows, cache, hip_stream);
 }
 
+wsvd_status wsvd_decode_attn_latent(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* c_Q, int32_t rq, const void* qk_fold,
+                                    const wsvd_cache* cache, int32_t max_seq_len, void* u_out, void* hip_stream) {
+  if (!ctx || !c_Q || !qk_fold || !u_out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (rq < 1 || rq > 64) return WSVD_E_SHAPE;
+  if (!aligned16(c_Q) || !aligned16(qk_fold) || !aligned16(u_out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 0) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  const int G = desc->n_q_heads / desc->n_kv_heads;
+  if ((desc->latent_dtype != WSVD_I8 && desc->latent_dtype != WSVD_I4) || G > 4) return WSVD_E_UNSUPPORTED;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  wsvd_layer_desc d = *desc;
+  d.q_dtype = WSVD_F32;                       // the Q latent arrives as the fp32 output of its projection
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, d, c_Q, nullptr, nullptr, nullptr, *cache, max_seq_len, u_out, p, grid, threads, 0);
+  p.qk_fold = (const float*)qk_fold;
+  p.rq = rq;
+  p.out_dim = d.rank;
+  hipError_t e = wsvd_launch_attn_latent(p, d.latent_dtype, d.rank, grid, threads, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_fold_qk(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* B_Q, int32_t rq, const void* B_K, void* out,
+                         void* hip_stream) {
+  if (!ctx || !B_Q || !B_K || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if (rq < 1 || rq > 64) return WSVD_E_SHAPE;
+  hipError_t e = wsvd_launch_fold_qk(B_Q, B_K, desc->factor_dtype, desc->n_q_heads, desc->n_kv_heads, rq, desc->rank, desc->d_head,
+                                     (float*)out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_fold_vo(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* B_V, const void* W_O, void* out, void* hip_stream) {
+  if (!ctx || !B_V || !W_O || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  hipError_t e = wsvd_launch_fold_vo(B_V, desc->factor_dtype, (const float*)W_O, desc->d_model, desc->n_q_heads, desc->n_kv_heads,
+                                     desc->rank, desc->d_head, (float*)out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_rmsnorm_quant_i8(wsvd_ctx* ctx, const void* x, const void* y_add, const void* gain, float eps, int64_t rows,
+                                  int64_t cols, void* x_out, int8_t* codes, void* scale_f16, void* hip_stream) {
+  if (!ctx || !x || !gain || !codes || !scale_f16) return WSVD_E_NULL;
+  if (y_add && !x_out) return WSVD_E_NULL;
+  if (rows < 0 || cols < 4 || cols % 4 != 0 || cols > 16384 || !(eps >= 0.f)) return WSVD_E_SHAPE;
+  if (!aligned16(x) || !aligned16(gain) || !aligned16(codes) || (y_add && (!aligned16(y_add) || !aligned16(x_out)))) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_rmsnorm_quant((const float*)x, (const float*)y_add, (const float*)gain, eps, rows, cols, (float*)x_out,
+                                           codes, scale_f16, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_swiglu_quant_i8(wsvd_ctx* ctx, const void* gate_up, int64_t rows, int64_t F, int8_t* codes, void* scale_f16,
+                                 void* hip_stream) {
+  if (!ctx || !gate_up || !codes || !scale_f16) return WSVD_E_NULL;
+  if (rows < 0 || F < 4 || F % 4 != 0 || F > 16384) return WSVD_E_SHAPE;
+  if (!aligned16(gate_up) || !aligned16(codes)) return WSVD_E_ALIGN;
+  hipError_t e = wsvd_launch_swiglu_quant((const float*)gate_up, rows, F, codes, scale_f16, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_probe_stream_read(wsvd_ctx* ctx, const void* ptr, size_t bytes, int32_t workgroups, void* hip_stream) {
   if (!ctx || !ptr) return WSVD_E_NULL;
   if (!aligned16(ptr)) return WSVD_E_ALIGN;
@@ -396,6 +465,7 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
   p.err_word = ctx->err_word;
   p.B = d.batch; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.d = d.d_head;
+  p.out_dim = d.d_head;
   p.t_cap = d.t_cap;
   p.q_dtype = d.q_dtype; p.factor_dtype = d.factor_dtype;
   const float sm = d.sm_scale != 0.f ? d.sm_scale : 1.0f / sqrtf((float)d.d_head);

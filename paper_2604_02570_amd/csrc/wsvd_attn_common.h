@@ -26,6 +26,11 @@ struct AttnParams {
   // plane by setting flags[h] / flags[Hkv + h] to epoch
   const int* flags;
   int epoch;
+  // latent-query / latent-output variant only: q is the Q latent [B,Hq,rq] fp32, qk_fold the per-head matrices
+  // B_Q B_K^T [Hq,rq,R] fp32, out is [B,Hq,R]
+  const float* qk_fold;
+  int rq;
+  int out_dim;               // floats per (sequence, head) of out: d, or R for the latent-output variant
 };
 
 struct WorkItem {
@@ -55,8 +60,8 @@ WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) { return decode_wo
 // A sequence with no rows: its outputs are zeros (written by the chunk-0 workgroup).
 WSVD_DEV void write_zero_outputs(const AttnParams& p, const WorkItem& w) {
   if (w.chunk != 0) return;
-  for (int i = threadIdx.x; i < p.G * p.d; i += blockDim.x)
-    p.out[((size_t)w.b * p.Hq + w.kv * p.G) * p.d + i] = 0.f;
+  for (int i = threadIdx.x; i < p.G * p.out_dim; i += blockDim.x)
+    p.out[((size_t)w.b * p.Hq + w.kv * p.G) * p.out_dim + i] = 0.f;
 }
 
 // ---- staging of the per-head factors into LDS.
@@ -233,6 +238,12 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       if (j == 0) { Lsh[g] = L; Msh[g] = M; }
     }
     __syncthreads();
+  }
+  if (!bv_lds) {
+    // latent-output variant: the normalised accumulator itself (B_V lives in the output projection)
+    for (int i = tid; i < G * R; i += blockDim.x)
+      p.out[((size_t)w.b * p.Hq + w.kv * G) * R + i] = Ush[i] / Lsh[i / R];
+    return;
   }
   // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c], B_V[kv] staged in LDS.
   // Four adjacent lanes share an output (a quarter of the latent dims each) and add up through DPP, which keeps

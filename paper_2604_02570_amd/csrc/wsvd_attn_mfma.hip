@@ -175,12 +175,13 @@ WSVD_DEV void split_fp16_pair(float x, float scale, _Float16& hi, _Float16& lo) 
 // very moment.  The row counts as present; the 64-row tile that contains it is kept out of the streaming loop and
 // done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
 // ROPE_D != 0: the rotary variant for head dimension ROPE_D (I8 latents; rs, ra non-null).
-template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0>
+template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0, bool LATENT = false>
 WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, const int cx, const int cy, const int cz,
                              RopeShared<R, G, (ROPE_D ? ROPE_D : 64)>* rs = nullptr, const RopeArgs* ra = nullptr) {
   constexpr bool ROPE = ROPE_D != 0;
   using RG = RopeGeom<(ROPE_D ? ROPE_D : 64)>;
   static_assert(!ROPE || (!I4 && !FUSED), "rotary variant: int8 latents, stand-alone launch");
+  static_assert(!LATENT || (!ROPE && !FUSED), "latent-query variant: stand-alone launch, no rotation");
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
@@ -209,9 +210,37 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   const int fac16 = R * p.d * 2 / 16;
   StageRegs<FIT> stk, stv;
   QRegs qr;
+  // LATENT: q~[g][j] = sum_i c_Q[g][i] (B_Q B_K^T)[h][i][j].  Work item (quarter of the i range, g, j), j fastest so
+  // that a wave's loads of the fold are contiguous; up to 16 products per item, the quarters meet in LDS.
+  constexpr int LQ = 16;                               // rq <= 64
+  constexpr int NLP = LATENT ? (4 * G * R + 255) / 256 : 1;   // passes at the smallest workgroup (256 threads)
+  float lat_part[NLP];
+  if constexpr (LATENT) {
+    const int qn = (p.rq + 3) >> 2;                    // i values per quarter
+#pragma unroll
+    for (int ps = 0; ps < NLP; ps++) {
+      const int item = min(tid + ps * (int)blockDim.x, 4 * G * R - 1);
+      const int j = item % R, g = (item / R) % G, part = item / (R * G);
+      const int h = cx * G + g;
+      const float* cq = (const float*)p.q + ((size_t)cz * p.Hq + h) * p.rq;
+      const float* fold = p.qk_fold + (size_t)h * p.rq * R + j;
+      float mv[LQ], cv[LQ];
+#pragma unroll
+      for (int ii = 0; ii < LQ; ii++) {
+        const int i = min(part * qn + ii, p.rq - 1);   // clamped: surplus slots are masked below
+        mv[ii] = fold[(size_t)i * R];
+        cv[ii] = cq[i];
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int ii = 0; ii < LQ; ii++) acc = (ii < qn && part * qn + ii < p.rq) ? fmaf(cv[ii], mv[ii], acc) : acc;
+      lat_part[ps] = acc;
+    }
+  } else {
   stage_issue<FIT>(stk, (const char*)p.BK + (size_t)cx * R * p.d * 2, fac16);
   stage_issue<FIT>(stv, (const char*)p.BV + (size_t)cx * R * p.d * 2, fac16);
   q_issue(p, cz, cx, qr);
+  }
   constexpr int DEPTH = 2;   // deeper prefetch costs registers and measured slower
   TileRegs<R, I4> buf[DEPTH];
   const int chunk_tiles = p.chunk_rows >> 6;
@@ -224,9 +253,20 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   }
 
   // ---- query absorption and its limbs
+  if constexpr (LATENT) {
+    float* qpart = (float*)bk_lds;       // [4][G*R] partial sums (B_K is not staged in this variant)
+#pragma unroll
+    for (int ps = 0; ps < NLP; ps++) {
+      const int item = tid + ps * (int)blockDim.x;
+      if (item < 4 * G * R) qpart[item] = lat_part[ps];
+    }
+    __syncthreads();
+    if (tid < G * R) qts[tid] = (qpart[tid] + qpart[G * R + tid] + qpart[2 * G * R + tid] + qpart[3 * G * R + tid]) * p.c_scale;
+  } else {
   stage_commit<FIT>(stk, bk_lds, fac16);
   stage_commit<FIT>(stv, bv_lds, fac16);
   q_commit(p, qr, 1.f, q_lds);          // an int8 query's scale is applied to delta below
+  }
   __syncthreads();
   if constexpr (ROPE) {
     constexpr int Dh = ROPE_D / 2;
@@ -289,7 +329,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     }
     if (tid < G) qdelta[tid] = 1.f;
   } else {
-  compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
+  if constexpr (!LATENT) compute_qtilde<R, 2>(p, bk_lds, q_lds, qts);
   if (tid < G * R) {
     const int g = tid / R, j = tid % R;
     const float v = qts[tid];
@@ -591,7 +631,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       for (int jj = 0; jj < KK; jj++) wu[wave][g][jj * 32 + lane] = u[g][jj] - zc;
     }
   }
-  if (w.n_splits == 1) {
+  if (w.n_splits == 1 && !LATENT) {
     // Whole sequence in this workgroup.  Each wave applies B_V to its own accumulator as soon as it is done
     // (o_w = u_w B_V, two adjacent head-dim columns per lane), while slower waves are still streaming; after the
     // barrier only a short weighted sum over the waves is left.
@@ -648,13 +688,21 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     if (j == 0) { Msh[g] = M; Lsh[g] = L; }
   }
   __syncthreads();
-  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, bv_lds);
+  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, LATENT ? nullptr : (const void*)bv_lds);
 }
 
 template <int R, int G, bool I4, int NT>
 __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   __shared__ AttnMfmaShared<R, G, NT> sh;
   attn_mfma_body<R, G, I4, NT, false>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Q latent in, latent-space output out (Section 3.4: the Q latent's up-projection B_Q meets B_K^T in one small matrix
+// per head, and B_V is fused into the output projection): no factor is staged at all.
+template <int R, int G, bool I4, int NT>
+__global__ __launch_bounds__(NT) void k_attn_mfma_latent(AttnParams p) {
+  __shared__ AttnMfmaShared<R, G, NT> sh;
+  attn_mfma_body<R, G, I4, NT, false, 0, true>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // ---------------------------------------------------------------- 5 to 8 query heads per kv head (I8 latents)
@@ -984,6 +1032,28 @@ static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStrea
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int R, bool I4, int NT>
+static hipError_t launch_m_latent(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
+  if (threads > NT || threads % 64 || threads < 256) return hipErrorInvalidValue;
+  switch (p.G) {
+    case 1: hipLaunchKernelGGL((k_attn_mfma_latent<R, 1, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((k_attn_mfma_latent<R, 2, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 3: hipLaunchKernelGGL((k_attn_mfma_latent<R, 3, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((k_attn_mfma_latent<R, 4, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    default: return hipErrorNotSupported;
+  }
+  return hipGetLastError();
+}
+
+// Latent-query / latent-output attention: int8 or int4 latents, up to 4 query heads per kv head, rq <= 64.
+hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (p.rq < 1 || p.rq > 64 || !p.qk_fold) return hipErrorInvalidValue;
+  if (latent_dtype == WSVD_I8 && rank == 32) return launch_m_latent<32, false, 1024>(p, grid, threads, s);
+  if (latent_dtype == WSVD_I8 && rank == 64) return launch_m_latent<64, false, 512>(p, grid, threads, s);
+  if (latent_dtype == WSVD_I4 && rank == 32) return launch_m_latent<32, true, 1024>(p, grid, threads, s);
+  return hipErrorNotSupported;
 }
 
 // largest workgroup (threads) each instantiation may be launched with

@@ -43,6 +43,14 @@ bool wsvd_append_uses_mfma(const wsvd_layer_desc& d);
 hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
                                  const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, double rope_base,
                                  void* out, hipStream_t s);
+hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s);
+hipError_t wsvd_launch_rmsnorm_quant(const float* x, const float* y_add, const float* gain, float eps, int64_t rows,
+                                     int64_t cols, float* x_out, int8_t* codes, void* scale_f16, hipStream_t s);
+hipError_t wsvd_launch_swiglu_quant(const float* gate_up, int64_t rows, int64_t F, int8_t* codes, void* scale_f16, hipStream_t s);
+hipError_t wsvd_launch_fold_qk(const void* BQ, const void* BK, int factor_dtype, int Hq, int Hkv, int rq, int r, int d, float* out,
+                               hipStream_t s);
+hipError_t wsvd_launch_fold_vo(const void* BV, int factor_dtype, const float* WO, int E, int Hq, int Hkv, int r, int d, float* out,
+                               hipStream_t s);
 // hipErrorNotSupported when there is no fused kernel for the combination
 hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
                                    const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,

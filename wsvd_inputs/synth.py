@@ -4,10 +4,11 @@ import dataclasses
 import numpy as np
 
 __all__ = ["Spec", "SPECS", "spec", "rng", "normal", "bf16_exact", "outlier_sigma", "factors",
-           "hidden_states", "latents_from_law", "ragged_lengths", "dense_wq", "int4_weight"]
+           "hidden_states", "latents_from_law", "ragged_lengths", "dense_wq", "int4_weight", "lowrank_q_factors",
+           "norm_gains"]
 
 # stream ids (second Philox key word)
-_S_AK, _S_AV, _S_BK, _S_BV, _S_WQ, _S_X, _S_XNEW, _S_LAT, _S_LEN, _S_OUT, _S_W4, _S_WO = range(1, 13)
+_S_AK, _S_AV, _S_BK, _S_BV, _S_WQ, _S_X, _S_XNEW, _S_LAT, _S_LEN, _S_OUT, _S_W4, _S_WO, _S_AQ, _S_BQ, _S_GAIN = range(1, 16)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -142,3 +143,16 @@ def int4_weight(sp: Spec, n_out: int, which: int, layer: int = 0):
     codes = np.clip(np.rint(g.standard_normal((n_out, sp.d_model), dtype=np.float32) * 2.5), -8, 7).astype(np.int8)
     scale = ((sp.d_model ** -0.5) / 2.5 * (0.75 + 0.5 * g.random(n_out, dtype=np.float32))).astype(np.float16)
     return codes, scale
+
+
+def lowrank_q_factors(sp: Spec, rq: int, layer: int = 0):
+    """Per-head low-rank query factors: A_Q [Hq,E,rq] ~ N(0,1/E) and B_Q [Hq,rq,d] ~ N(0,1/rq), fp32 (B_Q bf16-exact when
+    the factors are bf16), so that q = x A_Q B_Q has unit-variance entries like the dense query."""
+    AQ = normal(sp.seed, _S_AQ, (sp.n_q_heads, sp.d_model, rq), sp.d_model ** -0.5, sub=layer)
+    BQ = normal(sp.seed, _S_BQ, (sp.n_q_heads, rq, sp.d_head), rq ** -0.5, sub=layer)
+    return AQ, _as_dtype(BQ, sp.factor_dtype)
+
+
+def norm_gains(sp: Spec, which: int, layer: int = 0) -> np.ndarray:
+    """RMSNorm gain [E] = 1 + 0.1 N(0,1), fp32."""
+    return (1.0 + normal(sp.seed, _S_GAIN, (sp.d_model,), 0.1, sub=layer * 4 + which)).astype(np.float32)
