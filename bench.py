@@ -45,10 +45,12 @@ def parse():
     ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
-    ap.add_argument("--workload", choices=["c3", "c4", "c5"], default="c3",
+    ap.add_argument("--workload", choices=["c3", "c4", "c5", "layer"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
-                         "c5: the 28-layer grouped-query W4A8 attention block (secondary lines, same JSON shape)")
+                         "c5: the 28-layer grouped-query W4A8 attention block; "
+                         "layer: 32 quantised decoder layers of the decoding pipeline at the c3 shape (low-rank Q, B_V folded "
+                         "into W_O, SwiGLU FFN) (secondary lines, same JSON shape)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -73,6 +75,8 @@ def main():
         W.wsvd_set_option("max_threads", args.max_threads)
     if args.workload == "c5":
         return run_c5(args, np, torch, W, WI)
+    if args.workload == "layer":
+        return run_layer(args, np, torch, W, WI)
 
     sp = WI.spec(args.workload)
     i4 = sp.latent_dtype == "i4"
@@ -461,6 +465,154 @@ def run_c5(args, np, torch, W, WI):
         "roofline": {"kernel": "k_attn_gqa<64> (decode attention, 7 query heads per kv head, int8 latents)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES_C5,
+                     "algorithmic_bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 3)},
+    }
+    print(json.dumps(res))
+    W.wsvd_destroy(ctx)
+
+
+def run_layer(args, np, torch, W, WI):
+    """32 decoder layers of the paper's decoding pipeline (Section 3.4) in the quantised setting of Section 4.2, at the
+    batched int8 workload's shape (16 sequences, 32 heads, head dim 128, d_model 4096, rank 32 for Q, K and V, 2048 rows
+    of context, FFN 11008).  Per layer, 10 launches: [residual add +] RMSNorm -> int8; one W4A8 projection over the
+    stacked [A_Q; A_K; A_V]; latent store; attention from the Q latent to the latent-space output; int8; W4A8 W'_O
+    (B_V folded in); residual add + RMSNorm -> int8; W4A8 [W_g; W_u]; SiLU * up -> int8; W4A8 W_d.  Every layer has its
+    own cache (73.5 MB) and weights (76 MB int4) in HBM.  Weights are random int4 codes drawn on the device (their
+    values do not affect timing); layer 0's cache goes through the library's quantiser and is cloned."""
+    sp = WI.spec("c3")
+    B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
+    rq, F, NL = r, 11008, 32
+    steps = args.steps if args.steps != 320 else 20
+    warmup = args.warmup if args.warmup != 32 else 3
+    total = steps + warmup
+    T0 = T - 1
+    t_cap = (T0 + total + 63) // 64 * 64
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "f32", "f32", 0.0)
+    ctx = W.wsvd_create(0)
+    ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(ctx, ws)
+    cb, mb = W.wsvd_cache_bytes(desc)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    bf16_bits = lambda x32: dev((np.ascontiguousarray(x32, np.float32).view(np.uint32) >> 16).astype(np.uint16).view(np.int16))
+    AK, AV, BK, BV = WI.factors(sp)
+    _, BQ = WI.lowrank_q_factors(sp, rq)
+    M = torch.empty((Hq, rq, r), dtype=torch.float32, device="cuda")
+    W.wsvd_fold_qk(ctx, desc, bf16_bits(BQ), rq, bf16_bits(BK), M)
+    k0 = torch.zeros(cb, dtype=torch.uint8, device="cuda"); v0 = torch.zeros(cb, dtype=torch.uint8, device="cuda")
+    km0 = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm0 = torch.zeros(mb, dtype=torch.uint8, device="cuda")
+    sl0 = torch.full((B,), T0, dtype=torch.int32, device="cuda")
+    cache0 = W.make_cache(k0, v0, km0, vm0, sl0)
+    for which, A, plane in (("k", AK, 0), ("v", AV, 1)):
+        latd = dev(np.stack([WI.latents_from_law(sp, A, which, b, T0) for b in range(B)]))
+        codes = torch.empty((B * Hkv * T0, r), dtype=torch.int8, device="cuda")
+        meta = torch.empty(B * Hkv * T0, dtype=torch.int16, device="cuda")
+        W.wsvd_quantize_rows(ctx, desc, latd, B * Hkv * T0, codes, meta)
+        W.wsvd_cache_import(ctx, desc, plane, codes, meta, 0, T0, cache0)
+        del latd, codes, meta
+    assert W.wsvd_check(ctx) == 0
+    gen = torch.Generator(device="cuda"); gen.manual_seed(sp.seed)
+
+    def w4(n_out, k_in):   # random nibbles, fp16 scale per output channel such that code * scale has std ~ k_in^-1/2
+        codes = torch.randint(0, 256, (n_out, k_in // 2), dtype=torch.uint8, device="cuda", generator=gen)
+        scale = torch.full((n_out,), float(k_in ** -0.5 / 4.6), dtype=torch.float16, device="cuda")
+        return codes, scale.view(torch.int16)
+
+    n_qkv = Hq * rq + 2 * Hkv * r
+    layers = []
+    for l in range(NL):
+        t = (k0, v0, km0, vm0, sl0) if l == 0 else tuple(x.clone() for x in (k0, v0, km0, vm0, sl0))
+        layers.append(dict(t=t, cache=W.make_cache(*t), qkv=w4(n_qkv, E), wo=w4(E, Hq * r), gu=w4(2 * F, E), wd=w4(E, F),
+                           g1=dev(WI.norm_gains(sp, 0, l)), g2=dev(WI.norm_gains(sp, 1, l))))
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    i8 = lambda *s: torch.empty(s, dtype=torch.int8, device="cuda")
+    i16 = lambda *s: torch.empty(s, dtype=torch.int16, device="cuda")
+    x0 = dev(WI.hidden_states(sp, B, 1.0, which="new").astype(np.float32))
+    xr = f32(B, E)
+    hq, hs = i8(B, E), i16(B)
+    cq, lat, u = f32(B, Hq * rq), f32(B, 2 * Hkv * r), f32(B, Hq, r)
+    uq, us = i8(B, Hq * r), i16(B)
+    y, gu, down = f32(B, E), f32(B, 2 * F), f32(B, E)
+    aq, asc = i8(B, F), i16(B)
+
+    def step(attn_only=args.attn_only):
+        for l, Ly in enumerate(layers):
+            if attn_only:
+                W.wsvd_decode_attn_latent(ctx, desc, cq, rq, M, Ly["cache"], t_cap, u)
+                continue
+            if l == 0:
+                W.wsvd_rmsnorm_quant_i8(ctx, x0, None, Ly["g1"], 1e-5, B, E, None, hq, hs)
+            else:
+                W.wsvd_rmsnorm_quant_i8(ctx, xr, down, Ly["g1"], 1e-5, B, E, xr, hq, hs)
+            W.wsvd_linear_w4a8_split(ctx, hq, hs, Ly["qkv"][0], Ly["qkv"][1], B, E, n_qkv, Hq * rq, cq, lat)
+            W.wsvd_latent_store(ctx, desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, Ly["cache"])
+            W.wsvd_decode_attn_latent(ctx, desc, cq, rq, M, Ly["cache"], t_cap, u)
+            W.wsvd_quantize_act_i8(ctx, u, W.F32, B, Hq * r, uq, us)
+            W.wsvd_linear_w4a8(ctx, uq, us, Ly["wo"][0], Ly["wo"][1], B, Hq * r, E, y)
+            W.wsvd_rmsnorm_quant_i8(ctx, x0 if l == 0 else xr, y, Ly["g2"], 1e-5, B, E, xr, hq, hs)
+            W.wsvd_linear_w4a8(ctx, hq, hs, Ly["gu"][0], Ly["gu"][1], B, E, 2 * F, gu)
+            W.wsvd_swiglu_quant_i8(ctx, gu, B, F, aq, asc)
+            W.wsvd_linear_w4a8(ctx, aq, asc, Ly["wd"][0], Ly["wd"][1], B, F, E, down)
+
+    stream = torch.cuda.Stream()
+    use_graph = not args.no_graph
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            step()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for _ in range(steps):
+                    step()
+            stream.synchronize()
+            e0.record(stream); g.replay(); e1.record(stream)
+        else:
+            e0.record(stream)
+            for _ in range(steps):
+                step()
+            e1.record(stream)
+        stream.synchronize()
+        ms_total = e0.elapsed_time(e1)
+        assert W.wsvd_check(ctx, stream) == 0
+        rows_end = int(layers[0]["t"][4][0])
+        assert rows_end == T0 + (0 if args.attn_only else total), (rows_end, T0, total)
+        assert torch.isfinite(xr).all() or args.attn_only
+        n_rep = 3
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        step(True); stream.synchronize()
+        a0.record(stream)
+        for _ in range(n_rep):
+            step(True)
+        a1.record(stream); stream.synchronize()
+        attn_us = a0.elapsed_time(a1) * 1e3 / (n_rep * NL)
+        assert torch.isfinite(u).all()
+    row_bytes = Hkv * 2 * (r + 2)
+    rows_mean = T0 + warmup + (steps + 1) / 2
+    ms_per_step = ms_total / steps
+    value = NL * B * rows_mean * row_bytes / (ms_per_step * 1e-3) / 1e9
+    attn_bytes = B * rows_end * row_bytes
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    weight_bytes = (n_qkv * E + E * Hq * r + 2 * F * E + E * F) // 2
+    res = {
+        "metric": "latent_kv_hbm_GBps_per_decode_step", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 6),
+        "us_per_decode_step": round(ms_per_step * 1e3, 3), "us_per_layer": round(ms_per_step * 1e3 / NL, 3),
+        "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": "layer: 32 quantised decoder layers of the decoding pipeline, B=16 H=32 d_head=128 d_model=4096 "
+                               "r=32 (Q, K, V) T=2048 FFN=11008, int8 latents, int4 weights, int8 activations",
+                   "batch": B, "heads": Hq, "d_head": d, "d_model": E, "rank": r, "q_rank": rq, "d_ffn": F, "context": T, "layers": NL,
+                   "launch": "hip_graph_replay" if use_graph else "eager",
+                   "weight_MB_per_layer": round(weight_bytes / 1e6, 1), "cache_MB_per_layer": round(2 * (cb + mb) / 1e6, 1),
+                   "layer_hbm_GBps": round((weight_bytes + B * rows_mean * row_bytes) / (ms_per_step * 1e-3 / NL) / 1e9, 1),
+                   "step": "per layer: rmsnorm_quant_i8 (+ residual), linear_w4a8_split ([A_Q; A_K; A_V]), latent_store, "
+                           "decode_attn_latent, quantize_act_i8, linear_w4a8 (W'_O), rmsnorm_quant_i8 (+ residual), "
+                           "linear_w4a8 ([W_g; W_u]), swiglu_quant_i8, linear_w4a8 (W_d)"},
+        "roofline": {"kernel": "k_attn_mfma_latent<32,1,false,1024> (decode attention, Q latent in, latent-space output)",
+                     "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 3)},
     }
     print(json.dumps(res))

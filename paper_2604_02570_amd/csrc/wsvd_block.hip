@@ -30,100 +30,122 @@ WSVD_DEV void split_even_odd(const v4i lo, const v4i hi, v4i& even, v4i& odd) {
   even[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x06040200u); odd[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x07050301u);
 }
 
-// MB = blocks of 16 tokens (M <= 16 * MB)
-template <int MB>
+// MB = blocks of 16 tokens (M <= 16 * MB); NC = tiles of 16 output channels per workgroup (2 when there are plenty of
+// channels: the activations, which every workgroup reads in full from L2, are then fetched half as often).
+// k order inside a 256-element wave step: lane group g takes [32 g, 32 g + 32) and [128 + 32 g, 128 + 32 g + 32), so
+// that one load instruction covers 64 contiguous bytes of each of its 16 weight rows, and the four 16-byte pieces an
+// activation load takes from a row fall into one 128-byte line.
+template <int MB, int NC>
 __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __restrict__ x, const uint16_t* __restrict__ xs,
                                                                const uint8_t* __restrict__ w, const uint16_t* __restrict__ wsc,
                                                                int M, int K, int N, float* __restrict__ out,
                                                                int N1, float* __restrict__ out2) {
-  __shared__ int red[kLinWaves][MB][64][4];
+  __shared__ int red[kLinWaves][NC][MB][64][4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n0 = blockIdx.x * 16;
+  const int n0 = blockIdx.x * 16 * NC;
   const int col = lane & 15, grp = lane >> 4;
   const int n_steps = (K + kLinStepK - 1) / kLinStepK;
-  const uint8_t* wrow = w + (size_t)(n0 + col) * (size_t)(K >> 1);
+  const uint8_t* wrow[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) wrow[c] = w + (size_t)min(n0 + 16 * c + col, N - 1) * (size_t)(K >> 1);
   const int8_t* xrow[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) xrow[mb] = x + (size_t)min(mb * 16 + col, M - 1) * (size_t)K;
 
   // output coordinates of this thread in the final pass, and their scales (requested now, used at the very end)
-  constexpr int OPT = (MB * 256 + kLinWaves * 64 - 1) / (kLinWaves * 64);
+  constexpr int NOUT = NC * MB * 256;
+  constexpr int OPT = (NOUT + kLinWaves * 64 - 1) / (kLinWaves * 64);
   float sx[OPT], sw[OPT];
 #pragma unroll
   for (int it = 0; it < OPT; it++) {
-    const int o = min(it * kLinWaves * 64 + tid, MB * 256 - 1);
-    const int m = min((o >> 8) * 16 + ((o & 255) >> 4), M - 1);
+    const int o = min(it * kLinWaves * 64 + tid, NOUT - 1);
+    const int c = o / (MB * 256), rem = o % (MB * 256);
+    const int m = min((rem >> 8) * 16 + ((rem & 255) >> 4), M - 1);
     sx[it] = f16_bits_to_f32(xs[m]);
-    sw[it] = f16_bits_to_f32(wsc[n0 + (o & 15)]);
+    sw[it] = f16_bits_to_f32(wsc[min(n0 + 16 * c + (o & 15), N - 1)]);
   }
 
-  v4i acc[MB];
+  v4i acc[NC][MB];
 #pragma unroll
-  for (int mb = 0; mb < MB; mb++) acc[mb] = v4i{0, 0, 0, 0};
+  for (int c = 0; c < NC; c++)
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++) acc[c][mb] = v4i{0, 0, 0, 0};
 
   for (int s0 = wave; s0 < n_steps; s0 += kLinWaves * kLinU) {
-    v4i wr[kLinU][2], xr[kLinU][MB][4];
-    // all loads of the batch first (addresses clamped into the row; a group past K is masked below)
+    v4i wr[kLinU][NC][2], xr[kLinU][MB][4];
+    // all loads of the batch first (addresses clamped into the row; a half group past K is masked below)
 #pragma unroll
     for (int u = 0; u < kLinU; u++) {
-      const int k = (s0 + u * kLinWaves) * kLinStepK + 64 * grp;
-      const int kc = min(k, K - 64);
-      wr[u][0] = __builtin_nontemporal_load((const v4i*)(wrow + (kc >> 1)));
-      wr[u][1] = __builtin_nontemporal_load((const v4i*)(wrow + (kc >> 1) + 16));
+      const int kb = (s0 + u * kLinWaves) * kLinStepK + 32 * grp;
+      const int kc0 = min(kb, K - 32), kc1 = min(kb + 128, K - 32);
+      // the two halves of a row's 128-byte line back to back (they merge into one fetch), activations afterwards
 #pragma unroll
-      for (int mb = 0; mb < MB; mb++)
+      for (int c = 0; c < NC; c++) {
+        wr[u][c][0] = __builtin_nontemporal_load((const v4i*)(wrow[c] + (kc0 >> 1)));
+        wr[u][c][1] = __builtin_nontemporal_load((const v4i*)(wrow[c] + (kc1 >> 1)));
+      }
 #pragma unroll
-        for (int i = 0; i < 4; i++) xr[u][mb][i] = *(const v4i*)(xrow[mb] + kc + 16 * i);
+      for (int mb = 0; mb < MB; mb++) {
+        xr[u][mb][0] = *(const v4i*)(xrow[mb] + kc0);
+        xr[u][mb][1] = *(const v4i*)(xrow[mb] + kc0 + 16);
+        xr[u][mb][2] = *(const v4i*)(xrow[mb] + kc1);
+        xr[u][mb][3] = *(const v4i*)(xrow[mb] + kc1 + 16);
+      }
     }
     // keep the whole batch in flight: without this the scheduler sinks most loads below the first products to save
     // registers, which turns one memory round trip into four
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < kLinU; u++) {
-      const int k = (s0 + u * kLinWaves) * kLinStepK + 64 * grp;
-      const bool on = k < K;
-      const uint32_t top = on ? 0xF0F0F0F0u : 0u;
-      v4i wlo[2], whi[2];
+      const int kb = (s0 + u * kLinWaves) * kLinStepK + 32 * grp;
 #pragma unroll
-      for (int h = 0; h < 2; h++)
+      for (int h = 0; h < 2; h++) {
+        const uint32_t top = (kb + 128 * h < K) ? 0xF0F0F0F0u : 0u;
+        v4i xe[MB], xo[MB];
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-          const uint32_t raw = (uint32_t)wr[u][h][i];
-          wlo[h][i] = (int)((raw << 4) & top);   // 16 * w[even k]
-          whi[h][i] = (int)(raw & top);          // 16 * w[odd k]
+        for (int mb = 0; mb < MB; mb++) split_even_odd(xr[u][mb][2 * h], xr[u][mb][2 * h + 1], xe[mb], xo[mb]);
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+          v4i wlo, whi;
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            const uint32_t raw = (uint32_t)wr[u][c][h][i];
+            wlo[i] = (int)((raw << 4) & top);   // 16 * w[even k]
+            whi[i] = (int)(raw & top);          // 16 * w[odd k]
+          }
+#pragma unroll
+          for (int mb = 0; mb < MB; mb++) {
+            acc[c][mb] = mfma16(xe[mb], wlo, acc[c][mb]);
+            acc[c][mb] = mfma16(xo[mb], whi, acc[c][mb]);
+          }
         }
-#pragma unroll
-      for (int mb = 0; mb < MB; mb++) {
-        v4i xe, xo;
-        split_even_odd(xr[u][mb][0], xr[u][mb][1], xe, xo);
-        acc[mb] = mfma16(xe, wlo[0], acc[mb]);
-        acc[mb] = mfma16(xo, whi[0], acc[mb]);
-        split_even_odd(xr[u][mb][2], xr[u][mb][3], xe, xo);
-        acc[mb] = mfma16(xe, wlo[1], acc[mb]);
-        acc[mb] = mfma16(xo, whi[1], acc[mb]);
       }
     }
   }
 #pragma unroll
-  for (int mb = 0; mb < MB; mb++)
+  for (int c = 0; c < NC; c++)
 #pragma unroll
-    for (int v = 0; v < 4; v++) red[wave][mb][lane][v] = acc[mb][v];
+    for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+      for (int v = 0; v < 4; v++) red[wave][c][mb][lane][v] = acc[c][mb][v];
   __syncthreads();
-  // thread -> (token, channel), channel fastest so a 16-lane group writes 64 contiguous bytes
+  // thread -> (tile, token, channel), channel fastest so a 16-lane group writes 64 contiguous bytes
 #pragma unroll
   for (int it = 0; it < OPT; it++) {
     const int o = it * kLinWaves * 64 + tid;
-    if (o >= MB * 256) break;
-    const int mb = o >> 8, rem = o & 255;
-    const int c = rem & 15, rr = rem >> 4;
-    const int src_lane = (rr >> 2) * 16 + c, v = rr & 3;
+    if (o >= NOUT) break;
+    const int c = o / (MB * 256), rem0 = o % (MB * 256);
+    const int mb = rem0 >> 8, rem = rem0 & 255;
+    const int ch = rem & 15, rr = rem >> 4;
+    const int src_lane = (rr >> 2) * 16 + ch, v = rr & 3;
     int sum = 0;
 #pragma unroll
-    for (int k = 0; k < kLinWaves; k++) sum += red[k][mb][src_lane][v];
+    for (int k = 0; k < kLinWaves; k++) sum += red[k][c][mb][src_lane][v];
     const int m = mb * 16 + rr;
+    const int nt = n0 + 16 * c;
     // output columns [0, N1) form one row-major matrix, [N1, N) a second one (a 16-column tile never straddles)
-    float* dst = n0 < N1 ? out + (size_t)m * N1 + n0 : out2 + (size_t)m * (N - N1) + (n0 - N1);
-    if (m < M) dst[c] = (float)(sum >> 4) * sx[it] * sw[it];
+    float* dst = nt < N1 ? out + (size_t)m * N1 + nt : out2 + (size_t)m * (N - N1) + (nt - N1);
+    if (m < M && nt < N) dst[ch] = (float)(sum >> 4) * sx[it] * sw[it];
   }
 }
 
@@ -134,15 +156,24 @@ hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const v
   if (M < 1 || M > 64 || K < 64 || K % 64 != 0 || K > 65536 || N % 16 != 0) return hipErrorInvalidValue;
   if (n_first < 0 || n_first > N || n_first % 16 != 0 || (n_first < N && !out2)) return hipErrorInvalidValue;
   const int N1 = (int)n_first;
-  dim3 grid((unsigned)(N / 16)), block(kLinWaves * 64);
   const uint16_t* xs = (const uint16_t*)x_scale;
   const uint16_t* ws = (const uint16_t*)w_scale;
   const uint8_t* w = (const uint8_t*)w_i4;
-  switch ((M + 15) / 16) {
-    case 1: hipLaunchKernelGGL((k_linear_w4a8<1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
-    case 2: hipLaunchKernelGGL((k_linear_w4a8<2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
-    case 3: hipLaunchKernelGGL((k_linear_w4a8<3>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
-    default: hipLaunchKernelGGL((k_linear_w4a8<4>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+  const int mbk = (int)((M + 15) / 16);
+  dim3 block(kLinWaves * 64);
+  // two 16-channel tiles per workgroup once that still leaves a few workgroups per CU
+  if (mbk <= 2 && N / 32 >= 512) {
+    dim3 grid((unsigned)((N + 31) / 32));
+    if (mbk == 1) hipLaunchKernelGGL((k_linear_w4a8<1, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
+    else hipLaunchKernelGGL((k_linear_w4a8<2, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
+    return hipGetLastError();
+  }
+  dim3 grid((unsigned)(N / 16));
+  switch (mbk) {
+    case 1: hipLaunchKernelGGL((k_linear_w4a8<1, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+    case 2: hipLaunchKernelGGL((k_linear_w4a8<2, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+    case 3: hipLaunchKernelGGL((k_linear_w4a8<3, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
+    default: hipLaunchKernelGGL((k_linear_w4a8<4, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
   }
   return hipGetLastError();
 }
