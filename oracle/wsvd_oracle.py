@@ -35,6 +35,9 @@ zero query returns the mean V row; a two-token scalar case by hand; row-permutat
 invariance; large-score stability; quantiser round trip within one step; nibble packing
 exhaustive; one-hot token reproduces a row of A; the printed instance of Eq. 3
 (rho_2 = 50 % gives rho_1 ~ 51.5 %, Section 4.4) and the 25 % cache figure of Section 4.2.
+The pipeline functions: low-rank-Q attention and the latent-space output against torch attention on tensors formed by
+einsum, the folds by associativity, RMSNorm / SiLU against torch, the int4 weight quantiser by invariants and a hand
+case, the layer's glue re-done with torch ops.
 The numeric value of the output on Gaussian inputs is not printed anywhere in the paper:
 for that, parity rests on the pins above.
 
