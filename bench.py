@@ -51,6 +51,8 @@ def parse():
                          "c5: the 28-layer grouped-query W4A8 attention block; "
                          "layer: 32 quantised decoder layers of the decoding pipeline at the c3 shape (low-rank Q, B_V folded "
                          "into W_O, SwiGLU FFN) (secondary lines, same JSON shape)")
+    ap.add_argument("--linear-direct", action="store_true",
+                    help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -73,6 +75,8 @@ def main():
         W.wsvd_set_option("fused_step", 2)
     if args.max_threads:
         W.wsvd_set_option("max_threads", args.max_threads)
+    if args.linear_direct:
+        W.wsvd_set_option("linear_direct", 1)
     if args.workload == "c5":
         return run_c5(args, np, torch, W, WI)
     if args.workload == "layer":

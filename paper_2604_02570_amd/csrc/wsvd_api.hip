@@ -167,6 +167,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
   if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { g_append_mode = value; return WSVD_OK; }
   if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
+  if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { g_wsvd_linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }

@@ -149,7 +149,153 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
   }
 }
 
+// The same layer with both operands staged through wave-private LDS.  The matrix-core layout wants lane = (row, k
+// group), which read straight from row-major memory makes every load instruction touch 16 rows in 16- or 64-byte
+// pieces.  Here a wave fetches its step of the weights (16 rows x 128 bytes per tile) and of the activations (16 rows x
+// 256 bytes per token block) with whole 128-byte lines per row, writes them to its own LDS region and reads them back
+// in operand order.  Row strides of 144 and 272 bytes spread both access patterns evenly over the banks.  No
+// workgroup barrier is involved: a wave only ever touches its own region until the final reduction, whose per-wave
+// slots live inside that region too.  For M <= 32.
+constexpr int kLinWRow = 144, kLinXRow = 272;
+template <int MB, int NC>
+__global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8_staged(const int8_t* __restrict__ x, const uint16_t* __restrict__ xs,
+                                                                      const uint8_t* __restrict__ w, const uint16_t* __restrict__ wsc,
+                                                                      int M, int K, int N, float* __restrict__ out,
+                                                                      int N1, float* __restrict__ out2) {
+  constexpr int WBYTES = 16 * kLinWRow, XBYTES = 16 * kLinXRow;
+  constexpr int WAVE_LDS = NC * WBYTES + MB * XBYTES;
+  static_assert(WAVE_LDS >= NC * MB * 1024 && WAVE_LDS % 16 == 0, "the reduction slots must fit into a wave's region");
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kLinWaves][WAVE_LDS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * 16 * NC;
+  const int col = lane & 15, grp = lane >> 4;
+  const int n_steps = (K + kLinStepK - 1) / kLinStepK;
+  uint8_t* my = lds[wave];
+  // fetch coordinates: weights 8 rows x 8 pieces of 16 bytes per instruction, activations 4 rows x 16 pieces
+  const int wr_row = lane >> 3, wr_piece = lane & 7;
+  const int xr_row = lane >> 4, xr_piece = lane & 15;
+  const uint8_t* wsrc[NC][2];
+#pragma unroll
+  for (int c = 0; c < NC; c++)
+#pragma unroll
+    for (int i = 0; i < 2; i++) wsrc[c][i] = w + (size_t)min(n0 + 16 * c + 8 * i + wr_row, N - 1) * (size_t)(K >> 1);
+  const int8_t* xsrc[MB][4];
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+    for (int i = 0; i < 4; i++) xsrc[mb][i] = x + (size_t)min(mb * 16 + 4 * i + xr_row, M - 1) * (size_t)K;
+
+  constexpr int NOUT = NC * MB * 256;
+  constexpr int OPT = (NOUT + kLinWaves * 64 - 1) / (kLinWaves * 64);
+  float sx[OPT], sw[OPT];
+#pragma unroll
+  for (int it = 0; it < OPT; it++) {
+    const int o = min(it * kLinWaves * 64 + tid, NOUT - 1);
+    const int c = o / (MB * 256), rem = o % (MB * 256);
+    const int m = min((rem >> 8) * 16 + ((rem & 255) >> 4), M - 1);
+    sx[it] = f16_bits_to_f32(xs[m]);
+    sw[it] = f16_bits_to_f32(wsc[min(n0 + 16 * c + (o & 15), N - 1)]);
+  }
+
+  v4i acc[NC][MB];
+#pragma unroll
+  for (int c = 0; c < NC; c++)
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++) acc[c][mb] = v4i{0, 0, 0, 0};
+
+  for (int s0 = wave; s0 < n_steps; s0 += kLinWaves * kLinU) {
+    v4i wg[kLinU][NC][2], xg[kLinU][MB][4];
+    // all fetches of the batch first; a piece past the end of the row is fetched from the row's last 16 bytes instead
+    // (its products are masked below)
+#pragma unroll
+    for (int u = 0; u < kLinU; u++) {
+      const int step = s0 + u * kLinWaves;
+      const int wo = min(step * (kLinStepK / 2) + wr_piece * 16, (K >> 1) - 16);
+      const int xo = min(step * kLinStepK + xr_piece * 16, K - 16);
+#pragma unroll
+      for (int c = 0; c < NC; c++)
+#pragma unroll
+        for (int i = 0; i < 2; i++) wg[u][c][i] = __builtin_nontemporal_load((const v4i*)(wsrc[c][i] + wo));
+#pragma unroll
+      for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) xg[u][mb][i] = *(const v4i*)(xsrc[mb][i] + xo);
+    }
+    __builtin_amdgcn_sched_barrier(0);      // keep the whole batch in flight
+#pragma unroll
+    for (int u = 0; u < kLinU; u++) {
+      const int kb = (s0 + u * kLinWaves) * kLinStepK + 32 * grp;
+      // earlier reads of the region are done (same-wave LDS operations execute in order); fences for the compiler
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int c = 0; c < NC; c++)
+#pragma unroll
+        for (int i = 0; i < 2; i++) *(v4i*)(my + c * WBYTES + (8 * i + wr_row) * kLinWRow + wr_piece * 16) = wg[u][c][i];
+#pragma unroll
+      for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) *(v4i*)(my + NC * WBYTES + mb * XBYTES + (4 * i + xr_row) * kLinXRow + xr_piece * 16) = xg[u][mb][i];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int h = 0; h < 2; h++) {
+        const uint32_t top = (kb + 128 * h < K) ? 0xF0F0F0F0u : 0u;
+        v4i xe[MB], xo2[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++) {
+          const uint8_t* xp = my + NC * WBYTES + mb * XBYTES + col * kLinXRow + 128 * h + 32 * grp;
+          split_even_odd(*(const v4i*)xp, *(const v4i*)(xp + 16), xe[mb], xo2[mb]);
+        }
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+          const v4i raw4 = *(const v4i*)(my + c * WBYTES + col * kLinWRow + 64 * h + 16 * grp);
+          v4i wlo, whi;
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            const uint32_t raw = (uint32_t)raw4[i];
+            wlo[i] = (int)((raw << 4) & top);   // 16 * w[even k]
+            whi[i] = (int)(raw & top);          // 16 * w[odd k]
+          }
+#pragma unroll
+          for (int mb = 0; mb < MB; mb++) {
+            acc[c][mb] = mfma16(xe[mb], wlo, acc[c][mb]);
+            acc[c][mb] = mfma16(xo2[mb], whi, acc[c][mb]);
+          }
+        }
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  int* redw = (int*)my;                       // [NC][MB][64][4], inside this wave's own region
+#pragma unroll
+  for (int c = 0; c < NC; c++)
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++) *(v4i*)&redw[((c * MB + mb) * 64 + lane) * 4] = acc[c][mb];
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < OPT; it++) {
+    const int o = it * kLinWaves * 64 + tid;
+    if (o >= NOUT) break;
+    const int c = o / (MB * 256), rem0 = o % (MB * 256);
+    const int mb = rem0 >> 8, rem = rem0 & 255;
+    const int ch = rem & 15, rr = rem >> 4;
+    const int src_lane = (rr >> 2) * 16 + ch, v = rr & 3;
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kLinWaves; k++) sum += ((const int*)lds[k])[((c * MB + mb) * 64 + src_lane) * 4 + v];
+    const int m = mb * 16 + rr;
+    const int nt = n0 + 16 * c;
+    float* dst = nt < N1 ? out + (size_t)m * N1 + nt : out2 + (size_t)m * (N - N1) + (nt - N1);
+    if (m < M && nt < N) dst[ch] = (float)(sum >> 4) * sx[it] * sw[it];
+  }
+}
+
 }  // namespace
+
+int g_wsvd_linear_direct = 0;   // option "linear_direct": 1 = operands read straight from memory in operand order
 
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
                                    int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s) {
@@ -162,13 +308,21 @@ hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const v
   const int mbk = (int)((M + 15) / 16);
   dim3 block(kLinWaves * 64);
   // two 16-channel tiles per workgroup once that still leaves a few workgroups per CU
-  if (mbk <= 2 && N / 32 >= 512) {
-    dim3 grid((unsigned)((N + 31) / 32));
+  const bool two = N / 32 >= 512;
+  dim3 grid((unsigned)(two ? (N + 31) / 32 : N / 16));
+  if (mbk <= 2 && !g_wsvd_linear_direct) {
+    if (mbk == 1 && two) hipLaunchKernelGGL((k_linear_w4a8_staged<1, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
+    else if (mbk == 1) hipLaunchKernelGGL((k_linear_w4a8_staged<1, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
+    else if (two) hipLaunchKernelGGL((k_linear_w4a8_staged<2, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
+    else hipLaunchKernelGGL((k_linear_w4a8_staged<2, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
+    return hipGetLastError();
+  }
+  if (mbk <= 2 && two) {
     if (mbk == 1) hipLaunchKernelGGL((k_linear_w4a8<1, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
     else hipLaunchKernelGGL((k_linear_w4a8<2, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
     return hipGetLastError();
   }
-  dim3 grid((unsigned)(N / 16));
+  grid = dim3((unsigned)(N / 16));
   switch (mbk) {
     case 1: hipLaunchKernelGGL((k_linear_w4a8<1, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;
     case 2: hipLaunchKernelGGL((k_linear_w4a8<2, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2); break;

@@ -58,6 +58,8 @@ hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, cons
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
                                    int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s);
 
+extern int g_wsvd_linear_direct;   // option "linear_direct" (defined next to the linear layer's launcher)
+
 // workspace sizing shared by the API and the launchers
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d);
