@@ -348,7 +348,8 @@ wsvd_status wsvd_decode_attn_latent(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   if (max_seq_len < 0) return WSVD_E_SHAPE;
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
   const int G = desc->n_q_heads / desc->n_kv_heads;
-  if ((desc->latent_dtype != WSVD_I8 && desc->latent_dtype != WSVD_I4) || G > 4) return WSVD_E_UNSUPPORTED;
+  if (desc->latent_dtype != WSVD_I8 && desc->latent_dtype != WSVD_I4) return WSVD_E_UNSUPPORTED;
+  if (G > (desc->latent_dtype == WSVD_I8 ? 8 : 4)) return WSVD_E_UNSUPPORTED;
   size_t need;
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
@@ -357,7 +358,7 @@ wsvd_status wsvd_decode_attn_latent(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   AttnParams p;
   dim3 grid;
   int threads;
-  wsvd_attn_plan(ctx, d, c_Q, nullptr, nullptr, nullptr, *cache, max_seq_len, u_out, p, grid, threads, 0);
+  wsvd_attn_plan(ctx, d, c_Q, nullptr, nullptr, nullptr, *cache, max_seq_len, u_out, p, grid, threads, G > 4 ? 512 : 0);
   p.qk_fold = (const float*)qk_fold;
   p.rq = rq;
   p.out_dim = d.rank;

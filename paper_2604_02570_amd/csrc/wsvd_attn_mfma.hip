@@ -737,7 +737,9 @@ WSVD_DEV void load_gqa_tile(GqaTile<R>& t, const uint8_t* kplane, const uint8_t*
   }
 }
 
-template <int R, int NT>
+// LATENT: the Q latent comes in and the latent-space output goes out (no factor is read); launched with exactly NT
+// threads.
+template <int R, int NT, bool LATENT = false>
 __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   constexpr int KK = R / 32;
   constexpr int NWMAX = NT / 64;
@@ -778,6 +780,32 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   const size_t q_bytes = (size_t)p.B * p.Hq * p.d * q_esz;
   const int gq = l32 < G ? l32 : 0;                     // query column of this lane (columns past G are zeroed below)
   v4i bk_raw[MAXI], q_raw[MAXI][2];
+  // LATENT: q~[g][j] = sum_i c_Q[g][i] (B_Q B_K^T)[h][i][j]; work item (quarter of the i range, g, j), j fastest
+  constexpr int LQ = 16;                               // rq <= 64
+  constexpr int NLP = LATENT ? (4 * GS * R + NT - 1) / NT : 1;
+  float lat_part[NLP];
+  if constexpr (LATENT) {
+    const int qn = (p.rq + 3) >> 2;
+#pragma unroll
+    for (int ps = 0; ps < NLP; ps++) {
+      const int item = min(tid + ps * NT, 4 * G * R - 1);
+      const int j = item % R, g = (item / R) % G, part = item / (R * G);
+      const int h = blockIdx.x * G + g;
+      const float* cq = (const float*)p.q + ((size_t)blockIdx.z * p.Hq + h) * p.rq;
+      const float* fold = p.qk_fold + (size_t)h * p.rq * R + j;
+      float mv[LQ], cv[LQ];
+#pragma unroll
+      for (int ii = 0; ii < LQ; ii++) {
+        const int i = min(part * qn + ii, p.rq - 1);   // clamped: surplus slots are masked below
+        mv[ii] = fold[(size_t)i * R];
+        cv[ii] = cq[i];
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int ii = 0; ii < LQ; ii++) acc = (ii < qn && part * qn + ii < p.rq) ? fmaf(cv[ii], mv[ii], acc) : acc;
+      lat_part[ps] = acc;
+    }
+  } else {
 #pragma unroll
   for (int i = 0; i < MAXI; i++) {
     const int item = min(wave + i * NW, n_items - 1);   // unconditional, clamped
@@ -787,6 +815,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     const size_t o0 = off & ~(size_t)15;
     q_raw[i][0] = *(const v4i*)((const char*)p.q + o0);
     q_raw[i][1] = *(const v4i*)((const char*)p.q + min(o0 + 16, q_bytes - 16));
+  }
   }
   // ---- then the first tiles, requested speculatively below t_cap before the sequence length is known.  The barrier
   // (no memory wait) keeps every wave's small loads ahead of every wave's tile loads in the CU's memory pipeline, so
@@ -802,7 +831,14 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     for (int i = 0; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
   }
 
-  {
+  if constexpr (LATENT) {
+    float* qflat = &qpart[0][0][0];                     // [4][G * R] partial sums
+#pragma unroll
+    for (int ps = 0; ps < NLP; ps++) {
+      const int item = tid + ps * NT;
+      if (item < 4 * G * R) qflat[item] = lat_part[ps];
+    }
+  } else {
     v16f qacc = {0};
 #pragma unroll
     for (int i = 0; i < MAXI; i++) {
@@ -851,7 +887,12 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   for (int idx = tid; idx < GS * R; idx += blockDim.x) {
     const int g = idx / R, j = idx % R;
     float v = 0.f;
-    for (int k = (j >> 5) % RB; k < NW; k += RB) v += qpart[k][j & 31][g];   // the waves that worked on this row block
+    if constexpr (LATENT) {
+      const float* qflat = &qpart[0][0][0];
+      if (g < G) v = qflat[g * R + j] + qflat[G * R + g * R + j] + qflat[2 * G * R + g * R + j] + qflat[3 * G * R + g * R + j];
+    } else {
+      for (int k = (j >> 5) % RB; k < NW; k += RB) v += qpart[k][j & 31][g];   // the waves that worked on this row block
+    }
     v *= p.c_scale;
     const float amax = (R == 64) ? wave_max(fabsf(v)) : half_max(fabsf(v), lane);
     const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
@@ -992,7 +1033,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   // while the slower waves finish
   const int fac16 = R * p.d * 2 / 16;
   StageRegs<FIT> stv;
-  stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
+  if constexpr (!LATENT) stage_issue<FIT>(stv, (const char*)p.BV + (size_t)blockIdx.x * R * p.d * 2, fac16);
   // per-wave state -> LDS (a wave that had no tile contributes m = -inf, l = 0, u = 0)
 #pragma unroll
   for (int a = 0; a < 4; a++) {
@@ -1002,7 +1043,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
 #pragma unroll
     for (int jj = 0; jj < KK; jj++) wu[wave][a + 4 * hf][jj * 32 + l32] = u[a][jj];
   }
-  stage_commit<FIT>(stv, bv_lds, fac16);
+  if constexpr (!LATENT) stage_commit<FIT>(stv, bv_lds, fac16);
   __syncthreads();
   for (int idx = tid; idx < G * R; idx += blockDim.x) {
     const int g = idx / R, j = idx % R;
@@ -1018,7 +1059,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     if (j == 0) { Msh[g] = M; Lsh[g] = L; }
   }
   __syncthreads();
-  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, bv_lds);
+  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, LATENT ? nullptr : (const void*)bv_lds);
 }
 
 template <int R, bool I4, int NT>
@@ -1047,9 +1088,18 @@ static hipError_t launch_m_latent(const AttnParams& p, dim3 grid, int threads, h
   return hipGetLastError();
 }
 
-// Latent-query / latent-output attention: int8 or int4 latents, up to 4 query heads per kv head, rq <= 64.
+// Latent-query / latent-output attention: int8 latents with up to 8 query heads per kv head (5 to 8: exactly 512
+// threads), int4 latents with up to 4; rq <= 64.
 hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
   if (p.rq < 1 || p.rq > 64 || !p.qk_fold) return hipErrorInvalidValue;
+  if (p.G > 4) {
+    if (latent_dtype != WSVD_I8 || p.G > 8) return hipErrorNotSupported;
+    if (threads != 512) return hipErrorInvalidValue;
+    if (rank == 32) hipLaunchKernelGGL((k_attn_gqa<32, 512, true>), grid, dim3(512), 0, s, p);
+    else if (rank == 64) hipLaunchKernelGGL((k_attn_gqa<64, 512, true>), grid, dim3(512), 0, s, p);
+    else return hipErrorNotSupported;
+    return hipGetLastError();
+  }
   if (latent_dtype == WSVD_I8 && rank == 32) return launch_m_latent<32, false, 1024>(p, grid, threads, s);
   if (latent_dtype == WSVD_I8 && rank == 64) return launch_m_latent<64, false, 512>(p, grid, threads, s);
   if (latent_dtype == WSVD_I4 && rank == 32) return launch_m_latent<32, true, 1024>(p, grid, threads, s);

@@ -79,6 +79,10 @@ LATENT_CASES = [
     ("c5_small", 64, dict(n_q_heads=8, n_kv_heads=2, context=200)),         # rank 64, four heads per kv head
     ("c4_small", 32, dict()),                                               # int4 latents, ragged
     ("c4_small", 7, dict(n_q_heads=12, n_kv_heads=4)),                      # int4, three heads per kv head, odd rq
+    ("c5_small", 64, dict()),                                               # rank 64, seven heads per kv head
+    ("c3_small", 32, dict(n_q_heads=20, n_kv_heads=4, context=900)),        # rank 32, five heads per kv head
+    ("c3_small", 48, dict(n_q_heads=16, n_kv_heads=2, context=70)),         # eight heads per kv head
+    ("c5_small", 13, dict(n_q_heads=12, n_kv_heads=2, context=2500, batch=2)),   # six, several chunks
 ]
 
 
@@ -298,7 +302,8 @@ def _check_layer(c, L, gl, ref, before, what):
 @pytest.mark.parametrize("name,rq,F,over", [("c3_small", 32, 1408, dict()),
                                             ("c3_small", 32, 1408, dict(n_q_heads=8, n_kv_heads=4, context=700)),
                                             ("c5_small", 64, 1024, dict(n_q_heads=8, n_kv_heads=2)),
-                                            ("c4_small", 32, 1408, dict())], ids=["i8", "i8g2", "i8r64g4", "i4"])
+                                            ("c4_small", 32, 1408, dict()),
+                                            ("c5_small", 64, 1024, dict())], ids=["i8", "i8g2", "i8r64g4", "i4", "i8r64g7"])
 def test_decoder_layer_small(name, rq, F, over):
     c = build_layer_case(name, rq, F, **over)
     L = layer_for(c); L.upload(c.cache)
