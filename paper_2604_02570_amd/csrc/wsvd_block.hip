@@ -30,6 +30,54 @@ WSVD_DEV void split_even_odd(const v4i lo, const v4i hi, v4i& even, v4i& odd) {
   even[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x06040200u); odd[3] = __builtin_amdgcn_perm(hi[3], hi[2], 0x07050301u);
 }
 
+// The two halves every variant of the layer shares.  Output coordinates of a thread in the final pass and their
+// scales are requested at the very start and used at the very end; the final pass adds the waves' partial sums
+// (slot k of wave w at red[w * wave_stride + k], k = ((tile * MB + block) * 64 + lane) * 4 + register), undoes the
+// factor 16 and applies the two scales.  Thread -> (tile, token, channel), channel fastest, so a 16-lane group writes
+// 64 contiguous bytes.
+template <int MB, int NC>
+struct LinScales {
+  static constexpr int NOUT = NC * MB * 256;
+  static constexpr int OPT = (NOUT + kLinWaves * 64 - 1) / (kLinWaves * 64);
+  float sx[OPT], sw[OPT];
+};
+
+template <int MB, int NC>
+WSVD_DEV void linear_scales(LinScales<MB, NC>& sc, const uint16_t* xs, const uint16_t* wsc, int n0, int M, int N) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < LinScales<MB, NC>::OPT; it++) {
+    const int o = min(it * kLinWaves * 64 + tid, LinScales<MB, NC>::NOUT - 1);
+    const int c = o / (MB * 256), rem = o % (MB * 256);
+    const int m = min((rem >> 8) * 16 + ((rem & 255) >> 4), M - 1);
+    sc.sx[it] = f16_bits_to_f32(xs[m]);
+    sc.sw[it] = f16_bits_to_f32(wsc[min(n0 + 16 * c + (o & 15), N - 1)]);
+  }
+}
+
+template <int MB, int NC>
+WSVD_DEV void linear_finish(const LinScales<MB, NC>& sc, const int* red, int wave_stride, int n0, int M, int N, float* out,
+                            int N1, float* out2) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int it = 0; it < LinScales<MB, NC>::OPT; it++) {
+    const int o = it * kLinWaves * 64 + tid;
+    if (o >= LinScales<MB, NC>::NOUT) break;
+    const int c = o / (MB * 256), rem0 = o % (MB * 256);
+    const int mb = rem0 >> 8, rem = rem0 & 255;
+    const int ch = rem & 15, rr = rem >> 4;
+    const int src_lane = (rr >> 2) * 16 + ch, v = rr & 3;
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kLinWaves; k++) sum += red[k * wave_stride + ((c * MB + mb) * 64 + src_lane) * 4 + v];
+    const int m = mb * 16 + rr;
+    const int nt = n0 + 16 * c;
+    // output columns [0, N1) form one row-major matrix, [N1, N) a second one (a 16-column tile never straddles)
+    float* dst = nt < N1 ? out + (size_t)m * N1 + nt : out2 + (size_t)m * (N - N1) + (nt - N1);
+    if (m < M && nt < N) dst[ch] = (float)(sum >> 4) * sc.sx[it] * sc.sw[it];
+  }
+}
+
 // MB = blocks of 16 tokens (M <= 16 * MB); NC = tiles of 16 output channels per workgroup (2 when there are plenty of
 // channels: the activations, which every workgroup reads in full from L2, are then fetched half as often).
 // k order inside a 256-element wave step: lane group g takes [32 g, 32 g + 32) and [128 + 32 g, 128 + 32 g + 32), so
@@ -52,18 +100,8 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) xrow[mb] = x + (size_t)min(mb * 16 + col, M - 1) * (size_t)K;
 
-  // output coordinates of this thread in the final pass, and their scales (requested now, used at the very end)
-  constexpr int NOUT = NC * MB * 256;
-  constexpr int OPT = (NOUT + kLinWaves * 64 - 1) / (kLinWaves * 64);
-  float sx[OPT], sw[OPT];
-#pragma unroll
-  for (int it = 0; it < OPT; it++) {
-    const int o = min(it * kLinWaves * 64 + tid, NOUT - 1);
-    const int c = o / (MB * 256), rem = o % (MB * 256);
-    const int m = min((rem >> 8) * 16 + ((rem & 255) >> 4), M - 1);
-    sx[it] = f16_bits_to_f32(xs[m]);
-    sw[it] = f16_bits_to_f32(wsc[min(n0 + 16 * c + (o & 15), N - 1)]);
-  }
+  LinScales<MB, NC> sc;
+  linear_scales<MB, NC>(sc, xs, wsc, n0, M, N);
 
   v4i acc[NC][MB];
 #pragma unroll
@@ -129,24 +167,7 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8(const int8_t* __
 #pragma unroll
       for (int v = 0; v < 4; v++) red[wave][c][mb][lane][v] = acc[c][mb][v];
   __syncthreads();
-  // thread -> (tile, token, channel), channel fastest so a 16-lane group writes 64 contiguous bytes
-#pragma unroll
-  for (int it = 0; it < OPT; it++) {
-    const int o = it * kLinWaves * 64 + tid;
-    if (o >= NOUT) break;
-    const int c = o / (MB * 256), rem0 = o % (MB * 256);
-    const int mb = rem0 >> 8, rem = rem0 & 255;
-    const int ch = rem & 15, rr = rem >> 4;
-    const int src_lane = (rr >> 2) * 16 + ch, v = rr & 3;
-    int sum = 0;
-#pragma unroll
-    for (int k = 0; k < kLinWaves; k++) sum += red[k][c][mb][src_lane][v];
-    const int m = mb * 16 + rr;
-    const int nt = n0 + 16 * c;
-    // output columns [0, N1) form one row-major matrix, [N1, N) a second one (a 16-column tile never straddles)
-    float* dst = nt < N1 ? out + (size_t)m * N1 + nt : out2 + (size_t)m * (N - N1) + (nt - N1);
-    if (m < M && nt < N) dst[ch] = (float)(sum >> 4) * sx[it] * sw[it];
-  }
+  linear_finish<MB, NC>(sc, &red[0][0][0][0][0], NC * MB * 256, n0, M, N, out, N1, out2);
 }
 
 // The same layer with both operands staged through wave-private LDS.  The matrix-core layout wants lane = (row, k
@@ -185,17 +206,8 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8_staged(const int
 #pragma unroll
     for (int i = 0; i < 4; i++) xsrc[mb][i] = x + (size_t)min(mb * 16 + 4 * i + xr_row, M - 1) * (size_t)K;
 
-  constexpr int NOUT = NC * MB * 256;
-  constexpr int OPT = (NOUT + kLinWaves * 64 - 1) / (kLinWaves * 64);
-  float sx[OPT], sw[OPT];
-#pragma unroll
-  for (int it = 0; it < OPT; it++) {
-    const int o = min(it * kLinWaves * 64 + tid, NOUT - 1);
-    const int c = o / (MB * 256), rem = o % (MB * 256);
-    const int m = min((rem >> 8) * 16 + ((rem & 255) >> 4), M - 1);
-    sx[it] = f16_bits_to_f32(xs[m]);
-    sw[it] = f16_bits_to_f32(wsc[min(n0 + 16 * c + (o & 15), N - 1)]);
-  }
+  LinScales<MB, NC> sc;
+  linear_scales<MB, NC>(sc, xs, wsc, n0, M, N);
 
   v4i acc[NC][MB];
 #pragma unroll
@@ -275,22 +287,7 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8_staged(const int
 #pragma unroll
     for (int mb = 0; mb < MB; mb++) *(v4i*)&redw[((c * MB + mb) * 64 + lane) * 4] = acc[c][mb];
   __syncthreads();
-#pragma unroll
-  for (int it = 0; it < OPT; it++) {
-    const int o = it * kLinWaves * 64 + tid;
-    if (o >= NOUT) break;
-    const int c = o / (MB * 256), rem0 = o % (MB * 256);
-    const int mb = rem0 >> 8, rem = rem0 & 255;
-    const int ch = rem & 15, rr = rem >> 4;
-    const int src_lane = (rr >> 2) * 16 + ch, v = rr & 3;
-    int sum = 0;
-#pragma unroll
-    for (int k = 0; k < kLinWaves; k++) sum += ((const int*)lds[k])[((c * MB + mb) * 64 + src_lane) * 4 + v];
-    const int m = mb * 16 + rr;
-    const int nt = n0 + 16 * c;
-    float* dst = nt < N1 ? out + (size_t)m * N1 + nt : out2 + (size_t)m * (N - N1) + (nt - N1);
-    if (m < M && nt < N) dst[ch] = (float)(sum >> 4) * sx[it] * sw[it];
-  }
+  linear_finish<MB, NC>(sc, (const int*)&lds[0][0], WAVE_LDS / 4, n0, M, N, out, N1, out2);
 }
 
 }  // namespace
