@@ -53,7 +53,7 @@ __all__ = [
     "bf16_bits_from_f32", "f64_from_bf16_bits", "to_f64",
     "quantize_int8_rows", "dequantize_int8_rows",
     "quantize_int4_rows", "dequantize_int4_rows", "pack_int4", "unpack_int4",
-    "LatentCache", "project_latents", "latent_append",
+    "LatentCache", "project_latents", "latent_append", "latent_prefill",
     "dequant_cache_rows", "decode_attn_reconstructed", "decode_attn_absorbed",
     "rope_inv_freq", "rope_rotate", "decode_attn_rope_reconstructed",
     "softmax_weights",
@@ -264,6 +264,19 @@ def latent_append(cache: LatentCache, x64: np.ndarray, AK64: np.ndarray, AV64: n
         cache.store_rows("v", b, n, cV[b][:, None, :])
         cache.seq_lens[b] = n + 1
     return overflow
+
+
+def latent_prefill(cache: LatentCache, b: int, X64: np.ndarray, AK64: np.ndarray, AV64: np.ndarray) -> bool:
+    """Prefill of one sequence (Section 3.4: the input sequence is projected into low-rank latents and the K, V latents
+    are stored as the cache): X [n,E] are consecutive tokens of sequence b; token i goes to row seq_lens[b] + i.
+    Rows beyond t_cap are dropped and the sequence is left full; returns True in that case."""
+    n0 = int(cache.seq_lens[b])
+    n_fit = max(0, min(X64.shape[0], cache.t_cap - n0))
+    if n_fit:
+        cache.store_rows("k", b, n0, np.transpose(project_latents(X64[:n_fit], AK64), (1, 0, 2)))
+        cache.store_rows("v", b, n0, np.transpose(project_latents(X64[:n_fit], AV64), (1, 0, 2)))
+    cache.seq_lens[b] = n0 + n_fit
+    return n_fit < X64.shape[0]
 
 
 def dequant_cache_rows(cache: LatentCache, which: str, b: int, kv: int, n: int) -> np.ndarray:

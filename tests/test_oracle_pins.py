@@ -560,3 +560,28 @@ def test_decoder_layer_glue_against_torch():
     x2 = f32(x1 + f32(lin(fq(a.numpy()), t(Wd))))
     np.testing.assert_allclose(res["x2"], x2.numpy(), rtol=1e-6, atol=1e-6)
     assert np.abs(res["x2"] - x).max() > 0.1           # the layer does something
+
+
+def test_prefill_equals_successive_appends():
+    """Prefilling n tokens of one sequence == appending them one at a time (the append is pinned above); a prompt that
+    does not fit fills the sequence and says so; other sequences are untouched."""
+    rng = np.random.default_rng(31)
+    Hkv, E, r, n = 2, 24, 8, 11
+    AK = rng.standard_normal((Hkv, E, r)); AV = rng.standard_normal((Hkv, E, r))
+    X = rng.standard_normal((n, E))
+    for dtype in ("f32", "bf16", "i8", "i4"):
+        a = _rand_cache(rng, 2, Hkv, 5, r, dtype, t_cap=20)
+        b = O.LatentCache(2, Hkv, 20, r, dtype)
+        for name in ("k", "v", "k_scale", "v_scale", "k_zero", "v_zero", "seq_lens"):
+            if getattr(a, name) is not None:
+                getattr(b, name)[...] = getattr(a, name)
+        assert O.latent_prefill(a, 1, X, AK, AV) is False
+        for i in range(n):                      # one-sequence appends: a batch-1 view would need a second cache type,
+            x2 = np.zeros((2, E)); x2[1] = X[i]  # so sequence 0 gets a zero token and is compared up to its old length
+            O.latent_append(b, x2, AK, AV)
+        assert a.seq_lens.tolist() == [5, 16] and b.seq_lens.tolist() == [16, 16]
+        for name in ("k", "v", "k_scale", "v_scale", "k_zero", "v_zero"):
+            if getattr(a, name) is not None:
+                np.testing.assert_array_equal(getattr(a, name)[1, :, :16], getattr(b, name)[1, :, :16])
+                np.testing.assert_array_equal(getattr(a, name)[0, :, :5], getattr(b, name)[0, :, :5])
+        assert O.latent_prefill(a, 1, X, AK, AV) is True and a.seq_lens[1] == 20
