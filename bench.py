@@ -45,12 +45,13 @@ def parse():
     ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
-    ap.add_argument("--workload", choices=["c3", "c4", "c5", "layer"], default="c3",
+    ap.add_argument("--workload", choices=["c3", "c4", "c5", "layer", "prefill"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
                          "c5: the 28-layer grouped-query W4A8 attention block; "
                          "layer: 32 quantised decoder layers of the decoding pipeline at the c3 shape (low-rank Q, B_V folded "
-                         "into W_O, SwiGLU FFN) (secondary lines, same JSON shape)")
+                         "into W_O, SwiGLU FFN); prefill: building the c3 cache from hidden states, 64 tokens per launch "
+                         "(secondary lines, same JSON shape)")
     ap.add_argument("--linear-direct", action="store_true",
                     help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -81,6 +82,8 @@ def main():
         return run_c5(args, np, torch, W, WI)
     if args.workload == "layer":
         return run_layer(args, np, torch, W, WI)
+    if args.workload == "prefill":
+        return run_prefill(args, np, torch, W, WI)
 
     sp = WI.spec(args.workload)
     i4 = sp.latent_dtype == "i4"
@@ -618,6 +621,77 @@ def run_layer(args, np, torch, W, WI):
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": int(attn_bytes), "avg_launch_us": round(attn_us, 3)},
+    }
+    print(json.dumps(res))
+    W.wsvd_destroy(ctx)
+
+
+def run_prefill(args, np, torch, W, WI):
+    """Prefill of the cache at the batched int8 workload's shape: 16 sequences x 2048 prompt tokens, projected through
+    A_K and A_V (16.8 MB of bf16 factors), quantised and stored, 64 tokens of one sequence per launch
+    (wsvd_prefill_append).  A step = the whole cache of one layer (512 launches)."""
+    sp = WI.spec("c3")
+    B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
+    CH = 64
+    steps = args.steps if args.steps != 320 else 5
+    warmup = args.warmup if args.warmup != 32 else 1
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, T, "i8", "bf16", "bf16", "i8", "f32", 0.0)
+    dws = W.layer_desc(CH, Hq, Hkv, d, E, r, T, "i8", "bf16", "bf16", "i8", "f32", 0.0)
+    ctx = W.wsvd_create(0)
+    ws = torch.empty(max(W.wsvd_workspace_bytes(desc), W.wsvd_workspace_bytes(dws)), dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(ctx, ws)
+    cb, mb = W.wsvd_cache_bytes(desc)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    bf16_bits = lambda x32: dev((np.ascontiguousarray(x32, np.float32).view(np.uint32) >> 16).astype(np.uint16).view(np.int16))
+    AK, AV, _, _ = WI.factors(sp)
+    abytes = W.wsvd_factor_a_bytes(desc)
+    AKd = torch.empty(abytes, dtype=torch.uint8, device="cuda"); AVd = torch.empty(abytes, dtype=torch.uint8, device="cuda")
+    W.wsvd_pack_factor_a(ctx, desc, bf16_bits(AK), AKd); W.wsvd_pack_factor_a(ctx, desc, bf16_bits(AV), AVd)
+    k = torch.zeros(cb, dtype=torch.uint8, device="cuda"); v = torch.zeros(cb, dtype=torch.uint8, device="cuda")
+    km = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm = torch.zeros(mb, dtype=torch.uint8, device="cuda")
+    sl = torch.zeros(B, dtype=torch.int32, device="cuda")
+    cache = W.make_cache(k, v, km, vm, sl)
+    X = bf16_bits(WI.hidden_states(sp, T, 1.0, which="ctx", sub=0))          # one prompt's hidden states, reused per sequence
+    torch.cuda.synchronize()
+
+    def step():
+        sl.zero_()
+        for b in range(B):
+            for t0 in range(0, T, CH):
+                W.wsvd_prefill_append(ctx, desc, X[t0:t0 + CH], None, CH, b, AKd, AVd, cache)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            step()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            step()
+        e1.record(stream)
+        stream.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        assert W.wsvd_check(ctx, stream) == 0
+        assert (sl == T).all()
+    n_launch = B * (T // CH)
+    us_launch = ms * 1e3 / n_launch
+    factor_bytes = 2 * Hkv * E * r * 2
+    flops = 2.0 * CH * E * (2 * Hkv * r)
+    res = {
+        "metric": "prefill_cache_tokens_per_s", "value": round(B * T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4), "us_per_launch": round(us_launch, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "prefill: latent cache of one layer from hidden states, B=16 T=2048 d_model=4096 Hkv=32 r=32, "
+                               "int8 latents, 64 tokens of one sequence per launch",
+                   "batch": B, "context": T, "d_model": E, "kv_heads": Hkv, "rank": r, "tokens_per_launch": CH,
+                   "launches_per_step": n_launch, "launch": "eager"},
+        "roofline": {"kernel": "k_append_mfma<32,512,2> (projection of 64 tokens, quantise, store)", "bound": "hbm",
+                     "achieved": round(factor_bytes / (us_launch * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(factor_bytes / (us_launch * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(factor_bytes), "avg_launch_us": round(us_launch, 3),
+                     "mfma_view": {"achieved": round(flops / (us_launch * 1e-6) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                   "frac": round(flops / (us_launch * 1e-6) / 1e12 / 2500.0, 4)}},
     }
     print(json.dumps(res))
     W.wsvd_destroy(ctx)

@@ -225,6 +225,21 @@ wsvd_status wsvd_cache_export(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_
                               void *hip_stream);
 
 /*
+ * Prefill of the cache (Section 3.4: during prefilling the input sequence is projected into low-rank latents and the K, V
+ * latents are stored as the cache): x [n_tokens, E] holds consecutive tokens of ONE sequence, seq_index; token i is
+ * projected like wsvd_latent_append's rows, stored at row seq_lens[seq_index] + i of every kv head, and the length
+ * advances by n_tokens.  1 <= n_tokens <= 64 per call (a long prompt is a loop of calls); x, x_scale, A_K, A_V as for
+ * wsvd_latent_append.  The workspace must be large enough for a descriptor whose batch is n_tokens
+ * (WSVD_E_WORKSPACE otherwise).  Rows beyond t_cap are not stored: the sequence is left full and WSVD_E_CAPACITY is
+ * recorded in the device status word.  F32, BF16 and I8 latents (WSVD_E_UNSUPPORTED for I4, whose value plane packs two
+ * tokens into a byte: use wsvd_quantize_rows + wsvd_cache_import for those).  Attention over the prompt itself is not
+ * part of this call.
+ */
+wsvd_status wsvd_prefill_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
+                                int32_t n_tokens, int32_t seq_index, const void *A_K, const void *A_V, wsvd_cache *cache,
+                                void *hip_stream);
+
+/*
  * The rest of the decoding pipeline (Section 3.4, decoding-pipeline figure): the query is per-head low-rank too, and
  * the V-path up-projection is fused into the output projection.
  *

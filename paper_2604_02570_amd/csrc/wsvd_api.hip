@@ -187,6 +187,26 @@ wsvd_status wsvd_latent_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* x, const void* x_scale, int32_t n_tokens,
+                                int32_t seq_index, const void* A_K, const void* A_V, wsvd_cache* cache, void* hip_stream) {
+  if (!ctx || !x || !A_K || !A_V) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
+  if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
+  if (n_tokens < 1 || n_tokens > 64 || seq_index < 0 || seq_index >= desc->batch) return WSVD_E_SHAPE;
+  // two tokens of one sequence share the bytes of an int4 value plane: their stores would race within one launch
+  if (desc->latent_dtype == WSVD_I4) return WSVD_E_UNSUPPORTED;
+  wsvd_layer_desc d = *desc;
+  d.batch = n_tokens;                       // rows of x in this launch
+  size_t need;
+  wsvd_workspace_bytes(&d, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  hipError_t e = wsvd_launch_append(ctx, d, x, x_scale, A_K, A_V, *cache, (hipStream_t)hip_stream, seq_index);
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn_rope(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                                   const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len,
                                   float rope_base, void* out, void* hip_stream) {

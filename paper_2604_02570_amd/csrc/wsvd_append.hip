@@ -139,6 +139,7 @@ void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const voi
   p.B = d.batch; p.E = d.d_model; p.Hkv = d.n_kv_heads; p.t_cap = d.t_cap;
   p.ES = wsvd_append_esplits(d); p.ESL = d.d_model / p.ES;
   p.x_dtype = d.x_dtype; p.factor_dtype = d.factor_dtype; p.latent_dtype = d.latent_dtype;
+  p.one_seq = -1;
 }
 
 // waves per workgroup of the MFMA path: each wave gets a multiple of 16 elements, at least 64; up to 16 waves
@@ -152,9 +153,10 @@ int wsvd_append_mfma_waves(const wsvd_layer_desc& d) {
 bool wsvd_append_uses_mfma(const wsvd_layer_desc& d) { return append_mfma_path(d); }
 
 hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,
-                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s) {
+                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s, int one_seq) {
   AppendParams p;
   wsvd_append_params(ctx, d, x, x_scale, A_K, A_V, cache, p);
+  p.one_seq = one_seq;
   if (d.d_model % 64 != 0 || d.batch > kAppendMaxB) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.ES * p.Hkv * 2));
   const bool f32 = d.factor_dtype == WSVD_F32;

@@ -21,7 +21,17 @@ struct AppendParams {
   int fused;
   int epoch;
   int* flags;
+  // prefill of one sequence: all B rows of x are consecutive tokens of sequence one_seq (>= 0); token i goes to row
+  // seq_lens[one_seq] + i and the length advances by B.  -1: one token per sequence (decode).
+  int one_seq;
 };
+
+// which sequence a row of x belongs to, and the cache row it goes to given that sequence's length
+WSVD_DEV int append_seq_of(const AppendParams& p, int b) { return p.one_seq >= 0 ? p.one_seq : b; }
+WSVD_DEV int append_target_row(const AppendParams& p, int b) {
+  const int n = p.seq_lens[append_seq_of(p, b)];
+  return (p.one_seq >= 0 && n >= 0) ? n + b : n;
+}
 
 // Row stores.  In the fused decode step the attention workgroups of the SAME launch read the new row, possibly from
 // another XCD, so there the bytes go out with agent-scope stores.
@@ -163,19 +173,19 @@ WSVD_DEV void append_store_rows(const AppendParams& p, int pl, int kv, int b0, i
     const float c = crow[row][j];
     if (p.latent_dtype == WSVD_I8 || p.latent_dtype == WSVD_I4) {
       // the reductions need every lane of the wave: rows that must not be stored are redirected to a scratch-free no-op
-      if (__builtin_amdgcn_ballot_w64(on) == ~0ull) store_row_lanes<R>(p, pl, b0 + row, kv, n, j, c);
+      if (__builtin_amdgcn_ballot_w64(on) == ~0ull) store_row_lanes<R>(p, pl, append_seq_of(p, b0 + row), kv, n, j, c);
       else if (on) {                                   // ragged tail or a sequence at capacity: per-row sequential path
-        if (j == 0) store_row<R>(p, pl, b0 + row, kv, n, crow[row]);
+        if (j == 0) store_row<R>(p, pl, append_seq_of(p, b0 + row), kv, n, crow[row]);
       }
     } else if (on) {
-      store_row_lanes<R>(p, pl, b0 + row, kv, n, j, c);
+      store_row_lanes<R>(p, pl, append_seq_of(p, b0 + row), kv, n, j, c);
     }
   }
 }
 
 // sequence lengths -> LDS
 WSVD_DEV void append_read_lens(const AppendParams& p, int* n_sh) {
-  for (int b = threadIdx.x; b < p.B; b += blockDim.x) n_sh[b] = p.seq_lens[b];
+  for (int b = threadIdx.x; b < p.B; b += blockDim.x) n_sh[b] = append_target_row(p, b);
   __syncthreads();
 }
 
@@ -196,6 +206,15 @@ WSVD_DEV void append_bump(const AppendParams& p, const int* n_sh, int ticket /* 
   }
   __syncthreads();
   if (!*flag_sh) return;
+  if (p.one_seq >= 0) {
+    // the rows that fitted were stored; a prompt that does not fit leaves the sequence full and is reported
+    if (threadIdx.x == 0) {
+      const int n0 = n_sh[0];
+      if (n0 >= 0) p.seq_lens[p.one_seq] = min(n0 + p.B, p.t_cap);
+      if (n0 < 0 || n0 + p.B > p.t_cap) atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
+    }
+    return;
+  }
   for (int b = threadIdx.x; b < p.B; b += blockDim.x) {
     const int n = n_sh[b];
     if (n >= 0 && n < p.t_cap) p.seq_lens[b] = n + 1;
@@ -314,7 +333,7 @@ WSVD_DEV void append_mfma_body(const AppendParams& p, AppendMfmaShared<R, NG>& s
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
   int nreg[NLEN];
 #pragma unroll
-  for (int i = 0; i < NLEN; i++) nreg[i] = p.seq_lens[min(i * (int)blockDim.x + tid, p.B - 1)];
+  for (int i = 0; i < NLEN; i++) nreg[i] = append_target_row(p, min(i * (int)blockDim.x + tid, p.B - 1));
 
   const int ew = p.ESL / NW;                                 // d_model elements per wave (multiple of 16)
   const int ks_n = ew / 16;

@@ -1,0 +1,118 @@
+"""GPU parity tests for the prefill of the cache: consecutive tokens of one sequence projected, stored and counted in
+chunks of up to 64 (wsvd_prefill_append), against the oracle's ``latent_prefill``."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2604_02570_amd as W
+import wsvd_inputs as WI
+from cases import build_case
+from harness import as_dtype_dev, q_to_device
+from test_gpu_parity import check_out, layer_for, run_attend
+
+pytestmark = pytest.mark.gpu
+
+
+def _big_workspace(L, n_tokens=64):
+    """A workspace that also serves a chunk of n_tokens rows (sized with a descriptor whose batch is n_tokens)."""
+    d64 = type(L.desc).from_buffer_copy(L.desc)
+    d64.batch = n_tokens
+    need = max(W.wsvd_workspace_bytes(d64), W.wsvd_workspace_bytes(L.desc))
+    L.ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(L.ctx, L.ws)
+
+
+def _compare_rows(L, oc, b, t0, n, dtype):
+    """Rows [t0, t0 + n) of sequence b, both planes, against the oracle's cache.  Returns the number of accepted
+    one-step differences (values that sit on a rounding boundary of the storage format)."""
+    flips = 0
+    for plane, codes, scale in ((0, oc.k, oc.k_scale), (1, oc.v, oc.v_scale)):
+        gc, gs, _ = L.download(plane, t0, n)
+        gc = gc[b]; want = codes[b, :, t0:t0 + n]
+        if dtype == "f32":
+            np.testing.assert_allclose(gc.view(np.float32).reshape(want.shape), want, rtol=2e-5, atol=1e-6)
+        elif dtype == "bf16":
+            d = np.abs(gc.view(np.uint16).reshape(want.shape).astype(np.int32) - want.astype(np.int32))
+            assert d.max() <= 1 and (d != 0).mean() <= 5e-3, "bf16 latents differ by more than a rare last-bit rounding"
+            flips += int((d != 0).sum())
+        else:
+            ws = scale[b, :, t0:t0 + n]
+            same = gs[b].reshape(ws.shape) == ws
+            assert same.mean() >= 0.99, "row scales differ"
+            d = np.abs(gc.reshape(want.shape).astype(np.int32) - want.astype(np.int32))[same]
+            assert d.max() <= 1 and (d != 0).mean() <= 2e-3, "codes differ by more than a rare rounding-boundary step"
+            flips += int((d != 0).sum()) + int((~same).sum())
+    return flips
+
+
+@pytest.mark.parametrize("name,over", [("c3_small", dict()), ("c2_small", dict()), ("c1", dict(batch=2, context=70)),
+                                       ("c5_small", dict()), ("c3_small", dict(rank=64))], ids=["i8", "bf16", "f32", "i8r64g7", "i8r64"])
+def test_prefill_matches_oracle(name, over):
+    c = build_case(name, extra_cap=256, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    xdt = "f32" if sp.factor_dtype == "f32" else "bf16"
+    b = sp.batch - 1
+    n_total = 150
+    X = WI.hidden_states(sp, n_total, 1.0, which="ctx", sub=77)
+    if xdt == "bf16":
+        X = WI.bf16_exact(X)
+    AKd, AVd = L.pack_A(c.AK, sp.factor_dtype), L.pack_A(c.AV, sp.factor_dtype)
+    xd = as_dtype_dev(X, xdt)
+    n0 = int(c.cache.seq_lens[b])
+    others = c.cache.seq_lens.copy()
+    # the layer's workspace was sized for its own batch: a 64-token chunk needs more, and says so
+    if sp.batch < 64:
+        with pytest.raises(W.WsvdError) as e:
+            W.wsvd_prefill_append(L.ctx, L.desc, xd, None, 64, b, AKd, AVd, L.cache)
+        assert e.value.status == W.E_WORKSPACE
+    _big_workspace(L)
+    assert not O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    for i0, n in ((0, 64), (64, 64), (128, 22)):
+        W.wsvd_prefill_append(L.ctx, L.desc, xd[i0:i0 + n], None, n, b, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == 0
+    others[b] = n0 + n_total
+    assert (L.seq_lens.cpu().numpy() == others).all() and (c.cache.seq_lens == others).all()
+    flips = _compare_rows(L, c.cache, b, n0, n_total, sp.latent_dtype)
+    print(f"prefill {name}: one-step differences accepted = {flips}", flush=True)
+    # rows of the other sequences and the old rows of this one are untouched
+    m = int(min(others.min(), n0))
+    for plane, codes in ((0, c.cache.k), (1, c.cache.v)):
+        gc, _, _ = L.download(plane, 0, m)
+        assert (gc.reshape(codes[:, :, :m].shape) == codes[:, :, :m]).all()
+    # attention over the prefilled cache (GPU rows on the GPU side, oracle rows on the oracle side)
+    got, ref = run_attend(c, L)
+    check_out(got, ref, sp.latent_dtype, f"attention after prefill, {name}")
+    L.close()
+
+
+def test_prefill_capacity_int4_and_arguments():
+    c = build_case("c3_small", extra_cap=0)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    _big_workspace(L)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    X = WI.bf16_exact(WI.hidden_states(sp, 64, 1.0, which="ctx", sub=5))
+    xd = as_dtype_dev(X, "bf16")
+    b = 0
+    n0 = int(c.cache.seq_lens[b]); room = L.t_cap - n0
+    assert 0 < room < 64
+    assert O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, 64, b, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == W.E_CAPACITY
+    assert int(L.seq_lens[b]) == L.t_cap
+    _compare_rows(L, c.cache, b, n0, room, "i8")            # the rows that fitted are there
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, 3, b, AKd, AVd, L.cache)   # a full sequence: nothing stored, reported
+    assert W.wsvd_check(L.ctx) == W.E_CAPACITY and int(L.seq_lens[b]) == L.t_cap
+    for bad_n, bad_b in ((0, 0), (65, 0), (4, -1), (4, sp.batch)):
+        with pytest.raises(W.WsvdError) as e:
+            W.wsvd_prefill_append(L.ctx, L.desc, xd, None, bad_n, bad_b, AKd, AVd, L.cache)
+        assert e.value.status == W.E_SHAPE
+    L.close()
+    c4 = build_case("c4_small")
+    L4 = layer_for(c4); L4.upload(c4.cache)
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_prefill_append(L4.ctx, L4.desc, xd, None, 4, 0, AKd, AVd, L4.cache)
+    assert e.value.status == W.E_UNSUPPORTED
+    L4.close()
