@@ -53,7 +53,7 @@ __all__ = [
     "bf16_bits_from_f32", "f64_from_bf16_bits", "to_f64",
     "quantize_int8_rows", "dequantize_int8_rows",
     "quantize_int4_rows", "dequantize_int4_rows", "pack_int4", "unpack_int4",
-    "LatentCache", "project_latents", "latent_append", "latent_prefill",
+    "LatentCache", "project_latents", "latent_append", "latent_prefill", "causal_attn_reconstructed",
     "dequant_cache_rows", "decode_attn_reconstructed", "decode_attn_absorbed",
     "rope_inv_freq", "rope_rotate", "decode_attn_rope_reconstructed",
     "softmax_weights",
@@ -331,6 +331,29 @@ def decode_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndar
         s = sm_scale * (K @ q64[b, h])                               # [n]
         p = softmax_weights(s)
         out[b, h] = p @ V
+    return out
+
+
+def causal_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndarray, BV64: np.ndarray, sm_scale: float,
+                              n_after: int = 0) -> np.ndarray:
+    """Attention of several consecutive query tokens per sequence over the cache, each token seeing the rows up to and
+    including its own (prefill / multi-token decode; Section 3.4 runs the same reconstruction during prefilling).
+    q64 [B,Hkv,nq,G,d]: query token i of sequence b sits at row seq_lens[b] - n_after - nq + i of the cache (the nq
+    tokens' latents are already stored, followed by n_after later rows) and attends rows [0, that row].
+    K = C_K B_K, V = C_V B_V materialised, plain softmax.  Returns [B,Hkv,nq,G,d]; a token whose row index is negative
+    gets zeros."""
+    B, Hkv, nq, G, d = q64.shape
+    out = np.zeros_like(q64)
+    for b in range(B):
+        for kv in range(Hkv):
+            for i in range(nq):
+                n_vis = int(cache.seq_lens[b]) - n_after - nq + i + 1
+                if n_vis <= 0:
+                    continue
+                K = dequant_cache_rows(cache, "k", b, kv, n_vis) @ BK64[kv]
+                V = dequant_cache_rows(cache, "v", b, kv, n_vis) @ BV64[kv]
+                for g in range(G):
+                    out[b, kv, i, g] = softmax_weights(sm_scale * (K @ q64[b, kv, i, g])) @ V
     return out
 
 

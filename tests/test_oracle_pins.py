@@ -585,3 +585,32 @@ def test_prefill_equals_successive_appends():
                 np.testing.assert_array_equal(getattr(a, name)[1, :, :16], getattr(b, name)[1, :, :16])
                 np.testing.assert_array_equal(getattr(a, name)[0, :, :5], getattr(b, name)[0, :, :5])
         assert O.latent_prefill(a, 1, X, AK, AV) is True and a.seq_lens[1] == 20
+
+
+@pytest.mark.parametrize("dtype,G,n_after", [("f32", 1, 0), ("i8", 2, 3)])
+def test_causal_attention_against_torch_mask(dtype, G, n_after):
+    """K, V formed with torch, attention by torch with an explicit boolean mask; one query token reduces to the decode
+    routine."""
+    rng = np.random.default_rng(41)
+    B, Hkv, n, r, d, nq = 2, 2, 23, 8, 16, 5
+    cache = _rand_cache(rng, B, Hkv, n, r, dtype)
+    q = rng.standard_normal((B, Hkv, nq, G, d)); BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    sm = 0.3
+    got = O.causal_attn_reconstructed(cache, q, BK, BV, sm, n_after=n_after)
+    t = torch.from_numpy
+    K = torch.einsum("bknr,krc->bknc", t(_dequant_all(cache, "k")), t(BK))          # [B,Hkv,n,d]
+    V = torch.einsum("bknr,krc->bknc", t(_dequant_all(cache, "v")), t(BV))
+    pos = n - n_after - nq + torch.arange(nq)                                         # row of query token i
+    mask = (torch.arange(n)[None, :] <= pos[:, None])                                 # [nq, n]
+    for g in range(G):
+        ref = torch.nn.functional.scaled_dot_product_attention(t(q[:, :, :, g]), K, V, attn_mask=mask, scale=sm).numpy()
+        np.testing.assert_allclose(got[:, :, :, g], ref, rtol=1e-11, atol=1e-12)
+    # a single query token that is the newest row: the decode routine
+    q1 = q[:, :, -1:, :, :]
+    one = O.causal_attn_reconstructed(cache, q1, BK, BV, sm)
+    dec = O.decode_attn_reconstructed(cache, q1.reshape(B, Hkv * G, d), BK, BV, sm)
+    np.testing.assert_allclose(one.reshape(B, Hkv * G, d), dec, rtol=1e-12, atol=1e-13)
+    # tokens before the start of the sequence get zeros
+    cache.seq_lens[:] = 2
+    z = O.causal_attn_reconstructed(cache, q, BK, BV, sm)
+    assert (z[:, :, :3] == 0).all() and np.abs(z[:, :, 3:]).min() > 0
