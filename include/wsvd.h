@@ -240,6 +240,21 @@ wsvd_status wsvd_prefill_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, cons
                                 void *hip_stream);
 
 /*
+ * Attention of several consecutive query tokens per sequence, each seeing the cache rows up to and including its own
+ * (the attention of prefilling, Section 3.4, in chunks; also multi-token decoding).  The n_q tokens' latents are already
+ * in the cache (wsvd_prefill_append), followed by n_after later rows: query token i of sequence b sits at row
+ * seq_lens[b] - n_after - n_q + i.  A token whose row index is negative, and every token of an empty sequence, gets
+ * zeros.
+ *   q and out: [B, Hkv, n_q, G, d] (kv head, then token, then the G = Hq / Hkv query heads of that kv head), q of
+ *   desc->q_dtype (F32 or BF16; WSVD_E_DTYPE for I8), out F32.  n_q * G <= 8 query slots per launch, I8 latents, BF16
+ *   factors (WSVD_E_UNSUPPORTED otherwise).  The workspace must be large enough for a descriptor with Hkv * n_q * G
+ *   query heads (WSVD_E_WORKSPACE otherwise).  max_seq_len, stream, pointer and error conventions as wsvd_decode_attn.
+ */
+wsvd_status wsvd_prefill_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, int32_t n_q, int32_t n_after,
+                              const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len, void *out,
+                              void *hip_stream);
+
+/*
  * The rest of the decoding pipeline (Section 3.4, decoding-pipeline figure): the query is per-head low-rank too, and
  * the V-path up-projection is fused into the output projection.
  *

@@ -27,7 +27,8 @@ EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_by
            "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
-           "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append"]
+           "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
+           "wsvd_prefill_attn"]
 
 
 class WsvdError(RuntimeError):
@@ -92,6 +93,8 @@ def lib():
         L.wsvd_probe_stream_read.argtypes = [c_void_p, c_void_p, c_size_t, c_int32, c_void_p]
         L.wsvd_prefill_append.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
                                           POINTER(Cache), c_void_p]
+        L.wsvd_prefill_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_int32, c_void_p, c_void_p, POINTER(Cache),
+                                        c_int32, c_void_p, c_void_p]
         L.wsvd_fold_qk.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
         L.wsvd_fold_vo.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p]
         L.wsvd_decode_attn_latent.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_void_p, POINTER(Cache), c_int32,
@@ -246,6 +249,11 @@ def wsvd_linear_w4a8(ctx, x, x_scale, w_i4, w_scale, M, K, N, out, stream=None):
 def wsvd_prefill_append(ctx, desc, x, x_scale, n_tokens, seq_index, A_K, A_V, cache, stream=None):
     _ck(lib().wsvd_prefill_append(ctx, byref(desc), _ptr(x), _ptr(x_scale), int(n_tokens), int(seq_index), _ptr(A_K), _ptr(A_V),
                                   byref(cache), _stream(stream)), "wsvd_prefill_append")
+
+
+def wsvd_prefill_attn(ctx, desc, q, n_q, n_after, B_K, B_V, cache, max_seq_len, out, stream=None):
+    _ck(lib().wsvd_prefill_attn(ctx, byref(desc), _ptr(q), int(n_q), int(n_after), _ptr(B_K), _ptr(B_V), byref(cache),
+                                int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_prefill_attn")
 
 
 def wsvd_fold_qk(ctx, desc, B_Q, rq, B_K, out, stream=None):

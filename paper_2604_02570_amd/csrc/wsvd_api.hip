@@ -207,6 +207,35 @@ wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, cons
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_prefill_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, int32_t n_q, int32_t n_after,
+                              const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len, void* out,
+                              void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  const int Gr = desc->n_q_heads / desc->n_kv_heads;
+  if (n_q < 1 || n_after < 0 || max_seq_len < 0) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  if (desc->q_dtype == WSVD_I8) return WSVD_E_DTYPE;          // one scale per sequence cannot serve several tokens
+  if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16 || n_q * Gr > 8) return WSVD_E_UNSUPPORTED;
+  wsvd_layer_desc d = *desc;
+  d.n_q_heads = desc->n_kv_heads * n_q * Gr;                  // query slots take the place of query heads
+  size_t need;
+  wsvd_workspace_bytes(&d, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, d, q, nullptr, B_K, B_V, *cache, max_seq_len, out, p, grid, threads, 0);
+  if (threads > 512) wsvd_attn_plan(ctx, d, q, nullptr, B_K, B_V, *cache, max_seq_len, out, p, grid, threads, 512);
+  p.nq = n_q; p.Gr = Gr; p.n_after = n_after;
+  hipError_t e = wsvd_launch_attn_multi(p, d.rank, grid, threads, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn_rope(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                                   const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len,
                                   float rope_base, void* out, void* hip_stream) {

@@ -31,6 +31,9 @@ struct AttnParams {
   const float* qk_fold;
   int rq;
   int out_dim;               // floats per (sequence, head) of out: d, or R for the latent-output variant
+  // several query tokens per sequence (prefill / multi-token decode) only: G = nq * Gr query slots per kv head, slot
+  // s = token s / Gr, head s % Gr; token i sits at row seq_lens - n_after - nq + i and sees the rows up to its own
+  int nq, Gr, n_after;
 };
 
 struct WorkItem {
@@ -224,11 +227,12 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
         float Mn = M;
 #pragma unroll
         for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, mv[k]);                          // a clamped duplicate cannot change a max
-        const float keep = __builtin_amdgcn_exp2f(M - Mn);                           // 0 on the first batch (M = -inf, Mn finite)
+        // 0 on the first batch (M = -inf); a slot that saw no row in any split so far keeps M = Mn = -inf
+        const float keep = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
         L *= keep; U *= keep;
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-          const float e = (c0 + k < w.n_splits) ? __builtin_amdgcn_exp2f(mv[k] - Mn) : 0.f;
+          const float e = (c0 + k < w.n_splits && mv[k] != -INFINITY) ? __builtin_amdgcn_exp2f(mv[k] - Mn) : 0.f;
           L = fmaf(lv[k], e, L);
           U = fmaf(uv[k], e, U);
         }
@@ -269,7 +273,7 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       a1 = group_sum<4>(a1);
       if (part == 0 && (i >> 2) < n_pair) {
         const float L = Lsh[g];
-        float2 r; r.x = a0 / L; r.y = a1 / L;
+        float2 r; r.x = L > 0.f ? a0 / L : 0.f; r.y = L > 0.f ? a1 / L : 0.f;   // no visible row at all: zeros
         *(float2*)&p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + 2 * c2] = r;
       }
     }

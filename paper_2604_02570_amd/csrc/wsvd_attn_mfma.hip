@@ -739,7 +739,8 @@ WSVD_DEV void load_gqa_tile(GqaTile<R>& t, const uint8_t* kplane, const uint8_t*
 
 // LATENT: the Q latent comes in and the latent-space output goes out (no factor is read); launched with exactly NT
 // threads.
-template <int R, int NT, bool LATENT = false>
+// MULTI: the query slots are nq consecutive tokens x Gr heads; each slot only sees the rows up to its token's own.
+template <int R, int NT, bool LATENT = false, bool MULTI = false>
 __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   constexpr int KK = R / 32;
   constexpr int NWMAX = NT / 64;
@@ -919,10 +920,14 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     }
   }
   const float qs = q_scale_value(p, blockIdx.z, qs_raw);
-  const WorkItem w = decode_work(p, n_raw);
+  const WorkItem w = decode_work(p, MULTI ? n_raw - p.n_after : n_raw);
   if (w.n == 0) { write_zero_outputs(p, w); return; }
   if (!w.active) return;
   const int tile_end = (w.row_end + 63) >> 6;
+  // MULTI: rows visible to slot a of this lane (rows [0, lim)); may be <= 0 for a token before the sequence's start
+  int lim[4];
+#pragma unroll
+  for (int a = 0; a < 4; a++) lim[a] = MULTI ? w.n - p.nq + (a + 4 * hf) / p.Gr + 1 : 0;
 
   // slot a of this lane is query a + 4*hf
   float delta[4], m[4], wref[4], omega[4], winv[4], lsum[4], u[4][KK];
@@ -969,19 +974,22 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
 #pragma unroll
       for (int a = 0; a < 4; a++) {
         const float dot = limbs_to_f32(acc[4 * a], acc[4 * a + 1], acc[4 * a + 2]);
-        const float s = valid ? ksc * dot * delta[a] : -INFINITY;
+        const bool vis = MULTI ? (valid && tile * 64 + blk * 32 + l32 < lim[a]) : valid;
+        const float s = vis ? ksc * dot * delta[a] : -INFINITY;
         if (__builtin_amdgcn_ballot_w64(s > m[a]) != 0) {          // a new running max for a query of either half
           const float mn = fmaxf(m[a], half_max(s, lane));
-          const float alpha = __builtin_amdgcn_exp2f(m[a] - mn);     // 1 in the half whose max did not move
+          // 1 in the half whose max did not move; MULTI: a half whose slot still has no visible row keeps -inf
+          const float alpha = (MULTI && m[a] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[a] - mn);
           flush(a);
 #pragma unroll
           for (int jj = 0; jj < KK; jj++) u[a][jj] *= alpha;
           lsum[a] *= alpha;
           m[a] = mn;
         }
-        const float pw = __builtin_amdgcn_exp2f(s - m[a]);
+        // (a slot that has not seen a visible row yet has m = -inf: its hidden rows must not turn into NaN)
+        const float pw = (MULTI && !vis) ? 0.f : __builtin_amdgcn_exp2f(s - m[a]);
         lsum[a] += pw;
-        const float wt = valid ? pw * vsc : 0.f;
+        const float wt = vis ? pw * vsc : 0.f;
         if (__builtin_amdgcn_ballot_w64(wt > wref[a]) != 0) {
           flush(a);
           const float wn = 2.f * half_max(wt, lane);
@@ -1051,7 +1059,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     for (int k = 1; k < NW; k++) M = fmaxf(M, wm[k][g]);
     float L = 0.f, U = 0.f;
     for (int k = 0; k < NW; k++) {
-      const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
+      const float e = (MULTI && wm[k][g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(wm[k][g] - M);
       L = fmaf(wls[k][g], e, L);
       U = fmaf(wu[k][g][j], e, U);
     }
@@ -1104,6 +1112,16 @@ hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int ra
   if (latent_dtype == WSVD_I8 && rank == 64) return launch_m_latent<64, false, 512>(p, grid, threads, s);
   if (latent_dtype == WSVD_I4 && rank == 32) return launch_m_latent<32, true, 1024>(p, grid, threads, s);
   return hipErrorNotSupported;
+}
+
+// Several query tokens per sequence, each seeing the rows up to its own: I8 latents, nq * Gr <= 8 query slots.
+hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (p.nq < 1 || p.Gr < 1 || p.nq * p.Gr != p.G || p.G > 8 || p.n_after < 0) return hipErrorInvalidValue;
+  if (threads > 512 || threads % 64) return hipErrorInvalidValue;
+  if (rank == 32) hipLaunchKernelGGL((k_attn_gqa<32, 512, false, true>), grid, dim3(threads), 0, s, p);
+  else if (rank == 64) hipLaunchKernelGGL((k_attn_gqa<64, 512, false, true>), grid, dim3(threads), 0, s, p);
+  else return hipErrorNotSupported;
+  return hipGetLastError();
 }
 
 // largest workgroup (threads) each instantiation may be launched with

@@ -46,6 +46,7 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
                                  const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, double rope_base,
                                  void* out, hipStream_t s);
 hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s);
+hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
 hipError_t wsvd_launch_rmsnorm_quant(const float* x, const float* y_add, const float* gain, float eps, int64_t rows,
                                      int64_t cols, float* x_out, int8_t* codes, void* scale_f16, hipStream_t s);
 hipError_t wsvd_launch_swiglu_quant(const float* gate_up, int64_t rows, int64_t F, int8_t* codes, void* scale_f16, hipStream_t s);

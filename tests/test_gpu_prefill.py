@@ -116,3 +116,121 @@ def test_prefill_capacity_int4_and_arguments():
         W.wsvd_prefill_append(L4.ctx, L4.desc, xd, None, 4, 0, AKd, AVd, L4.cache)
     assert e.value.status == W.E_UNSUPPORTED
     L4.close()
+
+
+# ------------------------------------------------------------------------------------------ attention over the prompt
+def _multi_q(c, nq, seed=9):
+    """Queries of nq tokens per sequence in the layout [B, Hkv, nq, G, d], bf16-exact."""
+    sp = c.sp
+    G = sp.n_q_heads // sp.n_kv_heads
+    rng = np.random.default_rng(seed)
+    return WI.bf16_exact(rng.standard_normal((sp.batch, sp.n_kv_heads, nq, G, sp.d_head)).astype(np.float32))
+
+
+def _prefill_attn(L, c, q32, nq, n_after, max_len, q_dtype="bf16"):
+    sp = c.sp
+    G = sp.n_q_heads // sp.n_kv_heads
+    d = type(L.desc).from_buffer_copy(L.desc)
+    d.q_dtype = W.DTYPES[q_dtype]
+    dws = type(d).from_buffer_copy(d); dws.n_q_heads = sp.n_kv_heads * nq * G
+    L.ws = torch.empty(max(W.wsvd_workspace_bytes(dws), W.wsvd_workspace_bytes(L.desc)), dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(L.ctx, L.ws)
+    out = torch.full(q32.shape, float("nan"), dtype=torch.float32, device="cuda")
+    W.wsvd_prefill_attn(L.ctx, d, as_dtype_dev(q32, q_dtype), nq, n_after, as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16"),
+                        L.cache, max_len, out)
+    assert W.wsvd_check(L.ctx) == 0
+    return out.cpu().numpy().astype(np.float64)
+
+
+MULTI_CASES = [
+    ("c3_small", 8, 0, dict()),                                     # 8 tokens of one head per kv head
+    ("c3_small", 5, 0, dict(context=2000, batch=2)),                # several chunks of context
+    ("c3_small", 4, 11, dict(n_q_heads=8, n_kv_heads=4)),           # 4 tokens x 2 heads, 11 later rows in the cache
+    ("c3_small", 1, 0, dict(n_q_heads=16, n_kv_heads=2)),           # one token: the decode case through this entry
+    ("c5_small", 1, 0, dict()),                                     # rank 64, 7 heads per kv head
+    ("c3_small", 8, 64, dict(rank=64, context=700)),                # a full tile of later rows
+    ("c3_small", 3, 0, dict(context=130, q="f32")),
+]
+
+
+@pytest.mark.parametrize("name,nq,n_after,over", MULTI_CASES, ids=[f"{n}-nq{q}-after{a}-{'-'.join(f'{k}{v}' for k, v in o.items())}" for n, q, a, o in MULTI_CASES])
+def test_prefill_attention_matches_oracle(name, nq, n_after, over):
+    over = dict(over)
+    qd = over.pop("q", "bf16")
+    c = build_case(name, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    q32 = _multi_q(c, nq)
+    got = _prefill_attn(L, c, q32, nq, n_after, int(c.cache.seq_lens.max()), qd)
+    ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64),
+                                      c.sm_scale, n_after=n_after)
+    check_out(got, ref, "i8", f"prefill attention {name} nq={nq} n_after={n_after} {over}")
+    if nq > 1:      # the tokens really see different prefixes: dropping the mask would change the first token's output
+        full = O.causal_attn_reconstructed(c.cache, q32[:, :, :1].astype(np.float64), c.BK.astype(np.float64),
+                                           c.BV.astype(np.float64), c.sm_scale, n_after=n_after)
+        assert np.abs(full - ref[:, :, :1]).max() > 1e-4
+    L.close()
+
+
+def test_prefill_attention_short_sequences_and_errors():
+    """Sequences shorter than the token block (some tokens before the start), an empty one, lengths around tile edges."""
+    lens = [0, 1, 3, 8, 63, 64, 65, 66, 127, 128, 129, 200]
+    c = build_case("c3_small", batch=len(lens), context=200, ragged=(), extra_cap=0, steps=1)
+    for b, n in enumerate(lens):
+        c.cache.seq_lens[b] = n
+    L = layer_for(c); L.upload(c.cache)
+    nq = 4
+    q32 = _multi_q(c, nq)
+    got = _prefill_attn(L, c, q32, nq, 0, 200)
+    ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    assert (got[0] == 0).all() and (got[1, :, :3] == 0).all() and (got[2, :, :1] == 0).all()
+    check_out(got, ref, "i8", "prefill attention, short sequences")
+    d = L.desc
+    qd = as_dtype_dev(q32, "bf16")
+    out = torch.empty(q32.shape, dtype=torch.float32, device="cuda")
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    with pytest.raises(W.WsvdError) as e:            # the layer's own query type is int8
+        W.wsvd_prefill_attn(L.ctx, d, qd, nq, 0, BKd, BVd, L.cache, 200, out)
+    assert e.value.status == W.E_DTYPE
+    d2 = type(d).from_buffer_copy(d); d2.q_dtype = W.DTYPES["bf16"]
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_prefill_attn(L.ctx, d2, qd, 9, 0, BKd, BVd, L.cache, 200, out)
+    assert e.value.status == W.E_UNSUPPORTED
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_prefill_attn(L.ctx, d2, qd, 0, 0, BKd, BVd, L.cache, 200, out)
+    assert e.value.status == W.E_SHAPE
+    L.close()
+
+
+def test_prompt_prefill_end_to_end():
+    """A 150-token prompt: cache built in chunks of 64, attention of all its tokens in blocks of 8 with the later rows
+    already in the cache; every token's output against the oracle's causal attention over the oracle's own cache."""
+    c = build_case("c3_small", batch=2, context=37, extra_cap=256)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    _big_workspace(L)
+    b, n_total = 1, 150
+    X = WI.bf16_exact(WI.hidden_states(sp, n_total, 1.0, which="ctx", sub=3))
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    xd = as_dtype_dev(X, "bf16")
+    O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    for i0 in range(0, n_total, 64):
+        n = min(64, n_total - i0)
+        W.wsvd_prefill_append(L.ctx, L.desc, xd[i0:i0 + n], None, n, b, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == 0
+    n_end = int(c.cache.seq_lens[b])
+    rng = np.random.default_rng(12)
+    q_all = WI.bf16_exact(rng.standard_normal((sp.n_kv_heads, n_total, 1, sp.d_head)).astype(np.float32))   # [Hkv, tokens, G=1, d]
+    worst = 0.0
+    for i0 in (0, 8, 64, 136, 142):               # blocks at the start, across the chunk edge, and the ragged end
+        nq = min(8, n_total - i0)
+        n_after = n_total - i0 - nq
+        q32 = np.zeros((sp.batch, sp.n_kv_heads, nq, 1, sp.d_head), np.float32)
+        q32[b] = q_all[:, i0:i0 + nq]
+        got = _prefill_attn(L, c, q32, nq, n_after, n_end)
+        # sequence 0 is shorter than n_after: all its tokens are before its start
+        ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64),
+                                          c.sm_scale, n_after=n_after)
+        assert (got[0] == 0).all() or int(c.cache.seq_lens[0]) > n_after
+        check_out(got[b:b + 1], ref[b:b + 1], "i8", f"prompt tokens {i0}..{i0 + nq - 1}")
+    L.close()
