@@ -826,11 +826,10 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   GqaTile<R> buf[DEPTH];
   const int chunk_tiles = p.chunk_rows >> 6;
   int T = (int)blockIdx.y * chunk_tiles + wave;
-  {
-    const int spec_last = min(((int)blockIdx.y + 1) * chunk_tiles, p.t_cap >> 6) - 1;
-#pragma unroll
-    for (int i = 0; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
-  }
+  // Only the first tile goes out before the absorption: a wave cannot start on q~ before it has ISSUED its tile loads,
+  // and with every wave of the CU queueing two tiles that alone takes a couple of microseconds for the last one.
+  const int spec_last = min(((int)blockIdx.y + 1) * chunk_tiles, p.t_cap >> 6) - 1;
+  load_gqa_tile<R>(buf[0], kplane, vplane, kmeta, vmeta, min(T, spec_last), lane);
 
   if constexpr (LATENT) {
     float* qflat = &qpart[0][0][0];                     // [4][G * R] partial sums
@@ -883,6 +882,8 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
       for (int v = 0; v < 16; v++) qpart[wave][8 * (v >> 2) + 4 * hf + (v & 3)][l32] = qacc[v];
     }
   }
+#pragma unroll
+  for (int i = 1; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
   __syncthreads();
   // limbs of all 8 slots; slots past G are zero so they contribute nothing and cost nothing extra
   for (int idx = tid; idx < GS * R; idx += blockDim.x) {
