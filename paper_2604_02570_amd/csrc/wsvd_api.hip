@@ -168,6 +168,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { g_append_mode = value; return WSVD_OK; }
   if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { g_wsvd_linear_direct = value; return WSVD_OK; }
+  if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { g_wsvd_prefill_tiled = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
@@ -219,7 +220,14 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const 
   if (n_q < 1 || n_after < 0 || max_seq_len < 0) return WSVD_E_SHAPE;
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
   if (desc->q_dtype == WSVD_I8) return WSVD_E_DTYPE;          // one scale per sequence cannot serve several tokens
-  if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16 || n_q * Gr > 8) return WSVD_E_UNSUPPORTED;
+  if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
+  if ((int64_t)n_q * Gr > 8 || (g_wsvd_prefill_tiled && desc->q_dtype == WSVD_BF16)) {
+    // more query rows than the decode kernel has slots: the tiled kernel (one wavefront per 32 query rows)
+    if (desc->q_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
+    hipError_t e = wsvd_launch_prefill_attn(*desc, q, n_q, n_after, B_K, B_V, *cache, out, (hipStream_t)hip_stream);
+    if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+    return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+  }
   wsvd_layer_desc d = *desc;
   d.n_q_heads = desc->n_kv_heads * n_q * Gr;                  // query slots take the place of query heads
   size_t need;

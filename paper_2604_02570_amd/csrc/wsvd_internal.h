@@ -47,6 +47,10 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
                                  void* out, hipStream_t s);
 hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s);
 hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
+// tiled causal attention of nq query tokens per sequence (I8 latents, BF16 factors and queries); any nq
+hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int nq, int n_after, const void* B_K, const void* B_V,
+                                    const wsvd_cache& cache, void* out, hipStream_t s);
+extern int g_wsvd_prefill_tiled;   // option "prefill_tiled": 1 = the tiled kernel also for blocks of up to 8 query slots
 hipError_t wsvd_launch_rmsnorm_quant(const float* x, const float* y_add, const float* gain, float eps, int64_t rows,
                                      int64_t cols, float* x_out, int8_t* codes, void* scale_f16, hipStream_t s);
 hipError_t wsvd_launch_swiglu_quant(const float* gate_up, int64_t rows, int64_t F, int8_t* codes, void* scale_f16, hipStream_t s);

@@ -132,9 +132,10 @@ def _prefill_attn(L, c, q32, nq, n_after, max_len, q_dtype="bf16"):
     G = sp.n_q_heads // sp.n_kv_heads
     d = type(L.desc).from_buffer_copy(L.desc)
     d.q_dtype = W.DTYPES[q_dtype]
-    dws = type(d).from_buffer_copy(d); dws.n_q_heads = sp.n_kv_heads * nq * G
-    L.ws = torch.empty(max(W.wsvd_workspace_bytes(dws), W.wsvd_workspace_bytes(L.desc)), dtype=torch.uint8, device="cuda")
-    W.wsvd_set_workspace(L.ctx, L.ws)
+    if nq * G <= 8:        # the slot kernel merges context splits through the workspace; the tiled kernel needs none
+        dws = type(d).from_buffer_copy(d); dws.n_q_heads = sp.n_kv_heads * nq * G
+        L.ws = torch.empty(max(W.wsvd_workspace_bytes(dws), W.wsvd_workspace_bytes(L.desc)), dtype=torch.uint8, device="cuda")
+        W.wsvd_set_workspace(L.ctx, L.ws)
     out = torch.full(q32.shape, float("nan"), dtype=torch.float32, device="cuda")
     W.wsvd_prefill_attn(L.ctx, d, as_dtype_dev(q32, q_dtype), nq, n_after, as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16"),
                         L.cache, max_len, out)
@@ -233,4 +234,80 @@ def test_prompt_prefill_end_to_end():
                                           c.sm_scale, n_after=n_after)
         assert (got[0] == 0).all() or int(c.cache.seq_lens[0]) > n_after
         check_out(got[b:b + 1], ref[b:b + 1], "i8", f"prompt tokens {i0}..{i0 + nq - 1}")
+    L.close()
+
+
+# ------------------------------------------------------------------------------------------ tiled kernel (any n_q)
+TILED_CASES = [
+    ("c3_small", 32, 0, dict()),                                    # exactly one block of query rows
+    ("c3_small", 333, 0, dict()),                                   # the whole sequence as the prompt
+    ("c3_small", 50, 7, dict(context=2000, batch=2)),               # ragged last block, later rows in the cache
+    ("c3_small", 40, 0, dict(n_q_heads=8, n_kv_heads=4)),           # two heads per kv head: 80 query rows
+    ("c5_small", 20, 3, dict()),                                    # rank 64, seven heads per kv head: 140 rows
+    ("c3_small", 64, 64, dict(rank=64, context=700)),
+    ("c3_small", 9, 0, dict(d_head=64)),                            # head dim 64
+]
+
+
+@pytest.mark.parametrize("name,nq,n_after,over", TILED_CASES, ids=[f"{n}-nq{q}-after{a}-{'-'.join(f'{k}{v}' for k, v in o.items())}" for n, q, a, o in TILED_CASES])
+def test_prefill_attention_tiled_matches_oracle(name, nq, n_after, over):
+    c = build_case(name, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    q32 = _multi_q(c, nq, seed=21)
+    got = _prefill_attn(L, c, q32, nq, n_after, int(c.cache.seq_lens.max()))
+    ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64),
+                                      c.sm_scale, n_after=n_after)
+    check_out(got, ref, "i8", f"tiled prefill attention {name} nq={nq} n_after={n_after} {over}")
+    L.close()
+
+
+def test_prefill_attention_tiled_equals_slot_kernel_and_handles_short_sequences():
+    lens = [0, 1, 3, 8, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200]
+    c = build_case("c3_small", batch=len(lens), context=200, ragged=(), extra_cap=0, steps=1)
+    for b, n in enumerate(lens):
+        c.cache.seq_lens[b] = n
+    L = layer_for(c); L.upload(c.cache)
+    # 40 tokens: most sequences are shorter than the block, many tokens sit before the start
+    q32 = _multi_q(c, 40, seed=5)
+    got = _prefill_attn(L, c, q32, 40, 0, 200)
+    ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    assert (got[0] == 0).all() and (got[2, :, :37] == 0).all()
+    check_out(got, ref, "i8", "tiled prefill attention, short sequences")
+    # up to 8 slots both kernels apply: same result within the int8 bar of each against the oracle, and close to each other
+    q8 = _multi_q(c, 6, seed=6)
+    a = _prefill_attn(L, c, q8, 6, 2, 200)
+    W.wsvd_set_option("prefill_tiled", 1)
+    try:
+        t = _prefill_attn(L, c, q8, 6, 2, 200)
+    finally:
+        W.wsvd_set_option("prefill_tiled", 0)
+    ref8 = O.causal_attn_reconstructed(c.cache, q8.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale, n_after=2)
+    check_out(t, ref8, "i8", "tiled kernel, 6 tokens")
+    check_out(a, ref8, "i8", "slot kernel, 6 tokens")
+    assert np.abs(a - t).max() < 1e-3
+    L.close()
+
+
+def test_whole_prompt_in_one_call():
+    """Cache built in chunks of 64, then the attention of all 150 prompt tokens in a single launch."""
+    c = build_case("c3_small", batch=2, context=37, extra_cap=256)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    _big_workspace(L)
+    b, n_total = 1, 150
+    X = WI.bf16_exact(WI.hidden_states(sp, n_total, 1.0, which="ctx", sub=3))
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    xd = as_dtype_dev(X, "bf16")
+    O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    for i0 in range(0, n_total, 64):
+        n = min(64, n_total - i0)
+        W.wsvd_prefill_append(L.ctx, L.desc, xd[i0:i0 + n], None, n, b, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == 0
+    q32 = _multi_q(c, n_total, seed=13)
+    got = _prefill_attn(L, c, q32, n_total, 0, int(c.cache.seq_lens.max()))
+    ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    # sequence 0 holds 37 rows: its last 37 query tokens see a prefix, the first 113 sit before its start
+    assert (got[0, :, :113] == 0).all() and np.abs(got[0, :, 113:]).min() > 0
+    check_out(got, ref, "i8", "whole prompt, one launch")
     L.close()
