@@ -701,14 +701,33 @@ def run_prefill(args, np, torch, W, WI):
         a1.record(stream); stream.synchronize()
         ms_attn = a0.elapsed_time(a1) / steps
         assert W.wsvd_check(ctx, stream) == 0 and torch.isfinite(ob).all()
+        # the same attention in ONE launch of the tiled kernel: all 2048 query tokens of every sequence
+        G = Hq // Hkv
+        qall = bf16_bits(WI.normal(sp.seed, 98, (B, Hkv, T, G, d)))
+        oall = torch.empty((B, Hkv, T, G, d), dtype=torch.float32, device="cuda")
+        W.wsvd_prefill_attn(ctx, dq, qall, T, 0, BKd, BVd, cache, T, oall); stream.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record(stream)
+        for _ in range(steps):
+            W.wsvd_prefill_attn(ctx, dq, qall, T, 0, BKd, BVd, cache, T, oall)
+        t1.record(stream); stream.synchronize()
+        ms_tiled = t0.elapsed_time(t1) / steps
+        assert W.wsvd_check(ctx, stream) == 0 and torch.isfinite(oall).all()
     n_launch = B * (T // CH)
     us_launch = ms * 1e3 / n_launch
     factor_bytes = 2 * Hkv * E * r * 2
     flops = 2.0 * CH * E * (2 * Hkv * r)
     res = {
-        "metric": "prefill_tokens_per_s_per_layer", "value": round(B * T / ((ms + ms_attn) * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
-        "steps": steps, "warmup": warmup, "ms_per_step": round(ms + ms_attn, 4), "cache_build_ms": round(ms, 4),
-        "prompt_attention_ms": round(ms_attn, 4), "us_per_launch": round(us_launch, 3),
+        "metric": "prefill_tokens_per_s_per_layer", "value": round(B * T / ((ms + ms_tiled) * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(ms + ms_tiled, 4), "cache_build_ms": round(ms, 4),
+        "prompt_attention_ms": round(ms_tiled, 4), "us_per_launch": round(us_launch, 3),
+        "prompt_attention_tiled": {"launches": 1, "query_tokens_per_launch": T, "ms": round(ms_tiled, 4),
+                                   "score_pairs": int(B * Hq * T * (T + 1) // 2),
+                                   # per (query, key) pair and head: 2 r flops for the score and 2 r for the value, each done
+                                   # twice (two-term operands) on the matrix cores
+                                   "algorithmic_TFLOPs": round(B * Hq * T * (T + 1) / 2 * 4 * r / (ms_tiled * 1e-3) / 1e12, 2),
+                                   "mfma_TFLOPs_issued": round(B * Hq * T * (T + 1) / 2 * 8 * r / (ms_tiled * 1e-3) / 1e12, 2)},
+        "prompt_attention_in_blocks_of_8_ms": round(ms_attn, 4),
         "prompt_attention": {"launches": T // NQ, "query_tokens_per_launch": NQ, "us_per_launch": round(ms_attn * 1e3 / (T // NQ), 3),
                              "latent_bytes_streamed": int(B * Hkv * 2 * (r + 2) * sum(range(NQ, T + 1, NQ))),
                              "GBps": round(B * Hkv * 2 * (r + 2) * sum(range(NQ, T + 1, NQ)) / (ms_attn * 1e-3) / 1e9, 1)},

@@ -246,9 +246,11 @@ wsvd_status wsvd_prefill_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, cons
  * seq_lens[b] - n_after - n_q + i.  A token whose row index is negative, and every token of an empty sequence, gets
  * zeros.
  *   q and out: [B, Hkv, n_q, G, d] (kv head, then token, then the G = Hq / Hkv query heads of that kv head), q of
- *   desc->q_dtype (F32 or BF16; WSVD_E_DTYPE for I8), out F32.  n_q * G <= 8 query slots per launch, I8 latents, BF16
- *   factors (WSVD_E_UNSUPPORTED otherwise).  The workspace must be large enough for a descriptor with Hkv * n_q * G
- *   query heads (WSVD_E_WORKSPACE otherwise).  max_seq_len, stream, pointer and error conventions as wsvd_decode_attn.
+ *   desc->q_dtype (F32 or BF16; WSVD_E_DTYPE for I8), out F32.  I8 latents, BF16 factors (WSVD_E_UNSUPPORTED otherwise).
+ *   n_q * G <= 8: the decode kernel with one query slot per (token, head); the workspace must be large enough for a
+ *   descriptor with Hkv * n_q * G query heads (WSVD_E_WORKSPACE otherwise).  n_q * G > 8: a tiled kernel, BF16 queries
+ *   only (WSVD_E_UNSUPPORTED for F32), no workspace, any n_q (a whole prompt in one call); max_seq_len is not used by it.
+ *   Stream, pointer and error conventions as wsvd_decode_attn.
  */
 wsvd_status wsvd_prefill_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, int32_t n_q, int32_t n_after,
                               const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len, void *out,
