@@ -54,6 +54,8 @@ def parse():
                          "(secondary lines, same JSON shape)")
     ap.add_argument("--linear-direct", action="store_true",
                     help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
+    ap.add_argument("--project-shape", type=int, default=0, choices=[0, 21, 24, 42, 44],
+                    help="prefill: channel tiles x token tiles per wavefront of the tiled projection (tuning; 0 = the library's choice)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -651,7 +653,10 @@ def run_prefill(args, np, torch, W, WI):
     km = torch.zeros(mb, dtype=torch.uint8, device="cuda"); vm = torch.zeros(mb, dtype=torch.uint8, device="cuda")
     sl = torch.zeros(B, dtype=torch.int32, device="cuda")
     cache = W.make_cache(k, v, km, vm, sl)
-    X = bf16_bits(WI.hidden_states(sp, T, 1.0, which="ctx", sub=0))          # one prompt's hidden states, reused per sequence
+    X = bf16_bits(WI.hidden_states(sp, T, 1.0, which="ctx", sub=0))          # one prompt's hidden states ...
+    Xall = X.unsqueeze(0).repeat(B, 1, 1).contiguous()                        # ... for every sequence: [B, T, E]
+    if args.project_shape:
+        W.wsvd_set_option("project_shape", args.project_shape)
     torch.cuda.synchronize()
 
     def step():
@@ -671,9 +676,27 @@ def run_prefill(args, np, torch, W, WI):
             step()
         e1.record(stream)
         stream.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+        ms_chunks = e0.elapsed_time(e1) / steps
         assert W.wsvd_check(ctx, stream) == 0
         assert (sl == T).all()
+        k_ref = k.clone(); km_ref = km.clone()
+        # the same cache in ONE launch of the tiled projection: all 2048 tokens of all 16 sequences
+        def step_tiled():
+            sl.zero_()
+            W.wsvd_prefill_append(ctx, desc, Xall, None, T, -1, AKd, AVd, cache)
+        k.zero_(); km.zero_()
+        for _ in range(max(warmup, 1)):
+            step_tiled()
+        stream.synchronize()
+        assert W.wsvd_check(ctx, stream) == 0 and (sl == T).all()
+        same = float((k == k_ref).float().mean()); same_m = float((km == km_ref).float().mean())
+        assert same > 0.998 and same_m > 0.995, (same, same_m)       # both kernels round the same products in another order
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record(stream)
+        for _ in range(steps):
+            step_tiled()
+        p1.record(stream); stream.synchronize()
+        ms = p0.elapsed_time(p1) / steps
         # attention over the prompt: blocks of 8 query tokens of every sequence, the whole cache already in place
         NQ = 8
         dq = W.layer_desc(B, Hq, Hkv, d, E, r, T, "i8", "bf16", "bf16", "bf16", "f32", 0.0)
@@ -714,13 +737,15 @@ def run_prefill(args, np, torch, W, WI):
         ms_tiled = t0.elapsed_time(t1) / steps
         assert W.wsvd_check(ctx, stream) == 0 and torch.isfinite(oall).all()
     n_launch = B * (T // CH)
-    us_launch = ms * 1e3 / n_launch
-    factor_bytes = 2 * Hkv * E * r * 2
-    flops = 2.0 * CH * E * (2 * Hkv * r)
+    us_launch = ms_chunks * 1e3 / n_launch
+    flops = 2.0 * B * T * E * (2 * Hkv * r)                  # the projection of every token through A_K and A_V
+    proj_bytes = B * T * E * 2 + 2 * Hkv * E * r * 2 + B * Hkv * T * 2 * (r + 2)
     res = {
         "metric": "prefill_tokens_per_s_per_layer", "value": round(B * T / ((ms + ms_tiled) * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": round(ms + ms_tiled, 4), "cache_build_ms": round(ms, 4),
-        "prompt_attention_ms": round(ms_tiled, 4), "us_per_launch": round(us_launch, 3),
+        "prompt_attention_ms": round(ms_tiled, 4),
+        "cache_build_in_chunks_of_64": {"launches": n_launch, "ms": round(ms_chunks, 4), "us_per_launch": round(us_launch, 3),
+                                        "codes_equal_to_one_launch": round(same, 6), "scales_equal": round(same_m, 6)},
         "prompt_attention_tiled": {"launches": 1, "query_tokens_per_launch": T, "ms": round(ms_tiled, 4),
                                    "score_pairs": int(B * Hq * T * (T + 1) // 2),
                                    # per (query, key) pair and head: 2 r flops for the score and 2 r for the value, each done
@@ -733,16 +758,15 @@ def run_prefill(args, np, torch, W, WI):
                              "GBps": round(B * Hkv * 2 * (r + 2) * sum(range(NQ, T + 1, NQ)) / (ms_attn * 1e-3) / 1e9, 1)},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "prefill: latent cache of one layer from hidden states, then causal attention over the prompt, "
-                               "B=16 T=2048 d_model=4096 H=32 r=32, int8 latents; 64 tokens of one sequence per cache launch, "
-                               "8 query tokens of every sequence per attention launch",
-                   "batch": B, "context": T, "d_model": E, "kv_heads": Hkv, "rank": r, "tokens_per_launch": CH,
-                   "launches_per_step": n_launch, "launch": "eager"},
-        "roofline": {"kernel": "k_append_mfma<32,512,2> (projection of 64 tokens, quantise, store)", "bound": "hbm",
-                     "achieved": round(factor_bytes / (us_launch * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(factor_bytes / (us_launch * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "algorithmic_bytes_per_launch": int(factor_bytes), "avg_launch_us": round(us_launch, 3),
-                     "mfma_view": {"achieved": round(flops / (us_launch * 1e-6) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
-                                   "frac": round(flops / (us_launch * 1e-6) / 1e12 / 2500.0, 4)}},
+                               "B=16 T=2048 d_model=4096 H=32 r=32, int8 latents; one launch for the cache of all sequences "
+                               "and one for the attention of all query tokens",
+                   "batch": B, "context": T, "d_model": E, "kv_heads": Hkv, "rank": r, "launch": "eager"},
+        "roofline": {"kernel": "k_prefill_project (bf16 projection of all prompt tokens, quantise, store)", "bound": "mfma",
+                     "achieved": round(flops / (ms * 1e-3) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                     "frac": round(flops / (ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
+                     "algorithmic_flops_per_launch": int(flops), "avg_launch_us": round(ms * 1e3, 2),
+                     "hbm_view": {"algorithmic_bytes_per_launch": int(proj_bytes),
+                                  "achieved": round(proj_bytes / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s"}},
     }
     print(json.dumps(res))
     W.wsvd_destroy(ctx)

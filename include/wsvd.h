@@ -228,12 +228,15 @@ wsvd_status wsvd_cache_export(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_
  * Prefill of the cache (Section 3.4: during prefilling the input sequence is projected into low-rank latents and the K, V
  * latents are stored as the cache): x [n_tokens, E] holds consecutive tokens of ONE sequence, seq_index; token i is
  * projected like wsvd_latent_append's rows, stored at row seq_lens[seq_index] + i of every kv head, and the length
- * advances by n_tokens.  1 <= n_tokens <= 64 per call (a long prompt is a loop of calls); x, x_scale, A_K, A_V as for
- * wsvd_latent_append.  The workspace must be large enough for a descriptor whose batch is n_tokens
- * (WSVD_E_WORKSPACE otherwise).  Rows beyond t_cap are not stored: the sequence is left full and WSVD_E_CAPACITY is
- * recorded in the device status word.  F32, BF16 and I8 latents (WSVD_E_UNSUPPORTED for I4, whose value plane packs two
- * tokens into a byte: use wsvd_quantize_rows + wsvd_cache_import for those).  Attention over the prompt itself is not
- * part of this call.
+ * advances by n_tokens.  x, x_scale, A_K, A_V as for wsvd_latent_append.  Up to 64 tokens per call for every
+ * supported format (the append kernels; the workspace must be large enough for a descriptor whose batch is n_tokens,
+ * WSVD_E_WORKSPACE otherwise); any number of tokens per call with I8 latents and BF16 hidden states and factors (a tiled
+ * projection on the matrix cores, no workspace; WSVD_E_SHAPE for n_tokens > 64 with other formats).  With those formats
+ * seq_index = -1 stores n_tokens rows for EVERY sequence of the batch in one launch: x is then [batch, n_tokens, d_model]
+ * and each sequence's rows start at its own length (WSVD_E_SHAPE for seq_index = -1 with other formats).  Rows beyond
+ * t_cap are not stored: the sequence is left full and WSVD_E_CAPACITY is recorded in the device status word.  F32, BF16
+ * and I8 latents (WSVD_E_UNSUPPORTED for I4, whose value plane packs two tokens into a byte: use wsvd_quantize_rows +
+ * wsvd_cache_import for those).  Attention over the prompt itself is not part of this call.
  */
 wsvd_status wsvd_prefill_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
                                 int32_t n_tokens, int32_t seq_index, const void *A_K, const void *A_V, wsvd_cache *cache,

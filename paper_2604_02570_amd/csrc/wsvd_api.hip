@@ -169,6 +169,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { g_wsvd_linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { g_wsvd_prefill_tiled = value; return WSVD_OK; }
+  if (!strcmp(name, "project_shape") && (value == 0 || value == 21 || value == 24 || value == 42 || value == 44)) { g_wsvd_project_shape = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
@@ -196,7 +197,17 @@ wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, cons
   if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
   if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
   if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
-  if (n_tokens < 1 || n_tokens > 64 || seq_index < 0 || seq_index >= desc->batch) return WSVD_E_SHAPE;
+  if (n_tokens < 1 || seq_index < -1 || seq_index >= desc->batch) return WSVD_E_SHAPE;
+  if (n_tokens > 64 || seq_index < 0 || g_wsvd_prefill_tiled) {
+    // a prompt-sized block, or all sequences at once: the tiled projection (one launch for all its tokens)
+    const bool fits = desc->latent_dtype == WSVD_I8 && desc->factor_dtype == WSVD_BF16 && desc->x_dtype == WSVD_BF16;
+    if (!fits && (n_tokens > 64 || seq_index < 0)) return WSVD_E_SHAPE;
+    if (fits) {
+      hipError_t e = wsvd_launch_prefill_project(ctx, *desc, x, n_tokens, seq_index, A_K, A_V, *cache, (hipStream_t)hip_stream);
+      if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+      return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+    }
+  }
   // two tokens of one sequence share the bytes of an int4 value plane: their stores would race within one launch
   if (desc->latent_dtype == WSVD_I4) return WSVD_E_UNSUPPORTED;
   wsvd_layer_desc d = *desc;

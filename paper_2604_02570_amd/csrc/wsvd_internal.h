@@ -50,7 +50,11 @@ hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int 
 // tiled causal attention of nq query tokens per sequence (I8 latents, BF16 factors and queries); any nq
 hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int nq, int n_after, const void* B_K, const void* B_V,
                                     const wsvd_cache& cache, void* out, hipStream_t s);
-extern int g_wsvd_prefill_tiled;   // option "prefill_tiled": 1 = the tiled kernel also for blocks of up to 8 query slots
+// projection + quantise + store of n_tok consecutive tokens of sequence seq, or of every sequence when seq < 0 (x then
+// holds [batch, n_tok, d_model]); I8 latents, BF16 x and factors; any n_tok
+hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
+                                       const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s);
+extern int g_wsvd_prefill_tiled, g_wsvd_project_shape;   // option "prefill_tiled": 1 = the tiled kernel also for blocks of up to 8 query slots
 hipError_t wsvd_launch_rmsnorm_quant(const float* x, const float* y_add, const float* gain, float eps, int64_t rows,
                                      int64_t cols, float* x_out, int8_t* codes, void* scale_f16, hipStream_t s);
 hipError_t wsvd_launch_swiglu_quant(const float* gate_up, int64_t rows, int64_t F, int8_t* codes, void* scale_f16, hipStream_t s);

@@ -285,7 +285,176 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
   }
 }
 
+// ---------------------------------------------------------------- cache build for a whole prompt (int8 latents)
+// C^T [channels x tokens] = A^T x^T on bf16 MFMA.  The channels of both planes form one axis of 2 * Hkv * r / 32 tiles
+// of 32; a wavefront owns CT channel tiles x TT token tiles (CT * TT accumulators of 32 x 32), so each 1 KiB operand it
+// fetches feeds CT or TT products.  The A operand is the packed factor image the append kernels use (1 KiB per
+// 32 channels x 16 model dims, contiguous); the B operand is 16 bytes of a token's hidden state per lane.  The 4 waves
+// of a workgroup take 4 neighbouring channel groups of the same tokens, so the hidden states come out of the CU's
+// first-level cache after the first wave; operands are requested ST - 1 steps ahead of the products that use them.
+// A lane ends up with 16 of every 32 channels of ITS tokens (the other half wave holds the rest): the per-token scale of
+// a head is a maximum over registers plus one exchange, and the codes go out in the decode layout (4 consecutive
+// channels of a K row are 4 adjacent bytes; a V row is written byte by byte, its neighbours in a 16-byte group being
+// other tokens).
+struct ProjectParams {
+  const uint16_t* x;          // bf16 [n_seq, n_tok, E]
+  const uint16_t* A[2];       // packed factors
+  uint8_t* codes[2];
+  uint16_t* meta[2];
+  int* seq_lens;
+  int* err_word;
+  int Hkv, E, t_cap, n_tok, seq0;   // grid z = sequence - seq0
+};
+
+template <int R, int CT, int TT>
+__global__ __launch_bounds__(256) void k_prefill_project(ProjectParams p) {
+  constexpr int RT = R / 32, ST = 3;
+  static_assert(CT % RT == 0, "a head's channels stay in one wave");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, g2 = lane >> 5;
+  const int tiles_plane = p.Hkv * RT, tiles = 2 * tiles_plane;
+  const int ct0 = (blockIdx.x * 4 + wave) * CT;                         // first channel tile of this wave
+  if (ct0 >= tiles) return;
+  const int seq = p.seq0 + blockIdx.z;
+  const int n0 = p.seq_lens[seq];
+  const int n_steps = p.E >> 4;
+  const uint16_t* ap[CT];
+#pragma unroll
+  for (int c = 0; c < CT; c++) {
+    const int ct = min(ct0 + c, tiles - 1);
+    ap[c] = p.A[ct / tiles_plane] + ((size_t)(ct % tiles_plane) * n_steps * 64 + lane) * 8;
+  }
+  const uint16_t* xp[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; tt++) {
+    const int tok = min((int)(blockIdx.y * TT + tt) * 32 + n, p.n_tok - 1);
+    xp[tt] = p.x + ((size_t)blockIdx.z * p.n_tok + tok) * p.E + 8 * g2;
+  }
+  v16f acc[CT][TT];
+#pragma unroll
+  for (int c = 0; c < CT; c++)
+#pragma unroll
+    for (int tt = 0; tt < TT; tt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[c][tt][v] = 0.f;
+  v8bf16 fa[ST][CT], fb[ST][TT];
+  auto fetch = [&](int st, int ks) {
+    ks = min(ks, n_steps - 1);
+#pragma unroll
+    for (int c = 0; c < CT; c++) fa[st][c] = *(const v8bf16*)(ap[c] + (size_t)ks * 512);
+#pragma unroll
+    for (int tt = 0; tt < TT; tt++) fb[st][tt] = *(const v8bf16*)(xp[tt] + 16 * ks);
+  };
+#pragma unroll
+  for (int u = 0; u < ST - 1; u++) fetch(u, u);
+  for (int ks0 = 0; ks0 < n_steps; ks0 += ST) {
+#pragma unroll
+    for (int u = 0; u < ST; u++) {
+      fetch((u + ST - 1) % ST, ks0 + u + ST - 1);
+      if (ks0 + u < n_steps) {
+#pragma unroll
+        for (int c = 0; c < CT; c++)
+#pragma unroll
+          for (int tt = 0; tt < TT; tt++) acc[c][tt] = mfma_bf16(fa[u][c], fb[u][tt], acc[c][tt]);
+      }
+    }
+  }
+  // per token and head: symmetric int8 (the latent quantiser's rule), then the stores
+#pragma unroll
+  for (int h = 0; h < CT / RT; h++) {
+    const int ct = ct0 + h * RT;
+    if (ct >= tiles) break;
+    const int pl = ct / tiles_plane, kv = (ct % tiles_plane) / RT;
+    const size_t ph = (size_t)seq * p.Hkv + kv;
+    uint8_t* plane = p.codes[pl] + ph * (size_t)p.t_cap * R;
+#pragma unroll
+    for (int tt = 0; tt < TT; tt++) {
+      float a = 0.f;
+#pragma unroll
+      for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[h * RT + rt][tt][v]));
+      a = fmaxf(a, __shfl_xor(a, 32));
+      uint16_t sh = 0x3C00u;
+      if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
+      const float sc = f16_bits_to_f32(sh);
+      const int tok = (int)(blockIdx.y * TT + tt) * 32 + n;             // this lane's token of the prompt
+      const int t = n0 + tok;                                           // and its cache row
+      if (tok >= p.n_tok || n0 < 0 || t >= p.t_cap) continue;
+#pragma unroll
+      for (int rt = 0; rt < RT; rt++)
+#pragma unroll
+        for (int m4 = 0; m4 < 4; m4++) {
+          uint32_t pk = 0;
+          int q[4];
+#pragma unroll
+          for (int jj = 0; jj < 4; jj++) {
+            q[jj] = (int)fminf(fmaxf(__builtin_rintf(acc[h * RT + rt][tt][4 * m4 + jj] / sc), -127.f), 127.f);
+            pk |= ((uint32_t)q[jj] & 0xFFu) << (8 * jj);
+          }
+          const int j0 = 32 * rt + 8 * m4 + 4 * g2;                     // channels j0 .. j0 + 3
+          if (pl == 0) *(uint32_t*)(plane + i8_k_offset(t, j0, R)) = pk;
+          else {
+#pragma unroll
+            for (int jj = 0; jj < 4; jj++) plane[i8_v_offset(t, j0 + jj, R)] = (uint8_t)q[jj];
+          }
+        }
+      if (g2 == 0) p.meta[pl][ph * p.t_cap + t] = sh;
+    }
+  }
+}
+
+// after the projection: the lengths move on by the rows that fitted (one thread per sequence)
+__global__ void k_prefill_bump(int* seq_lens, int seq0, int n_seq, int n_tok, int t_cap, int* err_word) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_seq) return;
+  const int n0 = seq_lens[seq0 + i];
+  if (n0 >= 0) seq_lens[seq0 + i] = min(n0 + n_tok, t_cap);
+  if (n0 < 0 || n0 + n_tok > t_cap) atomicExch(err_word, (int)WSVD_E_CAPACITY);
+}
+
+template <int R, int CT, int TT>
+void launch_project(const ProjectParams& p, int n_seq, hipStream_t s) {
+  const int tiles = 2 * p.Hkv * (R / 32);
+  dim3 grid((unsigned)((tiles + 4 * CT - 1) / (4 * CT)), (unsigned)((p.n_tok + 32 * TT - 1) / (32 * TT)), (unsigned)n_seq);
+  hipLaunchKernelGGL((k_prefill_project<R, CT, TT>), grid, dim3(256), 0, s, p);
+}
+
 }  // namespace
+
+int g_wsvd_project_shape = 0;
+
+hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
+                                       const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s) {
+  if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16 || d.x_dtype != WSVD_BF16) return hipErrorNotSupported;
+  if (d.rank != 32 && d.rank != 64) return hipErrorNotSupported;
+  if (d.d_model % 16 != 0 || n_tok < 1) return hipErrorInvalidValue;
+  ProjectParams p;
+  p.x = (const uint16_t*)x; p.A[0] = (const uint16_t*)A_K; p.A[1] = (const uint16_t*)A_V;
+  p.codes[0] = (uint8_t*)cache.k_codes; p.codes[1] = (uint8_t*)cache.v_codes;
+  p.meta[0] = (uint16_t*)cache.k_meta; p.meta[1] = (uint16_t*)cache.v_meta;
+  p.seq_lens = cache.seq_lens; p.err_word = ctx->err_word;
+  p.Hkv = d.n_kv_heads; p.E = d.d_model; p.t_cap = d.t_cap; p.n_tok = n_tok;
+  const int n_seq = seq < 0 ? d.batch : 1;
+  p.seq0 = seq < 0 ? 0 : seq;
+  // small problems: small wave tiles, so that there are enough waves; prompt-sized ones: 4 x 4 tiles per wave
+  const long long work = (long long)n_seq * n_tok * d.n_kv_heads * d.rank;
+  int shape = g_wsvd_project_shape ? g_wsvd_project_shape : (work >= (1LL << 22) ? 44 : 21);
+  if (d.rank == 32) {
+    if (shape == 44) launch_project<32, 4, 4>(p, n_seq, s);
+    else if (shape == 42) launch_project<32, 4, 2>(p, n_seq, s);
+    else if (shape == 24) launch_project<32, 2, 4>(p, n_seq, s);
+    else launch_project<32, 2, 1>(p, n_seq, s);
+  } else {
+    if (shape == 44) launch_project<64, 4, 4>(p, n_seq, s);
+    else if (shape == 42) launch_project<64, 4, 2>(p, n_seq, s);
+    else if (shape == 24) launch_project<64, 2, 4>(p, n_seq, s);
+    else launch_project<64, 2, 1>(p, n_seq, s);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_prefill_bump, dim3((n_seq + 63) / 64), dim3(64), 0, s, cache.seq_lens, p.seq0, n_seq, n_tok, d.t_cap, ctx->err_word);
+  return hipGetLastError();
+}
 
 int g_wsvd_prefill_tiled = 0;
 

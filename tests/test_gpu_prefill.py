@@ -105,7 +105,7 @@ def test_prefill_capacity_int4_and_arguments():
     _compare_rows(L, c.cache, b, n0, room, "i8")            # the rows that fitted are there
     W.wsvd_prefill_append(L.ctx, L.desc, xd, None, 3, b, AKd, AVd, L.cache)   # a full sequence: nothing stored, reported
     assert W.wsvd_check(L.ctx) == W.E_CAPACITY and int(L.seq_lens[b]) == L.t_cap
-    for bad_n, bad_b in ((0, 0), (65, 0), (4, -1), (4, sp.batch)):
+    for bad_n, bad_b in ((0, 0), (4, -2), (4, sp.batch)):
         with pytest.raises(W.WsvdError) as e:
             W.wsvd_prefill_append(L.ctx, L.desc, xd, None, bad_n, bad_b, AKd, AVd, L.cache)
         assert e.value.status == W.E_SHAPE
@@ -116,6 +116,109 @@ def test_prefill_capacity_int4_and_arguments():
         W.wsvd_prefill_append(L4.ctx, L4.desc, xd, None, 4, 0, AKd, AVd, L4.cache)
     assert e.value.status == W.E_UNSUPPORTED
     L4.close()
+
+
+@pytest.mark.parametrize("name,over", [("c3_small", dict()), ("c5_small", dict()), ("c3_small", dict(rank=64, batch=2, context=45))],
+                         ids=["i8", "i8r64g7", "i8r64"])
+def test_prefill_whole_prompt_projection_matches_oracle(name, over):
+    """More than 64 tokens in one call: the tiled projection (int8 latents, bf16 hidden states and factors)."""
+    c = build_case(name, extra_cap=320, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    b = sp.batch - 1
+    n_total = 150 + 33 + 1
+    X = WI.bf16_exact(WI.hidden_states(sp, n_total, 1.0, which="ctx", sub=78))
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    xd = as_dtype_dev(X, "bf16")
+    n0 = int(c.cache.seq_lens[b])
+    others = c.cache.seq_lens.copy()
+    assert not O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    W.wsvd_prefill_append(L.ctx, L.desc, xd[:150], None, 150, b, AKd, AVd, L.cache)       # 4 full tiles and a ragged one
+    W.wsvd_set_option("prefill_tiled", 1)                                                  # short chunks on the same kernel
+    try:
+        W.wsvd_prefill_append(L.ctx, L.desc, xd[150:183], None, 33, b, AKd, AVd, L.cache)
+        W.wsvd_prefill_append(L.ctx, L.desc, xd[183:], None, 1, b, AKd, AVd, L.cache)
+    finally:
+        W.wsvd_set_option("prefill_tiled", 0)
+    assert W.wsvd_check(L.ctx) == 0
+    others[b] = n0 + n_total
+    assert (L.seq_lens.cpu().numpy() == others).all() and (c.cache.seq_lens == others).all()
+    flips = _compare_rows(L, c.cache, b, n0, n_total, "i8")
+    print(f"tiled projection {name}: one-step differences accepted = {flips}", flush=True)
+    m = int(min(others.min(), n0))
+    for plane, codes in ((0, c.cache.k), (1, c.cache.v)):
+        gc, _, _ = L.download(plane, 0, m)
+        assert (gc.reshape(codes[:, :, :m].shape) == codes[:, :, :m]).all()
+    got, ref = run_attend(c, L)
+    check_out(got, ref, "i8", f"attention after the tiled projection, {name}")
+    L.close()
+
+
+@pytest.mark.parametrize("shape", [0, 44, 42, 24])
+def test_prefill_all_sequences_in_one_call(shape):
+    """seq_index = -1: the same number of prompt tokens for every sequence, x = [batch, n_tokens, d_model]; every wave-tile
+    shape of the projection."""
+    c = build_case("c3_small", extra_cap=192)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    n = 100
+    X = np.stack([WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=40 + b)) for b in range(sp.batch)])
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    xd = as_dtype_dev(X.reshape(sp.batch * n, -1), "bf16")
+    starts = c.cache.seq_lens.copy()
+    for b in range(sp.batch):
+        assert not O.latent_prefill(c.cache, b, X[b].astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    W.wsvd_set_option("project_shape", shape)
+    try:
+        W.wsvd_prefill_append(L.ctx, L.desc, xd, None, n, -1, AKd, AVd, L.cache)
+    finally:
+        W.wsvd_set_option("project_shape", 0)
+    assert W.wsvd_check(L.ctx) == 0
+    assert (L.seq_lens.cpu().numpy() == starts + n).all()
+    flips = sum(_compare_rows(L, c.cache, b, int(starts[b]), n, "i8") for b in range(sp.batch))
+    print(f"all sequences, shape {shape}: one-step differences accepted = {flips}", flush=True)
+    m = int(starts.min())
+    for plane, codes in ((0, c.cache.k), (1, c.cache.v)):
+        gc, _, _ = L.download(plane, 0, m)
+        assert (gc.reshape(codes[:, :, :m].shape) == codes[:, :, :m]).all()
+    got, ref = run_attend(c, L)
+    check_out(got, ref, "i8", f"attention after the projection of all sequences, shape {shape}")
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_prefill_append(L.ctx, L.desc, xd, None, n, -2, AKd, AVd, L.cache)
+    assert e.value.status == W.E_SHAPE
+    L.close()
+
+
+def test_prefill_whole_prompt_projection_capacity_and_formats():
+    c = build_case("c3_small", extra_cap=70)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    X = WI.bf16_exact(WI.hidden_states(sp, 200, 1.0, which="ctx", sub=6))
+    xd = as_dtype_dev(X, "bf16")
+    b = int(np.argmax(c.cache.seq_lens))
+    n0 = int(c.cache.seq_lens[b]); room = L.t_cap - n0
+    assert 64 < room < 200
+    before = L.seq_lens.cpu().numpy().copy()
+    assert O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, 200, b, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == W.E_CAPACITY
+    before[b] = L.t_cap
+    assert (L.seq_lens.cpu().numpy() == before).all()
+    _compare_rows(L, c.cache, b, n0, room, "i8")            # the rows that fitted are there
+    snap = L.download(0, 0, L.t_cap)[0].copy()
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, 100, b, AKd, AVd, L.cache)   # a full sequence: nothing stored, reported
+    assert W.wsvd_check(L.ctx) == W.E_CAPACITY and int(L.seq_lens[b]) == L.t_cap
+    assert (L.download(0, 0, L.t_cap)[0] == snap).all()
+    L.close()
+    # other formats take at most 64 tokens per call
+    for name in ("c2_small", "c4_small"):
+        c2 = build_case(name, extra_cap=128)
+        L2 = layer_for(c2); L2.upload(c2.cache)
+        with pytest.raises(W.WsvdError) as e:
+            W.wsvd_prefill_append(L2.ctx, L2.desc, xd, None, 65, 0, AKd, AVd, L2.cache)
+        assert e.value.status == W.E_SHAPE
+        L2.close()
 
 
 # ------------------------------------------------------------------------------------------ attention over the prompt
@@ -194,8 +297,9 @@ def test_prefill_attention_short_sequences_and_errors():
         W.wsvd_prefill_attn(L.ctx, d, qd, nq, 0, BKd, BVd, L.cache, 200, out)
     assert e.value.status == W.E_DTYPE
     d2 = type(d).from_buffer_copy(d); d2.q_dtype = W.DTYPES["bf16"]
-    with pytest.raises(W.WsvdError) as e:
-        W.wsvd_prefill_attn(L.ctx, d2, qd, 9, 0, BKd, BVd, L.cache, 200, out)
+    d3 = type(d).from_buffer_copy(d); d3.q_dtype = W.DTYPES["f32"]
+    with pytest.raises(W.WsvdError) as e:            # more than 8 query rows per kv head: bf16 queries only
+        W.wsvd_prefill_attn(L.ctx, d3, qd, 9, 0, BKd, BVd, L.cache, 200, out)
     assert e.value.status == W.E_UNSUPPORTED
     with pytest.raises(W.WsvdError) as e:
         W.wsvd_prefill_attn(L.ctx, d2, qd, 0, 0, BKd, BVd, L.cache, 200, out)
