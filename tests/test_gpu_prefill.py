@@ -154,14 +154,16 @@ def test_prefill_whole_prompt_projection_matches_oracle(name, over):
     L.close()
 
 
-@pytest.mark.parametrize("shape", [0, 44, 42, 24])
-def test_prefill_all_sequences_in_one_call(shape):
-    """seq_index = -1: the same number of prompt tokens for every sequence, x = [batch, n_tokens, d_model]; every wave-tile
-    shape of the projection."""
-    c = build_case("c3_small", extra_cap=192)
+@pytest.mark.parametrize("name,over,shape,n", [("c3_small", {}, 0, 100), ("c3_small", {}, 1, 100), ("c3_small", {}, 44, 100),
+                                               ("c3_small", {}, 42, 100), ("c3_small", {}, 24, 100), ("c3_small", dict(rank=64), 1, 100),
+                                               ("c5_small", {}, 1, 300), ("c3_small", dict(batch=2, context=40), 1, 515)],
+                         ids=["auto", "staged", "d44", "d42", "d24", "staged-r64", "staged-r64g7-300", "staged-515"])
+def test_prefill_all_sequences_in_one_call(name, over, shape, n):
+    """seq_index = -1: the same number of prompt tokens for every sequence, x = [batch, n_tokens, d_model]; the staged
+    projection kernel and every wave-tile shape of the direct one."""
+    c = build_case(name, extra_cap=n + 92, **over)
     sp = c.sp
     L = layer_for(c); L.upload(c.cache)
-    n = 100
     X = np.stack([WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=40 + b)) for b in range(sp.batch)])
     AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
     xd = as_dtype_dev(X.reshape(sp.batch * n, -1), "bf16")
