@@ -748,10 +748,10 @@ def run_prefill(args, np, torch, W, WI):
                                         "codes_equal_to_one_launch": round(same, 6), "scales_equal": round(same_m, 6)},
         "prompt_attention_tiled": {"launches": 1, "query_tokens_per_launch": T, "ms": round(ms_tiled, 4),
                                    "score_pairs": int(B * Hq * T * (T + 1) // 2),
-                                   # per (query, key) pair and head: 2 r flops for the score and 2 r for the value, each done
-                                   # twice (two-term operands) on the matrix cores
+                                   # per (query, key) pair and head: 2 r flops for the score (done twice: the query latent is a
+                                   # two-term fp16 operand) and 2 r for the value
                                    "algorithmic_TFLOPs": round(B * Hq * T * (T + 1) / 2 * 4 * r / (ms_tiled * 1e-3) / 1e12, 2),
-                                   "mfma_TFLOPs_issued": round(B * Hq * T * (T + 1) / 2 * 8 * r / (ms_tiled * 1e-3) / 1e12, 2)},
+                                   "mfma_TFLOPs_issued": round(B * Hq * T * (T + 1) / 2 * 6 * r / (ms_tiled * 1e-3) / 1e12, 2)},
         "prompt_attention_in_blocks_of_8_ms": round(ms_attn, 4),
         "prompt_attention": {"launches": T // NQ, "query_tokens_per_launch": NQ, "us_per_launch": round(ms_attn * 1e3 / (T // NQ), 3),
                              "latent_bytes_streamed": int(B * Hkv * 2 * (r + 2) * sum(range(NQ, T + 1, NQ))),

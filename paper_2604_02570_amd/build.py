@@ -9,9 +9,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwsvd.so")
 SOURCES = ["wsvd_api.hip", "wsvd_quant.hip", "wsvd_append.hip", "wsvd_attn_generic.hip", "wsvd_attn_mfma.hip",
-           "wsvd_block.hip", "wsvd_layer.hip", "wsvd_prefill.hip"]
+           "wsvd_block.hip", "wsvd_layer.hip", "wsvd_prefill.hip", "wsvd_project.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
+# per-file additions.  The prompt attention reads every score tile back into the vector ALU, which binds it: its matrix
+# products write ordinary vector registers instead of accumulation registers (no copies between the two files).
+FILE_FLAGS = {"wsvd_prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose: bool = True, extra_flags=()) -> str:
@@ -21,7 +24,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *FILE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     objs = []
     for src, obj, pr in procs:

@@ -391,7 +391,8 @@ def test_prefill_attention_tiled_equals_slot_kernel_and_handles_short_sequences(
     ref8 = O.causal_attn_reconstructed(c.cache, q8.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale, n_after=2)
     check_out(t, ref8, "i8", "tiled kernel, 6 tokens")
     check_out(a, ref8, "i8", "slot kernel, 6 tokens")
-    assert np.abs(a - t).max() < 1e-3
+    # the two kernels agree to the tiled one's operand rounding (fp16 values and weights: 2^-12 relative each)
+    assert np.abs(a - t).max() < 1e-3 * np.abs(ref8).max()
     L.close()
 
 
