@@ -335,25 +335,30 @@ def decode_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndar
 
 
 def causal_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndarray, BV64: np.ndarray, sm_scale: float,
-                              n_after: int = 0) -> np.ndarray:
+                              n_after: int = 0, tokens=None) -> np.ndarray:
     """Attention of several consecutive query tokens per sequence over the cache, each token seeing the rows up to and
     including its own (prefill / multi-token decode; Section 3.4 runs the same reconstruction during prefilling).
     q64 [B,Hkv,nq,G,d]: query token i of sequence b sits at row seq_lens[b] - n_after - nq + i of the cache (the nq
     tokens' latents are already stored, followed by n_after later rows) and attends rows [0, that row].
     K = C_K B_K, V = C_V B_V materialised, plain softmax.  Returns [B,Hkv,nq,G,d]; a token whose row index is negative
-    gets zeros."""
+    gets zeros.  tokens: optional list of (b, kv, i) to compute; every other entry of the result is NaN (large cases
+    are checked on a sample)."""
     B, Hkv, nq, G, d = q64.shape
-    out = np.zeros_like(q64)
-    for b in range(B):
-        for kv in range(Hkv):
-            for i in range(nq):
-                n_vis = int(cache.seq_lens[b]) - n_after - nq + i + 1
-                if n_vis <= 0:
-                    continue
-                K = dequant_cache_rows(cache, "k", b, kv, n_vis) @ BK64[kv]
-                V = dequant_cache_rows(cache, "v", b, kv, n_vis) @ BV64[kv]
-                for g in range(G):
-                    out[b, kv, i, g] = softmax_weights(sm_scale * (K @ q64[b, kv, i, g])) @ V
+    if tokens is None:
+        out = np.zeros_like(q64)
+        todo = [(b, kv, i) for b in range(B) for kv in range(Hkv) for i in range(nq)]
+    else:
+        out = np.full(q64.shape, np.nan)
+        todo = list(tokens)
+    for b, kv, i in todo:
+        out[b, kv, i] = 0.0
+        n_vis = int(cache.seq_lens[b]) - n_after - nq + i + 1
+        if n_vis <= 0:
+            continue
+        K = dequant_cache_rows(cache, "k", b, kv, n_vis) @ BK64[kv]
+        V = dequant_cache_rows(cache, "v", b, kv, n_vis) @ BV64[kv]
+        for g in range(G):
+            out[b, kv, i, g] = softmax_weights(sm_scale * (K @ q64[b, kv, i, g])) @ V
     return out
 
 

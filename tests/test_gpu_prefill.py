@@ -418,3 +418,50 @@ def test_whole_prompt_in_one_call():
     assert (got[0, :, :113] == 0).all() and np.abs(got[0, :, 113:]).min() > 0
     check_out(got, ref, "i8", "whole prompt, one launch")
     L.close()
+
+
+def test_prefill_full_size_sampled():
+    """The batched int8 workload's shape in the launch configuration the benchmark times: the cache of all 16 x 2048
+    prompt tokens in one launch, then the attention of all of them in one launch.  The oracle builds the cache of two
+    of the sequences itself and computes a sample of their tokens' outputs."""
+    c = build_case("c3")
+    sp = c.sp
+    T = sp.context
+    G = sp.n_q_heads // sp.n_kv_heads
+    L = layer_for(c)
+    L.seq_lens.zero_()
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    X = np.stack([WI.bf16_exact(WI.hidden_states(sp, T, 1.0, which="ctx", sub=100 + b)) for b in range(sp.batch)])
+    xd = as_dtype_dev(X.reshape(sp.batch * T, -1), "bf16")
+    print("full-size prefill: projection launch", flush=True)
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, T, -1, AKd, AVd, L.cache)
+    torch.cuda.synchronize()
+    assert W.wsvd_check(L.ctx) == 0 and (L.seq_lens.cpu().numpy() == T).all()
+    seqs = [0, sp.batch - 1]
+    oc = O.LatentCache(sp.batch, sp.n_kv_heads, L.t_cap, sp.rank, "i8")
+    AK64, AV64 = c.AK.astype(np.float64), c.AV.astype(np.float64)
+    flips = 0
+    for b in seqs:
+        assert not O.latent_prefill(oc, b, X[b].astype(np.float64), AK64, AV64)
+        flips += _compare_rows(L, oc, b, 0, T, "i8")
+    print(f"full-size prefill: one-step differences accepted in 2 x {T} x {sp.n_kv_heads} rows = {flips}", flush=True)
+    # attention of the whole prompt
+    rng = np.random.default_rng(77)
+    q32 = WI.bf16_exact(rng.standard_normal((sp.batch, sp.n_kv_heads, T, G, sp.d_head), dtype=np.float32))
+    d = type(L.desc).from_buffer_copy(L.desc)
+    d.q_dtype = W.DTYPES["bf16"]
+    out = torch.full(q32.shape, float("nan"), dtype=torch.float32, device="cuda")
+    print("full-size prefill: attention launch", flush=True)
+    W.wsvd_prefill_attn(L.ctx, d, as_dtype_dev(q32, "bf16"), T, 0, as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16"),
+                        L.cache, T, out)
+    torch.cuda.synchronize()
+    assert W.wsvd_check(L.ctx) == 0
+    assert bool(torch.isfinite(out).all())
+    toks = [(b, int(kv), int(i)) for b in seqs for kv in rng.integers(0, sp.n_kv_heads, 3)
+            for i in (0, 31, 32, 1000, T - 33, T - 1)]
+    ref = O.causal_attn_reconstructed(oc, q32, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale, tokens=toks)
+    got = np.full(q32.shape, np.nan)
+    for t in toks:
+        got[t] = out[t].cpu().numpy()
+    check_out(got, ref, "i8", f"full-size prompt attention, {len(toks)} sampled (sequence, head, token) triples")
+    L.close()

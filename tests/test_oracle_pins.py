@@ -614,3 +614,22 @@ def test_causal_attention_against_torch_mask(dtype, G, n_after):
     cache.seq_lens[:] = 2
     z = O.causal_attn_reconstructed(cache, q, BK, BV, sm)
     assert (z[:, :, :3] == 0).all() and np.abs(z[:, :, 3:]).min() > 0
+
+
+def test_causal_attention_sample_option_only_selects():
+    """The tokens= option of the causal attention computes the same values for the listed (sequence, head, token)
+    triples and leaves every other entry NaN."""
+    import wsvd_inputs as WI
+    from cases import build_case
+    c = build_case("c3_small", batch=2, context=40)
+    sp = c.sp
+    G = sp.n_q_heads // sp.n_kv_heads
+    rng = np.random.default_rng(2)
+    q = rng.standard_normal((sp.batch, sp.n_kv_heads, 5, G, sp.d_head))
+    BK, BV = c.BK.astype(np.float64), c.BV.astype(np.float64)
+    full = O.causal_attn_reconstructed(c.cache, q, BK, BV, c.sm_scale, n_after=1)
+    toks = [(0, 0, 0), (1, sp.n_kv_heads - 1, 4), (1, 1, 2)]
+    part = O.causal_attn_reconstructed(c.cache, q, BK, BV, c.sm_scale, n_after=1, tokens=toks)
+    for t in toks:
+        assert np.array_equal(part[t], full[t])
+    assert np.isnan(part).sum() == part.size - len(toks) * G * sp.d_head
