@@ -75,7 +75,8 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
   __shared__ __attribute__((aligned(16))) _Float16 pt[32][40];          // P in fp16, [query][key], padded rows
 
   const int lane = threadIdx.x, n = lane & 31, g2 = lane >> 5;
-  const int kv = blockIdx.x, qb = blockIdx.y, b = blockIdx.z;
+  // the last query blocks see the most keys: they are started first, so that the launch does not end on its longest waves
+  const int kv = blockIdx.x, qb = gridDim.y - 1 - blockIdx.y, b = blockIdx.z;
   const int nb = p.seq_lens[b];
   const int n_eff = min(max(nb - p.n_after, 0), p.t_cap);
   const int rho = qb * 32 + n;                                          // this lane's query row
