@@ -54,7 +54,7 @@ __all__ = [
     "quantize_int8_rows", "dequantize_int8_rows",
     "quantize_int4_rows", "dequantize_int4_rows", "pack_int4", "unpack_int4",
     "LatentCache", "project_latents", "latent_append", "latent_prefill", "causal_attn_reconstructed",
-    "dequant_cache_rows", "decode_attn_reconstructed", "decode_attn_absorbed",
+    "dequant_cache_rows", "decode_attn_reconstructed", "decode_attn_absorbed", "decode_attn_shared_latent",
     "rope_inv_freq", "rope_rotate", "decode_attn_rope_reconstructed",
     "softmax_weights",
     "traffic_ratio", "param_ratio_rho1", "cache_ratio_rho2", "cache_row_bytes",
@@ -331,6 +331,30 @@ def decode_attn_reconstructed(cache: LatentCache, q64: np.ndarray, BK64: np.ndar
         s = sm_scale * (K @ q64[b, h])                               # [n]
         p = softmax_weights(s)
         out[b, h] = p @ V
+    return out
+
+
+def decode_attn_shared_latent(cache: LatentCache, q64: np.ndarray, BK64: np.ndarray, BV64: np.ndarray,
+                              sm_scale: float, heads=None) -> np.ndarray:
+    """The conventional whole-matrix scheme the method is contrasted with (Section 3.1, its figure's panel (b), and the
+    "W/o per-head" variant of the latency appendix): ONE latent C_K = X A_K of rank R per token, shared by all heads;
+    head h reconstructs K_h = C_K B_Kh with its own B_Kh [R, d] (likewise V_h = C_V B_Vh) and attends as usual:
+    o_h = softmax(sm_scale * q_h K_h^T) V_h.
+
+    cache: a LatentCache with ONE kv head of rank R.  q64 [B,H,d], BK64/BV64 [H,R,d].  Returns [B,H,d] fp64; a
+    sequence with no rows yields zeros; ``heads`` restricts the (b,h) pairs computed (others NaN)."""
+    B, H, d = q64.shape
+    assert cache.Hkv == 1 and BK64.shape == (H, cache.r, d) and BV64.shape == (H, cache.r, d)
+    out = np.full((B, H, d), np.nan) if heads is not None else np.zeros((B, H, d))
+    pairs = heads if heads is not None else [(b, h) for b in range(B) for h in range(H)]
+    for (b, h) in pairs:
+        n = int(cache.seq_lens[b])
+        if n == 0:
+            out[b, h] = 0.0
+            continue
+        K = dequant_cache_rows(cache, "k", b, 0, n) @ BK64[h]        # [n,d]: every head reads the whole shared latent
+        V = dequant_cache_rows(cache, "v", b, 0, n) @ BV64[h]
+        out[b, h] = softmax_weights(sm_scale * (K @ q64[b, h])) @ V
     return out
 
 

@@ -633,3 +633,98 @@ def test_causal_attention_sample_option_only_selects():
     for t in toks:
         assert np.array_equal(part[t], full[t])
     assert np.isnan(part).sum() == part.size - len(toks) * G * sp.d_head
+
+
+# ------------------------------------------------------------------ shared-latent (whole-matrix) contrast, Section 3.1
+def test_shared_latent_attention_brute_force_tiny():
+    """Python loops over every index on a tiny case."""
+    rng = np.random.default_rng(5)
+    B, H, R, d, n = 2, 3, 4, 3, 5
+    cache = O.LatentCache(B, 1, 8, R, "f32")
+    cache.k[:] = rng.standard_normal(cache.k.shape).astype(np.float32)
+    cache.v[:] = rng.standard_normal(cache.v.shape).astype(np.float32)
+    cache.seq_lens[:] = [n, 0]
+    q = rng.standard_normal((B, H, d)); BK = rng.standard_normal((H, R, d)); BV = rng.standard_normal((H, R, d))
+    got = O.decode_attn_shared_latent(cache, q, BK, BV, 0.7)
+    assert (got[1] == 0).all()
+    for h in range(H):
+        s = []
+        for t in range(n):
+            acc = 0.0
+            for c in range(d):
+                kc = sum(float(cache.k[0, 0, t, j]) * BK[h, j, c] for j in range(R))
+                acc += q[0, h, c] * kc
+            s.append(0.7 * acc)
+        m = max(s); e = [np.exp(x - m) for x in s]; z = sum(e)
+        for c in range(d):
+            want = sum(e[t] / z * sum(float(cache.v[0, 0, t, j]) * BV[h, j, c] for j in range(R)) for t in range(n))
+            assert abs(got[0, h, c] - want) <= 1e-12 * (1 + abs(want))
+
+
+def test_shared_latent_with_block_factors_is_the_per_head_scheme():
+    """Per-head SVD is the shared scheme with block-structured up-projections: if the shared latent is the heads' latents
+    side by side and B_Kh is zero outside head h's block, both schemes give the same attention (fp32 caches, so no
+    quantiser in between)."""
+    rng = np.random.default_rng(8)
+    B, H, r, d, n = 2, 4, 8, 16, 37
+    per = O.LatentCache(B, H, 64, r, "f32")
+    per.k[:] = rng.standard_normal(per.k.shape).astype(np.float32); per.v[:] = rng.standard_normal(per.v.shape).astype(np.float32)
+    per.seq_lens[:] = [n, 11]
+    sh = O.LatentCache(B, 1, 64, H * r, "f32")
+    sh.k[:, 0] = np.transpose(per.k, (0, 2, 1, 3)).reshape(B, 64, H * r)
+    sh.v[:, 0] = np.transpose(per.v, (0, 2, 1, 3)).reshape(B, 64, H * r)
+    sh.seq_lens[:] = per.seq_lens
+    BK = rng.standard_normal((H, r, d)); BV = rng.standard_normal((H, r, d)); q = rng.standard_normal((B, H, d))
+    BKs = np.zeros((H, H * r, d)); BVs = np.zeros((H, H * r, d))
+    for h in range(H):
+        BKs[h, h * r:(h + 1) * r] = BK[h]; BVs[h, h * r:(h + 1) * r] = BV[h]
+    a = O.decode_attn_reconstructed(per, q, BK, BV, 0.3)
+    b = O.decode_attn_shared_latent(sh, q, BKs, BVs, 0.3)
+    np.testing.assert_allclose(b, a, rtol=1e-12, atol=1e-13)
+
+
+def test_shared_latent_with_identity_factors_is_plain_attention():
+    """R = d and B_Kh = B_Vh = I: the latents ARE the keys and values of every head; torch's attention on them."""
+    import torch
+    rng = np.random.default_rng(9)
+    B, H, d, n = 1, 3, 8, 21
+    c = O.LatentCache(B, 1, 32, d, "f32")
+    c.k[:] = rng.standard_normal(c.k.shape).astype(np.float32); c.v[:] = rng.standard_normal(c.v.shape).astype(np.float32)
+    c.seq_lens[:] = n
+    q = rng.standard_normal((B, H, d))
+    eye = np.broadcast_to(np.eye(d), (H, d, d)).copy()
+    got = O.decode_attn_shared_latent(c, q, eye, eye, d ** -0.5)
+    K = torch.from_numpy(c.k[0, 0, :n].astype(np.float64)); V = torch.from_numpy(c.v[0, 0, :n].astype(np.float64))
+    want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q[0])[:, None, :], K[None].expand(H, n, d),
+                                                            V[None].expand(H, n, d))[:, 0].numpy()
+    np.testing.assert_allclose(got[0], want, rtol=1e-10, atol=1e-12)
+
+
+def test_shared_latent_int8_cache_reads_the_quantised_rows():
+    """With an int8 cache the scheme attends over the dequantised codes (one scale per token for the whole rank-R row)."""
+    rng = np.random.default_rng(10)
+    B, H, R, d, n = 1, 2, 64, 16, 9
+    c = O.LatentCache(B, 1, 64, R, "i8")
+    lat = rng.standard_normal((1, n, R))
+    c.store_rows("k", 0, 0, lat); c.store_rows("v", 0, 0, lat * 0.5); c.seq_lens[:] = n
+    assert c.k_scale.shape == (1, 1, 64)
+    BK = rng.standard_normal((H, R, d)); BV = rng.standard_normal((H, R, d)); q = rng.standard_normal((B, H, d))
+    f = O.LatentCache(B, 1, 64, R, "f32")
+    f.k[0, 0, :n] = (c.k[0, 0, :n].astype(np.float64) * c.k_scale[0, 0, :n].astype(np.float64)[:, None]).astype(np.float32)
+    f.v[0, 0, :n] = (c.v[0, 0, :n].astype(np.float64) * c.v_scale[0, 0, :n].astype(np.float64)[:, None]).astype(np.float32)
+    f.seq_lens[:] = n
+    np.testing.assert_allclose(O.decode_attn_shared_latent(c, q, BK, BV, 0.2), O.decode_attn_shared_latent(f, q, BK, BV, 0.2),
+                               rtol=1e-6, atol=1e-7)
+    part = O.decode_attn_shared_latent(c, q, BK, BV, 0.2, heads=[(0, 1)])
+    assert np.isnan(part[0, 0]).all() and np.array_equal(part[0, 1], O.decode_attn_shared_latent(c, q, BK, BV, 0.2)[0, 1])
+
+
+def test_shared_latent_generators_are_seeded_and_shaped():
+    import wsvd_inputs as WI
+    sp = WI.spec("c3_small")
+    BK, BV = WI.shared_up_factors(sp, 256)
+    assert BK.shape == (sp.n_q_heads, 256, sp.d_head) and np.array_equal(BK, WI.shared_up_factors(sp, 256)[0])
+    assert np.array_equal(BK, WI.bf16_exact(BK)) and not np.array_equal(BK, BV)
+    a = WI.shared_latents(sp, 256, "k", 1, 10); b = WI.shared_latents(sp, 256, "v", 1, 10)
+    assert a.shape == (10, 256) and a.dtype == np.float32 and not np.array_equal(a, b)
+    assert np.array_equal(a, WI.shared_latents(sp, 256, "k", 1, 10))

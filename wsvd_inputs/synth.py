@@ -5,10 +5,10 @@ import numpy as np
 
 __all__ = ["Spec", "SPECS", "spec", "rng", "normal", "bf16_exact", "outlier_sigma", "factors",
            "hidden_states", "latents_from_law", "ragged_lengths", "dense_wq", "int4_weight", "lowrank_q_factors",
-           "norm_gains"]
+           "norm_gains", "shared_up_factors", "shared_latents"]
 
 # stream ids (second Philox key word)
-_S_AK, _S_AV, _S_BK, _S_BV, _S_WQ, _S_X, _S_XNEW, _S_LAT, _S_LEN, _S_OUT, _S_W4, _S_WO, _S_AQ, _S_BQ, _S_GAIN = range(1, 16)
+_S_AK, _S_AV, _S_BK, _S_BV, _S_WQ, _S_X, _S_XNEW, _S_LAT, _S_LEN, _S_OUT, _S_W4, _S_WO, _S_AQ, _S_BQ, _S_GAIN, _S_SBK, _S_SBV, _S_SLAT = range(1, 19)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -156,3 +156,26 @@ def lowrank_q_factors(sp: Spec, rq: int, layer: int = 0):
 def norm_gains(sp: Spec, which: int, layer: int = 0) -> np.ndarray:
     """RMSNorm gain [E] = 1 + 0.1 N(0,1), fp32."""
     return (1.0 + normal(sp.seed, _S_GAIN, (sp.d_model,), 0.1, sub=layer * 4 + which)).astype(np.float32)
+
+
+def shared_up_factors(sp: Spec, R: int, layer: int = 0):
+    """Up-projection factors of the whole-matrix scheme: every head has its own B_Kh, B_Vh [R, d] over ONE shared latent
+    of rank R.  B_K, B_V [Hq, R, d] ~ N(0, 1/R), bf16-exact fp32."""
+    H, d = sp.n_q_heads, sp.d_head
+    BK = bf16_exact(normal(sp.seed, _S_SBK, (H, R, d), R ** -0.5, layer))
+    BV = bf16_exact(normal(sp.seed, _S_SBV, (H, R, d), R ** -0.5, layer))
+    return BK, BV
+
+
+def shared_latents(sp: Spec, R: int, which: str, b: int, n_rows: int, layer: int = 0) -> np.ndarray:
+    """Rows of the shared latent of one sequence, fp32 [n_rows, R]: unit-variance Gaussians with the per-channel spread
+    of the outlier profile (a few channels much wider than the rest) and the image-token prefix scaled like the
+    per-head recipe's."""
+    g = rng(sp.seed, _S_SLAT, (layer * 2 + (0 if which == "k" else 1)) * 4096 + b)
+    c = g.standard_normal((n_rows, R), dtype=np.float32)
+    prof = outlier_sigma(sp)
+    c *= np.resize(prof, R).astype(np.float32)[None, :]
+    n_img = min(n_rows, int(getattr(sp, "image_tokens", 0)))
+    if n_img:
+        c[:n_img] *= np.float32(getattr(sp, "image_sigma", 1.0))
+    return c
