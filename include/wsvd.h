@@ -262,6 +262,32 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const 
                               void *hip_stream);
 
 /*
+ * Decode attention of the conventional whole-matrix scheme the per-head method is contrasted with (Section 3.1 and panel
+ * (b) of its figure; the "W/o per-head" variant of the latency appendix): ONE latent of rank R per token and plane,
+ * C_K = X A_K, shared by all heads; head h has its own up-projections B_Kh, B_Vh [R, d]:
+ *     K_h = C_K B_Kh,  V_h = C_V B_Vh,  o_h = softmax(sm_scale * q_h K_h^T) V_h       (sm_scale <= 0: 1 / sqrt(d_head)).
+ * The kernels absorb B_Kh into the query and B_Vh into the output, and run all heads as the columns of one product over
+ * the shared latent, which is therefore streamed once per step (not once per head).
+ *   n_heads = 32; d_head 64 or 128; rank 256, 512 or 1024; t_cap a multiple of 128 (WSVD_E_UNSUPPORTED / WSVD_E_SHAPE).
+ *   q [B, H, d] BF16, B_K and B_V [H, R, d] BF16, out [B, H, d] F32 (all DEVICE, 16-byte aligned).
+ *   k_codes, v_codes: int8 latents, one plane of t_cap * R bytes per sequence, in 32-token blocks of 32 * R bytes.  Byte
+ *   of (token t, dim j): K plane  (t / 32) * 32 R + (((j / 32) * 2 + (j % 32) / 16) * 32 + t % 32) * 16 + j % 16,
+ *                        V plane  (t / 32) * 32 R + (((j / 32) * 2 + (t % 32) / 16) * 32 + j % 32) * 16 + t % 16
+ *   (the per-head cache layout with a single head of rank R).  k_scale, v_scale [B, t_cap] fp16: one symmetric scale per
+ *   token and plane (value = code * scale).  seq_lens [B] int32 (DEVICE): rows [0, seq_lens[b]) are attended; a sequence
+ *   with no rows gets zeros; rows beyond may hold anything.
+ *   workspace (DEVICE, 16-byte aligned) of at least wsvd_shared_workspace_bytes(...) bytes, owned by the caller, free for
+ *   reuse when the stream has passed the call (WSVD_E_WORKSPACE when too small).  Three launches on hip_stream; no host
+ *   synchronisation.  Scores run on exact int8 products (the query as three 7-bit limbs); the value product on fp16
+ *   operands (2^-12 relative): outputs agree with the exact result to about 2e-4 relative.
+ */
+wsvd_status wsvd_shared_workspace_bytes(int32_t batch, int32_t n_heads, int32_t d_head, int32_t rank, int32_t t_cap, size_t *bytes);
+wsvd_status wsvd_decode_attn_shared(wsvd_ctx *ctx, int32_t batch, int32_t n_heads, int32_t d_head, int32_t rank, int32_t t_cap,
+                                    float sm_scale, const void *q, const void *B_K, const void *B_V, const void *k_codes,
+                                    const void *v_codes, const void *k_scale, const void *v_scale, const int32_t *seq_lens,
+                                    void *workspace, size_t workspace_bytes, void *out, void *hip_stream);
+
+/*
  * The rest of the decoding pipeline (Section 3.4, decoding-pipeline figure): the query is per-head low-rank too, and
  * the V-path up-projection is fused into the output projection.
  *

@@ -28,7 +28,7 @@ EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_by
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
-           "wsvd_prefill_attn"]
+           "wsvd_prefill_attn", "wsvd_shared_workspace_bytes", "wsvd_decode_attn_shared"]
 
 
 class WsvdError(RuntimeError):
@@ -95,6 +95,9 @@ def lib():
                                           POINTER(Cache), c_void_p]
         L.wsvd_prefill_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_int32, c_void_p, c_void_p, POINTER(Cache),
                                         c_int32, c_void_p, c_void_p]
+        L.wsvd_shared_workspace_bytes.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int32, POINTER(c_size_t)]
+        L.wsvd_decode_attn_shared.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32, c_int32, c_float] + [c_void_p] * 9 + \
+                                             [c_size_t, c_void_p, c_void_p]
         L.wsvd_fold_qk.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
         L.wsvd_fold_vo.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p]
         L.wsvd_decode_attn_latent.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_void_p, POINTER(Cache), c_int32,
@@ -254,6 +257,21 @@ def wsvd_prefill_append(ctx, desc, x, x_scale, n_tokens, seq_index, A_K, A_V, ca
 def wsvd_prefill_attn(ctx, desc, q, n_q, n_after, B_K, B_V, cache, max_seq_len, out, stream=None):
     _ck(lib().wsvd_prefill_attn(ctx, byref(desc), _ptr(q), int(n_q), int(n_after), _ptr(B_K), _ptr(B_V), byref(cache),
                                 int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_prefill_attn")
+
+
+def wsvd_shared_workspace_bytes(batch, n_heads, d_head, rank, t_cap):
+    a = c_size_t()
+    _ck(lib().wsvd_shared_workspace_bytes(int(batch), int(n_heads), int(d_head), int(rank), int(t_cap), byref(a)),
+        "wsvd_shared_workspace_bytes")
+    return a.value
+
+
+def wsvd_decode_attn_shared(ctx, batch, n_heads, d_head, rank, t_cap, sm_scale, q, B_K, B_V, k_codes, v_codes, k_scale, v_scale,
+                            seq_lens, workspace, out, stream=None):
+    _ck(lib().wsvd_decode_attn_shared(ctx, int(batch), int(n_heads), int(d_head), int(rank), int(t_cap), float(sm_scale), _ptr(q),
+                                      _ptr(B_K), _ptr(B_V), _ptr(k_codes), _ptr(v_codes), _ptr(k_scale), _ptr(v_scale),
+                                      _ptr(seq_lens), _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out),
+                                      _stream(stream)), "wsvd_decode_attn_shared")
 
 
 def wsvd_fold_qk(ctx, desc, B_Q, rq, B_K, out, stream=None):

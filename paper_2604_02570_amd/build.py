@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwsvd.so")
 SOURCES = ["wsvd_api.hip", "wsvd_quant.hip", "wsvd_append.hip", "wsvd_attn_generic.hip", "wsvd_attn_mfma.hip",
-           "wsvd_block.hip", "wsvd_layer.hip", "wsvd_prefill.hip", "wsvd_project.hip"]
+           "wsvd_block.hip", "wsvd_layer.hip", "wsvd_prefill.hip", "wsvd_project.hip", "wsvd_shared.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 # per-file additions.  The prompt attention reads every score tile back into the vector ALU, which binds it: its matrix

@@ -255,6 +255,42 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const 
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+namespace {
+wsvd_status check_shared(int32_t batch, int32_t n_heads, int32_t d_head, int32_t rank, int32_t t_cap) {
+  if (batch < 1 || t_cap < 128 || t_cap % 128 != 0) return WSVD_E_SHAPE;
+  if (d_head != 64 && d_head != 128) return WSVD_E_SHAPE;
+  if (n_heads != 32) return WSVD_E_UNSUPPORTED;                    // the heads are the 32 columns of the matrix products
+  if (rank != 256 && rank != 512 && rank != 1024) return WSVD_E_UNSUPPORTED;
+  return WSVD_OK;
+}
+}  // namespace
+
+wsvd_status wsvd_shared_workspace_bytes(int32_t batch, int32_t n_heads, int32_t d_head, int32_t rank, int32_t t_cap, size_t* bytes) {
+  if (!bytes) return WSVD_E_NULL;
+  wsvd_status st = check_shared(batch, n_heads, d_head, rank, t_cap);
+  if (st != WSVD_OK) return st;
+  *bytes = wsvd_shared_ws_bytes(batch, rank, t_cap);
+  return WSVD_OK;
+}
+
+wsvd_status wsvd_decode_attn_shared(wsvd_ctx* ctx, int32_t batch, int32_t n_heads, int32_t d_head, int32_t rank, int32_t t_cap,
+                                    float sm_scale, const void* q, const void* B_K, const void* B_V, const void* k_codes,
+                                    const void* v_codes, const void* k_scale, const void* v_scale, const int32_t* seq_lens,
+                                    void* workspace, size_t workspace_bytes, void* out, void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !k_codes || !v_codes || !k_scale || !v_scale || !seq_lens || !workspace || !out) return WSVD_E_NULL;
+  wsvd_status st = check_shared(batch, n_heads, d_head, rank, t_cap);
+  if (st != WSVD_OK) return st;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_scale) ||
+      !aligned16(v_scale) || !aligned16(workspace) || !aligned16(out) || ((uintptr_t)seq_lens & 3u))
+    return WSVD_E_ALIGN;
+  if (workspace_bytes < wsvd_shared_ws_bytes(batch, rank, t_cap)) return WSVD_E_WORKSPACE;
+  const float sm = sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)d_head);
+  hipError_t e = wsvd_launch_attn_shared(batch, d_head, rank, t_cap, sm, q, B_K, B_V, k_codes, v_codes, k_scale, v_scale, seq_lens,
+                                         workspace, out, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn_rope(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                                   const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len,
                                   float rope_base, void* out, void* hip_stream) {

@@ -54,6 +54,12 @@ hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int
 // holds [batch, n_tok, d_model]); I8 latents, BF16 x and factors; any n_tok
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
                                        const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s);
+// decode attention over one shared rank-R latent (32 heads, rank 256 / 512 / 1024, int8 codes, bf16 q and factors):
+// three launches (query absorption, attention with split partials, merge + output projection)
+size_t wsvd_shared_ws_bytes(int batch, int rank, int t_cap);
+hipError_t wsvd_launch_attn_shared(int batch, int d_head, int rank, int t_cap, float sm_scale, const void* q, const void* B_K,
+                                   const void* B_V, const void* k_codes, const void* v_codes, const void* k_scale,
+                                   const void* v_scale, const int* seq_lens, void* workspace, void* out, hipStream_t s);
 extern int g_wsvd_prefill_tiled, g_wsvd_project_shape;   // option "prefill_tiled": 1 = the tiled kernel also for blocks of up to 8 query slots
 hipError_t wsvd_launch_rmsnorm_quant(const float* x, const float* y_add, const float* gain, float eps, int64_t rows,
                                      int64_t cols, float* x_out, int8_t* codes, void* scale_f16, hipStream_t s);

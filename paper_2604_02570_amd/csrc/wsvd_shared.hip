@@ -1,0 +1,398 @@
+// Decode attention over ONE shared rank-R latent per token with per-head up-projections: the conventional whole-matrix
+// scheme the per-head method is contrasted with (Section 3.1, panel (b) of its figure; the "W/o per-head" variant of the
+// latency appendix).  Built here in the form that suits the matrix cores: with the up-projection absorbed into the query,
+// the 32 heads are the columns of a GEMM over the shared latent,
+//     S [tokens x heads] = C_K [tokens x R] Q~^T [R x heads],     U^T [R x heads] += (diag(s_V) C_V)^T P [tokens x heads],
+// so the latent stream is read ONCE for all heads (not once per head, as a per-head kernel run on the shared latent
+// would), at the price of R-dimensional per-head queries and outputs: Q~_h = B_Kh q_h and o_h = B_Vh^T u_h move
+// 2 * H * R * d factor elements per step where the per-head scheme moves 2 * H * r * d.
+//   k_shared_absorb   Q~ [B, H, R] = (sm_scale log2 e) B_Kh q_h              bf16 MFMA, one wave per (head, 32 latent dims)
+//   k_shared_attn     per (sequence, split of its 128-token chunks): scores on int8 MFMA (the cache codes are the A
+//                     operand as stored; Q~ as three 7-bit limbs in LDS is the B operand), softmax down the head
+//                     columns, value product on fp16 MFMA with each wave owning a quarter of the R output dims;
+//                     partial (m, l, U) per split
+//   k_shared_out      merge of the splits, u = U / l, o_h = B_Vh^T u_h         vector ALU, one workgroup per (head, 4 sequences)
+// 32x32 accumulator layout throughout: lane L holds column L % 32, rows 8 (v / 4) + 4 (L / 32) + v % 4, v = 0..15.
+#include "wsvd_dev.h"
+#include "wsvd_internal.h"
+
+namespace {
+
+typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
+typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
+typedef _Float16 v4f16 __attribute__((ext_vector_type(4)));
+
+WSVD_DEV v16f mfma_bf16(v8bf16 a, v8bf16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+WSVD_DEV v16f mfma_f16(v8f16 a, v8f16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+
+// 8 int8 codes (two dwords) -> 8 fp16 operand elements, exact: a byte u = code + 128 under the high byte 0x64 reads as
+// the fp16 number 1024 + u
+WSVD_DEV v8f16 codes_f16(int d0, int d1) {
+  const uint32_t x0 = (uint32_t)d0 ^ 0x80808080u, x1 = (uint32_t)d1 ^ 0x80808080u;
+  v4i r;
+  r[0] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04010400u);
+  r[1] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04030402u);
+  r[2] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04010400u);
+  r[3] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04030402u);
+  return __builtin_bit_cast(v8f16, r) - (_Float16)1152;
+}
+
+constexpr int kSharedHeads = 32;          // the heads are the 32 columns of the products
+constexpr int kSharedChunk = 128;         // tokens per workgroup pass: one 32-token block per wave
+constexpr float kLimbRange = 1040000.f;   // |Q~ / delta| stays below 2^20: three signed 7-bit limbs
+
+struct SharedParams {
+  const uint16_t* q;          // bf16 [B, H, d]
+  const uint16_t* BK;         // bf16 [H, R, d]
+  const uint16_t* BV;
+  const uint8_t* k_codes;     // [B][t_cap * R], 32-token blocks
+  const uint8_t* v_codes;
+  const uint16_t* k_scale;    // fp16 [B][t_cap]
+  const uint16_t* v_scale;
+  const int* seq_lens;
+  float* qt;                  // workspace: Q~ [B, H, R]
+  float* pm;                  // workspace: partial running maxima [B, S, H]
+  float* pl;                  //            partial sums           [B, S, H]
+  float* pu;                  //            partial U              [B, S, H, R]
+  float* out;                 // fp32 [B, H, d]
+  int B, d, R, t_cap, S;
+  float c_scale;              // sm_scale * log2(e)
+};
+
+// ---------------------------------------------------------------- Q~ = c B_Kh q_h
+__global__ __launch_bounds__(64) void k_shared_absorb(SharedParams p) {
+  const int lane = threadIdx.x, n = lane & 31, g2 = lane >> 5;
+  const int jb = blockIdx.x, h = blockIdx.y;
+  const uint16_t* arow = p.BK + ((size_t)h * p.R + 32 * jb + n) * p.d + 8 * g2;
+  for (int bb = 0; bb < p.B; bb += 32) {
+    const int b = bb + n;
+    const uint16_t* qrow = p.q + ((size_t)min(b, p.B - 1) * kSharedHeads + h) * p.d + 8 * g2;
+    v16f acc;
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[v] = 0.f;
+    for (int ks = 0; ks < (p.d >> 4); ks++)
+      acc = mfma_bf16(*(const v8bf16*)(arow + 16 * ks), *(const v8bf16*)(qrow + 16 * ks), acc);
+    if (b < p.B) {
+      float* dst = p.qt + ((size_t)b * kSharedHeads + h) * p.R + 32 * jb + 4 * g2;
+#pragma unroll
+      for (int m4 = 0; m4 < 4; m4++) {
+        v4f o;
+#pragma unroll
+        for (int jj = 0; jj < 4; jj++) o[jj] = acc[4 * m4 + jj] * p.c_scale;
+        *(v4f*)(dst + 8 * m4) = o;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- attention over the shared latent, all heads at once
+// LDS: limbs [3][R / 32][64 lanes][16 B], then 4 float tables [4 waves][32], then P tiles [4 waves][32 heads][40] fp16.
+template <int R>
+__global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
+  constexpr int NKS = R / 32;             // 32-dim steps of the score contraction
+  constexpr int NKK = R / 128;            // 32-dim sub-blocks of the value dims one wave owns
+  extern __shared__ __align__(16) uint8_t sh_lds[];
+  v4i* limbs = (v4i*)sh_lds;                                            // [3][NKS][64]
+  float* hmax = (float*)(sh_lds + 3 * NKS * 1024);                      // [4][32] each
+  float* cmax = hmax + 128;
+  float* csum = cmax + 128;
+  float* ksc = csum + 128;
+  _Float16* pt = (_Float16*)(ksc + 128);                                // [4][32][40]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, g2 = lane >> 5;
+  const int split = blockIdx.x, b = blockIdx.y;
+  const int n_b = min(max(p.seq_lens[b], 0), p.t_cap);
+  const int n_chunks = (n_b + kSharedChunk - 1) / kSharedChunk;
+  const int per = (n_chunks + p.S - 1) / p.S;
+  const int c0 = split * per, c1 = min(c0 + per, n_chunks);
+  const size_t part = (size_t)b * p.S + split;
+  if (c0 >= c1) {                                                       // nothing for this split: the merge skips it
+    if (tid < kSharedHeads) { p.pm[part * kSharedHeads + tid] = -INFINITY; p.pl[part * kSharedHeads + tid] = 0.f; }
+    return;
+  }
+
+  // ---- Q~ of head n as three signed 7-bit limbs of round(Q~ / delta_n): lane (n, g2) of step ks holds dims
+  // 32 ks + 16 g2 .. + 15, the B operand of the int8 product as it is
+  const float* qrow = p.qt + ((size_t)b * kSharedHeads + n) * R + 16 * g2;
+  float amax = 0.f;
+  for (int ks = wave; ks < NKS; ks += 4)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; i4++) {
+      const v4f x = *(const v4f*)(qrow + 32 * ks + 4 * i4);
+      amax = fmaxf(amax, fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3]))));
+    }
+  amax = fmaxf(amax, __shfl_xor(amax, 32));
+  if (g2 == 0) hmax[wave * 32 + n] = amax;
+  __syncthreads();
+  const float hm = fmaxf(fmaxf(hmax[n], hmax[32 + n]), fmaxf(hmax[64 + n], hmax[96 + n]));
+  const float delta = hm > 0.f ? hm / kLimbRange : 1.0f;                // value of one unit of the integer query
+  const float inv_delta = 1.0f / delta;
+  for (int ks = wave; ks < NKS; ks += 4) {
+    v4i l0, l1, l2;
+#pragma unroll
+    for (int i4 = 0; i4 < 4; i4++) {
+      const v4f x = *(const v4f*)(qrow + 32 * ks + 4 * i4);
+      uint32_t w0 = 0, w1 = 0, w2 = 0;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const int Q = (int)__builtin_rintf(x[e] * inv_delta);
+        const int a0 = ((Q + 64) & 127) - 64, Q1 = (Q - a0) >> 7;       // Q = a0 + 128 Q1 exactly
+        const int a1 = ((Q1 + 64) & 127) - 64, a2 = (Q1 - a1) >> 7;
+        w0 |= ((uint32_t)a0 & 0xFFu) << (8 * e);
+        w1 |= ((uint32_t)a1 & 0xFFu) << (8 * e);
+        w2 |= ((uint32_t)a2 & 0xFFu) << (8 * e);
+      }
+      l0[i4] = (int)w0; l1[i4] = (int)w1; l2[i4] = (int)w2;
+    }
+    limbs[(0 * NKS + ks) * 64 + lane] = l0;
+    limbs[(1 * NKS + ks) * 64 + lane] = l1;
+    limbs[(2 * NKS + ks) * 64 + lane] = l2;
+  }
+  __syncthreads();
+
+  const uint8_t* kplane = p.k_codes + (size_t)b * p.t_cap * R;
+  const uint8_t* vplane = p.v_codes + (size_t)b * p.t_cap * R;
+  const uint16_t* kmeta = p.k_scale + (size_t)b * p.t_cap;
+  const uint16_t* vmeta = p.v_scale + (size_t)b * p.t_cap;
+
+  float m_run = -INFINITY, l_run = 0.f;                                 // of head n (every wave keeps its own copy)
+  v16f U[NKK];                                                          // rows = this wave's dims, columns = heads
+#pragma unroll
+  for (int kk = 0; kk < NKK; kk++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) U[kk][v] = 0.f;
+
+  for (int c = c0; c < c1; c++) {
+    // ---- scores of this wave's 32 tokens against all heads
+    const int t0 = c * kSharedChunk + 32 * wave;
+    const uint8_t* kp = kplane + (size_t)(t0 >> 5) * (32 * R) + (size_t)lane * 16;
+    if (g2 == 0) ksc[wave * 32 + n] = f16_bits_to_f32(kmeta[t0 + n]);
+    v16i a0, a1, a2;
+#pragma unroll
+    for (int v = 0; v < 16; v++) { a0[v] = 0; a1[v] = 0; a2[v] = 0; }
+    for (int ks0 = 0; ks0 < NKS; ks0 += 4) {
+      v4i ka[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) ka[u] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)(ks0 + u) * 1024));
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        a0 = mfma_i8(ka[u], limbs[(0 * NKS + ks0 + u) * 64 + lane], a0);
+        a1 = mfma_i8(ka[u], limbs[(1 * NKS + ks0 + u) * 64 + lane], a1);
+        a2 = mfma_i8(ka[u], limbs[(2 * NKS + ks0 + u) * 64 + lane], a2);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float sc[16];
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int m4 = 0; m4 < 4; m4++) {
+      const v4f k4 = *(const v4f*)&ksc[wave * 32 + 8 * m4 + 4 * g2];
+#pragma unroll
+      for (int jj = 0; jj < 4; jj++) {
+        const int v = 4 * m4 + jj;
+        const float s = fmaf(16384.f, (float)a2[v], fmaf(128.f, (float)a1[v], (float)a0[v])) * delta * k4[jj];
+        sc[v] = t0 + 8 * m4 + 4 * g2 + jj < n_b ? s : -INFINITY;        // rows past the sequence's end
+        bmax = fmaxf(bmax, sc[v]);
+      }
+    }
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+    if (g2 == 0) cmax[wave * 32 + n] = bmax;
+    __syncthreads();
+    const float m_new = fmaxf(m_run, fmaxf(fmaxf(cmax[n], cmax[32 + n]), fmaxf(cmax[64 + n], cmax[96 + n])));
+    const float alpha = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m_new);   // m_new is finite: the chunk has a row
+    float pw[16], psum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      pw[v] = sc[v] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sc[v] - m_new);
+      psum += pw[v];
+    }
+    psum += __shfl_xor(psum, 32);
+    if (g2 == 0) csum[wave * 32 + n] = psum;
+    _Float16* ptw = pt + (wave * 32 + n) * 40;
+#pragma unroll
+    for (int m4 = 0; m4 < 4; m4++) {
+      v4f p4;
+#pragma unroll
+      for (int jj = 0; jj < 4; jj++) p4[jj] = pw[4 * m4 + jj];
+      *(v2i*)&ptw[8 * m4 + 4 * g2] = __builtin_bit_cast(v2i, __builtin_convertvector(p4, v4f16));
+    }
+    __syncthreads();
+    l_run = fmaf(l_run, alpha, (csum[n] + csum[32 + n]) + (csum[64 + n] + csum[96 + n]));
+    m_run = m_new;
+
+    // ---- value product: this wave's quarter of the R dims, all four token blocks of the chunk
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int kk = 0; kk < NKK; kk++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) U[kk][v] *= alpha;
+    }
+    for (int tw = 0; tw < 4; tw++) {
+      const int tv = c * kSharedChunk + 32 * tw;
+      if (tv >= n_b) break;
+      const uint8_t* vp = vplane + (size_t)(tv >> 5) * (32 * R) + (size_t)(wave * NKK) * 1024 + (size_t)lane * 16;
+      v4i vc[NKK];
+#pragma unroll
+      for (int kk = 0; kk < NKK; kk++) vc[kk] = __builtin_nontemporal_load((const v4i*)(vp + kk * 1024));
+      v8f16 sv8[2] = {__builtin_bit_cast(v8f16, *(const v4i*)(vmeta + tv + 16 * g2)),
+                      __builtin_bit_cast(v8f16, *(const v4i*)(vmeta + tv + 16 * g2 + 8))};
+      if (tv + 32 > n_b) {      // rows never written may hold any scale: they contribute 0
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+          for (int e = 0; e < 8; e++)
+            if (tv + 16 * g2 + 8 * s + e >= n_b) sv8[s][e] = (_Float16)0;
+      }
+      const v8f16 bp0 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2];
+      const v8f16 bp1 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2 + 8];
+#pragma unroll
+      for (int kk = 0; kk < NKK; kk++) {
+        U[kk] = mfma_f16(codes_f16(vc[kk][0], vc[kk][1]) * sv8[0], bp0, U[kk]);
+        U[kk] = mfma_f16(codes_f16(vc[kk][2], vc[kk][3]) * sv8[1], bp1, U[kk]);
+      }
+    }
+    __syncthreads();                                                    // the tables and P tiles are reused by the next chunk
+  }
+
+  // ---- partial result of this split
+  if (wave == 0 && g2 == 0) { p.pm[part * kSharedHeads + n] = m_run; p.pl[part * kSharedHeads + n] = l_run; }
+  float* pu = p.pu + (part * kSharedHeads + n) * R + (size_t)(wave * NKK) * 32 + 4 * g2;
+#pragma unroll
+  for (int kk = 0; kk < NKK; kk++)
+#pragma unroll
+    for (int m4 = 0; m4 < 4; m4++) {
+      v4f o;
+#pragma unroll
+      for (int jj = 0; jj < 4; jj++) o[jj] = U[kk][4 * m4 + jj];
+      *(v4f*)(pu + 32 * kk + 8 * m4) = o;
+    }
+}
+
+// ---------------------------------------------------------------- merge of the splits and o_h = B_Vh^T u_h
+// One workgroup per (head, 4 sequences).  Thread (cp, jq): output channels 2 cp, 2 cp + 1 over the quarter jq of the R dims.
+constexpr int kOutSeqs = 4;
+__global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
+  extern __shared__ __align__(16) uint8_t so_lds[];
+  float* wn = (float*)so_lds;                                           // [4][32 splits]: weight of a split / total sum
+  float* uT = wn + kOutSeqs * 32;                                       // [R][4]
+  float* red = uT + (size_t)p.R * kOutSeqs;                             // [4 quarters][4 seqs][128 channels]
+  const int tid = threadIdx.x, h = blockIdx.x, b0 = blockIdx.y * kOutSeqs;
+  if (tid < kOutSeqs) {
+    const int b = b0 + tid;
+    float M = -INFINITY, L = 0.f;
+    if (b < p.B) {
+      for (int s = 0; s < p.S; s++) M = fmaxf(M, p.pm[((size_t)b * p.S + s) * kSharedHeads + h]);
+      for (int s = 0; s < p.S; s++) {
+        const float m = p.pm[((size_t)b * p.S + s) * kSharedHeads + h];
+        const float w = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
+        wn[tid * 32 + s] = w;
+        L += w * p.pl[((size_t)b * p.S + s) * kSharedHeads + h];
+      }
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    for (int s = 0; s < 32; s++) wn[tid * 32 + s] = (b < p.B && s < p.S) ? wn[tid * 32 + s] * inv : 0.f;
+  }
+  __syncthreads();
+  for (int j = tid; j < p.R; j += 256)
+#pragma unroll
+    for (int bi = 0; bi < kOutSeqs; bi++) {
+      float u = 0.f;
+      if (b0 + bi < p.B)
+        for (int s = 0; s < p.S; s++) {
+          const float w = wn[bi * 32 + s];
+          if (w != 0.f) u = fmaf(w, p.pu[(((size_t)(b0 + bi) * p.S + s) * kSharedHeads + h) * p.R + j], u);
+        }
+      uT[j * kOutSeqs + bi] = u;
+    }
+  __syncthreads();
+  const int cp = tid & 63, jq = tid >> 6;
+  float acc[kOutSeqs][2];
+#pragma unroll
+  for (int bi = 0; bi < kOutSeqs; bi++) acc[bi][0] = acc[bi][1] = 0.f;
+  if (2 * cp < p.d) {
+    const int jn = p.R >> 2;
+    const uint16_t* bv = p.BV + ((size_t)h * p.R + (size_t)jq * jn) * p.d + 2 * cp;
+    for (int j = 0; j < jn; j++) {
+      const uint32_t w = *(const uint32_t*)(bv + (size_t)j * p.d);
+      const float f0 = __uint_as_float(w << 16), f1 = __uint_as_float(w & 0xFFFF0000u);
+      const v4f u4 = *(const v4f*)&uT[(jq * jn + j) * kOutSeqs];
+#pragma unroll
+      for (int bi = 0; bi < kOutSeqs; bi++) { acc[bi][0] = fmaf(u4[bi], f0, acc[bi][0]); acc[bi][1] = fmaf(u4[bi], f1, acc[bi][1]); }
+    }
+#pragma unroll
+    for (int bi = 0; bi < kOutSeqs; bi++) {
+      red[(jq * kOutSeqs + bi) * 128 + 2 * cp] = acc[bi][0];
+      red[(jq * kOutSeqs + bi) * 128 + 2 * cp + 1] = acc[bi][1];
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < kOutSeqs * p.d; i += 256) {
+    const int bi = i / p.d, c = i % p.d;
+    if (b0 + bi < p.B)
+      p.out[((size_t)(b0 + bi) * kSharedHeads + h) * p.d + c] =
+          (red[(0 * kOutSeqs + bi) * 128 + c] + red[(1 * kOutSeqs + bi) * 128 + c]) +
+          (red[(2 * kOutSeqs + bi) * 128 + c] + red[(3 * kOutSeqs + bi) * 128 + c]);
+  }
+}
+
+int shared_splits(int batch, int t_cap) {
+  int s = (256 + batch - 1) / batch;
+  const int chunks = t_cap / kSharedChunk;
+  if (s > chunks) s = chunks;
+  if (s > 32) s = 32;
+  return s < 1 ? 1 : s;
+}
+
+}  // namespace
+
+size_t wsvd_shared_ws_bytes(int batch, int rank, int t_cap) {
+  const size_t S = (size_t)shared_splits(batch, t_cap);
+  const size_t floats = (size_t)batch * kSharedHeads * rank + 2 * (size_t)batch * S * kSharedHeads + (size_t)batch * S * kSharedHeads * rank;
+  return floats * sizeof(float);
+}
+
+hipError_t wsvd_launch_attn_shared(int batch, int d_head, int rank, int t_cap, float sm_scale, const void* q, const void* B_K,
+                                   const void* B_V, const void* k_codes, const void* v_codes, const void* k_scale,
+                                   const void* v_scale, const int* seq_lens, void* workspace, void* out, hipStream_t s) {
+  SharedParams p;
+  p.q = (const uint16_t*)q; p.BK = (const uint16_t*)B_K; p.BV = (const uint16_t*)B_V;
+  p.k_codes = (const uint8_t*)k_codes; p.v_codes = (const uint8_t*)v_codes;
+  p.k_scale = (const uint16_t*)k_scale; p.v_scale = (const uint16_t*)v_scale;
+  p.seq_lens = seq_lens;
+  p.B = batch; p.d = d_head; p.R = rank; p.t_cap = t_cap; p.S = shared_splits(batch, t_cap);
+  p.c_scale = sm_scale * 1.4426950408889634f;
+  p.qt = (float*)workspace;
+  p.pm = p.qt + (size_t)batch * kSharedHeads * rank;
+  p.pl = p.pm + (size_t)batch * p.S * kSharedHeads;
+  p.pu = p.pl + (size_t)batch * p.S * kSharedHeads;
+  p.out = (float*)out;
+
+  hipLaunchKernelGGL(k_shared_absorb, dim3((unsigned)(rank / 32), kSharedHeads), dim3(64), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  const size_t lds_attn = (size_t)3 * (rank / 32) * 1024 + 4 * 128 * sizeof(float) + 4 * 32 * 40 * sizeof(_Float16);
+  const void* fn = rank == 256 ? (const void*)k_shared_attn<256> : rank == 512 ? (const void*)k_shared_attn<512>
+                                                                                 : (const void*)k_shared_attn<1024>;
+  static bool raised[3] = {false, false, false};                        // the kernels' limit of dynamic LDS, raised once
+  const int ri = rank == 256 ? 0 : rank == 512 ? 1 : 2;
+  if (!raised[ri]) {
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_attn);
+    if (e != hipSuccess) return e;
+    raised[ri] = true;
+  }
+  dim3 grid((unsigned)p.S, (unsigned)batch);
+  if (rank == 256) hipLaunchKernelGGL((k_shared_attn<256>), grid, dim3(256), lds_attn, s, p);
+  else if (rank == 512) hipLaunchKernelGGL((k_shared_attn<512>), grid, dim3(256), lds_attn, s, p);
+  else if (rank == 1024) hipLaunchKernelGGL((k_shared_attn<1024>), grid, dim3(256), lds_attn, s, p);
+  else return hipErrorNotSupported;
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  const size_t lds_out = (size_t)(kOutSeqs * 32 + rank * kOutSeqs + 4 * kOutSeqs * 128) * sizeof(float);
+  hipLaunchKernelGGL(k_shared_out, dim3(kSharedHeads, (unsigned)((batch + kOutSeqs - 1) / kOutSeqs)), dim3(256), lds_out, s, p);
+  return hipGetLastError();
+}
