@@ -45,12 +45,13 @@ def parse():
     ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
-    ap.add_argument("--workload", choices=["c3", "c4", "c5", "layer", "prefill"], default="c3",
+    ap.add_argument("--workload", choices=["c3", "c4", "c5", "layer", "prefill", "shared"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
                          "c5: the 28-layer grouped-query W4A8 attention block; "
                          "layer: 32 quantised decoder layers of the decoding pipeline at the c3 shape (low-rank Q, B_V folded "
                          "into W_O, SwiGLU FFN); prefill: building the c3 cache from hidden states, 64 tokens per launch "
+                         "shared: the contrast scheme, decode attention over one shared rank-1024 latent per token "
                          "(secondary lines, same JSON shape)")
     ap.add_argument("--linear-direct", action="store_true",
                     help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
@@ -86,6 +87,8 @@ def main():
         return run_layer(args, np, torch, W, WI)
     if args.workload == "prefill":
         return run_prefill(args, np, torch, W, WI)
+    if args.workload == "shared":
+        return run_shared(args, np, torch, W, WI)
 
     sp = WI.spec(args.workload)
     i4 = sp.latent_dtype == "i4"
@@ -781,6 +784,78 @@ def run_prefill(args, np, torch, W, WI):
                                 "note": "avg_launch_us includes the length update kernel and the reset of the lengths between steps",
                                 "hbm_view": {"algorithmic_bytes_per_launch": int(proj_bytes),
                                              "achieved": round(proj_bytes / (ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s"}},
+    }
+    print(json.dumps(res))
+    W.wsvd_destroy(ctx)
+
+
+def run_shared(args, np, torch, W, WI):
+    """The contrast of the per-head scheme: decode attention over ONE shared latent of rank R = 32 heads x 32 per token
+    (the same cache bytes as the batched int8 workload: 16 sequences x 2048 tokens, int8 codes + one fp16 scale per token
+    and plane), every head with its own up-projections B_Kh, B_Vh [R, d].  A step = wsvd_decode_attn_shared (query
+    absorption, attention, merge + output projection); 8 cache sets (0.54 GB) are rotated so that the latents come from
+    HBM; replayed from a HIP graph."""
+    B, H, d, R, T = 16, 32, 128, 1024, 2048
+    steps = args.steps if args.steps != 320 else 160
+    warmup = args.warmup if args.warmup != 32 else 16
+    n_sets = 8
+    g = torch.Generator(device="cuda"); g.manual_seed(1234)
+    ctx = W.wsvd_create(0)
+    ws = torch.empty(W.wsvd_shared_workspace_bytes(B, H, d, R, T), dtype=torch.uint8, device="cuda")
+    sets = []
+    for _ in range(n_sets):
+        kc = torch.randint(0, 256, (B, T * R), dtype=torch.uint8, device="cuda", generator=g)
+        vc = torch.randint(0, 256, (B, T * R), dtype=torch.uint8, device="cuda", generator=g)
+        ks = (0.01 + 0.01 * torch.rand((B, T), device="cuda", generator=g)).to(torch.float16)
+        vs = (0.01 + 0.01 * torch.rand((B, T), device="cuda", generator=g)).to(torch.float16)
+        sets.append((kc, vc, ks, vs))
+    sl = torch.full((B,), T, dtype=torch.int32, device="cuda")
+    q = torch.randn((B, H, d), device="cuda", generator=g).to(torch.bfloat16)
+    BK = (torch.randn((H, R, d), device="cuda", generator=g) * R ** -0.5).to(torch.bfloat16)
+    BV = (torch.randn((H, R, d), device="cuda", generator=g) * R ** -0.5).to(torch.bfloat16)
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        kc, vc, ks, vs = sets[i % n_sets]
+        W.wsvd_decode_attn_shared(ctx, B, H, d, R, T, 0.0, q, BK, BV, kc, vc, ks, vs, sl, ws, out)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for i in range(warmup):
+            step(i)
+        stream.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=stream):
+            for i in range(n_sets):
+                step(i)
+        gr.replay(); stream.synchronize()
+        reps = max(1, steps // n_sets)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            gr.replay()
+        e1.record(stream); stream.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * n_sets)
+        assert W.wsvd_check(ctx, stream) == 0 and bool(torch.isfinite(out).all())
+    cache_bytes = 2 * B * T * (R + 2)
+    factor_bytes = 2 * H * R * d * 2
+    ws_floats = W.wsvd_shared_workspace_bytes(B, H, d, R, T) // 4
+    res = {
+        "metric": "decode_attn_latent_bandwidth", "value": round(cache_bytes / (us * 1e-6) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": reps * n_sets, "warmup": warmup, "ms_per_step": round(us * 1e-3, 5), "us_per_decode_step": round(us, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": "shared-latent contrast: decode attention over one rank-1024 int8 latent per token shared by 32 heads "
+                               "(B=16, T=2048, d_head=128), per-head up-projections [1024, 128]; same cache bytes as the per-head "
+                               "int8 workload (32 heads x rank 32)",
+                   "batch": B, "context": T, "heads": H, "rank": R, "cache_sets": n_sets, "launch": "hip_graph",
+                   "launches_per_step": 3},
+        # the step's three launches are timed together here; the kernel-trace summary under profiles/ splits them
+        "roofline": {"kernel": "wsvd_decode_attn_shared (k_shared_absorb + k_shared_attn + k_shared_out)", "bound": "hbm",
+                     "achieved": round(cache_bytes / (us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(cache_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(cache_bytes),
+                     "other_bytes_per_step": {"up_projection_factors": int(factor_bytes), "split_partials_written_and_read": int(2 * 4 * (ws_floats - B * H * R))},
+                     "int8_score_GOP_issued": round(3 * 2.0 * B * T * R * H / 1e9, 2), "fp16_value_GFLOP": round(2.0 * B * T * R * H / 1e9, 2)},
     }
     print(json.dumps(res))
     W.wsvd_destroy(ctx)

@@ -11,7 +11,7 @@
 //                     operand as stored; Q~ as three 7-bit limbs in LDS is the B operand), softmax down the head
 //                     columns, value product on fp16 MFMA with each wave owning a quarter of the R output dims;
 //                     partial (m, l, U) per split
-//   k_shared_out      merge of the splits, u = U / l, o_h = B_Vh^T u_h         vector ALU, one workgroup per (head, 4 sequences)
+//   k_shared_out      merge of the splits, u = U / l, o_h = B_Vh^T u_h         vector ALU, one workgroup per (head, sequence)
 // 32x32 accumulator layout throughout: lane L holds column L % 32, rows 8 (v / 4) + 4 (L / 32) + v % 4, v = 0..15.
 #include "wsvd_dev.h"
 #include "wsvd_internal.h"
@@ -115,28 +115,34 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
   // ---- Q~ of head n as three signed 7-bit limbs of round(Q~ / delta_n): lane (n, g2) of step ks holds dims
   // 32 ks + 16 g2 .. + 15, the B operand of the int8 product as it is
   const float* qrow = p.qt + ((size_t)b * kSharedHeads + n) * R + 16 * g2;
-  float amax = 0.f;
-  for (int ks = wave; ks < NKS; ks += 4)
+  constexpr int NQ = NKS / 4;                                           // steps this wave converts
+  v4f xq[NQ][4];                                                        // read once, all requests in flight together
 #pragma unroll
-    for (int i4 = 0; i4 < 4; i4++) {
-      const v4f x = *(const v4f*)(qrow + 32 * ks + 4 * i4);
-      amax = fmaxf(amax, fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3]))));
-    }
+  for (int i = 0; i < NQ; i++)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; i4++) xq[i][i4] = *(const v4f*)(qrow + 32 * (wave + 4 * i) + 4 * i4);
+  float amax = 0.f;
+#pragma unroll
+  for (int i = 0; i < NQ; i++)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; i4++)
+      amax = fmaxf(amax, fmaxf(fmaxf(fabsf(xq[i][i4][0]), fabsf(xq[i][i4][1])), fmaxf(fabsf(xq[i][i4][2]), fabsf(xq[i][i4][3]))));
   amax = fmaxf(amax, __shfl_xor(amax, 32));
   if (g2 == 0) hmax[wave * 32 + n] = amax;
   __syncthreads();
   const float hm = fmaxf(fmaxf(hmax[n], hmax[32 + n]), fmaxf(hmax[64 + n], hmax[96 + n]));
   const float delta = hm > 0.f ? hm / kLimbRange : 1.0f;                // value of one unit of the integer query
   const float inv_delta = 1.0f / delta;
-  for (int ks = wave; ks < NKS; ks += 4) {
+#pragma unroll
+  for (int i = 0; i < NQ; i++) {
+    const int ks = wave + 4 * i;
     v4i l0, l1, l2;
 #pragma unroll
     for (int i4 = 0; i4 < 4; i4++) {
-      const v4f x = *(const v4f*)(qrow + 32 * ks + 4 * i4);
       uint32_t w0 = 0, w1 = 0, w2 = 0;
 #pragma unroll
       for (int e = 0; e < 4; e++) {
-        const int Q = (int)__builtin_rintf(x[e] * inv_delta);
+        const int Q = (int)__builtin_rintf(xq[i][i4][e] * inv_delta);
         const int a0 = ((Q + 64) & 127) - 64, Q1 = (Q - a0) >> 7;       // Q = a0 + 128 Q1 exactly
         const int a1 = ((Q1 + 64) & 127) - 64, a2 = (Q1 - a1) >> 7;
         w0 |= ((uint32_t)a0 & 0xFFu) << (8 * e);
@@ -171,15 +177,24 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
     v16i a0, a1, a2;
 #pragma unroll
     for (int v = 0; v < 16; v++) { a0[v] = 0; a1[v] = 0; a2[v] = 0; }
-    for (int ks0 = 0; ks0 < NKS; ks0 += 4) {
-      v4i ka[4];
+    {
+      v4i ka[2][8];                                                     // two batches of 8 steps: one in use, one on its way
 #pragma unroll
-      for (int u = 0; u < 4; u++) ka[u] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)(ks0 + u) * 1024));
+      for (int u = 0; u < 8; u++) ka[0][u] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)u * 1024));
 #pragma unroll
-      for (int u = 0; u < 4; u++) {
-        a0 = mfma_i8(ka[u], limbs[(0 * NKS + ks0 + u) * 64 + lane], a0);
-        a1 = mfma_i8(ka[u], limbs[(1 * NKS + ks0 + u) * 64 + lane], a1);
-        a2 = mfma_i8(ka[u], limbs[(2 * NKS + ks0 + u) * 64 + lane], a2);
+      for (int bt = 0; bt < NKS / 8; bt++) {
+        if (bt + 1 < NKS / 8) {
+#pragma unroll
+          for (int u = 0; u < 8; u++)
+            ka[(bt + 1) & 1][u] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)(8 * (bt + 1) + u) * 1024));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+          const int ks = 8 * bt + u;
+          a0 = mfma_i8(ka[bt & 1][u], limbs[(0 * NKS + ks) * 64 + lane], a0);
+          a1 = mfma_i8(ka[bt & 1][u], limbs[(1 * NKS + ks) * 64 + lane], a1);
+          a2 = mfma_i8(ka[bt & 1][u], limbs[(2 * NKS + ks) * 64 + lane], a2);
+        }
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -230,28 +245,39 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
 #pragma unroll
         for (int v = 0; v < 16; v++) U[kk][v] *= alpha;
     }
-    for (int tw = 0; tw < 4; tw++) {
-      const int tv = c * kSharedChunk + 32 * tw;
-      if (tv >= n_b) break;
-      const uint8_t* vp = vplane + (size_t)(tv >> 5) * (32 * R) + (size_t)(wave * NKK) * 1024 + (size_t)lane * 16;
-      v4i vc[NKK];
+    {
+      const int cbase = c * kSharedChunk;
+      v4i vc[2][NKK];
+      v4i vsr[2][2];
+      auto vload = [&](int set, int tw) {
+        const int tv = cbase + 32 * tw;
+        const uint8_t* vp = vplane + (size_t)(tv >> 5) * (32 * R) + (size_t)(wave * NKK) * 1024 + (size_t)lane * 16;
 #pragma unroll
-      for (int kk = 0; kk < NKK; kk++) vc[kk] = __builtin_nontemporal_load((const v4i*)(vp + kk * 1024));
-      v8f16 sv8[2] = {__builtin_bit_cast(v8f16, *(const v4i*)(vmeta + tv + 16 * g2)),
-                      __builtin_bit_cast(v8f16, *(const v4i*)(vmeta + tv + 16 * g2 + 8))};
-      if (tv + 32 > n_b) {      // rows never written may hold any scale: they contribute 0
+        for (int kk = 0; kk < NKK; kk++) vc[set][kk] = __builtin_nontemporal_load((const v4i*)(vp + kk * 1024));
+        vsr[set][0] = *(const v4i*)(vmeta + tv + 16 * g2);
+        vsr[set][1] = *(const v4i*)(vmeta + tv + 16 * g2 + 8);
+      };
+      vload(0, 0);                                                      // (the chunk's first block always has a row)
 #pragma unroll
-        for (int s = 0; s < 2; s++)
+      for (int tw = 0; tw < 4; tw++) {
+        const int tv = cbase + 32 * tw;
+        if (tv >= n_b) break;
+        if (tw + 1 < 4 && tv + 32 < n_b) vload((tw + 1) & 1, tw + 1);
+        v8f16 sv8[2] = {__builtin_bit_cast(v8f16, vsr[tw & 1][0]), __builtin_bit_cast(v8f16, vsr[tw & 1][1])};
+        if (tv + 32 > n_b) {      // rows never written may hold any scale: they contribute 0
 #pragma unroll
-          for (int e = 0; e < 8; e++)
-            if (tv + 16 * g2 + 8 * s + e >= n_b) sv8[s][e] = (_Float16)0;
-      }
-      const v8f16 bp0 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2];
-      const v8f16 bp1 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2 + 8];
+          for (int s = 0; s < 2; s++)
 #pragma unroll
-      for (int kk = 0; kk < NKK; kk++) {
-        U[kk] = mfma_f16(codes_f16(vc[kk][0], vc[kk][1]) * sv8[0], bp0, U[kk]);
-        U[kk] = mfma_f16(codes_f16(vc[kk][2], vc[kk][3]) * sv8[1], bp1, U[kk]);
+            for (int e = 0; e < 8; e++)
+              if (tv + 16 * g2 + 8 * s + e >= n_b) sv8[s][e] = (_Float16)0;
+        }
+        const v8f16 bp0 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2];
+        const v8f16 bp1 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2 + 8];
+#pragma unroll
+        for (int kk = 0; kk < NKK; kk++) {
+          U[kk] = mfma_f16(codes_f16(vc[tw & 1][kk][0], vc[tw & 1][kk][1]) * sv8[0], bp0, U[kk]);
+          U[kk] = mfma_f16(codes_f16(vc[tw & 1][kk][2], vc[tw & 1][kk][3]) * sv8[1], bp1, U[kk]);
+        }
       }
     }
     __syncthreads();                                                    // the tables and P tiles are reused by the next chunk
@@ -272,12 +298,12 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
 }
 
 // ---------------------------------------------------------------- merge of the splits and o_h = B_Vh^T u_h
-// One workgroup per (head, 4 sequences).  Thread (cp, jq): output channels 2 cp, 2 cp + 1 over the quarter jq of the R dims.
-constexpr int kOutSeqs = 4;
+// One workgroup per (head, kOutSeqs sequences).  Thread (cp, jq): output channels 2 cp, 2 cp + 1 over the quarter jq of the R dims.
+constexpr int kOutSeqs = 1;
 __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
   extern __shared__ __align__(16) uint8_t so_lds[];
   float* wn = (float*)so_lds;                                           // [4][32 splits]: weight of a split / total sum
-  float* uT = wn + kOutSeqs * 32;                                       // [R][4]
+  float* uT = wn + kOutSeqs * 32;                                       // [R][kOutSeqs]
   float* red = uT + (size_t)p.R * kOutSeqs;                             // [4 quarters][4 seqs][128 channels]
   const int tid = threadIdx.x, h = blockIdx.x, b0 = blockIdx.y * kOutSeqs;
   if (tid < kOutSeqs) {
@@ -300,11 +326,19 @@ __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
 #pragma unroll
     for (int bi = 0; bi < kOutSeqs; bi++) {
       float u = 0.f;
-      if (b0 + bi < p.B)
-        for (int s = 0; s < p.S; s++) {
-          const float w = wn[bi * 32 + s];
-          if (w != 0.f) u = fmaf(w, p.pu[(((size_t)(b0 + bi) * p.S + s) * kSharedHeads + h) * p.R + j], u);
+      if (b0 + bi < p.B) {
+        const float* src = p.pu + (((size_t)(b0 + bi) * p.S) * kSharedHeads + h) * p.R + j;
+        for (int s0 = 0; s0 < p.S; s0 += 4) {                           // 4 loads in flight; a split that wrote nothing has
+          float x[4];                                                   // weight 0 and its (unwritten) values are dropped
+#pragma unroll
+          for (int i = 0; i < 4; i++) x[i] = src[(size_t)min(s0 + i, p.S - 1) * kSharedHeads * p.R];
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            const float w = s0 + i < p.S ? wn[bi * 32 + s0 + i] : 0.f;
+            u += w != 0.f ? w * x[i] : 0.f;
+          }
         }
+      }
       uT[j * kOutSeqs + bi] = u;
     }
   __syncthreads();
@@ -315,12 +349,19 @@ __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
   if (2 * cp < p.d) {
     const int jn = p.R >> 2;
     const uint16_t* bv = p.BV + ((size_t)h * p.R + (size_t)jq * jn) * p.d + 2 * cp;
-    for (int j = 0; j < jn; j++) {
-      const uint32_t w = *(const uint32_t*)(bv + (size_t)j * p.d);
-      const float f0 = __uint_as_float(w << 16), f1 = __uint_as_float(w & 0xFFFF0000u);
-      const v4f u4 = *(const v4f*)&uT[(jq * jn + j) * kOutSeqs];
+    for (int j0 = 0; j0 < jn; j0 += 16) {                               // (R / 4 is a multiple of 16) 16 loads in flight
+      uint32_t w[16];
 #pragma unroll
-      for (int bi = 0; bi < kOutSeqs; bi++) { acc[bi][0] = fmaf(u4[bi], f0, acc[bi][0]); acc[bi][1] = fmaf(u4[bi], f1, acc[bi][1]); }
+      for (int i = 0; i < 16; i++) w[i] = *(const uint32_t*)(bv + (size_t)(j0 + i) * p.d);
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        const float f0 = __uint_as_float(w[i] << 16), f1 = __uint_as_float(w[i] & 0xFFFF0000u);
+#pragma unroll
+        for (int bi = 0; bi < kOutSeqs; bi++) {
+          const float u = uT[(jq * jn + j0 + i) * kOutSeqs + bi];
+          acc[bi][0] = fmaf(u, f0, acc[bi][0]); acc[bi][1] = fmaf(u, f1, acc[bi][1]);
+        }
+      }
     }
 #pragma unroll
     for (int bi = 0; bi < kOutSeqs; bi++) {
