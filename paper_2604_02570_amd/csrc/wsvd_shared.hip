@@ -298,28 +298,27 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
 }
 
 // ---------------------------------------------------------------- merge of the splits and o_h = B_Vh^T u_h
-// One workgroup per (head, kOutSeqs sequences).  Thread (cp, jq): output channels 2 cp, 2 cp + 1 over the quarter jq of the R dims.
+// One workgroup per (head, kOutSeqs sequences).
 constexpr int kOutSeqs = 1;
 __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
   extern __shared__ __align__(16) uint8_t so_lds[];
   float* wn = (float*)so_lds;                                           // [4][32 splits]: weight of a split / total sum
   float* uT = wn + kOutSeqs * 32;                                       // [R][kOutSeqs]
-  float* red = uT + (size_t)p.R * kOutSeqs;                             // [4 quarters][4 seqs][128 channels]
+  float* red = uT + (size_t)p.R * kOutSeqs;                             // [16 slices][kOutSeqs][128 channels]
   const int tid = threadIdx.x, h = blockIdx.x, b0 = blockIdx.y * kOutSeqs;
-  if (tid < kOutSeqs) {
-    const int b = b0 + tid;
-    float M = -INFINITY, L = 0.f;
-    if (b < p.B) {
-      for (int s = 0; s < p.S; s++) M = fmaxf(M, p.pm[((size_t)b * p.S + s) * kSharedHeads + h]);
-      for (int s = 0; s < p.S; s++) {
-        const float m = p.pm[((size_t)b * p.S + s) * kSharedHeads + h];
-        const float w = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
-        wn[tid * 32 + s] = w;
-        L += w * p.pl[((size_t)b * p.S + s) * kSharedHeads + h];
-      }
-    }
-    const float inv = L > 0.f ? 1.0f / L : 0.f;
-    for (int s = 0; s < 32; s++) wn[tid * 32 + s] = (b < p.B && s < p.S) ? wn[tid * 32 + s] * inv : 0.f;
+  if ((tid >> 6) < kOutSeqs) {                                          // wave bi: lane s holds split s of sequence b0 + bi
+    const int bi = tid >> 6, sidx = tid & 63, b = b0 + bi;
+    const bool on = b < p.B && sidx < p.S;
+    const float m = on ? p.pm[((size_t)b * p.S + sidx) * kSharedHeads + h] : -INFINITY;
+    const float l = on ? p.pl[((size_t)b * p.S + sidx) * kSharedHeads + h] : 0.f;
+    float M = m;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float w = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
+    float L = w * l;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) L += __shfl_xor(L, o);
+    if (sidx < 32) wn[bi * 32 + sidx] = L > 0.f ? w / L : 0.f;
   }
   __syncthreads();
   for (int j = tid; j < p.R; j += 256)
@@ -342,40 +341,46 @@ __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
       uT[j * kOutSeqs + bi] = u;
     }
   __syncthreads();
-  const int cp = tid & 63, jq = tid >> 6;
-  float acc[kOutSeqs][2];
+  // thread (c8, js): output channels 8 c8 .. + 7 (one 16-byte load per row of B_Vh) over slice js of the R dims
+  const int c8 = tid & 15, js = tid >> 4;
+  float acc[kOutSeqs][8];
 #pragma unroll
-  for (int bi = 0; bi < kOutSeqs; bi++) acc[bi][0] = acc[bi][1] = 0.f;
-  if (2 * cp < p.d) {
-    const int jn = p.R >> 2;
-    const uint16_t* bv = p.BV + ((size_t)h * p.R + (size_t)jq * jn) * p.d + 2 * cp;
-    for (int j0 = 0; j0 < jn; j0 += 16) {                               // (R / 4 is a multiple of 16) 16 loads in flight
-      uint32_t w[16];
+  for (int bi = 0; bi < kOutSeqs; bi++)
 #pragma unroll
-      for (int i = 0; i < 16; i++) w[i] = *(const uint32_t*)(bv + (size_t)(j0 + i) * p.d);
+    for (int e = 0; e < 8; e++) acc[bi][e] = 0.f;
+  if (8 * c8 < p.d) {
+    const int jn = p.R >> 4;                                            // rows per slice: a multiple of 16
+    const uint16_t* bv = p.BV + ((size_t)h * p.R + (size_t)js * jn) * p.d + 8 * c8;
+    for (int j0 = 0; j0 < jn; j0 += 8) {                                // 8 loads in flight
+      v4i w[8];
 #pragma unroll
-      for (int i = 0; i < 16; i++) {
-        const float f0 = __uint_as_float(w[i] << 16), f1 = __uint_as_float(w[i] & 0xFFFF0000u);
+      for (int i = 0; i < 8; i++) w[i] = *(const v4i*)(bv + (size_t)(j0 + i) * p.d);
+#pragma unroll
+      for (int i = 0; i < 8; i++)
 #pragma unroll
         for (int bi = 0; bi < kOutSeqs; bi++) {
-          const float u = uT[(jq * jn + j0 + i) * kOutSeqs + bi];
-          acc[bi][0] = fmaf(u, f0, acc[bi][0]); acc[bi][1] = fmaf(u, f1, acc[bi][1]);
+          const float u = uT[(js * jn + j0 + i) * kOutSeqs + bi];
+#pragma unroll
+          for (int e2 = 0; e2 < 4; e2++) {
+            acc[bi][2 * e2] = fmaf(u, __uint_as_float((uint32_t)w[i][e2] << 16), acc[bi][2 * e2]);
+            acc[bi][2 * e2 + 1] = fmaf(u, __uint_as_float((uint32_t)w[i][e2] & 0xFFFF0000u), acc[bi][2 * e2 + 1]);
+          }
         }
-      }
     }
 #pragma unroll
-    for (int bi = 0; bi < kOutSeqs; bi++) {
-      red[(jq * kOutSeqs + bi) * 128 + 2 * cp] = acc[bi][0];
-      red[(jq * kOutSeqs + bi) * 128 + 2 * cp + 1] = acc[bi][1];
-    }
+    for (int bi = 0; bi < kOutSeqs; bi++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) red[(js * kOutSeqs + bi) * 128 + 8 * c8 + e] = acc[bi][e];
   }
   __syncthreads();
   for (int i = tid; i < kOutSeqs * p.d; i += 256) {
     const int bi = i / p.d, c = i % p.d;
-    if (b0 + bi < p.B)
-      p.out[((size_t)(b0 + bi) * kSharedHeads + h) * p.d + c] =
-          (red[(0 * kOutSeqs + bi) * 128 + c] + red[(1 * kOutSeqs + bi) * 128 + c]) +
-          (red[(2 * kOutSeqs + bi) * 128 + c] + red[(3 * kOutSeqs + bi) * 128 + c]);
+    if (b0 + bi < p.B) {
+      float o = 0.f;
+#pragma unroll
+      for (int q = 0; q < 16; q++) o += red[(q * kOutSeqs + bi) * 128 + c];
+      p.out[((size_t)(b0 + bi) * kSharedHeads + h) * p.d + c] = o;
+    }
   }
 }
 
@@ -433,7 +438,7 @@ hipError_t wsvd_launch_attn_shared(int batch, int d_head, int rank, int t_cap, f
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
-  const size_t lds_out = (size_t)(kOutSeqs * 32 + rank * kOutSeqs + 4 * kOutSeqs * 128) * sizeof(float);
+  const size_t lds_out = (size_t)(kOutSeqs * 32 + rank * kOutSeqs + 16 * kOutSeqs * 128) * sizeof(float);
   hipLaunchKernelGGL(k_shared_out, dim3(kSharedHeads, (unsigned)((batch + kOutSeqs - 1) / kOutSeqs)), dim3(256), lds_out, s, p);
   return hipGetLastError();
 }
