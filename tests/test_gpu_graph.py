@@ -143,3 +143,87 @@ def test_rotary_attention_graph_replays_equal_eager():
         assert np.array_equal(L.out.cpu().numpy(), ref), f"rotary replay {i}"
     assert W.wsvd_check(L.ctx) == 0
     L.close()
+
+
+def test_prefill_graph_replays_equal_eager():
+    """The two prompt-sized launches (tiled projection of all sequences, tiled causal attention) captured once; every
+    replay starts from the same lengths (a fill kernel inside the graph resets them) and must reproduce the eager
+    cache and outputs bit for bit."""
+    c = build_case("c3_small", extra_cap=256)
+    sp = c.sp
+    G = sp.n_q_heads // sp.n_kv_heads
+    L = layer_for(c); L.upload(c.cache)
+    n = 150
+    X = np.stack([WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=60 + b)) for b in range(sp.batch)])
+    xd = as_dtype_dev(X.reshape(sp.batch * n, -1), "bf16")
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    rng = np.random.default_rng(21)
+    q = as_dtype_dev(WI.bf16_exact(rng.standard_normal((sp.batch, sp.n_kv_heads, n, G, sp.d_head)).astype(np.float32)), "bf16")
+    out = torch.empty((sp.batch, sp.n_kv_heads, n, G, sp.d_head), dtype=torch.float32, device="cuda")
+    d = type(L.desc).from_buffer_copy(L.desc); d.q_dtype = W.DTYPES["bf16"]
+    lens0 = L.seq_lens.clone()
+    torch.cuda.synchronize()
+    snap = _snapshot(L)
+
+    def step():
+        L.seq_lens.copy_(lens0)                   # a copy kernel, not a memset node
+        W.wsvd_prefill_append(L.ctx, L.desc, xd, None, n, -1, AKd, AVd, L.cache)
+        W.wsvd_prefill_attn(L.ctx, d, q, n, 0, BKd, BVd, L.cache, int(c.cache.seq_lens.max()) + n, out)
+
+    step(); torch.cuda.synchronize()
+    assert W.wsvd_check(L.ctx) == 0
+    ref_out = out.cpu().numpy().copy()
+    ref = _snapshot(L)
+    assert (ref[4].cpu().numpy() == lens0.cpu().numpy() + n).all()
+    _restore(L, snap)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step(); stream.synchronize()
+    _restore(L, snap)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(g, stream=stream):
+            step()
+    for i in range(3):
+        _restore(L, snap)                         # the cache as it was before the prompt
+        out.fill_(float("nan")); torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref_out), f"prefill replay {i}: attention output differs"
+        for t, r in zip((L.k_codes, L.v_codes, L.k_meta, L.v_meta, L.seq_lens), ref):
+            assert torch.equal(t, r), f"prefill replay {i}: cache differs"
+        _ = torch.randn(2048, device="cuda").sum().item()
+    assert W.wsvd_check(L.ctx) == 0
+    L.close()
+
+
+def test_shared_latent_graph_replays_equal_eager():
+    from test_gpu_shared import SharedCase, H
+    c = SharedCase(3, 512, 128, [700, 130, 0], 768)
+    ctx = W.wsvd_create(0)
+    kc, vc, ks, vs, sl = c.device()
+    ws = torch.empty(W.wsvd_shared_workspace_bytes(c.B, H, c.d, c.R, c.t_cap), dtype=torch.uint8, device="cuda")
+    out = torch.empty((c.B, H, c.d), dtype=torch.float32, device="cuda")
+    q, BK, BV = as_dtype_dev(c.q, "bf16"), as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+
+    def step():
+        W.wsvd_decode_attn_shared(ctx, c.B, H, c.d, c.R, c.t_cap, c.sm, q, BK, BV, kc, vc, ks, vs, sl, ws, out)
+
+    step(); torch.cuda.synchronize()
+    ref = out.cpu().numpy().copy()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        step(); stream.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(g, stream=stream):
+            step()
+    for i in range(3):
+        out.fill_(float("nan")); ws.fill_(0xFF); torch.cuda.synchronize()      # stale workspace contents must not matter
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), ref), f"shared-latent replay {i}"
+        _ = torch.randn(2048, device="cuda").sum().item()
+    assert W.wsvd_check(ctx) == 0
+    W.wsvd_destroy(ctx)
