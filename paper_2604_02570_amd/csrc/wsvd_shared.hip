@@ -112,6 +112,11 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
     return;
   }
 
+  const uint8_t* kplane = p.k_codes + (size_t)b * p.t_cap * R;
+  const uint8_t* vplane = p.v_codes + (size_t)b * p.t_cap * R;
+  const uint16_t* kmeta = p.k_scale + (size_t)b * p.t_cap;
+  const uint16_t* vmeta = p.v_scale + (size_t)b * p.t_cap;
+
   // ---- Q~ of head n as three signed 7-bit limbs of round(Q~ / delta_n): lane (n, g2) of step ks holds dims
   // 32 ks + 16 g2 .. + 15, the B operand of the int8 product as it is
   const float* qrow = p.qt + ((size_t)b * kSharedHeads + n) * R + 16 * g2;
@@ -157,11 +162,6 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
   }
   __syncthreads();
 
-  const uint8_t* kplane = p.k_codes + (size_t)b * p.t_cap * R;
-  const uint8_t* vplane = p.v_codes + (size_t)b * p.t_cap * R;
-  const uint16_t* kmeta = p.k_scale + (size_t)b * p.t_cap;
-  const uint16_t* vmeta = p.v_scale + (size_t)b * p.t_cap;
-
   float m_run = -INFINITY, l_run = 0.f;                                 // of head n (every wave keeps its own copy)
   v16f U[NKK];                                                          // rows = this wave's dims, columns = heads
 #pragma unroll
@@ -172,31 +172,38 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
   for (int c = c0; c < c1; c++) {
     // ---- scores of this wave's 32 tokens against all heads
     const int t0 = c * kSharedChunk + 32 * wave;
-    const uint8_t* kp = kplane + (size_t)(t0 >> 5) * (32 * R) + (size_t)lane * 16;
     if (g2 == 0) ksc[wave * 32 + n] = f16_bits_to_f32(kmeta[t0 + n]);
     v16i a0, a1, a2;
 #pragma unroll
     for (int v = 0; v < 16; v++) { a0[v] = 0; a1[v] = 0; a2[v] = 0; }
+    // the K operands of the chunk: all R / 32 requests of this wave's 32 tokens in flight together (one trip to memory
+    // per chunk instead of one per batch)
+    v4i ka[NKS];
     {
-      v4i ka[2][8];                                                     // two batches of 8 steps: one in use, one on its way
+      const uint8_t* kp = kplane + (size_t)(t0 >> 5) * (32 * R) + (size_t)lane * 16;
 #pragma unroll
-      for (int u = 0; u < 8; u++) ka[0][u] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)u * 1024));
-#pragma unroll
-      for (int bt = 0; bt < NKS / 8; bt++) {
-        if (bt + 1 < NKS / 8) {
-#pragma unroll
-          for (int u = 0; u < 8; u++)
-            ka[(bt + 1) & 1][u] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)(8 * (bt + 1) + u) * 1024));
-        }
-#pragma unroll
-        for (int u = 0; u < 8; u++) {
-          const int ks = 8 * bt + u;
-          a0 = mfma_i8(ka[bt & 1][u], limbs[(0 * NKS + ks) * 64 + lane], a0);
-          a1 = mfma_i8(ka[bt & 1][u], limbs[(1 * NKS + ks) * 64 + lane], a1);
-          a2 = mfma_i8(ka[bt & 1][u], limbs[(2 * NKS + ks) * 64 + lane], a2);
-        }
-      }
+      for (int ks = 0; ks < NKS; ks++) ka[ks] = __builtin_nontemporal_load((const v4i*)(kp + (size_t)ks * 1024));
     }
+#pragma unroll
+    for (int ks = 0; ks < NKS; ks++) {
+      a0 = mfma_i8(ka[ks], limbs[(0 * NKS + ks) * 64 + lane], a0);
+      a1 = mfma_i8(ka[ks], limbs[(1 * NKS + ks) * 64 + lane], a1);
+      a2 = mfma_i8(ka[ks], limbs[(2 * NKS + ks) * 64 + lane], a2);
+      if ((ks & 3) == 3) __builtin_amdgcn_sched_barrier(0);             // keeps the limb reads from piling up in registers
+    }
+    // the chunk's value blocks are requested now, all at once: they arrive during the softmax
+    const int cbase = c * kSharedChunk;
+    v4i vc[4][NKK], vsr[4][2];
+#pragma unroll
+    for (int tw = 0; tw < 4; tw++) {
+      const int tv = min(cbase + 32 * tw, (n_b - 1) & ~31);             // (a block past the end: the last one again, unused)
+      const uint8_t* vp = vplane + (size_t)(tv >> 5) * (32 * R) + (size_t)(wave * NKK) * 1024 + (size_t)lane * 16;
+#pragma unroll
+      for (int kk = 0; kk < NKK; kk++) vc[tw][kk] = __builtin_nontemporal_load((const v4i*)(vp + kk * 1024));
+      vsr[tw][0] = *(const v4i*)(vmeta + tv + 16 * g2);
+      vsr[tw][1] = *(const v4i*)(vmeta + tv + 16 * g2 + 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -245,25 +252,11 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
 #pragma unroll
         for (int v = 0; v < 16; v++) U[kk][v] *= alpha;
     }
-    {
-      const int cbase = c * kSharedChunk;
-      v4i vc[2][NKK];
-      v4i vsr[2][2];
-      auto vload = [&](int set, int tw) {
-        const int tv = cbase + 32 * tw;
-        const uint8_t* vp = vplane + (size_t)(tv >> 5) * (32 * R) + (size_t)(wave * NKK) * 1024 + (size_t)lane * 16;
 #pragma unroll
-        for (int kk = 0; kk < NKK; kk++) vc[set][kk] = __builtin_nontemporal_load((const v4i*)(vp + kk * 1024));
-        vsr[set][0] = *(const v4i*)(vmeta + tv + 16 * g2);
-        vsr[set][1] = *(const v4i*)(vmeta + tv + 16 * g2 + 8);
-      };
-      vload(0, 0);                                                      // (the chunk's first block always has a row)
-#pragma unroll
-      for (int tw = 0; tw < 4; tw++) {
-        const int tv = cbase + 32 * tw;
-        if (tv >= n_b) break;
-        if (tw + 1 < 4 && tv + 32 < n_b) vload((tw + 1) & 1, tw + 1);
-        v8f16 sv8[2] = {__builtin_bit_cast(v8f16, vsr[tw & 1][0]), __builtin_bit_cast(v8f16, vsr[tw & 1][1])};
+    for (int tw = 0; tw < 4; tw++) {
+      const int tv = cbase + 32 * tw;
+      if (tv < n_b) {
+        v8f16 sv8[2] = {__builtin_bit_cast(v8f16, vsr[tw][0]), __builtin_bit_cast(v8f16, vsr[tw][1])};
         if (tv + 32 > n_b) {      // rows never written may hold any scale: they contribute 0
 #pragma unroll
           for (int s = 0; s < 2; s++)
@@ -275,8 +268,8 @@ __global__ __launch_bounds__(256) void k_shared_attn(SharedParams p) {
         const v8f16 bp1 = *(const v8f16*)&pt[(tw * 32 + n) * 40 + 16 * g2 + 8];
 #pragma unroll
         for (int kk = 0; kk < NKK; kk++) {
-          U[kk] = mfma_f16(codes_f16(vc[tw & 1][kk][0], vc[tw & 1][kk][1]) * sv8[0], bp0, U[kk]);
-          U[kk] = mfma_f16(codes_f16(vc[tw & 1][kk][2], vc[tw & 1][kk][3]) * sv8[1], bp1, U[kk]);
+          U[kk] = mfma_f16(codes_f16(vc[tw][kk][0], vc[tw][kk][1]) * sv8[0], bp0, U[kk]);
+          U[kk] = mfma_f16(codes_f16(vc[tw][kk][2], vc[tw][kk][3]) * sv8[1], bp1, U[kk]);
         }
       }
     }
