@@ -177,8 +177,8 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
       aV[kk][0] = codes_f16(vc[kk][0], vc[kk][1]) * sv8[0];
       aV[kk][1] = codes_f16(vc[kk][2], vc[kk][3]) * sv8[1];
     }
-    if (g2 == 0) sc_lds[n] = f16_bits_to_f32(ks_raw);
-    if (kb + 1 < n_kblocks) load_block(kb + 1);
+    sc_lds[n] = f16_bits_to_f32(ks_raw);                                // (both half waves hold the same value)
+    load_block(min(kb + 1, n_kblocks - 1));                             // (after the last block: that block again, unused)
 
     // scores of the block: rows = its 32 tokens, columns = the 32 queries
     const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
