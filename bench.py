@@ -55,7 +55,7 @@ def parse():
                          "(secondary lines, same JSON shape)")
     ap.add_argument("--linear-direct", action="store_true",
                     help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
-    ap.add_argument("--project-shape", type=int, default=0, choices=[0, 1, 21, 24, 42, 44],
+    ap.add_argument("--project-shape", type=int, default=0, choices=[0, 1, 2, 21, 24, 42, 44],
                     help="prefill: channel tiles x token tiles per wavefront of the tiled projection (tuning; 0 = the library's choice)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")

@@ -169,7 +169,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { g_wsvd_linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { g_wsvd_prefill_tiled = value; return WSVD_OK; }
-  if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 21 || value == 24 || value == 42 || value == 44)) { g_wsvd_project_shape = value; return WSVD_OK; }
+  if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 2 || value == 21 || value == 24 || value == 42 || value == 44)) { g_wsvd_project_shape = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }

@@ -147,10 +147,11 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 constexpr int kProjKC = 64, kProjXRow = 144;
 constexpr int kProjABytes = 8 * 4 * 1024, kProjXBytes = 256 * kProjXRow, kProjStage = kProjABytes + kProjXBytes;
 
-template <int R>
-__global__ __launch_bounds__(256) void k_prefill_project_lds(ProjectParams p) {
+template <int R, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void k_prefill_project_lds(ProjectParams p) {
   extern __shared__ __align__(16) uint8_t proj_lds[];
-  constexpr int RT = R / 32, CT = 4, TT = 4;
+  constexpr int RT = R / 32, CT = 4, TT = 16 / WAVES;                   // 2 x (WAVES / 2) waves, each 4 x TT tiles
+  constexpr int NT = 64 * WAVES, NLD = 2048 / NT;                       // threads; 16-byte pieces of A (and of x) per thread and chunk
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, g2 = lane >> 5;
   const int wc = wave & 1, wt = wave >> 1;
   const int tiles_plane = p.Hkv * RT, tiles = 2 * tiles_plane;
@@ -170,30 +171,31 @@ __global__ __launch_bounds__(256) void k_prefill_project_lds(ProjectParams p) {
   const int n_steps = p.E >> 4, n_chunks = p.E / kProjKC;
   // what this thread copies per chunk: 16 bytes of each of the 8 channel tiles, 16 bytes of 8 of the 256 token rows
   // (uniform base pointers plus 32-bit per-thread offsets: the loads address through scalar registers)
-  const uint8_t* asrc[8];
+  const uint8_t* asrc[NLD];
   const uint8_t* xbase = (const uint8_t*)p.x + (size_t)sq * p.n_tok * p.E * 2;
-  uint32_t xoff[8];
-  int xdst[8];
-  const uint32_t aoff = tid * 16;
+  uint32_t xoff[NLD];
+  int xdst[NLD];
+  const uint32_t aoff = (tid & 255) * 16;
 #pragma unroll
-  for (int j = 0; j < 8; j++) {
-    const int ct = min(cg * 8 + j, tiles - 1);
+  for (int j = 0; j < NLD; j++) {
+    const int u = tid + NT * j;                                         // piece u: tile u / 256 of A, row u / 8 of x
+    const int ct = min(cg * 8 + (u >> 8), tiles - 1);
     asrc[j] = (const uint8_t*)p.A[ct / tiles_plane] + (size_t)(ct % tiles_plane) * n_steps * 1024;
-    const int u = tid + 256 * j, row = u >> 3, sg = u & 7;
+    const int row = u >> 3, sg = u & 7;
     const int tok = min(by * 256 + row, p.n_tok - 1);
     xoff[j] = (uint32_t)tok * (uint32_t)(p.E * 2) + sg * 16;            // the launcher keeps n_tok * E * 2 below 2^31
     xdst[j] = kProjABytes + row * kProjXRow + sg * 16;
   }
-  v4u rg[16];                                                           // the chunk on its way: 8 pieces of A, 8 of x
+  v4u rg[2 * NLD];                                                      // the chunk on its way: NLD pieces of A, NLD of x
   auto fetch1 = [&](int j, int c) {
     c = min(c, n_chunks - 1);                     // (past the end: the last chunk again, written to the idle stage, never read)
-    if (j < 8) rg[j] = *(const v4u*)(asrc[j] + (size_t)c * 4096 + aoff);
-    else rg[j] = *(const v4u*)(xbase + (size_t)c * (kProjKC * 2) + xoff[j - 8]);
+    if (j < NLD) rg[j] = *(const v4u*)(asrc[j] + (size_t)c * 4096 + aoff);
+    else rg[j] = *(const v4u*)(xbase + (size_t)c * (kProjKC * 2) + xoff[j - NLD]);
   };
   auto commit1 = [&](int j, int st) {
     uint8_t* base = proj_lds + st * kProjStage;
-    if (j < 8) *(v4u*)(base + j * 4096 + tid * 16) = rg[j];
-    else *(v4u*)(base + xdst[j - 8]) = rg[j];
+    if (j < NLD) *(v4u*)(base + (tid + NT * j) * 16) = rg[j];
+    else *(v4u*)(base + xdst[j - NLD]) = rg[j];
   };
   v16f acc[CT][TT];
 #pragma unroll
@@ -203,17 +205,17 @@ __global__ __launch_bounds__(256) void k_prefill_project_lds(ProjectParams p) {
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[c][tt][v] = 0.f;
   const int a_off = wc * 4 * 4096 + lane * 16;                          // + c * 4096 + ks * 1024
-  const int x_off = kProjABytes + (wt * 128 + n) * kProjXRow + g2 * 16; // + tt * 32 rows + ks * 32 bytes
+  const int x_off = kProjABytes + (wt * 32 * TT + n) * kProjXRow + g2 * 16; // + tt * 32 rows + ks * 32 bytes
 #pragma unroll
-  for (int j = 0; j < 16; j++) fetch1(j, 0);
+  for (int j = 0; j < 2 * NLD; j++) fetch1(j, 0);
 #pragma unroll
-  for (int j = 0; j < 16; j++) commit1(j, 0);
+  for (int j = 0; j < 2 * NLD; j++) commit1(j, 0);
   __syncthreads();
-  // One wave per SIMD: nothing else fills the issue slots this wave leaves empty, so the order of its instructions is
-  // fixed by hand.  Per step of 16 model dims: the 8 operand reads of the NEXT step, then 4 groups of 4 products, each
-  // followed, in the first two steps, by two 16-byte requests of the next chunk and, in the last step, by four 16-byte
-  // writes of it to the idle stage: requests and writes trickle into the memory pipelines between products instead of
-  // blocking the wave in a burst.
+  // One or two waves per SIMD: little else fills the issue slots a wave leaves empty, so the order of its instructions
+  // is fixed by hand.  Per step of 16 model dims: the operand reads of the NEXT step, then 4 groups of TT products, each
+  // followed, in the first two steps, by its share of the 16-byte requests of the next chunk and, in the last step, by
+  // its share of the 16-byte writes of it to the idle stage: requests and writes trickle into the memory pipelines
+  // between products instead of blocking the wave in a burst.
   for (int c = 0; c < n_chunks; c++) {
     const uint8_t* base = proj_lds + (c & 1) * kProjStage;
     v8bf16 fa[2][CT], fb[2][TT];
@@ -233,17 +235,20 @@ __global__ __launch_bounds__(256) void k_prefill_project_lds(ProjectParams p) {
 #pragma unroll
         for (int tt = 0; tt < TT; tt++) acc[cc][tt] = mfma_bf16(fa[ks & 1][cc], fb[ks & 1][tt], acc[cc][tt]);
         __builtin_amdgcn_sched_barrier(0);
-        if (ks < 2) { fetch1(2 * (ks * 4 + cc), c + 1); fetch1(2 * (ks * 4 + cc) + 1, c + 1); }
+        if (ks < 2) {
+#pragma unroll
+          for (int j = 0; j < NLD / 4; j++) fetch1((NLD / 4) * (ks * 4 + cc) + j, c + 1);
+        }
         if (ks == 3) {
 #pragma unroll
-          for (int j = 0; j < 4; j++) commit1(4 * cc + j, (c + 1) & 1);
+          for (int j = 0; j < NLD / 2; j++) commit1((NLD / 2) * cc + j, (c + 1) & 1);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     __syncthreads();
   }
-  const int ct0 = (cg * 2 + wc) * CT, tb = by * 2 + wt;
+  const int ct0 = (cg * 2 + wc) * CT, tb = by * (8 / TT) + wt;
   if (ct0 >= tiles || tb * 32 * TT >= p.n_tok) return;
   project_store<R, CT, TT>(p, acc, ct0, tb, seq, n0);
 }
@@ -287,21 +292,26 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   const long long work = (long long)n_seq * n_tok * d.n_kv_heads * d.rank;
   const bool staged_ok = d.d_model % kProjKC == 0 && (long long)n_tok * d.d_model * 2 < (1LL << 31);
   int shape = g_wsvd_project_shape ? g_wsvd_project_shape : (work >= (1LL << 22) ? (staged_ok ? 1 : 44) : 21);
-  if (shape == 1 && !staged_ok) shape = 44;
-  if (shape == 1) {
+  if ((shape == 1 || shape == 2) && !staged_ok) shape = 44;
+  if (shape == 1 || shape == 2) {
     const int tiles = 2 * p.Hkv * (d.rank / 32);
     p.n_cg = (tiles + 7) / 8; p.tg_seq = (n_tok + 255) / 256; p.n_tg = p.tg_seq * n_seq;
     dim3 grid((unsigned)(p.n_cg * p.n_tg));
     const size_t lds = 2 * (size_t)kProjStage;
-    static bool raised[2] = {false, false};              // the kernels' limit of dynamic LDS, raised once
-    const void* fn = d.rank == 32 ? (const void*)k_prefill_project_lds<32> : (const void*)k_prefill_project_lds<64>;
-    if (!raised[d.rank == 64]) {
+    static bool raised[4] = {false, false, false, false};   // the kernels' limit of dynamic LDS, raised once
+    const bool w8 = shape == 2;
+    const void* fn = d.rank == 32 ? (w8 ? (const void*)k_prefill_project_lds<32, 8> : (const void*)k_prefill_project_lds<32, 4>)
+                                  : (w8 ? (const void*)k_prefill_project_lds<64, 8> : (const void*)k_prefill_project_lds<64, 4>);
+    const int fi = (d.rank == 64) * 2 + w8;
+    if (!raised[fi]) {
       hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
-      raised[d.rank == 64] = true;
+      raised[fi] = true;
     }
-    if (d.rank == 32) hipLaunchKernelGGL((k_prefill_project_lds<32>), grid, dim3(256), lds, s, p);
-    else hipLaunchKernelGGL((k_prefill_project_lds<64>), grid, dim3(256), lds, s, p);
+    if (d.rank == 32 && !w8) hipLaunchKernelGGL((k_prefill_project_lds<32, 4>), grid, dim3(256), lds, s, p);
+    else if (d.rank == 32) hipLaunchKernelGGL((k_prefill_project_lds<32, 8>), grid, dim3(512), lds, s, p);
+    else if (!w8) hipLaunchKernelGGL((k_prefill_project_lds<64, 4>), grid, dim3(256), lds, s, p);
+    else hipLaunchKernelGGL((k_prefill_project_lds<64, 8>), grid, dim3(512), lds, s, p);
   } else if (d.rank == 32) {
     if (shape == 44) launch_project<32, 4, 4, 4>(p, n_seq, s);
     else if (shape == 42) launch_project<32, 4, 2, 4>(p, n_seq, s);

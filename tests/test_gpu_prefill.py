@@ -156,8 +156,11 @@ def test_prefill_whole_prompt_projection_matches_oracle(name, over):
 
 @pytest.mark.parametrize("name,over,shape,n", [("c3_small", {}, 0, 100), ("c3_small", {}, 1, 100), ("c3_small", {}, 44, 100),
                                                ("c3_small", {}, 42, 100), ("c3_small", {}, 24, 100), ("c3_small", dict(rank=64), 1, 100),
-                                               ("c5_small", {}, 1, 300), ("c3_small", dict(batch=2, context=40), 1, 515)],
-                         ids=["auto", "staged", "d44", "d42", "d24", "staged-r64", "staged-r64g7-300", "staged-515"])
+                                               ("c5_small", {}, 1, 300), ("c3_small", dict(batch=2, context=40), 1, 515),
+                                               ("c3_small", {}, 2, 100), ("c5_small", {}, 2, 300),
+                                               ("c3_small", dict(batch=2, context=40, rank=64), 2, 515)],
+                         ids=["auto", "staged", "d44", "d42", "d24", "staged-r64", "staged-r64g7-300", "staged-515",
+                              "staged8", "staged8-r64g7-300", "staged8-r64-515"])
 def test_prefill_all_sequences_in_one_call(name, over, shape, n):
     """seq_index = -1: the same number of prompt tokens for every sequence, x = [batch, n_tokens, d_model]; the staged
     projection kernel and every wave-tile shape of the direct one."""
