@@ -774,6 +774,11 @@ def run_prefill(args, np, torch, W, WI):
                      "achieved": round(pairs * 6 / (ms_tiled * 1e-3) / 1e12, 2), "peak": 157.3, "unit": "TFLOP/s",
                      "frac": round(pairs * 6 / (ms_tiled * 1e-3) / 1e12 / 157.3, 4), "traffic": None,
                      "algorithmic_flops_per_launch": int(pairs * 6), "avg_launch_us": round(ms_tiled * 1e3, 2),
+                     # the same kernel against the vector ALU's issue rate without packed fp32: 256 CUs x 64 lanes x 2.4 GHz
+                     # = 39.3 T lane-operations/s; per pair 4.5 simple operations (scale, max, subtract, sum, half a packed
+                     # conversion), one exp2 at quarter rate (4 slots) and 3 slots of code conversion = 11.5 slots
+                     "valu_issue_view": {"achieved": round(pairs * 11.5 / (ms_tiled * 1e-3) / 1e12, 2), "peak": 39.3,
+                                         "unit": "T lane-ops/s", "frac": round(pairs * 11.5 / (ms_tiled * 1e-3) / 1e12 / 39.3, 4)},
                      "mfma_view": {"achieved": round(pairs * 4 * r / (ms_tiled * 1e-3) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
                                    "frac": round(pairs * 4 * r / (ms_tiled * 1e-3) / 1e12 / 2500.0, 4),
                                    "algorithmic_flops_per_launch": int(pairs * 4 * r)}},
