@@ -56,6 +56,9 @@ def lib():
     """Load libwsvd.so (built by paper_2604_02570_amd.build / __graft_entry__.build).  Fails loudly."""
     global _lib
     if _lib is None:
+        # PyTorch brings its own copy of the HIP runtime: it has to be loaded before this library pulls in the system's,
+        # or device calls made through the second copy fail
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             # nothing built yet: build in-tree once; a failed build raises (there is no fallback path)
             from .build import build
