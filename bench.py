@@ -28,6 +28,10 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy of known size.
 MEASURED_TRAFFIC_BYTES = 72_360_000   # 72.10 MB fetched + 0.26 MB written (profiles/attn_mfma_int8_c3_hbm_traffic.md)
 MEASURED_TRAFFIC_BYTES_C5 = 141_840_000   # 140.8 MB fetched + 1.03 MB written (profiles/attn_gqa_int8_c5_hbm_traffic.md)
+# prefill and shared-latent kernels (profiles/prefill_int8_c3_kernel_trace.md, profiles/attn_shared_int8_r1024_kernel_trace.md)
+MEASURED_TRAFFIC_PREFILL_ATTN = 894_500_000    # 357.6 MB fetched + 536.9 MB written (the fp32 outputs)
+MEASURED_TRAFFIC_PREFILL_PROJ = 881_700_000    # 808.3 MB fetched (factors once per XCD and round of workgroups) + 73.4 MB written
+MEASURED_TRAFFIC_SHARED_STEP = 186_000_000     # three launches: 142.9 MB fetched + 43.1 MB written
 
 
 def parse():
@@ -772,7 +776,8 @@ def run_prefill(args, np, torch, W, WI):
         # subtract, exp2, sum, weight conversion = 6 operations.
         "roofline": {"kernel": "k_prefill_attn (causal attention of all prompt tokens in latent space)", "bound": "alu",
                      "achieved": round(pairs * 6 / (ms_tiled * 1e-3) / 1e12, 2), "peak": 157.3, "unit": "TFLOP/s",
-                     "frac": round(pairs * 6 / (ms_tiled * 1e-3) / 1e12 / 157.3, 4), "traffic": None,
+                     "frac": round(pairs * 6 / (ms_tiled * 1e-3) / 1e12 / 157.3, 4), "traffic": MEASURED_TRAFFIC_PREFILL_ATTN,
+                     "algorithmic_bytes_per_launch": int(B * Hkv * T * (Hq // Hkv) * d * (2 + 4) + B * Hkv * T * 2 * (r + 2)),
                      "algorithmic_flops_per_launch": int(pairs * 6), "avg_launch_us": round(ms_tiled * 1e3, 2),
                      # the same kernel against the vector ALU's issue rate without packed fp32: 256 CUs x 64 lanes x 2.4 GHz
                      # = 39.3 T lane-operations/s; per pair 4.5 simple operations (scale, max, subtract, sum, half a packed
@@ -784,7 +789,7 @@ def run_prefill(args, np, torch, W, WI):
                                    "algorithmic_flops_per_launch": int(pairs * 4 * r)}},
         "roofline_projection": {"kernel": "k_prefill_project_lds (bf16 projection of all prompt tokens, quantise, store)", "bound": "mfma",
                                 "achieved": round(flops / (ms * 1e-3) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
-                                "frac": round(flops / (ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
+                                "frac": round(flops / (ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": MEASURED_TRAFFIC_PREFILL_PROJ,
                                 "algorithmic_flops_per_launch": int(flops), "avg_launch_us": round(ms * 1e3, 2),
                                 "note": "avg_launch_us includes the length update kernel and the reset of the lengths between steps",
                                 "hbm_view": {"algorithmic_bytes_per_launch": int(proj_bytes),
@@ -857,7 +862,7 @@ def run_shared(args, np, torch, W, WI):
         # the step's three launches are timed together here; the kernel-trace summary under profiles/ splits them
         "roofline": {"kernel": "wsvd_decode_attn_shared (k_shared_absorb + k_shared_attn + k_shared_out)", "bound": "hbm",
                      "achieved": round(cache_bytes / (us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(cache_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(cache_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_SHARED_STEP,
                      "algorithmic_bytes_per_launch": int(cache_bytes),
                      "other_bytes_per_step": {"up_projection_factors": int(factor_bytes), "split_partials_written_and_read": int(2 * 4 * (ws_floats - B * H * R))},
                      "int8_score_GOP_issued": round(3 * 2.0 * B * T * R * H / 1e9, 2), "fp16_value_GFLOP": round(2.0 * B * T * R * H / 1e9, 2)},

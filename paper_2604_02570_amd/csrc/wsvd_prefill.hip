@@ -142,8 +142,8 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
     const size_t off = (size_t)kb * (32 * R) + (size_t)lane * 16;
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
-      kc[kk] = __builtin_nontemporal_load((const v4i*)(kplane + off + kk * 1024));
-      vc[kk] = __builtin_nontemporal_load((const v4i*)(vplane + off + kk * 1024));
+      kc[kk] = *(const v4i*)(kplane + off + kk * 1024);                 // (plain loads: the other query blocks of this
+      vc[kk] = *(const v4i*)(vplane + off + kk * 1024);                 //  sequence and head read the same blocks again)
     }
     ks_raw = kmeta[kb * 32 + n];
     vs16[0] = *(const v4i*)(vmeta + kb * 32 + 16 * g2);
