@@ -163,7 +163,12 @@ wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const v
  *   "max_threads": cap on the attention workgroup size (0 = the kernel's own bound)
  *   "append_mode": number of d_model slices of the append (0 = automatic)
  *   "fused_step": wsvd_decode_step uses 0 = two launches (default), 1 = the single-launch kernel where one exists,
- *                 2 = the single-launch kernel or WSVD_E_UNSUPPORTED */
+ *                 2 = the single-launch kernel or WSVD_E_UNSUPPORTED
+ *   "linear_direct": 1 = the W4A8 linear layers read their operands straight from memory (no LDS staging)
+ *   "prefill_tiled": 1 = wsvd_prefill_attn and wsvd_prefill_append take their tiled kernels also for small calls
+ *   "project_shape": kernel of the tiled prefill projection: 0 = automatic, 1 / 2 = LDS-staged with 4 / 8 waves per
+ *                 workgroup, 44 / 42 / 24 / 21 = direct kernel with that many channel x token tiles per wave
+ * Unknown names and values out of range return WSVD_E_SHAPE. */
 wsvd_status wsvd_set_option(const char *name, int value);
 
 /*
