@@ -468,3 +468,29 @@ def test_prefill_full_size_sampled():
         got[t] = out[t].cpu().numpy()
     check_out(got, ref, "i8", f"full-size prompt attention, {len(toks)} sampled (sequence, head, token) triples")
     L.close()
+
+
+def test_prefill_all_sequences_capacity_of_some():
+    """seq_index = -1 with sequences of different lengths: those whose prompt does not fit are left full and reported,
+    the rows that fit are stored for all of them, the others advance by the whole prompt."""
+    c = build_case("c3_small", extra_cap=70)
+    sp = c.sp
+    c.cache.seq_lens[:] = [333, 400, 250]         # (rows past the built context hold the cache's initial contents)
+    L = layer_for(c); L.upload(c.cache)
+    n = 100
+    X = np.stack([WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=90 + b)) for b in range(sp.batch)])
+    xd = as_dtype_dev(X.reshape(sp.batch * n, -1), "bf16")
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    starts = c.cache.seq_lens.copy()
+    room = L.t_cap - starts
+    assert (room < n).any() and (room >= n).any(), "the case needs both kinds of sequences"
+    over = [O.latent_prefill(c.cache, b, X[b].astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+            for b in range(sp.batch)]
+    assert over == [bool(r < n) for r in room]
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, n, -1, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == W.E_CAPACITY
+    want = np.minimum(starts + n, L.t_cap)
+    assert (L.seq_lens.cpu().numpy() == want).all() and (c.cache.seq_lens == want).all()
+    for b in range(sp.batch):
+        _compare_rows(L, c.cache, b, int(starts[b]), int(want[b] - starts[b]), "i8")
+    L.close()
