@@ -547,7 +547,8 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
         omega[g] = wref[g] * (1.f / kLimbFull);
       }
       const int Q = (int)__builtin_rintf(wt * winv[g]);           // 0 .. 2^20
-      if (I4) zacc[g] = fmaf((float)Q * omega[g], vz, zacc[g]);
+      // a row past the end may hold any metadata bits (NaN included): its zero point must not meet its zero weight
+      if (I4) zacc[g] = fmaf((float)Q * omega[g], valid ? vz : 0.f, zacc[g]);
       wl[wave][g][0][wpos] = (uint8_t)(Q >> 14);
       wl[wave][g][1][wpos] = (uint8_t)((Q >> 7) & 127);
       wl[wave][g][2][wpos] = (uint8_t)(Q & 127);

@@ -39,7 +39,9 @@ class DeviceLayer:
         self.B, self.Hq, self.Hkv, self.d, self.E, self.r, self.t_cap = batch, n_q_heads, n_kv_heads, d_head, d_model, rank, t_cap
         self.ctx = W.wsvd_create(0)
         cb, mb = W.wsvd_cache_bytes(self.desc)
-        fill = 0xA5 if poison else 0           # garbage in never-written rows must not leak into results
+        # garbage in never-written rows must not leak into results: int codes 0xA5, float latents and metadata NaN
+        self.poison = poison
+        fill = (0xFF if latent_dtype in ("f32", "bf16") else 0xA5) if poison else 0
         self.k_codes = torch.full((cb,), fill, dtype=torch.uint8, device="cuda")
         self.v_codes = torch.full((cb,), fill, dtype=torch.uint8, device="cuda")
         self.k_meta = torch.full((max(mb, 16),), 0xFF if poison else 0, dtype=torch.uint8, device="cuda")  # fp16 NaN pattern
@@ -55,16 +57,34 @@ class DeviceLayer:
         W.wsvd_destroy(self.ctx)
 
     # ---- oracle cache (logical) -> device layout
-    def upload(self, oc: O.LatentCache, n_rows=None):
-        n_rows = n_rows or oc.t_cap
-        for plane, codes, scale, zero in ((0, oc.k, oc.k_scale, oc.k_zero), (1, oc.v, oc.v_scale, oc.v_zero)):
-            lc = dev(codes[:, :, :n_rows])
-            meta = None
-            if oc.dtype == "i8":
-                meta = dev(scale[:, :, :n_rows].view(np.uint16))
-            elif oc.dtype == "i4":
-                meta = dev(np.stack([scale[:, :, :n_rows].view(np.uint16), zero[:, :, :n_rows].view(np.uint16)], axis=-1))
-            W.wsvd_cache_import(self.ctx, self.desc, plane, lc, meta, 0, n_rows, self.cache)
+    def upload(self, oc: O.LatentCache, n_rows=None, keep_poison=True):
+        """Rows [0, n_rows) of the oracle's cache -> device (default: up to the longest sequence).  With keep_poison
+        the rows at and past each sequence's length are NOT the oracle's clean zeros but the poison pattern of the
+        constructor (codes 0xA5, metadata fp16 NaN, float latents NaN), so that the device planes look like memory the
+        append never wrote: a kernel that lets such a row reach a result fails its parity test."""
+        lens = oc.seq_lens.astype(np.int64)
+        n_rows = int(n_rows or lens.max())
+        if n_rows > 0:
+            past = np.arange(n_rows)[None, None, :] >= lens[:, None, None]          # [B, 1, n_rows]
+            past = np.broadcast_to(past, (oc.k.shape[0], oc.k.shape[1], n_rows))
+            for plane, codes, scale, zero in ((0, oc.k, oc.k_scale, oc.k_zero), (1, oc.v, oc.v_scale, oc.v_zero)):
+                host = np.ascontiguousarray(codes[:, :, :n_rows]).copy()
+                if keep_poison and self.poison:
+                    raw = host.view(np.uint8).reshape(host.shape[0], host.shape[1], n_rows, -1)
+                    raw[past] = 0xFF if oc.dtype in ("f32", "bf16") else 0xA5
+                lc = dev(host)
+                meta = None
+                if oc.dtype == "i8":
+                    m = scale[:, :, :n_rows].view(np.uint16).copy()
+                    if keep_poison and self.poison:
+                        m[past] = 0xFFFF
+                    meta = dev(m)
+                elif oc.dtype == "i4":
+                    m = np.stack([scale[:, :, :n_rows].view(np.uint16), zero[:, :, :n_rows].view(np.uint16)], axis=-1).copy()
+                    if keep_poison and self.poison:
+                        m[past] = 0xFFFF
+                    meta = dev(m)
+                W.wsvd_cache_import(self.ctx, self.desc, plane, lc, meta, 0, n_rows, self.cache)
         self.seq_lens.copy_(torch.from_numpy(oc.seq_lens.astype(np.int32)))
         torch.cuda.synchronize()
 
@@ -141,3 +161,50 @@ def err_stats(got: np.ndarray, ref: np.ndarray):
     diff = got - ref
     return float(np.abs(diff).max()), float(np.abs(diff).max() / max(np.abs(ref).max(), 1e-300)), \
         float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-300))
+
+
+def check_i8_rows(got_codes, got_scale, values64, what, code_tol=1e-3, scale_tol=1e-5):
+    """Symmetric int8 rows written by the GPU from fp32 values that may differ from the oracle's fp64 ones in the last
+    bits, against the oracle's quantiser applied to those fp64 values.  values64 [N, r] are the oracle's values before
+    quantisation, got_codes [N, r] int8, got_scale [N] fp16.  Accepted, and counted in the return value:
+      * a code one step away from the oracle's, only where value / scale lies within code_tol of a .5 rounding boundary;
+      * a scale one fp16 step away from the oracle's, only where max|row| / 127 lies within scale_tol (relative) of the
+        midpoint between the two fp16 neighbours.  (The fp16 spacing is itself 5e-4 .. 1e-3 relative, so a looser bound
+        would accept any row; 1e-5 is about 2 % of the spacing and covers what an fp32 evaluation of the maximum can
+        move.)  The codes of such a row are still checked, against the rule applied with the GPU's scale.
+    Anything else fails."""
+    v = np.asarray(values64, np.float64)
+    v = v.reshape(-1, v.shape[-1])
+    g = np.asarray(got_codes).reshape(v.shape).astype(np.int64)
+    gs = np.asarray(got_scale).reshape(-1).view(np.float16)
+    ref_codes, ref_scale = O.quantize_int8_rows(v.astype(np.float32))
+    r = ref_codes.astype(np.int64)
+    gbits = gs.view(np.uint16).astype(np.int64); rbits = ref_scale.view(np.uint16).astype(np.int64)
+    same = gbits == rbits
+    flips = 0
+    # rows whose scale agrees: codes equal, or one step apart on a rounding boundary
+    s64 = ref_scale.astype(np.float64)[:, None]
+    bad = (g != r) & same[:, None]
+    if bad.any():
+        assert np.abs(g - r)[bad].max() == 1, f"{what}: a code is off by more than one step"
+        x = (v / s64)[bad]
+        frac = np.abs(x - np.floor(x) - 0.5)
+        assert frac.max() < code_tol, f"{what}: code differs away from a rounding boundary (distance {frac.max():.3e} steps)"
+        flips += int(bad.sum())
+    # rows whose scale differs: neighbours in fp16, the exact scale on their midpoint, codes right under the GPU's scale
+    for i in np.nonzero(~same)[0]:
+        assert abs(int(gbits[i]) - int(rbits[i])) == 1, f"{what}: row {i}: scales {gs[i]} / {ref_scale[i]} are not fp16 neighbours"
+        a127 = np.abs(v[i]).max() / 127.0
+        mid = 0.5 * (float(gs[i]) + float(ref_scale[i]))
+        assert abs(a127 - mid) <= scale_tol * mid, \
+            f"{what}: row {i}: scale differs away from an fp16 rounding boundary (max/127 = {a127!r}, boundary {mid!r})"
+        x = v[i] / float(gs[i])
+        e = np.clip(np.rint(x), -127, 127).astype(np.int64)
+        d = g[i] != e
+        if d.any():
+            assert np.abs(g[i] - e)[d].max() == 1, f"{what}: row {i}: a code is off by more than one step"
+            frac = np.abs(x[d] - np.floor(x[d]) - 0.5)
+            assert frac.max() < code_tol, f"{what}: row {i}: code differs away from a rounding boundary"
+            flips += int(d.sum())
+        flips += 1
+    return flips

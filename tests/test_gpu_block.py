@@ -212,28 +212,31 @@ def test_block_c5_small(stagewise):
     L.close()
 
 
-def test_config5_block_full_size():
-    """One layer of the 28-layer workload at its real shape (batch 32, 28 query / 4 kv heads, rank 64, 8192 rows of
-    context).  The reconstructing oracle runs on a sample of heads; the absorbed oracle, checked against it on that
-    sample, provides every head, from which the oracle's own quantiser and W_O give the reference block output."""
+@pytest.mark.parametrize("layer", list(range(28)))
+def test_config5_block_full_size(layer):
+    """Every one of the 28 independent layers of the workload (per-layer seeds for weights, factors and cache, the same
+    hidden state fed to each) at its real shape: batch 32, 28 query / 4 kv heads, rank 64, 8192 rows of context, the
+    launches the benchmark times.  The reconstructing oracle runs on a sample of heads (96 for layer 3, 12 elsewhere);
+    the absorbed oracle, checked against it on that sample, provides every head, from which the oracle's own quantiser
+    and W_O give the reference block output."""
     import time
     t0 = time.time()
-    c = build_block_case("c5", layer=3)
+    c = build_block_case("c5", layer=layer)
     sp = c.sp
-    print(f"c5 inputs built in {time.time() - t0:.1f}s", flush=True)
     L = layer_for(c); L.upload(c.cache)
-    rng = np.random.default_rng(5)
-    heads = [(int(b), int(h)) for b, h in zip(rng.integers(0, sp.batch, 96), rng.integers(0, sp.n_q_heads, 96))]
+    rng = np.random.default_rng(5 + layer)
+    n_sample = 96 if layer == 3 else 12
+    heads = [(int(b), int(h)) for b, h in zip(rng.integers(0, sp.batch, n_sample), rng.integers(0, sp.n_q_heads, n_sample))]
     before = c.cache.seq_lens.copy()
     ref = _oracle_block(c, heads=heads)
     q32 = ref["q"].astype(np.float32).astype(np.float64)
     attn_all = O.decode_attn_absorbed(c.cache, q32, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
     m = ~np.isnan(ref["attn"])
-    assert m.sum() >= 64 * sp.d_head          # the 96 draws contain a few repeats
+    assert m.sum() >= (n_sample * 2 // 3) * sp.d_head          # the draws contain a few repeats
     assert np.abs(attn_all[m] - ref["attn"][m]).max() <= 1e-9 * np.abs(ref["attn"][m]).max()
     ref["attn"] = attn_all
     ref["o_codes"], ref["o_scale"] = O.quantize_act_i8(attn_all.reshape(sp.batch, -1).astype(np.float32))
     ref["y"] = O.linear_w4a8(ref["o_codes"], ref["o_scale"], O.pack_w4(c.wo[0]), c.wo[1])
-    print(f"c5 oracle done at {time.time() - t0:.1f}s", flush=True)
+    print(f"c5 layer {layer}: inputs and oracle in {time.time() - t0:.1f}s", flush=True)
     _run_block(c, L, False, ref=ref, before=before)
     L.close()

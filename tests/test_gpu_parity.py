@@ -122,7 +122,7 @@ def test_cache_import_export_round_trip(dtype, r):
         oc.store_rows("v", b, 0, rng.standard_normal((Hkv, t_cap, r)) * 3)
     fd = "f32" if dtype == "f32" else "bf16"
     L = DeviceLayer(B, Hkv, Hkv, 128 if r > 16 else 64, 512, r, t_cap, dtype, fd, fd, fd if dtype in ("f32", "bf16") else "i8")
-    L.upload(oc)
+    L.upload(oc, n_rows=t_cap, keep_poison=False)      # all rows as they are (the lengths stay 0: only the copies are tested)
     for plane, codes, scale, zero in ((0, oc.k, oc.k_scale, oc.k_zero), (1, oc.v, oc.v_scale, oc.v_zero)):
         for (t0, n) in ((0, t_cap), (5, 61), (64, 1), (33, 2)):
             gc, gs, gz = L.download(plane, t0, n)
@@ -294,7 +294,53 @@ def test_cross_workgroup_handoffs_are_repeatable(name, over):
             rows += [gc.copy(), gs.copy()] + ([gz.copy()] if gz is not None else [])
         if rows0 is None:
             rows0 = rows
-        assert all((a == b).all() for a, b in zip(rows, rows0)), f"append {it} differs from append 0"
+        # bit patterns, not values: rows past a shorter sequence's end hold NaN metadata
+        assert all(a.tobytes() == b.tobytes() for a, b in zip(rows, rows0)), f"append {it} differs from append 0"
+    L.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2_small", "c3_small", "c4_small", "c5_small"], ids=["f32", "bf16", "i8", "i4", "i8r64g7"])
+def test_append_then_attend_from_never_written_cache(name):
+    """Nothing is uploaded: the planes hold the poison pattern (codes 0xA5, metadata and float latents NaN bits) that
+    stands for memory the append never wrote, the lengths start at 0, and every row comes from wsvd_latent_append.
+    The attention is checked at lengths inside the first 32-row block, across the 64-row tile edge and past it: a kernel
+    that lets a never-written row of its last tile reach the result (a NaN scale or zero point times a zero weight)
+    returns NaN here."""
+    steps = 70
+    c = build_case(name, batch=3, steps=steps)
+    sp = c.sp
+    oc = O.LatentCache(sp.batch, sp.n_kv_heads, c.t_cap, sp.rank, sp.latent_dtype)
+    L = layer_for(c)
+    fd = sp.factor_dtype
+    AKd, AVd = L.pack_A(c.AK, fd), L.pack_A(c.AV, fd)
+    BKd, BVd = as_dtype_dev(c.BK, fd), as_dtype_dev(c.BV, fd)
+    AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
+    for step in range(steps):
+        x = c.x_new[step] if fd == "f32" else WI.bf16_exact(c.x_new[step])
+        assert not O.latent_append(oc, x.astype(np.float64), AK64, AV64).any()
+        assert L.append(as_dtype_dev(x, fd), None, AKd, AVd) == 0
+        if step + 1 in (1, 2, 31, 33, 63, 64, 65, 70):
+            qd, qs, q64 = q_to_device(c.q32[step], sp.q_dtype)
+            got = L.attend(qd, qs, BKd, BVd, step + 1)
+            ref = O.decode_attn_reconstructed(oc, q64, BK64, BV64, c.sm_scale)
+            check_out(got, ref, sp.latent_dtype, f"never-written cache {name}, {step + 1} rows")
+    assert (L.seq_lens.cpu().numpy() == steps).all()
+    L.close()
+
+
+@pytest.mark.parametrize("name,over", [("c4_small", dict()), ("c3_small", dict()), ("c5_small", dict()),
+                                       ("c4_small", dict(n_q_heads=16, n_kv_heads=4))], ids=["i4", "i8", "i8r64g7", "i4g4"])
+def test_rows_past_the_end_hold_nan_metadata(name, over):
+    """Regression: the last tile of a sequence whose length is not a multiple of 64 ends in rows that were never
+    written; their scale and zero point are fp16 NaN here, their codes 0xA5.  The output must be finite and right."""
+    c = build_case(name, batch=4, context=300, ragged=(), extra_cap=64, **over)
+    for b, n in enumerate((1, 37, 65, 299)):
+        c.cache.seq_lens[b] = n
+    L = layer_for(c); L.upload(c.cache)
+    meta = L.k_meta.cpu().numpy()
+    assert (meta[-64:] == 0xFF).all(), "the case needs poisoned rows behind the last sequence"
+    got, ref = run_attend(c, L)
+    check_out(got, ref, c.sp.latent_dtype, f"NaN metadata past the end, {name}{over}")
     L.close()
 
 
@@ -614,6 +660,47 @@ def test_config3_int8_full():
     L = layer_for(c); L.upload(c.cache)
     got, ref = run_attend(c, L)
     check_out(got, ref, "i8", "c3 full")
+    L.close()
+
+
+def test_config3_int8_append_and_step_full():
+    """The cache update of the batched int8 workload at its full shape (16 sequences, d_model 4096, 32 kv heads: the
+    launch the benchmark times, several d_model slices merged through the workspace), rows compared with the oracle's;
+    then a whole wsvd_decode_step at the same shape, all 512 heads against the materialising oracle."""
+    c = build_case("c3", steps=2)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
+    # 1. append alone
+    x = WI.bf16_exact(c.x_new[0]); x64 = x.astype(np.float64)
+    before = c.cache.seq_lens.copy()
+    cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+    assert not O.latent_append(c.cache, x64, AK64, AV64).any()
+    assert L.append(as_dtype_dev(x, "bf16"), None, AKd, AVd) == 0
+    assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+    flips = _append_compare(L, c.cache, cK, cV, before, "i8")
+    print(f"c3 full append: boundary flips accepted = {flips} of {2 * sp.batch * sp.n_kv_heads * sp.rank} codes", flush=True)
+    assert flips <= 8
+    # the rows before the new one are untouched
+    for plane, codes in ((0, c.cache.k), (1, c.cache.v)):
+        gc, _, _ = L.download(plane, 0, int(before.min()))
+        assert (gc.reshape(codes[:, :, :int(before.min())].shape) == codes[:, :, :int(before.min())]).all()
+    # 2. a whole decode step on top (from the oracle's cache, so that both sides attend over the same rows)
+    L.upload(c.cache)
+    x = WI.bf16_exact(c.x_new[1]); x64 = x.astype(np.float64)
+    before = c.cache.seq_lens.copy()
+    cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+    assert not O.latent_append(c.cache, x64, AK64, AV64).any()
+    qd, qs, q64 = q_to_device(c.q32[1], sp.q_dtype)
+    got, st = L.step(as_dtype_dev(x, "bf16"), AKd, AVd, qd, qs, BKd, BVd, int(c.cache.seq_lens.max()))
+    assert st == 0, W.status_str(st)
+    assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+    flips = _append_compare(L, c.cache, cK, cV, before, "i8")
+    assert flips <= 8
+    ref = O.decode_attn_reconstructed(c.cache, q64, BK64, BV64, c.sm_scale)
+    check_out(got, ref, "i8", "c3 full decode step (append + attention)")
     L.close()
 
 

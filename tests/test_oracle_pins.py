@@ -348,6 +348,62 @@ def test_attention_block_w4a8_consistency():
     np.testing.assert_allclose(res["y"], O.linear_w4a8(res["o_codes"], res["o_scale"], wo, wos), rtol=0)
 
 
+def test_attention_block_glue_against_torch():
+    """The block's own glue (what lies between the pinned pieces), re-done with torch ops on de-quantised tensors:
+    the [B, Hq, d] split of the query projection, the kv*r + j channel split of the two latent projections, the cache
+    update, grouped-query attention with K = C B_K, V = C B_V formed by einsum, the [B, Hq*d] flattening that the
+    per-token quantiser of o sees, and W_O.  Every head and channel has its own values, and Hq != Hkv, d != r, so a
+    transposed reshape, a wrong head / kv mapping or a wrong flattening order changes the result."""
+    rng = np.random.default_rng(26)
+    B, Hkv, G, n, r, d, E = 3, 2, 3, 21, 8, 16, 32
+    Hq = Hkv * G
+    cache = _rand_cache(rng, B, Hkv, n, r, "i8", t_cap=n + 2)
+    before = (cache.k.copy(), cache.v.copy())
+    x32 = (rng.standard_normal((B, E)) * 2).astype(np.float32)
+    xq, xs = O.quantize_act_i8(x32)
+    def w4(N, K):
+        c, s = O.quantize_w4_rows(rng.standard_normal((N, K)) / np.sqrt(K))
+        return O.pack_w4(c), s, (c.astype(np.float64) * s.astype(np.float64)[:, None])
+    wq_p, wq_s, Wq = w4(Hq * d, E)
+    ak_p, ak_s, Ak = w4(Hkv * r, E)
+    av_p, av_s, Av = w4(Hkv * r, E)
+    wo_p, wo_s, Wo = w4(E, Hq * d)
+    BK = rng.standard_normal((Hkv, r, d)); BV = rng.standard_normal((Hkv, r, d))
+    sm = 0.3
+    res = O.attention_block_w4a8(cache, xq, xs, wq_p, wq_s, ak_p, ak_s, av_p, av_s, BK, BV, wo_p, wo_s, Hq, d, sm)
+
+    t = torch.from_numpy
+    lin = torch.nn.functional.linear
+    f32 = lambda a: a.to(torch.float32).to(torch.float64)
+    X = t(xq.astype(np.float64) * xs.astype(np.float64)[:, None])          # the de-quantised hidden state
+    q = lin(X, t(Wq)); cK = lin(X, t(Ak)); cV = lin(X, t(Av))
+    np.testing.assert_allclose(res["q"], q.reshape(B, Hq, d).numpy(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(res["cK"], cK.reshape(B, Hkv, r).numpy(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(res["cV"], cV.reshape(B, Hkv, r).numpy(), rtol=1e-12, atol=1e-12)
+    # cache: old rows untouched, row n = the cache quantiser applied to head kv's slice [kv*r, (kv+1)*r), lengths + 1
+    assert (cache.seq_lens == n + 1).all()
+    assert (cache.k[:, :, :n] == before[0][:, :, :n]).all() and (cache.v[:, :, :n] == before[1][:, :, :n]).all()
+    for kv in range(Hkv):
+        kc, ks = O.quantize_int8_rows(cK[:, kv * r:(kv + 1) * r].numpy().astype(np.float32))
+        vc, vs = O.quantize_int8_rows(cV[:, kv * r:(kv + 1) * r].numpy().astype(np.float32))
+        assert (cache.k[:, kv, n] == kc).all() and (cache.k_scale[:, kv, n] == ks).all()
+        assert (cache.v[:, kv, n] == vc).all() and (cache.v_scale[:, kv, n] == vs).all()
+    # grouped-query attention over the materialised keys and values; query head h uses kv head h // G
+    CK = t(_dequant_all(cache, "k")); CV = t(_dequant_all(cache, "v"))        # [B, Hkv, n + 1, r]
+    K = torch.einsum("bktj,kjc->bktc", CK, t(BK)).repeat_interleave(G, dim=1)
+    V = torch.einsum("bktj,kjc->bktc", CV, t(BV)).repeat_interleave(G, dim=1)
+    qh = f32(q).reshape(B, Hq, 1, d)                                          # fp32 as it leaves the projection
+    o = torch.nn.functional.scaled_dot_product_attention(qh, K, V, scale=sm)[:, :, 0]       # [B, Hq, d]
+    np.testing.assert_allclose(res["attn"], o.numpy(), rtol=1e-10, atol=1e-11)
+    # per-token quantiser over the row [h*d + c], then W_O
+    oc, os_ = O.quantize_act_i8(o.reshape(B, Hq * d).numpy().astype(np.float32))
+    assert (res["o_codes"] == oc).all() and (res["o_scale"] == os_).all()
+    y = lin(t(oc.astype(np.float64) * os_.astype(np.float64)[:, None]), t(Wo))
+    np.testing.assert_allclose(res["y"], y.numpy(), rtol=1e-12, atol=1e-12)
+    # the pin has teeth: heads differ, so a permuted head order would not pass
+    assert np.abs(o[:, 0] - o[:, 1]).max() > 1e-3 and np.abs(o[:, 0] - o[:, G]).max() > 1e-3
+
+
 # ---- rotary variant (reconstruct, rotate, then q K^T) ---------------------------------------
 def test_rope_rotation_is_the_textbook_one():
     """Pairs (i, i + d/2) as complex numbers multiplied by exp(i pos theta_i): an independent formulation."""
