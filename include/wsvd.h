@@ -157,6 +157,22 @@ wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const v
                              const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,
                              void *out, void *hip_stream);
 
+/*
+ * wsvd_decode_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results as
+ * wsvd_decode_attn, but the split partials and tickets live in an array that is part of the library image
+ * (8 MiB of device memory per GPU the library runs on, held until the process ends) instead of the workspace set
+ * with wsvd_set_workspace, which is neither needed nor touched.  The call allocates nothing and frees nothing.
+ *   Limit: 65536 + 4 * batch * n_q_heads * ceil(t_cap / 256) * (rank + 2) bytes must fit in the 8 MiB
+ *   (all five documented workloads do); WSVD_E_WORKSPACE otherwise, nothing enqueued.
+ *   Every call on a GPU shares that GPU's array, from every context and stream: calls that overlap in time on one
+ *   GPU race on it.  Calls on one stream are ordered and safe.
+ * Enqueues a small clearing kernel and the attention kernel on hip_stream; error behaviour as wsvd_decode_attn.
+ */
+wsvd_status wsvd_decode_attn_static(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
+                                    const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,
+                                    void *out, void *hip_stream);
+
 /* Process-wide tuning knobs for benchmarks and tests; correct use never needs them.
  *   "wg_per_cu": scales the number of wavefronts the attention grid aims for (default 4 = one resident round)
  *   "min_chunk": smallest context chunk per workgroup in rows, multiple of 64, at least 256

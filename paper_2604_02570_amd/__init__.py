@@ -24,7 +24,7 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
-           "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
+           "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_static", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
@@ -77,6 +77,7 @@ def lib():
         L.wsvd_latent_store.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int64, POINTER(Cache), c_void_p]
         L.wsvd_decode_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                        POINTER(Cache), c_int32, c_void_p, c_void_p]
+        L.wsvd_decode_attn_static.argtypes = L.wsvd_decode_attn.argtypes
         L.wsvd_decode_attn_rope.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                             POINTER(Cache), c_int32, c_float, c_void_p, c_void_p]
         L.wsvd_decode_step.argtypes = [c_void_p, POINTER(LayerDesc)] + [c_void_p] * 8 + [POINTER(Cache), c_int32, c_void_p, c_void_p]
@@ -208,6 +209,11 @@ def wsvd_latent_store(ctx, desc, c_K, c_V, ld, cache, stream=None):
 def wsvd_decode_attn(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
     _ck(lib().wsvd_decode_attn(ctx, byref(desc), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V), byref(cache),
                                int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn")
+
+
+def wsvd_decode_attn_static(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
+    _ck(lib().wsvd_decode_attn_static(ctx, byref(desc), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V), byref(cache),
+                                      int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn_static")
 
 
 def wsvd_decode_attn_rope(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, rope_base, out, stream=None):

@@ -1,5 +1,6 @@
 // C ABI of the library: argument validation on the host, then kernel launches on the caller's stream.
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "wsvd_attn_common.h"
@@ -11,6 +12,41 @@ int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G);
 int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G);
 
 extern int g_append_mode;
+
+// ---------------------------------------------------------------- static scratch of wsvd_decode_attn_static
+// Device memory that belongs to the library image: one copy per GPU the library runs on, held until the process ends.
+// Laid out like a caller's workspace (tickets first, then the split partials).  Host code never uses the array's name
+// as an address: g_scratch_dev[device] holds what hipGetSymbolAddress returned with that device current.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_dev[kMaxDevices];          // per device; written once under g_scratch_mutex
+static std::mutex g_scratch_mutex;
+
+__global__ void k_fill_zero_i32(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// Address of this device's copy of the array (the device must be current); looked up and its ticket region cleared
+// the first time a context is created on the device.
+static hipError_t static_scratch_for_device(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_dev[device]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    e = hipMemset(ptr, 0, (size_t)kWsCounterInts * 4);
+    if (e != hipSuccess) return e;
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) return e;
+    g_scratch_dev[device] = ptr;
+  }
+  *out = g_scratch_dev[device];
+  return hipSuccess;
+}
 
 namespace {
 
@@ -117,6 +153,7 @@ wsvd_status wsvd_create(wsvd_ctx** out, int device_ordinal) {
   c->epoch = 0;
   if (hipMalloc((void**)&c->err_word, 4) != hipSuccess) { delete c; return WSVD_E_HIP; }
   if (hipMemset(c->err_word, 0, 4) != hipSuccess) { (void)hipFree(c->err_word); delete c; return WSVD_E_HIP; }
+  if (static_scratch_for_device(device_ordinal, &c->static_scratch) != hipSuccess) { (void)hipFree(c->err_word); delete c; return WSVD_E_HIP; }
   *out = c;
   return WSVD_OK;
 }
@@ -338,6 +375,38 @@ wsvd_status wsvd_decode_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
   hipError_t e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_decode_attn_static(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
+                                    const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len, void* out,
+                                    void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 0) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  // tickets + split partials of this layer must fit the static array
+  const size_t need = (size_t)kWsCounterInts * 4 + wsvd_attn_partial_floats(*desc) * 4;
+  if (need > kStaticScratchBytes) return WSVD_E_WORKSPACE;
+  if (!ctx->static_scratch) return WSVD_E_HIP;
+  hipStream_t s = (hipStream_t)hip_stream;
+  // the same launch as wsvd_decode_attn, with the array in the caller's workspace's place (a copy of the context on
+  // the stack: the caller's own workspace setting is left alone)
+  wsvd_ctx view = *ctx;
+  view.ws = ctx->static_scratch;
+  view.ws_bytes = kStaticScratchBytes;
+  // Tickets must start at zero.  They reset themselves at the end of every launch that uses them, but the array
+  // outlives every call (also one that was cut short), so they are cleared on the stream first: a fill kernel, not a
+  // memset node, so that the call can be captured into a graph.
+  const int n_tickets = desc->batch * desc->n_kv_heads;
+  hipLaunchKernelGGL(k_fill_zero_i32, dim3((n_tickets + 255) / 256), dim3(256), 0, s, (int*)view.ws, n_tickets);
+  if (hipGetLastError() != hipSuccess) return WSVD_E_HIP;
+  hipError_t e = wsvd_launch_attn(&view, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, s);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }

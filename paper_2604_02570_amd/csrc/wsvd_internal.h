@@ -12,6 +12,7 @@ struct wsvd_ctx {
   void* ws;          // caller-owned workspace
   size_t ws_bytes;
   int epoch;         // number of fused decode steps launched so far (value the append workgroups publish)
+  void* static_scratch;   // this device's copy of the library's static scratch array (wsvd_decode_attn_static)
 };
 
 struct AttnParams;
