@@ -27,6 +27,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy of known size.
 MEASURED_TRAFFIC_BYTES = 72_360_000   # 72.10 MB fetched + 0.26 MB written (profiles/attn_mfma_int8_c3_hbm_traffic.md)
+MEASURED_TRAFFIC_APPEND = None          # filled in from profiles/append_mfma_c3_hbm_traffic.md once measured
 MEASURED_TRAFFIC_BYTES_C5 = 141_840_000   # 140.8 MB fetched + 1.03 MB written (profiles/attn_gqa_int8_c5_hbm_traffic.md)
 # prefill and shared-latent kernels (profiles/prefill_int8_c3_kernel_trace.md, profiles/attn_shared_int8_r1024_kernel_trace.md)
 MEASURED_TRAFFIC_PREFILL_ATTN = 894_500_000    # 357.6 MB fetched + 536.9 MB written (the fp32 outputs)
@@ -40,6 +41,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=320)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--sets", type=int, default=16, help="distinct cache sets rotated through (cold HBM)")
+    ap.add_argument("--repeats", type=int, default=5, help="timed repeats of every measurement (median, min, max reported)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
@@ -61,6 +63,9 @@ def parse():
                     help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
     ap.add_argument("--project-shape", type=int, default=0, choices=[0, 1, 2, 21, 24, 42, 44],
                     help="prefill: channel tiles x token tiles per wavefront of the tiled projection (tuning; 0 = the library's choice)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="c3 attention only, through the profiling build of the library (libwsvd_timeline.so): prints when, "
+                         "relative to the first wavefront's start, the wavefronts of a launch pass the kernel's marked points")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference rows for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -78,6 +83,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.timeline:
+        return run_timeline(args, np, torch, W, WI)
     W.lib()   # fails loudly if the HIP library is missing
     if args.single_launch:
         W.wsvd_set_option("fused_step", 2)
@@ -98,8 +105,10 @@ def main():
     i4 = sp.latent_dtype == "i4"
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
     n_sets = max(1, args.sets if args.workload == "c3" else min(args.sets, 4))    # a c4 set is 340 MB
+    R = max(1, args.repeats)
     total_steps = args.warmup + args.steps
-    visits = (total_steps + n_sets - 1) // n_sets
+    # every repeat replays the same graph of args.steps steps, each of which appends a row: room for all of them
+    visits = (args.warmup + args.steps * (R + 1) + n_sets - 1) // n_sets + 8
     t_cap = (T + visits + 63) // 64 * 64
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, sp.latent_dtype, "bf16", "bf16", "i8", "f32", 0.0)
     ctx = W.wsvd_create(0)
@@ -125,17 +134,21 @@ def main():
     qsd = torch.empty(B, dtype=torch.int16, device="cuda")
     W.wsvd_quantize_act_i8(ctx, q32d, "f32", B, Hq * d, qd, qsd)
 
-    # ---- context latents -> the library's own quantiser -> device layout (set 0), then cloned into the other sets
+    # ---- context latents -> the library's own quantiser -> device layout (set 0), then copied into the other sets
     # The timed step appends one token, so attention runs over the workload's lengths on the first visit.  Every
     # sequence's plane is filled up to the longest length (rows past a sequence's own length are never read).
     lens0 = WI.ragged_lengths(sp).astype(np.int64) - 1
     T0 = int(lens0.max())
-    # a cache set is ONE allocation (K codes, V codes, K metadata, V metadata), so that the streaming-read probe
-    # can run over exactly the bytes the attention streams
-    def carve(buf):
-        return buf[:cb], buf[cb:2 * cb], buf[2 * cb:2 * cb + mb], buf[2 * cb + mb:]
-    buf0 = torch.zeros(2 * cb + 2 * mb, dtype=torch.uint8, device="cuda")
-    k0, v0, km0, vm0 = carve(buf0)
+    # All cache sets live in ONE allocation, as a serving system's cache pool does (one mapping, large pages); a set
+    # is one contiguous slice (K codes, V codes, K metadata, V metadata), so that the streaming-read probe can run
+    # over exactly the bytes the attention streams.
+    set_bytes = 2 * cb + 2 * mb
+    set_stride = (set_bytes + 4095) // 4096 * 4096
+    pool = torch.zeros(n_sets * set_stride, dtype=torch.uint8, device="cuda")
+    def carve(i):
+        buf = pool[i * set_stride: i * set_stride + set_bytes]
+        return buf[:cb], buf[cb:2 * cb], buf[2 * cb:2 * cb + mb], buf[2 * cb + mb:], buf
+    k0, v0, km0, vm0, buf0 = carve(0)
     sl0 = torch.from_numpy(lens0.astype(np.int32)).cuda()
     cache0 = W.make_cache(k0, v0, km0, vm0, sl0)
     for which, A, plane in (("k", AK, 0), ("v", AV, 1)):
@@ -149,10 +162,11 @@ def main():
         del codes, meta
     assert W.wsvd_check(ctx) == 0
     sets = [(k0, v0, km0, vm0, sl0, cache0, buf0)]
-    for _ in range(n_sets - 1):
-        b = buf0.clone(); sl = sl0.clone()
-        t = [*carve(b), sl]
-        sets.append((*t, W.make_cache(*t), b))
+    for i in range(1, n_sets):
+        t = carve(i)
+        t[4].copy_(buf0)
+        sl = sl0.clone()
+        sets.append((t[0], t[1], t[2], t[3], sl, W.make_cache(t[0], t[1], t[2], t[3], sl), t[4]))
     outs = [torch.empty((B, Hq, d), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
     torch.cuda.synchronize()
 
@@ -174,93 +188,94 @@ def main():
             W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, s[5])
             attend(s[5], outs[i % n_sets])
 
-    def attn_only(i):
-        s = sets[i % n_sets]
-        attend(s[5], outs[i % n_sets])
-
-    # rows attended (summed over the batch) at timed step i: initial lengths + the appends that set has seen so far
-    def rows_at(i):
-        return int(lens0.sum()) + B * (0 if args.attn_only else i // n_sets + 1)
-
     stream = torch.cuda.Stream()
     use_graph = not args.no_graph
+
+    def timed(fn, n, repeats, before=None):
+        """n calls of fn(i) back to back on the launch stream (replayed from one HIP graph, or eagerly), timed by HIP
+        events on that stream, `repeats` times; `before` runs untimed in front of every repeat.  Returns the per-call
+        microseconds of every repeat."""
+        g = None
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(n):
+                    fn(i)
+            stream.synchronize()
+        res = []
+        for _ in range(repeats):
+            if before is not None:
+                before()
+            stream.synchronize()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            if g is not None:
+                g.replay()
+            else:
+                for i in range(n):
+                    fn(i)
+            e1.record(stream)
+            stream.synchronize()
+            res.append(e0.elapsed_time(e1) * 1e3 / n)
+        return res
+
+    def stats(v):
+        return {"median": round(float(np.median(v)), 3), "min": round(float(min(v)), 3), "max": round(float(max(v)), 3), "repeats": len(v)}
+
+    row_bytes = Hkv * 2 * ((r // 2 + 4) if i4 else (r + 2))   # K and V code rows plus metadata, all kv heads
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
             step(i)
         stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        if use_graph:
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                for i in range(args.warmup, total_steps):
-                    step(i)
-            stream.synchronize()
-            torch.cuda.synchronize()
-            t_wall0 = time.perf_counter()
-            e0.record(stream)
-            g.replay()
-            e1.record(stream)
-            stream.synchronize()
-            torch.cuda.synchronize()
-            t_wall1 = time.perf_counter()
-        else:
-            torch.cuda.synchronize()
-            t_wall0 = time.perf_counter()
-            e0.record(stream)
-            for i in range(args.warmup, total_steps):
-                step(i)
-            e1.record(stream)
-            stream.synchronize()
-            torch.cuda.synchronize()
-            t_wall1 = time.perf_counter()
-        ms_total = e0.elapsed_time(e1)
+        assert W.wsvd_check(ctx, stream) == 0
+        # ---- the headline: EXACTLY args.steps steps, timed between synchronisations; then R - 1 more repeats of the
+        # same graph (the caches keep growing by one row per visit), median reported beside the first
+        lens_before = [int(s[4].sum()) for s in sets]
+        t_wall0 = time.perf_counter()
+        step_us = timed(lambda i: step(args.warmup + i), args.steps, R)
+        t_wall1 = time.perf_counter()
         assert W.wsvd_check(ctx, stream) == 0
         seq_after = [int(s[4].max()) for s in sets]
+        lens_after = [int(s[4].sum()) for s in sets]
+        # rows attended (summed over the batch) by each step of the FIRST timed replay: the set's length when the
+        # replay started plus the appends it has seen since
+        seen = [0] * n_sets
+        rows_first = 0
+        for j in range(args.steps):
+            si = (args.warmup + j) % n_sets
+            if not args.attn_only:
+                seen[si] += 1
+            rows_first += lens_before[si] + B * seen[si]
+        rows_mean = rows_first / args.steps
 
-        # ---- dominant kernel alone: decode attention, back-to-back launches, HIP events on the launch stream
+        # ---- dominant kernel alone: decode attention, back-to-back launches over the rotating sets (cold HBM)
         n_attn = max(args.steps, 64)
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for i in range(n_sets):
-            attn_only(i)
+            attend(sets[i][5], outs[i])
         stream.synchronize()
-        if use_graph:
-            ga = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(ga, stream=stream):
-                for i in range(n_attn):
-                    attn_only(i)
-            stream.synchronize()
-            a0.record(stream); ga.replay(); a1.record(stream)
-        else:
-            a0.record(stream)
-            for i in range(n_attn):
-                attn_only(i)
-            a1.record(stream)
-        stream.synchronize()
-        attn_us = a0.elapsed_time(a1) * 1e3 / n_attn
+        attn_all = timed(lambda i: attend(sets[i % n_sets][5], outs[i % n_sets]), n_attn, R)
         assert W.wsvd_check(ctx, stream) == 0
-
-        # ---- the same launches replaced by a pure reader over the same cache sets (whole allocations, i.e. the
-        # t_cap slack included: a few per cent more bytes than the attention needs)
+        # the same on ONE set over and over: that set (72 MB) stays in the 256 MB last-level cache ("warm")
+        warm_all = timed(lambda i: attend(sets[0][5], outs[0]), n_attn, R)
+        # ---- the append alone (its own lengths restored in front of every repeat)
+        snap = [s[4].clone() for s in sets]
+        def restore():
+            for s, c in zip(sets, snap):
+                s[4].copy_(c)
+        n_app = 4 * n_sets
+        app_all = [] if args.attn_only else timed(lambda i: W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, sets[i % n_sets][5]),
+                                                  n_app, R, before=restore)
+        restore()
+        assert W.wsvd_check(ctx, stream) == 0
+        # ---- the same launches replaced by a pure reader over the same cache sets (whole slices, i.e. the t_cap slack
+        # included: a few per cent more bytes than the attention needs)
         def probe(i):
-            W.wsvd_probe_stream_read(ctx, sets[i % n_sets][6], 2 * cb + 2 * mb, 2 * B * Hkv)
+            W.wsvd_probe_stream_read(ctx, sets[i % n_sets][6], set_bytes, 2 * B * Hkv)
         for i in range(n_sets):
             probe(i)
         stream.synchronize()
-        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        if use_graph:
-            gp = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gp, stream=stream):
-                for i in range(n_attn):
-                    probe(i)
-            stream.synchronize()
-            p0.record(stream); gp.replay(); p1.record(stream)
-        else:
-            p0.record(stream)
-            for i in range(n_attn):
-                probe(i)
-            p1.record(stream)
-        stream.synchronize()
-        probe_us = p0.elapsed_time(p1) * 1e3 / n_attn
+        probe_all = timed(probe, n_attn, R)
 
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -269,15 +284,15 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    # K and V code rows plus their metadata (int8: fp16 scale; int4: fp16 scale + zero point), all kv heads
-    row_bytes = Hkv * 2 * ((r // 2 + 4) if i4 else (r + 2))
-    bytes_steps = sum(rows_at(i) * row_bytes for i in range(args.warmup, total_steps))
-    bytes_per_step = bytes_steps / args.steps
-    ms_per_step = ms_total / args.steps
+    bytes_per_step = rows_mean * row_bytes
+    ms_per_step = step_us[0] * 1e-3                 # the K steps the contract asks for: the first timed replay
     value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
     rows_attn = [int(s[4].sum()) for s in sets]
     attn_bytes = sum(rows_attn[i % n_sets] * row_bytes for i in range(n_attn)) / n_attn
+    attn_us = float(np.median(attn_all))
+    probe_us = float(np.median(probe_all))
     achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    factor_bytes = 2 * Hkv * E * r * 2              # A_K and A_V, bf16: what one append must read
 
     res = {
         "metric": "latent_kv_hbm_GBps_per_decode_step",
@@ -288,6 +303,7 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 6),
         "us_per_decode_step": round(ms_per_step * 1e3, 3),
+        "us_per_decode_step_repeats": stats(step_us),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "higher_is_better": True,
         "scaling": "weak",
@@ -301,11 +317,14 @@ def main():
             "batch": B, "heads": Hq, "d_head": d, "d_model": E, "rank": r, "context": T,
             "context_drift_rows": max(seq_after) - int(lens0.max()) - 1,
             "rows_in_batch": int(lens0.sum()) + B,
-            "cache_sets_rotated": n_sets, "cache_set_MB": round(2 * (cb + mb) / 1e6, 1),
+            "cache_sets_rotated": n_sets, "cache_set_MB": round(set_bytes / 1e6, 1), "cache_pool": "one allocation",
             "launch": "hip_graph_replay" if use_graph else "eager",
             "step": "attention only" if args.attn_only else ("wsvd_decode_step (single-launch kernel)" if args.single_launch
                                                               else "wsvd_latent_append + wsvd_decode_attn"),
-            "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / args.steps, 6),
+            "timing": f"ms_per_step = the first timed replay of {args.steps} steps; us_per_decode_step_repeats = {R} replays",
+            "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / (args.steps * R), 6),
+            "attention_alone_us": stats(attn_all), "attention_alone_warm_single_set_us": stats(warm_all),
+            "append_alone_us": stats(app_all) if app_all else None,
         },
         "roofline": {
             "kernel": "k_attn_mfma<32,1,%s> (decode attention over %s latents)" % ("true", "int4") if i4 else
@@ -316,14 +335,27 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": None if i4 else MEASURED_TRAFFIC_BYTES,
+            "traffic_source": None if i4 else "rocprofv3 --pmc run recorded in profiles/attn_mfma_int8_c3_hbm_traffic.md (not measured in this run)",
             "algorithmic_bytes_per_launch": int(attn_bytes),
             "avg_launch_us": round(attn_us, 3),
+            "avg_launch_us_min_max": [round(min(attn_all), 3), round(max(attn_all), 3)],
+            "warm_single_set_us": round(float(np.median(warm_all)), 3),
             # context, not a peak: a kernel that only reads the same cache sets (t_cap slack included), same launch style
-            "stream_read_probe": {"bytes_per_launch": 2 * (cb + mb), "avg_launch_us": round(probe_us, 3),
-                                  "GBps": round(2 * (cb + mb) / (probe_us * 1e-6) / 1e9, 1),
+            "stream_read_probe": {"bytes_per_launch": set_bytes, "avg_launch_us": round(probe_us, 3),
+                                  "GBps": round(set_bytes / (probe_us * 1e-6) / 1e9, 1),
                                   "attention_time_over_probe_time": round(attn_us / probe_us, 3)},
         },
     }
+    if app_all:
+        app_us = float(np.median(app_all))
+        res["roofline_append"] = {
+            "kernel": "k_append_mfma (projection of the new token on the packed factors, quantise, store)",
+            "bound": "hbm", "achieved": round(factor_bytes / (app_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(factor_bytes / (app_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_APPEND if not i4 else None,
+            "traffic_source": "profiles/append_mfma_c3_hbm_traffic.md (not measured in this run)" if not i4 else None,
+            "algorithmic_bytes_per_launch": factor_bytes, "avg_launch_us": round(app_us, 3),
+            "note": "factor stream A_K + A_V (bf16); the same factors for every launch, so they come from the last-level cache "
+                    "after the first one: a latency chain, not a bandwidth-bound stream"}
 
     if args.rope:
         # The rotary variant is bound by vector arithmetic, not by the stream.  Per cached row the method needs, for
@@ -871,16 +903,100 @@ def run_shared(args, np, torch, W, WI):
     W.wsvd_destroy(ctx)
 
 
+def run_timeline(args, np, torch, W, WI):
+    """In-kernel timeline of the decode attention at the c3 shape.  Needs the profiling build of the library
+    (python -m paper_2604_02570_amd.build --timeline).  Launches rotate over 16 cache sets (cold HBM) and are made
+    eagerly, back to back on one stream; the last four launches record stamps, each into its own buffer, so that the
+    idle time between one launch's last wavefront and the next launch's first is visible too.  The cache holds
+    random codes with a constant scale: the kernel's timing does not depend on the values."""
+    from paper_2604_02570_amd import build as WB
+    if not os.path.exists(WB.LIB_TIMELINE):
+        WB.build(verbose=False, timeline=True)
+    W.use_library(WB.LIB_TIMELINE)
+    sp = WI.spec("c3")
+    B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
+    t_cap = (T + 63) // 64 * 64
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "i8", "f32", 0.0)
+    ctx = W.wsvd_create(0)
+    ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(ctx, ws)
+    cb, mb = W.wsvd_cache_bytes(desc)
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    n_sets = args.sets
+    sl = torch.full((B,), T, dtype=torch.int32, device="cuda")
+    caches = []
+    for _ in range(n_sets):
+        k = torch.randint(-127, 128, (cb,), dtype=torch.int8, device="cuda", generator=g)
+        v = torch.randint(-127, 128, (cb,), dtype=torch.int8, device="cuda", generator=g)
+        km = torch.full((mb // 2,), 0x2000, dtype=torch.int16, device="cuda")       # fp16 2^-7
+        vm = torch.full((mb // 2,), 0x2000, dtype=torch.int16, device="cuda")
+        caches.append(W.make_cache(k, v, km, vm, sl))
+    qd = torch.randint(-127, 128, (B, Hq, d), dtype=torch.int8, device="cuda", generator=g)
+    qsd = torch.full((B + (B & 1),), 0x2000, dtype=torch.int16, device="cuda")
+    BKd = (torch.randn((Hkv, r, d), device="cuda", generator=g) * r ** -0.5).to(torch.bfloat16)
+    BVd = (torch.randn((Hkv, r, d), device="cuda", generator=g) * r ** -0.5).to(torch.bfloat16)
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
+    n_keep, n_launch, max_wg = 4, 48, 8192
+    tl = [torch.zeros(max_wg * 256, dtype=torch.int64, device="cuda") for _ in range(n_keep)]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(n_launch):
+            keep = i - (n_launch - n_keep)
+            if i == n_launch - n_keep:
+                e0.record(stream)
+            W.wsvd_timeline_set_buffer(ctx, tl[keep] if keep >= 0 else None)
+            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, caches[i % n_sets], T, out)
+        e1.record(stream)
+        stream.synchronize()
+        assert W.wsvd_check(ctx, stream) == 0
+    us_launch = e0.elapsed_time(e1) * 1e3 / n_keep
+    names = ["kernel entry", "first loads issued", "factors staged", "query limbs ready", "first tile consumed",
+             "last tile consumed", "wave's partial written", "workgroup barrier passed", "output stored"]
+    lines = []
+    prev_end = None
+    summary = []
+    for k in range(n_keep):
+        a = tl[k].cpu().numpy().reshape(max_wg, 16, 16)
+        live = a[:, :, 0] > 0
+        n_wg = int(live.any(axis=1).sum()); n_wave = int(live.sum())
+        t0 = int(a[:, :, 0][live].min())
+        end = int(a[live].max())
+        lines.append(f"launch {k}: {n_wg} workgroups, {n_wave} wavefronts; last stamp {(end - t0) * 0.01:.2f} us after the first"
+                     + (f"; idle since the previous launch's last stamp {(t0 - prev_end) * 0.01:.2f} us" if prev_end else ""))
+        prev_end = end
+        rows = {}
+        for slot, nm in enumerate(names):
+            v = a[:, :, slot][live]
+            v = v[v > 0]
+            if v.size == 0:
+                continue
+            rel = (v - t0) * 0.01
+            rows[nm] = dict(n=int(v.size), min=float(rel.min()), p50=float(np.percentile(rel, 50)),
+                            p90=float(np.percentile(rel, 90)), max=float(rel.max()))
+            lines.append(f"  {slot} {nm:26s} n={v.size:5d}  min {rel.min():6.2f}  p50 {np.percentile(rel, 50):6.2f}  "
+                         f"p90 {np.percentile(rel, 90):6.2f}  max {rel.max():6.2f} us")
+        summary.append(rows)
+    print("\n".join(lines))
+    print(json.dumps({"timeline": "k_attn_mfma at c3 (B=16 H=32 r=32 T=2048, int8), eager back-to-back launches, "
+                                  "stamps = 100 MHz wall clock, us relative to the launch's first wavefront",
+                      "avg_launch_us_with_stamps": round(us_launch, 3), "launches": summary}))
+    W.wsvd_destroy(ctx)
+
+
 def cpu_baseline(np, row_bytes):
     """The fp64 oracle, as it stands, on the same workload: one decode step (append + attention) on the host cores."""
     import oracle as O
     from cases import build_case
     import wsvd_inputs as WI
+    # the oracle's loop over (sequence, head) pairs is plain single-threaded Python; only the matrix products inside
+    # it run on the BLAS thread pool
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        cores = 1
+        blas_threads = 1
+    cores = os.cpu_count() or 1
     c = build_case("c3")
     sp = c.sp
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
@@ -899,7 +1015,9 @@ def cpu_baseline(np, row_bytes):
             break
     per_step = dt / reps
     nbytes = sp.batch * sp.context * row_bytes
-    return {"value": round(nbytes / per_step / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+    return {"value": round(nbytes / per_step / 1e9, 4), "unit": "GB/s", "cores": int(cores), "threads_used": int(blas_threads),
+            "threads_note": "one Python thread walks the (sequence, head) pairs; the matrix products inside use the BLAS pool",
+            "kind": "oracle",
             "sample": f"the whole c3 step (append + attention over all {sp.batch * sp.n_q_heads} sequence-heads), "
                       f"{reps} repetitions, {per_step * 1e3:.1f} ms per step",
             "us_per_decode_step": round(per_step * 1e6, 1)}

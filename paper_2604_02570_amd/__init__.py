@@ -28,7 +28,7 @@ EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_by
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
-           "wsvd_prefill_attn", "wsvd_shared_workspace_bytes", "wsvd_decode_attn_shared"]
+           "wsvd_prefill_attn", "wsvd_shared_workspace_bytes", "wsvd_decode_attn_shared", "wsvd_timeline_set_buffer"]
 
 
 class WsvdError(RuntimeError):
@@ -50,6 +50,17 @@ class Cache(ctypes.Structure):
 
 
 _lib = None
+
+
+def use_library(path: str):
+    """Load another build of the library (the profiling build libwsvd_timeline.so) instead of libwsvd.so.  Must be
+    called before the first call into the library."""
+    global LIB_PATH
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    if not os.path.exists(path):
+        raise FileNotFoundError(path)
+    LIB_PATH = path
 
 
 def lib():
@@ -94,6 +105,7 @@ def lib():
                                        c_void_p, c_int32, c_void_p]
         L.wsvd_linear_w4a8_split.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
                                              c_int64, c_void_p, c_void_p, c_int32, c_void_p]
+        L.wsvd_timeline_set_buffer.argtypes = [c_void_p, c_void_p, c_size_t]
         L.wsvd_probe_stream_read.argtypes = [c_void_p, c_void_p, c_size_t, c_int32, c_void_p]
         L.wsvd_prefill_append.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p,
                                           POINTER(Cache), c_void_p]
@@ -314,3 +326,9 @@ def wsvd_linear_w4a8_split(ctx, x, x_scale, w_i4, w_scale, M, K, N, n_first, out
 
 def wsvd_probe_stream_read(ctx, buf, nbytes, workgroups, stream=None):
     _ck(lib().wsvd_probe_stream_read(ctx, _ptr(buf), int(nbytes), int(workgroups), _stream(stream)), "wsvd_probe_stream_read")
+
+
+def wsvd_timeline_set_buffer(ctx, buf):
+    """Profiling build only (include/wsvd_test.h); buf = int64 device tensor or None."""
+    n = 0 if buf is None else buf.numel() * buf.element_size()
+    _ck(lib().wsvd_timeline_set_buffer(ctx, _ptr(buf), n), "wsvd_timeline_set_buffer")

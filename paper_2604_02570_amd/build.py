@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwsvd.so")
+LIB_TIMELINE = os.path.join(HERE, "libwsvd_timeline.so")     # profiling build: in-kernel wall-clock stamps compiled in
 SOURCES = ["wsvd_api.hip", "wsvd_quant.hip", "wsvd_append.hip", "wsvd_attn_generic.hip", "wsvd_attn_mfma.hip",
            "wsvd_block.hip", "wsvd_layer.hip", "wsvd_prefill.hip", "wsvd_project.hip", "wsvd_shared.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -17,9 +18,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-tar
 FILE_FLAGS = {"wsvd_prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def build(verbose: bool = True, extra_flags=(), timeline: bool = False) -> str:
+    """Compile every source for gfx950 and link libwsvd.so; timeline=True builds the profiling variant
+    libwsvd_timeline.so (-DWSVD_TIMELINE) beside it instead."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build", "timeline" if timeline else "product")
+    lib_path = LIB_TIMELINE if timeline else LIB
+    if timeline:
+        extra_flags = (*extra_flags, "-DWSVD_TIMELINE")
     os.makedirs(objdir, exist_ok=True)
     procs = []
     for src in SOURCES:
@@ -35,14 +41,16 @@ def build(verbose: bool = True, extra_flags=()) -> str:
         if verbose and out.strip():
             print(out)
         objs.append(obj)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib_path]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}")
     if verbose:
-        print(f"built {LIB}")
-    return LIB
+        print(f"built {lib_path}")
+    return lib_path
 
 
 if __name__ == "__main__":
-    build(extra_flags=sys.argv[1:])
+    argv = sys.argv[1:]
+    tl = "--timeline" in argv
+    build(extra_flags=[a for a in argv if a != "--timeline"], timeline=tl)

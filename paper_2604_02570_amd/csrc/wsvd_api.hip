@@ -151,6 +151,8 @@ wsvd_status wsvd_create(wsvd_ctx** out, int device_ordinal) {
   c->ws = nullptr;
   c->ws_bytes = 0;
   c->epoch = 0;
+  c->timeline = nullptr;
+  c->timeline_bytes = 0;
   if (hipMalloc((void**)&c->err_word, 4) != hipSuccess) { delete c; return WSVD_E_HIP; }
   if (hipMemset(c->err_word, 0, 4) != hipSuccess) { (void)hipFree(c->err_word); delete c; return WSVD_E_HIP; }
   if (static_scratch_for_device(device_ordinal, &c->static_scratch) != hipSuccess) { (void)hipFree(c->err_word); delete c; return WSVD_E_HIP; }
@@ -580,6 +582,19 @@ wsvd_status wsvd_swiglu_quant_i8(wsvd_ctx* ctx, const void* gate_up, int64_t row
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_timeline_set_buffer(wsvd_ctx* ctx, void* dev_ptr, size_t bytes) {
+  if (!ctx) return WSVD_E_NULL;
+#ifdef WSVD_TIMELINE
+  if (dev_ptr && !aligned16(dev_ptr)) return WSVD_E_ALIGN;
+  ctx->timeline = (long long*)dev_ptr;
+  ctx->timeline_bytes = dev_ptr ? bytes : 0;
+  return WSVD_OK;
+#else
+  (void)dev_ptr; (void)bytes;
+  return WSVD_E_UNSUPPORTED;      // the product build carries no stamps
+#endif
+}
+
 wsvd_status wsvd_probe_stream_read(wsvd_ctx* ctx, const void* ptr, size_t bytes, int32_t workgroups, void* hip_stream) {
   if (!ctx || !ptr) return WSVD_E_NULL;
   if (!aligned16(ptr)) return WSVD_E_ALIGN;
@@ -676,6 +691,8 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
   grid = dim3((unsigned)d.n_kv_heads, (unsigned)p.n_chunks, (unsigned)d.batch);
   threads = nw * 64;
+  const size_t tl_need = (size_t)grid.x * grid.y * grid.z * kTimelineWaves * kTimelineSlots * sizeof(long long);
+  p.timeline = (ctx->timeline && ctx->timeline_bytes >= tl_need) ? ctx->timeline : nullptr;
 }
 
 hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,

@@ -34,6 +34,7 @@ struct AttnParams {
   // several query tokens per sequence (prefill / multi-token decode) only: G = nq * Gr query slots per kv head, slot
   // s = token s / Gr, head s % Gr; token i sits at row seq_lens - n_after - nq + i and sees the rows up to its own
   int nq, Gr, n_after;
+  long long* timeline;       // profiling build: stamp buffer (see WSVD_STAMP), else null
 };
 
 struct WorkItem {
@@ -185,9 +186,11 @@ WSVD_DEV void compute_qtilde(const AttnParams& p, const void* bk_lds, const floa
 // max (log2 domain), sum and un-normalised latent-space accumulator, visible to all threads.
 // If the sequence was split over several workgroups the partials go to the workspace and the last
 // workgroup to arrive (ticket) merges them in split order; then out = (u / l) B_V.
-template <int R, int ESZ>
-WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, float* Lsh, float* Ush, int* flag_sh,
-                        const void* bv_lds) {
+// First half of the tail: the cross-workgroup merge.  Returns false in the workgroups that only delivered a partial
+// (they are done); true in the one that now holds the whole sequence's (m, l, u) in Msh, Lsh, Ush, visible to all of
+// its threads.
+template <int R>
+WSVD_DEV bool attn_merge_splits(const AttnParams& p, const WorkItem& w, float* Msh, float* Lsh, float* Ush, int* flag_sh) {
   const int tid = threadIdx.x;
   const int G = p.G;
   if (w.n_splits > 1) {
@@ -208,7 +211,7 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       *flag_sh = last;
     }
     __syncthreads();
-    if (!*flag_sh) return;
+    if (!*flag_sh) return false;
     // The partials are read with cache-bypassing loads that cost a full memory round trip each, so they are
     // requested a batch of 8 splits at a time (24 independent loads in flight) and folded in split order.
     for (int i = tid; i < G * R; i += blockDim.x) {
@@ -243,6 +246,15 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
     }
     __syncthreads();
   }
+  return true;
+}
+
+template <int R, int ESZ>
+WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, float* Lsh, float* Ush, int* flag_sh,
+                        const void* bv_lds) {
+  const int tid = threadIdx.x;
+  const int G = p.G;
+  if (!attn_merge_splits<R>(p, w, Msh, Lsh, Ush, flag_sh)) return;
   if (!bv_lds) {
     // latent-output variant: the normalised accumulator itself (B_V lives in the output projection)
     for (int i = tid; i < G * R; i += blockDim.x)

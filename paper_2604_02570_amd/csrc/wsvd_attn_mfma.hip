@@ -16,6 +16,8 @@
 // Operand / result register layouts used here were checked on hardware:
 //   A: lane L holds row L%32, k = 16*(L/32)..+15;  B: lane L holds column L%32, same k;
 //   D: lane L, register v holds row 8*(v/4) + 4*(L/32) + v%4, column L%32.
+#include <type_traits>
+
 #include "wsvd_attn_common.h"
 #include "wsvd_append_body.h"
 #include "wsvd_internal.h"
@@ -28,31 +30,49 @@ struct TileRegs {
   uint32_t kmeta, vmeta;   // I8: fp16 scale in the low half; I4: scale | zero point << 16
 };
 
-// All offsets are 32-bit and relative to wave-uniform plane pointers, so the loads use the
-// scalar-base + vector-offset addressing form (one address instruction per tile).
+// A tile's loads come in two halves, in the order its data is needed: the key side (code blocks and metadata of
+// the keys: all the score pass needs) and the value side (metadata first: the weights need the scales before the value
+// pass needs the codes).  Loads return in issue order, so the score pass starts while the value side is still on
+// its way.
 template <int R, bool I4>
-WSVD_DEV void load_tile(TileRegs<R, I4>& t, const uint8_t* kplane, const uint8_t* vplane, const uint16_t* kmeta,
-                        const uint16_t* vmeta, int tile, int lane) {
+WSVD_DEV void load_tile_k(TileRegs<R, I4>& t, const uint8_t* kplane, const uint16_t* kmeta, int tile, int lane) {
+  const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
   if (I4) {
-    const uint32_t off = (uint32_t)tile * 1024u + (uint32_t)lane * 16u;
-    t.k[0][0] = __builtin_nontemporal_load((const v4i*)(kplane + off));
-    t.v[0][0] = __builtin_nontemporal_load((const v4i*)(vplane + off));
-    const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
+    t.k[0][0] = __builtin_nontemporal_load((const v4i*)(kplane + (uint32_t)tile * 1024u + (uint32_t)lane * 16u));
     t.kmeta = __builtin_nontemporal_load((const uint32_t*)kmeta + moff);
-    t.vmeta = __builtin_nontemporal_load((const uint32_t*)vmeta + moff);
   } else {
     const uint32_t off = (uint32_t)tile * (uint32_t)(64 * R) + (uint32_t)lane * 16u;
 #pragma unroll
     for (int blk = 0; blk < 2; blk++)
 #pragma unroll
-      for (int kk = 0; kk < R / 32; kk++) {
+      for (int kk = 0; kk < R / 32; kk++)
         t.k[kk][blk] = __builtin_nontemporal_load((const v4i*)(kplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
-        t.v[kk][blk] = __builtin_nontemporal_load((const v4i*)(vplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
-      }
-    const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
     t.kmeta = __builtin_nontemporal_load(kmeta + moff);
-    t.vmeta = __builtin_nontemporal_load(vmeta + moff);
   }
+}
+template <int R, bool I4>
+WSVD_DEV void load_tile_v(TileRegs<R, I4>& t, const uint8_t* vplane, const uint16_t* vmeta, int tile, int lane) {
+  const uint32_t moff = (uint32_t)tile * 64u + (uint32_t)lane;
+  if (I4) {
+    t.vmeta = __builtin_nontemporal_load((const uint32_t*)vmeta + moff);
+    t.v[0][0] = __builtin_nontemporal_load((const v4i*)(vplane + (uint32_t)tile * 1024u + (uint32_t)lane * 16u));
+  } else {
+    const uint32_t off = (uint32_t)tile * (uint32_t)(64 * R) + (uint32_t)lane * 16u;
+    t.vmeta = __builtin_nontemporal_load(vmeta + moff);
+#pragma unroll
+    for (int blk = 0; blk < 2; blk++)
+#pragma unroll
+      for (int kk = 0; kk < R / 32; kk++)
+        t.v[kk][blk] = __builtin_nontemporal_load((const v4i*)(vplane + off + (uint32_t)(blk * (32 * R) + kk * 1024)));
+  }
+}
+// All offsets are 32-bit and relative to wave-uniform plane pointers, so the loads use the
+// scalar-base + vector-offset addressing form (one address instruction per tile).
+template <int R, bool I4>
+WSVD_DEV void load_tile(TileRegs<R, I4>& t, const uint8_t* kplane, const uint8_t* vplane, const uint16_t* kmeta,
+                        const uint16_t* vmeta, int tile, int lane) {
+  load_tile_k<R, I4>(t, kplane, kmeta, tile, lane);
+  load_tile_v<R, I4>(t, vplane, vmeta, tile, lane);
 }
 
 // The same tile through agent-scope loads (dword granularity): coherent with write-through stores made by other
@@ -97,18 +117,28 @@ constexpr float kLimbFull = 1048576.f;    // 2^20: |quantised value| <= 2^20 fit
 constexpr int kMaxTilesPerFlush = 1024;   // 64 tokens * 127 * 127 per tile and limb: int32 holds > 2000 tiles
 
 // NT = launch bound (threads); the workgroup may be launched with any multiple of 64 threads up to NT.
-template <int R, int G, int NT>
-struct AttnMfmaShared {
-  static constexpr int NWMAX = NT / 64;
+// STAGED: the variants that build something from B_K in LDS (rotary) or fold partial sums there (latent query) keep
+// the staging areas; the plain kernel absorbs the query per wave on the matrix cores and needs none of them.
+template <int R, int G, bool STAGED>
+struct AttnStaging {
   v4i bk_lds[R * 128 * 2 / 16], bv_lds[R * 128 * 2 / 16];
   __attribute__((aligned(16))) float q_lds[G * 128];
   float qts[G * R];
-  __attribute__((aligned(16))) int8_t qlimb[G][3][R];       // limbs of q~ in operand k-order
-  float qdelta[G], qzsum[G];
+};
+template <int R, int G>
+struct AttnStaging<R, G, false> {
+  v4i bk_lds[1], bv_lds[1];
+  float q_lds[1], qts[1];
+};
+template <int R, int G, int NT, bool STAGED = true>
+struct AttnMfmaShared : AttnStaging<R, G, STAGED> {
+  static constexpr int NWMAX = NT / 64;
+  __attribute__((aligned(16))) int8_t qlimb[1][G][3][R];    // limbs of q~ in operand k-order
+  float qdelta[G], qzsum[G];                                // unit of the limbs, sum of the quantised query
   __attribute__((aligned(16))) uint8_t wl[NWMAX][G][3][64]; // per wave: limbs of the value weights, by token
-  float wm[NWMAX][G], wls[NWMAX][G];
-  __attribute__((aligned(16))) float wu[NWMAX][G][R];
-  float wo[NWMAX][G][128];                                  // per wave: its accumulator times B_V
+  __attribute__((aligned(16))) float wm[G][NWMAX], wls[G][NWMAX];   // per wave: running max (log2 domain), sum
+  float wu[NWMAX][G * R + 1];                               // per wave: un-normalised latent-space accumulator [g][j];
+                                                            // the odd row length keeps the merge's reads (lanes = waves) conflict-free
   float Msh[G], Lsh[G], Ush[G * R];
   int flag_sh;
 };
@@ -176,9 +206,10 @@ WSVD_DEV void split_fp16_pair(float x, float scale, _Float16& hi, _Float16& lo) 
 // done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
 // ROPE_D != 0: the rotary variant for head dimension ROPE_D (I8 latents; rs, ra non-null).
 template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0, bool LATENT = false>
-WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, const int cx, const int cy, const int cz,
-                             RopeShared<R, G, (ROPE_D ? ROPE_D : 64)>* rs = nullptr, const RopeArgs* ra = nullptr) {
+WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE_D != 0 || LATENT)>& sh, const int cx, const int cy,
+                             const int cz, RopeShared<R, G, (ROPE_D ? ROPE_D : 64)>* rs = nullptr, const RopeArgs* ra = nullptr) {
   constexpr bool ROPE = ROPE_D != 0;
+  constexpr bool STAGED = ROPE || LATENT;
   using RG = RopeGeom<(ROPE_D ? ROPE_D : 64)>;
   static_assert(!ROPE || (!I4 && !FUSED), "rotary variant: int8 latents, stand-alone launch");
   static_assert(!LATENT || (!ROPE && !FUSED), "latent-query variant: stand-alone launch, no rotation");
@@ -189,13 +220,17 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   constexpr int FIT = R / 16;           // 16-byte staging passes for an R x 128 bf16 factor
   auto& bk_lds = sh.bk_lds; auto& bv_lds = sh.bv_lds; auto& q_lds = sh.q_lds; auto& qts = sh.qts; auto& qlimb = sh.qlimb;
   auto& qdelta = sh.qdelta; auto& qzsum = sh.qzsum; auto& wl = sh.wl; auto& wm = sh.wm; auto& wls = sh.wls; auto& wu = sh.wu;
-  auto& wo = sh.wo; auto& Msh = sh.Msh; auto& Lsh = sh.Lsh; auto& Ush = sh.Ush; int& flag_sh = sh.flag_sh;
+  auto& Msh = sh.Msh; auto& Lsh = sh.Lsh; auto& Ush = sh.Ush; int& flag_sh = sh.flag_sh;
 
   // scalar loads first: issued ahead of the flood of vector loads they come back quickly, and nothing needs them
   // until the tile loop
   const int n_raw = p.seq_lens[cz];
   const uint32_t qs_raw = q_scale_raw(p, cz);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+  __builtin_amdgcn_s_setprio(3);          // streaming waves first (see the end of the tile loop)
+  [[maybe_unused]] long long* const tl = FUSED ? nullptr : p.timeline;
+  [[maybe_unused]] const int tl_wg = (cz * (int)gridDim.y + cy) * (int)gridDim.x + cx;
+  WSVD_STAMP(tl, tl_wg, wave, 0);
   const size_t ph = (size_t)cz * p.Hkv + cx;
   const size_t plane_bytes = (size_t)p.t_cap * (I4 ? R / 2 : R);
   const uint8_t* kplane = p.k_codes + ph * plane_bytes;
@@ -203,10 +238,155 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
   const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
 
-  // ---- loads, in the order they should come back: the small per-head inputs (B_K, B_V, queries) first, then
-  // DEPTH tiles per wave (a tile = 64 rows of K and V codes plus metadata), requested before the sequence length
-  // is known.  Every tile below t_cap is allocated memory, so the loads are safe; tiles past the sequence end are
-  // never consumed.  The prologue below then runs in the shadow of the first tiles' latency.
+  // ---- loads, in the order they should come back: the small per-head inputs first, then DEPTH tiles per wave (a
+  // tile = 64 rows of K and V codes plus metadata), requested before the sequence length is known.  Every tile below
+  // t_cap is allocated memory, so the loads are safe; tiles past the sequence end are never consumed.  The prologue
+  // below then runs in the shadow of the first tiles' latency.
+  constexpr int DEPTH = 2;   // deeper prefetch costs registers and measured slower
+  TileRegs<R, I4> buf[DEPTH];
+  const int chunk_tiles = p.chunk_rows >> 6;
+  int T = (int)cy * chunk_tiles + wave;
+  // unconditional (clamped to the chunk's last allocated tile): see stage_issue
+  const int spec_last = min(((int)cy + 1) * chunk_tiles, p.t_cap >> 6) - 1;
+  if constexpr (!STAGED) {
+    // Query absorption q~ = c_scale * B_K q on the matrix cores, by the workgroup's first wave alone, operands
+    // straight from memory (no staging in LDS): 8-16 KB of B_K and the queries are the only small loads of the
+    // workgroup, they sit at the head of that wave's queue, and a single barrier hands the limbs to the other waves,
+    // whose first tiles are in flight by then.  (Every wave absorbing for itself needs no barrier at all, but puts
+    // the whole factor through the CU's address pipeline once per wave, ahead of the tiles: measured slower.)
+    // D[i][j] = sum_k A[i][k] B[k][j] with V_MFMA_F32_32X32X16_BF16: column j = latent dim (B = B_K^T, a lane's 8
+    // operand elements are 16 contiguous bytes of row j of B_K), row i = 8 g + part: the contraction over the head
+    // dim is cut into d/16 parts of 16 (8 per half wave), row (g, part) carries q_g only in MFMA step `part` and
+    // zeros otherwise, so each lane needs just the 8 query elements of its own (g, part, half) and the parts add up
+    // afterwards: 4 accumulator registers plus one exchange between the half waves.
+    // Contraction order: step ks, half h, element e <-> head dim (d/2) h + 8 ks + e.
+    const int l32 = lane & 31, hf = lane >> 5;
+    const int nks = p.d >> 4;                                     // 8 (d = 128) or 4
+    const int qg = l32 >> 3, qpart = l32 & 7;                     // this lane's row: query slot, part
+    const bool qrow_on = qg < G && qpart < nks;
+    const bool leader = wave == 0;                                // wave-uniform
+    v4i bkr[KK][8];
+    v4i q_raw[2];
+    // the lane's 8 query elements: 8, 16 or 32 bytes inside one or two aligned 16-byte pieces
+    const int q_esz = p.q_dtype == WSVD_F32 ? 4 : p.q_dtype == WSVD_BF16 ? 2 : 1;
+    const size_t q_elem = ((size_t)cz * p.Hq + (size_t)cx * G + (qrow_on ? qg : 0)) * p.d + (p.d >> 1) * hf + 8 * (qrow_on ? qpart : 0);
+    const size_t q_off = q_elem * q_esz, q_o0 = q_off & ~(size_t)15;
+    const size_t q_bytes = (size_t)p.B * p.Hq * p.d * q_esz;
+    if (leader) {
+#pragma unroll
+    for (int jb = 0; jb < KK; jb++)
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        const int c = (p.d >> 1) * hf + 8 * min(ks, nks - 1);     // clamped
+        bkr[jb][ks] = *(const v4i*)((const char*)p.BK + (((size_t)cx * R + 32 * jb + l32) * p.d + c) * 2);
+      }
+    q_raw[0] = *(const v4i*)((const char*)p.q + q_o0);
+    q_raw[1] = *(const v4i*)((const char*)p.q + min(q_o0 + 16, q_bytes - 16));
+    }
+    // The barrier (no memory wait) puts the leader's small loads ahead of every wave's tile loads in the CU's address
+    // pipeline: the first two tiles of 16 waves are 190 KB of requests, more than a microsecond of that pipeline, and
+    // the absorption must not queue behind them.
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+    WSVD_STAMP(tl, tl_wg, wave, 1);
+
+    if (leader) {
+    float f[8];
+    if (p.q_dtype == WSVD_F32) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) { f[e] = __int_as_float(q_raw[0][e]); f[4 + e] = __int_as_float(q_raw[1][e]); }
+    } else if (p.q_dtype == WSVD_BF16) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        f[2 * e] = __uint_as_float((uint32_t)q_raw[0][e] << 16);
+        f[2 * e + 1] = __uint_as_float((uint32_t)q_raw[0][e] & 0xFFFF0000u);
+      }
+    } else {                                                      // int8: 8 bytes, the low or the high half of the piece
+      const bool hi = (q_off & 8) != 0;
+      const uint32_t d0 = (uint32_t)(hi ? q_raw[0][2] : q_raw[0][0]), d1 = (uint32_t)(hi ? q_raw[0][3] : q_raw[0][1]);
+#pragma unroll
+      for (int e = 0; e < 4; e++) { f[e] = (float)(int8_t)(d0 >> (8 * e)); f[4 + e] = (float)(int8_t)(d1 >> (8 * e)); }
+    }
+    if (!qrow_on) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) f[e] = 0.f;
+    }
+    // bf16 terms of the query chunk: one is exact for bf16 and int8 queries, an fp32 query takes three (hi + mid + lo
+    // reproduces it to 2^-24)
+    const int n_terms = p.q_dtype == WSVD_F32 ? 3 : 1;
+    v16f qacc[KK];
+#pragma unroll
+    for (int jb = 0; jb < KK; jb++)
+#pragma unroll
+      for (int x = 0; x < 16; x++) qacc[jb][x] = 0.f;
+    for (int t3 = 0; t3 < n_terms; t3++) {
+      v4i packed;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const uint32_t h0 = __float_as_uint(f[2 * e]) & 0xFFFF0000u, h1 = __float_as_uint(f[2 * e + 1]) & 0xFFFF0000u;
+        packed[e] = (int)((h0 >> 16) | h1);
+        f[2 * e] -= __uint_as_float(h0);                          // exact: the remainder has at most 16 significant bits
+        f[2 * e + 1] -= __uint_as_float(h1);
+      }
+      const v4i zero4 = {0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        if (ks < nks) {                                           // wave-uniform
+          const v8bf a_op = __builtin_bit_cast(v8bf, qpart == ks ? packed : zero4);
+#pragma unroll
+          for (int jb = 0; jb < KK; jb++)
+            qacc[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_op, __builtin_bit_cast(v8bf, bkr[jb][ks]), qacc[jb], 0, 0, 0);
+        }
+      }
+    }
+    // D row 8 g + part sits in register 4 g + part % 4 of half part / 4: add the four registers, then the two halves
+    // (after which lane L and lane L ^ 32 both hold q~[g][32 jb + L % 32])
+    float qt[G][KK];
+#pragma unroll
+    for (int g = 0; g < G; g++)
+#pragma unroll
+      for (int jb = 0; jb < KK; jb++) {
+        const float part = (qacc[jb][4 * g] + qacc[jb][4 * g + 1]) + (qacc[jb][4 * g + 2] + qacc[jb][4 * g + 3]);
+        qt[g][jb] = (part + __shfl_xor(part, 32)) * p.c_scale;
+      }
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+      float am = 0.f;
+#pragma unroll
+      for (int jb = 0; jb < KK; jb++) am = fmaxf(am, fabsf(qt[g][jb]));
+      const float amax = half_max(am, lane);                      // both halves hold all dims
+      const float inv = amax > 0.f ? kLimbFull / amax : 0.f;
+      float qsum = 0.f;
+#pragma unroll
+      for (int jb = 0; jb < KK; jb++) {
+        const int Q = (int)__builtin_rintf(qt[g][jb] * inv);
+        const int l0 = ((Q + 64) & 127) - 64;                     // balanced digits, each in [-64, 64]
+        const int Q1 = (Q - l0) >> 7;
+        const int l1 = ((Q1 + 64) & 127) - 64;
+        const int l2 = (Q1 - l1) >> 7;
+        qsum += (float)Q;
+        // position of dim j in the operand k-order.  I8: identity.  I4: a lane's 8 bytes hold dims 16g..16g+15 as
+        // nibble pairs; masking gives operand dwords [even dims 0..6, odd 1..7, even 8..14, odd 9..15].
+        const int j = 32 * jb + l32;
+        int pos = j;
+        if (I4) {
+          const int jj = j & 15;
+          pos = (j & 16) + ((jj >> 3) << 3) + ((jj & 1) << 2) + ((jj & 7) >> 1);
+        }
+        if (hf == 0) {
+          qlimb[0][g][0][pos] = (int8_t)l2;
+          qlimb[0][g][1][pos] = (int8_t)l1;
+          qlimb[0][g][2][pos] = (int8_t)l0;
+        }
+      }
+      const float zs = I4 ? half_sum(qsum, lane) : 0.f;
+      if (lane == 0) { qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f; qzsum[g] = zs; }
+    }
+    }   // leader
+    __syncthreads();
+    WSVD_STAMP(tl, tl_wg, wave, 3);
+  } else {
   const int fac16 = R * p.d * 2 / 16;
   StageRegs<FIT> stk, stv;
   QRegs qr;
@@ -241,16 +421,9 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   stage_issue<FIT>(stv, (const char*)p.BV + (size_t)cx * R * p.d * 2, fac16);
   q_issue(p, cz, cx, qr);
   }
-  constexpr int DEPTH = 2;   // deeper prefetch costs registers and measured slower
-  TileRegs<R, I4> buf[DEPTH];
-  const int chunk_tiles = p.chunk_rows >> 6;
-  int T = (int)cy * chunk_tiles + wave;
-  {
-    // unconditional (clamped to the chunk's last allocated tile): see stage_issue
-    const int spec_last = min(((int)cy + 1) * chunk_tiles, p.t_cap >> 6) - 1;
 #pragma unroll
-    for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
-  }
+  for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+  WSVD_STAMP(tl, tl_wg, wave, 1);
 
   // ---- query absorption and its limbs
   if constexpr (LATENT) {
@@ -268,6 +441,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   q_commit(p, qr, 1.f, q_lds);          // an int8 query's scale is applied to delta below
   }
   __syncthreads();
+  WSVD_STAMP(tl, tl_wg, wave, 2);
   if constexpr (ROPE) {
     constexpr int Dh = ROPE_D / 2;
     // block-to-block rotations: +32 tokens (second block of a tile), then on to the wave's next tile
@@ -347,14 +521,17 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       const int jj = j & 15;
       pos = (j & 16) + ((jj >> 3) << 3) + ((jj & 1) << 2) + ((jj & 7) >> 1);
     }
-    qlimb[g][0][pos] = (int8_t)l2;
-    qlimb[g][1][pos] = (int8_t)l1;
-    qlimb[g][2][pos] = (int8_t)l0;
+    qlimb[0][g][0][pos] = (int8_t)l2;
+    qlimb[0][g][1][pos] = (int8_t)l1;
+    qlimb[0][g][2][pos] = (int8_t)l0;
     const float zs = (R == 64) ? wave_sum((float)Q) : half_sum((float)Q, lane);
     if (j == 0) { qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f; qzsum[g] = zs; }
   }
   }
   __syncthreads();
+  WSVD_STAMP(tl, tl_wg, wave, 3);
+
+  }   // STAGED
 
   // A operands of the score MFMAs.  Row i of A: query slot a = i/8, row group (i/4)%2, limb i%4 (limb 3 unused).
   // a1 feeds block 0 of a tile (rows of group 0 only), a2 feeds block 1 (rows of group 1 only).
@@ -365,12 +542,13 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
     const bool act = (a < G) && (limb < 3);
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
-      const v4i val = *(const v4i*)&qlimb[a < G ? a : 0][limb < 3 ? limb : 0][kk * 32 + g2 * 16];
+      const v4i val = *(const v4i*)&qlimb[0][a < G ? a : 0][limb < 3 ? limb : 0][kk * 32 + g2 * 16];
       const v4i zero = {0, 0, 0, 0};
       a1[kk] = (act && grp == 0) ? val : zero;
       a2[kk] = (act && grp == 1) ? val : zero;
     }
   }
+
   // only now are the sequence length and the query scale needed
   const float qs = q_scale_value(p, cz, qs_raw);
   const bool has_new = FUSED && n_raw >= 0 && n_raw < p.t_cap;          // the row being appended by this launch
@@ -382,7 +560,10 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   const int tile_end = ((w.row_end + 63) >> 6) - (own_new ? 1 : 0);
   float delta[G], zsum[G];
 #pragma unroll
-  for (int g = 0; g < G; g++) { delta[g] = qdelta[g] * qs; zsum[g] = I4 ? qzsum[g] : 0.f; }
+  for (int g = 0; g < G; g++) {
+    delta[g] = qdelta[g] * qs;
+    zsum[g] = I4 ? qzsum[g] : 0.f;
+  }
 
   // rotary variant: this lane's position features (its token of the current block, the frequencies of its half)
   float fc[ROPE ? RG::NFH : 1], fs[ROPE ? RG::NFH : 1];
@@ -441,7 +622,12 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   // 32-token half; the low-nibble operand covers even tokens, the high-nibble operand odd tokens.
   const int wpos = I4 ? ((lane & 1) << 5) + ((lane >> 5) << 4) + ((lane & 31) >> 1) : lane;
 
-  auto compute = [&](TileRegs<R, I4>& t, int tile) {
+#ifdef WSVD_TIMELINE
+  bool tl_first = true;
+#endif
+  // refill: std::true_type = request tile `next` into the same registers as they fall free, the key side right after
+  // the score products, the value side at the end
+  auto compute = [&](auto refill, TileRegs<R, I4>& t, int tile, int next) {
     const bool valid = tile * 64 + lane < w.row_end;
     // ---------------- score pass
     v16i acc = {0};
@@ -467,6 +653,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       ksc = f16_bits_to_f32((uint16_t)t.kmeta);
       vsc = f16_bits_to_f32((uint16_t)t.vmeta);
     }
+    if constexpr (decltype(refill)::value && !ROPE) load_tile_k<R, I4>(t, kplane, kmeta, next, lane);
     float rdot[G];
     if constexpr (ROPE) {
       float sb[2][G];
@@ -577,7 +764,16 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
         vacc[jj] = mfma_i8(w1, t.v[jj][1], vacc[jj]);
       }
     }
+    if constexpr (decltype(refill)::value) {
+      if constexpr (ROPE) load_tile_k<R, I4>(t, kplane, kmeta, next, lane);      // (its key codes are read block by block)
+      load_tile_v<R, I4>(t, vplane, vmeta, next, lane);
+    }
+#ifdef WSVD_TIMELINE
+    if (tl_first) { WSVD_STAMP(tl, tl_wg, wave, 4); tl_first = false; }
+#endif
   };
+  constexpr std::true_type kRefill{};
+  constexpr std::false_type kNoRefill{};
 
   // ---- software pipeline over this wave's n tiles (T, T + NW, ...): compute a buffer, refill it.
   // The steady-state rounds issue their refills unconditionally, in straight-line code: a load under a branch
@@ -587,23 +783,37 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
   int done = 0;
   while (done + 2 * DEPTH <= n) {
 #pragma unroll
-    for (int i = 0; i < DEPTH; i++) {
-      compute(buf[i], T + (done + i) * NW);
-      load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
-    }
+    for (int i = 0; i < DEPTH; i++) compute(kRefill, buf[i], T + (done + i) * NW, T + (done + i + DEPTH) * NW);
     done += DEPTH;
+  }
+  // B_V is only needed by the epilogue.  Each thread asks for the elements of its own outputs now, when the steady
+  // part of the stream is over (16 latent-dim x column-pair dwords or fewer per output pass; the 8-16 KB of a head's
+  // B_V are shared by many workgroups and sit in L2): they arrive behind the last tiles, so nothing waits for them.
+  constexpr int BVP = STAGED ? 1 : (G * 64 * 4 + 255) / 256;     // output passes at the smallest workgroup (256 threads)
+  const int half_d = p.d >> 1, hd_shift = p.d == 128 ? 6 : 5, n_pair = G * half_d, bv_items = n_pair * 4;   // d is 64 or 128
+  uint32_t bvr[BVP][R / 4];
+  if constexpr (!STAGED) {
+    const uint32_t* bv32 = (const uint32_t*)p.BV + (size_t)cx * R * half_d;     // bf16 pairs (c, c + 1) of B_V[kv]
+#pragma unroll
+    for (int ps = 0; ps < BVP; ps++) {
+      const int i = tid + ps * (int)blockDim.x;
+      const int o = min(i >> 2, n_pair - 1), part = i & 3, c2 = o & (half_d - 1);
+#pragma unroll
+      for (int jj = 0; jj < R / 4; jj++) bvr[ps][jj] = bv32[(part * (R / 4) + jj) * half_d + c2];
+    }
+    __builtin_amdgcn_sched_barrier(0);     // the loads are issued here, not where their values are first used
   }
 #pragma unroll
   for (int i = 0; i < DEPTH; i++) {
     if (done + i < n) {
-      compute(buf[i], T + (done + i) * NW);
+      compute(kNoRefill, buf[i], T + (done + i) * NW, 0);
       if (done + i + DEPTH < n) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
     }
   }
   done += DEPTH;
 #pragma unroll
   for (int i = 0; i < DEPTH; i++)
-    if (done + i < n) compute(buf[i], T + (done + i) * NW);
+    if (done + i < n) compute(kNoRefill, buf[i], T + (done + i) * NW, 0);
 
   if (FUSED) {
     // the tile with the row appended by this launch, taken by the wave whose turn it would have been
@@ -617,84 +827,96 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT>& sh, 
       if (budget == 0 && lane == 0) atomicExch(p.err_word, (int)WSVD_E_HIP);   // never seen; keeps the kernel finite
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop whatever this CU / XCD cached of the tile earlier
       load_tile_coherent<R, I4>(buf[0], kplane, vplane, kmeta, vmeta, new_tile, lane);
-      compute(buf[0], new_tile);
+      compute(kNoRefill, buf[0], new_tile, 0);
     }
   }
+  WSVD_STAMP(tl, tl_wg, wave, 5);
+  // From here on this wave only takes issue slots away from the waves of the CU that are still streaming (their next
+  // tile request waits behind their arithmetic): lowest priority for the merge and the epilogue.
+  __builtin_amdgcn_s_setprio(0);
   // ---- per-wave state -> workgroup merge
 #pragma unroll
   for (int g = 0; g < G; g++) {
     flush(g);
     const float lw = wave_sum(lsum[g]);
     const float zc = I4 ? wave_sum(zacc[g]) : 0.f;
-    if (lane == 0) { wm[wave][g] = m[g]; wls[wave][g] = lw; }
+    if (lane == 0) { wm[g][wave] = m[g]; wls[g][wave] = lw; }
     if (lane < 32) {
 #pragma unroll
-      for (int jj = 0; jj < KK; jj++) wu[wave][g][jj * 32 + lane] = u[g][jj] - zc;
+      for (int jj = 0; jj < KK; jj++) wu[wave][g * R + jj * 32 + lane] = u[g][jj] - zc;
     }
   }
-  if (w.n_splits == 1 && !LATENT) {
-    // Whole sequence in this workgroup.  Each wave applies B_V to its own accumulator as soon as it is done
-    // (o_w = u_w B_V, two adjacent head-dim columns per lane), while slower waves are still streaming; after the
-    // barrier only a short weighted sum over the waves is left.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const uint32_t* bv32 = (const uint32_t*)bv_lds;              // bf16 pairs (c, c+1)
-    const int half_d = p.d >> 1;                                  // column pairs per row: 64 (d = 128) or 32
-    if (lane < half_d) {
+  WSVD_STAMP(tl, tl_wg, wave, 6);
+  __syncthreads();
+  WSVD_STAMP(tl, tl_wg, wave, 7);
+  // The waves' (m, l, u) -> the workgroup's.  The kernel's last wave waits for this chain with nothing to overlap it,
+  // so it is spread over the whole workgroup: one thread per (head, latent dim, wave slot), the slots of one (head,
+  // dim) in adjacent lanes, so that each thread has one exponential and the sums over the waves are DPP reductions.
+  // Slots run to the launch bound; those past the actual wave count are selected away (their LDS was never written).
+  {
+    constexpr int ITEMS = G * R * NWMAX;
+    for (int it0 = 0; it0 < ITEMS; it0 += (int)blockDim.x) {     // uniform trip count: whole groups stay active
+      const int it = it0 + tid;
+      const int k = it & (NWMAX - 1), gj = min(it / NWMAX, G * R - 1);
+      const int g = gj / R;
+      const bool on = k < NW;
+      const float mraw = wm[g][k], lraw = wls[g][k], uraw = wu[k][gj];
+      const float mk = on ? mraw : -INFINITY;
+      const float M = group_max<NWMAX>(mk);
+      // a wave without a tile holds m = -inf, l = 0, u = 0; at least one wave of an active workgroup has rows
+      const bool live = on && mk != -INFINITY;
+      const float e = __builtin_amdgcn_exp2f(live ? mk - M : 0.f);
+      const float U = group_sum<NWMAX>(live ? uraw * e : 0.f);
+      const float L = group_sum<NWMAX>(live ? lraw * e : 0.f);
+      if (k == 0 && it < ITEMS) {
+        Ush[gj] = U;
+        if (gj % R == 0) { Msh[g] = M; Lsh[g] = L; }
+      }
+    }
+  }
+  __syncthreads();
+  WSVD_STAMP(tl, tl_wg, wave, 9);
+  if constexpr (STAGED) {
+    attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, LATENT ? nullptr : (const void*)bv_lds);
+  } else {
+    if (!attn_merge_splits<R>(p, w, Msh, Lsh, Ush, &flag_sh)) return;
+    // out[b, h, c] = sum_j (U[g][j] / L[g]) B_V[kv][j][c] with this thread's B_V elements already in registers: four
+    // adjacent lanes share a column pair (a quarter of the latent dims each) and add up through DPP
 #pragma unroll
-      for (int g = 0; g < G; g++) {
-        float o0 = 0.f, o1 = 0.f;
+    for (int ps = 0; ps < BVP; ps++) {
+      const int i = tid + ps * (int)blockDim.x;
+      if (ps * (int)blockDim.x < bv_items) {                      // uniform: whole quads stay active
+        const int o = min(i >> 2, n_pair - 1), part = i & 3;
+        const int g = o >> hd_shift, c2 = o & (half_d - 1);
+        float a0 = 0.f, a1 = 0.f;
 #pragma unroll
-        for (int j4 = 0; j4 < R; j4 += 4) {
-          const v4f u4 = *(const v4f*)&wu[wave][g][j4];          // same address in every lane: one broadcast read
+        for (int j4 = 0; j4 < R / 4; j4 += 4) {
+          const v4f u4 = *(const v4f*)&Ush[g * R + part * (R / 4) + j4];
 #pragma unroll
           for (int jj = 0; jj < 4; jj++) {
-            const uint32_t bb = bv32[(j4 + jj) * half_d + lane];
-            o0 = fmaf(u4[jj], __uint_as_float(bb << 16), o0);
-            o1 = fmaf(u4[jj], __uint_as_float(bb & 0xFFFF0000u), o1);
+            const uint32_t bb = bvr[ps][j4 + jj];
+            a0 = fmaf(u4[jj], __uint_as_float(bb << 16), a0);
+            a1 = fmaf(u4[jj], __uint_as_float(bb & 0xFFFF0000u), a1);
           }
         }
-        wo[wave][g][2 * lane] = o0;
-        wo[wave][g][2 * lane + 1] = o1;
+        WSVD_STAMP(tl, tl_wg, wave, 10);
+        a0 = group_sum<4>(a0);
+        a1 = group_sum<4>(a1);
+        if (part == 0 && (i >> 2) < n_pair) {
+          const float L = Lsh[g];
+          const float rl = L > 0.f ? __builtin_amdgcn_rcpf(L) : 0.f;                 // no visible row at all: zeros
+          float2 r2; r2.x = a0 * rl; r2.y = a1 * rl;
+          *(float2*)&p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + 2 * c2] = r2;
+        }
       }
     }
-    __syncthreads();
-    for (int i = tid; i < G * p.d; i += blockDim.x) {
-      const int g = i / p.d, c = i % p.d;
-      float M = wm[0][g];
-      for (int k = 1; k < NW; k++) M = fmaxf(M, wm[k][g]);
-      float L = 0.f, O = 0.f;
-      for (int k = 0; k < NW; k++) {
-        const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
-        L = fmaf(wls[k][g], e, L);
-        O = fmaf(wo[k][g][c], e, O);
-      }
-      p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = O / L;
-    }
-    return;
   }
-  __syncthreads();
-  if (tid < G * R) {
-    const int g = tid / R, j = tid % R;
-    float M = wm[0][g];
-    for (int k = 1; k < NW; k++) M = fmaxf(M, wm[k][g]);
-    float L = 0.f, U = 0.f;
-    for (int k = 0; k < NW; k++) {
-      const float e = __builtin_amdgcn_exp2f(wm[k][g] - M);
-      L = fmaf(wls[k][g], e, L);
-      U = fmaf(wu[k][g][j], e, U);
-    }
-    Ush[tid] = U;
-    if (j == 0) { Msh[g] = M; Lsh[g] = L; }
-  }
-  __syncthreads();
-  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, LATENT ? nullptr : (const void*)bv_lds);
+  WSVD_STAMP(tl, tl_wg, wave, 8);
 }
 
 template <int R, int G, bool I4, int NT>
 __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
-  __shared__ AttnMfmaShared<R, G, NT> sh;
+  __shared__ AttnMfmaShared<R, G, NT, false> sh;
   attn_mfma_body<R, G, I4, NT, false>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
@@ -1072,14 +1294,17 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, LATENT ? nullptr : (const void*)bv_lds);
 }
 
+// Several query heads per kv head keep per-head state in registers: those instantiations are bounded to 8 waves per
+// workgroup (256 registers per lane) whatever NT says, a single head may use all of NT.
 template <int R, bool I4, int NT>
 static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
-  if (threads > NT || threads % 64) return hipErrorInvalidValue;
+  constexpr int NTG = NT > 512 ? 512 : NT;
+  if (threads > (p.G == 1 ? NT : NTG) || threads % 64) return hipErrorInvalidValue;
   switch (p.G) {
     case 1: hipLaunchKernelGGL((k_attn_mfma<R, 1, I4, NT>), grid, dim3(threads), 0, s, p); break;
-    case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4, NT>), grid, dim3(threads), 0, s, p); break;
-    case 3: hipLaunchKernelGGL((k_attn_mfma<R, 3, I4, NT>), grid, dim3(threads), 0, s, p); break;
-    case 4: hipLaunchKernelGGL((k_attn_mfma<R, 4, I4, NT>), grid, dim3(threads), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4, NTG>), grid, dim3(threads), 0, s, p); break;
+    case 3: hipLaunchKernelGGL((k_attn_mfma<R, 3, I4, NTG>), grid, dim3(threads), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((k_attn_mfma<R, 4, I4, NTG>), grid, dim3(threads), 0, s, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -1129,12 +1354,12 @@ hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int 
 // largest workgroup (threads) each instantiation may be launched with
 // wavefronts of these kernels one CU holds at a time (register-limited): the launch policy aims at one round
 int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G) {
-  (void)latent_dtype; (void)G;
-  return rank == 64 ? 8 : 16;
+  (void)latent_dtype;
+  return (rank == 64 || G > 1) ? 8 : 16;
 }
 
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
-  if (G > 4) return 512;
+  if (G > 1) return 512;
   return (latent_dtype == WSVD_I8 && rank == 64) ? 512 : 1024;
 }
 
@@ -1232,7 +1457,7 @@ struct StepParams {
 
 template <int R, int G, int NT>
 union StepShared {
-  AttnMfmaShared<R, G, NT> attn;
+  AttnMfmaShared<R, G, NT, false> attn;
   AppendMfmaShared<R, 1> app;
 };
 

@@ -16,6 +16,20 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+// ---------------------------------------------------------------- in-kernel timeline (profiling build only)
+// Built with -DWSVD_TIMELINE, lane 0 of every wavefront writes the chip-wide 100 MHz wall clock into
+// buf[(workgroup * 16 + wave) * 16 + slot] at the marked points; the product build compiles the marks out.
+constexpr int kTimelineWaves = 16, kTimelineSlots = 16;
+#ifdef WSVD_TIMELINE
+#define WSVD_STAMP(buf, wg, wave, slot)                                                                          \
+  do {                                                                                                           \
+    if ((buf) && (threadIdx.x & 63) == 0)                                                                        \
+      (buf)[((size_t)(wg) * kTimelineWaves + (wave)) * kTimelineSlots + (slot)] = (long long)wall_clock64();     \
+  } while (0)
+#else
+#define WSVD_STAMP(buf, wg, wave, slot) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------- storage formats
 WSVD_DEV float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 WSVD_DEV uint16_t f32_to_bf16_rne(float f) {
@@ -87,6 +101,15 @@ WSVD_DEV float half_sum(float x, int lane) {
   x = row16_sum(x);
   float lo = lane_bcast(x, 0) + lane_bcast(x, 16), hi = lane_bcast(x, 32) + lane_bcast(x, 48);
   return lane < 32 ? lo : hi;
+}
+// maximum over groups of N adjacent lanes (N = 2,4,8,16); every lane of the group gets the result
+template <int N>
+WSVD_DEV float group_max(float x) {
+  if (N >= 2) x = fmaxf(x, dpp_mov_f<kDppQuadSwap1>(x));
+  if (N >= 4) x = fmaxf(x, dpp_mov_f<kDppQuadSwap2>(x));
+  if (N >= 8) x = fmaxf(x, dpp_mov_f<kDppRowHalfMirror>(x));
+  if (N >= 16) x = fmaxf(x, dpp_mov_f<kDppRowMirror>(x));
+  return x;
 }
 // sum over groups of N adjacent lanes (N = 2,4,8,16); every lane of the group gets the result
 template <int N>

@@ -13,6 +13,8 @@ struct wsvd_ctx {
   size_t ws_bytes;
   int epoch;         // number of fused decode steps launched so far (value the append workgroups publish)
   void* static_scratch;   // this device's copy of the library's static scratch array (wsvd_decode_attn_static)
+  long long* timeline;    // profiling build: caller's stamp buffer (wsvd_timeline_set_buffer), else null
+  size_t timeline_bytes;
 };
 
 struct AttnParams;
