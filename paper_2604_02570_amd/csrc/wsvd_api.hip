@@ -11,7 +11,7 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G);
 int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G);
 
-extern int g_append_mode;
+extern int g_append_mode, g_append_helpers;
 
 // ---------------------------------------------------------------- static scratch of wsvd_decode_attn_static
 // Device memory that belongs to the library image: one copy per GPU the library runs on, held until the process ends.
@@ -192,7 +192,8 @@ wsvd_status wsvd_set_workspace(wsvd_ctx* ctx, void* dev_ptr, size_t bytes) {
   if (!aligned16(dev_ptr)) return WSVD_E_ALIGN;
   if (bytes < (size_t)kWsCounterInts * 4) return WSVD_E_WORKSPACE;
   if (hipSetDevice(ctx->device) != hipSuccess) return WSVD_E_HIP;
-  if (hipMemset(dev_ptr, 0, (size_t)kWsCounterInts * 4) != hipSuccess) return WSVD_E_HIP;
+  // tickets, flags and the append's pushed words all start at zero and are left at zero by every launch
+  if (hipMemset(dev_ptr, 0, bytes) != hipSuccess) return WSVD_E_HIP;
   if (hipDeviceSynchronize() != hipSuccess) return WSVD_E_HIP;
   ctx->ws = dev_ptr;
   ctx->ws_bytes = bytes;
@@ -205,6 +206,7 @@ wsvd_status wsvd_set_option(const char* name, int value) {
   if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { g_opt_wg_per_cu = value; return WSVD_OK; }
   if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
   if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { g_append_mode = value; return WSVD_OK; }
+  if (!strcmp(name, "append_helpers") && (value == -1 || value == 0 || value == 2)) { g_append_helpers = value; return WSVD_OK; }
   if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { g_wsvd_linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { g_wsvd_prefill_tiled = value; return WSVD_OK; }

@@ -97,6 +97,250 @@ hipError_t wsvd_launch_pack_factor_a(const wsvd_layer_desc& d, const void* src, 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- MFMA path: one finishing workgroup per unit
+// A unit = (plane, kv head, group of up to SB sequences).  Its contraction over d_model is cut into one LARGE share,
+// taken by the unit's finishing workgroup, and NP small ones, taken by helper workgroups (NP = 2: half of d_model, and
+// a quarter each; NP = 0: everything in one workgroup).  A helper sums its share and PUSHES the partial tile to the
+// finisher as 8-byte words {value, tag} written through to memory; the finisher, busy with twice as much of the factor
+// stream, asks for those words before it needs them and finds them valid when its own sum is done, adds them in
+// helper order (so the result does not depend on timing), quantises, stores the rows and clears the words again.
+// Compared with equal slices merged by "last arriver sums": no ticket, no wait for store acknowledgements, no read-back
+// after the last arrival: three dependent memory round trips less on the launch's critical path, while 3 * 2 * Hkv
+// workgroups still pull the factor stream instead of 2 * Hkv (a CU sustains only about 70 GB/s of such loads, so one
+// workgroup per unit spends 5 us fetching its 384 KB).
+// Helpers have the lower workgroup ids of their unit and never wait, so they are dispatched first and always finish;
+// the finisher's wait is bounded all the same (WSVD_E_HIP in the status word if a word never arrives).
+// Waves split the workgroup's share of d_model; a wave keeps the factor operands of its k-steps in registers
+// (requested in two batches around the staging of the hidden states, which all waves copy into LDS with coalesced
+// loads); partial tiles meet in LDS (in the hidden states' place) and are summed in wave order.
+constexpr uint32_t kLLTag = 0x4C4C5701u;      // marks a pushed word as written by the running launch's helper
+
+template <int R, int NT>
+__global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int xs_stride /* elements */, int NP,
+                                                     unsigned long long* ll /* [units][groups][NP][SB * R] */) {
+  extern __shared__ __align__(16) uint8_t app_lds[];
+  __shared__ int n_loc[32];
+  __shared__ int flag_sh;
+  constexpr int RTC = (R + 31) / 32;          // 32-channel row tiles (R = 16 uses half a tile)
+  constexpr int KB = 8;                       // k-steps (of 16 model dims) per batch of factor loads
+  uint16_t* xs = (uint16_t*)app_lds;                            // [SB][xs_stride] hidden states (bf16)
+  float (*red)[R + 1] = (float (*)[R + 1])app_lds;              // [NW * SB][R + 1] partial tiles, later [SB][R + 1] rows
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+  const int unit = (int)blockIdx.x / (NP + 1), role = (int)blockIdx.x % (NP + 1);   // role < NP: helper, NP: finisher
+  const bool finisher = role == NP;
+  const int pl = unit / p.Hkv, kv = unit % p.Hkv;
+  const int b0 = (int)blockIdx.y * SB, nb = min(SB, p.B - b0);
+  const int col = lane & 31, g = lane >> 5;
+  [[maybe_unused]] const int tl_wg = (int)(blockIdx.y * gridDim.x + blockIdx.x);
+  WSVD_STAMP(p.timeline, tl_wg, wave, 0);
+  // the lengths first: nothing depends on them until the rows are stored
+  const int nreg = finisher ? append_target_row(p, b0 + min(tid, nb - 1)) : 0;
+  const uint16_t* Ap = (const uint16_t*)p.A[pl];
+  const uint16_t* xp = (const uint16_t*)p.x;
+  // ---- this workgroup's share of the k-steps (16 model dims each), then this wave's share of that
+  const int nks = p.E >> 4;
+  const int nks_fin = NP ? (nks + 1) / 2 : nks;                 // the finisher's share comes first
+  const int per_helper = NP ? (nks - nks_fin + NP - 1) / NP : 0;
+  const int wg_k0 = finisher ? 0 : min(nks, nks_fin + role * per_helper);
+  const int wg_k1 = finisher ? nks_fin : min(nks, wg_k0 + per_helper);
+  const int per_wave = (wg_k1 - wg_k0 + NW - 1) / NW;
+  const int ks0 = min(wg_k1, wg_k0 + wave * per_wave), ks1 = min(wg_k1, ks0 + per_wave);
+  unsigned long long* ll_unit = ll + ((size_t)(unit * gridDim.y + blockIdx.y) * (NP ? NP : 1)) * (size_t)(SB * R);
+  v8bf aop[2][RTC][KB];
+  // Only the k-steps of the wave's own part are requested (wave-uniform predicate): the CU's address pipeline moves
+  // 64 bytes per clock, and with 16 waves asking for everything at once every surplus request delays the useful ones.
+  auto load_a = [&](int buf, int k0) {
+#pragma unroll
+    for (int k = 0; k < KB; k++) {
+      if (k0 + k < ks1) {
+#pragma unroll
+        for (int rt = 0; rt < RTC; rt++)
+          aop[buf][rt][k] = *(const v8bf*)(Ap + (((size_t)(kv * RTC + rt) * (size_t)nks + (size_t)(k0 + k)) * 64 + lane) * 8);
+      }
+    }
+  };
+  // ---- hidden states of the share -> LDS: whole 16-byte pieces, four per thread and trip in flight (wave-uniform
+  // predicate per piece); the factor batches go out between the first trip's requests and its LDS writes, so that a
+  // wave's first 16 k-steps cost one round trip
+  const int ppr = (wg_k1 - wg_k0) * 2;                          // 16-byte pieces per row
+  bool first = true;
+  for (int i0 = 0; i0 < nb * ppr || first; i0 += 4 * (int)blockDim.x) {
+    v4i piece[4];
+#pragma unroll
+    for (int it = 0; it < 4; it++) {
+      if (i0 + it * (int)blockDim.x + (wave << 6) < nb * ppr) {  // some lane of this wave has a piece
+        const int i = min(i0 + it * (int)blockDim.x + tid, nb * ppr - 1);
+        piece[it] = *(const v4i*)(xp + (size_t)(b0 + i / ppr) * p.E + (size_t)wg_k0 * 16 + (size_t)(i % ppr) * 8);
+      }
+    }
+    if (first) { load_a(0, ks0); load_a(1, ks0 + KB); first = false; WSVD_STAMP(p.timeline, tl_wg, wave, 1); }
+#pragma unroll
+    for (int it = 0; it < 4; it++) {
+      const int i = i0 + it * (int)blockDim.x + tid;
+      if (i < nb * ppr) *(v4i*)&xs[(size_t)(i / ppr) * xs_stride + (i % ppr) * 8] = piece[it];
+    }
+  }
+  if (tid < 32) n_loc[tid] = nreg;
+  __syncthreads();
+  WSVD_STAMP(p.timeline, tl_wg, wave, 2);
+  // every user of the old lengths draws a ticket once it holds them; whoever draws the last one advances them
+  const int ticket = (tid == 0 && finisher && !p.fused) ? append_reader_ticket(p) : 0;
+  v16f acc[RTC];
+#pragma unroll
+  for (int rt = 0; rt < RTC; rt++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[rt][v] = 0.f;
+  const uint16_t* xrow = xs + (size_t)min(col, nb - 1) * xs_stride + g * 8;   // columns past the group repeat its last row
+  auto mul = [&](int buf, int k0) {
+#pragma unroll
+    for (int k = 0; k < KB; k++)
+      if (k0 + k < ks1) {                                       // wave-uniform
+        const v8bf xo = *(const v8bf*)(xrow + (k0 + k - wg_k0) * 16);
+#pragma unroll
+        for (int rt = 0; rt < RTC; rt++) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[buf][rt][k], xo, acc[rt], 0, 0, 0);
+      }
+  };
+  for (int k0 = ks0; k0 < ks1; k0 += 2 * KB) {
+    mul(0, k0);
+    if (k0 + 2 * KB < ks1) load_a(0, k0 + 2 * KB);              // (wave-uniform; nothing is requested past the wave's part)
+    mul(1, k0 + KB);
+    if (k0 + 3 * KB < ks1) load_a(1, k0 + 3 * KB);
+  }
+  WSVD_STAMP(p.timeline, tl_wg, wave, 3);
+  // the finisher asks for the helpers' words now, one (sequence, channel) element per thread and helper: whatever
+  // has arrived by the time its own sum is done needs no second look
+  constexpr int NPMAX = 2, EPT = (16 * R + NT - 1) / NT;         // helpers; elements per thread (SB <= 16)
+  unsigned long long w[EPT][NPMAX];
+  if (finisher && NP) {
+#pragma unroll
+    for (int e = 0; e < EPT; e++) {
+      const int i = min(tid + e * (int)blockDim.x, SB * R - 1);
+#pragma unroll
+      for (int h = 0; h < NPMAX; h++)
+        w[e][h] = __hip_atomic_load(ll_unit + (size_t)min(h, NP - 1) * (SB * R) + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  __syncthreads();                                              // the hidden states are no longer read: their LDS is reused
+#pragma unroll
+  for (int rt = 0; rt < RTC; rt++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      // lane holds sequence column `col`, channel rows 8*(v/4) + 4*g + v%4
+      const int ch = rt * 32 + 8 * (v / 4) + 4 * g + (v % 4);
+      if (ch < R && col < nb) red[wave * SB + col][ch] = acc[rt][v];
+    }
+  __syncthreads();
+  WSVD_STAMP(p.timeline, tl_wg, wave, 4);
+  // sum over the waves in wave order, one thread per (sequence, channel); the result replaces wave 0's partial, which
+  // only this thread reads
+#pragma unroll
+  for (int e = 0; e < EPT; e++) {
+    const int i = tid + e * (int)blockDim.x;
+    if (i < nb * R) {
+      const int row = i / R, j = i % R;
+      float c = 0.f;
+      for (int k = 0; k < NW; k++) c += red[k * SB + row][j];
+      if (!finisher) {
+        // push: value and tag in one 8-byte store, written through; nobody waits for it
+        const unsigned long long word = ((unsigned long long)kLLTag << 32) | (unsigned long long)__float_as_uint(c);
+        __hip_atomic_store(ll_unit + (size_t)role * (SB * R) + (size_t)row * R + j, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        if (NP) {
+          unsigned long long* src = ll_unit + (size_t)row * R + j;
+#pragma unroll
+          for (int h = 0; h < NPMAX; h++) {
+            if (h < NP) {
+              unsigned long long v = w[e][h];
+              int budget = 1 << 14;
+              while ((uint32_t)(v >> 32) != kLLTag && budget > 0) {
+                __builtin_amdgcn_s_sleep(8);
+                v = __hip_atomic_load(src + (size_t)h * (SB * R), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                budget--;
+              }
+              if ((uint32_t)(v >> 32) != kLLTag) atomicExch(p.err_word, (int)WSVD_E_HIP);   // never seen; keeps the kernel finite
+              c += __uint_as_float((uint32_t)v);
+              // cleared for the next launch (a kernel boundary lies between); written through like the push itself
+              __hip_atomic_store(src + (size_t)h * (SB * R), 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+          }
+        }
+        red[row][j] = c;
+      }
+    }
+  }
+  if (!finisher) return;
+  __syncthreads();
+  WSVD_STAMP(p.timeline, tl_wg, wave, 5);
+  append_store_rows<R>(p, pl, kv, b0, nb, red, n_loc - b0);
+  WSVD_STAMP(p.timeline, tl_wg, wave, 6);
+  if (p.fused) return;
+  // ---- the lengths: advanced by the last finisher to have drawn a ticket (all others hold their copies by then)
+  __syncthreads();
+  if (tid == 0) {
+    const int last = (ticket == (int)(gridDim.x / (NP + 1) * gridDim.y) - 1);
+    if (last) __hip_atomic_store(p.tickets + 2 * p.Hkv, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    flag_sh = last;
+  }
+  __syncthreads();
+  if (!flag_sh) return;
+  if (p.one_seq >= 0) {
+    if (tid == 0) {
+      const int n0 = p.seq_lens[p.one_seq];
+      if (n0 >= 0) p.seq_lens[p.one_seq] = min(n0 + p.B, p.t_cap);
+      if (n0 < 0 || n0 + p.B > p.t_cap) atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
+    }
+    return;
+  }
+  for (int b = tid; b < p.B; b += blockDim.x) {
+    const int n = p.seq_lens[b];
+    if (n >= 0 && n < p.t_cap) p.seq_lens[b] = n + 1;
+    else atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
+  }
+}
+
+// sequences per workgroup: as many (up to 16) as fit LDS with the finisher's share of their hidden-state rows
+int g_append_helpers = -1;     // tuning: helpers per unit of the default kernel (-1 = automatic, 0 or 2)
+static int append_split_np(const wsvd_layer_desc& d) {
+  if (g_append_helpers >= 0) return d.d_model >= 1024 ? g_append_helpers : 0;
+  return d.d_model >= 1024 ? 2 : 0;
+}
+static int append_split_sb(const wsvd_layer_desc& d) {
+  const int share = append_split_np(d) ? (d.d_model / 16 + 1) / 2 * 16 : d.d_model;
+  int sb = 16;
+  while (sb > 1 && (size_t)sb * (share + 8) * 2 > (size_t)144 * 1024) sb >>= 1;
+  return sb;
+}
+static bool append_split_ok(const wsvd_layer_desc& d) {
+  const int share = append_split_np(d) ? (d.d_model / 16 + 1) / 2 * 16 : d.d_model;
+  return (size_t)append_split_sb(d) * (share + 8) * 2 <= (size_t)144 * 1024 && d.d_model % 16 == 0;
+}
+// 8-byte words the helpers push per launch (the workspace's append area holds them)
+size_t wsvd_append_ll_words(const wsvd_layer_desc& d) {
+  const int sb = append_split_sb(d);
+  return (size_t)2 * d.n_kv_heads * ((d.batch + sb - 1) / sb) * 2 * sb * d.rank;
+}
+
+template <int R, int NT>
+static hipError_t launch_append_split(const AppendParams& p, const wsvd_layer_desc& d, unsigned long long* ll, hipStream_t s) {
+  const int np = append_split_np(d), sb = append_split_sb(d);
+  const int share = np ? (d.d_model / 16 + 1) / 2 * 16 : d.d_model;
+  const int stride = share + 8;                           // row stride = 4 dwords mod 32 banks: conflict-free operand reads
+  const int groups = (d.batch + sb - 1) / sb;
+  const int nw = NT / 64;
+  size_t lds = (size_t)sb * stride * 2;
+  const size_t red_bytes = (size_t)nw * sb * (R + 1) * 4;
+  if (red_bytes > lds) lds = red_bytes;
+  static bool raised = false;                             // one attribute per instantiation (the template makes it so)
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_append_split<R, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  dim3 grid((unsigned)(2 * d.n_kv_heads * (np + 1)), (unsigned)groups);
+  hipLaunchKernelGGL((k_append_split<R, NT>), grid, dim3(NT), lds, s, p, sb, stride, np, ll);
+  return hipGetLastError();
+}
+
 // d_model slices per (plane, kv head).
 // One CU cannot pull more than a few tens of GB/s on its own, so the factor stream has to be spread over all of
 // them: the MFMA path aims at about one workgroup per CU (256) and merges the slices through the ticket.
@@ -122,7 +366,10 @@ int wsvd_append_esplits(const wsvd_layer_desc& d) {
   return es;
 }
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d) {
-  return (size_t)2 * d.n_kv_heads * wsvd_append_esplits(d) * d.batch * d.rank;
+  // the sliced kernel's partial sums (the most slices an option can ask for), or the pushed words of the default kernel
+  const size_t sliced = (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank;
+  const size_t pushed = append_mfma_path(d) && append_split_ok(d) ? 2 * wsvd_append_ll_words(d) : 0;
+  return sliced > pushed ? sliced : pushed;
 }
 
 void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
@@ -140,6 +387,7 @@ void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const voi
   p.ES = wsvd_append_esplits(d); p.ESL = d.d_model / p.ES;
   p.x_dtype = d.x_dtype; p.factor_dtype = d.factor_dtype; p.latent_dtype = d.latent_dtype;
   p.one_seq = -1;
+  p.timeline = ctx->timeline_bytes >= (size_t)4096 * kTimelineWaves * kTimelineSlots * sizeof(long long) ? ctx->timeline : nullptr;
 }
 
 // waves per workgroup of the MFMA path: each wave gets a multiple of 16 elements, at least 64; up to 16 waves
@@ -160,6 +408,16 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
   if (d.d_model % 64 != 0 || d.batch > kAppendMaxB) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.ES * p.Hkv * 2));
   const bool f32 = d.factor_dtype == WSVD_F32;
+  if (append_mfma_path(d) && g_append_mode == 0 && append_split_ok(d)) {
+    // the default ("append_mode" n > 0 asks for the kernel with n equal slices merged by the last arriver instead)
+    unsigned long long* ll = (unsigned long long*)((char*)ctx->ws + (size_t)kWsCounterInts * 4 + (wsvd_attn_partial_floats(d) + 3) / 4 * 16);
+    switch (d.rank) {
+      case 16: return launch_append_split<16, 1024>(p, d, ll, s);
+      case 32: return launch_append_split<32, 1024>(p, d, ll, s);
+      case 64: return launch_append_split<64, 512>(p, d, ll, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
   if (append_mfma_path(d)) {
     int nw = wsvd_append_mfma_waves(d);
     if (d.batch > 32) {

@@ -24,6 +24,7 @@ struct AppendParams {
   // prefill of one sequence: all B rows of x are consecutive tokens of sequence one_seq (>= 0); token i goes to row
   // seq_lens[one_seq] + i and the length advances by B.  -1: one token per sequence (decode).
   int one_seq;
+  long long* timeline;       // profiling build: stamp buffer (see WSVD_STAMP), else null
 };
 
 // which sequence a row of x belongs to, and the cache row it goes to given that sequence's length
