@@ -26,8 +26,8 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
 # HBM bytes per attention launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy of known size.
-MEASURED_TRAFFIC_BYTES = 72_360_000   # 72.10 MB fetched + 0.26 MB written (profiles/attn_mfma_int8_c3_hbm_traffic.md)
-MEASURED_TRAFFIC_APPEND = None          # filled in from profiles/append_mfma_c3_hbm_traffic.md once measured
+MEASURED_TRAFFIC_BYTES = 74_620_000   # 74.35 MB fetched + 0.26 MB written at 2073 rows (profiles/attn_mfma_int8_c3_hbm_traffic.md)
+MEASURED_TRAFFIC_APPEND = 20_040_000  # 18.66 MB fetched + 1.38 MB written (same file, section on the append)
 MEASURED_TRAFFIC_BYTES_C5 = 141_840_000   # 140.8 MB fetched + 1.03 MB written (profiles/attn_gqa_int8_c5_hbm_traffic.md)
 # prefill and shared-latent kernels (profiles/prefill_int8_c3_kernel_trace.md, profiles/attn_shared_int8_r1024_kernel_trace.md)
 MEASURED_TRAFFIC_PREFILL_ATTN = 894_500_000    # 357.6 MB fetched + 536.9 MB written (the fp32 outputs)
@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-only", action="store_true", help="only time the attention kernel (profiling runs)")
+    ap.add_argument("--skip-warm", action="store_true",
+                    help="leave out the warm (single cache set) attention launches, so that every attention launch of the "
+                         "process is a cold one and a kernel trace's average is the cold figure (profiling runs)")
     ap.add_argument("--rope", action="store_true",
                     help="c3 / c4: attention through wsvd_decode_attn_rope (rotary position embedding between the key "
                          "reconstruction and q K^T), a secondary line")
@@ -83,15 +86,22 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    def make_ctx():
+        """A context with the command line's tuning settings applied."""
+        c = W.wsvd_create(0)
+        if args.single_launch:
+            W.wsvd_ctx_set_option(c, "fused_step", 2)
+        if args.max_threads:
+            W.wsvd_ctx_set_option(c, "max_threads", args.max_threads)
+        if args.linear_direct:
+            W.wsvd_ctx_set_option(c, "linear_direct", 1)
+        if args.project_shape:
+            W.wsvd_ctx_set_option(c, "project_shape", args.project_shape)
+        return c
+    args.make_ctx = make_ctx
     if args.timeline:
         return run_timeline(args, np, torch, W, WI)
     W.lib()   # fails loudly if the HIP library is missing
-    if args.single_launch:
-        W.wsvd_set_option("fused_step", 2)
-    if args.max_threads:
-        W.wsvd_set_option("max_threads", args.max_threads)
-    if args.linear_direct:
-        W.wsvd_set_option("linear_direct", 1)
     if args.workload == "c5":
         return run_c5(args, np, torch, W, WI)
     if args.workload == "layer":
@@ -111,7 +121,7 @@ def main():
     visits = (args.warmup + args.steps * (R + 1) + n_sets - 1) // n_sets + 8
     t_cap = (T + visits + 63) // 64 * 64
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, sp.latent_dtype, "bf16", "bf16", "i8", "f32", 0.0)
-    ctx = W.wsvd_create(0)
+    ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     W.wsvd_set_workspace(ctx, ws)
     cb, mb = W.wsvd_cache_bytes(desc)
@@ -257,7 +267,7 @@ def main():
         attn_all = timed(lambda i: attend(sets[i % n_sets][5], outs[i % n_sets]), n_attn, R)
         assert W.wsvd_check(ctx, stream) == 0
         # the same on ONE set over and over: that set (72 MB) stays in the 256 MB last-level cache ("warm")
-        warm_all = timed(lambda i: attend(sets[0][5], outs[0]), n_attn, R)
+        warm_all = None if args.skip_warm else timed(lambda i: attend(sets[0][5], outs[0]), n_attn, R)
         # ---- the append alone (its own lengths restored in front of every repeat)
         snap = [s[4].clone() for s in sets]
         def restore():
@@ -323,7 +333,7 @@ def main():
                                                               else "wsvd_latent_append + wsvd_decode_attn"),
             "timing": f"ms_per_step = the first timed replay of {args.steps} steps; us_per_decode_step_repeats = {R} replays",
             "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / (args.steps * R), 6),
-            "attention_alone_us": stats(attn_all), "attention_alone_warm_single_set_us": stats(warm_all),
+            "attention_alone_us": stats(attn_all), "attention_alone_warm_single_set_us": stats(warm_all) if warm_all else None,
             "append_alone_us": stats(app_all) if app_all else None,
         },
         "roofline": {
@@ -339,7 +349,7 @@ def main():
             "algorithmic_bytes_per_launch": int(attn_bytes),
             "avg_launch_us": round(attn_us, 3),
             "avg_launch_us_min_max": [round(min(attn_all), 3), round(max(attn_all), 3)],
-            "warm_single_set_us": round(float(np.median(warm_all)), 3),
+            "warm_single_set_us": round(float(np.median(warm_all)), 3) if warm_all else None,
             # context, not a peak: a kernel that only reads the same cache sets (t_cap slack included), same launch style
             "stream_read_probe": {"bytes_per_launch": set_bytes, "avg_launch_us": round(probe_us, 3),
                                   "GBps": round(set_bytes / (probe_us * 1e-6) / 1e9, 1),
@@ -349,10 +359,10 @@ def main():
     if app_all:
         app_us = float(np.median(app_all))
         res["roofline_append"] = {
-            "kernel": "k_append_mfma (projection of the new token on the packed factors, quantise, store)",
+            "kernel": "k_append_split<32,1024> (projection of the new token on the packed factors, quantise, store)",
             "bound": "hbm", "achieved": round(factor_bytes / (app_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(factor_bytes / (app_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_APPEND if not i4 else None,
-            "traffic_source": "profiles/append_mfma_c3_hbm_traffic.md (not measured in this run)" if not i4 else None,
+            "traffic_source": "rocprofv3 --pmc run recorded in profiles/attn_mfma_int8_c3_hbm_traffic.md (not measured in this run)" if not i4 else None,
             "algorithmic_bytes_per_launch": factor_bytes, "avg_launch_us": round(app_us, 3),
             "note": "factor stream A_K + A_V (bf16); the same factors for every launch, so they come from the last-level cache "
                     "after the first one: a latency chain, not a bandwidth-bound stream"}
@@ -398,7 +408,7 @@ def run_c5(args, np, torch, W, WI):
     T0 = T - 1
     t_cap = (T0 + total + 63) // 64 * 64
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "f32", "f32", 0.0)
-    ctx = W.wsvd_create(0)
+    ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     W.wsvd_set_workspace(ctx, ws)
     cb, mb = W.wsvd_cache_bytes(desc)
@@ -536,7 +546,7 @@ def run_layer(args, np, torch, W, WI):
     T0 = T - 1
     t_cap = (T0 + total + 63) // 64 * 64
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "f32", "f32", 0.0)
-    ctx = W.wsvd_create(0)
+    ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     W.wsvd_set_workspace(ctx, ws)
     cb, mb = W.wsvd_cache_bytes(desc)
@@ -680,7 +690,7 @@ def run_prefill(args, np, torch, W, WI):
     warmup = args.warmup if args.warmup != 32 else 1
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, T, "i8", "bf16", "bf16", "i8", "f32", 0.0)
     dws = W.layer_desc(CH, Hq, Hkv, d, E, r, T, "i8", "bf16", "bf16", "i8", "f32", 0.0)
-    ctx = W.wsvd_create(0)
+    ctx = args.make_ctx()
     ws = torch.empty(max(W.wsvd_workspace_bytes(desc), W.wsvd_workspace_bytes(dws)), dtype=torch.uint8, device="cuda")
     W.wsvd_set_workspace(ctx, ws)
     cb, mb = W.wsvd_cache_bytes(desc)
@@ -696,8 +706,6 @@ def run_prefill(args, np, torch, W, WI):
     cache = W.make_cache(k, v, km, vm, sl)
     X = bf16_bits(WI.hidden_states(sp, T, 1.0, which="ctx", sub=0))          # one prompt's hidden states ...
     Xall = X.unsqueeze(0).repeat(B, 1, 1).contiguous()                        # ... for every sequence: [B, T, E]
-    if args.project_shape:
-        W.wsvd_set_option("project_shape", args.project_shape)
     torch.cuda.synchronize()
 
     def step():
@@ -842,7 +850,7 @@ def run_shared(args, np, torch, W, WI):
     warmup = args.warmup if args.warmup != 32 else 16
     n_sets = 8
     g = torch.Generator(device="cuda"); g.manual_seed(1234)
-    ctx = W.wsvd_create(0)
+    ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_shared_workspace_bytes(B, H, d, R, T), dtype=torch.uint8, device="cuda")
     sets = []
     for _ in range(n_sets):
@@ -917,7 +925,7 @@ def run_timeline(args, np, torch, W, WI):
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
     t_cap = (T + 63) // 64 * 64
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "i8", "f32", 0.0)
-    ctx = W.wsvd_create(0)
+    ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
     W.wsvd_set_workspace(ctx, ws)
     cb, mb = W.wsvd_cache_bytes(desc)

@@ -13,8 +13,9 @@
  *    by the caller; the library allocates only in wsvd_create (one error word) and never in a
  *    hot call.  Device pointers must be 16-byte aligned.
  *  - Hot calls enqueue on the caller's HIP stream (passed as void*, NULL = default stream) and
- *    return without synchronising.  One context per stream; calls on one context that overlap
- *    in time race on its workspace.
+ *    return without synchronising.  One context per stream AT A TIME: tickets, split partials and
+ *    the status word live in the context's workspace, so calls on one context that overlap in time
+ *    (two streams, two threads) corrupt each other.  Contexts are independent of each other.
  *  - Errors detectable on the host (NULL, unsupported shape / dtype, misalignment, workspace
  *    too small) return a non-zero status and enqueue nothing.  Conditions only the device can
  *    see (a sequence already at capacity on append) are recorded in the context's error word and
@@ -123,7 +124,9 @@ wsvd_status wsvd_pack_factor_a(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const
  *   (I8 / I4: the quantiser documented at wsvd_quantize_rows), written at row seq_lens[b];
  * then seq_lens[b] += 1.  A sequence with seq_lens[b] >= t_cap is left unchanged and the
  * context's error word is set to WSVD_E_CAPACITY.
- *   x       [B, d_model] of x_dtype;  x_scale: fp16 [B] iff x_dtype == I8, else NULL
+ *   x       [B, d_model] of x_dtype (F32 or BF16: every supported layer description has one of them).
+ *   x_scale reserved for pre-quantised activations, which no description accepts yet: pass NULL.  (An int8 hidden
+ *           state reaches the cache through wsvd_linear_w4a8_split + wsvd_latent_store instead.)
  *   A_K,A_V PACKED by wsvd_pack_factor_a (wsvd_factor_a_bytes bytes each).  d_model must be a multiple of 64.
  */
 wsvd_status wsvd_latent_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
@@ -173,19 +176,17 @@ wsvd_status wsvd_decode_attn_static(wsvd_ctx *ctx, const wsvd_layer_desc *desc, 
                                     const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,
                                     void *out, void *hip_stream);
 
-/* Process-wide tuning knobs for benchmarks and tests; correct use never needs them.
- *   "wg_per_cu": scales the number of wavefronts the attention grid aims for (default 4 = one resident round)
- *   "min_chunk": smallest context chunk per workgroup in rows, multiple of 64, at least 256
- *   "max_threads": cap on the attention workgroup size (0 = the kernel's own bound)
- *   "append_mode": number of d_model slices of the append (0 = automatic)
- *   "fused_step": wsvd_decode_step uses 0 = two launches (default), 1 = the single-launch kernel where one exists,
- *                 2 = the single-launch kernel or WSVD_E_UNSUPPORTED
- *   "linear_direct": 1 = the W4A8 linear layers read their operands straight from memory (no LDS staging)
- *   "prefill_tiled": 1 = wsvd_prefill_attn and wsvd_prefill_append take their tiled kernels also for small calls
- *   "project_shape": kernel of the tiled prefill projection: 0 = automatic, 1 / 2 = LDS-staged with 4 / 8 waves per
- *                 workgroup, 44 / 42 / 24 / 21 = direct kernel with that many channel x token tiles per wave
- * Unknown names and values out of range return WSVD_E_SHAPE. */
-wsvd_status wsvd_set_option(const char *name, int value);
+/*
+ * Tuning of ONE context's work decomposition; correct use never needs it, results agree to fp32 rounding whatever is
+ * set.  The setting applies to the calls made on this context afterwards (two contexts may differ).
+ *   "wg_per_cu":   scales the number of wavefronts the attention grid aims for (default 4 = one resident round)
+ *   "min_chunk":   smallest context chunk per attention workgroup in rows, multiple of 64, at least 256
+ *   "max_threads": cap on the attention workgroup size (0 = the kernel's own bound; else 256, 512, 768 or 1024)
+ *   "append_mode": 0 = the default append kernel; n > 0 = the kernel that cuts d_model into n equal slices
+ * Unknown names and values out of range return WSVD_E_SHAPE.  (Names that switch between alternative kernels for
+ * tests are listed in wsvd_test.h.)
+ */
+wsvd_status wsvd_ctx_set_option(wsvd_ctx *ctx, const char *name, int value);
 
 /*
  * Decode attention for a backbone with rotary position embedding: the kernel of Section 3.4 taken literally.
@@ -205,7 +206,7 @@ wsvd_status wsvd_decode_attn_rope(wsvd_ctx *ctx, const wsvd_layer_desc *desc, co
  * One decode step of a layer (Section 3.4, decoding pipeline): wsvd_latent_append followed by wsvd_decode_attn,
  * with the same arguments and the same results (the attention includes the row just appended).  By default the
  * two kernels are launched back to back.  A single-launch kernel exists for I8 / I4 latents with bf16 hidden
- * states and factors and at most 4 query heads per kv head ("fused_step" option); it measured no faster on
+ * states and factors and at most 4 query heads per kv head ("fused_step" setting of wsvd_test.h); it measured no faster on
  * MI355X, so it is not the default.
  *   max_seq_len: host upper bound on the sequence lengths AFTER the append (>= 1).
  * Capacity handling as in wsvd_latent_append: a full sequence is attended as it is and reported by wsvd_check.
@@ -346,13 +347,6 @@ wsvd_status wsvd_rmsnorm_quant_i8(wsvd_ctx *ctx, const void *x, const void *y_ad
                                   int64_t cols, void *x_out, int8_t *codes, void *scale_f16, void *hip_stream);
 wsvd_status wsvd_swiglu_quant_i8(wsvd_ctx *ctx, const void *gate_up, int64_t rows, int64_t F, int8_t *codes, void *scale_f16,
                                  void *hip_stream);
-
-/*
- * Measurement aid, not part of the method: a kernel that only READS `bytes` bytes (DEVICE pointer, 16-byte
- * aligned) with `workgroups` workgroups of 512 threads, each streaming one contiguous share.  Benchmarks run it
- * over the buffers the attention streams to report what a pure reader reaches on the same data.
- */
-wsvd_status wsvd_probe_stream_read(wsvd_ctx *ctx, const void *ptr, size_t bytes, int32_t workgroups, void *hip_stream);
 
 /*
  * Per-token symmetric int8 quantisation of activation rows (Section 4.2), same rounding rules as the

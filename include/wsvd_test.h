@@ -24,6 +24,24 @@ extern "C" {
  */
 wsvd_status wsvd_timeline_set_buffer(wsvd_ctx *ctx, void *dev_ptr, size_t bytes);
 
+/*
+ * Settings of wsvd_ctx_set_option (wsvd.h) that choose between alternative kernels, for tests and measurements:
+ *   "fused_step":     wsvd_decode_step uses 0 = two launches (default), 1 = the single-launch kernel where one exists,
+ *                     2 = the single-launch kernel or WSVD_E_UNSUPPORTED
+ *   "append_helpers": helper workgroups per unit of the default append kernel: -1 = automatic, 0 or 2
+ *   "linear_direct":  1 = the W4A8 linear layers read their operands straight from memory (no LDS staging)
+ *   "prefill_tiled":  1 = wsvd_prefill_attn and wsvd_prefill_append take their tiled kernels also for small calls
+ *   "project_shape":  kernel of the tiled prefill projection: 0 = automatic, 1 / 2 = LDS-staged with 4 / 8 waves per
+ *                     workgroup, 44 / 42 / 24 / 21 = direct kernel with that many channel x token tiles per wave
+ */
+
+/*
+ * Measurement aid, not part of the method: a kernel that only READS `bytes` bytes (DEVICE pointer, 16-byte
+ * aligned) with `workgroups` workgroups of 512 threads, each streaming one contiguous share.  Benchmarks run it
+ * over the buffers the attention streams to report what a pure reader reaches on the same data.
+ */
+wsvd_status wsvd_probe_stream_read(wsvd_ctx *ctx, const void *ptr, size_t bytes, int32_t workgroups, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
-           "wsvd_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_static", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
+           "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_static", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
@@ -82,7 +82,7 @@ def lib():
         L.wsvd_cache_bytes.argtypes = [POINTER(LayerDesc), POINTER(c_size_t), POINTER(c_size_t)]
         L.wsvd_workspace_bytes.argtypes = [POINTER(LayerDesc), POINTER(c_size_t)]
         L.wsvd_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
-        L.wsvd_set_option.argtypes = [c_char_p, c_int]
+        L.wsvd_ctx_set_option.argtypes = [c_void_p, c_char_p, c_int]
         L.wsvd_latent_append.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                          POINTER(Cache), c_void_p]
         L.wsvd_latent_store.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int64, POINTER(Cache), c_void_p]
@@ -188,8 +188,8 @@ def wsvd_set_workspace(ctx, ws_tensor):
     _ck(lib().wsvd_set_workspace(ctx, _ptr(ws_tensor), ws_tensor.numel() * ws_tensor.element_size()), "wsvd_set_workspace")
 
 
-def wsvd_set_option(name: str, value: int):
-    _ck(lib().wsvd_set_option(name.encode(), int(value)), "wsvd_set_option")
+def wsvd_ctx_set_option(ctx, name: str, value: int):
+    _ck(lib().wsvd_ctx_set_option(ctx, name.encode(), int(value)), "wsvd_ctx_set_option")
 
 
 def wsvd_factor_a_bytes(desc):

@@ -11,7 +11,6 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G);
 int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G);
 
-extern int g_append_mode, g_append_helpers;
 
 // ---------------------------------------------------------------- static scratch of wsvd_decode_attn_static
 // Device memory that belongs to the library image: one copy per GPU the library runs on, held until the process ends.
@@ -53,11 +52,6 @@ namespace {
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 inline bool is_pow2_rank(int r) { return r == 16 || r == 32 || r == 64; }
 
-int g_opt_wg_per_cu = 4;      // workgroups per CU the attention grid aims for
-int g_opt_min_chunk = 256;    // smallest context chunk per workgroup (rows)
-int g_opt_max_threads = 0;    // cap on the MFMA kernels' workgroup size (0 = their launch bound)
-int g_opt_fused_step = 0;     // wsvd_decode_step: 0 = two launches (default: the fused kernel measured no faster),
-                              // 1 = fused kernel where there is one, 2 = fused or WSVD_E_UNSUPPORTED (tests)
 
 wsvd_status check_desc(const wsvd_layer_desc* d) {
   if (!d) return WSVD_E_NULL;
@@ -200,18 +194,19 @@ wsvd_status wsvd_set_workspace(wsvd_ctx* ctx, void* dev_ptr, size_t bytes) {
   return WSVD_OK;
 }
 
-// Tuning knobs for benchmarks ("wg_per_cu", "min_chunk"); not needed for correct use.
-wsvd_status wsvd_set_option(const char* name, int value) {
-  if (!name) return WSVD_E_NULL;
-  if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { g_opt_wg_per_cu = value; return WSVD_OK; }
-  if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { g_opt_min_chunk = value; return WSVD_OK; }
-  if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { g_append_mode = value; return WSVD_OK; }
-  if (!strcmp(name, "append_helpers") && (value == -1 || value == 0 || value == 2)) { g_append_helpers = value; return WSVD_OK; }
-  if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { g_opt_fused_step = value; return WSVD_OK; }
-  if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { g_wsvd_linear_direct = value; return WSVD_OK; }
-  if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { g_wsvd_prefill_tiled = value; return WSVD_OK; }
-  if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 2 || value == 21 || value == 24 || value == 42 || value == 44)) { g_wsvd_project_shape = value; return WSVD_OK; }
-  if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { g_opt_max_threads = value; return WSVD_OK; }
+// Settings of one context: work decomposition (tuning) and the choice between alternative kernels (tests).
+wsvd_status wsvd_ctx_set_option(wsvd_ctx* ctx, const char* name, int value) {
+  if (!ctx || !name) return WSVD_E_NULL;
+  wsvd_options& o = ctx->opt;
+  if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { o.wg_per_cu = value; return WSVD_OK; }
+  if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { o.min_chunk = value; return WSVD_OK; }
+  if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { o.max_threads = value; return WSVD_OK; }
+  if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { o.append_mode = value; return WSVD_OK; }
+  if (!strcmp(name, "append_helpers") && (value == -1 || value == 0 || value == 2)) { o.append_helpers = value; return WSVD_OK; }
+  if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { o.fused_step = value; return WSVD_OK; }
+  if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { o.linear_direct = value; return WSVD_OK; }
+  if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { o.prefill_tiled = value; return WSVD_OK; }
+  if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 2 || value == 21 || value == 24 || value == 42 || value == 44)) { o.project_shape = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
 
@@ -239,7 +234,7 @@ wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, cons
   if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
   if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
   if (n_tokens < 1 || seq_index < -1 || seq_index >= desc->batch) return WSVD_E_SHAPE;
-  if (n_tokens > 64 || seq_index < 0 || g_wsvd_prefill_tiled) {
+  if (n_tokens > 64 || seq_index < 0 || ctx->opt.prefill_tiled) {
     // a prompt-sized block, or all sequences at once: the tiled projection (one launch for all its tokens)
     const bool fits = desc->latent_dtype == WSVD_I8 && desc->factor_dtype == WSVD_BF16 && desc->x_dtype == WSVD_BF16;
     if (!fits && (n_tokens > 64 || seq_index < 0)) return WSVD_E_SHAPE;
@@ -273,7 +268,7 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const 
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
   if (desc->q_dtype == WSVD_I8) return WSVD_E_DTYPE;          // one scale per sequence cannot serve several tokens
   if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
-  if ((int64_t)n_q * Gr > 8 || (g_wsvd_prefill_tiled && desc->q_dtype == WSVD_BF16)) {
+  if ((int64_t)n_q * Gr > 8 || (ctx->opt.prefill_tiled && desc->q_dtype == WSVD_BF16)) {
     // more query rows than the decode kernel has slots: the tiled kernel (one wavefront per 32 query rows)
     if (desc->q_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
     hipError_t e = wsvd_launch_prefill_attn(*desc, q, n_q, n_after, B_K, B_V, *cache, out, (hipStream_t)hip_stream);
@@ -432,10 +427,10 @@ wsvd_status wsvd_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
-  hipError_t e = g_opt_fused_step ? wsvd_launch_decode_step(ctx, *desc, x, x_scale, A_K, A_V, q, q_scale, B_K, B_V, *cache,
+  hipError_t e = ctx->opt.fused_step ? wsvd_launch_decode_step(ctx, *desc, x, x_scale, A_K, A_V, q, q_scale, B_K, B_V, *cache,
                                                             max_seq_len, out, s)
                                   : hipErrorNotSupported;
-  if (e == hipErrorNotSupported && g_opt_fused_step == 2) return WSVD_E_UNSUPPORTED;
+  if (e == hipErrorNotSupported && ctx->opt.fused_step == 2) return WSVD_E_UNSUPPORTED;
   if (e == hipErrorNotSupported) {
     // no fused kernel for this combination: the two calls back to back on the stream
     e = wsvd_launch_append(ctx, *desc, x, x_scale, A_K, A_V, *cache, s);
@@ -624,7 +619,7 @@ static wsvd_status linear_w4a8(wsvd_ctx* ctx, const int8_t* x, const void* x_sca
   if (n_first <= 0 || n_first > N || n_first % 32 != 0) return WSVD_E_SHAPE;
   if (!aligned16(x) || !aligned16(w_i4) || !aligned16(out) || !aligned16(out2)) return WSVD_E_ALIGN;
   hipError_t e = wsvd_launch_linear_w4a8(x, x_scale, w_i4, w_scale_f16, M, K, N, (float*)out, n_first, (float*)out2,
-                                         (hipStream_t)hip_stream);
+                                         ctx->opt.linear_direct != 0, (hipStream_t)hip_stream);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
@@ -673,21 +668,21 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   // and the rank-32 matrix-core kernels hold 16 per CU, the rank-64 ones 8), so that the grid runs in a single round:
   // a second round pays the prologue, the split merge and the B_V epilogue again with the memory system idle
   const int resident = mfma ? wsvd_attn_mfma_waves_per_cu(d.latent_dtype, d.rank, p.G) : 16;
-  const int waves_target = ctx->n_cu * resident * g_opt_wg_per_cu / 4;
+  const int waves_target = ctx->n_cu * resident * ctx->opt.wg_per_cu / 4;
   int waves_per_unit = (waves_target + n_units - 1) / n_units;
   const int max_tiles = max_rows / 64;
   if (waves_per_unit > max_tiles) waves_per_unit = max_tiles;
   int nw = 4;
   if (mfma) {
     const int bound = wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank, p.G);
-    const int nw_max = (g_opt_max_threads && g_opt_max_threads < bound ? g_opt_max_threads : bound) / 64;
+    const int nw_max = (ctx->opt.max_threads && ctx->opt.max_threads < bound ? ctx->opt.max_threads : bound) / 64;
     while (nw * 2 <= nw_max && nw * 2 <= waves_per_unit) nw *= 2;
     if (force_threads) nw = force_threads / 64;     // the fused step: one workgroup size for both roles
   }
   int chunks_wanted = waves_per_unit / nw;
   if (chunks_wanted < 1) chunks_wanted = 1;
   int chunk_rows = ((max_rows + chunks_wanted - 1) / chunks_wanted + 63) / 64 * 64;
-  const int min_chunk = g_opt_min_chunk < 256 ? 256 : g_opt_min_chunk;
+  const int min_chunk = ctx->opt.min_chunk < 256 ? 256 : ctx->opt.min_chunk;
   if (chunk_rows < min_chunk) chunk_rows = min_chunk;
   p.chunk_rows = chunk_rows;
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;

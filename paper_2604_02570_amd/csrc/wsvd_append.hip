@@ -299,9 +299,9 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
 }
 
 // sequences per workgroup: as many (up to 16) as fit LDS with the finisher's share of their hidden-state rows
-int g_append_helpers = -1;     // tuning: helpers per unit of the default kernel (-1 = automatic, 0 or 2)
-static int append_split_np(const wsvd_layer_desc& d) {
-  if (g_append_helpers >= 0) return d.d_model >= 1024 ? g_append_helpers : 0;
+// helpers per unit: two for model dims from 1024, none below (the "append_helpers" option overrides)
+static int append_split_np(const wsvd_layer_desc& d, int opt_helpers = -1) {
+  if (opt_helpers >= 0) return d.d_model >= 1024 ? opt_helpers : 0;
   return d.d_model >= 1024 ? 2 : 0;
 }
 static int append_split_sb(const wsvd_layer_desc& d) {
@@ -321,8 +321,9 @@ size_t wsvd_append_ll_words(const wsvd_layer_desc& d) {
 }
 
 template <int R, int NT>
-static hipError_t launch_append_split(const AppendParams& p, const wsvd_layer_desc& d, unsigned long long* ll, hipStream_t s) {
-  const int np = append_split_np(d), sb = append_split_sb(d);
+static hipError_t launch_append_split(const AppendParams& p, const wsvd_layer_desc& d, int opt_helpers, unsigned long long* ll,
+                                      hipStream_t s) {
+  const int np = append_split_np(d, opt_helpers), sb = append_split_sb(d);
   const int share = np ? (d.d_model / 16 + 1) / 2 * 16 : d.d_model;
   const int stride = share + 8;                           // row stride = 4 dwords mod 32 banks: conflict-free operand reads
   const int groups = (d.batch + sb - 1) / sb;
@@ -345,16 +346,15 @@ static hipError_t launch_append_split(const AppendParams& p, const wsvd_layer_de
 // One CU cannot pull more than a few tens of GB/s on its own, so the factor stream has to be spread over all of
 // them: the MFMA path aims at about one workgroup per CU (256) and merges the slices through the ticket.
 // The vector-ALU path keeps slices of at most 256 elements (its LDS staging size).
-int g_append_mode = 0;   // tuning: 0 = automatic, n > 0 = force n slices (MFMA path)
 static bool append_mfma_path(const wsvd_layer_desc& d) { return d.factor_dtype == WSVD_BF16 && d.x_dtype == WSVD_BF16; }
-int wsvd_append_esplits(const wsvd_layer_desc& d) {
+int wsvd_append_esplits(const wsvd_ctx* ctx, const wsvd_layer_desc& d) {
   if (!append_mfma_path(d)) {
     int esl = kAppendMaxESL;
     while (esl > 64 && d.d_model % esl != 0) esl >>= 1;
     return d.d_model / esl;
   }
   const int units = d.d_model / 64;                              // slices are multiples of 64 elements
-  int want = g_append_mode > 0 ? g_append_mode : 256 / (2 * d.n_kv_heads);
+  int want = ctx->opt.append_mode > 0 ? ctx->opt.append_mode : 256 / (2 * d.n_kv_heads);
   if (want < 1) want = 1;
   // smallest slice count >= want whose slices fit the kernel's LDS staging; else the largest count that exists
   int es = units;
@@ -384,7 +384,7 @@ void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const voi
   p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
   p.err_word = ctx->err_word;
   p.B = d.batch; p.E = d.d_model; p.Hkv = d.n_kv_heads; p.t_cap = d.t_cap;
-  p.ES = wsvd_append_esplits(d); p.ESL = d.d_model / p.ES;
+  p.ES = wsvd_append_esplits(ctx, d); p.ESL = d.d_model / p.ES;
   p.x_dtype = d.x_dtype; p.factor_dtype = d.factor_dtype; p.latent_dtype = d.latent_dtype;
   p.one_seq = -1;
   p.timeline = ctx->timeline_bytes >= (size_t)4096 * kTimelineWaves * kTimelineSlots * sizeof(long long) ? ctx->timeline : nullptr;
@@ -392,8 +392,8 @@ void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const voi
 
 // waves per workgroup of the MFMA path: each wave gets a multiple of 16 elements, at least 64; up to 16 waves
 // (rank 64: 8, register budget)
-int wsvd_append_mfma_waves(const wsvd_layer_desc& d) {
-  const int esl = d.d_model / wsvd_append_esplits(d);
+int wsvd_append_mfma_waves(const wsvd_ctx* ctx, const wsvd_layer_desc& d) {
+  const int esl = d.d_model / wsvd_append_esplits(ctx, d);
   int nw = d.rank == 64 ? 8 : 16;
   while (nw > 4 && ((esl / nw) % 16 != 0 || esl / nw < 64)) nw >>= 1;
   return nw;
@@ -408,18 +408,18 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
   if (d.d_model % 64 != 0 || d.batch > kAppendMaxB) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.ES * p.Hkv * 2));
   const bool f32 = d.factor_dtype == WSVD_F32;
-  if (append_mfma_path(d) && g_append_mode == 0 && append_split_ok(d)) {
+  if (append_mfma_path(d) && ctx->opt.append_mode == 0 && append_split_ok(d)) {
     // the default ("append_mode" n > 0 asks for the kernel with n equal slices merged by the last arriver instead)
     unsigned long long* ll = (unsigned long long*)((char*)ctx->ws + (size_t)kWsCounterInts * 4 + (wsvd_attn_partial_floats(d) + 3) / 4 * 16);
     switch (d.rank) {
-      case 16: return launch_append_split<16, 1024>(p, d, ll, s);
-      case 32: return launch_append_split<32, 1024>(p, d, ll, s);
-      case 64: return launch_append_split<64, 512>(p, d, ll, s);
+      case 16: return launch_append_split<16, 1024>(p, d, ctx->opt.append_helpers, ll, s);
+      case 32: return launch_append_split<32, 1024>(p, d, ctx->opt.append_helpers, ll, s);
+      case 64: return launch_append_split<64, 512>(p, d, ctx->opt.append_helpers, ll, s);
       default: return hipErrorInvalidValue;
     }
   }
   if (append_mfma_path(d)) {
-    int nw = wsvd_append_mfma_waves(d);
+    int nw = wsvd_append_mfma_waves(ctx, d);
     if (d.batch > 32) {
       // two groups of 32 sequences per pass over the factors; the second set of accumulators needs the register
       // budget of a workgroup of at most 8 waves

@@ -108,7 +108,6 @@ WSVD_DEV void load_tile_coherent(TileRegs<R, I4>& t, const uint8_t* kplane, cons
   }
 }
 
-WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
 
 // three limb dot products -> float: h*2^14 + m*2^7 + l
 WSVD_DEV float limbs_to_f32(int h, int m, int l) { return fmaf((float)h, 16384.f, fmaf((float)m, 128.f, (float)l)); }
@@ -1516,7 +1515,7 @@ hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, cons
   dim3 grid;
   int threads;
   // one workgroup size for both roles: the append's (its wave count follows from the d_model slice)
-  const int want = wsvd_append_mfma_waves(d) * 64;
+  const int want = wsvd_append_mfma_waves(ctx, d) * 64;
   if (want < 256 || want > wsvd_attn_mfma_max_threads(d.latent_dtype, d.rank, G)) return hipErrorNotSupported;
   wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, sp.a, grid, threads, want);
   wsvd_append_params(ctx, d, x, x_scale, A_K, A_V, cache, sp.ap);

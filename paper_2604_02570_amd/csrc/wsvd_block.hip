@@ -292,10 +292,9 @@ __global__ __launch_bounds__(kLinWaves * 64) void k_linear_w4a8_staged(const int
 
 }  // namespace
 
-int g_wsvd_linear_direct = 0;   // option "linear_direct": 1 = operands read straight from memory in operand order
 
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
-                                   int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s) {
+                                   int64_t K, int64_t N, float* out, int64_t n_first, float* out2, bool direct, hipStream_t s) {
   if (M < 1 || M > 64 || K < 64 || K % 64 != 0 || K > 65536 || N % 16 != 0) return hipErrorInvalidValue;
   if (n_first < 0 || n_first > N || n_first % 16 != 0 || (n_first < N && !out2)) return hipErrorInvalidValue;
   const int N1 = (int)n_first;
@@ -307,7 +306,7 @@ hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const v
   // two 16-channel tiles per workgroup once that still leaves a few workgroups per CU
   const bool two = N / 32 >= 512;
   dim3 grid((unsigned)(two ? (N + 31) / 32 : N / 16));
-  if (mbk <= 2 && !g_wsvd_linear_direct) {
+  if (mbk <= 2 && !direct) {
     if (mbk == 1 && two) hipLaunchKernelGGL((k_linear_w4a8_staged<1, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
     else if (mbk == 1) hipLaunchKernelGGL((k_linear_w4a8_staged<1, 1>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);
     else if (two) hipLaunchKernelGGL((k_linear_w4a8_staged<2, 2>), grid, block, 0, s, x, xs, w, ws, (int)M, (int)K, (int)N, out, N1, out2);

@@ -11,6 +11,9 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
+typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
+typedef _Float16 v4f16 __attribute__((ext_vector_type(4)));
 
 #define WSVD_DEV __device__ __forceinline__
 
@@ -29,6 +32,25 @@ constexpr int kTimelineWaves = 16, kTimelineSlots = 16;
 #else
 #define WSVD_STAMP(buf, wg, wave, slot) do { } while (0)
 #endif
+
+// ---------------------------------------------------------------- matrix-core helpers
+// 32x32 products of one wavefront.  Operand lane L holds row (column) L % 32 and the 8 (int8: 16) contraction
+// indices starting at 8 (16) * (L / 32); accumulator lane L holds column L % 32, rows 8 (v / 4) + 4 (L / 32) + v % 4.
+WSVD_DEV v16f mfma_bf16(v8bf16 a, v8bf16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+WSVD_DEV v16f mfma_f16(v8f16 a, v8f16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+
+// 8 int8 codes (two dwords) -> 8 fp16 operand elements, exact.  A byte u = code + 128 placed under the high byte 0x64
+// reads as the fp16 number 1024 + u; one byte permute builds two of them, one packed subtraction of 1152 ends it.
+WSVD_DEV v8f16 codes_f16(int d0, int d1) {
+  const uint32_t x0 = (uint32_t)d0 ^ 0x80808080u, x1 = (uint32_t)d1 ^ 0x80808080u;
+  v4i r;
+  r[0] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04010400u);
+  r[1] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04030402u);
+  r[2] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04010400u);
+  r[3] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04030402u);
+  return __builtin_bit_cast(v8f16, r) - (_Float16)1152;
+}
 
 // ---------------------------------------------------------------- storage formats
 WSVD_DEV float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }

@@ -5,7 +5,21 @@
 
 #include "../../include/wsvd.h"
 
+// Per-context tuning and test settings (wsvd_ctx_set_option); defaults = automatic.
+struct wsvd_options {
+  int wg_per_cu = 4;        // scales the number of wavefronts the attention grid aims for (4 = one resident round)
+  int min_chunk = 256;      // smallest context chunk per attention workgroup (rows)
+  int max_threads = 0;      // cap on the matrix-core attention kernels' workgroup size (0 = their launch bound)
+  int append_mode = 0;      // n > 0: the append kernel with n equal d_model slices merged by the last arriver
+  int append_helpers = -1;  // helpers per unit of the default append kernel (-1 = automatic, 0 or 2)
+  int fused_step = 0;       // wsvd_decode_step: 0 two launches, 1 the single-launch kernel where one exists, 2 that or UNSUPPORTED
+  int linear_direct = 0;    // W4A8 linear layers read operands straight from memory (no LDS staging)
+  int prefill_tiled = 0;    // the tiled prefill kernels also for small calls
+  int project_shape = 0;    // kernel of the tiled prefill projection (0 = automatic)
+};
+
 struct wsvd_ctx {
+  wsvd_options opt;
   int device;
   int n_cu;
   int* err_word;     // device, 4 bytes
@@ -43,7 +57,7 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
                     int force_threads);
 void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
                         const void* A_V, const wsvd_cache& cache, AppendParams& p);
-int wsvd_append_mfma_waves(const wsvd_layer_desc& d);
+int wsvd_append_mfma_waves(const wsvd_ctx* ctx, const wsvd_layer_desc& d);
 bool wsvd_append_uses_mfma(const wsvd_layer_desc& d);
 hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
                                  const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, double rope_base,
@@ -63,7 +77,6 @@ size_t wsvd_shared_ws_bytes(int batch, int rank, int t_cap);
 hipError_t wsvd_launch_attn_shared(int batch, int d_head, int rank, int t_cap, float sm_scale, const void* q, const void* B_K,
                                    const void* B_V, const void* k_codes, const void* v_codes, const void* k_scale,
                                    const void* v_scale, const int* seq_lens, void* workspace, void* out, hipStream_t s);
-extern int g_wsvd_prefill_tiled, g_wsvd_project_shape;   // option "prefill_tiled": 1 = the tiled kernel also for blocks of up to 8 query slots
 hipError_t wsvd_launch_rmsnorm_quant(const float* x, const float* y_add, const float* gain, float eps, int64_t rows,
                                      int64_t cols, float* x_out, int8_t* codes, void* scale_f16, hipStream_t s);
 hipError_t wsvd_launch_swiglu_quant(const float* gate_up, int64_t rows, int64_t F, int8_t* codes, void* scale_f16, hipStream_t s);
@@ -76,11 +89,10 @@ hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, cons
                                    const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,
                                    const wsvd_cache& cache, int max_seq_len, void* out, hipStream_t s);
 hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const void* w_i4, const void* w_scale, int64_t M,
-                                   int64_t K, int64_t N, float* out, int64_t n_first, float* out2, hipStream_t s);
+                                   int64_t K, int64_t N, float* out, int64_t n_first, float* out2, bool direct, hipStream_t s);
 
-extern int g_wsvd_linear_direct;   // option "linear_direct" (defined next to the linear layer's launcher)
 
 // workspace sizing shared by the API and the launchers
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d);
-int wsvd_append_esplits(const wsvd_layer_desc& d);
+int wsvd_append_esplits(const wsvd_ctx* ctx, const wsvd_layer_desc& d);

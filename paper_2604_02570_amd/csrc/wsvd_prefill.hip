@@ -22,10 +22,6 @@
 
 namespace {
 
-typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
-typedef _Float16 v4f16 __attribute__((ext_vector_type(4)));
-typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
-
 struct PrefillParams {
   const uint16_t* q;          // bf16 [B, Hkv, NR, d], NR = nq * G query rows per kv head (row = token * G + head)
   const uint16_t* BK;         // bf16 [Hkv, R, d]
@@ -40,9 +36,6 @@ struct PrefillParams {
   float c_scale;              // sm_scale * log2(e)
 };
 
-WSVD_DEV v16f mfma_bf16(v8bf16 a, v8bf16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-WSVD_DEV v16f mfma_f16(v8f16 a, v8f16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
-
 // x as an fp16 pair hi + lo; the fp32 value is pinned in a register so that hi is formed once (a fused
 // multiply-convert would otherwise round it a second way for the subtraction)
 WSVD_DEV void split_f16(float x, _Float16& hi, _Float16& lo) {
@@ -54,18 +47,6 @@ WSVD_DEV void split_f16(float x, _Float16& hi, _Float16& lo) {
 WSVD_DEV void split_bf16(float x, uint32_t& hi, uint32_t& lo) {
   hi = __float_as_uint(x) & 0xFFFF0000u;
   lo = __float_as_uint(x - __uint_as_float(hi)) & 0xFFFF0000u;
-}
-
-// 8 int8 codes (two dwords) -> 8 fp16 operand elements, exact.  A byte u = code + 128 placed under the high byte 0x64
-// reads as the fp16 number 1024 + u; one byte permute builds two of them, one packed subtraction of 1152 ends it.
-WSVD_DEV v8f16 codes_f16(int d0, int d1) {
-  const uint32_t x0 = (uint32_t)d0 ^ 0x80808080u, x1 = (uint32_t)d1 ^ 0x80808080u;
-  v4i r;
-  r[0] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04010400u);
-  r[1] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04030402u);
-  r[2] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04010400u);
-  r[3] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04030402u);
-  return __builtin_bit_cast(v8f16, r) - (_Float16)1152;
 }
 
 template <int R>
@@ -304,7 +285,6 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
 
 }  // namespace
 
-int g_wsvd_prefill_tiled = 0;
 
 hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int nq, int n_after, const void* B_K, const void* B_V,
                                     const wsvd_cache& cache, void* out, hipStream_t s) {

@@ -5,9 +5,6 @@
 
 namespace {
 
-typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
-WSVD_DEV v16f mfma_bf16(v8bf16 a, v8bf16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-
 // ---------------------------------------------------------------- cache build for a whole prompt (int8 latents)
 // C^T [channels x tokens] = A^T x^T on bf16 MFMA.  The channels of both planes form one axis of 2 * Hkv * r / 32 tiles
 // of 32; a wavefront owns CT channel tiles x TT token tiles (CT * TT accumulators of 32 x 32), so each 1 KiB operand it
@@ -271,7 +268,6 @@ void launch_project(const ProjectParams& p, int n_seq, hipStream_t s) {
 
 }  // namespace
 
-int g_wsvd_project_shape = 0;
 
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
                                        const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s) {
@@ -291,7 +287,7 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   // (option "project_shape": 1 = staged, 44 / 42 / 24 / 21 = variants of the direct kernel, for tuning and tests)
   const long long work = (long long)n_seq * n_tok * d.n_kv_heads * d.rank;
   const bool staged_ok = d.d_model % kProjKC == 0 && (long long)n_tok * d.d_model * 2 < (1LL << 31);
-  int shape = g_wsvd_project_shape ? g_wsvd_project_shape : (work >= (1LL << 22) ? (staged_ok ? 1 : 44) : 21);
+  int shape = ctx->opt.project_shape ? ctx->opt.project_shape : (work >= (1LL << 22) ? (staged_ok ? 1 : 44) : 21);
   if ((shape == 1 || shape == 2) && !staged_ok) shape = 44;
   if (shape == 1 || shape == 2) {
     const int tiles = 2 * p.Hkv * (d.rank / 32);

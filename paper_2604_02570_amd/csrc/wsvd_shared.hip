@@ -18,26 +18,6 @@
 
 namespace {
 
-typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
-typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
-typedef _Float16 v4f16 __attribute__((ext_vector_type(4)));
-
-WSVD_DEV v16f mfma_bf16(v8bf16 a, v8bf16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
-WSVD_DEV v16f mfma_f16(v8f16 a, v8f16 b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
-WSVD_DEV v16i mfma_i8(v4i a, v4i b, v16i c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
-
-// 8 int8 codes (two dwords) -> 8 fp16 operand elements, exact: a byte u = code + 128 under the high byte 0x64 reads as
-// the fp16 number 1024 + u
-WSVD_DEV v8f16 codes_f16(int d0, int d1) {
-  const uint32_t x0 = (uint32_t)d0 ^ 0x80808080u, x1 = (uint32_t)d1 ^ 0x80808080u;
-  v4i r;
-  r[0] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04010400u);
-  r[1] = (int)__builtin_amdgcn_perm(0x64646464u, x0, 0x04030402u);
-  r[2] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04010400u);
-  r[3] = (int)__builtin_amdgcn_perm(0x64646464u, x1, 0x04030402u);
-  return __builtin_bit_cast(v8f16, r) - (_Float16)1152;
-}
-
 constexpr int kSharedHeads = 32;          // the heads are the 32 columns of the products
 constexpr int kSharedChunk = 128;         // tokens per workgroup pass: one 32-token block per wave
 constexpr float kLimbRange = 1040000.f;   // |Q~ / delta| stays below 2^20: three signed 7-bit limbs

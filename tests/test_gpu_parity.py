@@ -221,15 +221,26 @@ def test_attention_independent_of_split_count(dtype):
     check_out(got, ref, dtype, "splits default policy")
     outs.append(got)
     try:
-        W.wsvd_set_option("max_threads", 256)
+        W.wsvd_ctx_set_option(L.ctx, "max_threads", 256)
         for mc in (2048, 1024, 512, 256):   # 1, 2, 3 and 6 context chunks per (sequence, kv head)
-            W.wsvd_set_option("min_chunk", mc)
+            W.wsvd_ctx_set_option(L.ctx, "min_chunk", mc)
             got, ref = run_attend(c, L)
             check_out(got, ref, dtype, f"splits min_chunk={mc}")
             outs.append(got)
+        # the settings belong to L's context: a second context on the same cache still launches the default policy
+        other = W.wsvd_create(0)
+        ws2 = torch.empty(W.wsvd_workspace_bytes(L.desc), dtype=torch.uint8, device="cuda")
+        W.wsvd_set_workspace(other, ws2)
+        qd, qs, _ = q_to_device(c.q32[0], c.sp.q_dtype)
+        fd = c.sp.factor_dtype
+        out2 = torch.full_like(L.out, float("nan"))
+        W.wsvd_decode_attn(other, L.desc, qd, qs, as_dtype_dev(c.BK, fd), as_dtype_dev(c.BV, fd), L.cache, int(c.cache.seq_lens.max()), out2)
+        assert W.wsvd_check(other) == 0
+        assert (out2.cpu().numpy().astype(np.float64) == outs[0]).all(), "a context's settings leaked into another context"
+        W.wsvd_destroy(other)
     finally:
-        W.wsvd_set_option("min_chunk", 256)
-        W.wsvd_set_option("max_threads", 0)
+        W.wsvd_ctx_set_option(L.ctx, "min_chunk", 256)
+        W.wsvd_ctx_set_option(L.ctx, "max_threads", 0)
     for o in outs[1:]:
         assert np.abs(o - outs[0]).max() <= 1e-5 * np.abs(outs[0]).max()
     # repeatability: same launch twice gives identical bits (fixed merge order)
@@ -265,8 +276,8 @@ def test_cross_workgroup_handoffs_are_repeatable(name, over):
     BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     n_max = int(c.cache.seq_lens.max())
     try:
-        W.wsvd_set_option("min_chunk", 256)
-        W.wsvd_set_option("max_threads", 256)          # many small chunks per sequence
+        W.wsvd_ctx_set_option(L.ctx, "min_chunk", 256)
+        W.wsvd_ctx_set_option(L.ctx, "max_threads", 256)          # many small chunks per sequence
         first = None
         for it in range(40):
             got = L.attend(qd, qs, BKd, BVd, n_max)
@@ -276,7 +287,7 @@ def test_cross_workgroup_handoffs_are_repeatable(name, over):
                 check_out(got, ref, sp.latent_dtype, f"repeatable {name}")
             assert (got == first).all(), f"launch {it} differs from launch 0"
     finally:
-        W.wsvd_set_option("max_threads", 0)
+        W.wsvd_ctx_set_option(L.ctx, "max_threads", 0)
     if sp.n_q_heads // sp.n_kv_heads > 4:
         L.close()
         return
@@ -552,7 +563,7 @@ def test_decode_step_matches_oracle(name, over, mode):
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
     flips = 0
     try:
-        W.wsvd_set_option("fused_step", mode)
+        W.wsvd_ctx_set_option(L.ctx, "fused_step", mode)
         for step in range(3):
             x = c.x_new[step]
             if xdt == "bf16":
@@ -570,7 +581,7 @@ def test_decode_step_matches_oracle(name, over, mode):
             check_out(got, ref, sp.latent_dtype, f"step {step} {name}{over}")
             L.upload(c.cache)      # continue from the oracle's cache so that later steps compare like with like
     finally:
-        W.wsvd_set_option("fused_step", 0)
+        W.wsvd_ctx_set_option(L.ctx, "fused_step", 0)
     assert flips <= max(2, 2 * sp.batch * sp.n_kv_heads * sp.rank * 3 // 500)
     L.close()
 
@@ -593,11 +604,11 @@ def test_decode_step_tile_boundaries_and_capacity():
     outs = []
     for mode in (2, 0):
         L.upload(c.cache)
-        W.wsvd_set_option("fused_step", mode)
+        W.wsvd_ctx_set_option(L.ctx, "fused_step", mode)
         try:
             got, st = L.step(as_dtype_dev(x, "bf16"), AKd, AVd, qd, qs, BKd, BVd, c.t_cap)
         finally:
-            W.wsvd_set_option("fused_step", 0)
+            W.wsvd_ctx_set_option(L.ctx, "fused_step", 0)
         assert st == W.E_CAPACITY
         lens_after = L.seq_lens.cpu().numpy()
         assert (lens_after[:-1] == np.array(lens[:-1]) + 1).all() and lens_after[-1] == c.t_cap

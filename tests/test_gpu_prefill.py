@@ -144,12 +144,12 @@ def test_prefill_whole_prompt_projection_matches_oracle(name, over):
     others = c.cache.seq_lens.copy()
     assert not O.latent_prefill(c.cache, b, X.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
     W.wsvd_prefill_append(L.ctx, L.desc, xd[:150], None, 150, b, AKd, AVd, L.cache)       # 4 full tiles and a ragged one
-    W.wsvd_set_option("prefill_tiled", 1)                                                  # short chunks on the same kernel
+    W.wsvd_ctx_set_option(L.ctx, "prefill_tiled", 1)                                                  # short chunks on the same kernel
     try:
         W.wsvd_prefill_append(L.ctx, L.desc, xd[150:183], None, 33, b, AKd, AVd, L.cache)
         W.wsvd_prefill_append(L.ctx, L.desc, xd[183:], None, 1, b, AKd, AVd, L.cache)
     finally:
-        W.wsvd_set_option("prefill_tiled", 0)
+        W.wsvd_ctx_set_option(L.ctx, "prefill_tiled", 0)
     assert W.wsvd_check(L.ctx) == 0
     others[b] = n0 + n_total
     assert (L.seq_lens.cpu().numpy() == others).all() and (c.cache.seq_lens == others).all()
@@ -183,11 +183,11 @@ def test_prefill_all_sequences_in_one_call(name, over, shape, n):
     starts = c.cache.seq_lens.copy()
     for b in range(sp.batch):
         assert not O.latent_prefill(c.cache, b, X[b].astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
-    W.wsvd_set_option("project_shape", shape)
+    W.wsvd_ctx_set_option(L.ctx, "project_shape", shape)
     try:
         W.wsvd_prefill_append(L.ctx, L.desc, xd, None, n, -1, AKd, AVd, L.cache)
     finally:
-        W.wsvd_set_option("project_shape", 0)
+        W.wsvd_ctx_set_option(L.ctx, "project_shape", 0)
     assert W.wsvd_check(L.ctx) == 0
     assert (L.seq_lens.cpu().numpy() == starts + n).all()
     flips = sum(_compare_rows(L, c.cache, b, int(starts[b]), n, "i8", _latents64(X[b], c.AK), _latents64(X[b], c.AV))
@@ -397,11 +397,11 @@ def test_prefill_attention_tiled_equals_slot_kernel_and_handles_short_sequences(
     # up to 8 slots both kernels apply: same result within the int8 bar of each against the oracle, and close to each other
     q8 = _multi_q(c, 6, seed=6)
     a = _prefill_attn(L, c, q8, 6, 2, 200)
-    W.wsvd_set_option("prefill_tiled", 1)
+    W.wsvd_ctx_set_option(L.ctx, "prefill_tiled", 1)
     try:
         t = _prefill_attn(L, c, q8, 6, 2, 200)
     finally:
-        W.wsvd_set_option("prefill_tiled", 0)
+        W.wsvd_ctx_set_option(L.ctx, "prefill_tiled", 0)
     ref8 = O.causal_attn_reconstructed(c.cache, q8.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale, n_after=2)
     check_out(t, ref8, "i8", "tiled kernel, 6 tokens")
     check_out(a, ref8, "i8", "slot kernel, 6 tokens")

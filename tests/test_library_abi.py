@@ -59,5 +59,6 @@ def test_host_only_validation_and_sizes():
         with pytest.raises(W.WsvdError) as e:
             W.wsvd_cache_bytes(W.layer_desc(**args))
         assert e.value.status == status, kw
-    with pytest.raises(W.WsvdError):
-        W.wsvd_set_option("no_such_option", 1)
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_ctx_set_option(None, "max_threads", 256)        # a context is required: the setting lives in it
+    assert e.value.status == W.E_NULL
