@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
-    ap.add_argument("--workload", choices=["c3", "c4", "c5", "layer", "prefill", "shared"], default="c3",
+    ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
                          "c5: the 28-layer grouped-query W4A8 attention block; "
@@ -110,6 +110,10 @@ def main():
         return run_prefill(args, np, torch, W, WI)
     if args.workload == "shared":
         return run_shared(args, np, torch, W, WI)
+    if args.workload in ("c1", "c2"):
+        return run_small(args, np, torch, W, WI)
+    if args.workload == "sweep":
+        return run_sweep(args, np, torch, W, WI)
 
     sp = WI.spec(args.workload)
     i4 = sp.latent_dtype == "i4"
@@ -989,6 +993,151 @@ def run_timeline(args, np, torch, W, WI):
     print(json.dumps({"timeline": "k_attn_mfma at c3 (B=16 H=32 r=32 T=2048, int8), eager back-to-back launches, "
                                   "stamps = 100 MHz wall clock, us relative to the launch's first wavefront",
                       "avg_launch_us_with_stamps": round(us_launch, 3), "launches": summary}))
+    W.wsvd_destroy(ctx)
+
+
+def run_small(args, np, torch, W, WI):
+    """The two single-sequence workloads: c1 (fp32 throughout, 8 heads, rank 16, 256 rows) and c2 (bf16 latents and
+    factors, the 7B head geometry, 640 rows of which 576 are image tokens).  A step is wsvd_latent_append +
+    wsvd_decode_attn on one sequence; the context rows are built by the library's own prefill call from generated
+    hidden states.  These steps move 0.26 MB / 5.2 MB: they are bound by the launch floor and the kernels' dependent
+    round trips, not by the stream, and the line says so through its roofline fraction."""
+    sp = WI.spec(args.workload)
+    B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
+    f32 = sp.latent_dtype == "f32"
+    dt = "f32" if f32 else "bf16"
+    n_sets, R = max(1, args.sets), max(1, args.repeats)
+    visits = (args.warmup + args.steps * (R + 1) + n_sets - 1) // n_sets + 8
+    t_cap = (T + visits + 63) // 64 * 64
+    desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, dt, dt, dt, dt, "f32", 0.0)
+    ctx = args.make_ctx()
+    # the prefill call below stores up to 64 tokens per launch through the append kernels: workspace for that batch
+    ws = torch.empty(max(W.wsvd_workspace_bytes(desc), W.wsvd_workspace_bytes(W.layer_desc(64, Hq, Hkv, d, E, r, t_cap, dt, dt, dt, dt, "f32", 0.0))),
+                     dtype=torch.uint8, device="cuda")
+    W.wsvd_set_workspace(ctx, ws)
+    cb, _ = W.wsvd_cache_bytes(desc)
+
+    def dev(x32):
+        x32 = np.ascontiguousarray(x32, np.float32)
+        if f32:
+            return torch.from_numpy(x32).cuda()
+        return torch.from_numpy((x32.view(np.uint32) >> 16).astype(np.uint16).view(np.int16)).cuda()
+
+    AK, AV, BK, BV = WI.factors(sp)
+    AKd, AVd = (torch.empty(W.wsvd_factor_a_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(2))
+    for src, dst in ((AK, AKd), (AV, AVd)):
+        W.wsvd_pack_factor_a(ctx, desc, dev(src), dst)
+    BKd, BVd = dev(BK), dev(BV)
+    x_new = WI.hidden_states(sp, B, 1.0, which="new")
+    if not f32:
+        x_new = WI.bf16_exact(x_new)
+    xd = dev(x_new)
+    q32 = (x_new.astype(np.float64) @ WI.dense_wq(sp).astype(np.float64)).astype(np.float32)
+    qd = dev(WI.bf16_exact(q32) if not f32 else q32)
+    T0 = T - 1
+    X = WI.hidden_states(sp, T0, 1.0, which="ctx", sub=0)
+    X[: min(sp.image_tokens, T0)] *= sp.image_sigma
+    Xd = dev(X if f32 else WI.bf16_exact(X))
+    sets = []
+    for i in range(n_sets):
+        k, v = (torch.zeros(cb, dtype=torch.uint8, device="cuda") for _ in range(2))
+        sl = torch.zeros(B, dtype=torch.int32, device="cuda")
+        cache = W.make_cache(k, v, None, None, sl)
+        if i == 0:
+            for t0 in range(0, T0, 64):
+                n = min(64, T0 - t0)
+                W.wsvd_prefill_append(ctx, desc, Xd[t0:t0 + n], None, n, 0, AKd, AVd, cache)
+        else:
+            k.copy_(sets[0][0]); v.copy_(sets[0][1]); sl.copy_(sets[0][2])
+        sets.append((k, v, sl, cache))
+    assert W.wsvd_check(ctx) == 0 and int(sets[0][2][0]) == T0
+    outs = [torch.empty((B, Hq, d), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
+    torch.cuda.synchronize()
+
+    def attend(i):
+        W.wsvd_decode_attn(ctx, desc, qd, None, BKd, BVd, sets[i % n_sets][3], t_cap, outs[i % n_sets])
+
+    def append(i):
+        W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, sets[i % n_sets][3])
+
+    def step(i):
+        append(i)
+        attend(i)
+
+    stream = torch.cuda.Stream()
+
+    def timed(fn, n, repeats, graph, before=None):
+        g = None
+        if graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(n):
+                    fn(i)
+            stream.synchronize()
+        res = []
+        for _ in range(repeats):
+            if before is not None:
+                before()
+            stream.synchronize()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            if g is not None:
+                g.replay()
+            else:
+                for i in range(n):
+                    fn(i)
+            e1.record(stream)
+            stream.synchronize()
+            res.append(e0.elapsed_time(e1) * 1e3 / n)
+        return res
+
+    def stats(v):
+        return {"median": round(float(np.median(v)), 3), "min": round(float(min(v)), 3), "max": round(float(max(v)), 3), "repeats": len(v)}
+
+    use_graph = not args.no_graph
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(i)
+        stream.synchronize()
+        step_us = timed(lambda i: step(args.warmup + i), args.steps, R, use_graph)
+        assert W.wsvd_check(ctx, stream) == 0
+        rows = float(np.mean([int(s[2][0]) for s in sets]))
+        snap = [s[2].clone() for s in sets]
+        def restore():
+            for s_, c_ in zip(sets, snap):
+                s_[2].copy_(c_)
+        attn_us = timed(attend, max(args.steps, 64), R, use_graph)
+        app_us = timed(append, 4 * n_sets, R, use_graph, before=restore)
+        restore()
+        eager_us = timed(lambda i: step(i), 4 * n_sets, R, False, before=restore)
+        restore()
+        assert W.wsvd_check(ctx, stream) == 0
+    esz = 4 if f32 else 2
+    row_bytes = Hkv * 2 * r * esz
+    bytes_step = rows * row_bytes
+    ms = step_us[0] * 1e-3
+    a_us = float(np.median(attn_us))
+    res = {
+        "metric": "latent_kv_hbm_GBps_per_decode_step", "value": round(bytes_step / (ms * 1e-3) / 1e9, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 6),
+        "us_per_decode_step": round(ms * 1e3, 3), "us_per_decode_step_repeats": stats(step_us),
+        "pct_of_hbm_peak": round(100.0 * bytes_step / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if f32 else "bf16", "data": "synthetic",
+        "config": {"workload": ("c1: single sequence, fp32 throughout, H=8 d_head=64 d_model=512 r=16 T=256" if f32 else
+                                "c2: single sequence, bf16 latents and factors, H=32 d_head=128 d_model=4096 r=32 T=640 (576 image tokens)"),
+                   "batch": B, "heads": Hq, "d_head": d, "d_model": E, "rank": r, "context": T, "cache_sets_rotated": n_sets,
+                   "launch": "hip_graph_replay" if use_graph else "eager", "step": "wsvd_latent_append + wsvd_decode_attn",
+                   "timing": f"ms_per_step = the first timed replay of {args.steps} steps; us_per_decode_step_repeats = {R} replays",
+                   "attention_alone_us": stats(attn_us), "append_alone_us": stats(app_us),
+                   "eager_step_us": stats(eager_us),
+                   "expected_bound": "launch floor and dependent round trips: one sequence gives the chip 8-32 workgroups of work per launch"},
+        "roofline": {"kernel": "k_attn_generic (decode attention over %s latents)" % dt, "bound": "hbm",
+                     "achieved": round(rows * row_bytes / (a_us * 1e-6) / 1e9, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(rows * row_bytes / (a_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 5), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(rows * row_bytes), "avg_launch_us": round(a_us, 3)},
+    }
+    print(json.dumps(res))
     W.wsvd_destroy(ctx)
 
 
