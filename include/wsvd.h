@@ -27,8 +27,14 @@
  *   latent F32  : factors, x, q F32; any rank above.
  *   latent BF16 : factors, x, q BF16.
  *   latent I8   : rank 32 or 64; factors BF16; x BF16 or F32; q I8 (+fp16 scale per token), F32 or BF16.
+ *                 Also rank 96 and 128 with d_head 128 and n_q_heads == n_kv_heads: wsvd_decode_attn, wsvd_decode_step,
+ *                 wsvd_latent_append / wsvd_prefill_append (x BF16), wsvd_quantize_rows, cache import / export; the other
+ *                 entry points return WSVD_E_UNSUPPORTED at these ranks.
  *   latent I4   : rank 32; otherwise as I8.
  *   out F32.  t_cap must be a multiple of 64.
+ *   Any other per-head rank r (the rank sweep of Eq. 2 / Table 7: r/d = 0.9 .. 0.5) runs at the next supported rank with
+ *   zero padding, which is exact: r_pad - r zero columns appended to every A_h and zero rows to every B_h give latent
+ *   channels that are identically zero, change neither a row's abs-max nor any product, and quantise to code 0.
  */
 #ifndef WSVD_H
 #define WSVD_H
@@ -290,7 +296,9 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const 
  *     K_h = C_K B_Kh,  V_h = C_V B_Vh,  o_h = softmax(sm_scale * q_h K_h^T) V_h       (sm_scale <= 0: 1 / sqrt(d_head)).
  * The kernels absorb B_Kh into the query and B_Vh into the output, and run all heads as the columns of one product over
  * the shared latent, which is therefore streamed once per step (not once per head).
- *   n_heads = 32; d_head 64 or 128; rank 256, 512 or 1024; t_cap a multiple of 128 (WSVD_E_UNSUPPORTED / WSVD_E_SHAPE).
+ *   n_heads = 32; d_head 64 or 128; rank 256, 512 or 1024, or a multiple of 128 up to 4096 (these with t_cap <= 16384:
+ *   one more small launch, the latent walked in slabs of 1024 dims); t_cap a multiple of 128 (WSVD_E_UNSUPPORTED /
+ *   WSVD_E_SHAPE).
  *   q [B, H, d] BF16, B_K and B_V [H, R, d] BF16, out [B, H, d] F32 (all DEVICE, 16-byte aligned).
  *   k_codes, v_codes: int8 latents, one plane of t_cap * R bytes per sequence, in 32-token blocks of 32 * R bytes.  Byte
  *   of (token t, dim j): K plane  (t / 32) * 32 R + (((j / 32) * 2 + (j % 32) / 16) * 32 + t % 32) * 16 + j % 16,

@@ -51,13 +51,16 @@ namespace {
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 inline bool is_pow2_rank(int r) { return r == 16 || r == 32 || r == 64; }
+// ranks 96 and 128: int8 latents, one query head per kv head (other ranks are zero-padded up to a supported one)
+inline bool is_wide_rank(int r) { return r == 96 || r == 128; }
 
 
 wsvd_status check_desc(const wsvd_layer_desc* d) {
   if (!d) return WSVD_E_NULL;
   if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->d_model <= 0 || d->d_model % 64 != 0) return WSVD_E_SHAPE;
   if (d->d_head != 64 && d->d_head != 128) return WSVD_E_SHAPE;
-  if (!is_pow2_rank(d->rank)) return WSVD_E_SHAPE;
+  if (!is_pow2_rank(d->rank) && !is_wide_rank(d->rank)) return WSVD_E_SHAPE;
+  if (is_wide_rank(d->rank) && (d->latent_dtype != WSVD_I8 || d->n_q_heads != d->n_kv_heads || d->d_head != 128)) return WSVD_E_UNSUPPORTED;
   if (d->n_q_heads % d->n_kv_heads != 0) return WSVD_E_SHAPE;
   const int G = d->n_q_heads / d->n_kv_heads;
   if (G < 1 || G > 8) return WSVD_E_SHAPE;
@@ -76,7 +79,7 @@ wsvd_status check_desc(const wsvd_layer_desc* d) {
       if (d->factor_dtype != WSVD_BF16) return WSVD_E_DTYPE;
       if (d->x_dtype != WSVD_BF16 && d->x_dtype != WSVD_F32) return WSVD_E_DTYPE;
       if (d->q_dtype != WSVD_I8 && d->q_dtype != WSVD_F32 && d->q_dtype != WSVD_BF16) return WSVD_E_DTYPE;
-      if (d->latent_dtype == WSVD_I8 && d->rank != 32 && d->rank != 64) return WSVD_E_UNSUPPORTED;
+      if (d->latent_dtype == WSVD_I8 && d->rank != 32 && d->rank != 64 && !is_wide_rank(d->rank)) return WSVD_E_UNSUPPORTED;
       if (d->latent_dtype == WSVD_I4 && d->rank != 32) return WSVD_E_UNSUPPORTED;
       break;
     default:
@@ -222,6 +225,7 @@ wsvd_status wsvd_latent_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
   hipError_t e = wsvd_launch_append(ctx, *desc, x, x_scale, A_K, A_V, *cache, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
@@ -234,9 +238,10 @@ wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, cons
   if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
   if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
   if (n_tokens < 1 || seq_index < -1 || seq_index >= desc->batch) return WSVD_E_SHAPE;
-  if (n_tokens > 64 || seq_index < 0 || ctx->opt.prefill_tiled) {
+  if (n_tokens > 64 || seq_index < 0 || ctx->opt.prefill_tiled || desc->rank > 64) {
     // a prompt-sized block, or all sequences at once: the tiled projection (one launch for all its tokens)
     const bool fits = desc->latent_dtype == WSVD_I8 && desc->factor_dtype == WSVD_BF16 && desc->x_dtype == WSVD_BF16;
+    if (!fits && desc->rank > 64) return WSVD_E_UNSUPPORTED;
     if (!fits && (n_tokens > 64 || seq_index < 0)) return WSVD_E_SHAPE;
     if (fits) {
       hipError_t e = wsvd_launch_prefill_project(ctx, *desc, x, n_tokens, seq_index, A_K, A_V, *cache, (hipStream_t)hip_stream);
@@ -267,7 +272,7 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const 
   if (n_q < 1 || n_after < 0 || max_seq_len < 0) return WSVD_E_SHAPE;
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
   if (desc->q_dtype == WSVD_I8) return WSVD_E_DTYPE;          // one scale per sequence cannot serve several tokens
-  if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
+  if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16 || desc->rank > 64) return WSVD_E_UNSUPPORTED;
   if ((int64_t)n_q * Gr > 8 || (ctx->opt.prefill_tiled && desc->q_dtype == WSVD_BF16)) {
     // more query rows than the decode kernel has slots: the tiled kernel (one wavefront per 32 query rows)
     if (desc->q_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
@@ -296,7 +301,9 @@ wsvd_status check_shared(int32_t batch, int32_t n_heads, int32_t d_head, int32_t
   if (batch < 1 || t_cap < 128 || t_cap % 128 != 0) return WSVD_E_SHAPE;
   if (d_head != 64 && d_head != 128) return WSVD_E_SHAPE;
   if (n_heads != 32) return WSVD_E_UNSUPPORTED;                    // the heads are the 32 columns of the matrix products
-  if (rank != 256 && rank != 512 && rank != 1024) return WSVD_E_UNSUPPORTED;
+  const bool wide = rank > 1024 && rank <= 4096 && rank % 128 == 0;    // walked in slabs of 1024: up to 16384 cached tokens
+  if (rank != 256 && rank != 512 && rank != 1024 && !wide) return WSVD_E_UNSUPPORTED;
+  if (wide && t_cap > 16384) return WSVD_E_UNSUPPORTED;
   return WSVD_OK;
 }
 }  // namespace
@@ -338,6 +345,7 @@ wsvd_status wsvd_decode_attn_rope(wsvd_ctx* ctx, const wsvd_layer_desc* desc, co
   if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
   if (max_seq_len < 0 || !(rope_base > 1.0f)) return WSVD_E_SHAPE;
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  if (desc->rank > 64) return WSVD_E_UNSUPPORTED;
   size_t need;
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
@@ -354,6 +362,7 @@ wsvd_status wsvd_latent_store(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const 
   if (st != WSVD_OK) return st;
   if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
   if (ld < (int64_t)desc->n_kv_heads * desc->rank) return WSVD_E_SHAPE;
+  if (desc->rank > 64) return WSVD_E_UNSUPPORTED;
   if (((uintptr_t)c_K & 3u) || ((uintptr_t)c_V & 3u)) return WSVD_E_ALIGN;
   hipError_t e = wsvd_launch_latent_store(ctx, *desc, c_K, c_V, ld, *cache, (hipStream_t)hip_stream);
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
@@ -521,7 +530,7 @@ wsvd_status wsvd_decode_attn_latent(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
   const int G = desc->n_q_heads / desc->n_kv_heads;
   if (desc->latent_dtype != WSVD_I8 && desc->latent_dtype != WSVD_I4) return WSVD_E_UNSUPPORTED;
-  if (G > (desc->latent_dtype == WSVD_I8 ? 8 : 4)) return WSVD_E_UNSUPPORTED;
+  if (G > (desc->latent_dtype == WSVD_I8 ? 8 : 4) || desc->rank > 64) return WSVD_E_UNSUPPORTED;
   size_t need;
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;

@@ -402,6 +402,12 @@ bool wsvd_append_uses_mfma(const wsvd_layer_desc& d) { return append_mfma_path(d
 
 hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,
                               const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s, int one_seq) {
+  if (d.rank > 64) {
+    // ranks 96 / 128 (int8 latents, bf16 hidden states and factors): the tiled projection with one token per sequence,
+    // then its length update: two launches
+    if (one_seq >= 0) return hipErrorNotSupported;
+    return wsvd_launch_prefill_project(ctx, d, x, 1, -1, A_K, A_V, cache, s);
+  }
   AppendParams p;
   wsvd_append_params(ctx, d, x, x_scale, A_K, A_V, cache, p);
   p.one_seq = one_seq;

@@ -1350,14 +1350,26 @@ hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int 
   return hipGetLastError();
 }
 
+// Ranks 96 and 128 (int8 latents, one query head per kv head): the tile registers alone are 96 / 128 per lane at the
+// prefetch depth of 2, so these run with at most 4 waves per workgroup and the whole 512-register file per lane.
+template <int R>
+static hipError_t launch_m_wide(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
+  if (p.G != 1) return hipErrorNotSupported;
+  if (threads > 256 || threads % 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((k_attn_mfma<R, 1, false, 256>), grid, dim3(threads), 0, s, p);
+  return hipGetLastError();
+}
+
 // largest workgroup (threads) each instantiation may be launched with
 // wavefronts of these kernels one CU holds at a time (register-limited): the launch policy aims at one round
 int wsvd_attn_mfma_waves_per_cu(int latent_dtype, int rank, int G) {
   (void)latent_dtype;
+  if (rank > 64) return 4;      // one wave per SIMD: 314 / 381 registers per lane
   return (rank == 64 || G > 1) ? 8 : 16;
 }
 
 int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
+  if (rank > 64) return 256;
   if (G > 1) return 512;
   return (latent_dtype == WSVD_I8 && rank == 64) ? 512 : 1024;
 }
@@ -1375,6 +1387,8 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
   if (latent_dtype == WSVD_I8 && rank == 32) return launch_m<32, false, 1024>(p, grid, threads, s);
   if (latent_dtype == WSVD_I8 && rank == 64) return launch_m<64, false, 512>(p, grid, threads, s);
   if (latent_dtype == WSVD_I4 && rank == 32) return launch_m<32, true, 1024>(p, grid, threads, s);
+  if (latent_dtype == WSVD_I8 && rank == 96) return launch_m_wide<96>(p, grid, threads, s);
+  if (latent_dtype == WSVD_I8 && rank == 128) return launch_m_wide<128>(p, grid, threads, s);
   return hipErrorInvalidValue;
 }
 

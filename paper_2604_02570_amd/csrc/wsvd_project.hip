@@ -272,7 +272,7 @@ void launch_project(const ProjectParams& p, int n_seq, hipStream_t s) {
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
                                        const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s) {
   if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16 || d.x_dtype != WSVD_BF16) return hipErrorNotSupported;
-  if (d.rank != 32 && d.rank != 64) return hipErrorNotSupported;
+  if (d.rank != 32 && d.rank != 64 && d.rank != 96 && d.rank != 128) return hipErrorNotSupported;
   if (d.d_model % 16 != 0 || n_tok < 1) return hipErrorInvalidValue;
   ProjectParams p;
   p.x = (const uint16_t*)x; p.A[0] = (const uint16_t*)A_K; p.A[1] = (const uint16_t*)A_V;
@@ -289,7 +289,12 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   const bool staged_ok = d.d_model % kProjKC == 0 && (long long)n_tok * d.d_model * 2 < (1LL << 31);
   int shape = ctx->opt.project_shape ? ctx->opt.project_shape : (work >= (1LL << 22) ? (staged_ok ? 1 : 44) : 21);
   if ((shape == 1 || shape == 2) && !staged_ok) shape = 44;
-  if (shape == 1 || shape == 2) {
+  if (d.rank > 64) {
+    // ranks 96 / 128: a wave owns the 3 / 4 channel tiles of one head and 1 or 4 token tiles
+    const bool big = work >= (1LL << 22);
+    if (d.rank == 96) { if (big) launch_project<96, 3, 4, 4>(p, n_seq, s); else launch_project<96, 3, 1, 4>(p, n_seq, s); }
+    else { if (big) launch_project<128, 4, 4, 4>(p, n_seq, s); else launch_project<128, 4, 1, 4>(p, n_seq, s); }
+  } else if (shape == 1 || shape == 2) {
     const int tiles = 2 * p.Hkv * (d.rank / 32);
     p.n_cg = (tiles + 7) / 8; p.tg_seq = (n_tok + 255) / 256; p.n_tg = p.tg_seq * n_seq;
     dim3 grid((unsigned)(p.n_cg * p.n_tg));

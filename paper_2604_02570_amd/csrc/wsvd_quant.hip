@@ -55,6 +55,8 @@ hipError_t wsvd_launch_quantize_rows(int latent_dtype, int rank, const float* c,
   if (latent_dtype == WSVD_I8) {
     if (rank == 32) hipLaunchKernelGGL(k_quantize_rows_i8<32>, grid, block, 0, s, c, n_rows, (int8_t*)codes, (uint16_t*)meta);
     else if (rank == 64) hipLaunchKernelGGL(k_quantize_rows_i8<64>, grid, block, 0, s, c, n_rows, (int8_t*)codes, (uint16_t*)meta);
+    else if (rank == 96) hipLaunchKernelGGL(k_quantize_rows_i8<96>, grid, block, 0, s, c, n_rows, (int8_t*)codes, (uint16_t*)meta);
+    else if (rank == 128) hipLaunchKernelGGL(k_quantize_rows_i8<128>, grid, block, 0, s, c, n_rows, (int8_t*)codes, (uint16_t*)meta);
     else return hipErrorInvalidValue;
   } else if (latent_dtype == WSVD_I4 && rank == 32) {
     hipLaunchKernelGGL(k_quantize_rows_i4<32>, grid, block, 0, s, c, n_rows, (uint8_t*)codes, (uint16_t*)meta);

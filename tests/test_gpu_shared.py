@@ -80,6 +80,12 @@ CASES = [
     ("r1024-empty", 2, 1024, 128, [700, 0], 768),
     ("r256-long", 1, 256, 128, [4000], 4096),           # several chunks per split
     ("r1024-batch40", 40, 1024, 64, [130 + 7 * b for b in range(40)], 512),
+    # ranks above 1024: the latent walked in slabs of 1024 dims (the last slab of 3712 has 640, that of 1152 has 128)
+    ("r2048", 2, 2048, 128, [300, 129], 384),
+    ("r3712-ragged", 3, 3712, 128, [1, 515, 1000], 1024),
+    ("r2560-d64-long", 1, 2560, 64, [4000], 4096),
+    ("r1280-3-chunks-per-split", 40, 1280, 64, [2000 - 47 * b for b in range(40)], 2048),
+    ("r1152-4-chunks-per-split", 64, 1152, 64, [2048 - 30 * b for b in range(64)], 2048),
 ]
 
 
@@ -114,6 +120,22 @@ def test_shared_latent_full_size_sampled():
     W.wsvd_destroy(ctx)
 
 
+def test_shared_latent_sweep_rank_full_size_sampled():
+    """The widest rank of the rank sweep (32 heads x per-head rank 115 = 3680, run as 3712) at 16 sequences x 2048 tokens."""
+    B, R, d, T = 16, 3712, 128, 2048
+    print("shared-latent rank 3712: building the oracle cache", flush=True)
+    c = SharedCase(B, R, d, [T] * B, T, seed_name="c3", garbage=False)
+    ctx = W.wsvd_create(0)
+    print("shared-latent rank 3712: GPU call", flush=True)
+    got = c.run(ctx)
+    rng = np.random.default_rng(4)
+    heads = [(int(b), int(h)) for b, h in zip(rng.integers(0, B, 8), rng.integers(0, H, 8))] + [(0, 0), (B - 1, H - 1)]
+    ref = c.oracle(heads=heads)
+    assert np.isfinite(got).all()
+    check_out(got, ref, "i8", f"shared latent rank 3712, full size, {len(heads)} sampled (sequence, head) pairs")
+    W.wsvd_destroy(ctx)
+
+
 def test_shared_latent_argument_errors():
     c = SharedCase(1, 256, 128, [40], 128)
     ctx = W.wsvd_create(0)
@@ -125,7 +147,8 @@ def test_shared_latent_argument_errors():
     def call(batch=1, heads=H, d=128, R=256, t_cap=128, wsp=ws):
         W.wsvd_decode_attn_shared(ctx, batch, heads, d, R, t_cap, 0.0, q, BK, BV, kc, vc, ks, vs, sl, wsp, out)
 
-    for kw, status in ((dict(heads=16), W.E_UNSUPPORTED), (dict(R=128), W.E_UNSUPPORTED), (dict(t_cap=100), W.E_SHAPE),
+    for kw, status in ((dict(heads=16), W.E_UNSUPPORTED), (dict(R=128), W.E_UNSUPPORTED), (dict(R=1100), W.E_UNSUPPORTED),
+                       (dict(R=4224), W.E_UNSUPPORTED), (dict(t_cap=100), W.E_SHAPE),
                        (dict(d=96), W.E_SHAPE), (dict(batch=0), W.E_SHAPE), (dict(wsp=ws[:1024]), W.E_WORKSPACE)):
         with pytest.raises(W.WsvdError) as e:
             call(**kw)

@@ -784,3 +784,29 @@ def test_shared_latent_generators_are_seeded_and_shaped():
     a = WI.shared_latents(sp, 256, "k", 1, 10); b = WI.shared_latents(sp, 256, "v", 1, 10)
     assert a.shape == (10, 256) and a.dtype == np.float32 and not np.array_equal(a, b)
     assert np.array_equal(a, WI.shared_latents(sp, 256, "k", 1, 10))
+
+
+@pytest.mark.parametrize("r,r_pad", [(115, 128), (77, 96), (5, 32)])
+def test_zero_padded_rank_is_the_same_problem(r, r_pad):
+    """A rank-r head run at a wider rank with zero columns in A and zero rows in B (how ranks between the supported
+    widths reach the library): the quantiser sees the same abs-max and emits zero codes for the padding, and the
+    attention result is the logical rank's (Section 3.1: K_h = C_h B_h only sums over the r latent channels)."""
+    rng = np.random.default_rng(r)
+    B, H, T, d, E = 2, 3, 37, 16, 48
+    AK = rng.standard_normal((H, E, r)) / np.sqrt(E); AV = rng.standard_normal((H, E, r)) / np.sqrt(E)
+    BK = rng.standard_normal((H, r, d)) / np.sqrt(r); BV = rng.standard_normal((H, r, d)) / np.sqrt(r)
+    pad_a = lambda a: np.concatenate([a, np.zeros(a.shape[:-1] + (r_pad - r,))], axis=-1)
+    pad_b = lambda b: np.concatenate([b, np.zeros((H, r_pad - r, d))], axis=1)
+    caches = [O.LatentCache(B, H, T + 3, rr, "i8") for rr in (r, r_pad)]
+    X = rng.standard_normal((T, B, E))
+    for t in range(T):
+        O.latent_append(caches[0], X[t], AK, AV)
+        O.latent_append(caches[1], X[t], pad_a(AK), pad_a(AV))
+    assert (caches[1].k[..., :r] == caches[0].k).all() and (caches[1].k[..., r:] == 0).all()
+    assert (caches[1].v[..., :r] == caches[0].v).all() and (caches[1].v[..., r:] == 0).all()
+    assert (caches[1].k_scale.view(np.uint16) == caches[0].k_scale.view(np.uint16)).all()
+    assert (caches[1].v_scale.view(np.uint16) == caches[0].v_scale.view(np.uint16)).all()
+    q = rng.standard_normal((B, H, d))
+    o0 = O.decode_attn_reconstructed(caches[0], q, BK, BV, 0.25)
+    o1 = O.decode_attn_reconstructed(caches[1], q, pad_b(BK), pad_b(BV), 0.25)
+    assert np.abs(o0 - o1).max() <= 1e-13 * np.abs(o0).max()
