@@ -527,7 +527,8 @@ __global__ __launch_bounds__(256) void k_shared_attn_big(SharedParams p) {
 }
 
 // ---------------------------------------------------------------- merge of the splits and o_h = B_Vh^T u_h
-// One workgroup per (head, kOutSeqs sequences).
+// One workgroup per (head, kOutSeqs sequences).  (4 sequences per workgroup read B_Vh a quarter as often but leave
+// three quarters of the CUs without a workgroup: measured 1.6 x slower at 16 sequences.)
 constexpr int kOutSeqs = 1;
 __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
   extern __shared__ __align__(16) uint8_t so_lds[];
@@ -556,12 +557,12 @@ __global__ __launch_bounds__(256) void k_shared_out(SharedParams p) {
       float u = 0.f;
       if (b0 + bi < p.B) {
         const float* src = p.pu + (((size_t)(b0 + bi) * p.S) * kSharedHeads + h) * p.R + j;
-        for (int s0 = 0; s0 < p.S; s0 += 4) {                           // 4 loads in flight; a split that wrote nothing has
-          float x[4];                                                   // weight 0 and its (unwritten) values are dropped
+        for (int s0 = 0; s0 < p.S; s0 += 16) {                          // 16 loads in flight (each trip of this loop is a
+          float x[16];                                                  // memory round trip); a split that wrote nothing has
+#pragma unroll                                                          // weight 0 and its (unwritten) values are dropped
+          for (int i = 0; i < 16; i++) x[i] = src[(size_t)min(s0 + i, p.S - 1) * kSharedHeads * p.R];
 #pragma unroll
-          for (int i = 0; i < 4; i++) x[i] = src[(size_t)min(s0 + i, p.S - 1) * kSharedHeads * p.R];
-#pragma unroll
-          for (int i = 0; i < 4; i++) {
+          for (int i = 0; i < 16; i++) {
             const float w = s0 + i < p.S ? wn[bi * 32 + s0 + i] : 0.f;
             u += w != 0.f ? w * x[i] : 0.f;
           }
@@ -657,6 +658,12 @@ hipError_t wsvd_launch_attn_shared(int batch, int d_head, int rank, int t_cap, f
   if (e != hipSuccess) return e;
 
   const size_t lds_out = (size_t)(kOutSeqs * 32 + rank * kOutSeqs + 16 * kOutSeqs * 128) * sizeof(float);
+  static bool raised_out = false;                                       // up to 99 KB at rank 4096
+  if (!raised_out) {
+    e = hipFuncSetAttribute((const void*)k_shared_out, hipFuncAttributeMaxDynamicSharedMemorySize, (int)((128 + 4096 * kOutSeqs + 16 * kOutSeqs * 128) * sizeof(float)));
+    if (e != hipSuccess) return e;
+    raised_out = true;
+  }
   if (rank > 1024) {
     hipLaunchKernelGGL(k_shared_qmax, dim3(kSharedHeads, (unsigned)batch), dim3(64), 0, s, p);
     const size_t lds_big = (size_t)3 * (kBigSlab / 32) * 1024 + (size_t)(2 + kBigChunks) * 128 * sizeof(float) +
