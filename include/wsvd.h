@@ -106,7 +106,7 @@ wsvd_status wsvd_destroy(wsvd_ctx *ctx);
 /* Bytes of ONE code plane and ONE metadata plane (K or V) for this layer (HOST outputs). */
 wsvd_status wsvd_cache_bytes(const wsvd_layer_desc *desc, size_t *codes_bytes, size_t *meta_bytes);
 
-/* Scratch the hot calls need for this layer (split partials, tickets); HOST output. */
+/* Scratch the hot calls need for this layer (counters, the words workgroups hand partial results over in); HOST output. */
 wsvd_status wsvd_workspace_bytes(const wsvd_layer_desc *desc, size_t *bytes);
 
 /* Hand the context a caller-owned device scratch buffer.  Clears it (synchronously). */
@@ -169,14 +169,18 @@ wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const v
 /*
  * wsvd_decode_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results as
- * wsvd_decode_attn, but the split partials and tickets live in an array that is part of the library image
- * (8 MiB of device memory per GPU the library runs on, held until the process ends) instead of the workspace set
- * with wsvd_set_workspace, which is neither needed nor touched.  The call allocates nothing and frees nothing.
- *   Limit: 65536 + 4 * batch * n_q_heads * ceil(t_cap / 256) * (rank + 2) bytes must fit in the 8 MiB
- *   (all five documented workloads do); WSVD_E_WORKSPACE otherwise, nothing enqueued.
+ * wsvd_decode_attn, but the words through which the splits of a long sequence reach the workgroup that merges them
+ * live in an array that is part of the library image (8 MiB of device memory per GPU the library runs on, held until
+ * the process ends) instead of the workspace set with wsvd_set_workspace, which is neither needed nor touched.  The
+ * call allocates nothing and frees nothing.
+ *   Limit: 65536 + 8 * batch * n_q_heads * n_chunks * (rank + 2) bytes must fit in the 8 MiB, n_chunks being the
+ *   number of context splits the launch policy picks for this call (1 when batch * n_kv_heads alone fills the chip:
+ *   then the term is 0; at most ceil(max_seq_len / 256)); all five documented workloads fit; WSVD_E_WORKSPACE
+ *   otherwise, nothing enqueued.
  *   Every call on a GPU shares that GPU's array, from every context and stream: calls that overlap in time on one
  *   GPU race on it.  Calls on one stream are ordered and safe.
- * Enqueues a small clearing kernel and the attention kernel on hip_stream; error behaviour as wsvd_decode_attn.
+ * Enqueues the attention kernel on hip_stream, behind a small clearing kernel when the context is split; error
+ * behaviour as wsvd_decode_attn.
  */
 wsvd_status wsvd_decode_attn_static(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
                                     const void *B_K, const void *B_V, const wsvd_cache *cache, int32_t max_seq_len,

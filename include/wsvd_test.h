@@ -33,6 +33,8 @@ wsvd_status wsvd_timeline_set_buffer(wsvd_ctx *ctx, void *dev_ptr, size_t bytes)
  *   "prefill_tiled":  1 = wsvd_prefill_attn and wsvd_prefill_append take their tiled kernels also for small calls
  *   "project_shape":  kernel of the tiled prefill projection: 0 = automatic, 1 / 2 = LDS-staged with 4 / 8 waves per
  *                     workgroup, 44 / 42 / 24 / 21 = direct kernel with that many channel x token tiles per wave
+ *   "static_limit_kib": wsvd_decode_attn_static treats its static array as this many KiB (0 = its real size, 8192): lets
+ *                     a test see the WSVD_E_WORKSPACE rejection with buffers that are valid for the call
  */
 
 /*

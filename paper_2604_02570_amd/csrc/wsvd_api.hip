@@ -110,9 +110,11 @@ wsvd_status check_cache(const wsvd_layer_desc& d, const wsvd_cache* c) {
 
 }  // namespace
 
+// size of the attention's split area in 4-byte units: one 8-byte word per (sequence, head, chunk, m | l | u_j), for
+// the largest number of chunks a launch policy can choose (chunks are at least 256 rows)
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d) {
   const size_t max_chunks = (size_t)(d.t_cap + 255) / 256;
-  return (size_t)d.batch * d.n_q_heads * max_chunks * (d.rank + 2);
+  return 2 * (size_t)d.batch * d.n_q_heads * max_chunks * (d.rank + 2);
 }
 
 extern "C" {
@@ -179,7 +181,7 @@ wsvd_status wsvd_workspace_bytes(const wsvd_layer_desc* desc, size_t* bytes) {
   wsvd_status st = check_desc(desc);
   if (st != WSVD_OK) return st;
   const size_t a = wsvd_attn_partial_floats(*desc), b = wsvd_append_partial_floats(*desc);
-  // the fused decode step runs both at once: the append's partial sums sit behind the attention's (16-byte aligned)
+  // counters, the attention's split words, the append's pushed words, the sliced append's partial sums (16-byte aligned)
   *bytes = (size_t)kWsCounterInts * 4 + ((a + 3) / 4 * 4 + b) * 4;
   return WSVD_OK;
 }
@@ -207,6 +209,7 @@ wsvd_status wsvd_ctx_set_option(wsvd_ctx* ctx, const char* name, int value) {
   if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { o.append_mode = value; return WSVD_OK; }
   if (!strcmp(name, "append_helpers") && (value == -1 || value == 0 || value == 2)) { o.append_helpers = value; return WSVD_OK; }
   if (!strcmp(name, "fused_step") && value >= 0 && value <= 2) { o.fused_step = value; return WSVD_OK; }
+  if (!strcmp(name, "static_limit_kib") && value >= 0 && value <= (int)(kStaticScratchBytes >> 10)) { o.static_limit_kib = value; return WSVD_OK; }
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { o.linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { o.prefill_tiled = value; return WSVD_OK; }
   if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 2 || value == 21 || value == 24 || value == 42 || value == 44)) { o.project_shape = value; return WSVD_OK; }
@@ -398,9 +401,10 @@ wsvd_status wsvd_decode_attn_static(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
   if (max_seq_len < 0) return WSVD_E_SHAPE;
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
-  // tickets + split partials of this layer must fit the static array
-  const size_t need = (size_t)kWsCounterInts * 4 + wsvd_attn_partial_floats(*desc) * 4;
-  if (need > kStaticScratchBytes) return WSVD_E_WORKSPACE;
+  // counters + the split words of this launch must fit the static array
+  const size_t need = (size_t)kWsCounterInts * 4 + wsvd_attn_split_bytes(ctx, *desc, max_seq_len);
+  const size_t limit = ctx->opt.static_limit_kib ? (size_t)ctx->opt.static_limit_kib << 10 : kStaticScratchBytes;
+  if (need > limit) return WSVD_E_WORKSPACE;
   if (!ctx->static_scratch) return WSVD_E_HIP;
   hipStream_t s = (hipStream_t)hip_stream;
   // the same launch as wsvd_decode_attn, with the array in the caller's workspace's place (a copy of the context on
@@ -408,12 +412,15 @@ wsvd_status wsvd_decode_attn_static(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   wsvd_ctx view = *ctx;
   view.ws = ctx->static_scratch;
   view.ws_bytes = kStaticScratchBytes;
-  // Tickets must start at zero.  They reset themselves at the end of every launch that uses them, but the array
-  // outlives every call (also one that was cut short), so they are cleared on the stream first: a fill kernel, not a
-  // memset node, so that the call can be captured into a graph.
-  const int n_tickets = desc->batch * desc->n_kv_heads;
-  hipLaunchKernelGGL(k_fill_zero_i32, dim3((n_tickets + 255) / 256), dim3(256), 0, s, (int*)view.ws, n_tickets);
-  if (hipGetLastError() != hipSuccess) return WSVD_E_HIP;
+  // The split words must start at zero.  Their consumer clears them at the end of every launch, but the array
+  // outlives every call (also one that was cut short), so the part this launch uses is cleared on the stream first: a
+  // fill kernel, not a memset node, so that the call can be captured into a graph.
+  const size_t split_bytes = need - (size_t)kWsCounterInts * 4;
+  if (split_bytes) {
+    const int n_ints = (int)(split_bytes / 4);
+    hipLaunchKernelGGL(k_fill_zero_i32, dim3((n_ints + 255) / 256), dim3(256), 0, s, (int*)((char*)view.ws + (size_t)kWsCounterInts * 4), n_ints);
+    if (hipGetLastError() != hipSuccess) return WSVD_E_HIP;
+  }
   hipError_t e = wsvd_launch_attn(&view, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, s);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
@@ -658,7 +665,7 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   p.seq_lens = cache.seq_lens;
   p.out = (float*)out;
   p.tickets = (int*)ctx->ws;
-  p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
+  p.partials = (unsigned long long*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
   p.err_word = ctx->err_word;
   p.B = d.batch; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.d = d.d_head;
   p.out_dim = d.d_head;
@@ -699,6 +706,15 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   threads = nw * 64;
   const size_t tl_need = (size_t)grid.x * grid.y * grid.z * kTimelineWaves * kTimelineSlots * sizeof(long long);
   p.timeline = (ctx->timeline && ctx->timeline_bytes >= tl_need) ? ctx->timeline : nullptr;
+}
+
+// bytes of split words the launch wsvd_attn_plan chooses for this call touches
+size_t wsvd_attn_split_bytes(const wsvd_ctx* ctx, const wsvd_layer_desc& d, int max_seq_len) {
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, d, nullptr, nullptr, nullptr, nullptr, wsvd_cache{}, max_seq_len, nullptr, p, grid, threads, 0);
+  return p.n_chunks > 1 ? (size_t)d.batch * d.n_q_heads * p.n_chunks * (d.rank + 2) * 8 : 0;
 }
 
 hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,

@@ -365,11 +365,14 @@ int wsvd_append_esplits(const wsvd_ctx* ctx, const wsvd_layer_desc& d) {
   }
   return es;
 }
+static size_t wsvd_append_pushed_floats(const wsvd_layer_desc& d) {
+  return append_mfma_path(d) && append_split_ok(d) ? (2 * wsvd_append_ll_words(d) + 3) / 4 * 4 : 0;
+}
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d) {
-  // the sliced kernel's partial sums (the most slices an option can ask for), or the pushed words of the default kernel
+  // the pushed words of the default kernel (which are zero between launches), then the sliced kernels' partial sums
+  // (the most slices an option can ask for)
   const size_t sliced = (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank;
-  const size_t pushed = append_mfma_path(d) && append_split_ok(d) ? 2 * wsvd_append_ll_words(d) : 0;
-  return sliced > pushed ? sliced : pushed;
+  return wsvd_append_pushed_floats(d) + sliced;
 }
 
 void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale, const void* A_K,
@@ -381,7 +384,7 @@ void wsvd_append_params(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const voi
   p.meta[0] = (uint16_t*)cache.k_meta; p.meta[1] = (uint16_t*)cache.v_meta;
   p.seq_lens = cache.seq_lens;
   p.tickets = (int*)ctx->ws + kWsCounterInts / 2;
-  p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4);
+  p.partials = (float*)((char*)ctx->ws + (size_t)kWsCounterInts * 4) + (wsvd_attn_partial_floats(d) + 3) / 4 * 4 + wsvd_append_pushed_floats(d);
   p.err_word = ctx->err_word;
   p.B = d.batch; p.E = d.d_model; p.Hkv = d.n_kv_heads; p.t_cap = d.t_cap;
   p.ES = wsvd_append_esplits(ctx, d); p.ESL = d.d_model / p.ES;

@@ -14,8 +14,8 @@ struct AttnParams {
   const uint16_t* v_meta;
   const int* seq_lens;
   float* out;                // [B,Hq,d] fp32
-  float* partials;           // [B*Hq][n_chunks][R+2] fp32 (m, l, u[R]) in the log2 domain, un-normalised
-  int* tickets;              // [B*Hkv]
+  unsigned long long* partials;   // [B*Hq][n_chunks][R+2] pushed words {fp32 value, tag} of (m, l, u[R]), log2 domain, un-normalised
+  int* tickets;              // [B*Hkv] (the fused decode step's counters)
   int B, Hq, Hkv, G, d, t_cap;
   int chunk_rows;            // rows of context per workgroup (multiple of 64)
   int n_chunks;              // grid extent along the context
@@ -184,68 +184,115 @@ WSVD_DEV void compute_qtilde(const AttnParams& p, const void* bk_lds, const floa
 
 // Tail of every attention kernel.  On entry Msh[g], Lsh[g], Ush[g*R+j] hold this workgroup's running
 // max (log2 domain), sum and un-normalised latent-space accumulator, visible to all threads.
-// If the sequence was split over several workgroups the partials go to the workspace and the last
-// workgroup to arrive (ticket) merges them in split order; then out = (u / l) B_V.
-// First half of the tail: the cross-workgroup merge.  Returns false in the workgroups that only delivered a partial
-// (they are done); true in the one that now holds the whole sequence's (m, l, u) in Msh, Lsh, Ush, visible to all of
-// its threads.
+// If the sequence was split over several workgroups, the workgroup of the LAST split finishes the sequence and the
+// others push their (m, l, u) to it: every value travels as one 8-byte word {value, tag}, written with an agent-scope
+// store, so a word is either absent (zero, or whatever an earlier launch left: never the tag) or complete, and the
+// finisher needs no ticket and no second trip: it asks for the words and asks again until they carry the tag.  Workgroups
+// are dispatched in order of their linear id and the splits of a (sequence, kv head) have increasing ids, so everything
+// the finisher waits for belongs to workgroups that were dispatched before it and wait for nothing themselves: the
+// wait ends whatever the number of workgroups the chip holds at a time (it is bounded all the same, and reports
+// through the status word).  The finisher folds the splits in split order (deterministic) and clears the words, so the
+// area is all zeros between launches.
+// Returns false in the workgroups that only delivered a partial (they are done); true in the one that now holds the
+// whole sequence's (m, l, u) in Msh, Lsh, Ush, visible to all of its threads.
+constexpr uint32_t kSplitTag = 0x53504C54u;
+WSVD_DEV unsigned long long split_word(float v) { return ((unsigned long long)kSplitTag << 32) | (unsigned long long)__float_as_uint(v); }
+
 template <int R>
 WSVD_DEV bool attn_merge_splits(const AttnParams& p, const WorkItem& w, float* Msh, float* Lsh, float* Ush, int* flag_sh) {
   const int tid = threadIdx.x;
   const int G = p.G;
-  if (w.n_splits > 1) {
-    // Cross-workgroup hand-off without cache-wide fences: partials are written and read with agent-scope
-    // (write-through / cache-bypassing) accesses, ordered by the workgroup barriers around the ticket.
+  if (w.n_splits <= 1) return true;
+  unsigned long long* const base = p.partials + (((size_t)w.b * p.Hq + (size_t)w.kv * G) * p.n_chunks) * (R + 2);
+  const size_t g_stride = (size_t)p.n_chunks * (R + 2);          // words between two heads of the group
+  if (w.chunk != w.n_splits - 1) {
     for (int i = tid; i < G * (R + 2); i += blockDim.x) {
       const int g = i / (R + 2), k = i % (R + 2);
       const float v = k == 0 ? Msh[g] : k == 1 ? Lsh[g] : Ush[g * R + (k - 2)];
-      agent_store(&p.partials[(((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks + w.chunk) * (R + 2) + k], v);
+      __hip_atomic_store(base + g * g_stride + (size_t)w.chunk * (R + 2) + k, split_word(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    wait_vmem_done();  // this thread's partial stores are acknowledged ...
-    __syncthreads();   // ... and so are everybody's, before the ticket is taken
-    if (tid == 0) {
-      int* t = p.tickets + (size_t)w.b * p.Hkv + w.kv;
-      const int old = __hip_atomic_fetch_add(t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int last = (old == w.n_splits - 1);
-      if (last) __hip_atomic_store(t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // all other tickets of this (b, kv) are taken
-      *flag_sh = last;
-    }
-    __syncthreads();
-    if (!*flag_sh) return false;
-    // The partials are read with cache-bypassing loads that cost a full memory round trip each, so they are
-    // requested a batch of 8 splits at a time (24 independent loads in flight) and folded in split order.
-    for (int i = tid; i < G * R; i += blockDim.x) {
-      const int g = i / R, j = i % R;
-      const float* base = p.partials + (((size_t)w.b * p.Hq + w.kv * G + g) * p.n_chunks) * (R + 2);
+    return false;
+  }
+  const int n_in = w.n_splits - 1;                               // splits pushed to this workgroup
+  constexpr int NI = 4;                                          // passes over the G * R <= 1024 items, >= 256 threads
+  float Mres[NI], Lres[NI], Ures[NI];
+  bool timed_out = false;
+#pragma unroll
+  for (int it = 0; it < NI; it++) {
+    const int i = tid + it * (int)blockDim.x;
+    if (i < G * R) {
+      const int g = i / R, jj = i % R;
+      const unsigned long long* src = base + g * g_stride;
       float M = -INFINITY, L = 0.f, U = 0.f;
-      for (int c0 = 0; c0 < w.n_splits; c0 += 8) {
+      for (int c0 = 0; c0 < n_in; c0 += 8) {
+        unsigned long long wm[8], wl[8], wu[8];
+        int budget = 1 << 14;
+        for (;;) {
+#pragma unroll
+          for (int k = 0; k < 8; k++) {
+            const unsigned long long* pc = src + (size_t)min(c0 + k, n_in - 1) * (R + 2);   // clamped: surplus slots are masked below
+            wm[k] = __hip_atomic_load(pc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            wl[k] = __hip_atomic_load(pc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            wu[k] = __hip_atomic_load(pc + 2 + jj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+          bool all = true;
+#pragma unroll
+          for (int k = 0; k < 8; k++)
+            all = all && (uint32_t)(wm[k] >> 32) == kSplitTag && (uint32_t)(wl[k] >> 32) == kSplitTag && (uint32_t)(wu[k] >> 32) == kSplitTag;
+          if (all) break;
+          if (--budget == 0) { timed_out = true; break; }
+          __builtin_amdgcn_s_sleep(4);
+        }
         float mv[8], lv[8], uv[8];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-          const float* pc = base + (size_t)min(c0 + k, w.n_splits - 1) * (R + 2);   // clamped: surplus slots are masked below
-          mv[k] = agent_load(pc);
-          lv[k] = agent_load(pc + 1);
-          uv[k] = agent_load(pc + 2 + j);
+          mv[k] = __uint_as_float((uint32_t)wm[k]); lv[k] = __uint_as_float((uint32_t)wl[k]); uv[k] = __uint_as_float((uint32_t)wu[k]);
         }
         float Mn = M;
 #pragma unroll
-        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, mv[k]);                          // a clamped duplicate cannot change a max
+        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, mv[k]);                        // a clamped duplicate cannot change a max
         // 0 on the first batch (M = -inf); a slot that saw no row in any split so far keeps M = Mn = -inf
         const float keep = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
         L *= keep; U *= keep;
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-          const float e = (c0 + k < w.n_splits && mv[k] != -INFINITY) ? __builtin_amdgcn_exp2f(mv[k] - Mn) : 0.f;
+          const float e = (c0 + k < n_in && mv[k] != -INFINITY) ? __builtin_amdgcn_exp2f(mv[k] - Mn) : 0.f;
           L = fmaf(lv[k], e, L);
           U = fmaf(uv[k], e, U);
         }
         M = Mn;
       }
-      Ush[i] = U;
-      if (j == 0) { Lsh[g] = L; Msh[g] = M; }
+      // this workgroup's own split comes last
+      const float mo = Msh[g];
+      const float Mn = fmaxf(M, mo);
+      const float keep = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
+      const float eo = mo == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mo - Mn);
+      Ures[it] = fmaf(Ush[i], eo, U * keep);
+      Lres[it] = fmaf(Lsh[g], eo, L * keep);
+      Mres[it] = Mn;
     }
-    __syncthreads();
   }
+  if (timed_out) atomicExch(p.err_word, (int)WSVD_E_HIP);       // never seen; keeps the wait finite
+  __syncthreads();                                               // every thread has read the words and the LDS values it needs
+#pragma unroll
+  for (int it = 0; it < NI; it++) {
+    const int i = tid + it * (int)blockDim.x;
+    if (i < G * R) {
+      const int g = i / R, jj = i % R;
+      Ush[i] = Ures[it];
+      if (jj == 0) { Lsh[g] = Lres[it]; Msh[g] = Mres[it]; }
+      unsigned long long* dst = base + g * g_stride;
+      for (int c = 0; c < n_in; c++) {
+        __hip_atomic_store(dst + (size_t)c * (R + 2) + 2 + jj, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (jj == 0) {
+          __hip_atomic_store(dst + (size_t)c * (R + 2), 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(dst + (size_t)c * (R + 2) + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  (void)flag_sh;
   return true;
 }
 

@@ -1538,7 +1538,6 @@ hipError_t wsvd_launch_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc& d, cons
   int* flags = (int*)ctx->ws + kWsStepFlagsInt;
   sp.a.flags = flags; sp.a.epoch = ctx->epoch; sp.a.err_word = ctx->err_word;
   sp.ap.fused = 1; sp.ap.epoch = ctx->epoch; sp.ap.flags = flags;
-  sp.ap.partials = sp.a.partials + (wsvd_attn_partial_floats(d) + 3) / 4 * 4;   // both kinds of partials are live at once
   sp.n_append = sp.ap.ES * sp.ap.Hkv * 2;
   sp.done = (int*)ctx->ws + kWsStepDoneInt;
   const int n_wg = sp.n_append + (int)(grid.x * grid.y * grid.z);

@@ -14,6 +14,7 @@ struct wsvd_options {
   int append_helpers = -1;  // helpers per unit of the default append kernel (-1 = automatic, 0 or 2)
   int fused_step = 0;       // wsvd_decode_step: 0 two launches, 1 the single-launch kernel where one exists, 2 that or UNSUPPORTED
   int linear_direct = 0;    // W4A8 linear layers read operands straight from memory (no LDS staging)
+  int static_limit_kib = 0; // wsvd_decode_attn_static: pretend the static array is this small (tests of the rejection; 0 = its size)
   int prefill_tiled = 0;    // the tiled prefill kernels also for small calls
   int project_shape = 0;    // kernel of the tiled prefill projection (0 = automatic)
 };
@@ -94,5 +95,6 @@ hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const v
 
 // workspace sizing shared by the API and the launchers
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
+size_t wsvd_attn_split_bytes(const wsvd_ctx* ctx, const wsvd_layer_desc& d, int max_seq_len);
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d);
 int wsvd_append_esplits(const wsvd_ctx* ctx, const wsvd_layer_desc& d);

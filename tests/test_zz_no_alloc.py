@@ -55,15 +55,25 @@ def test_static_scratch_attention_matches_the_workspace_one():
 
 
 def test_static_scratch_rejects_what_does_not_fit():
-    c = build_case("c3_small")
-    L = layer_for(c)
-    d = L.desc
-    huge = W.layer_desc(64, 32, 32, 128, 4096, 32, 65536, "i8", "bf16", "bf16", "i8")    # 71 MB of partials
-    q = torch.zeros((64, 32, 128), dtype=torch.int8, device="cuda")
+    """The split words a launch needs are bounded by what the chip runs at a time (a few MB at most with the default launch
+    policy), so the rejection is shown by shrinking the limit: the call below is valid in every other respect (all its
+    buffers have the sizes the descriptor promises), it is just not allowed the 300 KB of words its two splits need."""
+    c = build_case("c3_small", context=2000, batch=2)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    qd, qs, _ = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, sp.factor_dtype), as_dtype_dev(c.BV, sp.factor_dtype)
+    n_max = int(c.cache.seq_lens.max())
+    out = torch.full_like(L.out, float("nan"))
+    W.wsvd_ctx_set_option(L.ctx, "static_limit_kib", 65)           # counters (64 KiB) + 1 KiB
     with pytest.raises(W.WsvdError) as e:
-        W.wsvd_decode_attn_static(L.ctx, huge, q, L.k_meta, L.k_codes, L.k_codes, L.cache, 10, L.out)
+        W.wsvd_decode_attn_static(L.ctx, L.desc, qd, qs, BKd, BVd, L.cache, n_max, out)
     assert e.value.status == W.E_WORKSPACE
+    assert torch.isnan(out).all(), "a rejected call must not enqueue anything"
+    W.wsvd_ctx_set_option(L.ctx, "static_limit_kib", 0)
+    W.wsvd_decode_attn_static(L.ctx, L.desc, qd, qs, BKd, BVd, L.cache, n_max, out)     # the same call fits the real array
+    assert W.wsvd_check(L.ctx) == 0 and torch.isfinite(out).all()
     with pytest.raises(W.WsvdError) as e:         # the other host-side checks are wsvd_decode_attn's
-        W.wsvd_decode_attn_static(L.ctx, d, q, None, L.k_codes, L.k_codes, L.cache, 10, L.out)
+        W.wsvd_decode_attn_static(L.ctx, L.desc, qd, None, BKd, BVd, L.cache, n_max, out)
     assert e.value.status == W.E_NULL
     L.close()
