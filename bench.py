@@ -62,6 +62,8 @@ def parse():
                          "into W_O, SwiGLU FFN); prefill: building the c3 cache from hidden states, 64 tokens per launch "
                          "shared: the contrast scheme, decode attention over one shared rank-1024 latent per token "
                          "(secondary lines, same JSON shape)")
+    ap.add_argument("--two-launch-store", action="store_true",
+                    help="c5: wsvd_latent_store + wsvd_decode_attn instead of the single-launch wsvd_decode_attn_store")
     ap.add_argument("--linear-direct", action="store_true",
                     help="W4A8 linear layers read their operands straight from memory instead of staging them through LDS (tuning)")
     ap.add_argument("--project-shape", type=int, default=0, choices=[0, 1, 2, 21, 24, 42, 44],
@@ -466,8 +468,13 @@ def run_c5(args, np, torch, W, WI):
                 y = xs_buf[l & 1]
                 W.wsvd_quantize_act_i8(ctx, x, W.F32, B, E, xq, xsc)
                 W.wsvd_linear_w4a8_split(ctx, xq, xsc, Ly["wqkv"], Ly["wqkvs"], B, E, Hq * d + 2 * Hkv * r, Hq * d, q, lat)
-                W.wsvd_latent_store(ctx, desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, Ly["cache"])
-            W.wsvd_decode_attn(ctx, desc, q, None, BKd, BVd, Ly["cache"], t_cap, o)
+                if args.two_launch_store:
+                    W.wsvd_latent_store(ctx, desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, Ly["cache"])
+                    W.wsvd_decode_attn(ctx, desc, q, None, BKd, BVd, Ly["cache"], t_cap, o)
+                else:
+                    W.wsvd_decode_attn_store(ctx, desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, q, None, BKd, BVd, Ly["cache"], t_cap, o)
+            else:
+                W.wsvd_decode_attn(ctx, desc, q, None, BKd, BVd, Ly["cache"], t_cap, o)
             if not attn_only:
                 W.wsvd_quantize_act_i8(ctx, o, W.F32, B, Hq * d, oq, osc)
                 W.wsvd_linear_w4a8(ctx, oq, osc, Ly["wo"], Ly["wos"], B, Hq * d, E, y)
@@ -523,7 +530,9 @@ def run_c5(args, np, torch, W, WI):
         "config": {"workload": "c5: 28-layer grouped-query W4A8 attention block, B=32 Hq=28 Hkv=4 d_head=128 d_model=3584 r=64 T=8192",
                    "batch": B, "q_heads": Hq, "kv_heads": Hkv, "d_head": d, "d_model": E, "rank": r, "context": T, "layers": NL,
                    "launch": "hip_graph_replay" if use_graph else "eager",
-                   "step": "per layer: quantize_act_i8, linear_w4a8_split (W_Q | A_K | A_V), latent_store, decode_attn, quantize_act_i8, linear_w4a8 (W_O)"},
+                   "step": "per layer: quantize_act_i8, linear_w4a8_split (W_Q | A_K | A_V), " +
+                           ("latent_store, decode_attn" if args.two_launch_store else "decode_attn_store (latent store + attention, one launch)") +
+                           ", quantize_act_i8, linear_w4a8 (W_O)"},
         "roofline": {"kernel": "k_attn_gqa<64> (decode attention, 7 query heads per kv head, int8 latents)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES_C5,
@@ -925,7 +934,8 @@ def run_timeline(args, np, torch, W, WI):
     if not os.path.exists(WB.LIB_TIMELINE):
         WB.build(verbose=False, timeline=True)
     W.use_library(WB.LIB_TIMELINE)
-    sp = WI.spec("c3")
+    wl = "c5" if args.workload == "c5" else "c3"          # c5: the grouped-query kernel (28 query / 4 kv heads, rank 64, 8192 rows)
+    sp = WI.spec(wl)
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
     t_cap = (T + 63) // 64 * 64
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "i8", "f32", 0.0)
@@ -934,7 +944,7 @@ def run_timeline(args, np, torch, W, WI):
     W.wsvd_set_workspace(ctx, ws)
     cb, mb = W.wsvd_cache_bytes(desc)
     g = torch.Generator(device="cuda"); g.manual_seed(7)
-    n_sets = args.sets
+    n_sets = args.sets if wl == "c3" else 6
     sl = torch.full((B,), T, dtype=torch.int32, device="cuda")
     caches = []
     for _ in range(n_sets):
@@ -964,7 +974,8 @@ def run_timeline(args, np, torch, W, WI):
         assert W.wsvd_check(ctx, stream) == 0
     us_launch = e0.elapsed_time(e1) * 1e3 / n_keep
     names = ["kernel entry", "first loads issued", "factors staged", "query limbs ready", "first tile consumed",
-             "last tile consumed", "wave's partial written", "workgroup barrier passed", "output stored"]
+             "last tile consumed", "wave's partial written", "workgroup barrier passed", "output stored",
+             "workgroup merge done", "(output products done)", "splits merged (finishing workgroups)"]
     lines = []
     prev_end = None
     summary = []
@@ -990,8 +1001,9 @@ def run_timeline(args, np, torch, W, WI):
                          f"p90 {np.percentile(rel, 90):6.2f}  max {rel.max():6.2f} us")
         summary.append(rows)
     print("\n".join(lines))
-    print(json.dumps({"timeline": "k_attn_mfma at c3 (B=16 H=32 r=32 T=2048, int8), eager back-to-back launches, "
-                                  "stamps = 100 MHz wall clock, us relative to the launch's first wavefront",
+    print(json.dumps({"timeline": ("k_attn_mfma at c3 (B=16 H=32 r=32 T=2048, int8)" if wl == "c3" else
+                                   "k_attn_gqa at c5 (B=32, 28 query / 4 kv heads, r=64, T=8192, int8)") +
+                                  ", eager back-to-back launches, stamps = 100 MHz wall clock, us relative to the launch's first wavefront",
                       "avg_launch_us_with_stamps": round(us_launch, 3), "launches": summary}))
     W.wsvd_destroy(ctx)
 

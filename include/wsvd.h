@@ -167,13 +167,27 @@ wsvd_status wsvd_decode_attn(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const v
                              void *out, void *hip_stream);
 
 /*
+ * wsvd_latent_store followed by wsvd_decode_attn (Section 3.4, decoding pipeline: store the new token's latents, then
+ * attend over the cache including them) as ONE call: c_K, c_V, ld as for wsvd_latent_store; q, q_scale, B_K, B_V, out
+ * as for wsvd_decode_attn; max_seq_len bounds the lengths AFTER the store (>= 1).  Results are those of the two calls.
+ * With I8 latents and 5 to 8 query heads per kv head it is a single launch: the workgroup whose context chunk holds
+ * the new row quantises and stores it, keeps a copy for the wavefront that consumes the row's tile, and the last
+ * workgroup of a sequence to finish advances its length; every other combination runs the two kernels back to back.
+ * A sequence already at t_cap is left unchanged, is attended over its t_cap rows, and WSVD_E_CAPACITY is recorded in
+ * the device status word.
+ */
+wsvd_status wsvd_decode_attn_store(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const float *c_K, const float *c_V, int64_t ld,
+                                   const void *q, const void *q_scale, const void *B_K, const void *B_V,
+                                   wsvd_cache *cache, int32_t max_seq_len, void *out, void *hip_stream);
+
+/*
  * wsvd_decode_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results as
  * wsvd_decode_attn, but the words through which the splits of a long sequence reach the workgroup that merges them
  * live in an array that is part of the library image (8 MiB of device memory per GPU the library runs on, held until
  * the process ends) instead of the workspace set with wsvd_set_workspace, which is neither needed nor touched.  The
  * call allocates nothing and frees nothing.
- *   Limit: 65536 + 8 * batch * n_q_heads * n_chunks * (rank + 2) bytes must fit in the 8 MiB, n_chunks being the
+ *   Limit: 65536 + 8 * batch * n_q_heads * n_chunks * (max(rank, d_head) + 2) bytes must fit in the 8 MiB, n_chunks being the
  *   number of context splits the launch policy picks for this call (1 when batch * n_kv_heads alone fills the chip:
  *   then the term is 0; at most ceil(max_seq_len / 256)); all five documented workloads fit; WSVD_E_WORKSPACE
  *   otherwise, nothing enqueued.

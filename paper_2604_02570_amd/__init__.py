@@ -24,7 +24,7 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
-           "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_static", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
+           "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_store", "wsvd_decode_attn_static", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
@@ -89,6 +89,8 @@ def lib():
         L.wsvd_decode_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                        POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_decode_attn_static.argtypes = L.wsvd_decode_attn.argtypes
+        L.wsvd_decode_attn_store.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p,
+                                             c_void_p, POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_decode_attn_rope.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                             POINTER(Cache), c_int32, c_float, c_void_p, c_void_p]
         L.wsvd_decode_step.argtypes = [c_void_p, POINTER(LayerDesc)] + [c_void_p] * 8 + [POINTER(Cache), c_int32, c_void_p, c_void_p]
@@ -221,6 +223,11 @@ def wsvd_latent_store(ctx, desc, c_K, c_V, ld, cache, stream=None):
 def wsvd_decode_attn(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
     _ck(lib().wsvd_decode_attn(ctx, byref(desc), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V), byref(cache),
                                int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn")
+
+
+def wsvd_decode_attn_store(ctx, desc, c_K, c_V, ld, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
+    _ck(lib().wsvd_decode_attn_store(ctx, byref(desc), _ptr(c_K), _ptr(c_V), int(ld), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V),
+                                     byref(cache), int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn_store")
 
 
 def wsvd_decode_attn_static(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):

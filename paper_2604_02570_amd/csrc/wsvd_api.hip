@@ -114,7 +114,9 @@ wsvd_status check_cache(const wsvd_layer_desc& d, const wsvd_cache* c) {
 // the largest number of chunks a launch policy can choose (chunks are at least 256 rows)
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d) {
   const size_t max_chunks = (size_t)(d.t_cap + 255) / 256;
-  return 2 * (size_t)d.batch * d.n_q_heads * max_chunks * (d.rank + 2);
+  // (the kernels for 5..8 query heads per kv head hand over up-projected vectors of d_head elements instead of rank)
+  const size_t vec = (size_t)(d.rank > d.d_head ? d.rank : d.d_head) + 2;
+  return 2 * (size_t)d.batch * d.n_q_heads * max_chunks * vec;
 }
 
 extern "C" {
@@ -386,6 +388,43 @@ wsvd_status wsvd_decode_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
   hipError_t e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_decode_attn_store(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const float* c_K, const float* c_V, int64_t ld,
+                                   const void* q, const void* q_scale, const void* B_K, const void* B_V, wsvd_cache* cache,
+                                   int32_t max_seq_len, void* out, void* hip_stream) {
+  if (!ctx || !c_K || !c_V || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (ld < (int64_t)desc->n_kv_heads * desc->rank) return WSVD_E_SHAPE;
+  if (desc->rank > 64) return WSVD_E_UNSUPPORTED;
+  if (((uintptr_t)c_K & 3u) || ((uintptr_t)c_V & 3u)) return WSVD_E_ALIGN;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 1) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int G = desc->n_q_heads / desc->n_kv_heads;
+  if (desc->latent_dtype == WSVD_I8 && G > 4 && desc->batch <= 8192) {
+    AttnParams p;
+    dim3 grid;
+    int threads;
+    wsvd_attn_plan(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, p, grid, threads, 0);
+    p.new_k = c_K; p.new_v = c_V; p.new_ld = (long)ld;
+    p.done = (int*)ctx->ws;                   // one counter per sequence, zero between launches
+    p.seq_lens_rw = cache->seq_lens;
+    hipError_t e = wsvd_launch_attn_gqa_store(p, desc->rank, grid, threads, s);
+    if (e != hipErrorNotSupported) return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+  }
+  // no single-launch kernel for this combination: the two calls back to back on the stream
+  hipError_t e = wsvd_launch_latent_store(ctx, *desc, c_K, c_V, ld, *cache, s);
+  if (e == hipSuccess) e = wsvd_launch_attn(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, s);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
@@ -714,7 +753,8 @@ size_t wsvd_attn_split_bytes(const wsvd_ctx* ctx, const wsvd_layer_desc& d, int 
   dim3 grid;
   int threads;
   wsvd_attn_plan(ctx, d, nullptr, nullptr, nullptr, nullptr, wsvd_cache{}, max_seq_len, nullptr, p, grid, threads, 0);
-  return p.n_chunks > 1 ? (size_t)d.batch * d.n_q_heads * p.n_chunks * (d.rank + 2) * 8 : 0;
+  const size_t vec = (size_t)(d.rank > d.d_head ? d.rank : d.d_head) + 2;
+  return p.n_chunks > 1 ? (size_t)d.batch * d.n_q_heads * p.n_chunks * vec * 8 : 0;
 }
 
 hipError_t wsvd_launch_attn(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,

@@ -35,6 +35,13 @@ struct AttnParams {
   // s = token s / Gr, head s % Gr; token i sits at row seq_lens - n_after - nq + i and sees the rows up to its own
   int nq, Gr, n_after;
   long long* timeline;       // profiling build: stamp buffer (see WSVD_STAMP), else null
+  // store-and-attend variant only: the new token's fp32 latents [B][new_ld] (kv head h at h * R), the per-sequence
+  // counters of finished workgroups, the lengths to advance
+  const float* new_k;
+  const float* new_v;
+  long new_ld;
+  int* done;
+  int* seq_lens_rw;
 };
 
 struct WorkItem {
@@ -302,6 +309,7 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
   const int tid = threadIdx.x;
   const int G = p.G;
   if (!attn_merge_splits<R>(p, w, Msh, Lsh, Ush, flag_sh)) return;
+  WSVD_STAMP(p.timeline, ((int)blockIdx.z * (int)gridDim.y + (int)blockIdx.y) * (int)gridDim.x + (int)blockIdx.x, threadIdx.x >> 6, 11);
   if (!bv_lds) {
     // latent-output variant: the normalised accumulator itself (B_V lives in the output projection)
     for (int i = tid; i < G * R; i += blockDim.x)

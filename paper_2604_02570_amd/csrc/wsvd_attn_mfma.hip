@@ -962,8 +962,12 @@ WSVD_DEV void load_gqa_tile(GqaTile<R>& t, const uint8_t* kplane, const uint8_t*
 // LATENT: the Q latent comes in and the latent-space output goes out (no factor is read); launched with exactly NT
 // threads.
 // MULTI: the query slots are nq consecutive tokens x Gr heads; each slot only sees the rows up to its token's own.
-template <int R, int NT, bool LATENT = false, bool MULTI = false>
-__global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
+// STORE: the new token's K and V latents of this launch arrive as fp32 (p.new_k / p.new_v); the workgroup whose chunk
+// holds row seq_lens[b] quantises and stores them (as wsvd_latent_store would) and the attention runs over
+// seq_lens[b] + 1 rows, the new row being patched into the registers of the wave that consumes its tile.  The lengths
+// are advanced by the caller kernel once every workgroup of the sequence has finished.
+template <int R, int NT, bool LATENT, bool MULTI, bool STORE>
+WSVD_DEV void attn_gqa_body(const AttnParams& p) {
   constexpr int KK = R / 32;
   constexpr int NWMAX = NT / 64;
   constexpr int FIT = R / 16;
@@ -977,19 +981,39 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   __shared__ float wm[NWMAX][GS], wls[NWMAX][GS];
   __shared__ float wu[NWMAX][GS][R];
   __shared__ float Msh[GS], Lsh[GS], Ush[GS * R];
+  __shared__ __attribute__((aligned(16))) float Osh[LATENT ? 4 : GS * 128];   // un-normalised outputs of this workgroup's rows
   __shared__ int flag_sh;
+  __shared__ __attribute__((aligned(16))) uint8_t new_codes[2][STORE ? R : 16];   // STORE: the row stored by this launch, K | V
+  __shared__ uint16_t new_scale[2];
 
   const int n_raw = p.seq_lens[blockIdx.z];
   const uint32_t qs_raw = q_scale_raw(p, blockIdx.z);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
   const int hf = lane >> 5, l32 = lane & 31;
   const int G = p.G;
+  [[maybe_unused]] long long* const tl = p.timeline;
+  [[maybe_unused]] const int tl_wg = ((int)blockIdx.z * (int)gridDim.y + (int)blockIdx.y) * (int)gridDim.x + (int)blockIdx.x;
+  WSVD_STAMP(tl, tl_wg, wave, 0);
   const size_t ph = (size_t)blockIdx.z * p.Hkv + blockIdx.x;
   const size_t plane_bytes = (size_t)p.t_cap * R;
   const uint8_t* kplane = p.k_codes + ph * plane_bytes;
   const uint8_t* vplane = p.v_codes + ph * plane_bytes;
   const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap;
   const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap;
+  // STORE: rows attended = the old length + the row stored by this launch (a full sequence stays as it is and reports)
+  const bool has_new = STORE && n_raw >= 0 && n_raw < p.t_cap;
+  const int n_att = has_new ? n_raw + 1 : n_raw;
+  const int chunk_tiles0 = p.chunk_rows >> 6;
+  const int new_tile = n_raw >> 6;
+  const bool own_new = has_new && new_tile >= (int)blockIdx.y * chunk_tiles0 && new_tile < ((int)blockIdx.y + 1) * chunk_tiles0;
+  float new_c[2] = {0.f, 0.f};
+  if constexpr (STORE) {
+    if (n_raw >= p.t_cap && tid == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
+    if (own_new && wave == NW - 1 && lane < R) {          // requested first, used after the absorption's loads are out
+      new_c[0] = p.new_k[(size_t)blockIdx.z * p.new_ld + blockIdx.x * R + lane];
+      new_c[1] = p.new_v[(size_t)blockIdx.z * p.new_ld + blockIdx.x * R + lane];
+    }
+  }
 
   // ---- query absorption q~ = B_K q on the matrix cores, operands straight from global memory (no staging):
   // D[j][g] = sum_c B_K[j][c] q[g][c] as V_MFMA_F32_32X32X16_BF16 with A = a 32 x 16 block of B_K (row-major, so a
@@ -1052,6 +1076,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   // and with every wave of the CU queueing two tiles that alone takes a couple of microseconds for the last one.
   const int spec_last = min(((int)blockIdx.y + 1) * chunk_tiles, p.t_cap >> 6) - 1;
   load_gqa_tile<R>(buf[0], kplane, vplane, kmeta, vmeta, min(T, spec_last), lane);
+  WSVD_STAMP(tl, tl_wg, wave, 1);
 
   if constexpr (LATENT) {
     float* qflat = &qpart[0][0][0];                     // [4][G * R] partial sums
@@ -1106,7 +1131,35 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   }
 #pragma unroll
   for (int i = 1; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+  if constexpr (STORE) {
+    if (own_new && wave == NW - 1) {                      // wave-uniform
+      if (R == 64 || lane < R) {
+        // the cache row for later launches (the rule and the layout of wsvd_latent_store), and a copy in LDS for this
+        // one: the tile that holds the row is fetched like any other, possibly before these stores land, and the
+        // wave that consumes it overwrites the row's bytes in its registers from the copy
+        AppendParams ap = {};
+        ap.codes[0] = const_cast<uint8_t*>(p.k_codes); ap.codes[1] = const_cast<uint8_t*>(p.v_codes);
+        ap.meta[0] = const_cast<uint16_t*>(p.k_meta); ap.meta[1] = const_cast<uint16_t*>(p.v_meta);
+        ap.Hkv = p.Hkv; ap.t_cap = p.t_cap; ap.latent_dtype = WSVD_I8;
+#pragma unroll
+        for (int pl = 0; pl < 2; pl++) {
+          store_row_lanes<R>(ap, pl, (int)blockIdx.z, (int)blockIdx.x, n_raw, lane, new_c[pl]);
+          const float a = lanes_max<R>(fabsf(new_c[pl]));
+          uint16_t sh = 0x3C00u;
+          if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
+          const float sc = f16_bits_to_f32(sh);
+          new_codes[pl][lane] = (uint8_t)(int8_t)(int)fminf(fmaxf(__builtin_rintf(new_c[pl] / sc), -127.f), 127.f);
+          if (lane == 0) new_scale[pl] = sh;
+        }
+      }
+    }
+  }
   __syncthreads();
+  if constexpr (STORE) {
+    // every wave of this workgroup holds its copy of the old length by now (it decided own_new with it above): say so.
+    // No reply is waited for.
+    if (tid == 0) __hip_atomic_fetch_add(p.done + blockIdx.z, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   // limbs of all 8 slots; slots past G are zero so they contribute nothing and cost nothing extra
   for (int idx = tid; idx < GS * R; idx += blockDim.x) {
     const int g = idx / R, j = idx % R;
@@ -1132,6 +1185,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   }
   __syncthreads();
 
+  WSVD_STAMP(tl, tl_wg, wave, 3);
   v4i aop[KK];
   {
     const int a = l32 >> 3, hh = (l32 >> 2) & 1, limb = l32 & 3;
@@ -1143,7 +1197,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     }
   }
   const float qs = q_scale_value(p, blockIdx.z, qs_raw);
-  const WorkItem w = decode_work(p, MULTI ? n_raw - p.n_after : n_raw);
+  const WorkItem w = decode_work(p, MULTI ? n_raw - p.n_after : n_att);
   if (w.n == 0) { write_zero_outputs(p, w); return; }
   if (!w.active) return;
   const int tile_end = (w.row_end + 63) >> 6;
@@ -1180,6 +1234,30 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   const int wr_q = (l32 >> 3) + 4 * ((l32 >> 2) & 1), wr_limb = min(l32 & 3, 2);
 
   auto compute = [&](GqaTile<R>& t, int tile) {
+    if constexpr (STORE) {
+      if (own_new && tile == new_tile) {                   // wave-uniform: put the row stored by this launch into the tile
+        const int ti = n_raw & 63, blk = ti >> 5, tn = ti & 31;
+#pragma unroll
+        for (int b2 = 0; b2 < 2; b2++) {
+          if (b2 == blk) {
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++) {
+              // K: lane (token tn, dim half hf) holds dims 32 kk + 16 hf .. + 15 of its token
+              if (l32 == tn) t.k[kk][b2] = *(const v4i*)&new_codes[0][32 * kk + 16 * hf];
+              // V: lane (dim 32 kk + l32, token half hf) holds 16 tokens of its dim: byte tn % 16 of the half tn / 16
+              if (hf == (tn >> 4)) {
+                const uint32_t byte = new_codes[1][32 * kk + l32];
+                const int dw = (tn & 15) >> 2, sh8 = 8 * (tn & 3);
+#pragma unroll
+                for (int e = 0; e < 4; e++)
+                  if (e == dw) t.v[kk][b2][e] = (int)(((uint32_t)t.v[kk][b2][e] & ~(0xFFu << sh8)) | (byte << sh8));
+              }
+            }
+            if (l32 == tn) { t.kmeta[b2] = new_scale[0]; t.vmeta[b2] = new_scale[1]; }
+          }
+        }
+      }
+    }
     since_flush += 2;
     if (since_flush >= 2 * kMaxTilesPerFlush) {
       since_flush = 0;
@@ -1244,6 +1322,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < DEPTH; i++) {
       compute(buf[i], T + (done + i) * NW);
+      if (done == 0 && i == 0) WSVD_STAMP(tl, tl_wg, wave, 4);
       load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
     }
     done += DEPTH;
@@ -1260,6 +1339,7 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
   for (int i = 0; i < DEPTH; i++)
     if (done + i < n) compute(buf[i], T + (done + i) * NW);
 
+  WSVD_STAMP(tl, tl_wg, wave, 5);
   // B_V is only needed by the epilogue: requested now (it is shared by many workgroups and sits in L2), it arrives
   // while the slower waves finish
   const int fac16 = R * p.d * 2 / 16;
@@ -1274,8 +1354,10 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
 #pragma unroll
     for (int jj = 0; jj < KK; jj++) wu[wave][a + 4 * hf][jj * 32 + l32] = u[a][jj];
   }
+  WSVD_STAMP(tl, tl_wg, wave, 6);
   if constexpr (!LATENT) stage_commit<FIT>(stv, bv_lds, fac16);
   __syncthreads();
+  WSVD_STAMP(tl, tl_wg, wave, 7);
   for (int idx = tid; idx < G * R; idx += blockDim.x) {
     const int g = idx / R, j = idx % R;
     float M = wm[0][g];
@@ -1290,7 +1372,67 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
     if (j == 0) { Msh[g] = M; Lsh[g] = L; }
   }
   __syncthreads();
-  attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, LATENT ? nullptr : (const void*)bv_lds);
+  WSVD_STAMP(tl, tl_wg, wave, 9);
+  if constexpr (LATENT) {
+    attn_tail<R, 2>(p, w, Msh, Lsh, Ush, &flag_sh, nullptr);
+  } else {
+    // The up-projection is linear, so it is applied to this workgroup's own un-normalised accumulator BEFORE the splits
+    // meet: O[g][c] = sum_j U[g][j] B_V[j][c].  The products of all splits then run side by side, and what is left for
+    // the workgroup that finishes the sequence, once the other splits' words have arrived, is a weighted sum of short
+    // vectors, one division and the store.  Wave g takes query slot g; lane = column pair (one LDS dword of B_V carries
+    // both columns: consecutive lanes, consecutive dwords), U[g][j] is a broadcast read.
+    const int half_d = p.d >> 1;
+    const uint32_t* bv32 = (const uint32_t*)bv_lds;
+    for (int g = wave; g < G; g += NW) {
+      if (lane < half_d) {
+        float a0 = 0.f, a1 = 0.f;
+#pragma unroll 8
+        for (int j = 0; j < R; j++) {
+          const uint32_t bb = bv32[j * half_d + lane];
+          const float uj = Ush[g * R + j];
+          a0 = fmaf(uj, __uint_as_float(bb << 16), a0);
+          a1 = fmaf(uj, __uint_as_float(bb & 0xFFFF0000u), a1);
+        }
+        float2 o2; o2.x = a0; o2.y = a1;
+        *(float2*)&Osh[g * p.d + 2 * lane] = o2;
+      }
+    }
+    __syncthreads();
+    WSVD_STAMP(tl, tl_wg, wave, 10);
+    const bool fin = p.d == 128 ? attn_merge_splits<128>(p, w, Msh, Lsh, Osh, &flag_sh) : attn_merge_splits<64>(p, w, Msh, Lsh, Osh, &flag_sh);
+    if (fin) {
+      WSVD_STAMP(tl, tl_wg, wave, 11);
+      for (int i = tid; i < G * p.d; i += blockDim.x) {
+        const float L = Lsh[i / p.d];
+        p.out[((size_t)w.b * p.Hq + (size_t)w.kv * G) * p.d + i] = L > 0.f ? Osh[i] / L : 0.f;   // no visible row at all: zeros
+      }
+    }
+  }
+  WSVD_STAMP(tl, tl_wg, wave, 8);
+}
+
+template <int R, int NT, bool LATENT = false, bool MULTI = false>
+__global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
+  attn_gqa_body<R, NT, LATENT, MULTI, false>(p);
+}
+
+// latent store + attention in one launch.  The length of a sequence may advance as soon as every workgroup of the
+// sequence has read the old one: each says so early in its life (a counter, no reply awaited), and the workgroup with
+// the highest id of the sequence, which is dispatched after all the others, waits for the count on its way out (it is
+// complete long before, unless that workgroup had no rows to attend), clears it and writes the new length.
+template <int R, int NT>
+__global__ __launch_bounds__(NT) void k_attn_gqa_store(AttnParams p) {
+  attn_gqa_body<R, NT, false, false, true>(p);
+  if (blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1 && threadIdx.x == 0) {
+    int* cnt = p.done + blockIdx.z;
+    const int want = (int)(gridDim.x * gridDim.y);
+    int budget = 1 << 16;
+    while (__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want && --budget > 0) __builtin_amdgcn_s_sleep(8);
+    if (budget == 0) atomicExch(p.err_word, (int)WSVD_E_HIP);     // never seen; keeps the wait finite
+    __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int n = p.seq_lens[blockIdx.z];
+    if (n >= 0 && n < p.t_cap) p.seq_lens_rw[blockIdx.z] = n + 1;
+  }
 }
 
 // Several query heads per kv head keep per-head state in registers: those instantiations are bounded to 8 waves per
@@ -1357,6 +1499,16 @@ static hipError_t launch_m_wide(const AttnParams& p, dim3 grid, int threads, hip
   if (p.G != 1) return hipErrorNotSupported;
   if (threads > 256 || threads % 64) return hipErrorInvalidValue;
   hipLaunchKernelGGL((k_attn_mfma<R, 1, false, 256>), grid, dim3(threads), 0, s, p);
+  return hipGetLastError();
+}
+
+// latent store + attention in one launch: 5..8 query heads per kv head, I8 latents
+hipError_t wsvd_launch_attn_gqa_store(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (p.G <= 4 || p.G > 8) return hipErrorNotSupported;
+  if (threads > 512 || threads < 256 || threads % 64) return hipErrorInvalidValue;
+  if (rank == 32) hipLaunchKernelGGL((k_attn_gqa_store<32, 512>), grid, dim3(threads), 0, s, p);
+  else if (rank == 64) hipLaunchKernelGGL((k_attn_gqa_store<64, 512>), grid, dim3(threads), 0, s, p);
+  else return hipErrorNotSupported;
   return hipGetLastError();
 }
 

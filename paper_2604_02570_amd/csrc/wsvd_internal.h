@@ -95,6 +95,7 @@ hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const v
 
 // workspace sizing shared by the API and the launchers
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
+hipError_t wsvd_launch_attn_gqa_store(const struct AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
 size_t wsvd_attn_split_bytes(const wsvd_ctx* ctx, const wsvd_layer_desc& d, int max_seq_len);
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d);
 int wsvd_append_esplits(const wsvd_ctx* ctx, const wsvd_layer_desc& d);

@@ -8,7 +8,7 @@ import torch
 import oracle as O
 import paper_2604_02570_amd as W
 from cases import build_block_case
-from harness import DeviceLayer, as_dtype_dev, dev, err_stats
+from harness import DeviceLayer, as_dtype_dev, dev, err_stats, q_to_device
 from test_gpu_parity import _append_compare, check_out, layer_for
 
 pytestmark = pytest.mark.gpu
@@ -143,9 +143,10 @@ def _oracle_block(c, heads=None):
                                   O.pack_w4(c.wo[0]), c.wo[1], sp.n_q_heads, sp.d_head, c.sm_scale, heads=heads)
 
 
-def _run_block(c, L, stagewise, ref=None, before=None):
+def _run_block(c, L, stagewise, ref=None, before=None, one_launch_store=False):
     """The GPU chain.  stagewise=True re-seeds every stage with the oracle's output of the previous one, so each
-    stage is compared on identical inputs; False lets the GPU's own intermediates flow through."""
+    stage is compared on identical inputs; False lets the GPU's own intermediates flow through.  one_launch_store
+    (chained only): the store and the attention go through wsvd_decode_attn_store, as the benchmark's chain does."""
     sp = c.sp
     B, E, Hq, Hkv, d, r = sp.batch, sp.d_model, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.rank
     u16 = lambda a: dev(np.asarray(a, np.float16).view(np.uint16))
@@ -172,8 +173,16 @@ def _run_block(c, L, stagewise, ref=None, before=None):
         a, rmax, l2 = err_stats(got.astype(np.float64), want)
         print(f"block {what}: rel_max={rmax:.3e} rel_l2={l2:.3e}", flush=True)
         assert rmax <= 1e-6 and l2 <= 1e-6
-    # 3. store
-    W.wsvd_latent_store(L.ctx, L.desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, L.cache)
+    # 3. store (one_launch_store: together with 4.)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    if one_launch_store:
+        assert not stagewise
+        L.out.fill_(float("nan"))
+        W.wsvd_decode_attn_store(L.ctx, L.desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, q.view(B, Hq, d), None, BKd, BVd, L.cache,
+                                 int(before.max()) + 1, L.out)
+        assert (L.seq_lens.cpu().numpy() == before + 1).all()
+    else:
+        W.wsvd_latent_store(L.ctx, L.desc, lat, lat[:, Hkv * r:], 2 * Hkv * r, L.cache)
     assert W.wsvd_check(L.ctx) == 0
     flips = _append_compare(L, c.cache, ref["cK"], ref["cV"], before, sp.latent_dtype)
     print(f"block store: boundary flips accepted = {flips}", flush=True)
@@ -181,9 +190,8 @@ def _run_block(c, L, stagewise, ref=None, before=None):
     if stagewise:
         L.upload(c.cache)
     # 4. attention with the fp32 query as it left the projection
-    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     qd = dev(ref["q"].astype(np.float32).reshape(B, Hq, d)) if stagewise else q.view(B, Hq, d)
-    attn = L.attend(qd, None, BKd, BVd, int(c.cache.seq_lens.max()))
+    attn = L.out.cpu().numpy().astype(np.float64) if one_launch_store else L.attend(qd, None, BKd, BVd, int(c.cache.seq_lens.max()))
     check_out(attn, ref["attn"], "i8", f"block attention ({'stagewise' if stagewise else 'chained'})")
     # 5. int8 of the attention output, W_O
     o_in = dev(ref["attn"].reshape(B, Hq * d).astype(np.float32)) if stagewise else L.out.view(B, Hq * d)
@@ -204,12 +212,75 @@ def _run_block(c, L, stagewise, ref=None, before=None):
         assert a <= 2e-2 and l2 <= 1e-3
 
 
-@pytest.mark.parametrize("stagewise", [True, False], ids=["stagewise", "chained"])
-def test_block_c5_small(stagewise):
+@pytest.mark.parametrize("stagewise,one_launch", [(True, False), (False, False), (False, True)],
+                         ids=["stagewise", "chained", "chained-store-and-attend"])
+def test_block_c5_small(stagewise, one_launch):
     c = build_block_case("c5_small")
     L = layer_for(c); L.upload(c.cache)
-    _run_block(c, L, stagewise)
+    _run_block(c, L, stagewise, one_launch_store=one_launch)
     L.close()
+
+
+@pytest.mark.parametrize("name", ["c5_small", "c3_small", "c4_small"])
+def test_store_and_attend_equals_the_two_calls(name):
+    """wsvd_decode_attn_store against wsvd_latent_store + wsvd_decode_attn on a twin layer: the same cache bytes and
+    lengths afterwards; outputs within the bars of the oracle (a single launch attends the new row's tile last, so
+    the sums differ in order) and of each other.  c5_small takes the single-launch kernel (7 query heads per kv
+    head), the other two the two-launch route of the same entry point.  Ragged lengths, one sequence on a tile edge,
+    one empty, one full."""
+    from cases import build_case
+    c = build_case(name)
+    sp = c.sp
+    lens = c.cache.seq_lens.copy()
+    lens[0] = 64 if sp.batch > 1 else lens[0]                 # the new row opens a tile
+    if sp.batch > 2:
+        lens[1] = 0                                            # the new row is the only one
+    c.cache.seq_lens[:] = lens
+    rng = np.random.default_rng(11)
+    n_lat = sp.n_kv_heads * sp.rank
+    lat = (rng.standard_normal((sp.batch, 2 * n_lat)) * 0.7).astype(np.float32)
+    qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    outs, caches = [], []
+    for fused in (False, True):
+        L = layer_for(c); L.upload(c.cache)
+        d = dev(lat)
+        n_max = int(lens.max()) + 1
+        if fused:
+            L.out.fill_(float("nan"))
+            W.wsvd_decode_attn_store(L.ctx, L.desc, d, d[:, n_lat:], 2 * n_lat, qd, qs, BKd, BVd, L.cache, n_max, L.out)
+            torch.cuda.synchronize()
+            o = L.out.cpu().numpy().astype(np.float64)
+        else:
+            W.wsvd_latent_store(L.ctx, L.desc, d, d[:, n_lat:], 2 * n_lat, L.cache)
+            o = L.attend(qd, qs, BKd, BVd, n_max)
+        assert W.wsvd_check(L.ctx) == 0
+        assert (L.seq_lens.cpu().numpy() == lens + 1).all()
+        outs.append(o)
+        caches.append([L.download(pl, 0, n_max) for pl in (0, 1)])
+        if fused:                                              # a full sequence is left alone, attended as it is, and flagged
+            L.seq_lens[0] = L.t_cap
+            W.wsvd_decode_attn_store(L.ctx, L.desc, d, d[:, n_lat:], 2 * n_lat, qd, qs, BKd, BVd, L.cache, L.t_cap, L.out)
+            assert W.wsvd_check(L.ctx) == W.E_CAPACITY
+            after = L.seq_lens.cpu().numpy()
+            assert after[0] == L.t_cap and (after[1:] == lens[1:] + 2).all()
+        L.close()
+    for pl in (0, 1):
+        for a, b in zip(caches[0][pl], caches[1][pl]):
+            if a is not None:
+                for bi in range(sp.batch):                     # rows below each sequence's new length
+                    n = int(lens[bi]) + 1
+                    assert (np.asarray(a)[bi, :, :n].tobytes() == np.asarray(b)[bi, :, :n].tobytes()), (name, pl, bi)
+    # oracle: the same store, then the definition
+    for b in range(sp.batch):
+        n = int(lens[b])
+        c.cache.store_rows("k", b, n, lat[b, :n_lat].reshape(sp.n_kv_heads, 1, sp.rank).astype(np.float64))
+        c.cache.store_rows("v", b, n, lat[b, n_lat:].reshape(sp.n_kv_heads, 1, sp.rank).astype(np.float64))
+        c.cache.seq_lens[b] = n + 1
+    ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    for o, what in zip(outs, ("two calls", "one call")):
+        check_out(o, ref, sp.latent_dtype, f"store and attend, {name}, {what}")
+    assert np.abs(outs[0] - outs[1]).max() <= 1e-4 * max(np.abs(ref).max(), 1e-30)
 
 
 @pytest.mark.parametrize("layer", list(range(28)))
@@ -238,5 +309,5 @@ def test_config5_block_full_size(layer):
     ref["o_codes"], ref["o_scale"] = O.quantize_act_i8(attn_all.reshape(sp.batch, -1).astype(np.float32))
     ref["y"] = O.linear_w4a8(ref["o_codes"], ref["o_scale"], O.pack_w4(c.wo[0]), c.wo[1])
     print(f"c5 layer {layer}: inputs and oracle in {time.time() - t0:.1f}s", flush=True)
-    _run_block(c, L, False, ref=ref, before=before)
+    _run_block(c, L, False, ref=ref, before=before, one_launch_store=(layer % 2 == 1))    # odd layers: as the benchmark's chain
     L.close()
