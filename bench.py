@@ -62,6 +62,8 @@ def parse():
                          "into W_O, SwiGLU FFN); prefill: building the c3 cache from hidden states, 64 tokens per launch "
                          "shared: the contrast scheme, decode attention over one shared rank-1024 latent per token "
                          "(secondary lines, same JSON shape)")
+    ap.add_argument("--wg-per-cu", type=int, default=0,
+                    help="attention launch policy: wavefronts aimed at per CU in quarters of what is resident (tuning; 0 = the library's 4)")
     ap.add_argument("--two-launch-store", action="store_true",
                     help="c5: wsvd_latent_store + wsvd_decode_attn instead of the single-launch wsvd_decode_attn_store")
     ap.add_argument("--linear-direct", action="store_true",
@@ -95,6 +97,8 @@ def main():
             W.wsvd_ctx_set_option(c, "fused_step", 2)
         if args.max_threads:
             W.wsvd_ctx_set_option(c, "max_threads", args.max_threads)
+        if args.wg_per_cu:
+            W.wsvd_ctx_set_option(c, "wg_per_cu", args.wg_per_cu)
         if args.linear_direct:
             W.wsvd_ctx_set_option(c, "linear_direct", 1)
         if args.project_shape:

@@ -237,10 +237,14 @@ WSVD_DEV bool attn_merge_splits(const AttnParams& p, const WorkItem& w, float* M
         for (;;) {
 #pragma unroll
           for (int k = 0; k < 8; k++) {
-            const unsigned long long* pc = src + (size_t)min(c0 + k, n_in - 1) * (R + 2);   // clamped: surplus slots are masked below
-            wm[k] = __hip_atomic_load(pc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            wl[k] = __hip_atomic_load(pc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            wu[k] = __hip_atomic_load(pc + 2 + jj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (k == 0 || c0 + k < n_in) {                       // workgroup-uniform: only the splits that exist are asked for
+              const unsigned long long* pc = src + (size_t)(c0 + k) * (R + 2);
+              wm[k] = __hip_atomic_load(pc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              wl[k] = __hip_atomic_load(pc + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              wu[k] = __hip_atomic_load(pc + 2 + jj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+              wm[k] = wm[0]; wl[k] = wl[0]; wu[k] = wu[0];       // a duplicate of slot c0: masked in the fold below
+            }
           }
           bool all = true;
 #pragma unroll
@@ -248,7 +252,7 @@ WSVD_DEV bool attn_merge_splits(const AttnParams& p, const WorkItem& w, float* M
             all = all && (uint32_t)(wm[k] >> 32) == kSplitTag && (uint32_t)(wl[k] >> 32) == kSplitTag && (uint32_t)(wu[k] >> 32) == kSplitTag;
           if (all) break;
           if (--budget == 0) { timed_out = true; break; }
-          __builtin_amdgcn_s_sleep(4);
+          __builtin_amdgcn_s_sleep(1);
         }
         float mv[8], lv[8], uv[8];
 #pragma unroll
@@ -257,7 +261,7 @@ WSVD_DEV bool attn_merge_splits(const AttnParams& p, const WorkItem& w, float* M
         }
         float Mn = M;
 #pragma unroll
-        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, mv[k]);                        // a clamped duplicate cannot change a max
+        for (int k = 0; k < 8; k++) Mn = fmaxf(Mn, mv[k]);                        // a duplicate cannot change a max
         // 0 on the first batch (M = -inf); a slot that saw no row in any split so far keeps M = Mn = -inf
         const float keep = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
         L *= keep; U *= keep;
