@@ -135,6 +135,9 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
   WSVD_STAMP(p.timeline, tl_wg, wave, 0);
   // the lengths first: nothing depends on them until the rows are stored
   const int nreg = finisher ? append_target_row(p, b0 + min(tid, nb - 1)) : 0;
+  // ... and, for the finisher that will turn out to be the last one, the lengths it advances on its way out: asked for
+  // now, they cost nothing then (nobody writes them before that)
+  const int n_bump = (finisher && !p.fused) ? p.seq_lens[p.one_seq >= 0 ? p.one_seq : min(tid, p.B - 1)] : 0;
   const uint16_t* Ap = (const uint16_t*)p.A[pl];
   const uint16_t* xp = (const uint16_t*)p.x;
   // ---- this workgroup's share of the k-steps (16 model dims each), then this wave's share of that
@@ -251,9 +254,9 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
           for (int h = 0; h < NPMAX; h++) {
             if (h < NP) {
               unsigned long long v = w[e][h];
-              int budget = 1 << 14;
+              int budget = 1 << 16;
               while ((uint32_t)(v >> 32) != kLLTag && budget > 0) {
-                __builtin_amdgcn_s_sleep(8);
+                __builtin_amdgcn_s_sleep(1);
                 v = __hip_atomic_load(src + (size_t)h * (SB * R), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 budget--;
               }
@@ -285,14 +288,14 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
   if (!flag_sh) return;
   if (p.one_seq >= 0) {
     if (tid == 0) {
-      const int n0 = p.seq_lens[p.one_seq];
+      const int n0 = n_bump;
       if (n0 >= 0) p.seq_lens[p.one_seq] = min(n0 + p.B, p.t_cap);
       if (n0 < 0 || n0 + p.B > p.t_cap) atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
     }
     return;
   }
   for (int b = tid; b < p.B; b += blockDim.x) {
-    const int n = p.seq_lens[b];
+    const int n = b == tid ? n_bump : p.seq_lens[b];            // (more sequences than threads: the rest is read now)
     if (n >= 0 && n < p.t_cap) p.seq_lens[b] = n + 1;
     else atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
   }
