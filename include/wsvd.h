@@ -181,6 +181,33 @@ wsvd_status wsvd_decode_attn_store(wsvd_ctx *ctx, const wsvd_layer_desc *desc, c
                                    wsvd_cache *cache, int32_t max_seq_len, void *out, void *hip_stream);
 
 /*
+ * Paged cache (serving systems hand out the cache in pages): the K / V code and metadata planes are POOLS of n_pages
+ * pages; a page holds page_rows consecutive rows (a multiple of 64) of EVERY kv head of one sequence, each in the
+ * device layout of the contiguous planes (page p, kv head h: page_rows * row_bytes code bytes at
+ * ((p * Hkv + h) * page_rows * row_bytes, metadata likewise); block_table[b][i] names the page with rows
+ * [i * page_rows, (i + 1) * page_rows) of sequence b.  desc->t_cap must equal max_pages * page_rows.  Entries for pages
+ * a sequence does not reach yet are not read for results; an append into a row whose entry is outside [0, n_pages)
+ * stores nothing and records WSVD_E_SHAPE in the device status word.  The caller owns pools and table.
+ * Quantised latents (I8, I4) with up to 4 query heads per kv head and rank <= 64; x and factors BF16 for the append
+ * (WSVD_E_UNSUPPORTED otherwise).  Results are those of wsvd_latent_append / wsvd_decode_attn on the same rows.
+ */
+typedef struct {
+  void *k_codes, *v_codes;       /* DEVICE pools */
+  void *k_meta, *v_meta;
+  int32_t *seq_lens;             /* DEVICE [B] */
+  const int32_t *block_table;    /* DEVICE [B][max_pages] */
+  int32_t page_rows, max_pages, n_pages;
+} wsvd_paged_cache;
+/* Bytes of ONE code pool and ONE metadata pool (K or V) of n_pages pages (HOST outputs). */
+wsvd_status wsvd_paged_cache_bytes(const wsvd_layer_desc *desc, int32_t page_rows, int32_t n_pages, size_t *codes_bytes,
+                                   size_t *meta_bytes);
+wsvd_status wsvd_latent_append_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
+                                     const void *A_K, const void *A_V, wsvd_paged_cache *cache, void *hip_stream);
+wsvd_status wsvd_decode_attn_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
+                                   const void *B_K, const void *B_V, const wsvd_paged_cache *cache, int32_t max_seq_len,
+                                   void *out, void *hip_stream);
+
+/*
  * wsvd_decode_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results as
  * wsvd_decode_attn, but the words through which the splits of a long sequence reach the workgroup that merges them

@@ -24,7 +24,8 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
-           "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_store", "wsvd_decode_attn_static", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
+           "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_store", "wsvd_decode_attn_static",
+           "wsvd_paged_cache_bytes", "wsvd_latent_append_paged", "wsvd_decode_attn_paged", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
@@ -47,6 +48,12 @@ class LayerDesc(ctypes.Structure):
 class Cache(ctypes.Structure):
     _fields_ = [("k_codes", c_void_p), ("v_codes", c_void_p), ("k_meta", c_void_p), ("v_meta", c_void_p),
                 ("seq_lens", c_void_p)]
+
+
+class PagedCache(ctypes.Structure):
+    _fields_ = [("k_codes", c_void_p), ("v_codes", c_void_p), ("k_meta", c_void_p), ("v_meta", c_void_p),
+                ("seq_lens", c_void_p), ("block_table", c_void_p), ("page_rows", c_int32), ("max_pages", c_int32),
+                ("n_pages", c_int32)]
 
 
 _lib = None
@@ -89,6 +96,11 @@ def lib():
         L.wsvd_decode_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                        POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_decode_attn_static.argtypes = L.wsvd_decode_attn.argtypes
+        L.wsvd_paged_cache_bytes.argtypes = [POINTER(LayerDesc), c_int32, c_int32, POINTER(c_size_t), POINTER(c_size_t)]
+        L.wsvd_latent_append_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
+                                               POINTER(PagedCache), c_void_p]
+        L.wsvd_decode_attn_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
+                                             POINTER(PagedCache), c_int32, c_void_p, c_void_p]
         L.wsvd_decode_attn_store.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p,
                                              c_void_p, POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_decode_attn_rope.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
@@ -228,6 +240,29 @@ def wsvd_decode_attn(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, s
 def wsvd_decode_attn_store(ctx, desc, c_K, c_V, ld, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
     _ck(lib().wsvd_decode_attn_store(ctx, byref(desc), _ptr(c_K), _ptr(c_V), int(ld), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V),
                                      byref(cache), int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn_store")
+
+
+def make_paged_cache(k_codes, v_codes, k_meta, v_meta, seq_lens, block_table, page_rows, max_pages, n_pages) -> PagedCache:
+    c = PagedCache(_ptr(k_codes), _ptr(v_codes), _ptr(k_meta), _ptr(v_meta), _ptr(seq_lens), _ptr(block_table),
+                   int(page_rows), int(max_pages), int(n_pages))
+    c._keep = (k_codes, v_codes, k_meta, v_meta, seq_lens, block_table)   # keep the tensors alive
+    return c
+
+
+def wsvd_paged_cache_bytes(desc, page_rows, n_pages):
+    a, b = c_size_t(), c_size_t()
+    _ck(lib().wsvd_paged_cache_bytes(byref(desc), int(page_rows), int(n_pages), byref(a), byref(b)), "wsvd_paged_cache_bytes")
+    return a.value, b.value
+
+
+def wsvd_latent_append_paged(ctx, desc, x, x_scale, A_K, A_V, cache, stream=None):
+    _ck(lib().wsvd_latent_append_paged(ctx, byref(desc), _ptr(x), _ptr(x_scale), _ptr(A_K), _ptr(A_V), byref(cache),
+                                       _stream(stream)), "wsvd_latent_append_paged")
+
+
+def wsvd_decode_attn_paged(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
+    _ck(lib().wsvd_decode_attn_paged(ctx, byref(desc), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V), byref(cache),
+                                     int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn_paged")
 
 
 def wsvd_decode_attn_static(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):

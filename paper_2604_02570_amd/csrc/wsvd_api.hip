@@ -429,6 +429,73 @@ wsvd_status wsvd_decode_attn_store(wsvd_ctx* ctx, const wsvd_layer_desc* desc, c
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+namespace {
+wsvd_status check_paged(const wsvd_layer_desc& d, const wsvd_paged_cache* c) {
+  if (!c || !c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !c->seq_lens || !c->block_table) return WSVD_E_NULL;
+  if (d.latent_dtype != WSVD_I8 && d.latent_dtype != WSVD_I4) return WSVD_E_UNSUPPORTED;
+  if (d.rank > 64 || d.n_q_heads / d.n_kv_heads > 4) return WSVD_E_UNSUPPORTED;
+  if (c->page_rows < 64 || c->page_rows % 64 != 0 || c->max_pages < 1 || c->n_pages < 1) return WSVD_E_SHAPE;
+  if ((int64_t)c->max_pages * c->page_rows != d.t_cap) return WSVD_E_SHAPE;
+  if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta) ||
+      ((uintptr_t)c->seq_lens & 3u) || ((uintptr_t)c->block_table & 3u))
+    return WSVD_E_ALIGN;
+  return WSVD_OK;
+}
+}  // namespace
+
+wsvd_status wsvd_paged_cache_bytes(const wsvd_layer_desc* desc, int32_t page_rows, int32_t n_pages, size_t* codes_bytes,
+                                   size_t* meta_bytes) {
+  if (!codes_bytes || !meta_bytes) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if (page_rows < 64 || page_rows % 64 != 0 || n_pages < 1) return WSVD_E_SHAPE;
+  *codes_bytes = (size_t)n_pages * desc->n_kv_heads * page_rows * row_bytes_host(*desc);
+  *meta_bytes = (size_t)n_pages * desc->n_kv_heads * page_rows * meta_bytes_host(*desc);
+  return WSVD_OK;
+}
+
+wsvd_status wsvd_latent_append_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* x, const void* x_scale,
+                                     const void* A_K, const void* A_V, wsvd_paged_cache* cache, void* hip_stream) {
+  if (!ctx || !x || !A_K || !A_V) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_paged(*desc, cache)) != WSVD_OK) return st;
+  if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
+  if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  wsvd_cache view = {cache->k_codes, cache->v_codes, cache->k_meta, cache->v_meta, cache->seq_lens};
+  hipError_t e = wsvd_launch_append(ctx, *desc, x, x_scale, A_K, A_V, view, (hipStream_t)hip_stream, -1, cache);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
+wsvd_status wsvd_decode_attn_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
+                                   const void* B_K, const void* B_V, const wsvd_paged_cache* cache, int32_t max_seq_len,
+                                   void* out, void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_paged(*desc, cache)) != WSVD_OK) return st;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 0) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  wsvd_cache view = {cache->k_codes, cache->v_codes, cache->k_meta, cache->v_meta, cache->seq_lens};
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, *desc, q, q_scale, B_K, B_V, view, max_seq_len, out, p, grid, threads, 0);
+  p.block_table = cache->block_table; p.page_rows = cache->page_rows; p.max_pages = cache->max_pages; p.n_pages = cache->n_pages;
+  hipError_t e = wsvd_launch_attn_mfma(p, desc->latent_dtype, desc->rank, grid, threads, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn_static(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                                     const void* B_K, const void* B_V, const wsvd_cache* cache, int32_t max_seq_len, void* out,
                                     void* hip_stream) {

@@ -407,7 +407,11 @@ int wsvd_append_mfma_waves(const wsvd_ctx* ctx, const wsvd_layer_desc& d) {
 bool wsvd_append_uses_mfma(const wsvd_layer_desc& d) { return append_mfma_path(d); }
 
 hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,
-                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s, int one_seq) {
+                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s, int one_seq,
+                              const wsvd_paged_cache* paged) {
+  if (paged && !(d.rank <= 64 && append_mfma_path(d) && ctx->opt.append_mode == 0 && append_split_ok(d) &&
+                 (d.latent_dtype == WSVD_I8 || d.latent_dtype == WSVD_I4)))
+    return hipErrorNotSupported;           // paged cache: quantised latents through the default kernel
   if (d.rank > 64) {
     // ranks 96 / 128 (int8 latents, bf16 hidden states and factors): the tiled projection with one token per sequence,
     // then its length update: two launches
@@ -417,6 +421,7 @@ hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, con
   AppendParams p;
   wsvd_append_params(ctx, d, x, x_scale, A_K, A_V, cache, p);
   p.one_seq = one_seq;
+  if (paged) { p.block_table = paged->block_table; p.page_rows = paged->page_rows; p.max_pages = paged->max_pages; p.n_pages = paged->n_pages; }
   if (d.d_model % 64 != 0 || d.batch > kAppendMaxB) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.ES * p.Hkv * 2));
   const bool f32 = d.factor_dtype == WSVD_F32;

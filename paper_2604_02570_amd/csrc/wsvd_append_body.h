@@ -25,6 +25,9 @@ struct AppendParams {
   // seq_lens[one_seq] + i and the length advances by B.  -1: one token per sequence (decode).
   int one_seq;
   long long* timeline;       // profiling build: stamp buffer (see WSVD_STAMP), else null
+  // paged cache only (else null): codes / meta are pools of n_pages pages, a page = page_rows rows of every kv head
+  const int* block_table;    // [B][max_pages]
+  int page_rows, max_pages, n_pages;
 };
 
 // which sequence a row of x belongs to, and the cache row it goes to given that sequence's length
@@ -61,6 +64,33 @@ WSVD_DEV float load_x(const AppendParams& p, int b, int e) {
   return load_as_f32(p.x, idx, p.x_dtype);
 }
 
+// Where row t of (b, kv) lives: the plane of its codes (row_bytes per row), the index of its metadata entry, and the row
+// index inside that plane.  Contiguous cache: one plane of t_cap rows per (b, kv).  Paged cache (quantised latents): the
+// page block_table[b][t / page_rows] of the pools holds page_rows rows of every kv head in the same layout; an entry
+// outside the pools reports WSVD_E_SHAPE and the row goes to page 0's slot of nobody (ok = false: not stored).
+struct RowAddr {
+  uint8_t* plane;
+  size_t meta;
+  int t;
+  bool ok;
+};
+WSVD_DEV RowAddr append_row_addr(const AppendParams& p, int pl, int b, int kv, int t, int row_bytes) {
+  RowAddr a;
+  if (!p.block_table) {
+    const size_t ph = (size_t)b * p.Hkv + kv;
+    a.plane = p.codes[pl] + ph * (size_t)p.t_cap * row_bytes; a.meta = ph * p.t_cap + t; a.t = t; a.ok = true;
+    return a;
+  }
+  const int pg = min(t / p.page_rows, p.max_pages - 1);
+  int phys = p.block_table[(size_t)b * p.max_pages + pg];
+  a.ok = phys >= 0 && phys < p.n_pages;
+  if (!a.ok) { phys = 0; atomicExch(p.err_word, (int)WSVD_E_SHAPE); }
+  const size_t slot = (size_t)phys * p.Hkv + kv;
+  a.t = t - pg * p.page_rows;
+  a.plane = p.codes[pl] + slot * (size_t)p.page_rows * row_bytes; a.meta = slot * p.page_rows + a.t;
+  return a;
+}
+
 // Store one latent row (fp32 values in c[0..R)) of (b, kv) at row t of plane `pl`.
 template <int R>
 WSVD_DEV void store_row(const AppendParams& p, int pl, int b, int kv, int t, const float* c) {
@@ -77,9 +107,10 @@ WSVD_DEV void store_row(const AppendParams& p, int pl, int b, int kv, int t, con
 #pragma unroll
     for (int j = 0; j < R; j++) v[j] = c[j];
     const uint16_t sh = quantize_row_i8<R>(v, q);
-    uint8_t* plane = p.codes[pl] + ph * (size_t)p.t_cap * R;
-    for (int j = 0; j < R; j++) put_u8(p, plane + (pl == 0 ? i8_k_offset(t, j, R) : i8_v_offset(t, j, R)), (uint8_t)q[j]);
-    put_u16(p, &p.meta[pl][ph * p.t_cap + t], sh);
+    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R);
+    if (!ra.ok) return;
+    for (int j = 0; j < R; j++) put_u8(p, ra.plane + (pl == 0 ? i8_k_offset(ra.t, j, R) : i8_v_offset(ra.t, j, R)), (uint8_t)q[j]);
+    put_u16(p, &p.meta[pl][ra.meta], sh);
   } else {  // I4, R == 32
     float v[R];
     uint8_t q[R];
@@ -87,20 +118,22 @@ WSVD_DEV void store_row(const AppendParams& p, int pl, int b, int kv, int t, con
     for (int j = 0; j < R; j++) v[j] = c[j];
     uint16_t sh, zh;
     quantize_row_i4<R>(v, q, &sh, &zh);
-    uint8_t* plane = p.codes[pl] + ph * (size_t)p.t_cap * (R / 2);
+    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R / 2);
+    if (!ra.ok) return;
+    uint8_t* plane = ra.plane;
     if (pl == 0) {
-      for (int j = 0; j < R; j += 2) { int nib; put_u8(p, plane + i4_k_offset(t, j, &nib), (uint8_t)(q[j] | (q[j + 1] << 4))); }
+      for (int j = 0; j < R; j += 2) { int nib; put_u8(p, plane + i4_k_offset(ra.t, j, &nib), (uint8_t)(q[j] | (q[j + 1] << 4))); }
     } else {
       // tokens (t, t^1) share each byte; the other token was (or will be) written by a different launch
       for (int j = 0; j < R; j++) {
         int nib;
-        uint8_t* bp = plane + i4_v_offset(t, j, &nib);
+        uint8_t* bp = plane + i4_v_offset(ra.t, j, &nib);
         const uint8_t old = *bp;
         put_u8(p, bp, nib ? (uint8_t)((old & 0x0F) | (q[j] << 4)) : (uint8_t)((old & 0xF0) | q[j]));
       }
     }
-    put_u16(p, &p.meta[pl][(ph * p.t_cap + t) * 2], sh);
-    put_u16(p, &p.meta[pl][(ph * p.t_cap + t) * 2 + 1], zh);
+    put_u16(p, &p.meta[pl][ra.meta * 2], sh);
+    put_u16(p, &p.meta[pl][ra.meta * 2 + 1], zh);
   }
 }
 
@@ -129,9 +162,11 @@ WSVD_DEV void store_row_lanes(const AppendParams& p, int pl, int b, int kv, int 
     if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
     const float sc = f16_bits_to_f32(sh);
     const float v = fminf(fmaxf(__builtin_rintf(c / sc), -127.f), 127.f);
-    uint8_t* plane = p.codes[pl] + ph * (size_t)p.t_cap * R;
-    put_u8(p, plane + (pl == 0 ? i8_k_offset(t, j, R) : i8_v_offset(t, j, R)), (uint8_t)(int8_t)(int)v);
-    if (j == 0) put_u16(p, &p.meta[pl][ph * p.t_cap + t], sh);
+    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R);
+    if (ra.ok) {
+      put_u8(p, ra.plane + (pl == 0 ? i8_k_offset(ra.t, j, R) : i8_v_offset(ra.t, j, R)), (uint8_t)(int8_t)(int)v);
+      if (j == 0) put_u16(p, &p.meta[pl][ra.meta], sh);
+    }
   } else {  // I4, R == 32
     const float hi = lanes_max<R>(fmaxf(c, 0.f)), lo = -lanes_max<R>(fmaxf(-c, 0.f));
     uint16_t sh = 0x3C00u;
@@ -143,21 +178,22 @@ WSVD_DEV void store_row_lanes(const AppendParams& p, int pl, int b, int kv, int 
     const int zi = (int)z;
     int q = (int)fminf(fmaxf(__builtin_rintf(c / sc), -64.f), 64.f) + zi;
     q = q < 0 ? 0 : (q > 15 ? 15 : q);
-    uint8_t* plane = p.codes[pl] + ph * (size_t)p.t_cap * (R / 2);
+    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R / 2);
+    uint8_t* plane = ra.plane;
     int nib;
     if (pl == 0) {
       // dims (j, j+1) share a byte: the odd lane hands its code to the even lane
       const int qn = __builtin_amdgcn_update_dpp(0, q, kDppQuadSwap1, 0xF, 0xF, true);
-      if ((j & 1) == 0) put_u8(p, plane + i4_k_offset(t, j, &nib), (uint8_t)(q | (qn << 4)));
-    } else {
+      if ((j & 1) == 0 && ra.ok) put_u8(p, plane + i4_k_offset(ra.t, j, &nib), (uint8_t)(q | (qn << 4)));
+    } else if (ra.ok) {
       // tokens (t, t^1) share each byte; the other token was (or will be) written by a different launch
-      uint8_t* bp = plane + i4_v_offset(t, j, &nib);
+      uint8_t* bp = plane + i4_v_offset(ra.t, j, &nib);
       const uint8_t old = *bp;
       put_u8(p, bp, nib ? (uint8_t)((old & 0x0F) | (q << 4)) : (uint8_t)((old & 0xF0) | q));
     }
-    if (j == 0) {
-      put_u16(p, &p.meta[pl][(ph * p.t_cap + t) * 2], sh);
-      put_u16(p, &p.meta[pl][(ph * p.t_cap + t) * 2 + 1], f32_to_f16_bits_rne((float)zi));
+    if (j == 0 && ra.ok) {
+      put_u16(p, &p.meta[pl][ra.meta * 2], sh);
+      put_u16(p, &p.meta[pl][ra.meta * 2 + 1], f32_to_f16_bits_rne((float)zi));
     }
   }
 }

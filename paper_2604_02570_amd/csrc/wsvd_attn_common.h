@@ -42,6 +42,10 @@ struct AttnParams {
   long new_ld;
   int* done;
   int* seq_lens_rw;
+  // paged cache only (else block_table is null): k_codes / v_codes / k_meta / v_meta are pools of n_pages pages, a page
+  // = page_rows rows of every kv head; block_table [B][max_pages]
+  const int* block_table;
+  int page_rows, max_pages, n_pages;
 };
 
 struct WorkItem {

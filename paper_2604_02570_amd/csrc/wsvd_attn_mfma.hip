@@ -204,7 +204,7 @@ WSVD_DEV void split_fp16_pair(float x, float scale, _Float16& hi, _Float16& lo) 
 // very moment.  The row counts as present; the 64-row tile that contains it is kept out of the streaming loop and
 // done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
 // ROPE_D != 0: the rotary variant for head dimension ROPE_D (I8 latents; rs, ra non-null).
-template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0, bool LATENT = false>
+template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0, bool LATENT = false, bool PAGED = false>
 WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE_D != 0 || LATENT)>& sh, const int cx, const int cy,
                              const int cz, RopeShared<R, G, (ROPE_D ? ROPE_D : 64)>* rs = nullptr, const RopeArgs* ra = nullptr) {
   constexpr bool ROPE = ROPE_D != 0;
@@ -213,6 +213,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   static_assert(!ROPE || (!I4 && !FUSED), "rotary variant: int8 latents, stand-alone launch");
   static_assert(!LATENT || (!ROPE && !FUSED), "latent-query variant: stand-alone launch, no rotation");
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
+  static_assert(!PAGED || (!ROPE && !LATENT && !FUSED), "paged cache: the plain decode attention");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
   constexpr int NWMAX = NT / 64;
@@ -236,6 +237,28 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   const uint8_t* vplane = p.v_codes + ph * plane_bytes;
   const uint16_t* kmeta = p.k_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
   const uint16_t* vmeta = p.v_meta + ph * (size_t)p.t_cap * (I4 ? 2 : 1);
+  // Paged cache: rows [i * page_rows, (i + 1) * page_rows) of sequence b live in page block_table[b][i] of the pools,
+  // a page holding that row range of every kv head in the layout of the contiguous planes.  A tile (64 rows) never
+  // straddles pages.  Entries that are out of range (pages past the sequence's end may hold anything, and tiles are
+  // requested before the length is known) are read as page 0: such tiles are never consumed.
+  auto tile_load = [&](TileRegs<R, I4>& t, int tile, int which /* 0 both, 1 K side, 2 V side */) {
+    const uint8_t *kp = kplane, *vp = vplane;
+    const uint16_t *km = kmeta, *vm = vmeta;
+    int ti = tile;
+    if constexpr (PAGED) {
+      const int tpp = p.page_rows >> 6;
+      const int pg = min(tile / tpp, p.max_pages - 1);
+      int phys = p.block_table[(size_t)cz * p.max_pages + pg];
+      phys = (phys >= 0 && phys < p.n_pages) ? phys : 0;
+      const size_t slot = (size_t)phys * p.Hkv + cx;
+      const size_t pb = (size_t)p.page_rows * (I4 ? R / 2 : R), pm = (size_t)p.page_rows * (I4 ? 2 : 1);
+      kp = p.k_codes + slot * pb; vp = p.v_codes + slot * pb;
+      km = p.k_meta + slot * pm; vm = p.v_meta + slot * pm;
+      ti = tile - pg * tpp;
+    }
+    if (which != 2) load_tile_k<R, I4>(t, kp, km, ti, lane);
+    if (which != 1) load_tile_v<R, I4>(t, vp, vm, ti, lane);
+  };
 
   // ---- loads, in the order they should come back: the small per-head inputs first, then DEPTH tiles per wave (a
   // tile = 64 rows of K and V codes plus metadata), requested before the sequence length is known.  Every tile below
@@ -287,7 +310,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     // the absorption must not queue behind them.
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int i = 0; i < DEPTH; i++) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+    for (int i = 0; i < DEPTH; i++) tile_load(buf[i], min(T + i * NW, spec_last), 0);
     WSVD_STAMP(tl, tl_wg, wave, 1);
 
     if (leader) {
@@ -652,7 +675,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
       ksc = f16_bits_to_f32((uint16_t)t.kmeta);
       vsc = f16_bits_to_f32((uint16_t)t.vmeta);
     }
-    if constexpr (decltype(refill)::value && !ROPE) load_tile_k<R, I4>(t, kplane, kmeta, next, lane);
+    if constexpr (decltype(refill)::value && !ROPE) tile_load(t, next, 1);
     float rdot[G];
     if constexpr (ROPE) {
       float sb[2][G];
@@ -764,8 +787,8 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
       }
     }
     if constexpr (decltype(refill)::value) {
-      if constexpr (ROPE) load_tile_k<R, I4>(t, kplane, kmeta, next, lane);      // (its key codes are read block by block)
-      load_tile_v<R, I4>(t, vplane, vmeta, next, lane);
+      if constexpr (ROPE) tile_load(t, next, 1);      // (its key codes are read block by block)
+      tile_load(t, next, 2);
     }
 #ifdef WSVD_TIMELINE
     if (tl_first) { WSVD_STAMP(tl, tl_wg, wave, 4); tl_first = false; }
@@ -806,7 +829,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   for (int i = 0; i < DEPTH; i++) {
     if (done + i < n) {
       compute(kNoRefill, buf[i], T + (done + i) * NW, 0);
-      if (done + i + DEPTH < n) load_tile<R, I4>(buf[i], kplane, vplane, kmeta, vmeta, T + (done + i + DEPTH) * NW, lane);
+      if (done + i + DEPTH < n) tile_load(buf[i], T + (done + i + DEPTH) * NW, 0);
     }
   }
   done += DEPTH;
@@ -913,10 +936,10 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   WSVD_STAMP(tl, tl_wg, wave, 8);
 }
 
-template <int R, int G, bool I4, int NT>
+template <int R, int G, bool I4, int NT, bool PAGED = false>
 __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   __shared__ AttnMfmaShared<R, G, NT, false> sh;
-  attn_mfma_body<R, G, I4, NT, false>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
+  attn_mfma_body<R, G, I4, NT, false, 0, false, PAGED>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // Q latent in, latent-space output out (Section 3.4: the Q latent's up-projection B_Q meets B_K^T in one small matrix
@@ -1441,6 +1464,16 @@ template <int R, bool I4, int NT>
 static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
   constexpr int NTG = NT > 512 ? 512 : NT;
   if (threads > (p.G == 1 ? NT : NTG) || threads % 64) return hipErrorInvalidValue;
+  if (p.block_table) {                     // paged cache
+    switch (p.G) {
+      case 1: hipLaunchKernelGGL((k_attn_mfma<R, 1, I4, NT, true>), grid, dim3(threads), 0, s, p); break;
+      case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4, NTG, true>), grid, dim3(threads), 0, s, p); break;
+      case 3: hipLaunchKernelGGL((k_attn_mfma<R, 3, I4, NTG, true>), grid, dim3(threads), 0, s, p); break;
+      case 4: hipLaunchKernelGGL((k_attn_mfma<R, 4, I4, NTG, true>), grid, dim3(threads), 0, s, p); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (p.G) {
     case 1: hipLaunchKernelGGL((k_attn_mfma<R, 1, I4, NT>), grid, dim3(threads), 0, s, p); break;
     case 2: hipLaunchKernelGGL((k_attn_mfma<R, 2, I4, NTG>), grid, dim3(threads), 0, s, p); break;
@@ -1527,6 +1560,7 @@ int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
 }
 
 hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (p.block_table && (p.G > 4 || rank > 64)) return hipErrorNotSupported;      // paged cache: the paired-block kernel only
   if (p.G > 4) {
     // 5..8 query heads per kv head: I8 latents only
     if (latent_dtype != WSVD_I8 || p.G > 8) return hipErrorNotSupported;

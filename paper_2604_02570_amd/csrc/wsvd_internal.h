@@ -45,7 +45,8 @@ hipError_t wsvd_launch_quantize_act_i8(const void* x, int x_dtype, int64_t rows,
 // d.batch = rows of x.  one_seq < 0: row b is the next token of sequence b; one_seq >= 0: all rows are consecutive
 // tokens of that sequence.
 hipError_t wsvd_launch_append(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* x_scale,
-                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s, int one_seq = -1);
+                              const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s, int one_seq = -1,
+                              const wsvd_paged_cache* paged = nullptr);
 hipError_t wsvd_launch_latent_store(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const float* cK, const float* cV,
                                     int64_t ld, const wsvd_cache& cache, hipStream_t s);
 hipError_t wsvd_launch_pack_factor_a(const wsvd_layer_desc& d, const void* src, void* dst, hipStream_t s);

@@ -1,0 +1,156 @@
+"""Paged cache: wsvd_latent_append_paged / wsvd_decode_attn_paged against the contiguous-cache entry points on the same
+rows (bit-identical: the kernels do the same arithmetic, only the address of a tile or a row differs) and against the
+oracle.  The pools are filled by scattering the pages of a contiguous device cache (pure byte moves, done with torch
+indexing) through a shuffled block table, with more pages in the pool than the batch uses and poison in the rest."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2604_02570_amd as W
+import wsvd_inputs as WI
+from cases import build_case
+from harness import as_dtype_dev, q_to_device
+from test_gpu_parity import check_out, layer_for
+
+pytestmark = pytest.mark.gpu
+
+
+class Paged:
+    """Pools + block table built from a DeviceLayer's contiguous planes."""
+
+    def __init__(self, L, page_rows, seed=0, spare=5):
+        self.L, self.P = L, page_rows
+        assert L.t_cap % page_rows == 0
+        self.max_pages = L.t_cap // page_rows
+        self.n_pages = L.B * self.max_pages + spare
+        rb = {"i8": L.r, "i4": L.r // 2}[L.latent_dtype]
+        mb = {"i8": 2, "i4": 4}[L.latent_dtype]
+        self.rb, self.mb = rb, mb
+        cb, mbytes = W.wsvd_paged_cache_bytes(L.desc, page_rows, self.n_pages)
+        assert cb == self.n_pages * L.Hkv * page_rows * rb and mbytes == self.n_pages * L.Hkv * page_rows * mb
+        rng = np.random.default_rng(seed)
+        perm = rng.permutation(self.n_pages)[: L.B * self.max_pages].reshape(L.B, self.max_pages)
+        self.table_host = perm.astype(np.int32)
+        self.table = torch.from_numpy(self.table_host).cuda()
+        self.pools = [torch.full((self.n_pages, L.Hkv, page_rows * rb), 0xA5, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        self.mpools = [torch.full((self.n_pages, L.Hkv, page_rows * mb), 0xFF, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        self.scatter()
+        self.seq_lens = L.seq_lens.clone()
+        self.cache = W.make_paged_cache(self.pools[0], self.pools[1], self.mpools[0], self.mpools[1], self.seq_lens, self.table,
+                                        page_rows, self.max_pages, self.n_pages)
+
+    def _views(self):
+        L = self.L
+        codes = [t.view(L.B, L.Hkv, self.max_pages, self.P * self.rb) for t in (L.k_codes, L.v_codes)]
+        metas = [t[: L.B * L.Hkv * L.t_cap * self.mb].view(L.B, L.Hkv, self.max_pages, self.P * self.mb) for t in (L.k_meta, L.v_meta)]
+        return codes, metas
+
+    def scatter(self):
+        codes, metas = self._views()
+        idx = self.table.long().reshape(-1)
+        for pl in range(2):
+            self.pools[pl][idx] = codes[pl].permute(0, 2, 1, 3).reshape(-1, self.L.Hkv, self.P * self.rb)
+            self.mpools[pl][idx] = metas[pl].permute(0, 2, 1, 3).reshape(-1, self.L.Hkv, self.P * self.mb)
+
+    def gathered(self):
+        """The pools' content in the shape of the contiguous planes."""
+        L = self.L
+        idx = self.table.long().reshape(-1)
+        out = []
+        for pl in range(2):
+            c = self.pools[pl][idx].view(L.B, self.max_pages, L.Hkv, self.P * self.rb).permute(0, 2, 1, 3).reshape(-1)
+            m = self.mpools[pl][idx].view(L.B, self.max_pages, L.Hkv, self.P * self.mb).permute(0, 2, 1, 3).reshape(-1)
+            out.append((c, m))
+        return out
+
+
+CASES = [("c3_small", dict(), 64), ("c3_small", dict(context=1500, batch=2), 256), ("c4_small", dict(), 128),
+         ("c3_small", dict(n_q_heads=8, n_kv_heads=2), 64), ("c5_small", dict(n_q_heads=4, n_kv_heads=2), 64)]
+
+
+@pytest.mark.parametrize("name,over,page_rows", CASES, ids=["i8", "i8-split-context", "i4-ragged", "i8-4-heads-per-kv", "i8-rank64"])
+def test_paged_attention_and_append_equal_the_contiguous_ones(name, over, page_rows):
+    c = build_case(name, **over)
+    sp = c.sp
+    t_cap = (c.t_cap + page_rows - 1) // page_rows * page_rows
+    L = layer_for(c, t_cap=t_cap); L.upload(c.cache)
+    PG = Paged(L, page_rows, seed=len(name) + page_rows)
+    qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    n_max = int(c.cache.seq_lens.max())
+    # ---- attention over the uploaded rows
+    want = L.attend(qd, qs, BKd, BVd, n_max)
+    out = torch.full_like(L.out, float("nan"))
+    W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, PG.cache, n_max, out)
+    assert W.wsvd_check(L.ctx) == 0
+    got = out.cpu().numpy().astype(np.float64)
+    assert (got == want).all(), "paged attention differs from the contiguous one"
+    ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    check_out(got, ref, sp.latent_dtype, f"paged attention {name}")
+    # ---- three appends on both caches (rows cross page and tile boundaries in the ragged cases), then attention again
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    for step in range(3):
+        x = WI.bf16_exact(WI.hidden_states(sp, sp.batch, 1.0, which="new", sub=50 + step))
+        xd = as_dtype_dev(x, "bf16")
+        O.latent_append(c.cache, x.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+        assert L.append(xd, None, AKd, AVd) == 0
+        W.wsvd_latent_append_paged(L.ctx, L.desc, xd, None, AKd, AVd, PG.cache)
+        assert W.wsvd_check(L.ctx) == 0
+    assert (PG.seq_lens.cpu().numpy() == c.cache.seq_lens).all() and (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+    rb, mb = PG.rb, PG.mb
+    planes = [(L.k_codes, L.k_meta), (L.v_codes, L.v_meta)]
+    for pl, (gc, gm) in enumerate(PG.gathered()):
+        wc = planes[pl][0].view(sp.batch, sp.n_kv_heads, t_cap, -1) if sp.latent_dtype == "i8" else None
+        a = gc.view(sp.batch, sp.n_kv_heads, -1).cpu().numpy(); b = planes[pl][0].view(sp.batch, sp.n_kv_heads, -1).cpu().numpy()
+        am = gm.view(sp.batch, sp.n_kv_heads, -1).cpu().numpy()
+        bm = planes[pl][1][: sp.batch * sp.n_kv_heads * t_cap * mb].view(sp.batch, sp.n_kv_heads, -1).cpu().numpy()
+        for bi in range(sp.batch):
+            # whole 64-row blocks below the sequence's length hold the same bytes in both caches (rows past it are poison
+            # in both, but int4 value bytes pair two rows: compare up to the last complete pair)
+            n = int(c.cache.seq_lens[bi])
+            n_cmp = n // 64 * 64
+            assert a[bi, :, : n_cmp * rb].tobytes() == b[bi, :, : n_cmp * rb].tobytes(), (name, pl, bi)
+            assert am[bi, :, : n * mb].tobytes() == bm[bi, :, : n * mb].tobytes(), (name, pl, bi)
+    n_max = int(c.cache.seq_lens.max())
+    want = L.attend(qd, qs, BKd, BVd, n_max)
+    out.fill_(float("nan"))
+    W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, PG.cache, n_max, out)
+    assert W.wsvd_check(L.ctx) == 0
+    got = out.cpu().numpy().astype(np.float64)
+    assert (got == want).all(), "paged attention after paged appends differs from the contiguous path"
+    ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    check_out(got, ref, sp.latent_dtype, f"paged append + attention {name}")
+    L.close()
+
+
+def test_paged_cache_argument_checks_and_bad_entries():
+    c = build_case("c3_small")
+    sp = c.sp
+    L = layer_for(c, t_cap=384); L.upload(c.cache)
+    PG = Paged(L, 64)
+    qd, qs, _ = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    out = torch.full_like(L.out, float("nan"))
+    bad = W.make_paged_cache(PG.pools[0], PG.pools[1], PG.mpools[0], PG.mpools[1], PG.seq_lens, PG.table, 64, PG.max_pages + 1, PG.n_pages)
+    with pytest.raises(W.WsvdError) as e:            # max_pages * page_rows must be the descriptor's t_cap
+        W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, bad, 333, out)
+    assert e.value.status == W.E_SHAPE
+    bad = W.make_paged_cache(PG.pools[0], PG.pools[1], PG.mpools[0], PG.mpools[1], PG.seq_lens, PG.table, 96, 4, PG.n_pages)
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, bad, 333, out)
+    assert e.value.status == W.E_SHAPE
+    assert torch.isnan(out).all()
+    # an append into a row whose table entry is outside the pools: nothing stored, reported, the other sequences go through
+    tbl = PG.table.clone()
+    page_of_new_row = int(c.cache.seq_lens[1]) // 64
+    tbl[1, page_of_new_row] = PG.n_pages + 7
+    before = [p.clone() for p in PG.pools]
+    broken = W.make_paged_cache(PG.pools[0], PG.pools[1], PG.mpools[0], PG.mpools[1], PG.seq_lens, tbl, 64, PG.max_pages, PG.n_pages)
+    x = WI.bf16_exact(c.x_new[0])
+    W.wsvd_latent_append_paged(L.ctx, L.desc, as_dtype_dev(x, "bf16"), None, L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16"), broken)
+    assert W.wsvd_check(L.ctx) == W.E_SHAPE
+    touched = [(a != b).flatten(1).any(1).nonzero().flatten().tolist() for a, b in zip(PG.pools, before)]
+    good_pages = {int(PG.table_host[b, int(c.cache.seq_lens[b]) // 64]) for b in range(sp.batch) if b != 1}
+    assert set(touched[0]) <= good_pages and set(touched[1]) <= good_pages and len(touched[0]) > 0
+    L.close()

@@ -120,3 +120,50 @@ def test_wide_ranks_refuse_what_they_do_not_cover():
     d = W.layer_desc(2, 4, 4, 128, 512, 128, 128, "i4", "bf16", "bf16", "i8")      # int4 latents
     with pytest.raises(W.WsvdError):
         W.wsvd_cache_bytes(d)
+
+
+def test_heads_of_different_ranks_by_padding():
+    """Rank allocation that differs between the heads of one layer (the appendix's per-head rank search): every head is
+    padded with zero columns / rows to the layer's widest supported rank.  The oracle runs each head at its OWN rank;
+    the library runs the layer at rank 32 (heads of rank 20, 32, 9 and 27) and at rank 128 (heads of rank 115, 77, 128
+    and 64), append and attention."""
+    for ranks, r_pad in (([20, 32, 9, 27], 32), ([115, 77, 128, 64], 128)):
+        c = build_case("c3_small", rank=r_pad)
+        sp = c.sp
+        assert sp.n_kv_heads == len(ranks)
+        for h, r in enumerate(ranks):                         # zero the padding of every head's factors
+            c.AK[h, :, r:] = 0; c.AV[h, :, r:] = 0; c.BK[h, r:] = 0; c.BV[h, r:] = 0
+        # the oracle side, head by head at the head's own rank: a one-head cache each
+        x = WI.bf16_exact(c.x_new[0]).astype(np.float64)
+        ctx_rows = {}
+        T0 = int(c.cache.seq_lens.max())
+        rng = np.random.default_rng(3)
+        Xctx = WI.bf16_exact((rng.standard_normal((sp.batch, T0, sp.d_model)) * 0.8).astype(np.float32)).astype(np.float64)
+        ref = np.zeros((sp.batch, sp.n_q_heads, sp.d_head))
+        qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+        big = O.LatentCache(sp.batch, sp.n_kv_heads, c.t_cap, r_pad, "i8")
+        big.seq_lens[:] = c.cache.seq_lens
+        for h, r in enumerate(ranks):
+            one = O.LatentCache(sp.batch, 1, c.t_cap, r, "i8")
+            AKh, AVh = c.AK[h:h + 1, :, :r].astype(np.float64), c.AV[h:h + 1, :, :r].astype(np.float64)
+            for b in range(sp.batch):
+                n = int(c.cache.seq_lens[b])
+                one.store_rows("k", b, 0, np.transpose(O.project_latents(Xctx[b, :n], AKh), (1, 0, 2)))
+                one.store_rows("v", b, 0, np.transpose(O.project_latents(Xctx[b, :n], AVh), (1, 0, 2)))
+                one.seq_lens[b] = n
+            big.k[:, h, :, :r] = one.k[:, 0]; big.v[:, h, :, :r] = one.v[:, 0]
+            big.k_scale[:, h] = one.k_scale[:, 0]; big.v_scale[:, h] = one.v_scale[:, 0]
+            O.latent_append(one, x, AKh, AVh)
+            ref[:, h] = O.decode_attn_reconstructed(one, q64[:, h:h + 1], c.BK[h:h + 1, :r].astype(np.float64),
+                                                    c.BV[h:h + 1, :r].astype(np.float64), c.sm_scale)[:, 0]
+        L = device_layer(c, r_pad)
+        try:
+            L.upload(big)
+            st = L.append(as_dtype_dev(x.astype(np.float32), "bf16"), None, L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16"))
+            assert st == 0, W.status_str(st)
+            got = L.attend(qd, qs, as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16"), int(c.cache.seq_lens.max()) + 1)
+            a, _, l2 = err_stats(got, ref)
+            print(f"heads of ranks {ranks} run as {r_pad}: max_abs={a:.3e} rel_l2={l2:.3e}", flush=True)
+            assert np.isfinite(got).all() and a <= 2e-2 and l2 <= 1e-3
+        finally:
+            L.close()
