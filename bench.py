@@ -62,6 +62,8 @@ def parse():
                          "into W_O, SwiGLU FFN); prefill: building the c3 cache from hidden states, 64 tokens per launch "
                          "shared: the contrast scheme, decode attention over one shared rank-1024 latent per token "
                          "(secondary lines, same JSON shape)")
+    ap.add_argument("--paged", action="store_true",
+                    help="c3: also time the attention over a paged copy of the cache sets (pages of 256 rows, shuffled)")
     ap.add_argument("--wg-per-cu", type=int, default=0,
                     help="attention launch policy: wavefronts aimed at per CU in quarters of what is resident (tuning; 0 = the library's 4)")
     ap.add_argument("--two-launch-store", action="store_true",
@@ -130,6 +132,8 @@ def main():
     # every repeat replays the same graph of args.steps steps, each of which appends a row: room for all of them
     visits = (args.warmup + args.steps * (R + 1) + n_sets - 1) // n_sets + 8
     t_cap = (T + visits + 63) // 64 * 64
+    if args.paged:
+        t_cap = (t_cap + 255) // 256 * 256      # whole pages
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, sp.latent_dtype, "bf16", "bf16", "i8", "f32", 0.0)
     ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
@@ -296,6 +300,33 @@ def main():
             probe(i)
         stream.synchronize()
         probe_all = timed(probe, n_attn, R)
+        # ---- the same attention over a PAGED copy of the cache sets (pages of 256 rows of all kv heads, handed out in a
+        # shuffled order from one pool per plane): what the page indirection costs
+        paged_all = None
+        if args.paged and not i4:
+            P = 256
+            tc = t_cap // P * P
+            if tc == t_cap:
+                mp = t_cap // P
+                npg = n_sets * B * mp
+                rbp = r
+                pools = [torch.empty((npg, Hkv, P * rbp), dtype=torch.uint8, device="cuda") for _ in range(2)]
+                mpools = [torch.empty((npg, Hkv, P * 2), dtype=torch.uint8, device="cuda") for _ in range(2)]
+                perm = torch.randperm(npg, device="cuda")
+                pcs = []
+                for si, st_ in enumerate(sets):
+                    idx = perm[si * B * mp:(si + 1) * B * mp]
+                    for pl, (cpl, mpl) in enumerate(((st_[0], st_[2]), (st_[1], st_[3]))):
+                        pools[pl][idx] = cpl.view(B, Hkv, mp, P * rbp).permute(0, 2, 1, 3).reshape(-1, Hkv, P * rbp)
+                        mpools[pl][idx] = mpl.view(B, Hkv, mp, P * 2).permute(0, 2, 1, 3).reshape(-1, Hkv, P * 2)
+                    tbl = idx.view(B, mp).to(torch.int32).contiguous()
+                    pcs.append(W.make_paged_cache(pools[0], pools[1], mpools[0], mpools[1], st_[4], tbl, P, mp, npg))
+                stream.synchronize()
+                ref_out = outs[0].clone()
+                attend(sets[0][5], outs[0]); stream.synchronize(); ref_out.copy_(outs[0])
+                W.wsvd_decode_attn_paged(ctx, desc, qd, qsd, BKd, BVd, pcs[0], t_cap, outs[0]); stream.synchronize()
+                assert bool((outs[0] == ref_out).all()), "paged attention differs from the contiguous one"
+                paged_all = timed(lambda i: W.wsvd_decode_attn_paged(ctx, desc, qd, qsd, BKd, BVd, pcs[i % n_sets], t_cap, outs[i % n_sets]), n_attn, R)
 
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -345,6 +376,7 @@ def main():
             "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / (args.steps * R), 6),
             "attention_alone_us": stats(attn_all), "attention_alone_warm_single_set_us": stats(warm_all) if warm_all else None,
             "append_alone_us": stats(app_all) if app_all else None,
+            "paged_attention_alone_us": stats(paged_all) if paged_all else None,
         },
         "roofline": {
             "kernel": "k_attn_mfma<32,1,%s> (decode attention over %s latents)" % ("true", "int4") if i4 else

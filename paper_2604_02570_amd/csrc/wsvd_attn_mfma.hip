@@ -241,6 +241,14 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   // a page holding that row range of every kv head in the layout of the contiguous planes.  A tile (64 rows) never
   // straddles pages.  Entries that are out of range (pages past the sequence's end may hold anything, and tiles are
   // requested before the length is known) are read as page 0: such tiles are never consumed.
+  // The table entries of this workgroup's chunk are fetched once, one per lane, with the first loads of the kernel; a
+  // tile's entry is then a lane read (the tile index is wave-uniform), not a dependent trip to memory per tile.
+  [[maybe_unused]] int page_entry = 0, page0 = 0;
+  if constexpr (PAGED) {
+    const int tpp = p.page_rows >> 6;
+    page0 = ((int)cy * (p.chunk_rows >> 6)) / tpp;
+    page_entry = p.block_table[(size_t)cz * p.max_pages + min(page0 + lane, p.max_pages - 1)];
+  }
   auto tile_load = [&](TileRegs<R, I4>& t, int tile, int which /* 0 both, 1 K side, 2 V side */) {
     const uint8_t *kp = kplane, *vp = vplane;
     const uint16_t *km = kmeta, *vm = vmeta;
@@ -248,7 +256,9 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     if constexpr (PAGED) {
       const int tpp = p.page_rows >> 6;
       const int pg = min(tile / tpp, p.max_pages - 1);
-      int phys = p.block_table[(size_t)cz * p.max_pages + pg];
+      const int rel = __builtin_amdgcn_readfirstlane(pg - page0);
+      int phys = (rel >= 0 && rel < 64) ? __builtin_amdgcn_readlane(page_entry, rel)
+                                        : p.block_table[(size_t)cz * p.max_pages + pg];     // (chunks of more than 64 pages)
       phys = (phys >= 0 && phys < p.n_pages) ? phys : 0;
       const size_t slot = (size_t)phys * p.Hkv + cx;
       const size_t pb = (size_t)p.page_rows * (I4 ? R / 2 : R), pm = (size_t)p.page_rows * (I4 ? 2 : 1);
