@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
-    ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep"], default="c3",
+    ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep", "probe"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
                          "c5: the 28-layer grouped-query W4A8 attention block; "
@@ -122,6 +122,8 @@ def main():
         return run_small(args, np, torch, W, WI)
     if args.workload == "sweep":
         return run_sweep(args, np, torch, W, WI)
+    if args.workload == "probe":
+        return run_probe(args, np, torch, W, WI)
 
     sp = WI.spec(args.workload)
     i4 = sp.latent_dtype == "i4"
@@ -1318,6 +1320,59 @@ def run_sweep(args, np, torch, W, WI):
                                  "context only, not a target",
             }
             print(json.dumps(res), flush=True)
+    W.wsvd_destroy(ctx)
+
+
+def run_probe(args, np, torch, W, WI):
+    """The ceiling the attention is reported against, measured by itself: the read-only kernel (wsvd_probe_stream_read,
+    512-thread workgroups, each streaming one contiguous share) over buffers from 9 MB to 1.1 GB, every launch on a
+    different buffer of a rotating pool of at least 1.2 GB (cold HBM), launches replayed from a HIP graph, median of
+    --repeats replays.  A least-squares line time = t0 + bytes / rate over the sizes separates the fixed part of a
+    launch (dispatch ramp, first-request latency, drain, turnaround to the next launch) from the streaming rate."""
+    ctx = args.make_ctx()
+    R = max(1, args.repeats)
+    stream = torch.cuda.Stream()
+    sizes = [9 << 20, 18 << 20, 36 << 20, 72 << 20, 144 << 20, 288 << 20, 576 << 20, 1152 << 20]
+    pool_bytes = max(2 * sizes[-1], 1200 << 20)
+    pool = torch.empty(pool_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+    rows = []
+    for nbytes in sizes:
+        n_buf = max(2, pool_bytes // nbytes)
+        n_launch = int(min(64, max(8, 2 * n_buf)))
+        wgs = 1024
+        def probe(i):
+            off = (i % n_buf) * nbytes
+            W.wsvd_probe_stream_read(ctx, pool[off:off + nbytes], nbytes, wgs)
+        with torch.cuda.stream(stream):
+            for i in range(min(n_buf, 8)):
+                probe(i)
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(n_launch):
+                    probe(i)
+            g.replay(); stream.synchronize()
+            ts = []
+            for _ in range(R):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream); g.replay(); e1.record(stream); stream.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3 / n_launch)
+            del g
+        us = float(np.median(ts))
+        rows.append({"MB": round(nbytes / 1e6, 1), "us": round(us, 3), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                     "frac_of_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)})
+    x = np.array([r["MB"] * 1e6 for r in rows]); y = np.array([r["us"] * 1e-6 for r in rows])
+    slope, t0 = np.polyfit(x, y, 1)
+    res = {"metric": "stream_read_probe_GBps", "value": rows[3]["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": 0, "warmup": 0,
+           "ms_per_step": round(rows[3]["us"] * 1e-3, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "u8", "data": "synthetic",
+           "config": {"workload": "probe: read-only kernel over 9 MB .. 1.1 GB buffers, cold HBM, HIP graph replay", "sizes": rows,
+                      "fit": {"fixed_us_per_launch": round(t0 * 1e6, 3), "streaming_GBps": round(1.0 / slope / 1e9, 1),
+                              "streaming_frac_of_peak": round(1.0 / slope / 1e9 / HBM_PEAK_GBPS, 4)}},
+           "roofline": {"kernel": "k_stream_read", "bound": "hbm", "achieved": rows[3]["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": rows[3]["frac_of_peak"], "traffic": None, "algorithmic_bytes_per_launch": int(sizes[3]),
+                        "avg_launch_us": rows[3]["us"]}}
+    print(json.dumps(res))
     W.wsvd_destroy(ctx)
 
 
