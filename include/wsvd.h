@@ -307,9 +307,11 @@ wsvd_status wsvd_cache_export(wsvd_ctx *ctx, const wsvd_layer_desc *desc, int32_
  * projection on the matrix cores, no workspace; WSVD_E_SHAPE for n_tokens > 64 with other formats).  With those formats
  * seq_index = -1 stores n_tokens rows for EVERY sequence of the batch in one launch: x is then [batch, n_tokens, d_model]
  * and each sequence's rows start at its own length (WSVD_E_SHAPE for seq_index = -1 with other formats).  Rows beyond
- * t_cap are not stored: the sequence is left full and WSVD_E_CAPACITY is recorded in the device status word.  F32, BF16
- * and I8 latents (WSVD_E_UNSUPPORTED for I4, whose value plane packs two tokens into a byte: use wsvd_quantize_rows +
- * wsvd_cache_import for those).  Attention over the prompt itself is not part of this call.
+ * t_cap are not stored: the sequence is left full and WSVD_E_CAPACITY is recorded in the device status word.  F32, BF16,
+ * I8 and I4 latents.  I4 (x and factors BF16, any n_tokens, one sequence or all): a value byte holds two consecutive
+ * rows, so every target sequence must stand at an EVEN length when the call is made (a fresh prompt does); a sequence at
+ * an odd length is left unchanged and WSVD_E_SHAPE is recorded in the device status word.  Attention over the prompt
+ * itself is not part of this call.
  */
 wsvd_status wsvd_prefill_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
                                 int32_t n_tokens, int32_t seq_index, const void *A_K, const void *A_V, wsvd_cache *cache,

@@ -243,9 +243,12 @@ wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, cons
   if (desc->x_dtype == WSVD_I8 && !x_scale) return WSVD_E_NULL;
   if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
   if (n_tokens < 1 || seq_index < -1 || seq_index >= desc->batch) return WSVD_E_SHAPE;
-  if (n_tokens > 64 || seq_index < 0 || ctx->opt.prefill_tiled || desc->rank > 64) {
-    // a prompt-sized block, or all sequences at once: the tiled projection (one launch for all its tokens)
-    const bool fits = desc->latent_dtype == WSVD_I8 && desc->factor_dtype == WSVD_BF16 && desc->x_dtype == WSVD_BF16;
+  const bool i4 = desc->latent_dtype == WSVD_I4;
+  if (n_tokens > 64 || seq_index < 0 || ctx->opt.prefill_tiled || desc->rank > 64 || i4) {
+    // a prompt-sized block, or all sequences at once, or int4 latents (whose value bytes pair two rows: only the tiled
+    // kernel writes both rows of a byte from one place): the tiled projection (one launch for all its tokens)
+    const bool fits = (desc->latent_dtype == WSVD_I8 || i4) && desc->factor_dtype == WSVD_BF16 && desc->x_dtype == WSVD_BF16;
+    if (!fits && i4) return WSVD_E_UNSUPPORTED;
     if (!fits && desc->rank > 64) return WSVD_E_UNSUPPORTED;
     if (!fits && (n_tokens > 64 || seq_index < 0)) return WSVD_E_SHAPE;
     if (fits) {
@@ -254,8 +257,6 @@ wsvd_status wsvd_prefill_append(wsvd_ctx* ctx, const wsvd_layer_desc* desc, cons
       return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
     }
   }
-  // two tokens of one sequence share the bytes of an int4 value plane: their stores would race within one launch
-  if (desc->latent_dtype == WSVD_I4) return WSVD_E_UNSUPPORTED;
   wsvd_layer_desc d = *desc;
   d.batch = n_tokens;                       // rows of x in this launch
   size_t need;

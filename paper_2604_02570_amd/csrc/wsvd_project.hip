@@ -25,6 +25,7 @@ struct ProjectParams {
   int* err_word;
   int Hkv, E, t_cap, n_tok, seq0;   // direct kernel: grid z = sequence - seq0
   int n_cg, tg_seq, n_tg;           // staged kernel: channel groups, token groups per sequence and in all
+  int i4;                           // int4 latents (rank 32): asymmetric codes, two rows per value byte
 };
 
 // per token and head: symmetric int8 (the latent quantiser's rule), then the stores.  acc[c][tt] = channel tile ct0 + c
@@ -43,6 +44,53 @@ WSVD_DEV void project_store(const ProjectParams& p, v16f (&acc)[CT][TT], int ct0
     uint8_t* plane = p.codes[pl] + ph * (size_t)p.t_cap * R;
 #pragma unroll
     for (int tt = 0; tt < TT; tt++) {
+      const int tok = (tb * TT + tt) * 32 + n;                          // this lane's token of the prompt
+      const int t = n0 + tok;                                           // and its cache row
+      if constexpr (R == 32) {
+        if (p.i4) {
+          // int4 (rank 32: one channel tile per head): the rule of quantize_row_i4 on the 16 channels this lane holds
+          // and the 16 of its partner half; K bytes pair dims (2 adjacent registers), V bytes pair rows t, t ^ 1 = this
+          // lane and its neighbour (the caller guarantees an even start row, so row parity = lane parity)
+          float lo = 0.f, hi = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; v++) { lo = fminf(lo, acc[h][tt][v]); hi = fmaxf(hi, acc[h][tt][v]); }
+          lo = fminf(lo, __shfl_xor(lo, 32)); hi = fmaxf(hi, __shfl_xor(hi, 32));
+          uint16_t sh = 0x3C00u;
+          float z = 0.f;
+          const bool flat = (hi == lo);
+          if (!flat) sh = guard_scale_f16((hi - lo) / 15.0f);
+          const float sc = f16_bits_to_f32(sh);
+          if (!flat) z = fminf(fmaxf(__builtin_rintf(-lo / sc), 0.f), 15.f);
+          const int zi = (int)z;
+          const bool on = tok < p.n_tok && n0 >= 0 && (n0 & 1) == 0 && t < p.t_cap;
+          uint8_t* plane4 = p.codes[pl] + ph * (size_t)p.t_cap * 16;
+#pragma unroll
+          for (int m4 = 0; m4 < 4; m4++) {
+            int q[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; jj++) {
+              const float v = fminf(fmaxf(__builtin_rintf(acc[h][tt][4 * m4 + jj] / sc), -64.f), 64.f);
+              const int qq = (int)v + zi;
+              q[jj] = qq < 0 ? 0 : (qq > 15 ? 15 : qq);
+            }
+            const int j0 = 8 * m4 + 4 * g2;                             // channels j0 .. j0 + 3
+            if (pl == 0) {
+              int nib;
+              if (on) *(uint16_t*)(plane4 + i4_k_offset(t, j0, &nib)) = (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
+            } else {
+#pragma unroll
+              for (int jj = 0; jj < 4; jj++) {
+                const int qn = __builtin_amdgcn_update_dpp(0, q[jj], kDppQuadSwap1, 0xF, 0xF, true);   // the neighbour row's code
+                const bool nb_on = tok + 1 < p.n_tok && t + 1 < p.t_cap;
+                int nib;
+                if (on && (n & 1) == 0) plane4[i4_v_offset(t, j0 + jj, &nib)] = (uint8_t)(q[jj] | ((nb_on ? qn : 0) << 4));
+              }
+            }
+          }
+          if (on && g2 == 0) *(uint32_t*)&p.meta[pl][(ph * p.t_cap + t) * 2] = (uint32_t)sh | ((uint32_t)f32_to_f16_bits_rne((float)zi) << 16);
+          continue;
+        }
+      }
       float a = 0.f;
 #pragma unroll
       for (int rt = 0; rt < RT; rt++)
@@ -52,8 +100,6 @@ WSVD_DEV void project_store(const ProjectParams& p, v16f (&acc)[CT][TT], int ct0
       uint16_t sh = 0x3C00u;
       if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
       const float sc = f16_bits_to_f32(sh);
-      const int tok = (tb * TT + tt) * 32 + n;                          // this lane's token of the prompt
-      const int t = n0 + tok;                                           // and its cache row
       if (tok >= p.n_tok || n0 < 0 || t >= p.t_cap) continue;
 #pragma unroll
       for (int rt = 0; rt < RT; rt++)
@@ -251,10 +297,14 @@ __global__ __launch_bounds__(64 * WAVES) void k_prefill_project_lds(ProjectParam
 }
 
 // after the projection: the lengths move on by the rows that fitted (one thread per sequence)
-__global__ void k_prefill_bump(int* seq_lens, int seq0, int n_seq, int n_tok, int t_cap, int* err_word) {
+__global__ void k_prefill_bump(int* seq_lens, int seq0, int n_seq, int n_tok, int t_cap, int* err_word, int even_only) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n_seq) return;
   const int n0 = seq_lens[seq0 + i];
+  if (even_only && n0 >= 0 && (n0 & 1)) {      // int4: nothing was stored for a sequence that starts on an odd row
+    atomicExch(err_word, (int)WSVD_E_SHAPE);
+    return;
+  }
   if (n0 >= 0) seq_lens[seq0 + i] = min(n0 + n_tok, t_cap);
   if (n0 < 0 || n0 + n_tok > t_cap) atomicExch(err_word, (int)WSVD_E_CAPACITY);
 }
@@ -271,7 +321,8 @@ void launch_project(const ProjectParams& p, int n_seq, hipStream_t s) {
 
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
                                        const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s) {
-  if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16 || d.x_dtype != WSVD_BF16) return hipErrorNotSupported;
+  const bool i4 = d.latent_dtype == WSVD_I4 && d.rank == 32;
+  if ((d.latent_dtype != WSVD_I8 && !i4) || d.factor_dtype != WSVD_BF16 || d.x_dtype != WSVD_BF16) return hipErrorNotSupported;
   if (d.rank != 32 && d.rank != 64 && d.rank != 96 && d.rank != 128) return hipErrorNotSupported;
   if (d.d_model % 16 != 0 || n_tok < 1) return hipErrorInvalidValue;
   ProjectParams p;
@@ -281,6 +332,7 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   p.seq_lens = cache.seq_lens; p.err_word = ctx->err_word;
   p.Hkv = d.n_kv_heads; p.E = d.d_model; p.t_cap = d.t_cap; p.n_tok = n_tok;
   p.n_cg = p.tg_seq = p.n_tg = 0;
+  p.i4 = i4 ? 1 : 0;
   const int n_seq = seq < 0 ? d.batch : 1;
   p.seq0 = seq < 0 ? 0 : seq;
   // small problems: small wave tiles, so that there are enough waves; prompt-sized ones: the LDS-staged kernel
@@ -289,6 +341,7 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   const bool staged_ok = d.d_model % kProjKC == 0 && (long long)n_tok * d.d_model * 2 < (1LL << 31);
   int shape = ctx->opt.project_shape ? ctx->opt.project_shape : (work >= (1LL << 22) ? (staged_ok ? 1 : 44) : 21);
   if ((shape == 1 || shape == 2) && !staged_ok) shape = 44;
+  if (i4 && (shape == 1 || shape == 2)) shape = 44;      // int4: the direct kernels (the staged one stores int8 rows only)
   if (d.rank > 64) {
     // ranks 96 / 128: a wave owns the 3 / 4 channel tiles of one head and 1 or 4 token tiles
     const bool big = work >= (1LL << 22);
@@ -326,6 +379,6 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_prefill_bump, dim3((n_seq + 63) / 64), dim3(64), 0, s, cache.seq_lens, p.seq0, n_seq, n_tok, d.t_cap, ctx->err_word);
+  hipLaunchKernelGGL(k_prefill_bump, dim3((n_seq + 63) / 64), dim3(64), 0, s, cache.seq_lens, p.seq0, n_seq, n_tok, d.t_cap, ctx->err_word, p.i4);
   return hipGetLastError();
 }

@@ -120,12 +120,6 @@ def test_prefill_capacity_int4_and_arguments():
             W.wsvd_prefill_append(L.ctx, L.desc, xd, None, bad_n, bad_b, AKd, AVd, L.cache)
         assert e.value.status == W.E_SHAPE
     L.close()
-    c4 = build_case("c4_small")
-    L4 = layer_for(c4); L4.upload(c4.cache)
-    with pytest.raises(W.WsvdError) as e:
-        W.wsvd_prefill_append(L4.ctx, L4.desc, xd, None, 4, 0, AKd, AVd, L4.cache)
-    assert e.value.status == W.E_UNSUPPORTED
-    L4.close()
 
 
 @pytest.mark.parametrize("name,over", [("c3_small", dict()), ("c5_small", dict()), ("c3_small", dict(rank=64, batch=2, context=45))],
@@ -227,8 +221,8 @@ def test_prefill_whole_prompt_projection_capacity_and_formats():
     assert W.wsvd_check(L.ctx) == W.E_CAPACITY and int(L.seq_lens[b]) == L.t_cap
     assert (L.download(0, 0, L.t_cap)[0] == snap).all()
     L.close()
-    # other formats take at most 64 tokens per call
-    for name in ("c2_small", "c4_small"):
+    # float latents take at most 64 tokens per call (int4 goes through the tiled projection: test_prefill_int4_tiled)
+    for name in ("c2_small",):
         c2 = build_case(name, extra_cap=128)
         L2 = layer_for(c2); L2.upload(c2.cache)
         with pytest.raises(W.WsvdError) as e:
@@ -504,4 +498,104 @@ def test_prefill_all_sequences_capacity_of_some():
     assert (L.seq_lens.cpu().numpy() == want).all() and (c.cache.seq_lens == want).all()
     for b in range(sp.batch):
         _compare_rows(L, c.cache, b, int(starts[b]), int(want[b] - starts[b]), "i8", _latents64(X[b], c.AK), _latents64(X[b], c.AV))
+    L.close()
+
+
+def _check_i4_rows(L, plane, b, t0, n, values64, what):
+    """int4 rows [t0, t0 + n) of sequence b written by the GPU from fp32 sums, against the asymmetric rule applied to the
+    oracle's fp64 latents values64 [Hkv, n, r].  A row's scale / zero point may differ from the fp64 rule's only where
+    (hi - lo) / 15 sits within 1e-5 (relative) of the midpoint between two fp16 values, or -lo / s within 1e-3 of a .5
+    rounding boundary; its codes are then checked against the rule applied with the GPU's own scale and zero point.  A
+    code may differ by one step only where value / scale lies within 1e-3 of .5.  Returns the number of accepted flips."""
+    gc, gs, gz = L.download(plane, t0, n)
+    codes = O.unpack_int4(gc[b].reshape(-1, gc.shape[-1])).reshape(gc.shape[1], n, -1).astype(np.int64)     # [Hkv, n, r]
+    gs = gs[b].astype(np.float64); gz = gz[b].astype(np.float64)
+    v = np.asarray(values64, np.float64)
+    lo = np.minimum(v.min(-1), 0.0); hi = np.maximum(v.max(-1), 0.0)
+    flat = hi == lo
+    s_exact = np.where(flat, 1.0, (hi - lo) / 15.0)
+    s_ref = np.where(flat, 1.0, s_exact.astype(np.float32).astype(np.float16).astype(np.float64))
+    flips = 0
+    ds = gs != s_ref
+    if ds.any():
+        # the two fp16 neighbours of the exact value and their midpoint
+        f16 = s_exact[ds].astype(np.float16)
+        nb = np.where(f16.astype(np.float64) < s_exact[ds], np.nextafter(f16, np.float16(np.inf)), np.nextafter(f16, np.float16(-np.inf)))
+        mid = 0.5 * (f16.astype(np.float64) + nb.astype(np.float64))
+        assert (np.abs(s_exact[ds] - mid) <= 1e-5 * s_exact[ds]).all(), f"{what}: a scale differs away from an fp16 rounding boundary"
+        assert (np.abs(gs[ds] - s_ref[ds]) <= np.abs(nb.astype(np.float64) - f16.astype(np.float64)) * 1.001).all()
+        flips += int(ds.sum())
+    z_exact = np.where(flat, 0.0, -lo / gs)
+    z_ref = np.clip(np.rint(z_exact), 0, 15)
+    dz = gz != z_ref
+    if dz.any():
+        frac = z_exact[dz] - np.floor(z_exact[dz])
+        assert (np.abs(gz[dz] - z_ref[dz]) == 1).all() and (np.abs(frac - 0.5) < 1e-3).all(), f"{what}: a zero point differs away from a rounding boundary"
+        flips += int(dz.sum())
+    x = v / gs[..., None]
+    want = np.clip(np.clip(np.rint(x), -64, 64) + gz[..., None], 0, 15).astype(np.int64)
+    bad = codes != want
+    if bad.any():
+        frac = x[bad] - np.floor(x[bad])
+        assert (np.abs(codes[bad] - want[bad]) == 1).all() and (np.abs(frac - 0.5) < 1e-3).all(), \
+            f"{what}: {int(bad.sum())} codes differ away from a rounding boundary"
+        flips += int(bad.sum())
+    assert flips <= max(3, codes.size // 300), f"{what}: {flips} boundary flips in {codes.size} codes is too many to be rounding"
+    return flips
+
+
+@pytest.mark.parametrize("all_seqs", [False, True], ids=["one-sequence", "all-sequences"])
+def test_prefill_int4_tiled(all_seqs):
+    """int4 latents through the tiled projection: a value byte holds two consecutive rows, so both rows of a byte are
+    written from one place; the target sequences stand at even lengths (0, or an even number of uploaded rows)."""
+    c = build_case("c4_small", extra_cap=300, batch=4, context=300, ragged=(100, 300))
+    sp = c.sp
+    lens = (c.cache.seq_lens // 2 * 2).astype(np.int32)
+    lens[1] = 0                                             # a fresh sequence
+    c.cache.seq_lens[:] = lens
+    assert c.t_cap >= 300 + 151 + 1
+    L = layer_for(c); L.upload(c.cache)
+    n = 151 if not all_seqs else 70                        # odd counts: the last row of the block has no partner yet
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    if all_seqs:
+        X = np.stack([WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=60 + b)) for b in range(sp.batch)])
+        W.wsvd_prefill_append(L.ctx, L.desc, as_dtype_dev(X.reshape(sp.batch * n, -1), "bf16"), None, n, -1, AKd, AVd, L.cache)
+        targets = list(range(sp.batch))
+    else:
+        b = 2
+        X = np.zeros((sp.batch, n, sp.d_model), np.float32)
+        X[b] = WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=77))
+        W.wsvd_prefill_append(L.ctx, L.desc, as_dtype_dev(X[b], "bf16"), None, n, b, AKd, AVd, L.cache)
+        targets = [b]
+    assert W.wsvd_check(L.ctx) == 0
+    got_lens = L.seq_lens.cpu().numpy()
+    for b in range(sp.batch):
+        assert got_lens[b] == lens[b] + (n if b in targets else 0)
+    total = 0
+    for b in targets:
+        for plane, A in ((0, c.AK), (1, c.AV)):
+            total += _check_i4_rows(L, plane, b, int(lens[b]), n, _latents64(X[b], A), f"int4 prefill seq {b} plane {plane}")
+    print(f"int4 prefill ({'all' if all_seqs else 'one'}): {total} boundary flips accepted", flush=True)
+    # the rows that were there before are untouched (the first new row shares no byte with them: it is an even row)
+    for b in targets:
+        if lens[b]:
+            for plane, oc in ((0, c.cache.k), (1, c.cache.v)):
+                gc, _, _ = L.download(plane, 0, int(lens[b]))
+                assert (gc[b] == oc[b, :, : int(lens[b])]).all()
+    # one more token on top goes through the ordinary append (odd row: read-modify-write of the shared byte), then the
+    # attention over everything matches the oracle run on the same hidden states
+    for b in targets:
+        assert not O.latent_prefill(c.cache, b, X[b].astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    x1 = WI.bf16_exact(c.x_new[0])
+    O.latent_append(c.cache, x1.astype(np.float64), c.AK.astype(np.float64), c.AV.astype(np.float64))
+    assert L.append(as_dtype_dev(x1, "bf16"), None, AKd, AVd) == 0
+    qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
+    got = L.attend(qd, qs, as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16"), int(c.cache.seq_lens.max()))
+    ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
+    check_out(got, ref, "i4", "attention over an int4 cache built by the tiled prefill")
+    # a sequence that stands at an odd length is left alone and reported
+    odd = int(np.nonzero(L.seq_lens.cpu().numpy() % 2 == 1)[0][0])
+    before = int(L.seq_lens[odd])
+    W.wsvd_prefill_append(L.ctx, L.desc, as_dtype_dev(X[targets[0]][:8], "bf16"), None, 8, odd, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == W.E_SHAPE and int(L.seq_lens[odd]) == before
     L.close()
