@@ -46,7 +46,13 @@ struct AttnParams {
   // = page_rows rows of every kv head; block_table [B][max_pages]
   const int* block_table;
   int page_rows, max_pages, n_pages;
+  // a launch that covers only some of a kv head's query heads (groups larger than a kernel holds run as several
+  // launches): the first query head of kv head h is h * Gmem + g0 in q and out (0 / 0: Gmem = G, g0 = 0)
+  int Gmem, g0;
 };
+
+// first query head (row of q / out) of kv head `kv` in this launch
+WSVD_DEV size_t first_head(const AttnParams& p, int kv) { return (size_t)kv * (p.Gmem ? p.Gmem : p.G) + p.g0; }
 
 struct WorkItem {
   int b, kv, chunk, n, row_begin, row_end, n_splits;
@@ -76,7 +82,7 @@ WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) { return decode_wo
 WSVD_DEV void write_zero_outputs(const AttnParams& p, const WorkItem& w) {
   if (w.chunk != 0) return;
   for (int i = threadIdx.x; i < p.G * p.out_dim; i += blockDim.x)
-    p.out[((size_t)w.b * p.Hq + w.kv * p.G) * p.out_dim + i] = 0.f;
+    p.out[((size_t)w.b * p.Hq + first_head(p, w.kv)) * p.out_dim + i] = 0.f;
 }
 
 // ---- staging of the per-head factors into LDS.
@@ -115,7 +121,7 @@ using QRegs = QRegsT<2>;
 template <int N>
 WSVD_DEV void q_issue(const AttnParams& p, int b, int kv, QRegsT<N>& r) {
   // one unconditional dword load per element: the aligned dword that contains it (4 int8, 2 bf16 or 1 fp32)
-  const size_t base = ((size_t)b * p.Hq + (size_t)kv * p.G) * p.d;
+  const size_t base = ((size_t)b * p.Hq + first_head(p, kv)) * p.d;
   const int sh = p.q_dtype == WSVD_I8 ? 2 : p.q_dtype == WSVD_BF16 ? 1 : 0;
   const int n = p.G * p.d;
 #pragma unroll
@@ -321,7 +327,7 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
   if (!bv_lds) {
     // latent-output variant: the normalised accumulator itself (B_V lives in the output projection)
     for (int i = tid; i < G * R; i += blockDim.x)
-      p.out[((size_t)w.b * p.Hq + w.kv * G) * R + i] = Ush[i] / Lsh[i / R];
+      p.out[((size_t)w.b * p.Hq + first_head(p, w.kv)) * R + i] = Ush[i] / Lsh[i / R];
     return;
   }
   // out[b, h, c] = sum_j (U[g][j] / L[g]) * B_V[kv][j][c], B_V[kv] staged in LDS.
@@ -349,7 +355,7 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       if (part == 0 && (i >> 2) < n_pair) {
         const float L = Lsh[g];
         float2 r; r.x = L > 0.f ? a0 / L : 0.f; r.y = L > 0.f ? a1 / L : 0.f;   // no visible row at all: zeros
-        *(float2*)&p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + 2 * c2] = r;
+        *(float2*)&p.out[((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + 2 * c2] = r;
       }
     }
     return;
@@ -366,6 +372,6 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       acc = fmaf(Ush[g * R + j], ((const float*)bv_lds)[j * p.d + c], acc);
     }
     acc = group_sum<4>(acc);
-    if (part == 0 && (i >> 2) < n_out) p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + c] = acc / Lsh[g];
+    if (part == 0 && (i >> 2) < n_out) p.out[((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + c] = acc / Lsh[g];
   }
 }

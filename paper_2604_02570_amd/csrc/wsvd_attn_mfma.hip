@@ -301,7 +301,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     v4i q_raw[2];
     // the lane's 8 query elements: 8, 16 or 32 bytes inside one or two aligned 16-byte pieces
     const int q_esz = p.q_dtype == WSVD_F32 ? 4 : p.q_dtype == WSVD_BF16 ? 2 : 1;
-    const size_t q_elem = ((size_t)cz * p.Hq + (size_t)cx * G + (qrow_on ? qg : 0)) * p.d + (p.d >> 1) * hf + 8 * (qrow_on ? qpart : 0);
+    const size_t q_elem = ((size_t)cz * p.Hq + first_head(p, cx) + (qrow_on ? qg : 0)) * p.d + (p.d >> 1) * hf + 8 * (qrow_on ? qpart : 0);
     const size_t q_off = q_elem * q_esz, q_o0 = q_off & ~(size_t)15;
     const size_t q_bytes = (size_t)p.B * p.Hq * p.d * q_esz;
     if (leader) {
@@ -938,7 +938,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
           const float L = Lsh[g];
           const float rl = L > 0.f ? __builtin_amdgcn_rcpf(L) : 0.f;                 // no visible row at all: zeros
           float2 r2; r2.x = a0 * rl; r2.y = a1 * rl;
-          *(float2*)&p.out[((size_t)w.b * p.Hq + w.kv * G + g) * p.d + 2 * c2] = r2;
+          *(float2*)&p.out[((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + 2 * c2] = r2;
         }
       }
     }
@@ -1571,6 +1571,16 @@ int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
 
 hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
   if (p.block_table && (p.G > 4 || rank > 64)) return hipErrorNotSupported;      // paged cache: the paired-block kernel only
+  if (p.G > 4 && latent_dtype == WSVD_I4 && rank == 32 && p.G <= 8 && !p.block_table) {
+    // int4 latents with 5..8 query heads per kv head: two launches of the paired-block kernel, 4 heads then the rest
+    AttnParams q = p;
+    for (int g0 = 0; g0 < p.G; g0 += 4) {
+      q.G = p.G - g0 < 4 ? p.G - g0 : 4; q.Gmem = p.G; q.g0 = g0;
+      hipError_t e = launch_m<32, true, 1024>(q, grid, threads > 512 ? 512 : threads, s);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   if (p.G > 4) {
     // 5..8 query heads per kv head: I8 latents only
     if (latent_dtype != WSVD_I8 || p.G > 8) return hipErrorNotSupported;
@@ -1611,7 +1621,8 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
                                  void* out, hipStream_t s) {
   const int G = d.n_q_heads / d.n_kv_heads;
   if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16) return hipErrorNotSupported;
-  if (!((d.rank == 32 && G <= 4) || (d.rank == 64 && G <= 2))) return hipErrorNotSupported;
+  if (d.rank != 32 && d.rank != 64) return hipErrorNotSupported;
+  const int gmax = d.rank == 32 ? 4 : 2;               // query heads per kv head one launch holds (registers)
   AttnParams p;
   dim3 grid;
   int threads;
@@ -1634,15 +1645,26 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
     ra.rot[0][i][0] = (float)cos(th * 32.0);  ra.rot[0][i][1] = (float)sin(th * 32.0);
     ra.rot[1][i][0] = (float)cos(th * 480.0); ra.rot[1][i][1] = (float)sin(th * 480.0);
   }
-  if (d.rank == 32) {
-    switch (G) {
-      case 1: return launch_rope<32, 1>(p, ra, grid, threads, s);
-      case 2: return launch_rope<32, 2>(p, ra, grid, threads, s);
-      case 3: return launch_rope<32, 3>(p, ra, grid, threads, s);
-      default: return launch_rope<32, 4>(p, ra, grid, threads, s);
+  // Groups of more than gmax query heads per kv head (up to 8) run as several launches over the same cache, each on the
+  // next gmax heads of every kv head: the stream is read once per launch (this variant is bound by its arithmetic per
+  // (row, head), which is the same either way).
+  for (int g0 = 0; g0 < G; g0 += gmax) {
+    const int gl = G - g0 < gmax ? G - g0 : gmax;
+    p.G = gl; p.Gmem = G; p.g0 = g0;
+    hipError_t e;
+    if (d.rank == 32) {
+      switch (gl) {
+        case 1: e = launch_rope<32, 1>(p, ra, grid, threads, s); break;
+        case 2: e = launch_rope<32, 2>(p, ra, grid, threads, s); break;
+        case 3: e = launch_rope<32, 3>(p, ra, grid, threads, s); break;
+        default: e = launch_rope<32, 4>(p, ra, grid, threads, s); break;
+      }
+    } else {
+      e = gl == 1 ? launch_rope<64, 1>(p, ra, grid, threads, s) : launch_rope<64, 2>(p, ra, grid, threads, s);
     }
+    if (e != hipSuccess) return e;
   }
-  return G == 1 ? launch_rope<64, 1>(p, ra, grid, threads, s) : launch_rope<64, 2>(p, ra, grid, threads, s);
+  return hipSuccess;
 }
 
 // ---------------------------------------------------------------- fused decode step: append + attention in one launch

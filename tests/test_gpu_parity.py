@@ -176,6 +176,8 @@ SMALL = [
     ("c2_small", dict(n_q_heads=28)),                        # bf16 latents, G = 7
     ("c2_small", dict(n_q_heads=32, rank=64)),               # bf16 latents, G = 8, rank 64
     ("c1", dict(n_q_heads=40, n_kv_heads=8)),                # fp32 latents, G = 5
+    ("c4_small", dict(n_q_heads=28, n_kv_heads=4)),          # int4 latents, G = 7: two launches over head groups (4 + 3)
+    ("c4_small", dict(n_q_heads=20, n_kv_heads=4, q_dtype="f32", context=2000, ragged=())),   # int4, G = 5 (4 + 1), several chunks
 ]
 
 
@@ -494,6 +496,10 @@ ROPE_CASES = [
     ("c3_small", dict(n_q_heads=16, n_kv_heads=4, q_dtype="bf16", context=130)),   # four
     ("c3_small", dict(rank=64, context=700)),                 # rank 64
     ("c5_small", dict(n_q_heads=4, n_kv_heads=2, context=200)),    # rank 64, two query heads per kv head
+    ("c5_small", dict(context=200)),                          # rank 64, G = 7: launches over head groups of 2, 2, 2, 1
+    ("c3_small", dict(n_q_heads=28, n_kv_heads=4)),           # rank 32, G = 7: head groups of 4 and 3
+    ("c3_small", dict(n_q_heads=20, n_kv_heads=4, context=2000, batch=2)),   # G = 5 (4 + 1) over several chunks
+    ("c3_small", dict(n_q_heads=32, n_kv_heads=4, d_head=64, context=500)),  # G = 8 (4 + 4), head dim 64
 ]
 
 
