@@ -54,6 +54,12 @@ def parse():
     ap.add_argument("--max-threads", type=int, default=0, help="cap on the attention workgroup size (tuning)")
     ap.add_argument("--single-launch", action="store_true",
                     help="c3: the experimental single-launch wsvd_decode_step kernel instead of the two calls (measured no faster)")
+    ap.add_argument("--deferred-step", action="store_true",
+                    help="c3: insist on wsvd_decode_step's deferred-row pair of launches (projection, then attention that "
+                         "finishes the row); it is what the default step runs where the library supports it")
+    ap.add_argument("--two-call-step", action="store_true",
+                    help="c3 / c4: the step as wsvd_latent_append + wsvd_decode_attn instead of one wsvd_decode_step call")
+    ap.add_argument("--step-slices", type=int, default=0, help="d_model slices of the deferred step's projection launch (tuning)")
     ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep", "probe"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
                          "c4: the ragged int4 batch (64 sequences of 1024..4096 rows); "
@@ -97,6 +103,10 @@ def main():
         c = W.wsvd_create(0)
         if args.single_launch:
             W.wsvd_ctx_set_option(c, "fused_step", 2)
+        if args.deferred_step:
+            W.wsvd_ctx_set_option(c, "step_deferred", 2)
+        if args.step_slices:
+            W.wsvd_ctx_set_option(c, "step_slices", args.step_slices)
         if args.max_threads:
             W.wsvd_ctx_set_option(c, "max_threads", args.max_threads)
         if args.wg_per_cu:
@@ -208,7 +218,7 @@ def main():
         s = sets[i % n_sets]
         if args.attn_only:
             attend(s[5], outs[i % n_sets])
-        elif args.single_launch:
+        elif not args.two_call_step:
             W.wsvd_decode_step(ctx, desc, xd, None, AKd, AVd, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
         else:
             W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, s[5])
@@ -373,7 +383,9 @@ def main():
             "cache_sets_rotated": n_sets, "cache_set_MB": round(set_bytes / 1e6, 1), "cache_pool": "one allocation",
             "launch": "hip_graph_replay" if use_graph else "eager",
             "step": "attention only" if args.attn_only else ("wsvd_decode_step (single-launch kernel)" if args.single_launch
-                                                              else "wsvd_latent_append + wsvd_decode_attn"),
+                                                              else "wsvd_latent_append + wsvd_decode_attn" if args.two_call_step
+                                                              else "wsvd_decode_step (int8 latents: projection launch + attention launch that "
+                                                                   "finishes the row; otherwise append launch + attention launch)"),
             "timing": f"ms_per_step = the first timed replay of {args.steps} steps; us_per_decode_step_repeats = {R} replays",
             "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / (args.steps * R), 6),
             "attention_alone_us": stats(attn_all), "attention_alone_warm_single_set_us": stats(warm_all) if warm_all else None,
@@ -975,7 +987,7 @@ def run_timeline(args, np, torch, W, WI):
     wl = "c5" if args.workload == "c5" else "c3"          # c5: the grouped-query kernel (28 query / 4 kv heads, rank 64, 8192 rows)
     sp = WI.spec(wl)
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
-    t_cap = (T + 63) // 64 * 64
+    t_cap = (T + 63) // 64 * 64 + (64 if args.deferred_step else 0)     # the deferred step appends a row per launch
     desc = W.layer_desc(B, Hq, Hkv, d, E, r, t_cap, "i8", "bf16", "bf16", "i8", "f32", 0.0)
     ctx = args.make_ctx()
     ws = torch.empty(W.wsvd_workspace_bytes(desc), dtype=torch.uint8, device="cuda")
@@ -996,6 +1008,12 @@ def run_timeline(args, np, torch, W, WI):
     BKd = (torch.randn((Hkv, r, d), device="cuda", generator=g) * r ** -0.5).to(torch.bfloat16)
     BVd = (torch.randn((Hkv, r, d), device="cuda", generator=g) * r ** -0.5).to(torch.bfloat16)
     out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda")
+    if args.deferred_step:
+        # wsvd_decode_step as projection launch + attention launch that finishes the row: the stamps are the second one's
+        xd = (torch.randn((B, E), device="cuda", generator=g)).to(torch.bfloat16)
+        AKd, AVd = (torch.empty(W.wsvd_factor_a_bytes(desc), dtype=torch.uint8, device="cuda") for _ in range(2))
+        for dst in (AKd, AVd):
+            W.wsvd_pack_factor_a(ctx, desc, (torch.randn((Hkv, E, r), device="cuda", generator=g) * E ** -0.5).to(torch.bfloat16), dst)
     n_keep, n_launch, max_wg = 4, 48, 8192
     tl = [torch.zeros(max_wg * 256, dtype=torch.int64, device="cuda") for _ in range(n_keep)]
     stream = torch.cuda.Stream()
@@ -1006,7 +1024,10 @@ def run_timeline(args, np, torch, W, WI):
             if i == n_launch - n_keep:
                 e0.record(stream)
             W.wsvd_timeline_set_buffer(ctx, tl[keep] if keep >= 0 else None)
-            W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, caches[i % n_sets], T, out)
+            if args.deferred_step:
+                W.wsvd_decode_step(ctx, desc, xd, None, AKd, AVd, qd, qsd, BKd, BVd, caches[i % n_sets], t_cap, out)
+            else:
+                W.wsvd_decode_attn(ctx, desc, qd, qsd, BKd, BVd, caches[i % n_sets], T, out)
         e1.record(stream)
         stream.synchronize()
         assert W.wsvd_check(ctx, stream) == 0
@@ -1038,6 +1059,15 @@ def run_timeline(args, np, torch, W, WI):
             lines.append(f"  {slot} {nm:26s} n={v.size:5d}  min {rel.min():6.2f}  p50 {np.percentile(rel, 50):6.2f}  "
                          f"p90 {np.percentile(rel, 90):6.2f}  max {rel.max():6.2f} us")
         summary.append(rows)
+        # the same stamps by wavefront index within the workgroup (median over workgroups)
+        for slot in (1, 4, 5):
+            med = []
+            for wv in range(16):
+                v = a[:, wv, slot]
+                v = v[v > 0]
+                if v.size:
+                    med.append(f"{(np.median(v) - t0) * 0.01:.2f}")
+            lines.append(f"  {slot} {names[slot]:26s} median by wavefront index: " + " ".join(med))
     print("\n".join(lines))
     print(json.dumps({"timeline": ("k_attn_mfma at c3 (B=16 H=32 r=32 T=2048, int8)" if wl == "c3" else
                                    "k_attn_gqa at c5 (B=32, 28 query / 4 kv heads, r=64, T=8192, int8)") +

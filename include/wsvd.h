@@ -256,10 +256,14 @@ wsvd_status wsvd_decode_attn_rope(wsvd_ctx *ctx, const wsvd_layer_desc *desc, co
 
 /*
  * One decode step of a layer (Section 3.4, decoding pipeline): wsvd_latent_append followed by wsvd_decode_attn,
- * with the same arguments and the same results (the attention includes the row just appended).  By default the
- * two kernels are launched back to back.  A single-launch kernel exists for I8 / I4 latents with bf16 hidden
- * states and factors and at most 4 query heads per kv head ("fused_step" setting of wsvd_test.h); it measured no faster on
- * MI355X, so it is not the default.
+ * with the same arguments and the same results (the attention includes the row just appended).  Two launches.
+ * I8 latents, rank 32 / 64, bf16 hidden states and factors, at most 4 query heads per kv head: the first launch only
+ * projects (partial sums over slices of d_model into the workspace) and advances the lengths; the attention launch
+ * sums the slices, quantises, stores the new rows and takes them from registers, so the hand-off between the
+ * append's workgroups is the kernel boundary itself ("step_deferred" setting of wsvd_test.h; the stored codes may
+ * differ from wsvd_latent_append's where the fp32 sums, taken in another order, fall on the other side of a rounding
+ * boundary).  Every other combination: the append kernel and the attention kernel back to back.  A single-launch
+ * kernel also exists ("fused_step" setting); it measured no faster on MI355X, so it is not the default.
  *   max_seq_len: host upper bound on the sequence lengths AFTER the append (>= 1).
  * Capacity handling as in wsvd_latent_append: a full sequence is attended as it is and reported by wsvd_check.
  */

@@ -28,6 +28,10 @@ wsvd_status wsvd_timeline_set_buffer(wsvd_ctx *ctx, void *dev_ptr, size_t bytes)
  * Settings of wsvd_ctx_set_option (wsvd.h) that choose between alternative kernels, for tests and measurements:
  *   "fused_step":     wsvd_decode_step uses 0 = two launches (default), 1 = the single-launch kernel where one exists,
  *                     2 = the single-launch kernel or WSVD_E_UNSUPPORTED
+ *   "step_deferred":  which two launches: 1 = projection launch + attention launch that finishes the row where that
+ *                     pair exists (default), 2 = that pair or WSVD_E_UNSUPPORTED, 0 = always the append kernel + the
+ *                     attention kernel
+ *   "step_slices":    d_model slices of that projection launch: 0 = automatic (about one workgroup per CU), 1..4
  *   "append_helpers": helper workgroups per unit of the default append kernel: -1 = automatic, 0 or 2
  *   "linear_direct":  1 = the W4A8 linear layers read their operands straight from memory (no LDS staging)
  *   "prefill_tiled":  1 = wsvd_prefill_attn and wsvd_prefill_append take their tiled kernels also for small calls

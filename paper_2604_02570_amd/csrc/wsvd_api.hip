@@ -214,6 +214,8 @@ wsvd_status wsvd_ctx_set_option(wsvd_ctx* ctx, const char* name, int value) {
   if (!strcmp(name, "static_limit_kib") && value >= 0 && value <= (int)(kStaticScratchBytes >> 10)) { o.static_limit_kib = value; return WSVD_OK; }
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { o.linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { o.prefill_tiled = value; return WSVD_OK; }
+  if (!strcmp(name, "step_deferred") && value >= 0 && value <= 2) { o.step_deferred = value; return WSVD_OK; }
+  if (!strcmp(name, "step_slices") && value >= 0 && value <= 4) { o.step_slices = value; return WSVD_OK; }
   if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 2 || value == 21 || value == 24 || value == 42 || value == 44)) { o.project_shape = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
 }
@@ -554,6 +556,25 @@ wsvd_status wsvd_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
                                                             max_seq_len, out, s)
                                   : hipErrorNotSupported;
   if (e == hipErrorNotSupported && ctx->opt.fused_step == 2) return WSVD_E_UNSUPPORTED;
+  if (e == hipErrorNotSupported && ctx->opt.step_deferred && ctx->opt.append_mode == 0 && wsvd_step_deferred_ok(*desc)) {
+    // projection launch (partial sums, lengths advanced), then the attention launch that finishes the rows
+    float* parts = nullptr;
+    int* pending = nullptr;
+    int n_parts = 0;
+    e = wsvd_launch_append_project(ctx, *desc, x, A_K, A_V, *cache, &parts, &pending, &n_parts, s);
+    if (e == hipSuccess) {
+      AttnParams p;
+      dim3 grid;
+      int threads;
+      wsvd_attn_plan(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, p, grid, threads, 0);
+      const size_t plane = (size_t)desc->batch * desc->n_kv_heads * desc->rank;
+      p.new_k = parts; p.new_v = parts + plane; p.new_ld = (long)desc->n_kv_heads * desc->rank;
+      p.n_parts = n_parts; p.part_stride = (long)(2 * plane); p.pending = pending;
+      e = wsvd_launch_attn_newrow(p, desc->rank, grid, threads, s);
+    }
+    if (e != hipErrorNotSupported) return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+  }
+  if (e == hipErrorNotSupported && ctx->opt.step_deferred == 2) return WSVD_E_UNSUPPORTED;
   if (e == hipErrorNotSupported) {
     // no fused kernel for this combination: the two calls back to back on the stream
     e = wsvd_launch_append(ctx, *desc, x, x_scale, A_K, A_V, *cache, s);

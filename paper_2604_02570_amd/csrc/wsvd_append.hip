@@ -115,7 +115,11 @@ hipError_t wsvd_launch_pack_factor_a(const wsvd_layer_desc& d, const void* src, 
 // loads); partial tiles meet in LDS (in the hidden states' place) and are summed in wave order.
 constexpr uint32_t kLLTag = 0x4C4C5701u;      // marks a pushed word as written by the running launch's helper
 
-template <int R, int NT>
+// DEFER (the decode step's projection launch): NP equal slices of d_model per (plane, kv head), no finisher and no
+// hand-off inside the launch: every workgroup leaves its partial sums in p.defer_out, workgroup 0 of each group of
+// sequences advances the lengths and marks the rows as pending; the attention launch that follows sums the slices in
+// slice order, quantises and stores the rows (the kernel boundary is the hand-off).
+template <int R, int NT, bool DEFER = false>
 __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int xs_stride /* elements */, int NP,
                                                      unsigned long long* ll /* [units][groups][NP][SB * R] */) {
   extern __shared__ __align__(16) uint8_t app_lds[];
@@ -126,8 +130,9 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
   uint16_t* xs = (uint16_t*)app_lds;                            // [SB][xs_stride] hidden states (bf16)
   float (*red)[R + 1] = (float (*)[R + 1])app_lds;              // [NW * SB][R + 1] partial tiles, later [SB][R + 1] rows
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
-  const int unit = (int)blockIdx.x / (NP + 1), role = (int)blockIdx.x % (NP + 1);   // role < NP: helper, NP: finisher
-  const bool finisher = role == NP;
+  const int n_roles = DEFER ? NP : NP + 1;
+  const int unit = (int)blockIdx.x / n_roles, role = (int)blockIdx.x % n_roles;     // role < NP: helper, NP: finisher
+  const bool finisher = !DEFER && role == NP;
   const int pl = unit / p.Hkv, kv = unit % p.Hkv;
   const int b0 = (int)blockIdx.y * SB, nb = min(SB, p.B - b0);
   const int col = lane & 31, g = lane >> 5;
@@ -137,12 +142,13 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
   const int nreg = finisher ? append_target_row(p, b0 + min(tid, nb - 1)) : 0;
   // ... and, for the finisher that will turn out to be the last one, the lengths it advances on its way out: asked for
   // now, they cost nothing then (nobody writes them before that)
-  const int n_bump = (finisher && !p.fused) ? p.seq_lens[p.one_seq >= 0 ? p.one_seq : min(tid, p.B - 1)] : 0;
+  int n_bump = (finisher && !p.fused) ? p.seq_lens[p.one_seq >= 0 ? p.one_seq : min(tid, p.B - 1)] : 0;
+  if (DEFER && blockIdx.x == 0) n_bump = p.seq_lens[b0 + min(tid, nb - 1)];
   const uint16_t* Ap = (const uint16_t*)p.A[pl];
   const uint16_t* xp = (const uint16_t*)p.x;
   // ---- this workgroup's share of the k-steps (16 model dims each), then this wave's share of that
   const int nks = p.E >> 4;
-  const int nks_fin = NP ? (nks + 1) / 2 : nks;                 // the finisher's share comes first
+  const int nks_fin = DEFER ? 0 : NP ? (nks + 1) / 2 : nks;     // the finisher's share comes first
   const int per_helper = NP ? (nks - nks_fin + NP - 1) / NP : 0;
   const int wg_k0 = finisher ? 0 : min(nks, nks_fin + role * per_helper);
   const int wg_k1 = finisher ? nks_fin : min(nks, wg_k0 + per_helper);
@@ -243,7 +249,9 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
       const int row = i / R, j = i % R;
       float c = 0.f;
       for (int k = 0; k < NW; k++) c += red[k * SB + row][j];
-      if (!finisher) {
+      if constexpr (DEFER) {
+        p.defer_out[(((size_t)role * 2 + pl) * p.B + b0 + row) * ((size_t)p.Hkv * R) + (size_t)kv * R + j] = c;
+      } else if (!finisher) {
         // push: value and tag in one 8-byte store, written through; nobody waits for it
         const unsigned long long word = ((unsigned long long)kLLTag << 32) | (unsigned long long)__float_as_uint(c);
         __hip_atomic_store(ll_unit + (size_t)role * (SB * R) + (size_t)row * R + j, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -270,6 +278,16 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
         red[row][j] = c;
       }
     }
+  }
+  if constexpr (DEFER) {
+    if (blockIdx.x == 0 && tid < nb) {
+      const bool ok = n_bump >= 0 && n_bump < p.t_cap;
+      if (ok) p.seq_lens[b0 + tid] = n_bump + 1;
+      else atomicExch(p.err_word, (int)WSVD_E_CAPACITY);
+      p.pending[b0 + tid] = ok ? 1 : 0;
+    }
+    WSVD_STAMP(p.timeline, tl_wg, wave, 5);
+    return;
   }
   if (!finisher) return;
   __syncthreads();
@@ -345,6 +363,63 @@ static hipError_t launch_append_split(const AppendParams& p, const wsvd_layer_de
   return hipGetLastError();
 }
 
+static bool append_mfma_path(const wsvd_layer_desc& d);
+// The decode step's projection launch: `ns` equal d_model slices per (plane, kv head), partial sums to p.defer_out.
+template <int R, int NT>
+static hipError_t launch_append_project(const AppendParams& p, const wsvd_layer_desc& d, int ns, hipStream_t s) {
+  const int nks = d.d_model / 16;
+  const int share = (nks + ns - 1) / ns * 16;
+  const int stride = share + 8;
+  int sb = 16;
+  while (sb > 1 && (size_t)sb * stride * 2 > (size_t)144 * 1024) sb >>= 1;
+  const int groups = (d.batch + sb - 1) / sb;
+  const int nw = NT / 64;
+  size_t lds = (size_t)sb * stride * 2;
+  const size_t red_bytes = (size_t)nw * sb * (R + 1) * 4;
+  if (red_bytes > lds) lds = red_bytes;
+  if (lds > (size_t)150 * 1024) return hipErrorInvalidValue;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_append_split<R, NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  dim3 grid((unsigned)(2 * d.n_kv_heads * ns), (unsigned)groups);
+  hipLaunchKernelGGL((k_append_split<R, NT, true>), grid, dim3(NT), lds, s, p, sb, stride, ns, (unsigned long long*)nullptr);
+  return hipGetLastError();
+}
+
+// slices of the decode step's projection launch: about one workgroup per CU, at most 4, slices of whole k-steps
+int wsvd_step_slices(const wsvd_ctx* ctx, const wsvd_layer_desc& d) {
+  int ns = ctx->opt.step_slices > 0 ? ctx->opt.step_slices : ctx->n_cu / (2 * d.n_kv_heads);
+  if (ns > 4) ns = 4;
+  while (ns > 1 && d.d_model / 16 / ns < 4) ns--;
+  return ns < 1 ? 1 : ns;
+}
+bool wsvd_step_deferred_ok(const wsvd_layer_desc& d) {
+  return append_mfma_path(d) && d.latent_dtype == WSVD_I8 && (d.rank == 32 || d.rank == 64) &&
+         d.n_q_heads / d.n_kv_heads <= 4 && d.d_model % 16 == 0 && d.batch <= kAppendMaxB;
+}
+// floats of the step's partial sums (+ one word per sequence), inside the sliced kernels' partial area
+hipError_t wsvd_launch_append_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* A_K,
+                                      const void* A_V, const wsvd_cache& cache, float** parts, int** pending, int* n_parts,
+                                      hipStream_t s) {
+  AppendParams p;
+  wsvd_append_params(ctx, d, x, nullptr, A_K, A_V, cache, p);
+  const int ns = wsvd_step_slices(ctx, d);
+  const size_t part_floats = (size_t)ns * 2 * d.batch * d.n_kv_heads * d.rank;
+  if (part_floats > (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank) return hipErrorNotSupported;
+  p.defer_out = p.partials;
+  p.pending = (int*)(p.partials + part_floats);
+  p.timeline = nullptr;                  // (profiling build: the stamps of a step are its attention launch's)
+  *parts = p.defer_out; *pending = p.pending; *n_parts = ns;
+  switch (d.rank) {
+    case 32: return launch_append_project<32, 1024>(p, d, ns, s);
+    case 64: return launch_append_project<64, 512>(p, d, ns, s);
+    default: return hipErrorNotSupported;
+  }
+}
+
 // d_model slices per (plane, kv head).
 // One CU cannot pull more than a few tens of GB/s on its own, so the factor stream has to be spread over all of
 // them: the MFMA path aims at about one workgroup per CU (256) and merges the slices through the ticket.
@@ -374,7 +449,8 @@ static size_t wsvd_append_pushed_floats(const wsvd_layer_desc& d) {
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d) {
   // the pushed words of the default kernel (which are zero between launches), then the sliced kernels' partial sums
   // (the most slices an option can ask for)
-  const size_t sliced = (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank;
+  // (+ one word per sequence behind the decode step's partial sums, which use this area too)
+  const size_t sliced = (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank + ((size_t)d.batch + 3) / 4 * 4;
   return wsvd_append_pushed_floats(d) + sliced;
 }
 

@@ -28,6 +28,10 @@ struct AppendParams {
   // paged cache only (else null): codes / meta are pools of n_pages pages, a page = page_rows rows of every kv head
   const int* block_table;    // [B][max_pages]
   int page_rows, max_pages, n_pages;
+  // projection-only launch of the decode step (k_append_split<.., true>): partial sums [slice][plane][B][Hkv * R] fp32,
+  // and one word per sequence saying that its length was advanced and the row is still to be written
+  float* defer_out;
+  int* pending;
 };
 
 // which sequence a row of x belongs to, and the cache row it goes to given that sequence's length

@@ -49,6 +49,12 @@ struct AttnParams {
   // a launch that covers only some of a kv head's query heads (groups larger than a kernel holds run as several
   // launches): the first query head of kv head h is h * Gmem + g0 in q and out (0 / 0: Gmem = G, g0 = 0)
   int Gmem, g0;
+  // deferred-row variant only (the decode step's second launch): the step's projection launch has left the new token's
+  // latents as n_parts partial sums, new_k / new_v [part][B][new_ld] fp32 with part_stride floats between parts, has
+  // advanced the lengths already and set pending[b] != 0 for every sequence whose last row is still to be written
+  const int* pending;
+  int n_parts;
+  long part_stride;
 };
 
 // first query head (row of q / out) of kv head `kv` in this launch

@@ -204,7 +204,10 @@ WSVD_DEV void split_fp16_pair(float x, float scale, _Float16& hi, _Float16& lo) 
 // very moment.  The row counts as present; the 64-row tile that contains it is kept out of the streaming loop and
 // done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
 // ROPE_D != 0: the rotary variant for head dimension ROPE_D (I8 latents; rs, ra non-null).
-template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0, bool LATENT = false, bool PAGED = false>
+// NEWROW: the second launch of the decode step.  The projection launch before it has advanced the lengths and left the
+// new token's latents as partial sums; the workgroup whose chunk holds a sequence's last row sums them, quantises and
+// stores the row (as the append would have) and patches it into the registers of the wave that consumes its tile.
+template <int R, int G, bool I4, int NT, bool FUSED, int ROPE_D = 0, bool LATENT = false, bool PAGED = false, bool NEWROW = false>
 WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE_D != 0 || LATENT)>& sh, const int cx, const int cy,
                              const int cz, RopeShared<R, G, (ROPE_D ? ROPE_D : 64)>* rs = nullptr, const RopeArgs* ra = nullptr) {
   constexpr bool ROPE = ROPE_D != 0;
@@ -214,6 +217,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   static_assert(!LATENT || (!ROPE && !FUSED), "latent-query variant: stand-alone launch, no rotation");
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(!PAGED || (!ROPE && !LATENT && !FUSED), "paged cache: the plain decode attention");
+  static_assert(!NEWROW || (!ROPE && !LATENT && !FUSED && !PAGED && !I4), "deferred row: the plain int8 decode attention");
   static_assert(G >= 1 && G <= 4, "paired-block kernel handles up to 4 query heads per kv head");
   constexpr int KK = R / 32;
   constexpr int NWMAX = NT / 64;
@@ -225,8 +229,15 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   // scalar loads first: issued ahead of the flood of vector loads they come back quickly, and nothing needs them
   // until the tile loop
   const int n_raw = p.seq_lens[cz];
+  [[maybe_unused]] const int pend_raw = NEWROW ? p.pending[cz] : 0;
   const uint32_t qs_raw = q_scale_raw(p, cz);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
+  // NEWROW: the row stored by this launch (K | V codes and scales): written by the workgroup's last wave, read by the
+  // wave that consumes the row's tile once new_ready says so
+  __shared__ __attribute__((aligned(16))) uint8_t new_codes[2][NEWROW ? R : 16];
+  __shared__ uint16_t new_scale[2];
+  __shared__ int new_ready;
+  if (NEWROW && tid == 0) new_ready = 0;          // (ordered before its first use by the workgroup barrier below)
   __builtin_amdgcn_s_setprio(3);          // streaming waves first (see the end of the tile loop)
   [[maybe_unused]] long long* const tl = FUSED ? nullptr : p.timeline;
   [[maybe_unused]] const int tl_wg = (cz * (int)gridDim.y + cy) * (int)gridDim.x + cx;
@@ -280,6 +291,10 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   int T = (int)cy * chunk_tiles + wave;
   // unconditional (clamped to the chunk's last allocated tile): see stage_issue
   const int spec_last = min(((int)cy + 1) * chunk_tiles, p.t_cap >> 6) - 1;
+  constexpr int MAXP = 4;                                        // NEWROW: partial sums per latent element, at most
+  // rank 32: lanes 0..31 carry the K row's dims, lanes 32..63 the V row's (np_a); rank 64: np_a = K, np_b = V
+  [[maybe_unused]] float np_a[NEWROW ? MAXP : 1], np_b[NEWROW && R == 64 ? MAXP : 1];
+  [[maybe_unused]] bool nr_mine = false;
   if constexpr (!STAGED) {
     // Query absorption q~ = c_scale * B_K q on the matrix cores, by the workgroup's first wave alone, operands
     // straight from memory (no staging in LDS): 8-16 KB of B_K and the queries are the only small loads of the
@@ -314,6 +329,23 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
       }
     q_raw[0] = *(const v4i*)((const char*)p.q + q_o0);
     q_raw[1] = *(const v4i*)((const char*)p.q + min(q_o0 + 16, q_bytes - 16));
+    }
+    // NEWROW: the workgroup's last wave asks for the partial sums of its (sequence, kv head) now, ahead of the tiles and
+    // whether or not the row turns out to be this workgroup's (the addresses do not depend on the length).  They were
+    // written by the launch before this one, on other XCDs: they come from memory, not from this XCD's L2
+    if constexpr (NEWROW) {
+      if (wave == NW - 1) {
+        const float* src = (R == 32 && lane >= 32) ? p.new_v : p.new_k;
+        const size_t o = (size_t)cz * p.new_ld + (size_t)cx * R + (lane & (R - 1));
+        // straight-line, clamped (a surplus slot repeats the last part and is left out of the sum): loads under
+        // branches made the compiler wait for them on the spot, in front of the barrier below
+#pragma unroll
+        for (int sidx = 0; sidx < MAXP; sidx++) {
+          const size_t po = (size_t)min(sidx, p.n_parts - 1) * p.part_stride + o;
+          np_a[sidx] = src[po];
+          if constexpr (R == 64) np_b[sidx] = p.new_v[po];
+        }
+      }
     }
     // The barrier (no memory wait) puts the leader's small loads ahead of every wave's tile loads in the CU's address
     // pipeline: the first two tiles of 16 waves are 190 KB of requests, more than a microsecond of that pipeline, and
@@ -418,6 +450,47 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     }   // leader
     __syncthreads();
     WSVD_STAMP(tl, tl_wg, wave, 3);
+    if constexpr (NEWROW) {
+      // The row, by the last wave, off everybody else's path: the other waves go on to their tiles, the wave that
+      // consumes the row's tile (its last one) looks at new_ready when it gets there.
+      // (A sequence longer than the caller's bound is reported by decode_work; its row is still stored, by the last chunk.)
+      if (wave == NW - 1) {
+        const int row = n_raw - 1, ct = p.chunk_rows >> 6, cyo = min((row >> 6) / ct, p.n_chunks - 1);
+        if (pend_raw != 0 && n_raw >= 1 && n_raw <= p.t_cap && (int)cy == cyo) {       // wave-uniform
+          // (the empty statements pin the first use of the loaded values here: hoisted to the loads, the first
+          // addition made the whole workgroup wait for them in front of the barrier above)
+#pragma unroll
+          for (int sidx = 0; sidx < MAXP; sidx++) {
+            asm volatile("" : "+v"(np_a[sidx]));
+            if constexpr (R == 64) asm volatile("" : "+v"(np_b[sidx]));
+          }
+          // The cache row for later launches (the rule and the layout of the append kernels' row store), and a copy in
+          // LDS for this one: the tile that holds the row is fetched like any other, possibly before these stores land;
+          // its consumer overwrites the row's bytes in registers.  One pass with both rows side by side at rank 32.
+          const int j = lane & (R - 1);
+#pragma unroll
+          for (int pass = 0; pass < (R == 32 ? 1 : 2); pass++) {
+            const int pl = R == 32 ? (lane >> 5) : pass;
+            float c = 0.f;
+#pragma unroll
+            for (int sidx = 0; sidx < MAXP; sidx++)                    // slice order
+              c += sidx < p.n_parts ? (pass == 0 ? np_a[sidx] : np_b[R == 64 ? sidx : 0]) : 0.f;
+            const float a = R == 64 ? wave_max(fabsf(c)) : half_max(fabsf(c), lane);
+            uint16_t sh16 = 0x3C00u;
+            if (a != 0.f) sh16 = guard_scale_f16(a / 127.0f);
+            const float sc = f16_bits_to_f32(sh16);
+            const uint8_t code = (uint8_t)(int8_t)(int)fminf(fmaxf(__builtin_rintf(c / sc), -127.f), 127.f);
+            uint8_t* plane = const_cast<uint8_t*>(pl ? p.v_codes : p.k_codes) + ph * plane_bytes;
+            plane[pl ? i8_v_offset(row, j, R) : i8_k_offset(row, j, R)] = code;
+            if (j == 0) const_cast<uint16_t*>(pl ? p.v_meta : p.k_meta)[ph * (size_t)p.t_cap + row] = sh16;
+            new_codes[pl][j] = code;
+            if (j == 0) new_scale[pl] = sh16;
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+          if (lane == 0) __hip_atomic_store(&new_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
+    }
   } else {
   const int fac16 = R * p.d * 2 / 16;
   StageRegs<FIT> stk, stv;
@@ -590,6 +663,9 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   const int new_tile = n_raw >> 6;                                      // tile of the new row (its chunk's last tile)
   const bool own_new = has_new && new_tile >= cy * chunk_tiles && new_tile < (cy + 1) * chunk_tiles;
   const int tile_end = ((w.row_end + 63) >> 6) - (own_new ? 1 : 0);
+  [[maybe_unused]] const int nr_row = n_raw - 1, nr_tile = nr_row >> 6;
+  if constexpr (NEWROW)
+    nr_mine = pend_raw != 0 && n_raw >= 1 && n_raw <= p.t_cap && nr_tile >= cy * chunk_tiles && nr_tile < (cy + 1) * chunk_tiles;
   float delta[G], zsum[G];
 #pragma unroll
   for (int g = 0; g < G; g++) {
@@ -661,6 +737,38 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   // the score products, the value side at the end
   auto compute = [&](auto refill, TileRegs<R, I4>& t, int tile, int next) {
     const bool valid = tile * 64 + lane < w.row_end;
+    if constexpr (NEWROW) {
+      if (nr_mine && tile == nr_tile) {                    // wave-uniform: put the row stored by this launch into the tile
+        int budget = 1 << 20;                              // (the last wave wrote it microseconds ago; the bound keeps the kernel finite)
+        while (__hip_atomic_load(&new_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0 && budget > 0) {
+          __builtin_amdgcn_s_sleep(2);
+          budget--;
+        }
+        if (budget == 0 && lane == 0) atomicExch(p.err_word, (int)WSVD_E_HIP);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int ti = nr_row & 63, blk = ti >> 5, tn = ti & 31;
+        const int l32 = lane & 31, hf = lane >> 5;
+#pragma unroll
+        for (int b2 = 0; b2 < 2; b2++) {
+          if (b2 == blk) {
+#pragma unroll
+            for (int kk = 0; kk < KK; kk++) {
+              // K: lane (token tn, dim half hf) holds dims 32 kk + 16 hf .. + 15 of its token
+              if (l32 == tn) t.k[kk][b2] = *(const v4i*)&new_codes[0][32 * kk + 16 * hf];
+              // V: lane (dim 32 kk + l32, token half hf) holds 16 tokens of its dim: byte tn % 16 of the half tn / 16
+              if (hf == (tn >> 4)) {
+                const uint32_t byte = new_codes[1][32 * kk + l32];
+                const int dw = (tn & 15) >> 2, sh8 = 8 * (tn & 3);
+#pragma unroll
+                for (int e = 0; e < 4; e++)
+                  if (e == dw) t.v[kk][b2][e] = (int)(((uint32_t)t.v[kk][b2][e] & ~(0xFFu << sh8)) | (byte << sh8));
+              }
+            }
+          }
+        }
+        if (lane == ti) { t.kmeta = new_scale[0]; t.vmeta = new_scale[1]; }
+      }
+    }
     // ---------------- score pass
     v16i acc = {0};
     float ksc, kz = 0.f, vsc, vz = 0.f;
@@ -950,6 +1058,12 @@ template <int R, int G, bool I4, int NT, bool PAGED = false>
 __global__ __launch_bounds__(NT) void k_attn_mfma(AttnParams p) {
   __shared__ AttnMfmaShared<R, G, NT, false> sh;
   attn_mfma_body<R, G, I4, NT, false, 0, false, PAGED>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+template <int R, int G, int NT>
+__global__ __launch_bounds__(NT) void k_attn_mfma_newrow(AttnParams p) {
+  __shared__ AttnMfmaShared<R, G, NT, false> sh;
+  attn_mfma_body<R, G, false, NT, false, 0, false, false, true>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // Q latent in, latent-space output out (Section 3.4: the Q latent's up-projection B_Q meets B_K^T in one small matrix
@@ -1492,6 +1606,27 @@ static hipError_t launch_m(const AttnParams& p, dim3 grid, int threads, hipStrea
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int R, int NT>
+static hipError_t launch_m_newrow(const AttnParams& p, dim3 grid, int threads, hipStream_t s) {
+  constexpr int NTG = NT > 512 ? 512 : NT;
+  if (threads > (p.G == 1 ? NT : NTG) || threads % 64) return hipErrorInvalidValue;
+  switch (p.G) {
+    case 1: hipLaunchKernelGGL((k_attn_mfma_newrow<R, 1, NT>), grid, dim3(threads), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((k_attn_mfma_newrow<R, 2, NTG>), grid, dim3(threads), 0, s, p); break;
+    case 3: hipLaunchKernelGGL((k_attn_mfma_newrow<R, 3, NTG>), grid, dim3(threads), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((k_attn_mfma_newrow<R, 4, NTG>), grid, dim3(threads), 0, s, p); break;
+    default: return hipErrorNotSupported;
+  }
+  return hipGetLastError();
+}
+// int8 latents, rank 32 / 64, up to 4 query heads per kv head, at most 4 partial sums
+hipError_t wsvd_launch_attn_newrow(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s) {
+  if (!p.pending || !p.new_k || !p.new_v || p.n_parts < 1 || p.n_parts > 4 || p.block_table) return hipErrorInvalidValue;
+  if (rank == 32) return launch_m_newrow<32, 1024>(p, grid, threads, s);
+  if (rank == 64) return launch_m_newrow<64, 512>(p, grid, threads, s);
+  return hipErrorNotSupported;
 }
 
 template <int R, bool I4, int NT>

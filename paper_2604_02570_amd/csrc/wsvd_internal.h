@@ -17,6 +17,8 @@ struct wsvd_options {
   int static_limit_kib = 0; // wsvd_decode_attn_static: pretend the static array is this small (tests of the rejection; 0 = its size)
   int prefill_tiled = 0;    // the tiled prefill kernels also for small calls
   int project_shape = 0;    // kernel of the tiled prefill projection (0 = automatic)
+  int step_deferred = 1;    // wsvd_decode_step: projection launch + attention launch that finishes the row: 1 where supported, 2 that or UNSUPPORTED
+  int step_slices = 0;      // d_model slices of that projection launch (0 = automatic)
 };
 
 struct wsvd_ctx {
@@ -97,6 +99,11 @@ hipError_t wsvd_launch_linear_w4a8(const int8_t* x, const void* x_scale, const v
 // workspace sizing shared by the API and the launchers
 size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
 hipError_t wsvd_launch_attn_gqa_store(const struct AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
+hipError_t wsvd_launch_attn_newrow(const struct AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
+bool wsvd_step_deferred_ok(const wsvd_layer_desc& d);
+hipError_t wsvd_launch_append_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* A_K,
+                                      const void* A_V, const wsvd_cache& cache, float** parts, int** pending, int* n_parts,
+                                      hipStream_t s);
 size_t wsvd_attn_split_bytes(const wsvd_ctx* ctx, const wsvd_layer_desc& d, int max_seq_len);
 size_t wsvd_append_partial_floats(const wsvd_layer_desc& d);
 int wsvd_append_esplits(const wsvd_ctx* ctx, const wsvd_layer_desc& d);

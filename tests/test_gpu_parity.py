@@ -551,8 +551,25 @@ STEP_CASES = [
     ("c4_small", dict(), 2),                                      # int4, ragged lengths
     ("c2_small", dict(), 1),                                      # bf16 latents: no single-launch kernel, two launches
     ("c1", dict(batch=3, context=70), 1),                         # fp32: likewise
-    ("c3_small", dict(), 0),                                      # the default: two launches
+    ("c3_small", dict(), 0),                                      # the append launch and the attention launch
+    # mode 3: projection launch + attention launch that sums the slices, quantises, stores and patches the row
+    ("c3_small", dict(), 3),
+    ("c3_small", dict(context=2000, batch=2), 3),                 # several chunks: the row's chunk finishes it
+    ("c3_small", dict(rank=64, context=700), 3),
+    ("c3_small", dict(n_q_heads=8, n_kv_heads=4, q_dtype="f32"), 3),
+    ("c5_small", dict(n_q_heads=8, n_kv_heads=2), 3),             # rank 64, four query heads per kv head
+    ("c3_small", dict(batch=21, context=130), 3),                 # two groups of sequences in the projection launch
+    ("c3_small", dict(), -1),                                     # whatever the library does by default
+    ("c4_small", dict(), -1),
 ]
+
+
+def _set_step_mode(ctx, mode):
+    """0 two launches, 1 / 2 the single-launch kernel (where it exists / or refuse), 3 the deferred-row pair of launches."""
+    if mode < 0:
+        return                                          # the context's defaults
+    W.wsvd_ctx_set_option(ctx, "fused_step", mode if mode in (1, 2) else 0)
+    W.wsvd_ctx_set_option(ctx, "step_deferred", 2 if mode == 3 else 0)
 
 
 @pytest.mark.parametrize("name,over,mode", STEP_CASES, ids=[f"{n}-{'-'.join(f'{k}{v}' for k, v in o.items())}" for n, o, _ in STEP_CASES])
@@ -569,7 +586,7 @@ def test_decode_step_matches_oracle(name, over, mode):
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
     flips = 0
     try:
-        W.wsvd_ctx_set_option(L.ctx, "fused_step", mode)
+        _set_step_mode(L.ctx, mode)
         for step in range(3):
             x = c.x_new[step]
             if xdt == "bf16":
@@ -587,7 +604,7 @@ def test_decode_step_matches_oracle(name, over, mode):
             check_out(got, ref, sp.latent_dtype, f"step {step} {name}{over}")
             L.upload(c.cache)      # continue from the oracle's cache so that later steps compare like with like
     finally:
-        W.wsvd_ctx_set_option(L.ctx, "fused_step", 0)
+        _set_step_mode(L.ctx, -1 if mode < 0 else 0)
     assert flips <= max(2, 2 * sp.batch * sp.n_kv_heads * sp.rank * 3 // 500)
     L.close()
 
@@ -608,13 +625,13 @@ def test_decode_step_tile_boundaries_and_capacity():
     x = WI.bf16_exact(c.x_new[0]); x64 = x.astype(np.float64)
     qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
     outs = []
-    for mode in (2, 0):
+    for mode in (2, 3, 0):
         L.upload(c.cache)
-        W.wsvd_ctx_set_option(L.ctx, "fused_step", mode)
+        _set_step_mode(L.ctx, mode)
         try:
             got, st = L.step(as_dtype_dev(x, "bf16"), AKd, AVd, qd, qs, BKd, BVd, c.t_cap)
         finally:
-            W.wsvd_ctx_set_option(L.ctx, "fused_step", 0)
+            _set_step_mode(L.ctx, 0)
         assert st == W.E_CAPACITY
         lens_after = L.seq_lens.cpu().numpy()
         assert (lens_after[:-1] == np.array(lens[:-1]) + 1).all() and lens_after[-1] == c.t_cap
@@ -627,7 +644,8 @@ def test_decode_step_tile_boundaries_and_capacity():
     ref = O.decode_attn_reconstructed(oc, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
     for got in outs:
         check_out(got, ref, "i8", "step at tile boundaries")
-    assert np.abs(outs[0] - outs[1]).max() <= 1e-5 * np.abs(outs[1]).max()
+    for o in outs[:-1]:
+        assert np.abs(o - outs[-1]).max() <= 1e-5 * np.abs(outs[-1]).max()
     L.close()
 
 
