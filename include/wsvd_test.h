@@ -31,6 +31,9 @@ wsvd_status wsvd_timeline_set_buffer(wsvd_ctx *ctx, void *dev_ptr, size_t bytes)
  *   "step_deferred":  which two launches: 1 = projection launch + attention launch that finishes the row where that
  *                     pair exists (default), 2 = that pair or WSVD_E_UNSUPPORTED, 0 = always the append kernel + the
  *                     attention kernel
+ *   "timeline_kernel": profiling build, wsvd_decode_step: 0 = the attention launch writes the stamps (default), 1 = the
+ *                     projection launch does (slots: 0 entry, 1 loads issued, 2 hidden states staged, 3 products
+ *                     done, 4 wave partials in LDS, 5 partial sums stored)
  *   "step_slices":    d_model slices of that projection launch: 0 = automatic (about one workgroup per CU), 1..4
  *   "append_helpers": helper workgroups per unit of the default append kernel: -1 = automatic, 0 or 2
  *   "linear_direct":  1 = the W4A8 linear layers read their operands straight from memory (no LDS staging)

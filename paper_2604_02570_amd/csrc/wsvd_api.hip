@@ -215,6 +215,7 @@ wsvd_status wsvd_ctx_set_option(wsvd_ctx* ctx, const char* name, int value) {
   if (!strcmp(name, "linear_direct") && value >= 0 && value <= 1) { o.linear_direct = value; return WSVD_OK; }
   if (!strcmp(name, "prefill_tiled") && value >= 0 && value <= 1) { o.prefill_tiled = value; return WSVD_OK; }
   if (!strcmp(name, "step_deferred") && value >= 0 && value <= 2) { o.step_deferred = value; return WSVD_OK; }
+  if (!strcmp(name, "timeline_kernel") && value >= 0 && value <= 1) { o.timeline_kernel = value; return WSVD_OK; }
   if (!strcmp(name, "step_slices") && value >= 0 && value <= 4) { o.step_slices = value; return WSVD_OK; }
   if (!strcmp(name, "project_shape") && (value == 0 || value == 1 || value == 2 || value == 21 || value == 24 || value == 42 || value == 44)) { o.project_shape = value; return WSVD_OK; }
   return WSVD_E_SHAPE;
@@ -570,6 +571,7 @@ wsvd_status wsvd_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
       const size_t plane = (size_t)desc->batch * desc->n_kv_heads * desc->rank;
       p.new_k = parts; p.new_v = parts + plane; p.new_ld = (long)desc->n_kv_heads * desc->rank;
       p.n_parts = n_parts; p.part_stride = (long)(2 * plane); p.pending = pending;
+      if (ctx->opt.timeline_kernel == 1) p.timeline = nullptr;
       e = wsvd_launch_attn_newrow(p, desc->rank, grid, threads, s);
     }
     if (e != hipErrorNotSupported) return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;

@@ -411,7 +411,7 @@ hipError_t wsvd_launch_append_project(const wsvd_ctx* ctx, const wsvd_layer_desc
   if (part_floats > (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank) return hipErrorNotSupported;
   p.defer_out = p.partials;
   p.pending = (int*)(p.partials + part_floats);
-  p.timeline = nullptr;                  // (profiling build: the stamps of a step are its attention launch's)
+  if (ctx->opt.timeline_kernel != 1) p.timeline = nullptr;    // (profiling build: by default a step's stamps are its attention launch's)
   *parts = p.defer_out; *pending = p.pending; *n_parts = ns;
   switch (d.rank) {
     case 32: return launch_append_project<32, 1024>(p, d, ns, s);

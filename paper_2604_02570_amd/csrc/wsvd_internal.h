@@ -18,6 +18,7 @@ struct wsvd_options {
   int prefill_tiled = 0;    // the tiled prefill kernels also for small calls
   int project_shape = 0;    // kernel of the tiled prefill projection (0 = automatic)
   int step_deferred = 1;    // wsvd_decode_step: projection launch + attention launch that finishes the row: 1 where supported, 2 that or UNSUPPORTED
+  int timeline_kernel = 0;  // profiling build, wsvd_decode_step: whose stamps are recorded: 0 the attention launch's, 1 the projection launch's
   int step_slices = 0;      // d_model slices of that projection launch (0 = automatic)
 };
 
