@@ -57,8 +57,9 @@ def parse():
     ap.add_argument("--deferred-step", action="store_true",
                     help="c3: insist on wsvd_decode_step's deferred-row pair of launches (projection, then attention that "
                          "finishes the row); it is what the default step runs where the library supports it")
-    ap.add_argument("--two-call-step", action="store_true",
-                    help="c3 / c4: the step as wsvd_latent_append + wsvd_decode_attn instead of one wsvd_decode_step call")
+    ap.add_argument("--decode-step-call", action="store_true",
+                    help="c3 / c4: the headline step as ONE wsvd_decode_step call instead of wsvd_latent_append + "
+                         "wsvd_decode_attn (the default line reports that call beside the headline, see decode_step_call)")
     ap.add_argument("--step-slices", type=int, default=0, help="d_model slices of the deferred step's projection launch (tuning)")
     ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep", "probe"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
@@ -142,7 +143,8 @@ def main():
     R = max(1, args.repeats)
     total_steps = args.warmup + args.steps
     # every repeat replays the same graph of args.steps steps, each of which appends a row: room for all of them
-    visits = (args.warmup + args.steps * (R + 1) + n_sets - 1) // n_sets + 8
+    # (+ one more graph's worth for the wsvd_decode_step leg, which starts every repeat from the same lengths)
+    visits = (args.warmup + args.steps * (R + 2) + n_sets - 1) // n_sets + 8
     t_cap = (T + visits + 63) // 64 * 64
     if args.paged:
         t_cap = (t_cap + 255) // 256 * 256      # whole pages
@@ -218,7 +220,7 @@ def main():
         s = sets[i % n_sets]
         if args.attn_only:
             attend(s[5], outs[i % n_sets])
-        elif not args.two_call_step:
+        elif args.single_launch or args.deferred_step or args.decode_step_call:
             W.wsvd_decode_step(ctx, desc, xd, None, AKd, AVd, qd, qsd, BKd, BVd, s[5], t_cap, outs[i % n_sets])
         else:
             W.wsvd_latent_append(ctx, desc, xd, None, AKd, AVd, s[5])
@@ -285,6 +287,28 @@ def main():
             rows_first += lens_before[si] + B * seen[si]
         rows_mean = rows_first / args.steps
 
+        # ---- the same step as ONE wsvd_decode_step call (int8 latents: a projection launch, then an attention launch that
+        # sums the projection's slices, quantises, stores the new rows and attends), same graph protocol, every repeat
+        # from the lengths the headline left; then that attention launch alone (it can be launched again and again: the
+        # step's partial sums stay in the workspace, it stores the same rows and returns the same output)
+        dstep_all = satt_all = None
+        plain_step = not (args.attn_only or args.single_launch or args.deferred_step or args.decode_step_call or args.rope or args.paged)
+        if plain_step and args.workload == "c3":
+            snap0 = [s[4].clone() for s in sets]
+            def restore0():
+                for s, c in zip(sets, snap0):
+                    s[4].copy_(c)
+            dstep_all = timed(lambda i: W.wsvd_decode_step(ctx, desc, xd, None, AKd, AVd, qd, qsd, BKd, BVd, sets[i % n_sets][5], t_cap,
+                                                           outs[i % n_sets]), args.steps, R, before=restore0)
+            assert W.wsvd_check(ctx, stream) == 0
+            try:
+                satt_all = timed(lambda i: W.wsvd_test_step_attention(ctx, desc, qd, qsd, BKd, BVd, sets[i % n_sets][5], t_cap,
+                                                                      outs[i % n_sets]), max(args.steps, 64), R)
+            except W.WsvdError:
+                satt_all = None
+            restore0()
+            stream.synchronize()
+            assert W.wsvd_check(ctx, stream) == 0
         # ---- dominant kernel alone: decode attention, back-to-back launches over the rotating sets (cold HBM)
         n_attn = max(args.steps, 64)
         for i in range(n_sets):
@@ -383,9 +407,10 @@ def main():
             "cache_sets_rotated": n_sets, "cache_set_MB": round(set_bytes / 1e6, 1), "cache_pool": "one allocation",
             "launch": "hip_graph_replay" if use_graph else "eager",
             "step": "attention only" if args.attn_only else ("wsvd_decode_step (single-launch kernel)" if args.single_launch
-                                                              else "wsvd_latent_append + wsvd_decode_attn" if args.two_call_step
                                                               else "wsvd_decode_step (int8 latents: projection launch + attention launch that "
-                                                                   "finishes the row; otherwise append launch + attention launch)"),
+                                                                   "finishes the row; otherwise append launch + attention launch)"
+                                                              if (args.deferred_step or args.decode_step_call)
+                                                              else "wsvd_latent_append + wsvd_decode_attn"),
             "timing": f"ms_per_step = the first timed replay of {args.steps} steps; us_per_decode_step_repeats = {R} replays",
             "host_wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / (args.steps * R), 6),
             "attention_alone_us": stats(attn_all), "attention_alone_warm_single_set_us": stats(warm_all) if warm_all else None,
@@ -412,6 +437,20 @@ def main():
                                   "attention_time_over_probe_time": round(attn_us / probe_us, 3)},
         },
     }
+    if dstep_all:
+        res["decode_step_call"] = {
+            "what": "the same step as one wsvd_decode_step call: projection launch (k_append_split<32,1024,true>) + attention launch "
+                    "that finishes the new rows (k_attn_mfma_newrow<32,1,1024>); same graph protocol, lengths as the headline left them",
+            "us_per_decode_step": stats(dstep_all),
+            "GBps_at_the_headline_rows": round(rows_mean * row_bytes / (float(np.median(dstep_all)) * 1e-6) / 1e9, 1)}
+        if satt_all:
+            sa = float(np.median(satt_all))
+            res["decode_step_call"]["roofline_attention_launch"] = {
+                "kernel": "k_attn_mfma_newrow<32,1,1024> alone (wsvd_test_step_attention: re-launch of the step's second launch)",
+                "bound": "hbm", "achieved": round(attn_bytes / (sa * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(attn_bytes / (sa * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_us": round(sa, 3), "avg_launch_us_min_max": [round(min(satt_all), 3), round(max(satt_all), 3)],
+                "note": "besides the stream it loads 8 partial sums per latent element pair, quantises and stores 512 rows"}
     if app_all:
         app_us = float(np.median(app_all))
         res["roofline_append"] = {

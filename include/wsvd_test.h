@@ -45,6 +45,18 @@ wsvd_status wsvd_timeline_set_buffer(wsvd_ctx *ctx, void *dev_ptr, size_t bytes)
  */
 
 /*
+ * Measurement aid: launches once more the SECOND launch of the last deferred-row wsvd_decode_step made on this context
+ * with this description (the attention that sums the step's partial sums, quantises, stores the new rows and attends
+ * over them).  The partial sums and the pending words of that step are still in the workspace, the lengths of `cache`
+ * must already include the step's row (any cache that went through such a step with the same hidden states will do):
+ * the launch stores the same rows again and returns the same output, so a benchmark can time this kernel alone.
+ * Arguments as wsvd_decode_attn.  WSVD_E_UNSUPPORTED where wsvd_decode_step has no such pair of launches.
+ */
+wsvd_status wsvd_test_step_attention(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
+                                     const void *B_K, const void *B_V, wsvd_cache *cache, int32_t max_seq_len, void *out,
+                                     void *hip_stream);
+
+/*
  * Measurement aid, not part of the method: a kernel that only READS `bytes` bytes (DEVICE pointer, 16-byte
  * aligned) with `workgroups` workgroups of 512 threads, each streaming one contiguous share.  Benchmarks run it
  * over the buffers the attention streams to report what a pure reader reaches on the same data.

@@ -27,7 +27,7 @@ EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_by
            "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_store", "wsvd_decode_attn_static",
            "wsvd_paged_cache_bytes", "wsvd_latent_append_paged", "wsvd_decode_attn_paged", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
-           "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
+           "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_test_step_attention", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
            "wsvd_prefill_attn", "wsvd_shared_workspace_bytes", "wsvd_decode_attn_shared", "wsvd_timeline_set_buffer"]
 
@@ -96,6 +96,7 @@ def lib():
         L.wsvd_decode_attn.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                        POINTER(Cache), c_int32, c_void_p, c_void_p]
         L.wsvd_decode_attn_static.argtypes = L.wsvd_decode_attn.argtypes
+        L.wsvd_test_step_attention.argtypes = L.wsvd_decode_attn.argtypes
         L.wsvd_paged_cache_bytes.argtypes = [POINTER(LayerDesc), c_int32, c_int32, POINTER(c_size_t), POINTER(c_size_t)]
         L.wsvd_latent_append_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                                POINTER(PagedCache), c_void_p]
@@ -235,6 +236,12 @@ def wsvd_latent_store(ctx, desc, c_K, c_V, ld, cache, stream=None):
 def wsvd_decode_attn(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
     _ck(lib().wsvd_decode_attn(ctx, byref(desc), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V), byref(cache),
                                int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_decode_attn")
+
+
+def wsvd_test_step_attention(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):
+    """Measurement aid (include/wsvd_test.h): the second launch of the last deferred-row wsvd_decode_step, once more."""
+    _ck(lib().wsvd_test_step_attention(ctx, byref(desc), _ptr(q), _ptr(q_scale), _ptr(B_K), _ptr(B_V), byref(cache),
+                                       int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_test_step_attention")
 
 
 def wsvd_decode_attn_store(ctx, desc, c_K, c_V, ld, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):

@@ -536,6 +536,43 @@ wsvd_status wsvd_decode_attn_static(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+// the second launch of the deferred-row decode step
+static hipError_t launch_step_attention(wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale, const void* B_K,
+                                        const void* B_V, const wsvd_cache& cache, int max_seq_len, void* out, float* parts,
+                                        int* pending, int n_parts, hipStream_t s) {
+  AttnParams p;
+  dim3 grid;
+  int threads;
+  wsvd_attn_plan(ctx, d, q, q_scale, B_K, B_V, cache, max_seq_len, out, p, grid, threads, 0);
+  const size_t plane = (size_t)d.batch * d.n_kv_heads * d.rank;
+  p.new_k = parts; p.new_v = parts + plane; p.new_ld = (long)d.n_kv_heads * d.rank;
+  p.n_parts = n_parts; p.part_stride = (long)(2 * plane); p.pending = pending;
+  if (ctx->opt.timeline_kernel == 1) p.timeline = nullptr;
+  return wsvd_launch_attn_newrow(p, d.rank, grid, threads, s);
+}
+
+wsvd_status wsvd_test_step_attention(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale, const void* B_K,
+                                     const void* B_V, wsvd_cache* cache, int32_t max_seq_len, void* out, void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
+  if (desc->q_dtype == WSVD_I8 && !q_scale) return WSVD_E_NULL;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (max_seq_len < 1) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  size_t need;
+  wsvd_workspace_bytes(desc, &need);
+  if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;
+  float* parts = nullptr;
+  int* pending = nullptr;
+  int n_parts = 0;
+  if (!wsvd_step_deferred_ok(*desc) || !wsvd_step_partials(ctx, *desc, &parts, &pending, &n_parts)) return WSVD_E_UNSUPPORTED;
+  hipError_t e = launch_step_attention(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, parts, pending, n_parts, (hipStream_t)hip_stream);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* x, const void* x_scale, const void* A_K,
                              const void* A_V, const void* q, const void* q_scale, const void* B_K, const void* B_V,
                              wsvd_cache* cache, int32_t max_seq_len, void* out, void* hip_stream) {
@@ -563,17 +600,7 @@ wsvd_status wsvd_decode_step(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const v
     int* pending = nullptr;
     int n_parts = 0;
     e = wsvd_launch_append_project(ctx, *desc, x, A_K, A_V, *cache, &parts, &pending, &n_parts, s);
-    if (e == hipSuccess) {
-      AttnParams p;
-      dim3 grid;
-      int threads;
-      wsvd_attn_plan(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, p, grid, threads, 0);
-      const size_t plane = (size_t)desc->batch * desc->n_kv_heads * desc->rank;
-      p.new_k = parts; p.new_v = parts + plane; p.new_ld = (long)desc->n_kv_heads * desc->rank;
-      p.n_parts = n_parts; p.part_stride = (long)(2 * plane); p.pending = pending;
-      if (ctx->opt.timeline_kernel == 1) p.timeline = nullptr;
-      e = wsvd_launch_attn_newrow(p, desc->rank, grid, threads, s);
-    }
+    if (e == hipSuccess) e = launch_step_attention(ctx, *desc, q, q_scale, B_K, B_V, *cache, max_seq_len, out, parts, pending, n_parts, s);
     if (e != hipErrorNotSupported) return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
   }
   if (e == hipErrorNotSupported && ctx->opt.step_deferred == 2) return WSVD_E_UNSUPPORTED;

@@ -400,19 +400,28 @@ bool wsvd_step_deferred_ok(const wsvd_layer_desc& d) {
   return append_mfma_path(d) && d.latent_dtype == WSVD_I8 && (d.rank == 32 || d.rank == 64) &&
          d.n_q_heads / d.n_kv_heads <= 4 && d.d_model % 16 == 0 && d.batch <= kAppendMaxB;
 }
-// floats of the step's partial sums (+ one word per sequence), inside the sliced kernels' partial area
+// where the step's partial sums and its pending words live: inside the sliced kernels' partial area of the workspace
+bool wsvd_step_partials(const wsvd_ctx* ctx, const wsvd_layer_desc& d, float** parts, int** pending, int* n_parts) {
+  AppendParams p;
+  wsvd_cache none = {};
+  wsvd_append_params(ctx, d, nullptr, nullptr, nullptr, nullptr, none, p);
+  const int ns = wsvd_step_slices(ctx, d);
+  const size_t part_floats = (size_t)ns * 2 * d.batch * d.n_kv_heads * d.rank;
+  if (part_floats > (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank) return false;
+  *parts = p.partials; *pending = (int*)(p.partials + part_floats); *n_parts = ns;
+  return true;
+}
 hipError_t wsvd_launch_append_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* A_K,
                                       const void* A_V, const wsvd_cache& cache, float** parts, int** pending, int* n_parts,
                                       hipStream_t s) {
   AppendParams p;
   wsvd_append_params(ctx, d, x, nullptr, A_K, A_V, cache, p);
-  const int ns = wsvd_step_slices(ctx, d);
-  const size_t part_floats = (size_t)ns * 2 * d.batch * d.n_kv_heads * d.rank;
-  if (part_floats > (size_t)2 * d.n_kv_heads * (d.d_model / 64) * d.batch * d.rank) return hipErrorNotSupported;
-  p.defer_out = p.partials;
-  p.pending = (int*)(p.partials + part_floats);
+  int ns = 0;
+  if (!wsvd_step_partials(ctx, d, parts, pending, &ns)) return hipErrorNotSupported;
+  p.defer_out = *parts;
+  p.pending = *pending;
   if (ctx->opt.timeline_kernel != 1) p.timeline = nullptr;    // (profiling build: by default a step's stamps are its attention launch's)
-  *parts = p.defer_out; *pending = p.pending; *n_parts = ns;
+  *n_parts = ns;
   switch (d.rank) {
     case 32: return launch_append_project<32, 1024>(p, d, ns, s);
     case 64: return launch_append_project<64, 512>(p, d, ns, s);

@@ -102,6 +102,7 @@ size_t wsvd_attn_partial_floats(const wsvd_layer_desc& d);
 hipError_t wsvd_launch_attn_gqa_store(const struct AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
 hipError_t wsvd_launch_attn_newrow(const struct AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
 bool wsvd_step_deferred_ok(const wsvd_layer_desc& d);
+bool wsvd_step_partials(const wsvd_ctx* ctx, const wsvd_layer_desc& d, float** parts, int** pending, int* n_parts);
 hipError_t wsvd_launch_append_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, const void* A_K,
                                       const void* A_V, const wsvd_cache& cache, float** parts, int** pending, int* n_parts,
                                       hipStream_t s);

@@ -602,6 +602,15 @@ def test_decode_step_matches_oracle(name, over, mode):
             assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all(), "seq_lens not advanced by exactly one"
             flips += _append_compare(L, c.cache, cK, cV, before, sp.latent_dtype)
             check_out(got, ref, sp.latent_dtype, f"step {step} {name}{over}")
+            if mode == 3:
+                # the step's second launch once more (measurement aid): same rows stored again, same output, bit for bit
+                planes = [t.clone() for t in (L.k_codes, L.v_codes, L.k_meta, L.v_meta)]
+                out2 = torch.full_like(L.out, float("nan"))
+                W.wsvd_test_step_attention(L.ctx, L.desc, qd, qs, BKd, BVd, L.cache, int(c.cache.seq_lens.max()), out2)
+                assert W.wsvd_check(L.ctx) == 0
+                assert (out2.cpu().numpy().astype(np.float64) == got).all()
+                assert all((a == b).all() for a, b in zip(planes, (L.k_codes, L.v_codes, L.k_meta, L.v_meta)))
+                assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
             L.upload(c.cache)      # continue from the oracle's cache so that later steps compare like with like
     finally:
         _set_step_mode(L.ctx, -1 if mode < 0 else 0)
