@@ -26,7 +26,8 @@
  * Supported set: d_head in {64,128}; rank in {16,32,64}; n_q_heads / n_kv_heads in 1..8;
  *   latent F32  : factors, x, q F32; any rank above.
  *   latent BF16 : factors, x, q BF16.
- *   latent I8   : rank 32 or 64; factors BF16; x BF16 or F32; q I8 (+fp16 scale per token), F32 or BF16.
+ *   latent I8   : rank 32 or 64; factors BF16; x BF16, F32 or I8 (+fp16 scale per token); q I8 (+fp16 scale per token),
+ *                 F32 or BF16.
  *                 Also rank 96 and 128 with d_head 128 and n_q_heads == n_kv_heads: wsvd_decode_attn, wsvd_decode_step,
  *                 wsvd_latent_append / wsvd_prefill_append (x BF16), wsvd_quantize_rows, cache import / export; the other
  *                 entry points return WSVD_E_UNSUPPORTED at these ranks.
@@ -130,9 +131,12 @@ wsvd_status wsvd_pack_factor_a(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const
  *   (I8 / I4: the quantiser documented at wsvd_quantize_rows), written at row seq_lens[b];
  * then seq_lens[b] += 1.  A sequence with seq_lens[b] >= t_cap is left unchanged and the
  * context's error word is set to WSVD_E_CAPACITY.
- *   x       [B, d_model] of x_dtype (F32 or BF16: every supported layer description has one of them).
- *   x_scale reserved for pre-quantised activations, which no description accepts yet: pass NULL.  (An int8 hidden
- *           state reaches the cache through wsvd_linear_w4a8_split + wsvd_latent_store instead.)
+ *   x       [B, d_model] of x_dtype.
+ *   x_scale x_dtype I8 (quantised latents only): fp16 [B], one scale per token; the hidden state is x * x_scale (the
+ *           activation format of Section 4.2).  NULL otherwise.  The matrix-core kernels, the paged cache, the tiled
+ *           prefill and the single-launch step take BF16 hidden states; I8 and F32 ones go through the vector-ALU
+ *           append kernel (functional path).  With int4 weights as well, wsvd_linear_w4a8_split + wsvd_latent_store
+ *           is the route.
  *   A_K,A_V PACKED by wsvd_pack_factor_a (wsvd_factor_a_bytes bytes each).  d_model must be a multiple of 64.
  */
 wsvd_status wsvd_latent_append(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,

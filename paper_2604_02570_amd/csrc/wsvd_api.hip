@@ -77,7 +77,7 @@ wsvd_status check_desc(const wsvd_layer_desc* d) {
     case WSVD_I8:
     case WSVD_I4:
       if (d->factor_dtype != WSVD_BF16) return WSVD_E_DTYPE;
-      if (d->x_dtype != WSVD_BF16 && d->x_dtype != WSVD_F32) return WSVD_E_DTYPE;
+      if (d->x_dtype != WSVD_BF16 && d->x_dtype != WSVD_F32 && d->x_dtype != WSVD_I8) return WSVD_E_DTYPE;
       if (d->q_dtype != WSVD_I8 && d->q_dtype != WSVD_F32 && d->q_dtype != WSVD_BF16) return WSVD_E_DTYPE;
       if (d->latent_dtype == WSVD_I8 && d->rank != 32 && d->rank != 64 && !is_wide_rank(d->rank)) return WSVD_E_UNSUPPORTED;
       if (d->latent_dtype == WSVD_I4 && d->rank != 32) return WSVD_E_UNSUPPORTED;

@@ -437,6 +437,45 @@ def test_append_matches_oracle(name, over):
     L.close()
 
 
+@pytest.mark.parametrize("name", ["c3_small", "c4_small"], ids=["i8", "i4"])
+def test_append_int8_hidden_states(name):
+    """x given as int8 codes with one fp16 scale per token (the activation format of Section 4.2): the latents are those
+    of the dequantised hidden state.  Decode append (two steps), then a prefill call of a few tokens of one sequence, then
+    attention over everything against the oracle."""
+    c = build_case(name)
+    sp = c.sp
+    L = DeviceLayer(sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, c.t_cap, sp.latent_dtype, "bf16", "i8",
+                    sp.q_dtype, c.sm_scale)
+    L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    AK64, AV64 = c.AK.astype(np.float64), c.AV.astype(np.float64)
+    flips = 0
+    for step in range(2):
+        codes, s = O.quantize_act_i8(c.x_new[step % c.x_new.shape[0]])
+        x64 = codes.astype(np.float64) * s.astype(np.float64)[:, None]
+        before = c.cache.seq_lens.copy()
+        cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+        assert not O.latent_append(c.cache, x64, AK64, AV64).any()
+        assert L.append(dev(codes), dev(s.view(np.uint16)), AKd, AVd) == 0
+        assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+        flips += _append_compare(L, c.cache, cK, cV, before, sp.latent_dtype)
+        L.upload(c.cache)
+    assert flips <= 2
+    if sp.latent_dtype == "i8":        # (int4 latents take the tiled prefill, which wants bf16 hidden states)
+        n_tok, b = sp.batch, 1             # (the layer's workspace is sized for `batch` rows of x)
+        X = WI.hidden_states(sp, n_tok, 1.0, which="new", sub=77)
+        codes, s = O.quantize_act_i8(X)
+        X64 = codes.astype(np.float64) * s.astype(np.float64)[:, None]
+        n0 = int(c.cache.seq_lens[b])
+        O.latent_prefill(c.cache, b, X64, AK64, AV64)
+        W.wsvd_prefill_append(L.ctx, L.desc, dev(codes), dev(s.view(np.uint16)), n_tok, b, AKd, AVd, L.cache)
+        assert W.wsvd_check(L.ctx) == 0
+        assert int(L.seq_lens[b]) == n0 + n_tok == int(c.cache.seq_lens[b])
+    got, ref = run_attend(c, L)
+    check_out(got, ref, sp.latent_dtype, f"attention after int8-x appends {name}")
+    L.close()
+
+
 def test_append_one_hot_token_and_capacity():
     """x = e_k appends row k of A (rounded to the storage format); a full sequence is left alone and flagged."""
     c = build_case("c2_small", batch=3)
