@@ -32,7 +32,8 @@
  *                 wsvd_latent_append / wsvd_prefill_append (x BF16), wsvd_quantize_rows, cache import / export; the other
  *                 entry points return WSVD_E_UNSUPPORTED at these ranks.
  *   latent I4   : rank 32; otherwise as I8.
- *   out F32.  t_cap must be a multiple of 64.
+ *   out F32 or BF16 (round to nearest even; the decode attention entry points: wsvd_decode_attn and its _rope, _store,
+ *   _paged and _static forms, wsvd_decode_step; wsvd_prefill_attn writes F32 only).  t_cap must be a multiple of 64.
  *   Any other per-head rank r (the rank sweep of Eq. 2 / Table 7: r/d = 0.9 .. 0.5) runs at the next supported rank with
  *   zero padding, which is exact: r_pad - r zero columns appended to every A_h and zero rows to every B_h give latent
  *   channels that are identically zero, change neither a row's abs-max nor any product, and quantise to code 0.

@@ -66,7 +66,7 @@ wsvd_status check_desc(const wsvd_layer_desc* d) {
   if (G < 1 || G > 8) return WSVD_E_SHAPE;
   if (d->t_cap <= 0 || d->t_cap % 64 != 0) return WSVD_E_SHAPE;
   if ((int64_t)d->batch * d->n_kv_heads > kWsCounterInts / 4) return WSVD_E_SHAPE;
-  if (d->out_dtype != WSVD_F32) return WSVD_E_DTYPE;
+  if (d->out_dtype != WSVD_F32 && d->out_dtype != WSVD_BF16) return WSVD_E_DTYPE;
   switch (d->latent_dtype) {
     case WSVD_F32:
       if (d->factor_dtype != WSVD_F32 || d->x_dtype != WSVD_F32 || d->q_dtype != WSVD_F32) return WSVD_E_DTYPE;
@@ -277,6 +277,7 @@ wsvd_status wsvd_prefill_attn(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const 
   if (st != WSVD_OK) return st;
   if ((st = check_cache(*desc, cache)) != WSVD_OK) return st;
   if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (desc->out_dtype != WSVD_F32) return WSVD_E_UNSUPPORTED;       // the prompt kernels write fp32
   const int Gr = desc->n_q_heads / desc->n_kv_heads;
   if (n_q < 1 || n_after < 0 || max_seq_len < 0) return WSVD_E_SHAPE;
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
@@ -707,6 +708,7 @@ wsvd_status wsvd_decode_attn_latent(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   p.qk_fold = (const float*)qk_fold;
   p.rq = rq;
   p.out_dim = d.rank;
+  p.out_bf16 = 0;                              // the latent-space output is fp32 whatever the layer's output format
   hipError_t e = wsvd_launch_attn_latent(p, d.latent_dtype, d.rank, grid, threads, (hipStream_t)hip_stream);
   if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
@@ -826,6 +828,7 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   p.err_word = ctx->err_word;
   p.B = d.batch; p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.d = d.d_head;
   p.out_dim = d.d_head;
+  p.out_bf16 = d.out_dtype == WSVD_BF16;
   p.t_cap = d.t_cap;
   p.q_dtype = d.q_dtype; p.factor_dtype = d.factor_dtype;
   const float sm = d.sm_scale != 0.f ? d.sm_scale : 1.0f / sqrtf((float)d.d_head);

@@ -55,7 +55,18 @@ struct AttnParams {
   const int* pending;
   int n_parts;
   long part_stride;
+  int out_bf16;              // out holds bf16 (round to nearest even) instead of fp32; never for the latent-space output
 };
+
+// element idx (pair idx, idx + 1) of the output, in the layer's output format
+WSVD_DEV void out_put(const AttnParams& p, size_t idx, float v) {
+  if (p.out_bf16) ((uint16_t*)p.out)[idx] = f32_to_bf16_rne(v);
+  else p.out[idx] = v;
+}
+WSVD_DEV void out_put2(const AttnParams& p, size_t idx, float a, float b) {      // idx even
+  if (p.out_bf16) *(uint32_t*)((uint16_t*)p.out + idx) = (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+  else { float2 r; r.x = a; r.y = b; *(float2*)&p.out[idx] = r; }
+}
 
 // first query head (row of q / out) of kv head `kv` in this launch
 WSVD_DEV size_t first_head(const AttnParams& p, int kv) { return (size_t)kv * (p.Gmem ? p.Gmem : p.G) + p.g0; }
@@ -88,7 +99,7 @@ WSVD_DEV WorkItem decode_work(const AttnParams& p, int n_raw) { return decode_wo
 WSVD_DEV void write_zero_outputs(const AttnParams& p, const WorkItem& w) {
   if (w.chunk != 0) return;
   for (int i = threadIdx.x; i < p.G * p.out_dim; i += blockDim.x)
-    p.out[((size_t)w.b * p.Hq + first_head(p, w.kv)) * p.out_dim + i] = 0.f;
+    out_put(p, ((size_t)w.b * p.Hq + first_head(p, w.kv)) * p.out_dim + i, 0.f);
 }
 
 // ---- staging of the per-head factors into LDS.
@@ -360,8 +371,8 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       a1 = group_sum<4>(a1);
       if (part == 0 && (i >> 2) < n_pair) {
         const float L = Lsh[g];
-        float2 r; r.x = L > 0.f ? a0 / L : 0.f; r.y = L > 0.f ? a1 / L : 0.f;   // no visible row at all: zeros
-        *(float2*)&p.out[((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + 2 * c2] = r;
+        out_put2(p, ((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + 2 * c2, L > 0.f ? a0 / L : 0.f,
+                 L > 0.f ? a1 / L : 0.f);                                          // no visible row at all: zeros
       }
     }
     return;
@@ -378,6 +389,6 @@ WSVD_DEV void attn_tail(const AttnParams& p, const WorkItem& w, float* Msh, floa
       acc = fmaf(Ush[g * R + j], ((const float*)bv_lds)[j * p.d + c], acc);
     }
     acc = group_sum<4>(acc);
-    if (part == 0 && (i >> 2) < n_out) p.out[((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + c] = acc / Lsh[g];
+    if (part == 0 && (i >> 2) < n_out) out_put(p, ((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + c, acc / Lsh[g]);
   }
 }

@@ -1045,8 +1045,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
         if (part == 0 && (i >> 2) < n_pair) {
           const float L = Lsh[g];
           const float rl = L > 0.f ? __builtin_amdgcn_rcpf(L) : 0.f;                 // no visible row at all: zeros
-          float2 r2; r2.x = a0 * rl; r2.y = a1 * rl;
-          *(float2*)&p.out[((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + 2 * c2] = r2;
+          out_put2(p, ((size_t)w.b * p.Hq + first_head(p, w.kv) + g) * p.d + 2 * c2, a0 * rl, a1 * rl);
         }
       }
     }
@@ -1551,7 +1550,7 @@ WSVD_DEV void attn_gqa_body(const AttnParams& p) {
       WSVD_STAMP(tl, tl_wg, wave, 11);
       for (int i = tid; i < G * p.d; i += blockDim.x) {
         const float L = Lsh[i / p.d];
-        p.out[((size_t)w.b * p.Hq + (size_t)w.kv * G) * p.d + i] = L > 0.f ? Osh[i] / L : 0.f;   // no visible row at all: zeros
+        out_put(p, ((size_t)w.b * p.Hq + (size_t)w.kv * G) * p.d + i, L > 0.f ? Osh[i] / L : 0.f);   // no visible row at all: zeros
       }
     }
   }

@@ -525,6 +525,58 @@ def test_host_side_errors():
     L.close()
 
 
+# ------------------------------------------------------------------------------------------ bf16 output
+BF16_OUT = [("c1", dict(batch=3, context=70)), ("c2_small", dict()), ("c3_small", dict()), ("c3_small", dict(n_q_heads=16, n_kv_heads=4)),
+            ("c3_small", dict(context=2000, batch=2)), ("c4_small", dict()), ("c5_small", dict(context=2000)),
+            ("c3_small", dict(rank=128, d_head=128))]
+
+
+@pytest.mark.parametrize("name,over", BF16_OUT, ids=[f"{n}-{'-'.join(f'{k}{v}' for k, v in o.items())}" for n, o in BF16_OUT])
+def test_attention_bf16_output_is_the_rounded_fp32_output(name, over):
+    """out_dtype = BF16: every kernel rounds the value it would have stored as fp32 (round to nearest even), so the
+    result must be the rounded fp32 result bit for bit; sequences of length 0 give zeros."""
+    c = build_case(name, **over)
+    sp = c.sp
+    c.cache.seq_lens[0] = 0
+    L = layer_for(c); L.upload(c.cache)
+    got32, ref = run_attend(c, L)
+    check_out(got32, ref, sp.latent_dtype, f"fp32 out {name}{over}")
+    xdt = "f32" if sp.factor_dtype == "f32" else "bf16"
+    desc16 = W.layer_desc(sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, L.desc.t_cap, sp.latent_dtype,
+                          sp.factor_dtype, xdt, sp.q_dtype, "bf16", c.sm_scale)
+    qd, qs, _ = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, sp.factor_dtype), as_dtype_dev(c.BV, sp.factor_dtype)
+    out16 = torch.full((sp.batch, sp.n_q_heads, sp.d_head), float("nan"), dtype=torch.bfloat16, device="cuda")
+    W.wsvd_decode_attn(L.ctx, desc16, qd, qs, BKd, BVd, L.cache, int(c.cache.seq_lens.max()), out16)
+    assert W.wsvd_check(L.ctx) == 0
+    want = torch.from_numpy(got32.astype(np.float32)).to(torch.bfloat16)
+    assert (out16.cpu().view(torch.int16) == want.view(torch.int16)).all()
+    assert (out16[0] == 0).all()
+    if sp.latent_dtype == "i8" and sp.rank <= 64 and sp.n_q_heads // sp.n_kv_heads <= 4:
+        # the rotary variant and the decode step (projection launch + attention launch that finishes the row)
+        L.out.fill_(float("nan"))
+        W.wsvd_decode_attn_rope(L.ctx, L.desc, qd, qs, BKd, BVd, L.cache, int(c.cache.seq_lens.max()), 10000.0, L.out)
+        out16.fill_(float("nan"))
+        W.wsvd_decode_attn_rope(L.ctx, desc16, qd, qs, BKd, BVd, L.cache, int(c.cache.seq_lens.max()), 10000.0, out16)
+        assert W.wsvd_check(L.ctx) == 0
+        assert (out16.cpu().view(torch.int16) == L.out.cpu().to(torch.bfloat16).view(torch.int16)).all()
+        AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+        xd = as_dtype_dev(WI.bf16_exact(c.x_new[0]), "bf16")
+        lens0 = L.seq_lens.clone()
+        L.out.fill_(float("nan"))
+        W.wsvd_decode_step(L.ctx, L.desc, xd, None, AKd, AVd, qd, qs, BKd, BVd, L.cache, int(c.cache.seq_lens.max()) + 1, L.out)
+        L.seq_lens.copy_(lens0)
+        out16.fill_(float("nan"))
+        W.wsvd_decode_step(L.ctx, desc16, xd, None, AKd, AVd, qd, qs, BKd, BVd, L.cache, int(c.cache.seq_lens.max()) + 1, out16)
+        assert W.wsvd_check(L.ctx) == 0
+        assert (out16.cpu().view(torch.int16) == L.out.cpu().to(torch.bfloat16).view(torch.int16)).all()
+    # the prompt kernels write fp32 only
+    with pytest.raises(W.WsvdError) as e:
+        W.wsvd_prefill_attn(L.ctx, desc16, qd, 1, 0, BKd, BVd, L.cache, int(c.cache.seq_lens.max()), out16)
+    assert e.value.status == W.E_UNSUPPORTED
+    L.close()
+
+
 # ------------------------------------------------------------------------------------------ rotary variant
 ROPE_CASES = [
     ("c3_small", dict()),                                     # rank 32, head dim 128, int8 query

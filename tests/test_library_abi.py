@@ -52,7 +52,7 @@ def test_host_only_validation_and_sizes():
     assert codes == 64 * 32 * 4160 * 16 and meta == 64 * 32 * 4160 * 4
     assert W.wsvd_workspace_bytes(d) >= 65536
     for kw, status in ((dict(d_head=96), 2), (dict(rank=48), 2), (dict(n_q_heads=33), 2), (dict(t_cap=100), 2),
-                       (dict(latent_dtype="i4", rank=64), 6), (dict(factor_dtype="f32"), 3), (dict(out_dtype="bf16"), 3)):
+                       (dict(latent_dtype="i4", rank=64), 6), (dict(factor_dtype="f32"), 3), (dict(out_dtype="i8"), 3)):
         args = dict(batch=16, n_q_heads=32, n_kv_heads=32, d_head=128, d_model=4096, rank=32, t_cap=2048, latent_dtype="i8",
                     factor_dtype="bf16", x_dtype="bf16", q_dtype="i8", out_dtype="f32")
         args.update(kw)
