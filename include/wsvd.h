@@ -208,6 +208,13 @@ wsvd_status wsvd_paged_cache_bytes(const wsvd_layer_desc *desc, int32_t page_row
                                    size_t *meta_bytes);
 wsvd_status wsvd_latent_append_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, const void *x_scale,
                                      const void *A_K, const void *A_V, wsvd_paged_cache *cache, void *hip_stream);
+/* Prompt into a paged cache: wsvd_prefill_append (its tiled projection: any number of tokens, one sequence or all with
+ * seq_index = -1, x [n_seq, n_tokens, d_model] BF16, int4 latents from an even length) with the rows going to the pages
+ * of block_table; a table entry outside the pools is reported (WSVD_E_SHAPE through wsvd_check) and its rows are not
+ * stored.  The stored bytes are those wsvd_prefill_append puts into a contiguous cache. */
+wsvd_status wsvd_prefill_append_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, int32_t n_tokens,
+                                      int32_t seq_index, const void *A_K, const void *A_V, wsvd_paged_cache *cache,
+                                      void *hip_stream);
 wsvd_status wsvd_decode_attn_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
                                    const void *B_K, const void *B_V, const wsvd_paged_cache *cache, int32_t max_seq_len,
                                    void *out, void *hip_stream);

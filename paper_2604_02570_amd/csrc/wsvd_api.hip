@@ -476,6 +476,21 @@ wsvd_status wsvd_latent_append_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc,
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_prefill_append_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* x, int32_t n_tokens, int32_t seq_index,
+                                      const void* A_K, const void* A_V, wsvd_paged_cache* cache, void* hip_stream) {
+  if (!ctx || !x || !A_K || !A_V) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_paged(*desc, cache)) != WSVD_OK) return st;
+  if (desc->x_dtype != WSVD_BF16 || desc->factor_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
+  if (!aligned16(x) || !aligned16(A_K) || !aligned16(A_V)) return WSVD_E_ALIGN;
+  if (n_tokens < 1 || seq_index < -1 || seq_index >= desc->batch) return WSVD_E_SHAPE;
+  wsvd_cache view = {cache->k_codes, cache->v_codes, cache->k_meta, cache->v_meta, cache->seq_lens};
+  hipError_t e = wsvd_launch_prefill_project(ctx, *desc, x, n_tokens, seq_index, A_K, A_V, view, (hipStream_t)hip_stream, cache);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                                    const void* B_K, const void* B_V, const wsvd_paged_cache* cache, int32_t max_seq_len,
                                    void* out, void* hip_stream) {

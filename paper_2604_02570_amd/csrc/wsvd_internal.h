@@ -75,7 +75,8 @@ hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int
 // projection + quantise + store of n_tok consecutive tokens of sequence seq, or of every sequence when seq < 0 (x then
 // holds [batch, n_tok, d_model]); I8 latents, BF16 x and factors; any n_tok
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
-                                       const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s);
+                                       const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s,
+                                       const wsvd_paged_cache* paged = nullptr);
 // decode attention over one shared rank-R latent (32 heads, rank 256 / 512 / 1024, int8 codes, bf16 q and factors):
 // three launches (query absorption, attention with split partials, merge + output projection)
 size_t wsvd_shared_ws_bytes(int batch, int rank, int t_cap);

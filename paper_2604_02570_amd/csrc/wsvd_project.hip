@@ -26,7 +26,32 @@ struct ProjectParams {
   int Hkv, E, t_cap, n_tok, seq0;   // direct kernel: grid z = sequence - seq0
   int n_cg, tg_seq, n_tg;           // staged kernel: channel groups, token groups per sequence and in all
   int i4;                           // int4 latents (rank 32): asymmetric codes, two rows per value byte
+  // paged cache only (else null): codes / meta are pools of n_pages pages, a page = page_rows rows of every kv head in the
+  // layout of a contiguous plane; block_table [B][max_pages]
+  const int* block_table;
+  int page_rows, max_pages, n_pages;
 };
+
+// Where row t of (sequence, kv head) lives: its plane (row_bytes per row), its row inside that plane, the index of its
+// metadata entry.  Paged: a table entry outside the pools is reported and the row is not stored (ok = false).
+struct ProjRow { uint8_t* plane; size_t meta; int t; bool ok; };
+WSVD_DEV ProjRow project_row(const ProjectParams& p, int pl, int seq, int kv, int t, int row_bytes) {
+  ProjRow r;
+  if (!p.block_table) {
+    const size_t ph = (size_t)seq * p.Hkv + kv;
+    r.plane = p.codes[pl] + ph * (size_t)p.t_cap * row_bytes; r.meta = ph * p.t_cap + t; r.t = t; r.ok = true;
+    return r;
+  }
+  const int pg = min(max(t, 0) / p.page_rows, p.max_pages - 1);
+  const int e = p.block_table[(size_t)seq * p.max_pages + pg];
+  r.ok = e >= 0 && e < p.n_pages;
+  if (!r.ok) atomicExch(p.err_word, (int)WSVD_E_SHAPE);
+  const size_t slot = (size_t)(r.ok ? e : 0) * p.Hkv + kv;
+  r.t = t - pg * p.page_rows;
+  r.plane = p.codes[pl] + slot * (size_t)p.page_rows * row_bytes;
+  r.meta = slot * p.page_rows + r.t;
+  return r;
+}
 
 // per token and head: symmetric int8 (the latent quantiser's rule), then the stores.  acc[c][tt] = channel tile ct0 + c
 // x token tile tb * TT + tt of this wave, in the 32 x 32 accumulator order.
@@ -62,8 +87,11 @@ WSVD_DEV void project_store(const ProjectParams& p, v16f (&acc)[CT][TT], int ct0
           const float sc = f16_bits_to_f32(sh);
           if (!flat) z = fminf(fmaxf(__builtin_rintf(-lo / sc), 0.f), 15.f);
           const int zi = (int)z;
-          const bool on = tok < p.n_tok && n0 >= 0 && (n0 & 1) == 0 && t < p.t_cap;
-          uint8_t* plane4 = p.codes[pl] + ph * (size_t)p.t_cap * 16;
+          bool on = tok < p.n_tok && n0 >= 0 && (n0 & 1) == 0 && t < p.t_cap;
+          ProjRow pr = {p.codes[pl] + ph * (size_t)p.t_cap * 16, ph * p.t_cap + t, t, true};
+          if (p.block_table && on) { pr = project_row(p, pl, seq, kv, t, 16); on = pr.ok; }
+          uint8_t* plane4 = pr.plane;
+          const int tr = pr.t;
 #pragma unroll
           for (int m4 = 0; m4 < 4; m4++) {
             int q[4];
@@ -76,18 +104,18 @@ WSVD_DEV void project_store(const ProjectParams& p, v16f (&acc)[CT][TT], int ct0
             const int j0 = 8 * m4 + 4 * g2;                             // channels j0 .. j0 + 3
             if (pl == 0) {
               int nib;
-              if (on) *(uint16_t*)(plane4 + i4_k_offset(t, j0, &nib)) = (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
+              if (on) *(uint16_t*)(plane4 + i4_k_offset(tr, j0, &nib)) = (uint16_t)(q[0] | (q[1] << 4) | (q[2] << 8) | (q[3] << 12));
             } else {
 #pragma unroll
               for (int jj = 0; jj < 4; jj++) {
                 const int qn = __builtin_amdgcn_update_dpp(0, q[jj], kDppQuadSwap1, 0xF, 0xF, true);   // the neighbour row's code
                 const bool nb_on = tok + 1 < p.n_tok && t + 1 < p.t_cap;
                 int nib;
-                if (on && (n & 1) == 0) plane4[i4_v_offset(t, j0 + jj, &nib)] = (uint8_t)(q[jj] | ((nb_on ? qn : 0) << 4));
+                if (on && (n & 1) == 0) plane4[i4_v_offset(tr, j0 + jj, &nib)] = (uint8_t)(q[jj] | ((nb_on ? qn : 0) << 4));
               }
             }
           }
-          if (on && g2 == 0) *(uint32_t*)&p.meta[pl][(ph * p.t_cap + t) * 2] = (uint32_t)sh | ((uint32_t)f32_to_f16_bits_rne((float)zi) << 16);
+          if (on && g2 == 0) *(uint32_t*)&p.meta[pl][pr.meta * 2] = (uint32_t)sh | ((uint32_t)f32_to_f16_bits_rne((float)zi) << 16);
           continue;
         }
       }
@@ -101,6 +129,10 @@ WSVD_DEV void project_store(const ProjectParams& p, v16f (&acc)[CT][TT], int ct0
       if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
       const float sc = f16_bits_to_f32(sh);
       if (tok >= p.n_tok || n0 < 0 || t >= p.t_cap) continue;
+      ProjRow pr = {plane, ph * p.t_cap + t, t, true};
+      if (p.block_table) { pr = project_row(p, pl, seq, kv, t, R); if (!pr.ok) continue; }
+      uint8_t* const pln = pr.plane;
+      const int tr = pr.t;
 #pragma unroll
       for (int rt = 0; rt < RT; rt++)
 #pragma unroll
@@ -113,13 +145,13 @@ WSVD_DEV void project_store(const ProjectParams& p, v16f (&acc)[CT][TT], int ct0
             pk |= ((uint32_t)q[jj] & 0xFFu) << (8 * jj);
           }
           const int j0 = 32 * rt + 8 * m4 + 4 * g2;                     // channels j0 .. j0 + 3
-          if (pl == 0) *(uint32_t*)(plane + i8_k_offset(t, j0, R)) = pk;
+          if (pl == 0) *(uint32_t*)(pln + i8_k_offset(tr, j0, R)) = pk;
           else {
 #pragma unroll
-            for (int jj = 0; jj < 4; jj++) plane[i8_v_offset(t, j0 + jj, R)] = (uint8_t)q[jj];
+            for (int jj = 0; jj < 4; jj++) pln[i8_v_offset(tr, j0 + jj, R)] = (uint8_t)q[jj];
           }
         }
-      if (g2 == 0) p.meta[pl][ph * p.t_cap + t] = sh;
+      if (g2 == 0) p.meta[pl][pr.meta] = sh;
     }
   }
 }
@@ -320,8 +352,10 @@ void launch_project(const ProjectParams& p, int n_seq, hipStream_t s) {
 
 
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,
-                                       const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s) {
+                                       const void* A_K, const void* A_V, const wsvd_cache& cache, hipStream_t s,
+                                       const wsvd_paged_cache* paged) {
   const bool i4 = d.latent_dtype == WSVD_I4 && d.rank == 32;
+  if (paged && d.rank > 64) return hipErrorNotSupported;
   if ((d.latent_dtype != WSVD_I8 && !i4) || d.factor_dtype != WSVD_BF16 || d.x_dtype != WSVD_BF16) return hipErrorNotSupported;
   if (d.rank != 32 && d.rank != 64 && d.rank != 96 && d.rank != 128) return hipErrorNotSupported;
   if (d.d_model % 16 != 0 || n_tok < 1) return hipErrorInvalidValue;
@@ -333,6 +367,8 @@ hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_des
   p.Hkv = d.n_kv_heads; p.E = d.d_model; p.t_cap = d.t_cap; p.n_tok = n_tok;
   p.n_cg = p.tg_seq = p.n_tg = 0;
   p.i4 = i4 ? 1 : 0;
+  p.block_table = nullptr; p.page_rows = p.max_pages = p.n_pages = 0;
+  if (paged) { p.block_table = paged->block_table; p.page_rows = paged->page_rows; p.max_pages = paged->max_pages; p.n_pages = paged->n_pages; }
   const int n_seq = seq < 0 ? d.batch : 1;
   p.seq0 = seq < 0 ? 0 : seq;
   // small problems: small wave tiles, so that there are enough waves; prompt-sized ones: the LDS-staged kernel

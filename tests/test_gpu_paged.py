@@ -154,3 +154,70 @@ def test_paged_cache_argument_checks_and_bad_entries():
     good_pages = {int(PG.table_host[b, int(c.cache.seq_lens[b]) // 64]) for b in range(sp.batch) if b != 1}
     assert set(touched[0]) <= good_pages and set(touched[1]) <= good_pages and len(touched[0]) > 0
     L.close()
+
+
+@pytest.mark.parametrize("name,over,all_seqs", [("c3_small", dict(), False), ("c3_small", dict(), True),
+                                                ("c5_small", dict(n_q_heads=4, n_kv_heads=2), False), ("c4_small", dict(batch=4, context=300, ragged=(100, 300)), False),
+                                                ("c4_small", dict(batch=4, context=300, ragged=(100, 300)), True)],
+                         ids=["i8-one", "i8-all", "i8-rank64-one", "i4-one", "i4-all"])
+def test_paged_prefill_equals_the_contiguous_one(name, over, all_seqs):
+    """wsvd_prefill_append_paged against wsvd_prefill_append (the same tiled projection, only the address of a row
+    differs): the same bytes in the pages as in the contiguous planes, the same attention afterwards; a prompt that
+    crosses several pages; a table entry outside the pools."""
+    c = build_case(name, extra_cap=300, **over)
+    sp = c.sp
+    if sp.latent_dtype == "i4":
+        c.cache.seq_lens[:] = c.cache.seq_lens // 2 * 2       # the tiled int4 store wants an even start row
+    L = layer_for(c); L.upload(c.cache)
+    PG = Paged(L, 64, seed=11)
+    n = 70 if all_seqs else (150 if sp.latent_dtype == "i4" else 151)     # (int4: the next block starts on an even row again)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    lens0 = c.cache.seq_lens.copy()
+    if all_seqs:
+        X = np.stack([WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=60 + b)) for b in range(sp.batch)])
+        xd, seq, targets = as_dtype_dev(X.reshape(sp.batch * n, -1), "bf16"), -1, list(range(sp.batch))
+    else:
+        b = 1
+        xd, seq, targets = as_dtype_dev(WI.bf16_exact(WI.hidden_states(sp, n, 1.0, which="ctx", sub=77)), "bf16"), b, [b]
+    W.wsvd_prefill_append(L.ctx, L.desc, xd, None, n, seq, AKd, AVd, L.cache)
+    assert W.wsvd_check(L.ctx) == 0
+    W.wsvd_prefill_append_paged(L.ctx, L.desc, xd, n, seq, AKd, AVd, PG.cache)
+    assert W.wsvd_check(L.ctx) == 0
+    want_lens = lens0 + np.array([n if b in targets else 0 for b in range(sp.batch)])
+    assert (PG.seq_lens.cpu().numpy() == want_lens).all() and (L.seq_lens.cpu().numpy() == want_lens).all()
+    rb, mb = PG.rb, PG.mb
+    planes = [(L.k_codes, L.k_meta), (L.v_codes, L.v_meta)]
+    t_cap = L.t_cap
+    for pl, (gc, gm) in enumerate(PG.gathered()):
+        a = gc.view(sp.batch, sp.n_kv_heads, -1).cpu().numpy(); bb = planes[pl][0].view(sp.batch, sp.n_kv_heads, -1).cpu().numpy()
+        am = gm.view(sp.batch, sp.n_kv_heads, -1).cpu().numpy()
+        bm = planes[pl][1][: sp.batch * sp.n_kv_heads * t_cap * mb].view(sp.batch, sp.n_kv_heads, -1).cpu().numpy()
+        for bi in range(sp.batch):
+            nn = int(want_lens[bi])
+            n_cmp = nn // 64 * 64
+            assert a[bi, :, : n_cmp * rb].tobytes() == bb[bi, :, : n_cmp * rb].tobytes(), (name, pl, bi)
+            assert am[bi, :, : nn * mb].tobytes() == bm[bi, :, : nn * mb].tobytes(), (name, pl, bi)
+    qd, qs, _ = q_to_device(c.q32[0], sp.q_dtype)
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    n_max = int(want_lens.max())
+    want = L.attend(qd, qs, BKd, BVd, n_max)
+    out = torch.full_like(L.out, float("nan"))
+    W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, PG.cache, n_max, out)
+    assert W.wsvd_check(L.ctx) == 0
+    assert (out.cpu().numpy().astype(np.float64) == want).all(), "attention over the paged prompt differs from the contiguous one"
+    # a table entry outside the pools under the rows of a second prompt block: reported, those rows not stored
+    tbl = PG.table.clone()
+    tb = targets[0]
+    bad_page = int(want_lens[tb]) // 64 + 1                    # the page after the one the block starts in
+    tbl[tb, bad_page] = PG.n_pages + 3
+    before = [p.clone() for p in PG.pools]
+    broken = W.make_paged_cache(PG.pools[0], PG.pools[1], PG.mpools[0], PG.mpools[1], PG.seq_lens, tbl, 64, PG.max_pages, PG.n_pages)
+    n2 = 130
+    x2 = as_dtype_dev(WI.bf16_exact(WI.hidden_states(sp, n2, 1.0, which="ctx", sub=99)), "bf16")
+    W.wsvd_prefill_append_paged(L.ctx, L.desc, x2, n2, tb, AKd, AVd, broken)
+    assert W.wsvd_check(L.ctx) == W.E_SHAPE
+    touched = set((PG.pools[0] != before[0]).flatten(1).any(1).nonzero().flatten().tolist())
+    first = int(want_lens[tb]) // 64
+    allowed = {int(PG.table_host[tb, pg]) for pg in range(first, min(PG.max_pages, (int(want_lens[tb]) + n2 + 63) // 64)) if pg != bad_page}
+    assert touched and touched <= allowed, (touched, allowed)
+    L.close()
