@@ -258,7 +258,8 @@ wsvd_status wsvd_ctx_set_option(wsvd_ctx *ctx, const char *name, int value);
  * else is wsvd_decode_attn.  Rotation: dims (i, i + d_head/2) form a plane turned by position * theta_i with
  * theta_i = rope_base^(-2i/d_head) ("rotate-half" pairing).  With the rotation between the reconstruction and the
  * product, B_K cannot be folded into the query, so every cached row costs 2 * rank * d_head flops per query head.
- * Supported: I8 latents, bf16 factors, rank 32 or 64, up to 8 query heads per kv head (one launch holds 4 heads of a
+ * Supported: I8 latents (rank 32 or 64) and I4 latents (rank 32; the codes minus the token's zero point are the
+ * operands), bf16 factors, up to 8 query heads per kv head (one launch holds 4 heads of a
  * group at rank 32 and 2 at rank 64; larger groups run as several launches over the same cache, one per set of
  * heads); WSVD_E_UNSUPPORTED otherwise.  rope_base > 1 (10000 is the usual value).
  */

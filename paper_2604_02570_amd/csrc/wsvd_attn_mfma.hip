@@ -203,7 +203,7 @@ WSVD_DEV void split_fp16_pair(float x, float scale, _Float16& hi, _Float16& lo) 
 // FUSED: the workgroup is part of a decode-step launch whose append workgroups are writing row seq_lens[b] at this
 // very moment.  The row counts as present; the 64-row tile that contains it is kept out of the streaming loop and
 // done last by one wave, after the two planes' flags show the launch's epoch, through agent-scope loads.
-// ROPE_D != 0: the rotary variant for head dimension ROPE_D (I8 latents; rs, ra non-null).
+// ROPE_D != 0: the rotary variant for head dimension ROPE_D (rs, ra non-null).
 // NEWROW: the second launch of the decode step.  The projection launch before it has advanced the lengths and left the
 // new token's latents as partial sums; the workgroup whose chunk holds a sequence's last row sums them, quantises and
 // stores the row (as the append would have) and patches it into the registers of the wave that consumes its tile.
@@ -213,7 +213,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   constexpr bool ROPE = ROPE_D != 0;
   constexpr bool STAGED = ROPE || LATENT;
   using RG = RopeGeom<(ROPE_D ? ROPE_D : 64)>;
-  static_assert(!ROPE || (!I4 && !FUSED), "rotary variant: int8 latents, stand-alone launch");
+  static_assert(!ROPE || !FUSED, "rotary variant: stand-alone launch");
   static_assert(!LATENT || (!ROPE && !FUSED), "latent-query variant: stand-alone launch, no rotation");
   static_assert(!I4 || R == 32, "int4 latents: rank 32 only");
   static_assert(!PAGED || (!ROPE && !LATENT && !FUSED), "paged cache: the plain decode attention");
@@ -772,7 +772,10 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     // ---------------- score pass
     v16i acc = {0};
     float ksc, kz = 0.f, vsc, vz = 0.f;
-    if (I4) {
+    if constexpr (ROPE && I4) {
+      ksc = f16_bits_to_f32((uint16_t)(t.kmeta & 0xFFFF)); kz = f16_bits_to_f32((uint16_t)(t.kmeta >> 16));
+      vsc = f16_bits_to_f32((uint16_t)(t.vmeta & 0xFFFF)); vz = f16_bits_to_f32((uint16_t)(t.vmeta >> 16));
+    } else if (I4) {
       const uint32_t msk = 0x0F0F0F0Fu;
       const v4i raw = t.k[0][0];
       v4i s0, s1;   // slot 0 = tokens 0..31 (dwords 0,1), slot 1 = tokens 32..63 (dwords 2,3)
@@ -816,6 +819,21 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
         float part[G];
 #pragma unroll
         for (int g = 0; g < G; g++) part[g] = 0.f;
+        if constexpr (I4) {
+          // int4: the lane's 8 bytes of this block are dims 16 hf .. + 15 of its token as nibble pairs (low = even dim);
+          // the code minus the token's zero point is the operand (small integers: exact in fp16).  The zero point in
+          // this lane's metadata belongs to token `lane` of the tile; the block's token is 32 blk + lane % 32.
+          const float zb = __shfl(kz, 32 * blk + (lane & 31));
+#pragma unroll
+          for (int x = 0; x < 2; x++) {
+            const uint32_t dw = (uint32_t)t.k[0][0][2 * blk + x];
+#pragma unroll
+            for (int b = 0; b < 4; b++) {
+              bop[x][2 * b] = (_Float16)((float)((dw >> (8 * b)) & 15u) - zb);
+              bop[x][2 * b + 1] = (_Float16)((float)((dw >> (8 * b + 4)) & 15u) - zb);
+            }
+          }
+        } else {
 #pragma unroll
         for (int kk = 0; kk < KK; kk++)
 #pragma unroll
@@ -824,6 +842,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
 #pragma unroll
             for (int b = 0; b < 4; b++) bop[2 * kk + (x >> 1)][4 * (x & 1) + b] = (_Float16)(int)(int8_t)(dw >> (8 * b));
           }
+        }
         v16f dc = product(0);
 #pragma unroll
         for (int idx = 0; idx < NI; idx++) {
@@ -853,7 +872,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
 #pragma unroll
     for (int g = 0; g < G; g++) {
       float dot = ROPE ? rdot[g] : limbs_to_f32(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2]);
-      if (I4) dot = fmaf(-kz, zsum[g], dot);
+      if (I4 && !ROPE) dot = fmaf(-kz, zsum[g], dot);          // (the rotary variant has taken the zero point out of the codes)
       const float s = valid ? ksc * dot * delta[g] : -INFINITY;
       if (__builtin_amdgcn_ballot_w64(s > m[g]) != 0) {          // a new running max somewhere in this tile
         const float mn = fmaxf(m[g], wave_max(s));
@@ -1733,29 +1752,30 @@ hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank
 }
 
 // ---------------------------------------------------------------- rotary variant: launch
-template <int R, int G, int D, int NT>
+template <int R, int G, int D, int NT, bool I4 = false>
 __global__ __launch_bounds__(NT) void k_attn_rope(AttnParams p, RopeArgs ra) {
   __shared__ AttnMfmaShared<R, G, NT> sh;
   __shared__ RopeShared<R, G, D> rs;
-  attn_mfma_body<R, G, false, NT, false, D>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z, &rs, &ra);
+  attn_mfma_body<R, G, I4, NT, false, D>(p, sh, blockIdx.x, blockIdx.y, blockIdx.z, &rs, &ra);
 }
 
-template <int R, int G>
+template <int R, int G, bool I4 = false>
 static hipError_t launch_rope(const AttnParams& p, const RopeArgs& ra, dim3 grid, int threads, hipStream_t s) {
-  if (p.d == 128) hipLaunchKernelGGL((k_attn_rope<R, G, 128, 512>), grid, dim3(threads), 0, s, p, ra);
-  else if (p.d == 64) hipLaunchKernelGGL((k_attn_rope<R, G, 64, 512>), grid, dim3(threads), 0, s, p, ra);
+  if (p.d == 128) hipLaunchKernelGGL((k_attn_rope<R, G, 128, 512, I4>), grid, dim3(threads), 0, s, p, ra);
+  else if (p.d == 64) hipLaunchKernelGGL((k_attn_rope<R, G, 64, 512, I4>), grid, dim3(threads), 0, s, p, ra);
   else return hipErrorNotSupported;
   return hipGetLastError();
 }
 
-// I8 latents; rank 32 with up to 4 query heads per kv head, rank 64 with up to 2 (the N^T operand images of all heads
+// I8 latents (rank 32 / 64) or I4 latents (rank 32); per launch rank 32 with up to 4 query heads per kv head, rank 64 with up to 2 (the N^T operand images of all heads
 // of the group live in LDS).  hipErrorNotSupported otherwise.
 hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q, const void* q_scale,
                                  const void* B_K, const void* B_V, const wsvd_cache& cache, int max_seq_len, double rope_base,
                                  void* out, hipStream_t s) {
   const int G = d.n_q_heads / d.n_kv_heads;
-  if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16) return hipErrorNotSupported;
-  if (d.rank != 32 && d.rank != 64) return hipErrorNotSupported;
+  const bool i4 = d.latent_dtype == WSVD_I4;
+  if ((d.latent_dtype != WSVD_I8 && !i4) || d.factor_dtype != WSVD_BF16) return hipErrorNotSupported;
+  if (d.rank != 32 && (d.rank != 64 || i4)) return hipErrorNotSupported;
   const int gmax = d.rank == 32 ? 4 : 2;               // query heads per kv head one launch holds (registers)
   AttnParams p;
   dim3 grid;
@@ -1786,7 +1806,14 @@ hipError_t wsvd_launch_attn_rope(const wsvd_ctx* ctx, const wsvd_layer_desc& d, 
     const int gl = G - g0 < gmax ? G - g0 : gmax;
     p.G = gl; p.Gmem = G; p.g0 = g0;
     hipError_t e;
-    if (d.rank == 32) {
+    if (i4) {
+      switch (gl) {
+        case 1: e = launch_rope<32, 1, true>(p, ra, grid, threads, s); break;
+        case 2: e = launch_rope<32, 2, true>(p, ra, grid, threads, s); break;
+        case 3: e = launch_rope<32, 3, true>(p, ra, grid, threads, s); break;
+        default: e = launch_rope<32, 4, true>(p, ra, grid, threads, s); break;
+      }
+    } else if (d.rank == 32) {
       switch (gl) {
         case 1: e = launch_rope<32, 1>(p, ra, grid, threads, s); break;
         case 2: e = launch_rope<32, 2>(p, ra, grid, threads, s); break;

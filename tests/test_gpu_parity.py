@@ -591,6 +591,9 @@ ROPE_CASES = [
     ("c3_small", dict(n_q_heads=28, n_kv_heads=4)),           # rank 32, G = 7: head groups of 4 and 3
     ("c3_small", dict(n_q_heads=20, n_kv_heads=4, context=2000, batch=2)),   # G = 5 (4 + 1) over several chunks
     ("c3_small", dict(n_q_heads=32, n_kv_heads=4, d_head=64, context=500)),  # G = 8 (4 + 4), head dim 64
+    ("c4_small", dict()),                                     # int4 latents (ragged lengths): codes minus zero point as operands
+    ("c4_small", dict(n_q_heads=8, n_kv_heads=4, q_dtype="bf16")),
+    ("c4_small", dict(n_q_heads=28, n_kv_heads=4, d_head=64, context=1500, ragged=())),   # int4, G = 7, head dim 64, several chunks
 ]
 
 
@@ -624,7 +627,7 @@ def test_attention_rope_edge_lengths_and_other_base():
         assert (got[0] == 0).all()
         check_out(got, ref, "rope", f"rope edges base={base}")
     # unsupported combinations are refused, not mis-computed
-    c4 = build_case("c4_small")
+    c4 = build_case("c2_small")
     L4 = layer_for(c4); L4.upload(c4.cache)
     qd4, qs4, _ = q_to_device(c4.q32[0], c4.sp.q_dtype)
     with pytest.raises(W.WsvdError) as e:
