@@ -215,6 +215,12 @@ wsvd_status wsvd_latent_append_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc,
 wsvd_status wsvd_prefill_append_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *x, int32_t n_tokens,
                                       int32_t seq_index, const void *A_K, const void *A_V, wsvd_paged_cache *cache,
                                       void *hip_stream);
+/* Attention over the prompt from a paged cache: wsvd_prefill_attn's tiled kernel (any n_q; BF16 queries, I8 latents,
+ * F32 out) with every 32-token cache block taken from the page the table names.  Results are those of
+ * wsvd_prefill_attn (tiled kernel) on the same rows. */
+wsvd_status wsvd_prefill_attn_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, int32_t n_q, int32_t n_after,
+                                    const void *B_K, const void *B_V, const wsvd_paged_cache *cache, int32_t max_seq_len,
+                                    void *out, void *hip_stream);
 wsvd_status wsvd_decode_attn_paged(wsvd_ctx *ctx, const wsvd_layer_desc *desc, const void *q, const void *q_scale,
                                    const void *B_K, const void *B_V, const wsvd_paged_cache *cache, int32_t max_seq_len,
                                    void *out, void *hip_stream);

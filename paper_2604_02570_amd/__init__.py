@@ -25,7 +25,7 @@ OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_CAPACITY, E_UNSUPPORTED, E_HIP, E_WORKS
 # every symbol include/wsvd.h declares
 EXPORTS = ["wsvd_create", "wsvd_destroy", "wsvd_cache_bytes", "wsvd_workspace_bytes", "wsvd_set_workspace",
            "wsvd_ctx_set_option", "wsvd_latent_append", "wsvd_latent_store", "wsvd_decode_attn", "wsvd_decode_attn_store", "wsvd_decode_attn_static",
-           "wsvd_paged_cache_bytes", "wsvd_latent_append_paged", "wsvd_prefill_append_paged", "wsvd_decode_attn_paged", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
+           "wsvd_paged_cache_bytes", "wsvd_latent_append_paged", "wsvd_prefill_append_paged", "wsvd_prefill_attn_paged", "wsvd_decode_attn_paged", "wsvd_decode_attn_rope", "wsvd_decode_step", "wsvd_check", "wsvd_status_str",
            "wsvd_factor_a_bytes", "wsvd_pack_factor_a", "wsvd_quantize_rows", "wsvd_cache_import", "wsvd_cache_export", "wsvd_quantize_act_i8", "wsvd_linear_w4a8",
            "wsvd_linear_w4a8_split", "wsvd_probe_stream_read", "wsvd_test_step_attention", "wsvd_fold_qk", "wsvd_fold_vo", "wsvd_decode_attn_latent",
            "wsvd_rmsnorm_quant_i8", "wsvd_swiglu_quant_i8", "wsvd_prefill_append",
@@ -100,6 +100,8 @@ def lib():
         L.wsvd_paged_cache_bytes.argtypes = [POINTER(LayerDesc), c_int32, c_int32, POINTER(c_size_t), POINTER(c_size_t)]
         L.wsvd_latent_append_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
                                                POINTER(PagedCache), c_void_p]
+        L.wsvd_prefill_attn_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_int32, c_void_p, c_void_p,
+                                              POINTER(PagedCache), c_int32, c_void_p, c_void_p]
         L.wsvd_prefill_append_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_int32, c_int32, c_void_p, c_void_p,
                                                 POINTER(PagedCache), c_void_p]
         L.wsvd_decode_attn_paged.argtypes = [c_void_p, POINTER(LayerDesc), c_void_p, c_void_p, c_void_p, c_void_p,
@@ -272,6 +274,11 @@ def wsvd_latent_append_paged(ctx, desc, x, x_scale, A_K, A_V, cache, stream=None
 def wsvd_prefill_append_paged(ctx, desc, x, n_tokens, seq_index, A_K, A_V, cache, stream=None):
     _ck(lib().wsvd_prefill_append_paged(ctx, byref(desc), _ptr(x), int(n_tokens), int(seq_index), _ptr(A_K), _ptr(A_V), byref(cache),
                                         _stream(stream)), "wsvd_prefill_append_paged")
+
+
+def wsvd_prefill_attn_paged(ctx, desc, q, n_q, n_after, B_K, B_V, cache, max_seq_len, out, stream=None):
+    _ck(lib().wsvd_prefill_attn_paged(ctx, byref(desc), _ptr(q), int(n_q), int(n_after), _ptr(B_K), _ptr(B_V), byref(cache),
+                                      int(max_seq_len), _ptr(out), _stream(stream)), "wsvd_prefill_attn_paged")
 
 
 def wsvd_decode_attn_paged(ctx, desc, q, q_scale, B_K, B_V, cache, max_seq_len, out, stream=None):

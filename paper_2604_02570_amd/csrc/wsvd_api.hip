@@ -491,6 +491,24 @@ wsvd_status wsvd_prefill_append_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc
   return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
 }
 
+wsvd_status wsvd_prefill_attn_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, int32_t n_q, int32_t n_after,
+                                    const void* B_K, const void* B_V, const wsvd_paged_cache* cache, int32_t max_seq_len, void* out,
+                                    void* hip_stream) {
+  if (!ctx || !q || !B_K || !B_V || !out) return WSVD_E_NULL;
+  wsvd_status st = check_desc(desc);
+  if (st != WSVD_OK) return st;
+  if ((st = check_paged(*desc, cache)) != WSVD_OK) return st;
+  if (!aligned16(q) || !aligned16(B_K) || !aligned16(B_V) || !aligned16(out)) return WSVD_E_ALIGN;
+  if (desc->out_dtype != WSVD_F32) return WSVD_E_UNSUPPORTED;
+  if (n_q < 1 || n_after < 0 || max_seq_len < 0) return WSVD_E_SHAPE;
+  if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
+  if (desc->latent_dtype != WSVD_I8 || desc->factor_dtype != WSVD_BF16 || desc->q_dtype != WSVD_BF16) return WSVD_E_UNSUPPORTED;
+  wsvd_cache view = {cache->k_codes, cache->v_codes, cache->k_meta, cache->v_meta, cache->seq_lens};
+  hipError_t e = wsvd_launch_prefill_attn(*desc, q, n_q, n_after, B_K, B_V, view, out, (hipStream_t)hip_stream, cache);
+  if (e == hipErrorNotSupported) return WSVD_E_UNSUPPORTED;
+  return e == hipSuccess ? WSVD_OK : WSVD_E_HIP;
+}
+
 wsvd_status wsvd_decode_attn_paged(wsvd_ctx* ctx, const wsvd_layer_desc* desc, const void* q, const void* q_scale,
                                    const void* B_K, const void* B_V, const wsvd_paged_cache* cache, int32_t max_seq_len,
                                    void* out, void* hip_stream) {

@@ -71,7 +71,8 @@ hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int ra
 hipError_t wsvd_launch_attn_multi(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s);
 // tiled causal attention of nq query tokens per sequence (I8 latents, BF16 factors and queries); any nq
 hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int nq, int n_after, const void* B_K, const void* B_V,
-                                    const wsvd_cache& cache, void* out, hipStream_t s);
+                                    const wsvd_cache& cache, void* out, hipStream_t s,
+                                    const wsvd_paged_cache* paged = nullptr);
 // projection + quantise + store of n_tok consecutive tokens of sequence seq, or of every sequence when seq < 0 (x then
 // holds [batch, n_tok, d_model]); I8 latents, BF16 x and factors; any n_tok
 hipError_t wsvd_launch_prefill_project(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* x, int n_tok, int seq,

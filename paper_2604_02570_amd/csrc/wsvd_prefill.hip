@@ -34,6 +34,10 @@ struct PrefillParams {
   float* out;                 // fp32 [B, Hkv, NR, d]
   int B, Hkv, G, d, t_cap, nq, n_after, NR;
   float c_scale;              // sm_scale * log2(e)
+  // paged cache only (else null): the planes are pools of n_pages pages, a page = page_rows rows of every kv head in the
+  // layout of a contiguous plane; block_table [B][max_pages]
+  const int* block_table;
+  int page_rows, max_pages, n_pages;
 };
 
 // x as an fp16 pair hi + lo; the fp32 value is pinned in a register so that hi is formed once (a fused
@@ -119,16 +123,34 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
   // one block ahead in registers: codes of both planes, the lane's K scale, the V scales of the lane half's 16 tokens
   v4i kc[KK], vc[KK], vs16[2];
   uint16_t ks_raw;
+  // paged cache: the table entries of the first 64 pages, one per lane, fetched once; a block's page is then a lane
+  // read with a wave-uniform index (a 32-token block never straddles pages).  Entries outside the pools read page 0
+  // (blocks past a sequence's end are never consumed; a bad entry under live rows is the append's to report).
+  int page_entry = 0;
+  if (p.block_table) page_entry = p.block_table[(size_t)b * p.max_pages + min(lane, p.max_pages - 1)];
   auto load_block = [&](int kb) {
+    const uint8_t *kp = kplane, *vp = vplane;
+    const uint16_t *km = kmeta, *vm = vmeta;
+    if (p.block_table) {
+      const int bpp = p.page_rows >> 5;                                 // blocks per page
+      const int pg = min(kb / bpp, p.max_pages - 1);
+      int e = pg < 64 ? __builtin_amdgcn_readlane(page_entry, __builtin_amdgcn_readfirstlane(pg))
+                      : p.block_table[(size_t)b * p.max_pages + pg];
+      e = (e >= 0 && e < p.n_pages) ? e : 0;
+      const size_t slot = (size_t)e * p.Hkv + kv;
+      kp = p.k_codes + slot * (size_t)p.page_rows * R; vp = p.v_codes + slot * (size_t)p.page_rows * R;
+      km = p.k_meta + slot * (size_t)p.page_rows; vm = p.v_meta + slot * (size_t)p.page_rows;
+      kb -= pg * bpp;
+    }
     const size_t off = (size_t)kb * (32 * R) + (size_t)lane * 16;
 #pragma unroll
     for (int kk = 0; kk < KK; kk++) {
-      kc[kk] = *(const v4i*)(kplane + off + kk * 1024);                 // (plain loads: the other query blocks of this
-      vc[kk] = *(const v4i*)(vplane + off + kk * 1024);                 //  sequence and head read the same blocks again)
+      kc[kk] = *(const v4i*)(kp + off + kk * 1024);                     // (plain loads: the other query blocks of this
+      vc[kk] = *(const v4i*)(vp + off + kk * 1024);                     //  sequence and head read the same blocks again)
     }
-    ks_raw = kmeta[kb * 32 + n];
-    vs16[0] = *(const v4i*)(vmeta + kb * 32 + 16 * g2);
-    vs16[1] = *(const v4i*)(vmeta + kb * 32 + 16 * g2 + 8);
+    ks_raw = km[kb * 32 + n];
+    vs16[0] = *(const v4i*)(vm + kb * 32 + 16 * g2);
+    vs16[1] = *(const v4i*)(vm + kb * 32 + 16 * g2 + 8);
   };
   load_block(0);
 
@@ -287,7 +309,7 @@ __global__ __launch_bounds__(64) void k_prefill_attn(PrefillParams p) {
 
 
 hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int nq, int n_after, const void* B_K, const void* B_V,
-                                    const wsvd_cache& cache, void* out, hipStream_t s) {
+                                    const wsvd_cache& cache, void* out, hipStream_t s, const wsvd_paged_cache* paged) {
   if (d.latent_dtype != WSVD_I8 || d.factor_dtype != WSVD_BF16 || d.q_dtype != WSVD_BF16) return hipErrorNotSupported;
   if (d.d_head % 32 != 0 || nq < 1 || n_after < 0) return hipErrorInvalidValue;
   PrefillParams p;
@@ -297,6 +319,8 @@ hipError_t wsvd_launch_prefill_attn(const wsvd_layer_desc& d, const void* q, int
   p.seq_lens = cache.seq_lens; p.out = (float*)out;
   p.B = d.batch; p.Hkv = d.n_kv_heads; p.G = d.n_q_heads / d.n_kv_heads; p.d = d.d_head; p.t_cap = d.t_cap;
   p.nq = nq; p.n_after = n_after;
+  p.block_table = nullptr; p.page_rows = p.max_pages = p.n_pages = 0;
+  if (paged) { p.block_table = paged->block_table; p.page_rows = paged->page_rows; p.max_pages = paged->max_pages; p.n_pages = paged->n_pages; }
   const int64_t NR = (int64_t)nq * p.G;
   if (NR > (int64_t)65535 * 32) return hipErrorInvalidValue;
   p.NR = (int)NR;

@@ -221,3 +221,34 @@ def test_paged_prefill_equals_the_contiguous_one(name, over, all_seqs):
     allowed = {int(PG.table_host[tb, pg]) for pg in range(first, min(PG.max_pages, (int(want_lens[tb]) + n2 + 63) // 64)) if pg != bad_page}
     assert touched and touched <= allowed, (touched, allowed)
     L.close()
+
+
+@pytest.mark.parametrize("name,over,nq,n_after", [("c3_small", dict(context=500, ragged=(20, 500), batch=4), 70, 0),
+                                                  ("c3_small", dict(n_q_heads=8, n_kv_heads=4, context=300), 33, 5),
+                                                  ("c5_small", dict(n_q_heads=4, n_kv_heads=2, context=400), 40, 0)],
+                         ids=["i8", "i8-2-heads-per-kv-later-rows", "i8-rank64"])
+def test_paged_prompt_attention_equals_the_contiguous_one(name, over, nq, n_after):
+    """wsvd_prefill_attn_paged against wsvd_prefill_attn's tiled kernel on the same rows (pages of 64 rows in shuffled
+    order, poison in the spare ones): bit-identical, and close to the oracle."""
+    c = build_case(name, **over)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    PG = Paged(L, 64, seed=5)
+    G = sp.n_q_heads // sp.n_kv_heads
+    rng = np.random.default_rng(9)
+    q32 = WI.bf16_exact(rng.standard_normal((sp.batch, sp.n_kv_heads, nq, G, sp.d_head)).astype(np.float32))
+    d = type(L.desc).from_buffer_copy(L.desc)
+    d.q_dtype = W.DTYPES["bf16"]
+    qd = as_dtype_dev(q32, "bf16")
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    n_max = int(c.cache.seq_lens.max())
+    want = torch.full(q32.shape, float("nan"), dtype=torch.float32, device="cuda")
+    W.wsvd_prefill_attn(L.ctx, d, qd, nq, n_after, BKd, BVd, L.cache, n_max, want)
+    got = torch.full(q32.shape, float("nan"), dtype=torch.float32, device="cuda")
+    W.wsvd_prefill_attn_paged(L.ctx, d, qd, nq, n_after, BKd, BVd, PG.cache, n_max, got)
+    assert W.wsvd_check(L.ctx) == 0
+    assert (got.cpu().view(torch.int32) == want.cpu().view(torch.int32)).all()
+    ref = O.causal_attn_reconstructed(c.cache, q32.astype(np.float64), c.BK.astype(np.float64), c.BV.astype(np.float64),
+                                      c.sm_scale, n_after=n_after)
+    check_out(got.cpu().numpy().astype(np.float64), ref, "i8", f"paged prompt attention {name}")
+    L.close()
