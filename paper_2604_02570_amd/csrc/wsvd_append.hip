@@ -218,7 +218,7 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
   WSVD_STAMP(p.timeline, tl_wg, wave, 3);
   // the finisher asks for the helpers' words now, one (sequence, channel) element per thread and helper: whatever
   // has arrived by the time its own sum is done needs no second look
-  constexpr int NPMAX = 2, EPT = (16 * R + NT - 1) / NT;         // helpers; elements per thread (SB <= 16)
+  constexpr int NPMAX = 2, EPT = (32 * R + NT - 1) / NT;         // helpers; elements per thread (SB <= 32)
   unsigned long long w[EPT][NPMAX];
   if (finisher && NP) {
 #pragma unroll
@@ -319,15 +319,18 @@ __global__ __launch_bounds__(NT) void k_append_split(AppendParams p, int SB, int
   }
 }
 
-// sequences per workgroup: as many (up to 16) as fit LDS with the finisher's share of their hidden-state rows
-// helpers per unit: two for model dims from 1024, none below (the "append_helpers" option overrides)
+// sequences per workgroup: 16, or 32 for larger batches (all 32 columns of the matrix-core tile: half as many passes over
+// the factors), fewer when the finisher's share of their hidden-state rows does not fit LDS
+// helpers per unit: two for model dims from 1024 (one when the batch needs more than one group of 32 sequences: the
+// finisher and one helper per unit and group are then one workgroup per CU for up to 64 sequences of 32 kv heads, a
+// single round), none below (the "append_helpers" option overrides)
 static int append_split_np(const wsvd_layer_desc& d, int opt_helpers = -1) {
   if (opt_helpers >= 0) return d.d_model >= 1024 ? opt_helpers : 0;
-  return d.d_model >= 1024 ? 2 : 0;
+  return d.d_model >= 1024 ? (d.batch > 32 ? 1 : 2) : 0;
 }
 static int append_split_sb(const wsvd_layer_desc& d) {
   const int share = append_split_np(d) ? (d.d_model / 16 + 1) / 2 * 16 : d.d_model;
-  int sb = 16;
+  int sb = d.batch > 16 ? 32 : 16;
   while (sb > 1 && (size_t)sb * (share + 8) * 2 > (size_t)144 * 1024) sb >>= 1;
   return sb;
 }
