@@ -834,14 +834,12 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
             }
           }
         } else {
+        // int8 codes -> fp16 through a byte permute and one packed subtraction per two codes (codes_f16)
 #pragma unroll
-        for (int kk = 0; kk < KK; kk++)
-#pragma unroll
-          for (int x = 0; x < 4; x++) {
-            const int dw = t.k[kk][blk][x];
-#pragma unroll
-            for (int b = 0; b < 4; b++) bop[2 * kk + (x >> 1)][4 * (x & 1) + b] = (_Float16)(int)(int8_t)(dw >> (8 * b));
-          }
+        for (int kk = 0; kk < KK; kk++) {
+          bop[2 * kk] = __builtin_bit_cast(v8h, codes_f16(t.k[kk][blk][0], t.k[kk][blk][1]));
+          bop[2 * kk + 1] = __builtin_bit_cast(v8h, codes_f16(t.k[kk][blk][2], t.k[kk][blk][3]));
+        }
         }
         v16f dc = product(0);
 #pragma unroll
