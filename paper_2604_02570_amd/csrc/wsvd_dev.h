@@ -229,7 +229,8 @@ WSVD_DEV size_t a_packed_offset(int kv, int j, int e, int rank, int d_model) {
 // ---------------------------------------------------------------- workspace layout (host + device)
 // [0, kWsCounterInts*4): counters (zeroed by wsvd_set_workspace, self-resetting); then the attention's split words and the
 // append's pushed words (8-byte {value, tag} words, cleared by their consumer: zero between launches); then the fp32
-// partial sums of the sliced append kernels.
+// partial sums of the sliced append kernels, which the decode step's projection launch uses for its slices too (followed
+// by its one pending word per sequence); no invariant there: written before read.
 // ints [0, 8192): unused; [8192, 12288): append tickets; [12288, 16000): fused-step row flags
 // (2*Hkv, hold the epoch of the last step); [16000]: fused-step finished-workgroup counter.
 constexpr int kWsCounterInts = 16384;
