@@ -232,7 +232,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
   [[maybe_unused]] const int pend_raw = NEWROW ? p.pending[cz] : 0;
   const uint32_t qs_raw = q_scale_raw(p, cz);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NW = blockDim.x >> 6;
-  // NEWROW: the row stored by this launch (K | V codes and scales): written by the workgroup's last wave, read by the
+  // NEWROW: the row stored by this launch (K | V codes and scales): written by wave 1 or 2, read by the
   // wave that consumes the row's tile once new_ready says so
   __shared__ __attribute__((aligned(16))) uint8_t new_codes[2][NEWROW ? R : 16];
   __shared__ uint16_t new_scale[2];
@@ -330,11 +330,11 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     q_raw[0] = *(const v4i*)((const char*)p.q + q_o0);
     q_raw[1] = *(const v4i*)((const char*)p.q + min(q_o0 + 16, q_bytes - 16));
     }
-    // NEWROW: the workgroup's last wave asks for the partial sums of its (sequence, kv head) now, ahead of the tiles and
+    // NEWROW: waves 1 and 2 ask for the partial sums of their (sequence, kv head) now, ahead of the tiles and
     // whether or not the row turns out to be this workgroup's (the addresses do not depend on the length).  They were
     // written by the launch before this one, on other XCDs: they come from memory, not from this XCD's L2
     if constexpr (NEWROW) {
-      if (wave == NW - 1) {
+      if (wave == 1 || wave == 2) {
         const float* src = (R == 32 && lane >= 32) ? p.new_v : p.new_k;
         const size_t o = (size_t)cz * p.new_ld + (size_t)cx * R + (lane & (R - 1));
         // straight-line, clamped (a surplus slot repeats the last part and is left out of the sum): loads under
@@ -451,12 +451,16 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     __syncthreads();
     WSVD_STAMP(tl, tl_wg, wave, 3);
     if constexpr (NEWROW) {
-      // The row, by the last wave, off everybody else's path: the other waves go on to their tiles, the wave that
+      // The row, by one wave, off everybody else's path: the other waves go on to their tiles, the wave that
       // consumes the row's tile (its last one) looks at new_ready when it gets there.
       // (A sequence longer than the caller's bound is reported by decode_work; its row is still stored, by the last chunk.)
-      if (wave == NW - 1) {
+      // The producer is wave 1, or wave 2 when wave 1 is the tile's consumer: both have asked for the partial sums; the
+      // early waves of a workgroup get their tiles first and finish first, so the row's work costs the workgroup nothing
+      // there (on the last wave it made that wave the workgroup's last by 0.8 us).
+      if (wave == 1 || wave == 2) {
         const int row = n_raw - 1, ct = p.chunk_rows >> 6, cyo = min((row >> 6) / ct, p.n_chunks - 1);
-        if (pend_raw != 0 && n_raw >= 1 && n_raw <= p.t_cap && (int)cy == cyo) {       // wave-uniform
+        const int consumer = ((row >> 6) - cyo * ct) % NW;
+        if (pend_raw != 0 && n_raw >= 1 && n_raw <= p.t_cap && (int)cy == cyo && wave == (consumer == 1 ? 2 : 1)) {       // wave-uniform
           // (the empty statements pin the first use of the loaded values here: hoisted to the loads, the first
           // addition made the whole workgroup wait for them in front of the barrier above)
 #pragma unroll
@@ -1640,6 +1644,7 @@ static hipError_t launch_m_newrow(const AttnParams& p, dim3 grid, int threads, h
 // int8 latents, rank 32 / 64, up to 4 query heads per kv head, at most 4 partial sums
 hipError_t wsvd_launch_attn_newrow(const AttnParams& p, int rank, dim3 grid, int threads, hipStream_t s) {
   if (!p.pending || !p.new_k || !p.new_v || p.n_parts < 1 || p.n_parts > 4 || p.block_table) return hipErrorInvalidValue;
+  if (threads < 256) return hipErrorInvalidValue;          // waves 1 and 2 carry the row's work
   if (rank == 32) return launch_m_newrow<32, 1024>(p, grid, threads, s);
   if (rank == 64) return launch_m_newrow<64, 512>(p, grid, threads, s);
   return hipErrorNotSupported;
