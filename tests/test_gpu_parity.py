@@ -861,6 +861,46 @@ def test_config3_int8_full_rope():
     L.close()
 
 
+def test_config4_int4_append_and_step_full():
+    """The cache update of the ragged int4 workload at its full shape (64 sequences, d_model 4096, 32 kv heads: the launch
+    the benchmark times - two groups of 32 sequences, a finisher and one helper per (plane, kv head) and group), rows
+    compared with the oracle's; then a whole wsvd_decode_step on top, sampled heads against the materialising oracle."""
+    c = build_case("c4", steps=2)
+    sp = c.sp
+    L = layer_for(c); L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
+    AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
+    x = WI.bf16_exact(c.x_new[0]); x64 = x.astype(np.float64)
+    before = c.cache.seq_lens.copy()
+    cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+    assert not O.latent_append(c.cache, x64, AK64, AV64).any()
+    assert L.append(as_dtype_dev(x, "bf16"), None, AKd, AVd) == 0
+    assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+    flips = _append_compare(L, c.cache, cK, cV, before, "i4")
+    print(f"c4 full append: boundary flips accepted = {flips} of {2 * sp.batch * sp.n_kv_heads * sp.rank} codes", flush=True)
+    assert flips <= 16
+    L.upload(c.cache)
+    x = WI.bf16_exact(c.x_new[1]); x64 = x.astype(np.float64)
+    before = c.cache.seq_lens.copy()
+    cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+    assert not O.latent_append(c.cache, x64, AK64, AV64).any()
+    qd, qs, q64 = q_to_device(c.q32[1], sp.q_dtype)
+    got, st = L.step(as_dtype_dev(x, "bf16"), AKd, AVd, qd, qs, BKd, BVd, int(c.cache.seq_lens.max()))
+    assert st == 0, W.status_str(st)
+    assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+    flips = _append_compare(L, c.cache, cK, cV, before, "i4")
+    assert flips <= 16
+    rng = np.random.default_rng(14)
+    heads = sorted(set((int(b), int(h)) for b, h in zip(rng.integers(0, sp.batch, 48), rng.integers(0, sp.n_q_heads, 48))))
+    ref = O.decode_attn_reconstructed(c.cache, q64, BK64, BV64, c.sm_scale, heads=heads)
+    m = ~np.isnan(ref)
+    a, _, l2 = err_stats(got[m], ref[m])
+    print(f"c4 full decode step, {len(heads)} sampled (sequence, head) pairs: max_abs={a:.3e} rel_l2={l2:.3e}", flush=True)
+    assert np.isfinite(got).all() and a <= 2e-2 and l2 <= 1e-3
+    L.close()
+
+
 def test_config4_int4_ragged_full():
     c = build_case("c4")
     sp = c.sp
