@@ -1152,6 +1152,8 @@ WSVD_DEV void attn_gqa_body(const AttnParams& p) {
   __shared__ int flag_sh;
   __shared__ __attribute__((aligned(16))) uint8_t new_codes[2][STORE ? R : 16];   // STORE: the row stored by this launch, K | V
   __shared__ uint16_t new_scale[2];
+  __shared__ int new_ready;                                                       // STORE: set once new_codes / new_scale are written
+  if (STORE && threadIdx.x == 0) new_ready = 0;                                   // (ordered before its use by the barriers below)
 
   const int n_raw = p.seq_lens[blockIdx.z];
   const uint32_t qs_raw = q_scale_raw(p, blockIdx.z);
@@ -1296,31 +1298,6 @@ WSVD_DEV void attn_gqa_body(const AttnParams& p) {
       for (int v = 0; v < 16; v++) qpart[wave][8 * (v >> 2) + 4 * hf + (v & 3)][l32] = qacc[v];
     }
   }
-#pragma unroll
-  for (int i = 1; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
-  if constexpr (STORE) {
-    if (own_new && wave == NW - 1) {                      // wave-uniform
-      if (R == 64 || lane < R) {
-        // the cache row for later launches (the rule and the layout of wsvd_latent_store), and a copy in LDS for this
-        // one: the tile that holds the row is fetched like any other, possibly before these stores land, and the
-        // wave that consumes it overwrites the row's bytes in its registers from the copy
-        AppendParams ap = {};
-        ap.codes[0] = const_cast<uint8_t*>(p.k_codes); ap.codes[1] = const_cast<uint8_t*>(p.v_codes);
-        ap.meta[0] = const_cast<uint16_t*>(p.k_meta); ap.meta[1] = const_cast<uint16_t*>(p.v_meta);
-        ap.Hkv = p.Hkv; ap.t_cap = p.t_cap; ap.latent_dtype = WSVD_I8;
-#pragma unroll
-        for (int pl = 0; pl < 2; pl++) {
-          store_row_lanes<R>(ap, pl, (int)blockIdx.z, (int)blockIdx.x, n_raw, lane, new_c[pl]);
-          const float a = lanes_max<R>(fabsf(new_c[pl]));
-          uint16_t sh = 0x3C00u;
-          if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
-          const float sc = f16_bits_to_f32(sh);
-          new_codes[pl][lane] = (uint8_t)(int8_t)(int)fminf(fmaxf(__builtin_rintf(new_c[pl] / sc), -127.f), 127.f);
-          if (lane == 0) new_scale[pl] = sh;
-        }
-      }
-    }
-  }
   __syncthreads();
   if constexpr (STORE) {
     // every wave of this workgroup holds its copy of the old length by now (it decided own_new with it above): say so.
@@ -1351,6 +1328,39 @@ WSVD_DEV void attn_gqa_body(const AttnParams& p) {
     if (j == 0) qdelta[g] = amax > 0.f ? amax / kLimbFull : 0.f;
   }
   __syncthreads();
+  // The second tile only now: in front of the barriers above its request blocked at the full memory pipeline, and every
+  // wave of the workgroup waited there for the slowest one's request to go out (the limbs were ready 3.4 us after the
+  // first tile requests).
+#pragma unroll
+  for (int i = 1; i < DEPTH; i++) load_gqa_tile<R>(buf[i], kplane, vplane, kmeta, vmeta, min(T + i * NW, spec_last), lane);
+  if constexpr (STORE) {
+    // The row, by the last wave, behind the last barrier of the prologue and so off everybody else's path (its latents were written by the
+    // launch before this one, on other XCDs: they come from memory, and in front of the barrier the whole workgroup
+    // waited for them); the wave that consumes the row's tile looks at new_ready when it gets there.
+    if (own_new && wave == NW - 1) {                      // wave-uniform
+      if (R == 64 || lane < R) {
+        // the cache row for later launches (the rule and the layout of wsvd_latent_store), and a copy in LDS for this
+        // one: the tile that holds the row is fetched like any other, possibly before these stores land, and the
+        // wave that consumes it overwrites the row's bytes in its registers from the copy
+        AppendParams ap = {};
+        ap.codes[0] = const_cast<uint8_t*>(p.k_codes); ap.codes[1] = const_cast<uint8_t*>(p.v_codes);
+        ap.meta[0] = const_cast<uint16_t*>(p.k_meta); ap.meta[1] = const_cast<uint16_t*>(p.v_meta);
+        ap.Hkv = p.Hkv; ap.t_cap = p.t_cap; ap.latent_dtype = WSVD_I8;
+#pragma unroll
+        for (int pl = 0; pl < 2; pl++) {
+          store_row_lanes<R>(ap, pl, (int)blockIdx.z, (int)blockIdx.x, n_raw, lane, new_c[pl]);
+          const float a = lanes_max<R>(fabsf(new_c[pl]));
+          uint16_t sh = 0x3C00u;
+          if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
+          const float sc = f16_bits_to_f32(sh);
+          new_codes[pl][lane] = (uint8_t)(int8_t)(int)fminf(fmaxf(__builtin_rintf(new_c[pl] / sc), -127.f), 127.f);
+          if (lane == 0) new_scale[pl] = sh;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      if (lane == 0) __hip_atomic_store(&new_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+  }
 
   WSVD_STAMP(tl, tl_wg, wave, 3);
   v4i aop[KK];
@@ -1403,6 +1413,13 @@ WSVD_DEV void attn_gqa_body(const AttnParams& p) {
   auto compute = [&](GqaTile<R>& t, int tile) {
     if constexpr (STORE) {
       if (own_new && tile == new_tile) {                   // wave-uniform: put the row stored by this launch into the tile
+        int budget = 1 << 20;                              // (written microseconds ago; the bound keeps the kernel finite)
+        while (__hip_atomic_load(&new_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == 0 && budget > 0) {
+          __builtin_amdgcn_s_sleep(2);
+          budget--;
+        }
+        if (budget == 0 && lane == 0) atomicExch(p.err_word, (int)WSVD_E_HIP);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         const int ti = n_raw & 63, blk = ti >> 5, tn = ti & 31;
 #pragma unroll
         for (int b2 = 0; b2 < 2; b2++) {
@@ -1584,13 +1601,15 @@ __global__ __launch_bounds__(NT) void k_attn_gqa(AttnParams p) {
 }
 
 // latent store + attention in one launch.  The length of a sequence may advance as soon as every workgroup of the
-// sequence has read the old one: each says so early in its life (a counter, no reply awaited), and the workgroup with
-// the highest id of the sequence, which is dispatched after all the others, waits for the count on its way out (it is
-// complete long before, unless that workgroup had no rows to attend), clears it and writes the new length.
+// sequence has read the old one: each says so early in its life (a counter, no reply awaited), and one workgroup of
+// the sequence waits for the count on its way out (it is complete long before; the wait is bounded, and the workgroups
+// it waits for need nothing from it), clears it and writes the new length.
 template <int R, int NT>
 __global__ __launch_bounds__(NT) void k_attn_gqa_store(AttnParams p) {
   attn_gqa_body<R, NT, false, false, true>(p);
-  if (blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1 && threadIdx.x == 0) {
+  // (the FIRST context chunk's workgroup: with several chunks it only delivers its partial result and is done well before
+  // the chunk that merges them, so this trip to the counter is over before the launch's last workgroup is)
+  if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0 && threadIdx.x == 0) {
     int* cnt = p.done + blockIdx.z;
     const int want = (int)(gridDim.x * gridDim.y);
     int budget = 1 << 16;
