@@ -60,6 +60,7 @@ def parse():
     ap.add_argument("--decode-step-call", action="store_true",
                     help="c3 / c4: the headline step as ONE wsvd_decode_step call instead of wsvd_latent_append + "
                          "wsvd_decode_attn (the default line reports that call beside the headline, see decode_step_call)")
+    ap.add_argument("--min-chunk", type=int, default=0, help="smallest context chunk per attention workgroup, rows (tuning)")
     ap.add_argument("--step-slices", type=int, default=0, help="d_model slices of the deferred step's projection launch (tuning)")
     ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep", "probe"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
@@ -106,6 +107,8 @@ def main():
             W.wsvd_ctx_set_option(c, "fused_step", 2)
         if args.deferred_step:
             W.wsvd_ctx_set_option(c, "step_deferred", 2)
+        if args.min_chunk:
+            W.wsvd_ctx_set_option(c, "min_chunk", args.min_chunk)
         if args.step_slices:
             W.wsvd_ctx_set_option(c, "step_slices", args.step_slices)
         if args.max_threads:
