@@ -426,7 +426,7 @@ hipError_t wsvd_launch_append_project(const wsvd_ctx* ctx, const wsvd_layer_desc
   if (ctx->opt.timeline_kernel != 1) p.timeline = nullptr;    // (profiling build: by default a step's stamps are its attention launch's)
   *n_parts = ns;
   switch (d.rank) {
-    case 32: return launch_append_project<32, 1024>(p, d, ns, s);
+    case 32: return launch_append_project<32, 512>(p, d, ns, s);      // (8 waves: 6.7 us at config 3; 16: 6.9 us; 4: 7.4 us)
     case 64: return launch_append_project<64, 512>(p, d, ns, s);
     default: return hipErrorNotSupported;
   }
