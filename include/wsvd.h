@@ -249,7 +249,9 @@ wsvd_status wsvd_decode_attn_static(wsvd_ctx *ctx, const wsvd_layer_desc *desc, 
  * Tuning of ONE context's work decomposition; correct use never needs it, results agree to fp32 rounding whatever is
  * set.  The setting applies to the calls made on this context afterwards (two contexts may differ).
  *   "wg_per_cu":   scales the number of wavefronts the attention grid aims for (default 4 = one resident round)
- *   "min_chunk":   smallest context chunk per attention workgroup in rows, multiple of 64, at least 256
+ *   "min_chunk":   smallest context chunk per attention workgroup in rows: 0 (default) = automatic (256 rows, and no
+ *                  split of a (sequence, kv head) whose latents are too few for a split to pay); else a multiple of 64
+ *                  (values below 256 count as 256), taken as given
  *   "max_threads": cap on the attention workgroup size (0 = the kernel's own bound; else 256, 512, 768 or 1024)
  *   "append_mode": 0 = the default append kernel; n > 0 = the kernel that cuts d_model into n equal slices
  * Unknown names and values out of range return WSVD_E_SHAPE.  (Names that switch between alternative kernels for

@@ -206,7 +206,7 @@ wsvd_status wsvd_ctx_set_option(wsvd_ctx* ctx, const char* name, int value) {
   if (!ctx || !name) return WSVD_E_NULL;
   wsvd_options& o = ctx->opt;
   if (!strcmp(name, "wg_per_cu") && value >= 1 && value <= 64) { o.wg_per_cu = value; return WSVD_OK; }
-  if (!strcmp(name, "min_chunk") && value >= 64 && value % 64 == 0) { o.min_chunk = value; return WSVD_OK; }
+  if (!strcmp(name, "min_chunk") && value >= 0 && value % 64 == 0) { o.min_chunk = value; return WSVD_OK; }
   if (!strcmp(name, "max_threads") && (value == 0 || (value >= 256 && value <= 1024 && value % 256 == 0))) { o.max_threads = value; return WSVD_OK; }
   if (!strcmp(name, "append_mode") && value >= 0 && value <= 64) { o.append_mode = value; return WSVD_OK; }
   if (!strcmp(name, "append_helpers") && (value == -1 || value == 0 || value == 2)) { o.append_helpers = value; return WSVD_OK; }
@@ -891,6 +891,7 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   int chunks_wanted = waves_per_unit / nw;
   if (chunks_wanted < 1) chunks_wanted = 1;
   int chunk_rows = ((max_rows + chunks_wanted - 1) / chunks_wanted + 63) / 64 * 64;
+  const bool auto_chunk = ctx->opt.min_chunk == 0;          // no explicit setting: the policy below may also undo a split
   int min_chunk = ctx->opt.min_chunk < 256 ? 256 : ctx->opt.min_chunk;
   // fp32 / bf16 latents (4-wave workgroups, single sequences in practice): a second chunk costs a hand-off between
   // workgroups (about 3 us) and saves half a chunk's stream; below 1024 rows per chunk that is a loss (640 rows of bf16
@@ -899,6 +900,15 @@ void wsvd_attn_plan(const wsvd_ctx* ctx, const wsvd_layer_desc& d, const void* q
   if (chunk_rows < min_chunk) chunk_rows = min_chunk;
   p.chunk_rows = chunk_rows;
   p.n_chunks = (max_rows + chunk_rows - 1) / chunk_rows;
+  // A split costs a hand-off between workgroups at the end (2.6 us measured) and saves part of one workgroup's stream
+  // (about 60 GB/s: 2.35 us for the 139 KB of a 2048-row rank-32 int8 unit).  With at most one unit per two compute units
+  // and below about 300 KB per (sequence, kv head) no split pays: 1 to 4 sequences of 32 heads and 2048 rows take
+  // 7.8-9.0 us as one chunk and 9.4-10.7 us as two; from 8 sequences on the two are level, at 12 the split wins by 0.7 us.
+  if (auto_chunk && mfma && p.n_chunks > 1 && n_units * 2 <= ctx->n_cu &&
+      (size_t)max_rows * 2 * (size_t)(row_bytes_host(d) + meta_bytes_host(d)) < (size_t)300 * 1024) {
+    p.chunk_rows = (max_rows + 63) / 64 * 64;
+    p.n_chunks = 1;
+  }
   grid = dim3((unsigned)d.n_kv_heads, (unsigned)p.n_chunks, (unsigned)d.batch);
   threads = nw * 64;
   const size_t tl_need = (size_t)grid.x * grid.y * grid.z * kTimelineWaves * kTimelineSlots * sizeof(long long);

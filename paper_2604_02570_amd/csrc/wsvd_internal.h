@@ -8,7 +8,7 @@
 // Per-context tuning and test settings (wsvd_ctx_set_option); defaults = automatic.
 struct wsvd_options {
   int wg_per_cu = 4;        // scales the number of wavefronts the attention grid aims for (4 = one resident round)
-  int min_chunk = 256;      // smallest context chunk per attention workgroup (rows)
+  int min_chunk = 0;        // smallest context chunk per attention workgroup (rows); 0 = automatic (256, and no split at all where none pays)
   int max_threads = 0;      // cap on the matrix-core attention kernels' workgroup size (0 = their launch bound)
   int append_mode = 0;      // n > 0: the append kernel with n equal d_model slices merged by the last arriver
   int append_helpers = -1;  // helpers per unit of the default append kernel (-1 = automatic, 0 or 2)

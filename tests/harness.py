@@ -32,12 +32,15 @@ class DeviceLayer:
     """A layer's device-side state: context, descriptor, cache planes, workspace."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, d_head, d_model, rank, t_cap, latent_dtype, factor_dtype,
-                 x_dtype, q_dtype, sm_scale=0.0, poison=True):
+                 x_dtype, q_dtype, sm_scale=0.0, poison=True, min_chunk=256):
         self.desc = W.layer_desc(batch, n_q_heads, n_kv_heads, d_head, d_model, rank, t_cap, latent_dtype, factor_dtype,
                                  x_dtype, q_dtype, "f32", sm_scale)
         self.latent_dtype = latent_dtype
         self.B, self.Hq, self.Hkv, self.d, self.E, self.r, self.t_cap = batch, n_q_heads, n_kv_heads, d_head, d_model, rank, t_cap
         self.ctx = W.wsvd_create(0)
+        # the tests' small shapes would mostly run as single chunks under the library's automatic policy: chunks of 256
+        # rows keep the split paths (hand-off, merge) in play; min_chunk=0 (the full-size cases) = the automatic policy
+        W.wsvd_ctx_set_option(self.ctx, "min_chunk", min_chunk)
         cb, mb = W.wsvd_cache_bytes(self.desc)
         # garbage in never-written rows must not leak into results: int codes 0xA5, float latents and metadata NaN
         self.poison = poison

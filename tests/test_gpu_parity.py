@@ -39,11 +39,11 @@ def check_out(got, ref, dtype, what=""):
     assert l2 <= t["rel_l2"], f"{what}: rel L2 {l2} > {t['rel_l2']}"
 
 
-def layer_for(c, t_cap=None):
+def layer_for(c, t_cap=None, min_chunk=256):
     sp = c.sp
     return DeviceLayer(sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, t_cap or c.t_cap,
                        sp.latent_dtype, sp.factor_dtype, "f32" if sp.factor_dtype == "f32" else "bf16", sp.q_dtype,
-                       c.sm_scale)
+                       c.sm_scale, min_chunk=min_chunk)
 
 
 def run_attend(c, L, step=0, heads=None, max_len=None):
@@ -219,6 +219,7 @@ def test_attention_independent_of_split_count(dtype):
     L = layer_for(c)
     L.upload(c.cache)
     outs = []
+    W.wsvd_ctx_set_option(L.ctx, "min_chunk", 0)      # the library's own policy (the harness pins 256-row chunks)
     got, ref = run_attend(c, L)             # default policy: one large workgroup per (sequence, kv head)
     check_out(got, ref, dtype, "splits default policy")
     outs.append(got)
@@ -243,8 +244,10 @@ def test_attention_independent_of_split_count(dtype):
     finally:
         W.wsvd_ctx_set_option(L.ctx, "min_chunk", 256)
         W.wsvd_ctx_set_option(L.ctx, "max_threads", 0)
+    # each variant sits 2e-5 .. 6e-5 (max abs; 4e-6 .. 7e-6 rel L2) from the oracle through its own order of fp32 sums and
+    # its own reference maxima for the probabilities' limbs: two variants differ by at most the sum of two such errors
     for o in outs[1:]:
-        assert np.abs(o - outs[0]).max() <= 1e-5 * np.abs(outs[0]).max()
+        assert np.abs(o - outs[0]).max() <= 2.5e-5 * np.abs(outs[0]).max()
     # repeatability: same launch twice gives identical bits (fixed merge order)
     g1, _ = run_attend(c, L); g2, _ = run_attend(c, L)
     assert (g1 == g2).all()
@@ -655,6 +658,10 @@ STEP_CASES = [
     ("c3_small", dict(batch=21, context=130), 3),                 # two groups of sequences in the projection launch
     ("c3_small", dict(), -1),                                     # whatever the library does by default
     ("c4_small", dict(), -1),
+    # -2: the defaults, the library's own chunk policy included (2000 rows of a few sequences stay one chunk)
+    ("c3_small", dict(context=2000, batch=2), -2),
+    ("c4_small", dict(context=2000, batch=2), -2),
+    ("c5_small", dict(context=2000, batch=2), -2),
 ]
 
 
@@ -681,6 +688,8 @@ def test_decode_step_matches_oracle(name, over, mode):
     flips = 0
     try:
         _set_step_mode(L.ctx, mode)
+        if mode == -2:
+            W.wsvd_ctx_set_option(L.ctx, "min_chunk", 0)
         for step in range(3):
             x = c.x_new[step]
             if xdt == "bf16":
@@ -708,6 +717,7 @@ def test_decode_step_matches_oracle(name, over, mode):
             L.upload(c.cache)      # continue from the oracle's cache so that later steps compare like with like
     finally:
         _set_step_mode(L.ctx, -1 if mode < 0 else 0)
+        W.wsvd_ctx_set_option(L.ctx, "min_chunk", 256)
     assert flips <= max(2, 2 * sp.batch * sp.n_kv_heads * sp.rank * 3 // 500)
     L.close()
 
@@ -755,7 +765,7 @@ def test_decode_step_tile_boundaries_and_capacity():
 # ------------------------------------------------------------------------------------------ the five workloads, full size
 def test_config1_fp32_full():
     c = build_case("c1")
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     got, ref = run_attend(c, L)                       # 256 rows, no append
     check_out(got, ref, "f32", "c1 attend(256)")
     x = c.x_new[0]
@@ -773,7 +783,7 @@ def test_config2_bf16_32_steps():
     running the same steps on its cache."""
     c = build_case("c2")
     sp = c.sp
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
     BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
@@ -795,7 +805,7 @@ def test_config2_bf16_32_steps():
 
 def test_config3_int8_full():
     c = build_case("c3")
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     got, ref = run_attend(c, L)
     check_out(got, ref, "i8", "c3 full")
     L.close()
@@ -807,7 +817,7 @@ def test_config3_int8_append_and_step_full():
     then a whole wsvd_decode_step at the same shape, all 512 heads against the materialising oracle."""
     c = build_case("c3", steps=2)
     sp = c.sp
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
     BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
@@ -847,7 +857,7 @@ def test_config3_int8_full_rope():
     and rotates the keys of a sample of (sequence, head) pairs."""
     c = build_case("c3")
     sp = c.sp
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     rng = np.random.default_rng(33)
     heads = [(int(b), int(h)) for b, h in zip(rng.integers(0, sp.batch, 96), rng.integers(0, sp.n_q_heads, 96))]
     heads += [(0, 0), (sp.batch - 1, sp.n_q_heads - 1)]
@@ -867,7 +877,7 @@ def test_config4_int4_append_and_step_full():
     compared with the oracle's; then a whole wsvd_decode_step on top, sampled heads against the materialising oracle."""
     c = build_case("c4", steps=2)
     sp = c.sp
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
     BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     AK64, AV64, BK64, BV64 = (a.astype(np.float64) for a in (c.AK, c.AV, c.BK, c.BV))
@@ -904,7 +914,7 @@ def test_config4_int4_append_and_step_full():
 def test_config4_int4_ragged_full():
     c = build_case("c4")
     sp = c.sp
-    L = layer_for(c); L.upload(c.cache)
+    L = layer_for(c, min_chunk=0); L.upload(c.cache)
     rng = np.random.default_rng(4)
     heads = [(int(b), int(h)) for b, h in zip(rng.integers(0, sp.batch, 192), rng.integers(0, sp.n_q_heads, 192))]
     heads += [(int(np.argmin(c.lens)), 0), (int(np.argmax(c.lens)), sp.n_q_heads - 1)]

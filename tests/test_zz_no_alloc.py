@@ -26,6 +26,7 @@ def _both(c):
     n_max = int(c.cache.seq_lens.max())
     want = L.attend(qd, qs, BKd, BVd, n_max)
     bare = W.wsvd_create(0)                       # no wsvd_set_workspace on this one
+    W.wsvd_ctx_set_option(bare, "min_chunk", 256)  # the layer's decomposition: bit-equal outputs, and splits in use
     out = torch.full_like(L.out, float("nan"))
     W.wsvd_decode_attn_static(bare, L.desc, qd, qs, BKd, BVd, L.cache, n_max, out)
     assert W.wsvd_check(bare) == 0
