@@ -61,6 +61,8 @@ def parse():
                     help="c3 / c4: the headline step as ONE wsvd_decode_step call instead of wsvd_latent_append + "
                          "wsvd_decode_attn (the default line reports that call beside the headline, see decode_step_call)")
     ap.add_argument("--min-chunk", type=int, default=0, help="smallest context chunk per attention workgroup, rows (tuning)")
+    ap.add_argument("--batch", type=int, default=0, help="c3 / c4 with another number of sequences (a variation, not the headline workload)")
+    ap.add_argument("--context", type=int, default=0, help="c3 with another context length (a variation, not the headline workload)")
     ap.add_argument("--step-slices", type=int, default=0, help="d_model slices of the deferred step's projection launch (tuning)")
     ap.add_argument("--workload", choices=["c1", "c2", "c3", "c4", "c5", "layer", "prefill", "shared", "sweep", "probe"], default="c3",
                     help="c3 (default): the batched int8 decode step the headline metric is quoted on; "
@@ -140,6 +142,10 @@ def main():
         return run_probe(args, np, torch, W, WI)
 
     sp = WI.spec(args.workload)
+    varied = {k: v for k, v in (("batch", args.batch), ("context", args.context)) if v}
+    if varied:
+        assert not (sp.ragged and args.context), "--context: the ragged workload draws its lengths from its own bounds"
+        sp = WI.spec(args.workload, **varied)
     i4 = sp.latent_dtype == "i4"
     B, Hq, Hkv, d, E, r, T = sp.batch, sp.n_q_heads, sp.n_kv_heads, sp.d_head, sp.d_model, sp.rank, sp.context
     n_sets = max(1, args.sets if args.workload == "c3" else min(args.sets, 4))    # a c4 set is 340 MB
@@ -415,9 +421,10 @@ def main():
         "dtype": "i4" if i4 else "i8",
         "data": "synthetic",
         "config": {
-            "workload": ("c4: ragged int4 decode step (append + attention), B=64 H=32 d_head=128 d_model=4096 r=32 T=1024..4096"
+            "workload": (f"c4: ragged int4 decode step (append + attention), B={B} H=32 d_head=128 d_model=4096 r=32 T=1024..4096"
                          if i4 else
-                         "c3: batched int8 decode step (append + attention), B=16 H=32 d_head=128 d_model=4096 r=32 T=2048"),
+                         f"c3: batched int8 decode step (append + attention), B={B} H=32 d_head=128 d_model=4096 r=32 T={T}")
+                        + (" (a variation of the workload: --batch / --context)" if varied else ""),
             "batch": B, "heads": Hq, "d_head": d, "d_model": E, "rank": r, "context": T,
             "context_drift_rows": max(seq_after) - int(lens0.max()) - 1,
             "rows_in_batch": int(lens0.sum()) + B,
@@ -502,7 +509,7 @@ def main():
                                          "unit": "TFLOP/s", "frac": round(mfma_flops / secs / 1e12 / 2500.0, 4),
                                          "algorithmic_flops_per_launch": int(mfma_flops)},
                            "hbm_view": hbm}
-    if not args.no_cpu_baseline and args.workload == "c3" and not args.rope:
+    if not args.no_cpu_baseline and args.workload == "c3" and not args.rope and not varied:
         res["cpu_baseline"] = cpu_baseline(np, row_bytes)
     print(json.dumps(res))
     W.wsvd_destroy(ctx)
