@@ -95,55 +95,9 @@ WSVD_DEV RowAddr append_row_addr(const AppendParams& p, int pl, int b, int kv, i
   return a;
 }
 
-// Store one latent row (fp32 values in c[0..R)) of (b, kv) at row t of plane `pl`.
-template <int R>
-WSVD_DEV void store_row(const AppendParams& p, int pl, int b, int kv, int t, const float* c) {
-  const size_t ph = (size_t)b * p.Hkv + kv;
-  if (p.latent_dtype == WSVD_F32) {
-    float* dst = (float*)p.codes[pl] + (ph * p.t_cap + t) * R;
-    for (int j = 0; j < R; j++) dst[j] = c[j];
-  } else if (p.latent_dtype == WSVD_BF16) {
-    uint16_t* dst = (uint16_t*)p.codes[pl] + (ph * p.t_cap + t) * R;
-    for (int j = 0; j < R; j++) dst[j] = f32_to_bf16_rne(c[j]);
-  } else if (p.latent_dtype == WSVD_I8) {
-    float v[R];
-    int8_t q[R];
-#pragma unroll
-    for (int j = 0; j < R; j++) v[j] = c[j];
-    const uint16_t sh = quantize_row_i8<R>(v, q);
-    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R);
-    if (!ra.ok) return;
-    for (int j = 0; j < R; j++) put_u8(p, ra.plane + (pl == 0 ? i8_k_offset(ra.t, j, R) : i8_v_offset(ra.t, j, R)), (uint8_t)q[j]);
-    put_u16(p, &p.meta[pl][ra.meta], sh);
-  } else {  // I4, R == 32
-    float v[R];
-    uint8_t q[R];
-#pragma unroll
-    for (int j = 0; j < R; j++) v[j] = c[j];
-    uint16_t sh, zh;
-    quantize_row_i4<R>(v, q, &sh, &zh);
-    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R / 2);
-    if (!ra.ok) return;
-    uint8_t* plane = ra.plane;
-    if (pl == 0) {
-      for (int j = 0; j < R; j += 2) { int nib; put_u8(p, plane + i4_k_offset(ra.t, j, &nib), (uint8_t)(q[j] | (q[j + 1] << 4))); }
-    } else {
-      // tokens (t, t^1) share each byte; the other token was (or will be) written by a different launch
-      for (int j = 0; j < R; j++) {
-        int nib;
-        uint8_t* bp = plane + i4_v_offset(ra.t, j, &nib);
-        const uint8_t old = *bp;
-        put_u8(p, bp, nib ? (uint8_t)((old & 0x0F) | (q[j] << 4)) : (uint8_t)((old & 0xF0) | q[j]));
-      }
-    }
-    put_u16(p, &p.meta[pl][ra.meta * 2], sh);
-    put_u16(p, &p.meta[pl][ra.meta * 2 + 1], zh);
-  }
-}
-
 // Store one latent row with R cooperating lanes (a half wave for R = 32, a wave for R = 64, 16 lanes for R = 16):
 // lane j holds c_j.  Same arithmetic per element as quantize_row_i8 / quantize_row_i4 (max / min are exact in any
-// order), so the stored bits are identical to the sequential routine's.
+// order), so the stored bits are identical to those routines'.
 template <int R>
 WSVD_DEV float lanes_max(float x) {   // max over the R adjacent lanes that hold one row
   x = row16_max(x);
@@ -153,8 +107,9 @@ WSVD_DEV float lanes_max(float x) {   // max over the R adjacent lanes that hold
   return R == 64 ? fmaxf(a, b) : (lane < 32 ? a : b);
 }
 
+// `on` (the same for all lanes of a row): false = take part in the reductions, form no address, store nothing.
 template <int R>
-WSVD_DEV void store_row_lanes(const AppendParams& p, int pl, int b, int kv, int t, int j, float c) {
+WSVD_DEV void store_row_lanes(const AppendParams& p, int pl, int b, int kv, int t, int j, float c, bool on = true) {
   const size_t ph = (size_t)b * p.Hkv + kv;
   if (p.latent_dtype == WSVD_F32) {
     ((float*)p.codes[pl])[(ph * p.t_cap + t) * R + j] = c;
@@ -166,7 +121,9 @@ WSVD_DEV void store_row_lanes(const AppendParams& p, int pl, int b, int kv, int 
     if (a != 0.f) sh = guard_scale_f16(a / 127.0f);
     const float sc = f16_bits_to_f32(sh);
     const float v = fminf(fmaxf(__builtin_rintf(c / sc), -127.f), 127.f);
-    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R);
+    RowAddr ra;
+    ra.ok = false;
+    if (on) ra = append_row_addr(p, pl, b, kv, t, R);
     if (ra.ok) {
       put_u8(p, ra.plane + (pl == 0 ? i8_k_offset(ra.t, j, R) : i8_v_offset(ra.t, j, R)), (uint8_t)(int8_t)(int)v);
       if (j == 0) put_u16(p, &p.meta[pl][ra.meta], sh);
@@ -182,7 +139,9 @@ WSVD_DEV void store_row_lanes(const AppendParams& p, int pl, int b, int kv, int 
     const int zi = (int)z;
     int q = (int)fminf(fmaxf(__builtin_rintf(c / sc), -64.f), 64.f) + zi;
     q = q < 0 ? 0 : (q > 15 ? 15 : q);
-    const RowAddr ra = append_row_addr(p, pl, b, kv, t, R / 2);
+    RowAddr ra;
+    ra.ok = false; ra.plane = nullptr; ra.t = 0; ra.meta = 0;
+    if (on) ra = append_row_addr(p, pl, b, kv, t, R / 2);
     uint8_t* plane = ra.plane;
     int nib;
     if (pl == 0) {
@@ -213,11 +172,11 @@ WSVD_DEV void append_store_rows(const AppendParams& p, int pl, int kv, int b0, i
     const bool on = (r0 + rsub < nb) && n >= 0 && n < p.t_cap;
     const float c = crow[row][j];
     if (p.latent_dtype == WSVD_I8 || p.latent_dtype == WSVD_I4) {
-      // the reductions need every lane of the wave: rows that must not be stored are redirected to a scratch-free no-op
-      if (__builtin_amdgcn_ballot_w64(on) == ~0ull) store_row_lanes<R>(p, pl, append_seq_of(p, b0 + row), kv, n, j, c);
-      else if (on) {                                   // ragged tail or a sequence at capacity: per-row sequential path
-        if (j == 0) store_row<R>(p, pl, append_seq_of(p, b0 + row), kv, n, crow[row]);
-      }
+      // the reductions need every lane of the wave: the lanes of a row that must not be stored (the surplus ones of a
+      // ragged tail, a sequence at capacity) go through them on the clamped row's values and skip the stores.  (A
+      // single sequence, or the odd row of a group, used to fall back to one lane quantising the row by itself:
+      // 2 us more for the launch.)
+      if (__builtin_amdgcn_ballot_w64(on) != 0ull) store_row_lanes<R>(p, pl, append_seq_of(p, b0 + row), kv, n, j, c, on);
     } else if (on) {
       store_row_lanes<R>(p, pl, append_seq_of(p, b0 + row), kv, n, j, c);
     }

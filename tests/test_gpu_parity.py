@@ -370,11 +370,11 @@ def test_large_scores_stay_finite():
 
 
 # ------------------------------------------------------------------------------------------ append
-def _append_compare(L, oc, c64K, c64V, t_rows, dtype):
+def _append_compare(L, oc, c64K, c64V, t_rows, dtype, only=None):
     """Compare GPU-written rows with the oracle's; c64K/V [B,Hkv,r] are the oracle's fp64 latents."""
     flips = 0
     for plane, ocodes, oscale, ozero, c64 in ((0, oc.k, oc.k_scale, oc.k_zero, c64K), (1, oc.v, oc.v_scale, oc.v_zero, c64V)):
-        for b in range(oc.B):
+        for b in (range(oc.B) if only is None else only):
             t = int(t_rows[b])
             gc, gs, gz = L.download(plane, t, 1)
             gc = gc[b, :, 0]; want = ocodes[b, :, t]
@@ -437,6 +437,50 @@ def test_append_matches_oracle(name, over):
     print(f"append {name}: boundary flips accepted = {total_flips}", flush=True)
     n_codes = 2 * sp.batch * sp.n_kv_heads * sp.rank * 3
     assert total_flips <= max(2, n_codes // 500), "too many rounding flips to be boundary cases"
+    L.close()
+
+
+@pytest.mark.parametrize("name", ["c3_small", "c4_small"], ids=["i8", "i4"])
+def test_append_quantised_partly_filled_groups(name):
+    """The lanes of a wave quantise several rows side by side.  Groups that do not fill a wave: three sequences with the
+    middle one at capacity (its lanes take part in the reductions and store nothing; reported, left untouched), then a
+    single sequence."""
+    c = build_case(name, batch=3)
+    sp = c.sp
+    AK64, AV64 = c.AK.astype(np.float64), c.AV.astype(np.float64)
+    L = layer_for(c)
+    c.cache.seq_lens[:] = [5, c.t_cap, 0]
+    L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    held = [L.download(pl, 0, c.t_cap) for pl in (0, 1)]
+    x = WI.bf16_exact(c.x_new[0]); x64 = x.astype(np.float64)
+    cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+    before = c.cache.seq_lens.copy()
+    full = O.latent_append(c.cache, x64, AK64, AV64)
+    assert full.tolist() == [False, True, False]
+    st = L.append(as_dtype_dev(x, "bf16"), None, AKd, AVd)
+    assert st == 5, "capacity overflow must be reported by wsvd_check"
+    assert L.seq_lens.cpu().numpy().tolist() == [6, c.t_cap, 1]
+    flips = _append_compare(L, c.cache, cK, cV, before, sp.latent_dtype, only=(0, 2))
+    for pl in (0, 1):
+        now = L.download(pl, 0, c.t_cap)
+        for a, b in zip(held[pl], now):
+            if a is not None:
+                assert a[1].tobytes() == b[1].tobytes(), "a sequence at capacity must not be modified"
+    L.close()
+    c = build_case(name, batch=1)
+    AK64, AV64 = c.AK.astype(np.float64), c.AV.astype(np.float64)
+    L = layer_for(c); L.upload(c.cache)
+    AKd, AVd = L.pack_A(c.AK, "bf16"), L.pack_A(c.AV, "bf16")
+    x = WI.bf16_exact(c.x_new[0]); x64 = x.astype(np.float64)
+    cK = O.project_latents(x64, AK64); cV = O.project_latents(x64, AV64)
+    before = c.cache.seq_lens.copy()
+    assert not O.latent_append(c.cache, x64, AK64, AV64).any()
+    st = L.append(as_dtype_dev(x, "bf16"), None, AKd, AVd)
+    assert st == 0, W.status_str(st)
+    assert (L.seq_lens.cpu().numpy() == c.cache.seq_lens).all()
+    flips += _append_compare(L, c.cache, cK, cV, before, sp.latent_dtype)
+    assert flips <= 2
     L.close()
 
 
