@@ -402,7 +402,7 @@ wsvd_status wsvd_decode_attn_shared(wsvd_ctx *ctx, int32_t batch, int32_t n_head
  * wsvd_decode_attn_latent: the attention that goes with the two folds.  c_Q [B, Hq, rq] F32 is the Q latent as it leaves
  *   its down-projection, qk_fold the output of wsvd_fold_qk; scores sm_scale * C_K (c_Q M)^T, softmax, and
  *   u_out[b, h, :] = p^T C_V [B, Hq, r] F32 (zeros for an empty sequence).  B_K and B_V are not read.
- *   I8 latents with at most 8 query heads per kv head, I4 latents with at most 4 (WSVD_E_UNSUPPORTED otherwise);
+ *   I8 or I4 latents, rank up to 64, at most 8 query heads per kv head (WSVD_E_UNSUPPORTED otherwise);
  *   desc->q_dtype is ignored.
  *   Pointers DEVICE, 16-byte aligned; max_seq_len, workspace, stream and error behaviour as wsvd_decode_attn.
  */

@@ -728,7 +728,7 @@ wsvd_status wsvd_decode_attn_latent(wsvd_ctx* ctx, const wsvd_layer_desc* desc, 
   if (max_seq_len > desc->t_cap) return WSVD_E_CAPACITY;
   const int G = desc->n_q_heads / desc->n_kv_heads;
   if (desc->latent_dtype != WSVD_I8 && desc->latent_dtype != WSVD_I4) return WSVD_E_UNSUPPORTED;
-  if (G > (desc->latent_dtype == WSVD_I8 ? 8 : 4) || desc->rank > 64) return WSVD_E_UNSUPPORTED;
+  if (G > 8 || desc->rank > 64) return WSVD_E_UNSUPPORTED;
   size_t need;
   wsvd_workspace_bytes(desc, &need);
   if (!ctx->ws || ctx->ws_bytes < need) return WSVD_E_WORKSPACE;

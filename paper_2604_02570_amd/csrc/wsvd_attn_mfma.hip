@@ -510,7 +510,7 @@ WSVD_DEV void attn_mfma_body(const AttnParams& p, AttnMfmaShared<R, G, NT, (ROPE
     for (int ps = 0; ps < NLP; ps++) {
       const int item = min(tid + ps * (int)blockDim.x, 4 * G * R - 1);
       const int j = item % R, g = (item / R) % G, part = item / (R * G);
-      const int h = cx * G + g;
+      const int h = (int)first_head(p, cx) + g;
       const float* cq = (const float*)p.q + ((size_t)cz * p.Hq + h) * p.rq;
       const float* fold = p.qk_fold + (size_t)h * p.rq * R + j;
       float mv[LQ], cv[LQ];
@@ -1683,9 +1683,19 @@ static hipError_t launch_m_latent(const AttnParams& p, dim3 grid, int threads, h
 }
 
 // Latent-query / latent-output attention: int8 latents with up to 8 query heads per kv head (5 to 8: exactly 512
-// threads), int4 latents with up to 4; rq <= 64.
+// threads), int4 latents likewise (5 to 8: two launches over the same cache); rq <= 64.
 hipError_t wsvd_launch_attn_latent(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
   if (p.rq < 1 || p.rq > 64 || !p.qk_fold) return hipErrorInvalidValue;
+  if (p.G > 4 && latent_dtype == WSVD_I4 && rank == 32 && p.G <= 8) {
+    // int4 latents with 5..8 query heads per kv head: two launches of the paired-block kernel, 4 heads then the rest
+    AttnParams q = p;
+    for (int g0 = 0; g0 < p.G; g0 += 4) {
+      q.G = p.G - g0 < 4 ? p.G - g0 : 4; q.Gmem = p.G; q.g0 = g0;
+      hipError_t e = launch_m_latent<32, true, 1024>(q, grid, threads > 512 ? 512 : threads, s);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   if (p.G > 4) {
     if (latent_dtype != WSVD_I8 || p.G > 8) return hipErrorNotSupported;
     if (threads != 512) return hipErrorInvalidValue;

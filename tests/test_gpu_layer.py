@@ -77,6 +77,8 @@ LATENT_CASES = [
     ("c3_small", 32, dict(n_q_heads=20, n_kv_heads=4, context=900)),        # rank 32, five heads per kv head
     ("c3_small", 48, dict(n_q_heads=16, n_kv_heads=2, context=70)),         # eight heads per kv head
     ("c5_small", 13, dict(n_q_heads=12, n_kv_heads=2, context=2500, batch=2)),   # six, several chunks
+    ("c4_small", 32, dict(n_q_heads=28, n_kv_heads=4)),                     # int4, seven heads per kv head: 4 + 3 in two launches
+    ("c4_small", 20, dict(n_q_heads=10, n_kv_heads=2, context=2000, batch=2, ragged=())),   # int4, five, several chunks
 ]
 
 
