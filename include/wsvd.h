@@ -193,8 +193,10 @@ wsvd_status wsvd_decode_attn_store(wsvd_ctx *ctx, const wsvd_layer_desc *desc, c
  * [i * page_rows, (i + 1) * page_rows) of sequence b.  desc->t_cap must equal max_pages * page_rows.  Entries for pages
  * a sequence does not reach yet are not read for results; an append into a row whose entry is outside [0, n_pages)
  * stores nothing and records WSVD_E_SHAPE in the device status word.  The caller owns pools and table.
- * Quantised latents (I8, I4) with up to 4 query heads per kv head and rank <= 64; x and factors BF16 for the append
- * (WSVD_E_UNSUPPORTED otherwise).  Results are those of wsvd_latent_append / wsvd_decode_attn on the same rows.
+ * Quantised latents (I8, I4), rank <= 64, up to 8 query heads per kv head; x and factors BF16 for the append
+ * (WSVD_E_UNSUPPORTED otherwise).  Results are those of wsvd_latent_append / wsvd_decode_attn on the same rows (bit for
+ * bit up to 4 query heads per kv head and for I4; 5..8 heads over I8 latents run as two launches over head sets of 4,
+ * the cache read by each, and agree with wsvd_decode_attn to fp32 rounding).
  */
 typedef struct {
   void *k_codes, *v_codes;       /* DEVICE pools */

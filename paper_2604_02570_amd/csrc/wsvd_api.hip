@@ -438,7 +438,7 @@ namespace {
 wsvd_status check_paged(const wsvd_layer_desc& d, const wsvd_paged_cache* c) {
   if (!c || !c->k_codes || !c->v_codes || !c->k_meta || !c->v_meta || !c->seq_lens || !c->block_table) return WSVD_E_NULL;
   if (d.latent_dtype != WSVD_I8 && d.latent_dtype != WSVD_I4) return WSVD_E_UNSUPPORTED;
-  if (d.rank > 64 || d.n_q_heads / d.n_kv_heads > 4) return WSVD_E_UNSUPPORTED;
+  if (d.rank > 64) return WSVD_E_UNSUPPORTED;
   if (c->page_rows < 64 || c->page_rows % 64 != 0 || c->max_pages < 1 || c->n_pages < 1) return WSVD_E_SHAPE;
   if ((int64_t)c->max_pages * c->page_rows != d.t_cap) return WSVD_E_SHAPE;
   if (!aligned16(c->k_codes) || !aligned16(c->v_codes) || !aligned16(c->k_meta) || !aligned16(c->v_meta) ||

@@ -1755,17 +1755,23 @@ int wsvd_attn_mfma_max_threads(int latent_dtype, int rank, int G) {
 }
 
 hipError_t wsvd_launch_attn_mfma(const AttnParams& p, int latent_dtype, int rank, dim3 grid, int threads, hipStream_t s) {
-  if (p.block_table && (p.G > 4 || rank > 64)) return hipErrorNotSupported;      // paged cache: the paired-block kernel only
-  if (p.G > 4 && latent_dtype == WSVD_I4 && rank == 32 && p.G <= 8 && !p.block_table) {
-    // int4 latents with 5..8 query heads per kv head: two launches of the paired-block kernel, 4 heads then the rest
+  if (p.block_table && rank > 64) return hipErrorNotSupported;                   // paged cache: the paired-block kernel only
+  const bool i4_32 = latent_dtype == WSVD_I4 && rank == 32;
+  const bool i8_paged = p.block_table && latent_dtype == WSVD_I8 && (rank == 32 || rank == 64);
+  if (p.G > 4 && p.G <= 8 && (i4_32 || i8_paged)) {
+    // 5..8 query heads per kv head over int4 latents, or over a paged int8 cache: two launches of the paired-block
+    // kernel, 4 heads then the rest
     AttnParams q = p;
+    const int nt = threads > 512 ? 512 : threads;
     for (int g0 = 0; g0 < p.G; g0 += 4) {
       q.G = p.G - g0 < 4 ? p.G - g0 : 4; q.Gmem = p.G; q.g0 = g0;
-      hipError_t e = launch_m<32, true, 1024>(q, grid, threads > 512 ? 512 : threads, s);
+      hipError_t e = i4_32 ? launch_m<32, true, 1024>(q, grid, nt, s)
+                   : rank == 32 ? launch_m<32, false, 1024>(q, grid, nt, s) : launch_m<64, false, 512>(q, grid, nt, s);
       if (e != hipSuccess) return e;
     }
     return hipSuccess;
   }
+  if (p.block_table && p.G > 4) return hipErrorNotSupported;
   if (p.G > 4) {
     // 5..8 query heads per kv head: I8 latents only
     if (latent_dtype != WSVD_I8 || p.G > 8) return hipErrorNotSupported;

@@ -66,10 +66,14 @@ class Paged:
 
 
 CASES = [("c3_small", dict(), 64), ("c3_small", dict(context=1500, batch=2), 256), ("c4_small", dict(), 128),
-         ("c3_small", dict(n_q_heads=8, n_kv_heads=2), 64), ("c5_small", dict(n_q_heads=4, n_kv_heads=2), 64)]
+         ("c3_small", dict(n_q_heads=8, n_kv_heads=2), 64), ("c5_small", dict(n_q_heads=4, n_kv_heads=2), 64),
+         # 5..8 query heads per kv head: head sets of 4 in consecutive launches (int8: the contiguous cache runs another kernel)
+         ("c5_small", dict(), 64), ("c3_small", dict(n_q_heads=10, n_kv_heads=2, context=1500, batch=2), 256),
+         ("c4_small", dict(n_q_heads=24, n_kv_heads=4), 128)]
 
 
-@pytest.mark.parametrize("name,over,page_rows", CASES, ids=["i8", "i8-split-context", "i4-ragged", "i8-4-heads-per-kv", "i8-rank64"])
+@pytest.mark.parametrize("name,over,page_rows", CASES, ids=["i8", "i8-split-context", "i4-ragged", "i8-4-heads-per-kv", "i8-rank64",
+                                                            "i8-rank64-7-heads-per-kv", "i8-5-heads-per-kv-split-context", "i4-6-heads-per-kv"])
 def test_paged_attention_and_append_equal_the_contiguous_ones(name, over, page_rows):
     c = build_case(name, **over)
     sp = c.sp
@@ -79,13 +83,17 @@ def test_paged_attention_and_append_equal_the_contiguous_ones(name, over, page_r
     qd, qs, q64 = q_to_device(c.q32[0], sp.q_dtype)
     BKd, BVd = as_dtype_dev(c.BK, "bf16"), as_dtype_dev(c.BV, "bf16")
     n_max = int(c.cache.seq_lens.max())
+    # int8 latents with more than 4 query heads per kv head: the contiguous cache goes through the grouped-query kernel,
+    # the paged one through the paired-block kernel; equal up to rounding, not bit for bit
+    same_kernel = not (sp.latent_dtype == "i8" and sp.n_q_heads // sp.n_kv_heads > 4)
     # ---- attention over the uploaded rows
     want = L.attend(qd, qs, BKd, BVd, n_max)
     out = torch.full_like(L.out, float("nan"))
     W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, PG.cache, n_max, out)
     assert W.wsvd_check(L.ctx) == 0
     got = out.cpu().numpy().astype(np.float64)
-    assert (got == want).all(), "paged attention differs from the contiguous one"
+    assert (got == want).all() or not same_kernel, "paged attention differs from the contiguous one"
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
     ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
     check_out(got, ref, sp.latent_dtype, f"paged attention {name}")
     # ---- three appends on both caches (rows cross page and tile boundaries in the ragged cases), then attention again
@@ -118,7 +126,8 @@ def test_paged_attention_and_append_equal_the_contiguous_ones(name, over, page_r
     W.wsvd_decode_attn_paged(L.ctx, L.desc, qd, qs, BKd, BVd, PG.cache, n_max, out)
     assert W.wsvd_check(L.ctx) == 0
     got = out.cpu().numpy().astype(np.float64)
-    assert (got == want).all(), "paged attention after paged appends differs from the contiguous path"
+    assert (got == want).all() or not same_kernel, "paged attention after paged appends differs from the contiguous path"
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
     ref = O.decode_attn_reconstructed(c.cache, q64, c.BK.astype(np.float64), c.BV.astype(np.float64), c.sm_scale)
     check_out(got, ref, sp.latent_dtype, f"paged append + attention {name}")
     L.close()
