@@ -77,8 +77,12 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
     for (int v = 0; v < VPL; v++) u[g][v] = 0.f;
   }
 
-  for (int t0 = w.row_begin + grp; t0 < w.row_end; t0 += NGRP * UNROLL) {
-    v4i kr[UNROLL], vr[UNROLL];
+  // Two batches of UNROLL rows per lane group in flight: the next batch is requested before the current one is
+  // consumed, so a short chunk (640 rows = 3 batches) waits for memory twice, not three times: 8.3 -> 7.9 us for the
+  // single 640-row bf16 sequence.  Rows are consumed in the same order as without the prefetch.  (Measured slower:
+  // the first batches and B_V requested in front of the query absorption, 8.5-8.9 us.)
+  constexpr int STEP = NGRP * UNROLL;
+  auto load_rows = [&](v4i (&kr)[UNROLL], v4i (&vr)[UNROLL], int t0) {
 #pragma unroll
     for (int k = 0; k < UNROLL; k++) {
       const int t = t0 + k * NGRP;
@@ -87,6 +91,8 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
         vr[k] = *(const v4i*)(vb + (size_t)t * ROWB);
       }
     }
+  };
+  auto use_rows = [&](const v4i (&kr)[UNROLL], const v4i (&vr)[UNROLL], int t0) {
 #pragma unroll
     for (int k = 0; k < UNROLL; k++) {
       const int t = t0 + k * NGRP;
@@ -109,6 +115,20 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
           m[g] = mn;
         }
       }
+    }
+  };
+  {
+    v4i ka[UNROLL], va[UNROLL], kb2[UNROLL], vb2[UNROLL];
+    int t0 = w.row_begin + grp;
+    load_rows(ka, va, t0);
+    while (t0 < w.row_end) {
+      load_rows(kb2, vb2, t0 + STEP);       // (nothing is requested past the chunk's end)
+      use_rows(ka, va, t0);
+      t0 += STEP;
+      if (t0 >= w.row_end) break;
+      load_rows(ka, va, t0 + STEP);
+      use_rows(kb2, vb2, t0);
+      t0 += STEP;
     }
   }
   // NOTE: group_sum uses DPP across the LPR lanes of a row; lanes of a group take the same branch
