@@ -39,6 +39,10 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
   __shared__ float Msh[G], Lsh[G], Ush[G * R];
   __shared__ float gm[NGRP * G], gl[NGRP * G];
   __shared__ float gu[NGRP * G * R];
+  // parts the merge of the NGRP lane groups is divided into (a power of two that divides NGRP; 1 = a single pass)
+  constexpr int NPART = G * R >= 256 ? 1 : (256 / (G * R) >= 8 ? 8 : 256 / (G * R) >= 4 ? 4 : 2);
+  static_assert(NGRP % NPART == 0, "the lane groups divide evenly over the parts");
+  __shared__ float pm[NPART * G], pl[NPART * G], pu[NPART * G * R];
   __shared__ int flag_sh;
 
   const WorkItem w = decode_work(p, p.seq_lens[blockIdx.z]);
@@ -141,15 +145,39 @@ __global__ __launch_bounds__(256) void k_attn_generic(AttnParams p) {
     for (int v = 0; v < VPL; v++) gu[(grp * G + g) * R + sl * VPL + v] = u[g][v];
   }
   __syncthreads();
+  // Merge of the lane groups' partial results, one thread per (part of the groups, head, latent dim), then one per
+  // (head, latent dim) over the parts: with a single head of rank 32 a lone pass would leave 224 of the 256 threads idle
+  // while 32 walk 64 groups each.
+  if constexpr (NPART > 1) {
+    for (int i = tid; i < NPART * G * R; i += 256) {
+      const int part = i / (G * R), g = (i / R) % G, j = i % R;
+      const int k0 = part * (NGRP / NPART), k1 = k0 + NGRP / NPART;
+      float M = -INFINITY;
+      for (int k = k0; k < k1; k++) M = fmaxf(M, gm[k * G + g]);
+      float L = 0.f, U = 0.f;
+      for (int k = k0; k < k1; k++) {
+        const float e = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(gm[k * G + g] - M);   // a part without any row
+        L = fmaf(gl[k * G + g], e, L);
+        U = fmaf(gu[(k * G + g) * R + j], e, U);
+      }
+      pu[i] = U;
+      if (j == 0) { pm[part * G + g] = M; pl[part * G + g] = L; }
+    }
+    __syncthreads();
+  }
   for (int i = tid; i < G * R; i += 256) {
     const int g = i / R, j = i % R;
+    const float* sm = NPART > 1 ? pm : gm;
+    const float* sl_ = NPART > 1 ? pl : gl;
+    const float* su = NPART > 1 ? pu : gu;
+    constexpr int NS = NPART > 1 ? NPART : NGRP;
     float M = -INFINITY;
-    for (int k = 0; k < NGRP; k++) M = fmaxf(M, gm[k * G + g]);
+    for (int k = 0; k < NS; k++) M = fmaxf(M, sm[k * G + g]);
     float L = 0.f, U = 0.f;
-    for (int k = 0; k < NGRP; k++) {
-      const float e = __builtin_amdgcn_exp2f(gm[k * G + g] - M);
-      L = fmaf(gl[k * G + g], e, L);
-      U = fmaf(gu[(k * G + g) * R + j], e, U);
+    for (int k = 0; k < NS; k++) {
+      const float e = __builtin_amdgcn_exp2f(sm[k * G + g] - M);      // the workgroup holds at least one row: M is finite
+      L = fmaf(sl_[k * G + g], e, L);
+      U = fmaf(su[(k * G + g) * R + j], e, U);
     }
     Ush[i] = U;
     if (j == 0) { Msh[g] = M; Lsh[g] = L; }
